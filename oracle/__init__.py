@@ -1,0 +1,25 @@
+"""CPU oracle for the cyclic/hybrid decode-attention share (test infrastructure).
+
+A plain, slow, fp64 statement of what the path computes, written from the paper
+(Section 3.1: cyclic KVCache placement, hybrid attention, load-aware DP-rank
+routing) and from the textbook definition of softmax attention.  It exists only
+to check the HIP library: tests, the smoke check and the benchmark's CPU
+baseline leg may call it; the product never does, and nothing here imports the
+product.
+
+All four parts are pinned by tests that do not go through this code's own
+formulas a second time (worked examples from the paper's figures, closed forms,
+brute force, invariants, library routines); no function here is "parity
+unpinned".
+"""
+from .formats import bf16_bits_to_f64, e4m3_bytes_to_f64, E4M3_TABLE  # noqa: F401
+from .placement import build_placement  # noqa: F401
+from .worklist import build_worklist, ITEM_FIELDS, PAIR_FIELDS  # noqa: F401
+from .attention import (  # noqa: F401
+    attend,
+    gather_pair_kv,
+    decode_attention_pairs,
+    decode_attention_items,
+    merge_lse,
+    unsharded_attention,
+)

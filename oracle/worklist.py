@@ -1,0 +1,52 @@
+"""One rank's ragged (request, KV head, chunk) work list (oracle side).
+
+The paper's hybrid attention (Section 3.1) leaves each rank with an irregular
+set of (request, head) pairs: a cyclic subset of heads for tensor-parallel
+requests and every head of the data-parallel requests routed to it.  This list
+is that set written down for one kernel launch, with long contexts cut into
+chunks of ``chunk_tokens`` (split-K) and a longest-first launch order.
+
+Conventions (they are the interface, so both sides state them):
+pairs are numbered in (request, head) ascending order; a pair's chunks are
+consecutive items; item i writes partial rows [i*G, i*G+G); the query rows of a
+pair start at request*H_q + head*G (consecutive q-heads share a KV head); pair
+p's final rows are [p*G, p*G+G); ``sched`` lists item indices by decreasing
+token count, equal counts in increasing item index.
+"""
+import numpy as np
+
+ITEM_FIELDS = ("req", "kv_head", "tok_begin", "tok_end", "pair", "chunk", "q_row", "part_row")
+PAIR_FIELDS = ("req", "kv_head", "ctx_len", "n_chunks")
+
+
+def build_worklist(ctx_len, owner, rank: int, chunk_tokens: int, n_q_heads: int, n_kv_heads: int,
+                   page_tokens: int = 16):
+    """Return (items [n_items][8] int32, pairs [n_pairs][4] int32, sched int32,
+    chunk_indptr int64 [n_pairs+1]) for ``rank``."""
+    H = int(n_kv_heads)
+    if n_q_heads % H:
+        raise ValueError("q heads must be a multiple of KV heads")
+    G = n_q_heads // H
+    C = int(chunk_tokens)
+    if C < 0 or C % page_tokens:
+        raise ValueError("chunk must be a whole number of pages")
+    items, pairs, indptr = [], [], [0]
+    for r in range(len(ctx_len)):
+        L = int(ctx_len[r])
+        for h in range(H):
+            if int(owner[r][h]) != rank:
+                continue
+            p = len(pairs)
+            n_chunks = 1 if C == 0 else -(-L // C)
+            pairs.append((r, h, L, n_chunks))
+            for c in range(n_chunks):
+                begin = 0 if C == 0 else c * C
+                end = L if C == 0 else min(L, (c + 1) * C)
+                i = len(items)
+                items.append((r, h, begin, end, p, c, r * n_q_heads + h * G, i * G))
+            indptr.append(len(items))
+    items = np.array(items, dtype=np.int32).reshape(-1, 8)
+    pairs = np.array(pairs, dtype=np.int32).reshape(-1, 4)
+    length = items[:, 3] - items[:, 2]
+    sched = sorted(range(len(items)), key=lambda i: (-int(length[i]), i))
+    return items, pairs, np.array(sched, dtype=np.int32), np.array(indptr, dtype=np.int64)
