@@ -1,0 +1,230 @@
+/*
+ * failsafe.h - C ABI of the cyclic/hybrid decode-attention share for MI355X (gfx950).
+ *
+ * One GPU's share of one batched decode-attention step over a paged KVCache when
+ * the KV heads of a model are spread over R surviving tensor-parallel ranks:
+ *
+ *   fs_build_placement   which rank owns each (request, KV head)        host
+ *   fs_build_worklist    one rank's ragged (request, head, chunk) list  host
+ *   fs_decode_attention  per-item partial attention (out, lse)          device
+ *   fs_merge_lse         split-K partials -> final (out, lse)           device
+ *
+ * The placement rules are those of the paper's Section 3.1 ("Memory and
+ * Computation Balancer": Cyclic Placement, Hybrid Attention, Load-Aware DP-Rank
+ * Routing); attention is the decode phase of Section 2.1.1 over KVCache blocks.
+ *
+ * General rules
+ *  - Plain C types only.  Every pointer is marked HOST or DEVICE below.
+ *  - The caller owns every buffer.  The library allocates nothing that outlives
+ *    a call and frees nothing of the caller's.
+ *  - Host builders never touch the GPU and are pure functions of their inputs.
+ *  - Device calls enqueue work on `stream` (a hipStream_t passed as void*, NULL
+ *    = the null stream) and return without synchronising.
+ *  - Every call returns an fs_status; nothing throws or aborts.  After a
+ *    non-OK status fs_last_error() gives a message (thread-local).
+ */
+#ifndef FAILSAFE_H
+#define FAILSAFE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FS_ABI_VERSION 1
+
+#if defined(__GNUC__)
+#define FS_API __attribute__((visibility("default")))
+#else
+#define FS_API
+#endif
+
+typedef enum {
+  FS_OK = 0,
+  FS_EINVAL = -1,       /* an argument is out of range or inconsistent            */
+  FS_ECAPACITY = -2,    /* an output array is too small; needed counts returned   */
+  FS_EHIP = -3,         /* a HIP runtime call failed                              */
+  FS_EUNSUPPORTED = -4  /* valid in principle, not built (e.g. head_dim != 128)   */
+} fs_status;
+
+enum { FS_MODE_TP = 0, FS_MODE_DP = 1 };          /* per request                  */
+enum { FS_KV_BF16 = 0, FS_KV_FP8_E4M3 = 1 };      /* storage type of K and V      */
+
+/* Shape of one decode batch. */
+typedef struct {
+  int32_t n_req;        /* B   requests in the batch, >= 0                        */
+  int32_t n_q_heads;    /* H_q query heads, a multiple of n_kv_heads              */
+  int32_t n_kv_heads;   /* H_kv                                                   */
+  int32_t head_dim;     /* d, 128 is the only size built                          */
+  int32_t page_tokens;  /* tokens per KVCache block, 16 is the only size built    */
+  int32_t n_ranks;      /* R   surviving tensor-parallel ranks, >= 1              */
+} fs_shape;
+
+/* One unit of kernel work: tokens [tok_begin, tok_end) of one (request, KV head).
+ * 32 bytes; arrays of these are compared bit for bit against the oracle. */
+typedef struct {
+  int32_t req;          /* request index                                          */
+  int32_t kv_head;      /* KV head index                                          */
+  int32_t tok_begin;    /* first token, a multiple of page_tokens                 */
+  int32_t tok_end;      /* one past the last token, <= ctx_len[req]               */
+  int32_t pair;         /* index of the (request, head) pair in this rank's list  */
+  int32_t chunk;        /* index of this chunk within its pair                    */
+  int32_t q_row;        /* first query row: req*H_q + kv_head*G  (G = H_q/H_kv)   */
+  int32_t part_row;     /* first partial-output row: item_index*G                 */
+} fs_work_item;
+
+typedef struct {
+  int32_t req, kv_head, ctx_len, n_chunks;
+} fs_pair;
+
+/* ---------------------------------------------------------------------------
+ * fs_build_placement - Section 3.1, Cyclic Placement + Hybrid Attention +
+ * Load-Aware DP-Rank Routing, at request granularity.
+ *
+ * Requests are taken in index order (arrival order).  A tensor-parallel
+ * request r puts KV head h on rank (h + rot[r] + layer) mod R (mathematical
+ * mod, rot may be negative) and adds ctx_len[r] to that rank's load per head.
+ * rot == NULL means rot[r] = r.  The paper's layer-by-layer rotation is
+ * rot[r] = 0 with layer = the layer index.  A data-parallel request puts all
+ * H_kv heads on the rank whose running load is smallest (lowest rank among
+ * equals) and adds H_kv*ctx_len[r] there.  Load is counted in KV tokens x KV
+ * heads and includes everything placed so far, tensor-parallel shares too.
+ *
+ *  ctx_len   HOST in   [n_req]            cached tokens per request, each >= 1
+ *  mode      HOST in   [n_req]            FS_MODE_TP or FS_MODE_DP
+ *  rot       HOST in   [n_req] or NULL
+ *  owner     HOST out  [n_req*n_kv_heads] owning rank of (r, h) at r*H_kv + h
+ *  dp_rank   HOST out  [n_req]            the rank of a DP request, -1 for TP
+ *  rank_load HOST in/out [n_ranks]        running load; zero it for a fresh batch
+ *
+ * FS_EINVAL: NULL pointer, n_ranks < 1, n_kv_heads < 1, n_req < 0,
+ * ctx_len < 1, mode not 0/1.  On error the outputs are unspecified.
+ */
+FS_API fs_status fs_build_placement(const fs_shape* shape, const int32_t* ctx_len, const uint8_t* mode,
+                             const int32_t* rot, int32_t layer,
+                             int32_t* owner, int32_t* dp_rank, int64_t* rank_load);
+
+/* ---------------------------------------------------------------------------
+ * fs_build_worklist - the ragged per-(request, head) list that hybrid attention
+ * (Section 3.1) leaves on one rank, cut into split-K chunks.
+ *
+ * Pairs (r, h) with owner == rank are numbered in ascending (r, h).  Pair p is
+ * cut into ceil(ctx_len/chunk_tokens) items of chunk_tokens tokens (the last
+ * may be shorter); chunk_tokens == 0 means one item per pair.  Items of a pair
+ * are consecutive; chunk_indptr[p] is the first item of pair p.  sched lists
+ * item indices by decreasing token count, equal counts by increasing index
+ * (longest first, so the short ones fill the tail of the launch).
+ *
+ *  owner        HOST in  [n_req*n_kv_heads]
+ *  chunk_tokens 0 or a positive multiple of page_tokens
+ *  items        HOST out [items_cap]   may be NULL with items_cap 0 (count only)
+ *  pairs        HOST out [pairs_cap]   may be NULL with pairs_cap 0
+ *  sched        HOST out [items_cap]   may be NULL iff items is NULL
+ *  chunk_indptr HOST out [pairs_cap+1] may be NULL iff pairs is NULL
+ *  n_items, n_pairs  HOST out  always written when the shape is valid
+ *
+ * FS_ECAPACITY: a non-NULL array is too small; nothing but the counts is valid.
+ * FS_EINVAL: bad shape, rank outside [0, R), bad chunk_tokens, owner outside
+ * [0, R), ctx_len < 1, counts beyond int32 rows.
+ */
+FS_API fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len, const int32_t* owner,
+                            int32_t rank, int32_t chunk_tokens,
+                            fs_work_item* items, int64_t items_cap,
+                            fs_pair* pairs, int64_t pairs_cap,
+                            int32_t* sched, int64_t* chunk_indptr,
+                            int64_t* n_items, int64_t* n_pairs);
+
+/* ---------------------------------------------------------------------------
+ * The paged KVCache as the kernels read it.
+ *
+ * A slot is one KVCache block of one KV head: page_tokens x head_dim elements
+ * of K and as many of V.  Slot s of K starts at k_pool + s*k_slot_stride bytes
+ * (likewise V), so K and V may live in two pools or interleaved in one.  Slot
+ * starts must be 16-byte aligned.  page_ids[page_indptr[p] + i] is the slot of
+ * page i of this rank's pair p.
+ *
+ * Element order inside a slot is chosen for the gfx950 matrix cores so that a
+ * wavefront's 16-byte loads are contiguous 1 KiB runs AND land directly in MFMA
+ * operand registers; fs_kv_elem_offset() is the definition:
+ *
+ *  bf16 K (16 tok x 128):  [d/32][(d%32)/8][tok][d%8]
+ *  bf16 V (16 tok x 128):  [d/32][tok/4][d%16][(d/16)%2][tok%4]
+ *  fp8  K and V         :  [tok][d]   (token-major, 128 bytes per token)
+ *
+ * fp8 is OCP e4m3 (finite-only, max 448); element value = code * scale[slot]
+ * with one fp32 scale per slot for K and one for V.
+ */
+typedef struct {
+  const void* q;               /* DEVICE [n_req][n_q_heads][head_dim] bf16        */
+  const void* k_pool;          /* DEVICE                                          */
+  const void* v_pool;          /* DEVICE                                          */
+  int64_t k_slot_stride;       /* bytes between consecutive K slots               */
+  int64_t v_slot_stride;       /* bytes between consecutive V slots               */
+  const float* k_scale;        /* DEVICE [n_slots], fp8 only, else NULL           */
+  const float* v_scale;        /* DEVICE [n_slots], fp8 only, else NULL           */
+  const int64_t* page_indptr;  /* DEVICE [n_pairs+1]                              */
+  const int32_t* page_ids;     /* DEVICE [page_indptr[n_pairs]]                   */
+  int32_t kv_dtype;            /* FS_KV_BF16 or FS_KV_FP8_E4M3                    */
+  float sm_scale;              /* softmax scale, 1/sqrt(head_dim) in the paper's models */
+} fs_kv_view;
+
+/* Element offset (in elements) of (tok, d) inside a slot; is_v selects the V
+ * order.  Returns -1 for arguments out of range or an unknown kv_dtype. */
+FS_API int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, int32_t d);
+
+/* ---------------------------------------------------------------------------
+ * fs_decode_attention - decode-phase attention (Section 2.1.1) for every item
+ * of the list, one launch.  For item i and g in [0, G), with q = query row
+ * q_row+g and t over the item's tokens:
+ *     s_t = sm_scale * <q, K_t>
+ *     part_lse[part_row+g] = ln sum_t exp(s_t)
+ *     part_o[part_row+g][:] = sum_t exp(s_t - lse) * V_t
+ * Scores, softmax and accumulation are fp32; the softmax weights enter the
+ * P.V product rounded to bf16.  Tokens at or beyond tok_end are never used,
+ * whatever their bits.
+ *
+ *  items_dev  DEVICE in  [n_items]     as built by fs_build_worklist
+ *  sched_dev  DEVICE in  [n_items]     launch order, or NULL for index order
+ *  part_o     DEVICE out [n_items*G][head_dim] fp32
+ *  part_lse   DEVICE out [n_items*G]   fp32
+ *
+ * n_items == 0 is a no-op.  FS_EINVAL: NULL pointers, bad shape, G > 16,
+ * misaligned pools/strides.  FS_EUNSUPPORTED: head_dim != 128, page_tokens !=
+ * 16, fp8 with G > 8.  FS_EHIP: launch failure.  Item contents are trusted
+ * (they are device memory); build them with fs_build_worklist.
+ */
+FS_API fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv,
+                              const fs_work_item* items_dev, const int32_t* sched_dev,
+                              int64_t n_items, float* part_o, float* part_lse, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * fs_merge_lse - combine the chunk partials of each pair (split-K merge):
+ *     lse = ln sum_c exp(lse_c),   out = sum_c exp(lse_c - lse) * o_c
+ * Rows [p*G, p*G+G) of out/lse belong to pair p; its partial rows are
+ * [chunk_indptr[p]*G, chunk_indptr[p+1]*G).
+ *
+ *  part_o, part_lse  DEVICE in   as written by fs_decode_attention
+ *  chunk_indptr_dev  DEVICE in   [n_pairs+1]
+ *  out               DEVICE out  [n_pairs*G][head_dim] fp32
+ *  lse               DEVICE out  [n_pairs*G] fp32
+ *
+ * n_pairs == 0 is a no-op.  FS_EINVAL: NULL pointers, group < 1.
+ * FS_EUNSUPPORTED: head_dim != 128.
+ */
+FS_API fs_status fs_merge_lse(const float* part_o, const float* part_lse, const int64_t* chunk_indptr_dev,
+                       int64_t n_pairs, int32_t group, int32_t head_dim,
+                       float* out, float* lse, void* stream);
+
+/* Launch-shape knobs for measurement sweeps ("waves_per_group" in {1,2,4}, "prefetch_pages" in [1,3]).
+ * Unknown key or a value outside the documented range: FS_EINVAL, nothing changes. */
+FS_API fs_status fs_set_option(const char* key, int32_t value);
+FS_API int32_t   fs_get_option(const char* key);   /* -1 for an unknown key */
+
+FS_API const char* fs_last_error(void);   /* message of this thread's last non-OK status */
+FS_API int32_t     fs_abi_version(void);  /* FS_ABI_VERSION the library was built with   */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAILSAFE_H */

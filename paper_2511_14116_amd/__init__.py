@@ -1,0 +1,15 @@
+"""MI355X-native cyclic/hybrid decode-attention share (thin binding over libfailsafe.so).
+
+Every step of the path runs in the native library (host builders in C++, kernels in
+HIP for gfx950); this package only marshals arguments.  There is no fallback: if the
+library is not built, importing the binding's functions raises.
+"""
+from .binding import (  # noqa: F401
+    FS_OK, FS_EINVAL, FS_ECAPACITY, FS_EHIP, FS_EUNSUPPORTED,
+    FS_MODE_TP, FS_MODE_DP, FS_KV_BF16, FS_KV_FP8_E4M3,
+    FsError, FsShape, FsKvView, ITEM_DTYPE, PAIR_DTYPE,
+    library_path, load_library,
+    fs_build_placement, fs_build_worklist, fs_decode_attention, fs_merge_lse,
+    fs_kv_elem_offset, fs_set_option, fs_get_option, fs_last_error, fs_abi_version,
+)
+from .layout import slot_permutation, pack_slots  # noqa: F401

@@ -1,0 +1,185 @@
+"""ctypes binding for include/failsafe.h: same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+FS_OK, FS_EINVAL, FS_ECAPACITY, FS_EHIP, FS_EUNSUPPORTED = 0, -1, -2, -3, -4
+FS_MODE_TP, FS_MODE_DP = 0, 1
+FS_KV_BF16, FS_KV_FP8_E4M3 = 0, 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class FsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"fs_status {status}: {message}")
+        self.status = status
+
+
+class FsShape(C.Structure):
+    _fields_ = [("n_req", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("page_tokens", C.c_int32), ("n_ranks", C.c_int32)]
+
+
+class FsKvView(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("k_pool", C.c_void_p), ("v_pool", C.c_void_p),
+                ("k_slot_stride", C.c_int64), ("v_slot_stride", C.c_int64),
+                ("k_scale", C.c_void_p), ("v_scale", C.c_void_p),
+                ("page_indptr", C.c_void_p), ("page_ids", C.c_void_p),
+                ("kv_dtype", C.c_int32), ("sm_scale", C.c_float)]
+
+
+ITEM_DTYPE = np.dtype([(n, np.int32) for n in
+                       ("req", "kv_head", "tok_begin", "tok_end", "pair", "chunk", "q_row", "part_row")])
+PAIR_DTYPE = np.dtype([(n, np.int32) for n in ("req", "kv_head", "ctx_len", "n_chunks")])
+
+
+def library_path() -> str:
+    return os.path.join(_PKG, "libfailsafe.so")
+
+
+def load_library(path: str | None = None):
+    """Load libfailsafe.so (built in-tree by paper_2511_14116_amd/build.py).  No fallback."""
+    global _LIB
+    if _LIB is not None and path is None:
+        return _LIB
+    p = path or library_path()
+    if not os.path.exists(p):
+        raise FileNotFoundError(
+            f"{p} is not built; run `python -m paper_2511_14116_amd.build` (needs hipcc) first")
+    lib = C.CDLL(p)
+    i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+    lib.fs_build_placement.argtypes = [C.POINTER(FsShape), i32p, u8p, i32p, C.c_int32, i32p, i32p, i64p]
+    lib.fs_build_placement.restype = C.c_int
+    lib.fs_build_worklist.argtypes = [C.POINTER(FsShape), i32p, i32p, C.c_int32, C.c_int32,
+                                      C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                      C.c_void_p, C.c_void_p, i64p, i64p]
+    lib.fs_build_worklist.restype = C.c_int
+    lib.fs_kv_elem_offset.argtypes = [C.c_int32] * 4
+    lib.fs_kv_elem_offset.restype = C.c_int32
+    lib.fs_decode_attention.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
+                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fs_decode_attention.restype = C.c_int
+    lib.fs_merge_lse.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                 C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fs_merge_lse.restype = C.c_int
+    lib.fs_set_option.argtypes = [C.c_char_p, C.c_int32]
+    lib.fs_set_option.restype = C.c_int
+    lib.fs_get_option.argtypes = [C.c_char_p]
+    lib.fs_get_option.restype = C.c_int32
+    lib.fs_last_error.argtypes = []
+    lib.fs_last_error.restype = C.c_char_p
+    lib.fs_abi_version.argtypes = []
+    lib.fs_abi_version.restype = C.c_int32
+    if path is None:
+        _LIB = lib
+    return lib
+
+
+def fs_last_error() -> str:
+    return load_library().fs_last_error().decode()
+
+
+def fs_abi_version() -> int:
+    return load_library().fs_abi_version()
+
+
+def _check(st: int):
+    if st != FS_OK:
+        raise FsError(st, fs_last_error())
+
+
+def _ptr(x):
+    """Address of a device tensor / host array / raw int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    raise TypeError(type(x))
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def fs_build_placement(shape: FsShape, ctx_len, mode, rot=None, layer: int = 0, rank_load=None):
+    """-> (owner [B][H_kv] int32, dp_rank [B] int32, rank_load [R] int64)."""
+    lib = load_library()
+    B, H, R = shape.n_req, shape.n_kv_heads, shape.n_ranks
+    ctx = _host(ctx_len, np.int32)
+    md = _host(mode, np.uint8)
+    if len(ctx) != B or len(md) != B:
+        raise ValueError("ctx_len and mode must have n_req entries")
+    rt = None if rot is None else _host(rot, np.int32)
+    owner = np.empty((max(B, 0), max(H, 0)), dtype=np.int32)
+    dp = np.empty(max(B, 0), dtype=np.int32)
+    load = np.zeros(max(R, 0), dtype=np.int64) if rank_load is None else np.array(rank_load, dtype=np.int64)
+    i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+    st = lib.fs_build_placement(C.byref(shape), ctx.ctypes.data_as(i32p), md.ctypes.data_as(u8p),
+                                None if rt is None else rt.ctypes.data_as(i32p), layer,
+                                owner.ctypes.data_as(i32p), dp.ctypes.data_as(i32p), load.ctypes.data_as(i64p))
+    _check(st)
+    return owner, dp, load
+
+
+def fs_build_worklist(shape: FsShape, ctx_len, owner, rank: int, chunk_tokens: int, out=None):
+    """-> (items [n] ITEM_DTYPE, pairs [m] PAIR_DTYPE, sched [n] int32, chunk_indptr [m+1] int64).
+
+    ``out`` may hold preallocated host arrays (items, pairs, sched, chunk_indptr), e.g. views
+    of pinned memory; they are filled in place and sliced to the counts."""
+    lib = load_library()
+    ctx = _host(ctx_len, np.int32)
+    own = _host(owner, np.int32)
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    n_items, n_pairs = C.c_int64(0), C.c_int64(0)
+    if out is None:
+        st = lib.fs_build_worklist(C.byref(shape), ctx.ctypes.data_as(i32p), own.ctypes.data_as(i32p), rank,
+                                   chunk_tokens, None, 0, None, 0, None, None, C.byref(n_items), C.byref(n_pairs))
+        _check(st)
+        items = np.empty(n_items.value, dtype=ITEM_DTYPE)
+        pairs = np.empty(n_pairs.value, dtype=PAIR_DTYPE)
+        sched = np.empty(n_items.value, dtype=np.int32)
+        indptr = np.empty(n_pairs.value + 1, dtype=np.int64)
+    else:
+        items, pairs, sched, indptr = out
+    st = lib.fs_build_worklist(C.byref(shape), ctx.ctypes.data_as(i32p), own.ctypes.data_as(i32p), rank,
+                               chunk_tokens, items.ctypes.data, len(items), pairs.ctypes.data, len(pairs),
+                               sched.ctypes.data, indptr.ctypes.data, C.byref(n_items), C.byref(n_pairs))
+    _check(st)
+    n, m = n_items.value, n_pairs.value
+    return items[:n], pairs[:m], sched[:n], indptr[:m + 1]
+
+
+def fs_kv_elem_offset(kv_dtype: int, is_v: int, tok: int, d: int) -> int:
+    return load_library().fs_kv_elem_offset(kv_dtype, is_v, tok, d)
+
+
+def fs_decode_attention(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int,
+                        part_o, part_lse, stream=None) -> None:
+    st = load_library().fs_decode_attention(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
+                                            n_items, _ptr(part_o), _ptr(part_lse), _ptr(stream))
+    _check(st)
+
+
+def fs_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,
+                 out, lse, stream=None) -> None:
+    st = load_library().fs_merge_lse(_ptr(part_o), _ptr(part_lse), _ptr(chunk_indptr_dev), n_pairs, group,
+                                     head_dim, _ptr(out), _ptr(lse), _ptr(stream))
+    _check(st)
+
+
+def fs_set_option(key: str, value: int) -> None:
+    _check(load_library().fs_set_option(key.encode(), value))
+
+
+def fs_get_option(key: str) -> int:
+    return load_library().fs_get_option(key.encode())

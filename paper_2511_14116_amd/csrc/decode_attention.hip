@@ -1,0 +1,522 @@
+// fs_decode_attention: per-item partial decode attention over a paged KVCache, gfx950 only.
+//
+// What is computed is the decode phase of Section 2.1.1 of the paper (one new query token per
+// request against all cached keys) for the ragged (request, KV head, chunk) list that the
+// paper's hybrid attention (Section 3.1) leaves on one rank.  The kernel design below is not
+// from the paper, which describes no kernel.
+//
+// bf16 path (GQA groups up to 16 q-heads):
+//   One workgroup per work item, in the longest-first order the list prescribes; the hardware
+//   dispatcher hands the next item to whichever CU frees a slot, which is list scheduling.
+//   The item's pages are split evenly over the workgroup's wavefronts.  A wavefront streams
+//   K and V pages with 16-byte-per-lane loads that are each one contiguous 1 KiB run, straight
+//   into MFMA operand registers (the in-slot element order is built for that), several pages
+//   ahead of the arithmetic.  Per page:
+//     S^T[tok][q] = K . Q^T      4 x v_mfma_f32_16x16x32_bf16   (A = K page, B = Q^T)
+//     online softmax in fp32, log2 domain; a lane owns q-head lane%16 and tokens 4*(lane/16)+r
+//     O^T[d][q]  += V^T . P^T    8 x v_mfma_f32_16x16x16_bf16   (A = V page, B = P^T as bf16)
+//   The S^T accumulator layout is exactly the B-operand layout of the second product, so the
+//   softmax weights never move between lanes; only the running max needs a 2-step cross-lane
+//   exchange.  Wavefronts merge (max, sum, O) through LDS at the end of the item.
+//
+// fp8 path (e4m3 K/V with one fp32 scale per slot, small groups): plain fp32 VALU, since with
+// one q-head per KV head there is no dense contraction to give the matrix cores.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "fs_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct DecodeParams {
+  const uint16_t* __restrict__ q;
+  const char* __restrict__ k_pool;
+  const char* __restrict__ v_pool;
+  int64_t k_stride;
+  int64_t v_stride;
+  const float* __restrict__ k_scale;
+  const float* __restrict__ v_scale;
+  const int64_t* __restrict__ page_indptr;
+  const int32_t* __restrict__ page_ids;
+  const fs_work_item* __restrict__ items;
+  const int32_t* __restrict__ sched;
+  float* __restrict__ part_o;
+  float* __restrict__ part_lse;
+  int32_t group;
+  float scale_log2;   // sm_scale * log2(e): scores live in the log2 domain
+};
+
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kORow = 132;   // floats per q row of the LDS merge buffer (128 + pad against bank conflicts)
+
+// Butterfly steps across the four 16-lane rows of a wavefront.  v_permlane16_swap / v_permlane32_swap
+// exchange rows (halves) between two registers; fed the same value twice they leave, in every lane,
+// the lane's own value in one result and its partner's (lane^16, lane^32) in the other.
+__device__ __forceinline__ float max_xor16(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned a = r[0], b = r[1];   // (copy the elements out: a bit_cast of r[i] itself reads element 0)
+  return fmaxf(__uint_as_float(a), __uint_as_float(b));
+}
+__device__ __forceinline__ float max_xor32(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const unsigned a = r[0], b = r[1];   // (copy the elements out: a bit_cast of r[i] itself reads element 0)
+  return fmaxf(__uint_as_float(a), __uint_as_float(b));
+}
+__device__ __forceinline__ float sum_xor16(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned a = r[0], b = r[1];
+  return __uint_as_float(a) + __uint_as_float(b);
+}
+__device__ __forceinline__ float sum_xor32(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const unsigned a = r[0], b = r[1];
+  return __uint_as_float(a) + __uint_as_float(b);
+}
+
+// One page's operands in registers: K as 4 A-operands of the 16x16x32 product (k = 32 d each),
+// V as 4 x (2 A-operands of the 16x16x16 product) (16 d rows each, k = 16 tokens).
+struct PageRegs {
+  u32x4 k[4];
+  u32x4 v[4];
+};
+
+__device__ __forceinline__ void load_page(PageRegs& r, const char* __restrict__ k_pool,
+                                          const char* __restrict__ v_pool, int64_t k_stride,
+                                          int64_t v_stride, int32_t slot, int lane) {
+  const u32x4* kp = reinterpret_cast<const u32x4*>(k_pool + slot * k_stride) + lane;
+  const u32x4* vp = reinterpret_cast<const u32x4*>(v_pool + slot * v_stride) + lane;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) r.k[s] = __builtin_nontemporal_load(kp + s * 64);
+#pragma unroll
+  for (int s = 0; s < 4; ++s) r.v[s] = __builtin_nontemporal_load(vp + s * 64);
+}
+
+struct SoftmaxState {
+  float m;        // running max (log2 domain) of this lane's q-head, same in the 4 lanes that share it
+  float l;        // this lane's share of the running sum
+  f32x4 acc[8];   // O^T[d = 16j + 4*(lane/16) + r][q = lane%16]
+};
+
+template <bool FULL>
+__device__ __forceinline__ void consume_page(SoftmaxState& st, PageRegs& pg, const bf16x8 (&qreg)[4],
+                                             float scale_log2, int valid, int kb) {
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pg.k[c]), qreg[c], s, 0, 0, 0);
+
+  float x[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) x[r] = s[r] * scale_log2;
+  if (!FULL && valid < fs::kPageTokens) {   // last page of the context: tokens past the end do not exist
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (4 * kb + r >= valid) x[r] = -INFINITY;
+    const uint32_t m0 = (4 * kb + 0 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid ? 0xFFFF0000u : 0u);
+    const uint32_t m1 = (4 * kb + 2 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid ? 0xFFFF0000u : 0u);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {   // whatever bits sit there (NaN included) must not reach the product
+      pg.v[c].x &= m0; pg.v[c].y &= m1; pg.v[c].z &= m0; pg.v[c].w &= m1;
+    }
+  }
+  float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+  mx = max_xor32(max_xor16(mx));
+  const float m_new = fmaxf(st.m, mx);
+  if (__any(m_new > st.m)) {
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // first page: exp2(-inf) = 0
+    st.l *= alpha;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
+    st.m = m_new;
+  }
+  f32x4 p;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(x[r] - st.m);
+  st.l += (p[0] + p[1]) + (p[2] + p[3]);
+  const s16x4 pb = __builtin_bit_cast(s16x4, __builtin_convertvector(p, bf16x4));
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const uint2 lo = make_uint2(pg.v[c].x, pg.v[c].y), hi = make_uint2(pg.v[c].z, pg.v[c].w);
+    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pb, st.acc[2 * c], 0, 0, 0);
+    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pb, st.acc[2 * c + 1], 0, 0, 0);
+  }
+}
+
+// Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.
+template <int WAVES>
+__device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_total, int wave, int lane,
+                                                int G, float* __restrict__ part_o,
+                                                float* __restrict__ part_lse, int part_row,
+                                                float* sm_o, float* sm_m, float* sm_l) {
+  const int qi = lane & 15, kb = lane >> 4;
+  if (lane < 16) {
+    sm_m[wave * 16 + lane] = st.m;
+    sm_l[wave * 16 + lane] = l_total;
+  }
+  float* row = sm_o + (wave * 16 + qi) * kORow + 4 * kb;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + 16 * j) = st.acc[j];
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
+    const int q = idx >> 5, d4 = idx & 31;
+    float M = sm_m[q];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sm_m[w * 16 + q]);
+    float L = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const float wgt = __builtin_amdgcn_exp2f(sm_m[w * 16 + q] - M);   // a wave with no pages has m = -inf
+      L += wgt * sm_l[w * 16 + q];
+      o += wgt * *reinterpret_cast<const f32x4*>(sm_o + (w * 16 + q) * kORow + 4 * d4);
+    }
+    const float inv = 1.0f / L;
+    *reinterpret_cast<f32x4*>(part_o + static_cast<int64_t>(part_row + q) * fs::kHeadDim + 4 * d4) = o * inv;
+    if (d4 == 0) part_lse[part_row + q] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+  }
+}
+
+template <int WAVES, int NBUF>
+__global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodeParams P) {
+  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
+  __shared__ float sm_m[WAVES * 16];
+  __shared__ float sm_l[WAVES * 16];
+
+  const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
+  const fs_work_item it = P.items[item_idx];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qi = lane & 15, kb = lane >> 4;
+  const int G = P.group;
+
+  const int n_tok = it.tok_end - it.tok_begin;
+  const int n_pages = (n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
+  const int32_t* __restrict__ ids = P.page_ids + P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+  const int per = (n_pages + WAVES - 1) / WAVES;
+  const int p0 = wave * per;
+  const int p1 = min(n_pages, p0 + per);
+
+  // Q^T as the B operand: lane (q = lane%16, kb = lane/16) holds Q[q][32c + 8kb .. +8) for c = 0..3.
+  bf16x8 qreg[4];
+  {
+    // rows beyond the group are zero; they are read from a row that exists and then blanked
+    const int qrow = it.q_row + min(qi, G - 1);
+    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      u32x4 v = qp[4 * c];
+      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
+      qreg[c] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  SoftmaxState st;
+  st.m = -INFINITY;
+  st.l = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // NBUF register buffers; NBUF-1 pages are in flight while one is consumed.  The steady-state
+  // loop is branch-free (every prefetch is in range, every page is full), so the loads of
+  // pages i+1.. stay outstanding while page i is consumed; the ragged end is a second loop.
+  PageRegs buf[NBUF];
+#pragma unroll
+  for (int u = 0; u < NBUF - 1; ++u)
+    if (p0 + u < p1) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, ids[p0 + u], lane);
+
+  int i = p0;
+  for (; i + 2 * NBUF - 2 < p1; i += NBUF) {
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u) {
+      load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, ids[i + u + NBUF - 1], lane);
+      consume_page<true>(st, buf[u], qreg, P.scale_log2, fs::kPageTokens, kb);
+    }
+  }
+  // here pages i .. i+NBUF-2 (those below p1) are in flight in buf[0 .. NBUF-2]
+#pragma unroll
+  for (int u = 0; u < 2 * NBUF - 2; ++u) {
+    const int pi = i + u;
+    if (pi < p1) {
+      const int pn = pi + NBUF - 1;
+      if (pn < p1) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, ids[pn], lane);
+      consume_page<false>(st, buf[u % NBUF], qreg, P.scale_log2, min(fs::kPageTokens, n_tok - pi * fs::kPageTokens), kb);
+    }
+  }
+
+  const float l_total = sum_xor32(sum_xor16(st.l));
+  merge_and_store<WAVES>(st, l_total, wave, lane, G, P.part_o, P.part_lse, it.part_row, sm_o, sm_m, sm_l);
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp8 e4m3 path.  Slots are token-major (128 bytes per token).  Lane (c = lane%8, ts = lane/8)
+// owns d in [16c, 16c+16) and the tokens ts and ts+8 of every page, so one wave-wide 16-byte
+// load covers eight whole token rows (1 KiB contiguous).  The 8 lanes of a token row add their
+// partial dot products with three DPP steps; each of the 8 token subsets keeps its own running
+// (max, sum, o[16]) so nothing else crosses lanes until the item ends.
+// ---------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ void cvt16(const u32x4 raw, float (&f)[16]) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], false);
+    const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], true);
+    f[4 * i + 0] = lo[0]; f[4 * i + 1] = lo[1]; f[4 * i + 2] = hi[0]; f[4 * i + 3] = hi[1];
+  }
+}
+
+__device__ __forceinline__ float sum_over_8_lanes(float v) {
+  v += __shfl_xor(v, 1, 64);
+  v += __shfl_xor(v, 2, 64);
+  v += __shfl_xor(v, 4, 64);
+  return v;
+}
+
+struct Fp8Page {
+  u32x4 k[2];
+  u32x4 v[2];
+  float ks, vs;
+};
+
+__device__ __forceinline__ void load_page_fp8(Fp8Page& r, const DecodeParams& P, int32_t slot, int lane) {
+  const u32x4* kp = reinterpret_cast<const u32x4*>(P.k_pool + slot * P.k_stride) + lane;
+  const u32x4* vp = reinterpret_cast<const u32x4*>(P.v_pool + slot * P.v_stride) + lane;
+  r.k[0] = __builtin_nontemporal_load(kp);
+  r.k[1] = __builtin_nontemporal_load(kp + 64);
+  r.v[0] = __builtin_nontemporal_load(vp);
+  r.v[1] = __builtin_nontemporal_load(vp + 64);
+  r.ks = P.k_scale[slot];
+  r.vs = P.v_scale[slot];
+}
+
+template <int WAVES, int NBUF, int GMAX>
+__global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodeParams P) {
+  // merge buffer: [wave][token subset][g] (m, l) and o[128]
+  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 8 * GMAX * kORow];
+  __shared__ float sm_m[WAVES * 8 * GMAX];
+  __shared__ float sm_l[WAVES * 8 * GMAX];
+
+  const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
+  const fs_work_item it = P.items[item_idx];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = lane & 7, ts = lane >> 3;
+  const int G = P.group;
+
+  const int n_tok = it.tok_end - it.tok_begin;
+  const int n_pages = (n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
+  const int32_t* __restrict__ ids = P.page_ids + P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+  const int per = (n_pages + WAVES - 1) / WAVES;
+  const int p0 = wave * per;
+  const int p1 = min(n_pages, p0 + per);
+
+  // this lane's 16 d of every q row, pre-multiplied by the softmax scale (fp32)
+  float qf[GMAX][16];
+#pragma unroll
+  for (int g = 0; g < GMAX; ++g) {
+    if (g < G) {
+      const uint4* qp = reinterpret_cast<const uint4*>(P.q + static_cast<int64_t>(it.q_row + g) * fs::kHeadDim + 16 * c);
+      const uint4 a = qp[0], b = qp[1];
+      const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        qf[g][2 * i] = __uint_as_float(w[i] << 16) * P.scale_log2;
+        qf[g][2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u) * P.scale_log2;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) qf[g][i] = 0.f;
+    }
+  }
+
+  float m[GMAX], l[GMAX], o[GMAX][16];
+#pragma unroll
+  for (int g = 0; g < GMAX; ++g) {
+    m[g] = -INFINITY;
+    l[g] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[g][i] = 0.f;
+  }
+
+  Fp8Page buf[NBUF];
+#pragma unroll
+  for (int u = 0; u < NBUF - 1; ++u)
+    if (p0 + u < p1) load_page_fp8(buf[u], P, ids[p0 + u], lane);
+  int32_t slot_next = (p0 + NBUF - 1 < p1) ? ids[p0 + NBUF - 1] : 0;
+
+  for (int i = p0; i < p1; i += NBUF) {
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u) {
+      const int pi = i + u;
+      if (pi < p1) {
+        const int pn = pi + NBUF - 1;
+        if (pn < p1) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, slot_next, lane);
+        slot_next = (pn + 1 < p1) ? ids[pn + 1] : 0;
+        const Fp8Page& pg = buf[u];
+        const int valid = min(fs::kPageTokens, n_tok - pi * fs::kPageTokens);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {          // token ts + 8h of this page
+          const bool live = ts + 8 * h < valid;
+          float kf[16], vf[16];
+          cvt16(pg.k[h], kf);
+          cvt16(pg.v[h], vf);
+#pragma unroll
+          for (int g = 0; g < GMAX; ++g) {
+            if (g < G) {
+              float dot = 0.f;
+#pragma unroll
+              for (int e = 0; e < 16; ++e) dot = fmaf(qf[g][e], kf[e], dot);
+              float x = sum_over_8_lanes(dot) * pg.ks;
+              x = live ? x : -INFINITY;
+              const float m_new = fmaxf(m[g], x);
+              // m_new = -inf only while this subset has seen no live token; keep the state at zero then
+              const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m[g] - m_new);
+              const float p = live ? __builtin_amdgcn_exp2f(x - m_new) : 0.f;
+              l[g] = l[g] * alpha + p;
+              const float pv = p * pg.vs;
+#pragma unroll
+              for (int e = 0; e < 16; ++e) o[g][e] = fmaf(o[g][e], alpha, live ? pv * vf[e] : 0.f);
+              m[g] = m_new;
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // merge the WAVES*8 token subsets of each q row
+#pragma unroll
+  for (int g = 0; g < GMAX; ++g) {
+    if (g < G) {
+      const int slot = (wave * 8 + ts) * GMAX + g;
+      if (c == 0) { sm_m[slot] = m[g]; sm_l[slot] = l[g]; }
+      float* row = sm_o + slot * kORow + 16 * c;
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4)
+        *reinterpret_cast<f32x4*>(row + 4 * e4) = f32x4{o[g][4 * e4], o[g][4 * e4 + 1], o[g][4 * e4 + 2], o[g][4 * e4 + 3]};
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
+    const int g = idx >> 5, d4 = idx & 31;
+    float M = -INFINITY;
+    for (int s = 0; s < WAVES * 8; ++s) M = fmaxf(M, sm_m[s * GMAX + g]);
+    float L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < WAVES * 8; ++s) {
+      const float ms = sm_m[s * GMAX + g];
+      if (ms != -INFINITY) {
+        const float wgt = __builtin_amdgcn_exp2f(ms - M);
+        L += wgt * sm_l[s * GMAX + g];
+        acc += wgt * *reinterpret_cast<const f32x4*>(sm_o + (s * GMAX + g) * kORow + 4 * d4);
+      }
+    }
+    const float inv = 1.0f / L;
+    *reinterpret_cast<f32x4*>(P.part_o + static_cast<int64_t>(it.part_row + g) * fs::kHeadDim + 4 * d4) = acc * inv;
+    if (d4 == 0) P.part_lse[it.part_row + g] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+  }
+}
+
+template <typename K>
+fs_status launch(K kernel, int threads, const DecodeParams& P, int64_t n_items, hipStream_t stream) {
+  hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(n_items)), dim3(threads), 0, stream, P);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_decode_attention: launch failed: %s", hipGetErrorString(e));
+  return FS_OK;
+}
+
+}  // namespace
+
+extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv,
+                                         const fs_work_item* items_dev, const int32_t* sched_dev,
+                                         int64_t n_items, float* part_o, float* part_lse, void* stream) {
+  if (!shape || !kv) return fs::fail(FS_EINVAL, "fs_decode_attention: shape or kv is NULL");
+  if (shape->n_kv_heads < 1 || shape->n_q_heads < shape->n_kv_heads || shape->n_q_heads % shape->n_kv_heads)
+    return fs::fail(FS_EINVAL, "fs_decode_attention: n_q_heads %d is not a multiple of n_kv_heads %d",
+                    shape->n_q_heads, shape->n_kv_heads);
+  if (shape->head_dim != fs::kHeadDim)
+    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention: head_dim %d (only %d is built)", shape->head_dim, fs::kHeadDim);
+  if (shape->page_tokens != fs::kPageTokens)
+    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention: page_tokens %d (only %d is built)", shape->page_tokens,
+                    fs::kPageTokens);
+  const int G = shape->n_q_heads / shape->n_kv_heads;
+  if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "fs_decode_attention: group %d > %d", G, fs::kMaxGroup);
+  if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "fs_decode_attention: n_items out of range");
+  if (kv->kv_dtype != FS_KV_BF16 && kv->kv_dtype != FS_KV_FP8_E4M3)
+    return fs::fail(FS_EINVAL, "fs_decode_attention: unknown kv_dtype %d", kv->kv_dtype);
+  if (kv->kv_dtype == FS_KV_FP8_E4M3 && G > fs::kMaxGroupFp8)
+    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention: fp8 KV with group %d > %d", G, fs::kMaxGroupFp8);
+  if (n_items == 0) return FS_OK;
+  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev || !part_o || !part_lse)
+    return fs::fail(FS_EINVAL, "fs_decode_attention: NULL device pointer");
+  if (kv->kv_dtype == FS_KV_FP8_E4M3 && (!kv->k_scale || !kv->v_scale))
+    return fs::fail(FS_EINVAL, "fs_decode_attention: fp8 KV needs k_scale and v_scale");
+  const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * (kv->kv_dtype == FS_KV_BF16 ? 2 : 1);
+  if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
+      (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
+      (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
+      (reinterpret_cast<uintptr_t>(part_o) & 15))
+    return fs::fail(FS_EINVAL, "fs_decode_attention: pools, strides, q and part_o must be 16-byte aligned and "
+                               "strides at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
+  if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "fs_decode_attention: sm_scale is not finite");
+
+  DecodeParams P;
+  P.q = static_cast<const uint16_t*>(kv->q);
+  P.k_pool = static_cast<const char*>(kv->k_pool);
+  P.v_pool = static_cast<const char*>(kv->v_pool);
+  P.k_stride = kv->k_slot_stride;
+  P.v_stride = kv->v_slot_stride;
+  P.k_scale = kv->k_scale;
+  P.v_scale = kv->v_scale;
+  P.page_indptr = kv->page_indptr;
+  P.page_ids = kv->page_ids;
+  P.items = items_dev;
+  P.sched = sched_dev;
+  P.part_o = part_o;
+  P.part_lse = part_lse;
+  P.group = G;
+  P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int waves = fs::options().waves_per_group;
+
+  const int nbuf = fs::options().prefetch_pages + 1;
+
+#define FS_PICK(KERNEL, ...)                                                             \
+  switch (waves * 10 + nbuf) {                                                           \
+    case 12: return launch(KERNEL<1, 2 __VA_ARGS__>, 64, P, n_items, s);                 \
+    case 13: return launch(KERNEL<1, 3 __VA_ARGS__>, 64, P, n_items, s);                 \
+    case 14: return launch(KERNEL<1, 4 __VA_ARGS__>, 64, P, n_items, s);                 \
+    case 22: return launch(KERNEL<2, 2 __VA_ARGS__>, 128, P, n_items, s);                \
+    case 23: return launch(KERNEL<2, 3 __VA_ARGS__>, 128, P, n_items, s);                \
+    case 24: return launch(KERNEL<2, 4 __VA_ARGS__>, 128, P, n_items, s);                \
+    case 42: return launch(KERNEL<4, 2 __VA_ARGS__>, 256, P, n_items, s);                \
+    case 43: return launch(KERNEL<4, 3 __VA_ARGS__>, 256, P, n_items, s);                \
+    case 44: return launch(KERNEL<4, 4 __VA_ARGS__>, 256, P, n_items, s);                \
+    default: return fs::fail(FS_EINVAL, "fs_decode_attention: no kernel for waves_per_group %d, prefetch_pages %d", \
+                             waves, nbuf - 1);                                           \
+  }
+
+  if (kv->kv_dtype == FS_KV_BF16) {
+    FS_PICK(decode_bf16_kernel)
+  }
+  if (G == 1) {
+#define FS_COMMA_ONE , 1
+    FS_PICK(decode_fp8_kernel, FS_COMMA_ONE)
+#undef FS_COMMA_ONE
+  }
+#undef FS_PICK
+  if (G <= 4) return launch(decode_fp8_kernel<2, 2, 4>, 128, P, n_items, s);
+  return launch(decode_fp8_kernel<1, 2, 8>, 64, P, n_items, s);
+}

@@ -1,0 +1,24 @@
+// Internal helpers shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <cstdarg>
+#include <cstdint>
+
+#include "failsafe.h"
+
+namespace fs {
+
+// Record a message for fs_last_error() and hand the status back.
+fs_status fail(fs_status st, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+constexpr int kHeadDim = 128;
+constexpr int kPageTokens = 16;
+constexpr int kMaxGroup = 16;       // q-heads per KV head that fit one MFMA tile column set
+constexpr int kMaxGroupFp8 = 8;
+
+struct Options {
+  int waves_per_group;   // wavefronts cooperating on one work item (1, 2 or 4)
+  int prefetch_pages;    // KV pages a wavefront keeps in flight ahead of the one it is consuming (1..3)
+};
+Options& options();
+
+}  // namespace fs

@@ -1,0 +1,178 @@
+// Host-side integer builders: head -> rank placement and one rank's work list.
+//
+// Placement follows the paper's Section 3.1: KV heads go round the ranks
+// cyclically with a rotating start (Cyclic Placement); a request is either
+// spread that way or kept whole on one rank (Hybrid Attention at request
+// granularity); whole requests go to the rank with the least running load
+// (Load-Aware DP-Rank Routing).  The work list is the ragged set of (request,
+// head) pairs this leaves on a rank, cut into split-K chunks, longest first.
+#include <algorithm>
+#include <limits>
+#include <numeric>
+#include <vector>
+
+#include "fs_internal.h"
+
+namespace {
+
+fs_status check_shape(const fs_shape* s, const char* who) {
+  if (!s) return fs::fail(FS_EINVAL, "%s: shape is NULL", who);
+  if (s->n_req < 0) return fs::fail(FS_EINVAL, "%s: n_req %d < 0", who, s->n_req);
+  if (s->n_ranks < 1) return fs::fail(FS_EINVAL, "%s: n_ranks %d < 1", who, s->n_ranks);
+  if (s->n_kv_heads < 1) return fs::fail(FS_EINVAL, "%s: n_kv_heads %d < 1", who, s->n_kv_heads);
+  return FS_OK;
+}
+
+inline int32_t floor_mod(int64_t a, int32_t m) {
+  int64_t r = a % m;
+  return static_cast<int32_t>(r < 0 ? r + m : r);
+}
+
+}  // namespace
+
+extern "C" fs_status fs_build_placement(const fs_shape* shape, const int32_t* ctx_len,
+                                        const uint8_t* mode, const int32_t* rot, int32_t layer,
+                                        int32_t* owner, int32_t* dp_rank, int64_t* rank_load) {
+  if (fs_status st = check_shape(shape, "fs_build_placement")) return st;
+  const int32_t B = shape->n_req, H = shape->n_kv_heads, R = shape->n_ranks;
+  if (!rank_load) return fs::fail(FS_EINVAL, "fs_build_placement: rank_load is NULL");
+  if (B > 0 && (!ctx_len || !mode || !owner || !dp_rank))
+    return fs::fail(FS_EINVAL, "fs_build_placement: NULL array with n_req %d", B);
+  for (int32_t r = 0; r < B; ++r) {
+    const int64_t L = ctx_len[r];
+    if (L < 1) return fs::fail(FS_EINVAL, "fs_build_placement: ctx_len[%d] = %d < 1", r, ctx_len[r]);
+    int32_t* own = owner + static_cast<int64_t>(r) * H;
+    if (mode[r] == FS_MODE_TP) {
+      const int64_t start = static_cast<int64_t>(rot ? rot[r] : r) + layer;
+      int32_t k = floor_mod(start, R);
+      for (int32_t h = 0; h < H; ++h) {
+        own[h] = k;
+        rank_load[k] += L;
+        if (++k == R) k = 0;
+      }
+      dp_rank[r] = -1;
+    } else if (mode[r] == FS_MODE_DP) {
+      int32_t best = 0;
+      for (int32_t k = 1; k < R; ++k)
+        if (rank_load[k] < rank_load[best]) best = k;   // strict: equal loads keep the lowest rank
+      std::fill(own, own + H, best);
+      dp_rank[r] = best;
+      rank_load[best] += static_cast<int64_t>(H) * L;
+    } else {
+      return fs::fail(FS_EINVAL, "fs_build_placement: mode[%d] = %d is neither TP nor DP", r, mode[r]);
+    }
+  }
+  return FS_OK;
+}
+
+extern "C" fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len,
+                                       const int32_t* owner, int32_t rank, int32_t chunk_tokens,
+                                       fs_work_item* items, int64_t items_cap,
+                                       fs_pair* pairs, int64_t pairs_cap,
+                                       int32_t* sched, int64_t* chunk_indptr,
+                                       int64_t* n_items, int64_t* n_pairs) {
+  if (fs_status st = check_shape(shape, "fs_build_worklist")) return st;
+  const int32_t B = shape->n_req, H = shape->n_kv_heads, R = shape->n_ranks;
+  if (!n_items || !n_pairs) return fs::fail(FS_EINVAL, "fs_build_worklist: count outputs are NULL");
+  if (shape->page_tokens < 1)
+    return fs::fail(FS_EINVAL, "fs_build_worklist: page_tokens %d < 1", shape->page_tokens);
+  if (shape->n_q_heads < H || shape->n_q_heads % H)
+    return fs::fail(FS_EINVAL, "fs_build_worklist: n_q_heads %d is not a multiple of n_kv_heads %d",
+                    shape->n_q_heads, H);
+  if (rank < 0 || rank >= R) return fs::fail(FS_EINVAL, "fs_build_worklist: rank %d outside [0, %d)", rank, R);
+  if (chunk_tokens < 0 || chunk_tokens % shape->page_tokens)
+    return fs::fail(FS_EINVAL, "fs_build_worklist: chunk_tokens %d is not a multiple of page_tokens %d",
+                    chunk_tokens, shape->page_tokens);
+  if (B > 0 && (!ctx_len || !owner)) return fs::fail(FS_EINVAL, "fs_build_worklist: NULL input array");
+  if ((items == nullptr) != (sched == nullptr) || (pairs == nullptr) != (chunk_indptr == nullptr))
+    return fs::fail(FS_EINVAL, "fs_build_worklist: items/sched and pairs/chunk_indptr come in pairs");
+  if (items_cap < 0 || pairs_cap < 0 || (!items && items_cap) || (!pairs && pairs_cap))
+    return fs::fail(FS_EINVAL, "fs_build_worklist: capacities do not match the arrays");
+  const int32_t G = shape->n_q_heads / H;
+  const int64_t C = chunk_tokens;
+
+  // Pass 1: validate and count, so that a short array is reported before anything is written.
+  int64_t ni = 0, np = 0;
+  for (int32_t r = 0; r < B; ++r) {
+    const int64_t L = ctx_len[r];
+    if (L < 1) return fs::fail(FS_EINVAL, "fs_build_worklist: ctx_len[%d] = %d < 1", r, ctx_len[r]);
+    const int64_t nc = C ? (L + C - 1) / C : 1;
+    for (int32_t h = 0; h < H; ++h) {
+      const int32_t k = owner[static_cast<int64_t>(r) * H + h];
+      if (k < 0 || k >= R)
+        return fs::fail(FS_EINVAL, "fs_build_worklist: owner[%d][%d] = %d outside [0, %d)", r, h, k, R);
+      if (k == rank) { ++np; ni += nc; }
+    }
+  }
+  *n_items = ni;
+  *n_pairs = np;
+  if (ni * G > std::numeric_limits<int32_t>::max() ||
+      static_cast<int64_t>(B) * shape->n_q_heads > std::numeric_limits<int32_t>::max())
+    return fs::fail(FS_EINVAL, "fs_build_worklist: row numbers exceed int32 (%lld items x G=%d)",
+                    static_cast<long long>(ni), G);
+  if (!items && !pairs) return FS_OK;
+  if ((items && items_cap < ni) || (pairs && pairs_cap < np))
+    return fs::fail(FS_ECAPACITY, "fs_build_worklist: need %lld items and %lld pairs, have room for %lld and %lld",
+                    static_cast<long long>(ni), static_cast<long long>(np),
+                    static_cast<long long>(items_cap), static_cast<long long>(pairs_cap));
+
+  // Pass 2: emit.
+  int64_t i = 0, p = 0;
+  for (int32_t r = 0; r < B; ++r) {
+    const int32_t L = ctx_len[r];
+    const int32_t nc = static_cast<int32_t>(C ? (L + C - 1) / C : 1);
+    for (int32_t h = 0; h < H; ++h) {
+      if (owner[static_cast<int64_t>(r) * H + h] != rank) continue;
+      if (pairs) {
+        pairs[p] = fs_pair{r, h, L, nc};
+        chunk_indptr[p] = i;
+      }
+      if (items) {
+        for (int32_t c = 0; c < nc; ++c) {
+          fs_work_item& it = items[i + c];
+          it.req = r;
+          it.kv_head = h;
+          it.tok_begin = C ? static_cast<int32_t>(c * C) : 0;
+          it.tok_end = C ? static_cast<int32_t>(std::min<int64_t>(L, (c + 1) * C)) : L;
+          it.pair = static_cast<int32_t>(p);
+          it.chunk = c;
+          it.q_row = r * shape->n_q_heads + h * G;
+          it.part_row = static_cast<int32_t>((i + c) * G);
+        }
+      }
+      i += nc;
+      ++p;
+    }
+  }
+  if (pairs) chunk_indptr[np] = ni;
+
+  if (items) {
+    // Longest first; equal lengths keep index order.  Lengths are bounded by the chunk size (or
+    // the longest context), so a counting sort keeps this linear for big batches.
+    int32_t max_len = 0;
+    for (int64_t j = 0; j < ni; ++j) max_len = std::max(max_len, items[j].tok_end - items[j].tok_begin);
+    if (static_cast<int64_t>(max_len) <= 4 * ni + 1024) {
+      std::vector<int64_t> start(static_cast<size_t>(max_len) + 2, 0);
+      for (int64_t j = 0; j < ni; ++j) ++start[max_len - (items[j].tok_end - items[j].tok_begin) + 1];
+      for (size_t b = 1; b < start.size(); ++b) start[b] += start[b - 1];
+      for (int64_t j = 0; j < ni; ++j)
+        sched[start[max_len - (items[j].tok_end - items[j].tok_begin)]++] = static_cast<int32_t>(j);
+    } else {
+      std::iota(sched, sched + ni, 0);
+      std::stable_sort(sched, sched + ni, [&](int32_t a, int32_t b) {
+        return items[a].tok_end - items[a].tok_begin > items[b].tok_end - items[b].tok_begin;
+      });
+    }
+  }
+  return FS_OK;
+}
+
+extern "C" int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, int32_t d) {
+  if (tok < 0 || tok >= fs::kPageTokens || d < 0 || d >= fs::kHeadDim) return -1;
+  if (kv_dtype == FS_KV_FP8_E4M3) return tok * fs::kHeadDim + d;
+  if (kv_dtype != FS_KV_BF16) return -1;
+  if (!is_v)   // K: [d/32][(d%32)/8][tok][d%8]: one 16-byte piece per (token, 8 d) in MFMA A-operand order
+    return (d / 32) * 512 + ((d % 32) / 8) * 128 + tok * 8 + (d % 8);
+  // V: [d/32][tok/4][d%16][(d/16)%2][tok%4]: four tokens of one d sit together (the MFMA reduces over tokens)
+  return (d / 32) * 512 + (tok / 4) * 128 + (d % 16) * 8 + ((d / 16) % 2) * 4 + (tok % 4);
+}

@@ -1,0 +1,174 @@
+"""The C++ host builders against the oracle, bit for bit (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2511_14116_amd as fs
+from workloads import CONFIGS, make_requests
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(fs.library_path()):
+        from paper_2511_14116_amd.build import build
+        build(verbose=False)
+    return fs.load_library()
+
+
+def _shape(B, Hq, Hkv, R, d=128, page=16):
+    return fs.FsShape(B, Hq, Hkv, d, page, R)
+
+
+def _items_as_rows(items):
+    return items.view(np.int32).reshape(-1, 8)
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "failsafe.h")) as f:
+        header = f.read()
+    declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
+    assert {"fs_build_placement", "fs_build_worklist", "fs_decode_attention", "fs_merge_lse",
+            "fs_kv_elem_offset", "fs_set_option", "fs_get_option", "fs_last_error",
+            "fs_abi_version"} <= declared
+    lib = C.CDLL(fs.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert fs.fs_abi_version() == 1
+
+
+def test_struct_sizes_match_the_header():
+    assert C.sizeof(fs.FsShape) == 24 and fs.ITEM_DTYPE.itemsize == 32 and fs.PAIR_DTYPE.itemsize == 16
+    assert C.sizeof(fs.FsKvView) == 80
+
+
+@pytest.mark.parametrize("cfg_id", sorted(CONFIGS))
+def test_configs_bit_exact(cfg_id):
+    w = make_requests(cfg_id)
+    sh = _shape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"])
+    owner, dp, load = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    o_owner, o_dp, o_load = oracle.build_placement(w["ctx_len"], w["mode"], w["n_ranks"], w["n_kv_heads"])
+    assert owner.tobytes() == o_owner.tobytes()
+    assert dp.tobytes() == o_dp.tobytes() and load.tobytes() == o_load.tobytes()
+    ranks = range(w["n_ranks"]) if cfg_id in (0, 3) else [0]
+    for k in ranks:
+        for chunk in sorted({w["chunk_tokens"], 0, 2048}):
+            items, pairs, sched, indptr = fs.fs_build_worklist(sh, w["ctx_len"], owner, k, chunk)
+            oi, op, osch, oind = oracle.build_worklist(w["ctx_len"], o_owner, k, chunk,
+                                                       w["n_q_heads"], w["n_kv_heads"])
+            assert _items_as_rows(items).tobytes() == oi.tobytes()
+            assert pairs.view(np.int32).reshape(-1, 4).tobytes() == op.tobytes()
+            assert sched.tobytes() == osch.tobytes() and indptr.tobytes() == oind.tobytes()
+
+
+def test_random_small_cases_bit_exact():
+    rng = np.random.default_rng(11)
+    for _ in range(300):
+        R = int(rng.integers(1, 9)); H = int(rng.integers(1, 9)); G = int(rng.integers(1, 5))
+        B = int(rng.integers(0, 12))
+        ctx = rng.integers(1, 400, size=B).astype(np.int32)
+        mode = (rng.random(B) < 0.4).astype(np.uint8)
+        rot = rng.integers(-20, 20, size=B).astype(np.int32) if rng.random() < 0.5 else None
+        layer = int(rng.integers(0, 5))
+        init = rng.integers(0, 1000, size=R)
+        sh = _shape(B, H * G, H, R)
+        owner, dp, load = fs.fs_build_placement(sh, ctx, mode, rot=rot, layer=layer, rank_load=init)
+        oo, od, ol = oracle.build_placement(ctx, mode, R, H, rot=rot, layer=layer, rank_load=init)
+        assert owner.tobytes() == oo.tobytes() and dp.tobytes() == od.tobytes() and load.tobytes() == ol.tobytes()
+        k = int(rng.integers(0, R)); chunk = int(rng.choice([0, 16, 32, 128]))
+        items, pairs, sched, indptr = fs.fs_build_worklist(sh, ctx, owner, k, chunk)
+        oi, op, osch, oind = oracle.build_worklist(ctx, oo, k, chunk, H * G, H)
+        assert _items_as_rows(items).tobytes() == oi.tobytes()
+        assert pairs.view(np.int32).reshape(-1, 4).tobytes() == op.tobytes()
+        assert sched.tobytes() == osch.tobytes() and indptr.tobytes() == oind.tobytes()
+
+
+def test_sched_sort_fallback_path_matches():
+    # few items with very different lengths take the comparison sort instead of the counting sort
+    ctx = np.array([100000, 7, 100000, 50000], dtype=np.int32)
+    sh = _shape(4, 2, 2, 1)
+    owner, _, _ = fs.fs_build_placement(sh, ctx, np.zeros(4, np.uint8))
+    items, pairs, sched, indptr = fs.fs_build_worklist(sh, ctx, owner, 0, 0)
+    _, _, osch, _ = oracle.build_worklist(ctx, owner, 0, 0, 2, 2)
+    assert sched.tolist() == osch.tolist() == [0, 1, 4, 5, 6, 7, 2, 3]
+
+
+def test_error_statuses():
+    sh = _shape(1, 4, 2, 3)
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_placement(sh, [0], [0])
+    assert e.value.status == fs.FS_EINVAL and "ctx_len" in str(e.value)
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_placement(sh, [5], [3])
+    assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError):
+        fs.fs_build_placement(_shape(1, 4, 2, 0), [5], [0])
+    owner = np.zeros((1, 2), np.int32)
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_worklist(sh, [5], owner, 3, 0)
+    assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_worklist(sh, [5], owner, 0, 24)
+    assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_worklist(sh, [5], np.full((1, 2), 7, np.int32), 0, 0)
+    assert e.value.status == fs.FS_EINVAL
+    # capacity: arrays too small -> FS_ECAPACITY
+    small = (np.empty(1, fs.ITEM_DTYPE), np.empty(1, fs.PAIR_DTYPE), np.empty(1, np.int32), np.empty(2, np.int64))
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_worklist(sh, [5], owner, 0, 0, out=small)
+    assert e.value.status == fs.FS_ECAPACITY and "2 items" in str(e.value)
+    with pytest.raises(fs.FsError):
+        fs.fs_set_option("waves_per_group", 3)
+    with pytest.raises(fs.FsError):
+        fs.fs_set_option("no_such_knob", 1)
+    assert fs.fs_get_option("no_such_knob") == -1 and fs.fs_get_option("waves_per_group") in (1, 2, 4)
+
+
+def test_device_entry_points_validate_before_touching_the_gpu():
+    sh = _shape(1, 4, 2, 3)
+    kv = fs.FsKvView()
+    fs.fs_decode_attention(sh, kv, None, None, 0, None, None)            # empty list: no-op
+    fs.fs_merge_lse(None, None, None, 0, 2, 128, None, None)             # no pairs: no-op
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention(sh, kv, None, None, 3, None, None)
+    assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention(_shape(1, 4, 2, 3, d=64), kv, None, None, 3, None, None)
+    assert e.value.status == fs.FS_EUNSUPPORTED
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention(_shape(1, 34, 2, 3), kv, None, None, 3, None, None)
+    assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_merge_lse(None, None, None, 4, 2, 64, None, None)
+    assert e.value.status == fs.FS_EUNSUPPORTED
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_merge_lse(None, None, None, 4, 2, 128, None, None)
+    assert e.value.status == fs.FS_EINVAL
+
+
+def test_slot_orders_are_permutations_with_the_documented_formulas():
+    for is_v in (False, True):
+        src = fs.slot_permutation(fs.FS_KV_BF16, is_v)
+        assert sorted(src.tolist()) == list(range(2048))
+    # K: 16-byte pieces (8 consecutive d of one token); lanes (d/8 % 4, tok) of a 64-lane load are contiguous
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 0, 0, 0) == 0
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 0, 1, 0) == 8
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 0, 0, 8) == 128
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 0, 0, 32) == 512
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 0, 15, 127) == 2047
+    # V: 4 consecutive tokens of one d sit together
+    assert [fs.fs_kv_elem_offset(fs.FS_KV_BF16, 1, t, 0) for t in range(5)] == [0, 1, 2, 3, 128]
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 1, 0, 16) == 4
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 1, 0, 1) == 8
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 1, 0, 32) == 512
+    assert np.array_equal(fs.slot_permutation(fs.FS_KV_FP8_E4M3, True), np.arange(2048))
+    assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 0, 16, 0) == -1 and fs.fs_kv_elem_offset(7, 0, 0, 0) == -1
+    x = np.arange(2 * 2048, dtype=np.uint16).reshape(2, 16, 128)
+    y = fs.pack_slots(x, fs.FS_KV_BF16, False)
+    assert y[1].reshape(-1)[8] == 2048 + 1 * 128 + 0
