@@ -181,7 +181,7 @@ FS_API int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, in
  *     part_lse[part_row+g] = ln sum_t exp(s_t)
  *     part_o[part_row+g][:] = sum_t exp(s_t - lse) * V_t
  * Scores, softmax and accumulation are fp32; the softmax weights enter the
- * P.V product rounded to bf16.  Tokens at or beyond tok_end are never used,
+ * P.V product as a sum of two bf16 terms (16 significant bits).  Tokens at or beyond tok_end are never used,
  * whatever their bits.
  *
  *  items_dev  DEVICE in  [n_items]     as built by fs_build_worklist

@@ -14,7 +14,7 @@
 //   ahead of the arithmetic.  Per page:
 //     S^T[tok][q] = K . Q^T      4 x v_mfma_f32_16x16x32_bf16   (A = K page, B = Q^T)
 //     online softmax in fp32, log2 domain; a lane owns q-head lane%16 and tokens 4*(lane/16)+r
-//     O^T[d][q]  += V^T . P^T    8 x v_mfma_f32_16x16x16_bf16   (A = V page, B = P^T as bf16)
+//     O^T[d][q]  += V^T . P^T    16 x v_mfma_f32_16x16x16_bf16  (A = V page, B = P^T as bf16 hi + lo)
 //   The S^T accumulator layout is exactly the B-operand layout of the second product, so the
 //   softmax weights never move between lanes; only the running max needs a 2-step cross-lane
 //   exchange.  Wavefronts merge (max, sum, O) through LDS at the end of the item.
@@ -145,12 +145,20 @@ __device__ __forceinline__ void consume_page(SoftmaxState& st, PageRegs& pg, con
 #pragma unroll
   for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(x[r] - st.m);
   st.l += (p[0] + p[1]) + (p[2] + p[3]);
-  const s16x4 pb = __builtin_bit_cast(s16x4, __builtin_convertvector(p, bf16x4));
+  // The weights enter the matrix cores as bf16.  One bf16 keeps 8 bits, which for a short context
+  // (weights near 1/2) costs ~2e-3 of |V| - the whole error budget.  Splitting p = hi + lo into two
+  // bf16 terms keeps 16 bits; the second product rides on matrix-core time that is idle anyway.
+  const bf16x4 ph = __builtin_convertvector(p, bf16x4);
+  const bf16x4 pl = __builtin_convertvector(p - __builtin_convertvector(ph, f32x4), bf16x4);
+  const s16x4 pb = __builtin_bit_cast(s16x4, ph), pc = __builtin_bit_cast(s16x4, pl);
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const uint2 lo = make_uint2(pg.v[c].x, pg.v[c].y), hi = make_uint2(pg.v[c].z, pg.v[c].w);
-    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pb, st.acc[2 * c], 0, 0, 0);
-    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pb, st.acc[2 * c + 1], 0, 0, 0);
+    const s16x4 va = __builtin_bit_cast(s16x4, lo), vb = __builtin_bit_cast(s16x4, hi);
+    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb, st.acc[2 * c], 0, 0, 0);
+    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pb, st.acc[2 * c + 1], 0, 0, 0);
+    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pc, st.acc[2 * c], 0, 0, 0);
+    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pc, st.acc[2 * c + 1], 0, 0, 0);
   }
 }
 

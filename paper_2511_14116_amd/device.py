@@ -1,0 +1,83 @@
+"""Device-side plumbing for one rank's share: torch owns the memory and the stream, the
+library does every step of the path.  Used by the GPU tests, the smoke check and bench.py."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .layout import pack_slots
+
+_KV_CODE = {"bf16": B.FS_KV_BF16, "fp8": B.FS_KV_FP8_E4M3}
+
+
+class DeviceShare:
+    """Q, the paged K/V pool (repacked into kernel order) and the page table on the GPU."""
+
+    def __init__(self, shape: B.FsShape, q_bits: np.ndarray, kv: dict, sm_scale: float,
+                 interleave_kv: bool = True, device: str = "cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("DeviceShare needs a GPU; there is no CPU fallback")
+        self.shape = shape
+        self.device = torch.device(device)
+        self.group = shape.n_q_heads // shape.n_kv_heads
+        self.kv_dtype = _KV_CODE[kv["kv_dtype"]]
+        self.q = torch.from_numpy(q_bits.view(np.int16)).to(self.device)
+        tdt = torch.int16 if self.kv_dtype == B.FS_KV_BF16 else torch.uint8
+        view = (lambda a: a.view(np.int16)) if self.kv_dtype == B.FS_KV_BF16 else (lambda a: a)
+        k = pack_slots(torch.from_numpy(view(kv["k_pool"])).to(self.device), self.kv_dtype, False)
+        v = pack_slots(torch.from_numpy(view(kv["v_pool"])).to(self.device), self.kv_dtype, True)
+        n_slots, T, D = k.shape
+        slot_bytes = T * D * k.element_size()
+        if interleave_kv:
+            # K and V of a slot side by side: one 2*slot_bytes run per (page, head)
+            both = torch.empty((n_slots, 2, T * D), dtype=tdt, device=self.device)
+            both[:, 0] = k.reshape(n_slots, -1)
+            both[:, 1] = v.reshape(n_slots, -1)
+            del k, v
+            self._pool = both
+            k_ptr, v_ptr = both.data_ptr(), both.data_ptr() + slot_bytes
+            k_stride = v_stride = 2 * slot_bytes
+        else:
+            self._pool = (k, v)
+            k_ptr, v_ptr = k.data_ptr(), v.data_ptr()
+            k_stride = v_stride = slot_bytes
+        self.k_scale = self.v_scale = None
+        if kv["k_scale"] is not None:
+            self.k_scale = torch.from_numpy(kv["k_scale"]).to(self.device)
+            self.v_scale = torch.from_numpy(kv["v_scale"]).to(self.device)
+        self.page_indptr = torch.from_numpy(kv["page_indptr"]).to(self.device)
+        self.page_ids = torch.from_numpy(kv["page_ids"]).to(self.device)
+        self.view = B.FsKvView(
+            q=self.q.data_ptr(), k_pool=k_ptr, v_pool=v_ptr, k_slot_stride=k_stride, v_slot_stride=v_stride,
+            k_scale=None if self.k_scale is None else self.k_scale.data_ptr(),
+            v_scale=None if self.v_scale is None else self.v_scale.data_ptr(),
+            page_indptr=self.page_indptr.data_ptr(), page_ids=self.page_ids.data_ptr(),
+            kv_dtype=self.kv_dtype, sm_scale=float(sm_scale))
+        self.kv_bytes = int(kv["page_indptr"][-1]) * 2 * slot_bytes
+        self.n_items = self.n_pairs = 0
+
+    def set_worklist(self, items: np.ndarray, pairs: np.ndarray, sched: np.ndarray, chunk_indptr: np.ndarray):
+        """Upload a work list and size the partial and final output buffers for it."""
+        self.n_items, self.n_pairs = len(items), len(pairs)
+        G, D = self.group, self.shape.head_dim
+        dev = self.device
+        self.items = torch.from_numpy(np.ascontiguousarray(items).view(np.int32).reshape(-1, 8)).to(dev)
+        self.sched = torch.from_numpy(np.ascontiguousarray(sched)).to(dev)
+        self.chunk_indptr = torch.from_numpy(np.ascontiguousarray(chunk_indptr)).to(dev)
+        self.part_o = torch.full((self.n_items * G, D), float("nan"), dtype=torch.float32, device=dev)
+        self.part_lse = torch.full((self.n_items * G,), float("nan"), dtype=torch.float32, device=dev)
+        self.out = torch.full((self.n_pairs * G, D), float("nan"), dtype=torch.float32, device=dev)
+        self.lse = torch.full((self.n_pairs * G,), float("nan"), dtype=torch.float32, device=dev)
+
+    def decode(self, use_sched: bool = True):
+        B.fs_decode_attention(self.shape, self.view, self.items, self.sched if use_sched else None,
+                              self.n_items, self.part_o, self.part_lse, torch.cuda.current_stream().cuda_stream)
+
+    def merge(self):
+        B.fs_merge_lse(self.part_o, self.part_lse, self.chunk_indptr, self.n_pairs, self.group,
+                       self.shape.head_dim, self.out, self.lse, torch.cuda.current_stream().cuda_stream)
+
+    def run(self, use_sched: bool = True):
+        self.decode(use_sched)
+        self.merge()

@@ -1,0 +1,314 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: placement maps and work lists bit-exact; fp32 outputs within 2e-3 abs + 1e-2 rel of the
+fp64 oracle; LSE within 1e-3.  Every input is seeded and synthetic.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_14116_amd as fs
+from paper_2511_14116_amd.device import DeviceShare
+from workloads import make_requests, make_q, make_kv_pool
+
+pytestmark = pytest.mark.gpu
+
+ABS_TOL, REL_TOL, LSE_TOL = 2e-3, 1e-2, 1e-3
+
+
+def say(msg):
+    print(f"[parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(fs.library_path()):
+        raise RuntimeError("libfailsafe.so is not built: GPU tests never fall back to anything else")
+    fs.load_library()
+    yield
+    fs.fs_set_option("waves_per_group", 4)
+    fs.fs_set_option("prefetch_pages", 2)
+
+
+def check(out, lse, ref_o, ref_l, what):
+    out = np.asarray(out, dtype=np.float64); lse = np.asarray(lse, dtype=np.float64)
+    assert np.isfinite(out).all() and np.isfinite(lse).all(), f"{what}: non-finite output"
+    err = np.abs(out - ref_o)
+    tol = ABS_TOL + REL_TOL * np.abs(ref_o)
+    worst = float((err / tol).max()) if err.size else 0.0
+    lerr = float(np.abs(lse - ref_l).max()) if lse.size else 0.0
+    say(f"{what}: max err/tol {worst:.3f}, max |err| {float(err.max()) if err.size else 0:.2e}, lse err {lerr:.2e}")
+    assert worst <= 1.0, f"{what}: output outside 2e-3 + 1e-2*|ref| (worst ratio {worst})"
+    assert lerr <= LSE_TOL, f"{what}: lse off by {lerr}"
+
+
+def shape_of(w):
+    return fs.FsShape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["head_dim"], w["page_tokens"], w["n_ranks"])
+
+
+def run_rank(w, q, rank, chunk, owner, interleave=True, use_sched=True, pairs_subset=None):
+    """Build rank's list with the library, run the kernels, return everything needed to compare."""
+    sh = shape_of(w)
+    items, pairs, sched, indptr = fs.fs_build_worklist(sh, w["ctx_len"], owner, rank, chunk)
+    kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1) if len(pairs) else np.zeros((0, 2)),
+                      w["ctx_len"], kv_dtype=w["kv_dtype"])
+    ds = DeviceShare(sh, q, kv, w["sm_scale"], interleave_kv=interleave)
+    ds.set_worklist(items, pairs, sched, indptr)
+    ds.run(use_sched=use_sched)
+    torch.cuda.synchronize()
+    return ds, kv, items, pairs, sched, indptr
+
+
+def pairs_rows(pairs):
+    return pairs.view(np.int32).reshape(-1, 4)
+
+
+def items_rows(items):
+    return items.view(np.int32).reshape(-1, 8)
+
+
+# ------------------------------------------------------------------------------------------------
+def test_config0_every_rank_and_reassembly():
+    """Tiny all-TP batch, R=7: each rank's share against the oracle, then all shares gathered by
+    head against unsharded attention for every (request, q-head)."""
+    w = make_requests(0)
+    q = make_q(w["seed"], w["n_req"], w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, dp, load = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    o_owner, o_dp, o_load = oracle.build_placement(w["ctx_len"], w["mode"], w["n_ranks"], w["n_kv_heads"])
+    assert owner.tobytes() == o_owner.tobytes() and load.tobytes() == o_load.tobytes()
+    G = w["group"]
+    B, Hq = w["n_req"], w["n_q_heads"]
+    full_o = np.full((B, Hq, 128), np.nan); full_l = np.full((B, Hq), np.nan)
+    for k in range(w["n_ranks"]):
+        say(f"config 0 rank {k}")
+        ds, kv, items, pairs, sched, indptr = run_rank(w, q, k, w["chunk_tokens"], owner)
+        oi, op, osch, oind = oracle.build_worklist(w["ctx_len"], o_owner, k, w["chunk_tokens"], Hq, w["n_kv_heads"])
+        assert items_rows(items).tobytes() == oi.tobytes() and sched.tobytes() == osch.tobytes()
+        ref_o, ref_l = oracle.decode_attention_pairs(q, kv, op, Hq, G, w["sm_scale"])
+        out, lse = ds.out.cpu().numpy(), ds.lse.cpu().numpy()
+        check(out, lse, ref_o, ref_l, f"cfg0 rank {k}")
+        for p, (r, h, L, _n) in enumerate(op):
+            full_o[r, h * G:(h + 1) * G] = out[p * G:(p + 1) * G]
+            full_l[r, h * G:(h + 1) * G] = lse[p * G:(p + 1) * G]
+    all_pairs = np.array([(r, h) for r in range(B) for h in range(w["n_kv_heads"])])
+    kv_all = make_kv_pool(w["seed"], all_pairs, w["ctx_len"])
+    un_o, un_l = oracle.unsharded_attention(q, kv_all, w["ctx_len"], Hq, w["n_kv_heads"], w["sm_scale"])
+    check(full_o, full_l, un_o, un_l, "cfg0 all ranks gathered vs unsharded")
+
+
+@pytest.mark.parametrize("waves", [1, 2, 4])
+@pytest.mark.parametrize("prefetch", [1, 2, 3])
+def test_launch_shapes_on_ragged_lengths(waves, prefetch):
+    """Every wavefront count and prefetch depth on lengths that hit all loop phases: fewer pages
+    than wavefronts, exact multiples, one token, ragged tails."""
+    fs.fs_set_option("waves_per_group", waves)
+    fs.fs_set_option("prefetch_pages", prefetch)
+    lens = [1, 2, 15, 16, 17, 31, 32, 33, 47, 48, 64, 65, 95, 96, 97, 127, 128, 129, 160, 161, 255, 256,
+            257, 300, 511, 512, 513, 700, 1000, 1023, 1024, 1025]
+    w = make_requests(0, n_req=len(lens))
+    w["ctx_len"] = np.array(lens, dtype=np.int32)
+    w["n_ranks"] = 3
+    q = make_q(w["seed"] + 1, w["n_req"], w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    for chunk in (0, 256):
+        say(f"ragged waves={waves} prefetch={prefetch} chunk={chunk}")
+        ds, kv, items, pairs, sched, indptr = run_rank(w, q, 1, chunk, owner)
+        ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
+        check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"ragged w{waves} p{prefetch} c{chunk}")
+    fs.fs_set_option("waves_per_group", 4)
+    fs.fs_set_option("prefetch_pages", 2)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (12, 4), (32, 8), (64, 8), (32, 2)])
+def test_group_sizes(Hq, Hkv):
+    """G = 1, 2, 3, 4, 8, 16 q-heads per KV head."""
+    rng = np.random.default_rng(Hq * 100 + Hkv)
+    B = 6
+    w = make_requests(1, n_req=B)
+    w.update(n_q_heads=Hq, n_kv_heads=Hkv, group=Hq // Hkv, n_ranks=3,
+             ctx_len=rng.integers(1, 900, size=B).astype(np.int32), mode=np.array([0, 1, 0, 1, 0, 0], np.uint8))
+    q = make_q(w["seed"] + 2, B, Hq, 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    for k in range(3):
+        say(f"group Hq={Hq} Hkv={Hkv} rank {k}")
+        ds, kv, items, pairs, sched, indptr = run_rank(w, q, k, 128, owner)
+        if len(pairs) == 0:
+            continue
+        ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), Hq, Hq // Hkv, w["sm_scale"])
+        check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"G={Hq // Hkv} rank {k}")
+
+
+def test_partials_and_merge_separately():
+    """fs_decode_attention's per-item partials and fs_merge_lse, each against its own oracle twin."""
+    w = make_requests(1, n_req=12, max_len=3000)
+    q = make_q(w["seed"], 12, w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 256, owner)
+    G = w["group"]
+    po, pl = oracle.decode_attention_items(q, kv, items_rows(items), G, w["sm_scale"])
+    check(ds.part_o.cpu().numpy(), ds.part_lse.cpu().numpy(), po, pl, "partials, chunk 256")
+    # merge alone, on the oracle's own partials rounded to fp32 (so only the merge is under test)
+    po32 = torch.from_numpy(po.astype(np.float32)).cuda(); pl32 = torch.from_numpy(pl.astype(np.float32)).cuda()
+    out = torch.empty((len(pairs) * G, 128), dtype=torch.float32, device="cuda"); lse = torch.empty(len(pairs) * G, dtype=torch.float32, device="cuda")
+    fs.fs_merge_lse(po32, pl32, ds.chunk_indptr, len(pairs), G, 128, out, lse, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    mo, ml = oracle.merge_lse(po32.cpu().numpy().astype(np.float64), pl32.cpu().numpy().astype(np.float64), indptr, G)
+    check(out.cpu().numpy(), lse.cpu().numpy(), mo, ml, "merge alone")
+
+
+def test_merge_with_widely_spread_lse():
+    """Chunks whose lse differ by hundreds: weights underflow to zero without NaN."""
+    rng = np.random.default_rng(5)
+    G, n_pairs = 4, 9
+    counts = [1, 2, 3, 5, 8, 1, 17, 64, 2]
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    n_items = int(indptr[-1])
+    po = rng.standard_normal((n_items * G, 128)).astype(np.float32)
+    pl = (rng.standard_normal(n_items * G) * 60).astype(np.float32)
+    out = torch.empty((n_pairs * G, 128), dtype=torch.float32, device="cuda"); lse = torch.empty(n_pairs * G, dtype=torch.float32, device="cuda")
+    fs.fs_merge_lse(torch.from_numpy(po).cuda(), torch.from_numpy(pl).cuda(), torch.from_numpy(indptr).cuda(),
+                    n_pairs, G, 128, out, lse, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    mo, ml = oracle.merge_lse(po.astype(np.float64), pl.astype(np.float64), indptr, G)
+    check(out.cpu().numpy(), lse.cpu().numpy(), mo, ml, "merge, spread lse")
+
+
+def test_single_key_closed_form_and_layout_variants():
+    """L = 1: out is the V row exactly (weight 1.0 is exact in bf16) and lse is the score; the same
+    share gives the same bits with K/V interleaved or in two pools, scheduled or in index order."""
+    w = make_requests(0, n_req=8)
+    w["ctx_len"] = np.array([1, 1, 1, 16, 17, 1, 300, 1], dtype=np.int32)
+    q = make_q(w["seed"], 8, w["n_q_heads"], 128)
+    sh = shape_of(w)
+    w["n_ranks"] = 1; sh.n_ranks = 1
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 0, owner)
+    out = ds.out.cpu().numpy(); lse = ds.lse.cpu().numpy()
+    G = w["group"]
+    for p, (r, h, L, _n) in enumerate(pairs_rows(pairs)):
+        if L != 1:
+            continue
+        K, V = oracle.gather_pair_kv(kv, p, 0, 1)
+        for g in range(G):
+            assert np.array_equal(out[p * G + g].astype(np.float64), V[0]), "single key must return its V row"
+            s = w["sm_scale"] * float(oracle.bf16_bits_to_f64(q[r, h * G + g]) @ K[0])
+            assert abs(lse[p * G + g] - s) < 1e-5 * max(1.0, abs(s))
+    ds2, *_ = run_rank(w, q, 0, 0, owner, interleave=False, use_sched=False)
+    assert torch.equal(ds.out, ds2.out) and torch.equal(ds.lse, ds2.lse)
+
+
+def test_unused_slots_and_page_tails_are_never_read():
+    """The generator poisons spare slots and the tail of each last page with NaN patterns; a finite
+    result on lengths with every tail size proves they were not used."""
+    lens = list(range(1, 34))
+    w = make_requests(0, n_req=len(lens))
+    w["ctx_len"] = np.array(lens, dtype=np.int32); w["n_ranks"] = 2
+    q = make_q(w["seed"], len(lens), w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 16, owner)
+    ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
+    check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, "poisoned tails, chunk 16")
+
+
+def test_large_scores_stay_finite():
+    """Scores around +-90 (softmax scale 1.0): the running-max rescale keeps everything finite."""
+    w = make_requests(0, n_req=4)
+    w["ctx_len"] = np.array([200, 77, 1024, 33], dtype=np.int32); w["n_ranks"] = 1
+    w["sm_scale"] = 1.0
+    q = make_q(w["seed"], 4, w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 128, owner)
+    ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], 1.0)
+    # with near one-hot weights the lse is ~|score|: compare it relatively
+    out = ds.out.cpu().numpy().astype(np.float64); lse = ds.lse.cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    assert (np.abs(out - ref_o) <= ABS_TOL + REL_TOL * np.abs(ref_o) + 2e-2).all()
+    assert (np.abs(lse - ref_l) <= 1e-5 * np.abs(ref_l) + 1e-3).all()
+
+
+def test_empty_rank_is_a_no_op():
+    w = make_requests(0, n_req=1)
+    w["ctx_len"] = np.array([40], dtype=np.int32); w["mode"] = np.array([1], np.uint8)
+    q = make_q(w["seed"], 1, w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, dp, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    empty = [k for k in range(w["n_ranks"]) if k != dp[0]][0]
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, empty, 0, owner)
+    assert ds.n_items == 0 and ds.n_pairs == 0 and ds.out.numel() == 0
+
+
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("G,Hkv", [(1, 8), (4, 2)])
+def test_fp8_small(G, Hkv):
+    rng = np.random.default_rng(G)
+    B = 10
+    w = make_requests(4, n_req=B)
+    w.update(n_q_heads=G * Hkv, n_kv_heads=Hkv, group=G, n_ranks=3,
+             ctx_len=np.array([1, 7, 16, 17, 100, 129, 512, 777, 1500, 2048], dtype=np.int32))
+    q = make_q(w["seed"], B, G * Hkv, 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    for k in range(3):
+        for chunk in (0, 512):
+            say(f"fp8 G={G} rank {k} chunk {chunk}")
+            ds, kv, items, pairs, sched, indptr = run_rank(w, q, k, chunk, owner)
+            ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), G * Hkv, G, w["sm_scale"])
+            check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"fp8 G={G} rank {k} chunk {chunk}")
+
+
+# ------------------------------------------------------------------------------------------------
+def _full_config(cfg_id, rank, n_sample, **req_kw):
+    """A config at its full size in the launch shape the benchmark times; the oracle checks a sample
+    of pairs one by one (the longest, the shortest and seeded random ones)."""
+    w = make_requests(cfg_id, **req_kw)
+    q = make_q(w["seed"], w["n_req"], w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, dp, load = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    o_owner, _, o_load = oracle.build_placement(w["ctx_len"], w["mode"], w["n_ranks"], w["n_kv_heads"])
+    assert owner.tobytes() == o_owner.tobytes() and load.tobytes() == o_load.tobytes()
+    say(f"config {cfg_id} rank {rank}: generating pool")
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, rank, w["chunk_tokens"], owner)
+    oi, op, osch, oind = oracle.build_worklist(w["ctx_len"], o_owner, rank, w["chunk_tokens"], w["n_q_heads"], w["n_kv_heads"])
+    assert items_rows(items).tobytes() == oi.tobytes() and sched.tobytes() == osch.tobytes() and indptr.tobytes() == oind.tobytes()
+    say(f"config {cfg_id} rank {rank}: {len(pairs)} pairs, {len(items)} items, {ds.kv_bytes / 1e6:.1f} MB of K+V")
+    out = ds.out.cpu().numpy(); lse = ds.lse.cpu().numpy()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    rng = np.random.default_rng(cfg_id)
+    L = op[:, 2]
+    pick = {int(np.argmax(L)), int(np.argmin(L))} | set(rng.choice(len(op), size=min(n_sample, len(op)), replace=False).tolist())
+    G = w["group"]
+    for p in sorted(pick):
+        sub = op[p:p + 1]
+        # gather_pair_kv indexes by pair number: give it a one-pair view
+        view = dict(kv, page_indptr=np.array([0, kv["page_indptr"][p + 1] - kv["page_indptr"][p]]),
+                    page_ids=kv["page_ids"][kv["page_indptr"][p]:kv["page_indptr"][p + 1]])
+        ref_o, ref_l = oracle.decode_attention_pairs(q, view, sub, w["n_q_heads"], G, w["sm_scale"])
+        check(out[p * G:(p + 1) * G], lse[p * G:(p + 1) * G], ref_o, ref_l, f"cfg{cfg_id} rank {rank} pair {p} (L={L[p]})")
+    return ds
+
+
+def test_config1_full_size_sampled():
+    _full_config(1, 0, 24)
+
+
+def test_config2_full_size_sampled():
+    _full_config(2, 0, 16)
+
+
+def test_config3_forced_tail_sampled():
+    _full_config(3, 0, 12, force_first_len=131072)
+
+
+def test_config4_fp8_full_size_sampled():
+    _full_config(4, 0, 24)
