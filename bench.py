@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark: one GPU's cyclic/hybrid decode-attention share on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--rank k]
+
+A step is one pass of the whole hot path over one synthetic batch: placement (S1+S2) and the
+rank's work list (S3) built on the host by the library, the list copied to the GPU, the
+attention sweep (S4) and the split-K merge (S5).  Q, the paged K/V pool and the page table are
+resident in HBM before the timed region starts.  Host work for step t+1 overlaps the GPU work
+of step t (nothing synchronises inside the timed region), as it would in a serving loop.
+
+Prints ONE JSON line.  `value` is algorithmic GB/s of the whole step; `roofline` is the
+attention kernel alone against the HBM peak; `cpu_baseline` is the fp64 oracle timed on this
+box's host cores (context, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
+# (see profiles/); None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="synthetic batch 0..4 (2 = 70B-shaped, the target)")
+    ap.add_argument("--rank", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=None, help="override the split-K chunk (tokens)")
+    ap.add_argument("--waves", type=int, default=None)
+    ap.add_argument("--prefetch", type=int, default=None)
+    ap.add_argument("--separate-kv", action="store_true", help="K and V in two pools instead of interleaved")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--force-tail", action="store_true", help="config 3: request 0 gets 131072 tokens")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (one rank's share at its real shape); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2511_14116_amd as fs
+    from workloads import make_requests, make_q, make_kv_pool
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path to time", file=sys.stderr)
+        return 2
+    if not os.path.exists(fs.library_path()):
+        from paper_2511_14116_amd.build import build
+        build(verbose=False)
+    fs.load_library()
+    if args.waves:
+        fs.fs_set_option("waves_per_group", args.waves)
+    if args.prefetch:
+        fs.fs_set_option("prefetch_pages", args.prefetch)
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+    sptr = stream.cuda_stream
+
+    # ---- synthetic batch ---------------------------------------------------------------------
+    kw = dict(force_first_len=131072) if (args.config == 3 and args.force_tail) else {}
+    w = make_requests(args.config, **kw)
+    chunk = w["chunk_tokens"] if args.chunk is None else args.chunk
+    B, Hq, Hkv, R, G = w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"], w["group"]
+    shape = fs.FsShape(B, Hq, Hkv, w["head_dim"], w["page_tokens"], R)
+    ctx, mode = w["ctx_len"], w["mode"]
+    q_bits = make_q(w["seed"], B, Hq, w["head_dim"])
+    owner, dp_rank, rank_load = fs.fs_build_placement(shape, ctx, mode)
+    items, pairs, sched, chunk_indptr = fs.fs_build_worklist(shape, ctx, owner, args.rank, chunk)
+    n_items, n_pairs = len(items), len(pairs)
+    if n_items == 0:
+        print("bench.py: this rank's share is empty", file=sys.stderr)
+        return 2
+    kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx, kv_dtype=w["kv_dtype"])
+
+    from paper_2511_14116_amd.device import DeviceShare
+    ds = DeviceShare(shape, q_bits, kv, w["sm_scale"], interleave_kv=not args.separate_kv)
+
+    # ---- algorithmic bytes ---------------------------------------------------------------------
+    tok_heads = int(rank_load[args.rank])
+    n_pages = int(kv["page_indptr"][-1])
+    elt = 2 if w["kv_dtype"] == "bf16" else 1
+    kv_bytes = tok_heads * 2 * w["head_dim"] * elt          # K and V rows actually attended
+    scale_bytes = n_pages * 8 if w["kv_dtype"] == "fp8" else 0
+    q_bytes = n_pairs * G * w["head_dim"] * 2
+    table_bytes = n_pages * 4 + n_items * 32 + n_items * 4
+    part_bytes = n_items * G * (w["head_dim"] * 4 + 4)
+    out_bytes = n_pairs * G * (w["head_dim"] * 4 + 4)
+    decode_bytes = kv_bytes + scale_bytes + q_bytes + table_bytes + part_bytes
+    merge_bytes = part_bytes + out_bytes + (n_pairs + 1) * 8
+    step_bytes = decode_bytes + merge_bytes
+
+    # ---- device buffers for the per-step work list -----------------------------------------------
+    def up(x):
+        return (x + 255) & ~255
+    off_items = 0
+    off_sched = up(off_items + n_items * 32)
+    off_indptr = up(off_sched + n_items * 4)
+    blob_bytes = up(off_indptr + (n_pairs + 1) * 8)
+    dev_blob = torch.empty(blob_bytes, dtype=torch.uint8, device=dev)
+    n_host = 4
+    host_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(n_host)]
+    host_events = [torch.cuda.Event() for _ in range(n_host)]
+    host_views = []
+    for hb in host_blobs:
+        a = hb.numpy()
+        host_views.append((a[off_items:off_items + n_items * 32].view(fs.ITEM_DTYPE),
+                           np.empty(n_pairs, dtype=fs.PAIR_DTYPE),
+                           a[off_sched:off_sched + n_items * 4].view(np.int32),
+                           a[off_indptr:off_indptr + (n_pairs + 1) * 8].view(np.int64)))
+    items_ptr = dev_blob.data_ptr() + off_items
+    sched_ptr = dev_blob.data_ptr() + off_sched
+    indptr_ptr = dev_blob.data_ptr() + off_indptr
+    part_o = torch.empty((n_items * G, w["head_dim"]), dtype=torch.float32, device=dev)
+    part_lse = torch.empty(n_items * G, dtype=torch.float32, device=dev)
+    out = torch.empty((n_pairs * G, w["head_dim"]), dtype=torch.float32, device=dev)
+    lse = torch.empty(n_pairs * G, dtype=torch.float32, device=dev)
+
+    host_us = []
+
+    def step(i: int, ev=None):
+        t0 = time.perf_counter()
+        hb = i % n_host
+        host_events[hb].synchronize()                       # the copy that last used this buffer is done
+        own, _dp, _load = fs.fs_build_placement(shape, ctx, mode)                          # S1 + S2
+        fs.fs_build_worklist(shape, ctx, own, args.rank, chunk, out=host_views[hb])        # S3
+        dev_blob.copy_(host_blobs[hb], non_blocking=True)
+        host_events[hb].record(stream)
+        host_us.append((time.perf_counter() - t0) * 1e6)
+        if ev is not None:
+            ev[0].record(stream)
+        fs.fs_decode_attention(shape, ds.view, items_ptr, sched_ptr, n_items, part_o, part_lse, sptr)   # S4
+        if ev is not None:
+            ev[1].record(stream)
+        fs.fs_merge_lse(part_o, part_lse, indptr_ptr, n_pairs, G, w["head_dim"], out, lse, sptr)        # S5
+        if ev is not None:
+            ev[2].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    host_us.clear()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    dec_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
+    mrg_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
+
+    # sanity: the timed configuration produced finite numbers
+    if not (torch.isfinite(out).all().item() and torch.isfinite(lse).all().item()):
+        print("bench.py: non-finite output", file=sys.stderr)
+        return 1
+
+    # ---- stream-read probe over the same pool ----------------------------------------------------
+    probe_gbs = None
+    if not args.no_probe:
+        pool = ds._pool if not isinstance(ds._pool, tuple) else ds._pool[0]
+        nbytes = (pool.numel() * pool.element_size()) & ~15
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        for _ in range(3):
+            fs.fs_stream_read_probe(pool, nbytes, sink, sptr)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        e0.record(stream)
+        for _ in range(reps):
+            fs.fs_stream_read_probe(pool, nbytes, sink, sptr)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        probe_gbs = nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    # ---- CPU baseline: the oracle on this machine's host cores ---------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = min(16, len(os.sched_getaffinity(0)))
+        pr = pairs.view(np.int32).reshape(-1, 4)
+        budget = 12_000_000                      # tok.heads: keeps this leg to some tens of seconds
+        csum = np.cumsum(pr[:, 2].astype(np.int64))
+        n_s = int(min(len(pr), max(1, np.searchsorted(csum, budget) + 1)))
+        t1 = time.perf_counter()
+        oo, ol = oracle.decode_attention_pairs(q_bits, kv, pr[:n_s], Hq, G, w["sm_scale"], workers=cores)
+        dt = time.perf_counter() - t1
+        s_tok = int(csum[n_s - 1])
+        got = out[: n_s * G].cpu().numpy().astype(np.float64)
+        err_ok = bool((np.abs(got - oo) <= 2e-3 + 1e-2 * np.abs(oo)).all()
+                      and (np.abs(lse[: n_s * G].cpu().numpy() - ol) <= 1e-3).all())
+        cpu = {"value": round(s_tok * 2 * w["head_dim"] * elt / dt / 1e9, 4), "unit": "GB/s", "cores": cores,
+               "kind": "oracle", "sample": f"first {n_s} of {n_pairs} pairs of rank {args.rank} "
+               f"({s_tok} KV-token-heads), fp64 numpy, {dt:.2f} s",
+               "kv_token_heads_per_s": round(s_tok / dt, 1), "gpu_matches_oracle_on_sample": err_ok}
+
+    dec_avg_ms = float(dec_ms.mean())
+    achieved = decode_bytes / (dec_avg_ms * 1e-3) / 1e9
+    key = f"cfg{args.config}_rank{args.rank}"
+    result = {
+        "metric": "achieved HBM GB/s (% of peak) and KV-token-heads/s, rank-0 share, 1 MI355X",
+        "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w["kv_dtype"] == "bf16" else "fp8_e4m3",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {w['name']}: B={B}, Hq={Hq}, Hkv={Hkv}, d=128, page=16, "
+                               f"R={R}, rank {args.rank}, chunk={chunk}, seed={w['seed']}",
+                   "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
+                   "kv_bytes": kv_bytes, "step_bytes": step_bytes,
+                   "waves_per_group": fs.fs_get_option("waves_per_group"),
+                   "prefetch_pages": fs.fs_get_option("prefetch_pages"),
+                   "kv_layout": "separate" if args.separate_kv else "interleaved"},
+        "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+        "kv_token_heads_per_s": round(tok_heads / (ms_per_step * 1e-3), 1),
+        "kernel_ms": {"decode_avg": round(dec_avg_ms, 5), "decode_p50": round(float(np.median(dec_ms)), 5),
+                      "decode_p10": round(float(np.percentile(dec_ms, 10)), 5),
+                      "decode_p90": round(float(np.percentile(dec_ms, 90)), 5),
+                      "merge_avg": round(float(mrg_ms.mean()), 5)},
+        "host_builder_us": {"avg": round(float(np.mean(host_us)), 1), "p90": round(float(np.percentile(host_us, 90)), 1)},
+        "stream_read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else "decode_bf16_kernel",
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "algorithmic_bytes_per_launch": decode_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(key)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

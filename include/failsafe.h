@@ -216,6 +216,19 @@ FS_API fs_status fs_merge_lse(const float* part_o, const float* part_lse, const 
                        int64_t n_pairs, int32_t group, int32_t head_dim,
                        float* out, float* lse, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * fs_stream_read_probe - measurement aid, not a step of the path: read `bytes`
+ * bytes once with the access pattern of the attention sweep (16 bytes per lane,
+ * contiguous per wavefront) and discard them.  Timing it gives the read rate this
+ * GPU actually reaches, to set beside the nominal HBM peak.
+ *
+ *  buf_dev   DEVICE in   16-byte aligned, bytes a positive multiple of 16
+ *  sink_dev  DEVICE out  at least 4 bytes (written only in a 1-in-2^32 case)
+ *
+ * FS_EINVAL: NULL pointer, bad size or alignment.  FS_EHIP: launch failure.
+ */
+FS_API fs_status fs_stream_read_probe(const void* buf_dev, int64_t bytes, void* sink_dev, void* stream);
+
 /* Launch-shape knobs for measurement sweeps ("waves_per_group" in {1,2,4}, "prefetch_pages" in [1,3]).
  * Unknown key or a value outside the documented range: FS_EINVAL, nothing changes. */
 FS_API fs_status fs_set_option(const char* key, int32_t value);

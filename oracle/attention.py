@@ -53,8 +53,14 @@ def gather_pair_kv(kv: dict, pair_index: int, tok_begin: int, tok_end: int):
 
 
 def _run(fn, n, workers):
+    """Run fn(0..n-1), optionally on `workers` threads (one pair or item each).  While several
+    workers run, the BLAS behind numpy is held to one thread apiece so they do not fight."""
     if workers and workers > 1 and n > 1:
-        with ThreadPoolExecutor(max_workers=workers) as ex:
+        try:
+            from threadpoolctl import threadpool_limits
+        except ImportError:                      # pragma: no cover
+            from contextlib import nullcontext as threadpool_limits
+        with threadpool_limits(1), ThreadPoolExecutor(max_workers=workers) as ex:
             return list(ex.map(fn, range(n)))
     return [fn(i) for i in range(n)]
 
