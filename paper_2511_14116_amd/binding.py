@@ -183,6 +183,74 @@ def fs_stream_read_probe(buf_dev, nbytes: int, sink_dev, stream=None) -> None:
     _check(load_library().fs_stream_read_probe(_ptr(buf_dev), nbytes, _ptr(sink_dev), _ptr(stream)))
 
 
+class BoundCall:
+    """One library call with its arguments marshalled once.  A serving loop that repeats the
+    same call on the same buffers every step pays only the foreign call itself afterwards.
+    The arrays the pointers refer to are kept alive by the object."""
+
+    __slots__ = ("_fn", "_args", "_keep", "n_items", "n_pairs")
+
+    def __init__(self, fn, args, keep, n_items=None, n_pairs=None):
+        self._fn, self._args, self._keep = fn, args, keep
+        self.n_items, self.n_pairs = n_items, n_pairs
+
+    def __call__(self) -> None:
+        st = self._fn(*self._args)
+        if st != FS_OK:
+            raise FsError(st, fs_last_error())
+
+
+def _vp(x):
+    p = _ptr(x)
+    return C.c_void_p(p) if p is not None else None
+
+
+def bind_build_placement(shape: FsShape, ctx_len: np.ndarray, mode: np.ndarray, owner: np.ndarray,
+                         dp_rank: np.ndarray, rank_load: np.ndarray, rot=None, layer: int = 0) -> BoundCall:
+    """fs_build_placement on caller-held arrays (int32 ctx_len/owner/dp_rank, uint8 mode, int64
+    rank_load).  rank_load is in/out: zero it before each call for a fresh batch."""
+    lib = load_library()
+    for a, dt in ((ctx_len, np.int32), (mode, np.uint8), (owner, np.int32), (dp_rank, np.int32), (rank_load, np.int64)):
+        if a.dtype != dt or not a.flags.c_contiguous:
+            raise TypeError("bind_build_placement needs contiguous arrays of the documented dtypes")
+    i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+    args = (C.byref(shape), ctx_len.ctypes.data_as(i32p), mode.ctypes.data_as(u8p),
+            None if rot is None else rot.ctypes.data_as(i32p), C.c_int32(layer),
+            owner.ctypes.data_as(i32p), dp_rank.ctypes.data_as(i32p), rank_load.ctypes.data_as(i64p))
+    return BoundCall(lib.fs_build_placement, args, (shape, ctx_len, mode, rot, owner, dp_rank, rank_load))
+
+
+def bind_build_worklist(shape: FsShape, ctx_len: np.ndarray, owner: np.ndarray, rank: int, chunk_tokens: int,
+                        items: np.ndarray, pairs: np.ndarray, sched: np.ndarray, chunk_indptr: np.ndarray) -> BoundCall:
+    """fs_build_worklist into caller-held arrays (e.g. views of pinned memory).  After a call the
+    counts are in .n_items.value and .n_pairs.value."""
+    lib = load_library()
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    n_items, n_pairs = C.c_int64(0), C.c_int64(0)
+    args = (C.byref(shape), ctx_len.ctypes.data_as(i32p), owner.ctypes.data_as(i32p), C.c_int32(rank),
+            C.c_int32(chunk_tokens), C.c_void_p(items.ctypes.data), C.c_int64(len(items)),
+            C.c_void_p(pairs.ctypes.data), C.c_int64(len(pairs)), C.c_void_p(sched.ctypes.data),
+            C.c_void_p(chunk_indptr.ctypes.data), C.byref(n_items), C.byref(n_pairs))
+    return BoundCall(lib.fs_build_worklist, args, (shape, ctx_len, owner, items, pairs, sched, chunk_indptr),
+                     n_items, n_pairs)
+
+
+def bind_decode_attention(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int,
+                          part_o, part_lse, stream=None) -> BoundCall:
+    lib = load_library()
+    args = (C.byref(shape), C.byref(kv), _vp(items_dev), _vp(sched_dev), C.c_int64(n_items),
+            _vp(part_o), _vp(part_lse), _vp(stream))
+    return BoundCall(lib.fs_decode_attention, args, (shape, kv, items_dev, sched_dev, part_o, part_lse))
+
+
+def bind_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,
+                   out, lse, stream=None) -> BoundCall:
+    lib = load_library()
+    args = (_vp(part_o), _vp(part_lse), _vp(chunk_indptr_dev), C.c_int64(n_pairs), C.c_int32(group),
+            C.c_int32(head_dim), _vp(out), _vp(lse), _vp(stream))
+    return BoundCall(lib.fs_merge_lse, args, (part_o, part_lse, chunk_indptr_dev, out, lse))
+
+
 def fs_set_option(key: str, value: int) -> None:
     _check(load_library().fs_set_option(key.encode(), value))
 
