@@ -43,6 +43,7 @@ def main() -> int:
     ap.add_argument("--separate-kv", action="store_true", help="K and V in two pools instead of interleaved")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying HIP graphs")
     ap.add_argument("--force-tail", action="store_true", help="config 3: request 0 gets 131072 tokens")
     args = ap.parse_args()
 
@@ -107,20 +108,19 @@ def main() -> int:
 
     # ---- device buffers for the per-step work list -----------------------------------------------
     # One blob per step holds items | sched | chunk_indptr.  The host writes it into pinned memory
-    # (4 buffers in rotation) and a side stream copies it into one of two device blobs while the
-    # kernels of the previous step still run; the compute stream only waits for that copy.
+    # (N_SLOTS buffers in rotation, each with its own device blob).  The GPU side of a step - copy
+    # the blob, sweep, merge - is captured once per slot as a HIP graph, so a step costs the host
+    # one graph launch and the GPU sees the three nodes back to back.
     def up(x):
         return (x + 255) & ~255
     off_items = 0
     off_sched = up(off_items + n_items * 32)
     off_indptr = up(off_sched + n_items * 4)
     blob_bytes = up(off_indptr + (n_pairs + 1) * 8)
-    n_dev, n_host = 2, 4
-    dev_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, device=dev) for _ in range(n_dev)]
-    host_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(n_host)]
-    copied = [torch.cuda.Event() for _ in range(n_host)]        # H2D copy of this pinned buffer finished
-    consumed = [torch.cuda.Event() for _ in range(n_dev)]       # kernels reading this device blob finished
-    copy_stream = torch.cuda.Stream()
+    N_SLOTS = 4
+    dev_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, device=dev) for _ in range(N_SLOTS)]
+    host_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(N_SLOTS)]
+    slot_done = [torch.cuda.Event() for _ in range(N_SLOTS)]     # the step that last used this slot finished
     host_views = []
     for hb in host_blobs:
         a = hb.numpy()
@@ -141,61 +141,118 @@ def main() -> int:
     mode_c = np.ascontiguousarray(mode, dtype=np.uint8)
     call_place = fs.bind_build_placement(shape, ctx_c, mode_c, owner_buf, dp_buf, load_buf)
     call_list = [fs.bind_build_worklist(shape, ctx_c, owner_buf, args.rank, chunk, *hv) for hv in host_views]
-    call_decode, call_merge = [], []
-    for db in dev_blobs:
-        base = db.data_ptr()
-        call_decode.append(fs.bind_decode_attention(shape, ds.view, base + off_items, base + off_sched, n_items,
-                                                    part_o, part_lse, sptr))
-        call_merge.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"],
-                                            out, lse, sptr))
 
-    host_us, wait_us, enqueue_us = [], [], []
+    def bind_gpu_calls(stream_ptr):
+        dec, mrg = [], []
+        for db in dev_blobs:
+            base = db.data_ptr()
+            dec.append(fs.bind_decode_attention(shape, ds.view, base + off_items, base + off_sched, n_items,
+                                                part_o, part_lse, stream_ptr))
+            mrg.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"],
+                                         out, lse, stream_ptr))
+        return dec, mrg
 
-    def step(i: int, ev=None):
-        t0 = time.perf_counter()
-        hb, db = i % n_host, i % n_dev
-        while not copied[hb].query():                       # the copy that last read this pinned buffer is done
-            pass                                            # (a busy poll: a blocking wait costs a timer tick)
-        t1 = time.perf_counter()
+    call_decode, call_merge = bind_gpu_calls(sptr)
+
+    def build_host(slot: int):
         load_buf.fill(0)
         call_place()                                        # S1 + S2
-        call_list[hb]()                                     # S3
-        t2 = time.perf_counter()
-        wait_us.append((t1 - t0) * 1e6)
-        host_us.append((t2 - t1) * 1e6)
-        copy_stream.wait_event(consumed[db])                # step i-2 no longer reads this device blob
-        with torch.cuda.stream(copy_stream):
-            dev_blobs[db].copy_(host_blobs[hb], non_blocking=True)
-            copied[hb].record(copy_stream)
-        stream.wait_event(copied[hb])
+        call_list[slot]()                                   # S3
+
+    # The GPU side of step i reads device blob i % N_SLOTS and, next to it, uploads the blob of
+    # step i+1 (which the host has built by then), so the upload never sits between two sweeps.
+    def enqueue_eager(slot: int, ev=None):
         if ev is not None:
             ev[0].record(stream)
-        call_decode[db]()                                   # S4
+        call_decode[slot]()                                 # S4
         if ev is not None:
             ev[1].record(stream)
-        call_merge[db]()                                    # S5
-        consumed[db].record(stream)
-        enqueue_us.append((time.perf_counter() - t2) * 1e6)
+        call_merge[slot]()                                  # S5
+        nxt = (slot + 1) % N_SLOTS
+        dev_blobs[nxt].copy_(host_blobs[nxt], non_blocking=True)
 
+    for slot in range(N_SLOTS):                             # warm everything up eagerly once
+        build_host(slot)
+    dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
+    for slot in range(N_SLOTS):
+        enqueue_eager(slot)
+    torch.cuda.synchronize()
+
+    # one HIP graph per slot: sweep -> merge -> upload of the next step's blob
+    graphs = None
+    if not args.no_graph:
+        cap_stream = torch.cuda.Stream()
+        cap_decode, cap_merge = bind_gpu_calls(cap_stream.cuda_stream)
+        graphs = []
+        for slot in range(N_SLOTS):
+            g = torch.cuda.CUDAGraph()
+            nxt = (slot + 1) % N_SLOTS
+            with torch.cuda.graph(g, stream=cap_stream):
+                cap_decode[slot]()
+                cap_merge[slot]()
+                dev_blobs[nxt].copy_(host_blobs[nxt], non_blocking=True)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+    host_us, wait_us, enqueue_us = [], [], []
+    EVENT_EVERY = 8          # every 8th step runs eagerly with HIP events around the attention kernel
+
+    def step(i: int, ev=None):
+        # on entry the blob of step i is built and its upload is enqueued; build the one of step i+1
+        t0 = time.perf_counter()
+        slot, nxt = i % N_SLOTS, (i + 1) % N_SLOTS
+        while not slot_done[slot].query():                  # step i-N_SLOTS, the last reader of pinned blob nxt,
+            pass                                            # is done (busy poll: a blocking wait costs a timer tick)
+        t1 = time.perf_counter()
+        build_host(nxt)
+        t2 = time.perf_counter()
+        if graphs is None or ev is not None:
+            enqueue_eager(slot, ev)
+        else:
+            graphs[slot].replay()
+        slot_done[slot].record(stream)
+        t3 = time.perf_counter()
+        wait_us.append((t1 - t0) * 1e6)
+        host_us.append((t2 - t1) * 1e6)
+        enqueue_us.append((t3 - t2) * 1e6)
+
+    build_host(0)
+    dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
     host_us.clear(); wait_us.clear(); enqueue_us.clear()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    timed = [i for i in range(args.steps) if graphs is None or i % EVENT_EVERY == 0]
+    events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(2)] for i in timed}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, events[i])
+        step(i, events.get(i))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    dec_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
+    dec_ms = np.array([e[0].elapsed_time(e[1]) for e in events.values()])
+
+    # a graph step and an eager step must leave the same bits behind
+    if graphs is not None:
+        build_host(0)
+        build_host(1)
+        dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
+        graphs[0].replay()
+        torch.cuda.synchronize()
+        g_out, g_lse = out.clone(), lse.clone()
+        out.fill_(float("nan")); lse.fill_(float("nan"))
+        enqueue_eager(0)
+        torch.cuda.synchronize()
+        if not (torch.equal(g_out, out) and torch.equal(g_lse, lse)):
+            print("bench.py: graph replay and eager launch disagree", file=sys.stderr)
+            return 1
 
     # the merge kernel alone, timed after the region (its events would only add gaps inside it)
     m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     m0.record(stream)
     for _ in range(20):
-        call_merge[(args.steps - 1) % n_dev]()
+        call_merge[0]()
     m1.record(stream)
     torch.cuda.synchronize()
     mrg_ms = np.array([m0.elapsed_time(m1) / 20])
@@ -261,7 +318,8 @@ def main() -> int:
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),
-                   "kv_layout": "separate" if args.separate_kv else "interleaved"},
+                   "kv_layout": "separate" if args.separate_kv else "interleaved",
+                   "launch": "eager" if graphs is None else f"hip graph per slot; every {EVENT_EVERY}th step eager with events"},
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "kv_token_heads_per_s": round(tok_heads / (ms_per_step * 1e-3), 1),
         "kernel_ms": {"decode_avg": round(dec_avg_ms, 5), "decode_p50": round(float(np.median(dec_ms)), 5),

@@ -36,13 +36,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Read-only inputs that a wavefront indexes uniformly (page ids) are read through the constant
-// address space: that is what lets the compiler use scalar loads for them even in a kernel that
-// also stores to global memory.  Valid because nothing writes these arrays while a launch runs.
-typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
-__device__ __forceinline__ const_i32_ptr as_constant(const int32_t* p) {
-  return (const_i32_ptr)(p);
-}
 
 struct DecodeParams {
   const uint16_t* __restrict__ q;
@@ -149,12 +142,9 @@ __device__ __forceinline__ void consume_page(SoftmaxState& st, PageRegs& pg, con
     for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
     st.m = m_new;
   }
-  // A step that carries no token (valid == 0) can meet a running max that is still -inf;
-  // subtracting 0 instead keeps exp2(-inf - m) at 0 rather than NaN.
-  const float m_sub = (!FULL && st.m == -INFINITY) ? 0.f : st.m;
   f32x4 p;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(x[r] - m_sub);
+  for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(x[r] - st.m);
   st.l += (p[0] + p[1]) + (p[2] + p[3]);
   // The weights enter the matrix cores as bf16.  One bf16 keeps 8 bits, which for a short context
   // (weights near 1/2) costs ~2e-3 of |V| - the whole error budget.  Splitting p = hi + lo into two
@@ -278,171 +268,6 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
 
   const float l_total = sum_xor32(sum_xor16(st.l));
   merge_and_store<WAVES>(st, l_total, wave, lane, G, P.part_o, P.part_lse, it.part_row, sm_o, sm_m, sm_l);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Persistent variant of the bf16 kernel.  With one workgroup per item, every item pays a start-up
-// (four dependent loads before the first K/V byte moves) and a drain (no loads while the last
-// pages are consumed, then the merge).  Here a fixed set of workgroups - as many as the chip keeps
-// resident - each walks through several items, and a wavefront's page stream runs across item
-// boundaries: while it finishes item A its loads for item B are already in flight.
-//
-// Items are dealt from the longest-first order in rounds, alternating direction (round r gives
-// workgroup b position r*n + b or r*n + n-1-b), so the workgroup that drew the longest item of
-// one round draws the shortest of the next.  The metadata of a workgroup's items (one per lane,
-// up to 64 rounds at a time) is fetched once up front; after that everything a wavefront needs to
-// step from page to page is in scalar registers.
-//
-// Each ring slot carries a descriptor: how many tokens of the page are valid (0 = no page in this
-// step), whether it is the wavefront's first page of an item (take the prefetched Q) and whether
-// it ends the wavefront's part of an item (run the merge).  Loads are issued unconditionally in
-// every step (a step with nothing to fetch re-reads the last slot) so the number of outstanding
-// loads per step is fixed and the wait before each use stays as shallow as possible.
-// ---------------------------------------------------------------------------------------------
-template <int WAVES, int NBUF>
-__global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent(const DecodeParams P, const int n_items) {
-  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
-  __shared__ float sm_m[WAVES * 16];
-  __shared__ float sm_l[WAVES * 16];
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qi = lane & 15, kb = lane >> 4;
-  const int G = P.group;
-  const int nwg = gridDim.x, b = blockIdx.x;
-  const int q_lane_row = min(qi, G - 1);
-
-  for (int round0 = 0; static_cast<int64_t>(round0) * nwg < n_items; round0 += 64) {
-    // ---- this workgroup's items of rounds round0 .. round0+63, one per lane
-    const int rnd = round0 + lane;
-    const int64_t pos = static_cast<int64_t>(rnd) * nwg + ((rnd & 1) ? nwg - 1 - b : b);
-    const bool has = pos < n_items;
-    int m_ntok = 0, m_qrow = 0, m_prow = 0, m_base_lo = 0, m_base_hi = 0;
-    if (has) {
-      const int idx = P.sched ? P.sched[pos] : static_cast<int>(pos);
-      const fs_work_item it = P.items[idx];
-      const int64_t base = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
-      m_ntok = it.tok_end - it.tok_begin;
-      m_qrow = it.q_row;
-      m_prow = it.part_row;
-      m_base_lo = static_cast<int>(base & 0xFFFFFFFFll);
-      m_base_hi = static_cast<int>(base >> 32);
-    }
-    const int n_rounds = __builtin_popcountll(__ballot(has));   // positions grow with the round: a prefix
-    if (n_rounds == 0) break;
-
-    // ---- load-side cursor (scalars)
-    int jL = 0, pL = 0, p0L = 0, p1L = 0, ntokL = 0, qrowL = 0;
-    const_i32_ptr idsL = as_constant(P.page_ids);
-    auto set_item = [&](int j) {
-      ntokL = __builtin_amdgcn_readlane(m_ntok, j);
-      qrowL = __builtin_amdgcn_readlane(m_qrow, j);
-      const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(m_base_lo, j));
-      const int32_t hi = __builtin_amdgcn_readlane(m_base_hi, j);
-      idsL = as_constant(P.page_ids) + ((static_cast<int64_t>(hi) << 32) | lo);
-      const int n_pages = (ntokL + fs::kPageTokens - 1) / fs::kPageTokens;
-      const int per = (n_pages + WAVES - 1) / WAVES;
-      p0L = wave * per;
-      p1L = min(n_pages, p0L + per);
-      pL = p0L;
-    };
-    set_item(0);
-    int32_t slot_dummy = idsL[0];                     // every item has at least one page
-    int32_t slot_next = pL < p1L ? idsL[pL] : slot_dummy;
-    bool q_free = true;
-    u32x4 q_next[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) q_next[c] = u32x4{0u, 0u, 0u, 0u};
-
-    PageRegs buf[NBUF];
-    int d_valid[NBUF], d_flags[NBUF];
-
-    // one step of the load side: describe ring slot `r` and issue its loads
-    auto gen = [&](PageRegs& dst, int& dv, int& df) {
-      int32_t slot = slot_dummy;
-      dv = 0;
-      df = 0;
-      if (jL < n_rounds) {
-        if (pL < p1L) {
-          const bool first = pL == p0L;
-          if (!first || q_free) {
-            if (first) {   // Q of the item this wavefront is entering, well ahead of its first use
-              const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrowL + q_lane_row) * fs::kHeadDim) + kb;
-#pragma unroll
-              for (int c = 0; c < 4; ++c) q_next[c] = qp[4 * c];
-              q_free = false;
-            }
-            slot = slot_next;
-            slot_dummy = slot;
-            dv = min(fs::kPageTokens, ntokL - pL * fs::kPageTokens);
-            df = (first ? 1 : 0) | (pL + 1 == p1L ? 2 : 0);
-            ++pL;
-          }   // else: the previous item's Q has not been taken yet - an empty step
-        } else {
-          df = 2;   // this wavefront has no page of the item, but it still joins the item's merge
-        }
-        if (df & 2) {
-          ++jL;
-          if (jL < n_rounds) set_item(jL);
-        }
-      }
-      load_page(dst, P.k_pool, P.v_pool, P.k_stride, P.v_stride, slot, lane);
-      slot_next = (jL < n_rounds && pL < p1L) ? idsL[pL] : slot_dummy;
-    };
-
-    // ---- consume side
-    SoftmaxState st;
-    auto reset_state = [&]() {
-      st.m = -INFINITY;
-      st.l = 0.f;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    };
-    reset_state();
-    bf16x8 qreg[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) qreg[c] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-    int jC = 0;
-
-    auto use = [&](PageRegs& src, int dv, int df) {
-      if (df & 1) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) qreg[c] = __builtin_bit_cast(bf16x8, qi < G ? q_next[c] : u32x4{0u, 0u, 0u, 0u});
-        q_free = true;
-      }
-      // Every step runs the page arithmetic, also the rare empty ones (all 16 tokens masked, so
-      // they add nothing): a ring slot is then read on every path before it is refilled, and the
-      // compiler can keep the waits of the steady state as shallow as the ring allows.
-      consume_page<false>(st, src, qreg, P.scale_log2, dv, kb);
-      if (df & 2) {
-        const float l_total = sum_xor32(sum_xor16(st.l));
-        merge_and_store<WAVES>(st, l_total, wave, lane, G, P.part_o, P.part_lse,
-                               __builtin_amdgcn_readlane(m_prow, jC), sm_o, sm_m, sm_l);
-        __syncthreads();   // the merge buffer is reused by the next item
-        reset_state();
-        ++jC;
-      }
-    };
-
-#pragma unroll
-    for (int u = 0; u < NBUF - 1; ++u) gen(buf[u], d_valid[u], d_flags[u]);
-    // the ring is walked with compile-time slot numbers (so it stays in registers); leaving the
-    // loop from the middle of a lap is a plain exit, not a path that rejoins the steady state
-#define FS_RING_STEP(u)                                                                                     \
-  if (jC >= n_rounds) break;                                                                                \
-  gen(buf[((u) + NBUF - 1) % NBUF], d_valid[((u) + NBUF - 1) % NBUF], d_flags[((u) + NBUF - 1) % NBUF]);    \
-  use(buf[(u)], d_valid[(u)], d_flags[(u)]);
-    while (true) {
-      FS_RING_STEP(0)
-      FS_RING_STEP(1)
-      if constexpr (NBUF > 2) { FS_RING_STEP(2) }
-      if constexpr (NBUF > 3) { FS_RING_STEP(3) }
-    }
-#undef FS_RING_STEP
-    // Loads of the last (empty) steps may still be in flight; settle them before the ring is
-    // reused by another batch of rounds, so that path does not cost the steady state a drain.
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -623,43 +448,6 @@ fs_status launch(K kernel, int threads, const DecodeParams& P, int64_t n_items, 
   return FS_OK;
 }
 
-// Grid of the persistent kernel: as many workgroups as the GPU keeps resident at once.
-template <typename K>
-fs_status launch_resident(K kernel, int threads, const DecodeParams& P, int64_t n_items, hipStream_t stream) {
-  static int resident = 0;   // per kernel instantiation; one GPU model per process
-  if (resident == 0) {
-    int dev = 0, cus = 0, per_cu = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0);
-    if (e != hipSuccess || cus < 1 || per_cu < 1)
-      return fs::fail(FS_EHIP, "fs_decode_attention: occupancy query failed: %s", hipGetErrorString(e));
-    resident = cus * per_cu;
-  }
-  int grid = fs::options().persistent_groups > 0 ? fs::options().persistent_groups : resident;
-  if (grid > n_items) grid = static_cast<int>(n_items);
-  hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(grid)), dim3(threads), 0, stream, P, static_cast<int>(n_items));
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_decode_attention: launch failed: %s", hipGetErrorString(e));
-  return FS_OK;
-}
-
-fs_status launch_persistent_bf16(int waves, int nbuf, const DecodeParams& P, int64_t n_items, hipStream_t s) {
-  switch (waves * 10 + nbuf) {
-    case 12: return launch_resident(decode_bf16_persistent<1, 2>, 64, P, n_items, s);
-    case 13: return launch_resident(decode_bf16_persistent<1, 3>, 64, P, n_items, s);
-    case 14: return launch_resident(decode_bf16_persistent<1, 4>, 64, P, n_items, s);
-    case 22: return launch_resident(decode_bf16_persistent<2, 2>, 128, P, n_items, s);
-    case 23: return launch_resident(decode_bf16_persistent<2, 3>, 128, P, n_items, s);
-    case 24: return launch_resident(decode_bf16_persistent<2, 4>, 128, P, n_items, s);
-    case 42: return launch_resident(decode_bf16_persistent<4, 2>, 256, P, n_items, s);
-    case 43: return launch_resident(decode_bf16_persistent<4, 3>, 256, P, n_items, s);
-    case 44: return launch_resident(decode_bf16_persistent<4, 4>, 256, P, n_items, s);
-    default: return fs::fail(FS_EINVAL, "fs_decode_attention: no kernel for waves_per_group %d, prefetch_pages %d",
-                             waves, nbuf - 1);
-  }
-}
-
 }  // namespace
 
 extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv,
@@ -731,9 +519,6 @@ extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view
                              waves, nbuf - 1);                                           \
   }
 
-  if (kv->kv_dtype == FS_KV_BF16 && fs::options().persistent) {
-    return launch_persistent_bf16(waves, nbuf, P, n_items, s);
-  }
   if (kv->kv_dtype == FS_KV_BF16) {
     FS_PICK(decode_bf16_kernel)
   }

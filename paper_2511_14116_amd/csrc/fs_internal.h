@@ -18,8 +18,6 @@ constexpr int kMaxGroupFp8 = 8;
 struct Options {
   int waves_per_group;   // wavefronts cooperating on one work item (1, 2 or 4)
   int prefetch_pages;    // KV pages a wavefront keeps in flight ahead of the one it is consuming (1..3)
-  int persistent;        // 1: resident workgroups walk several items each (bf16 path); 0: one workgroup per item
-  int persistent_groups; // 0: as many workgroups as stay resident; else that many (measurement sweeps)
 };
 Options& options();
 

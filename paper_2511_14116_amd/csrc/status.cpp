@@ -17,7 +17,7 @@ fs_status fail(fs_status st, const char* fmt, ...) {
 }
 
 Options& options() {
-  static Options o{4, 2, 0, 0};
+  static Options o{4, 2};
   return o;
 }
 
@@ -41,16 +41,6 @@ extern "C" fs_status fs_set_option(const char* key, int32_t value) {
     fs::options().prefetch_pages = value;
     return FS_OK;
   }
-  if (!strcmp(key, "persistent")) {
-    if (value != 0 && value != 1) return fs::fail(FS_EINVAL, "persistent must be 0 or 1 (got %d)", value);
-    fs::options().persistent = value;
-    return FS_OK;
-  }
-  if (!strcmp(key, "persistent_groups")) {
-    if (value < 0 || value > 65536) return fs::fail(FS_EINVAL, "persistent_groups must be in [0, 65536] (got %d)", value);
-    fs::options().persistent_groups = value;
-    return FS_OK;
-  }
   return fs::fail(FS_EINVAL, "fs_set_option: unknown key '%s'", key);
 }
 
@@ -58,7 +48,5 @@ extern "C" int32_t fs_get_option(const char* key) {
   if (!key) return -1;
   if (!strcmp(key, "waves_per_group")) return fs::options().waves_per_group;
   if (!strcmp(key, "prefetch_pages")) return fs::options().prefetch_pages;
-  if (!strcmp(key, "persistent")) return fs::options().persistent;
-  if (!strcmp(key, "persistent_groups")) return fs::options().persistent_groups;
   return -1;
 }

@@ -312,3 +312,35 @@ def test_config3_forced_tail_sampled():
 
 def test_config4_fp8_full_size_sampled():
     _full_config(4, 0, 24)
+
+
+# ------------------------------------------------------------------------------------------------
+def test_hip_graph_replays_match_eager():
+    """The benchmark replays the step's GPU side as a HIP graph.  Captured once, replayed several
+    times with eager work and synchronisation in between, every replay must reproduce the eager
+    result bit for bit (the kernels are deterministic)."""
+    w = make_requests(1, n_req=24, max_len=2500)
+    q = make_q(w["seed"], 24, w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 256, owner)
+    eager_o, eager_l = ds.out.clone(), ds.lse.clone()
+    cap = torch.cuda.Stream()
+    dec = fs.bind_decode_attention(sh, ds.view, ds.items, ds.sched, ds.n_items, ds.part_o, ds.part_lse, cap.cuda_stream)
+    mrg = fs.bind_merge_lse(ds.part_o, ds.part_lse, ds.chunk_indptr, ds.n_pairs, ds.group, 128, ds.out, ds.lse, cap.cuda_stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=cap):
+        dec()
+        mrg()
+    for rep in range(4):
+        ds.out.fill_(float("nan")); ds.lse.fill_(float("nan")); ds.part_o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ds.out, eager_o) and torch.equal(ds.lse, eager_l), f"replay {rep} differs"
+        ds.run()                       # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(ds.out, eager_o)
+    ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
+    check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, "graph replay vs oracle")

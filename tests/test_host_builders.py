@@ -172,3 +172,28 @@ def test_slot_orders_are_permutations_with_the_documented_formulas():
     x = np.arange(2 * 2048, dtype=np.uint16).reshape(2, 16, 128)
     y = fs.pack_slots(x, fs.FS_KV_BF16, False)
     assert y[1].reshape(-1)[8] == 2048 + 1 * 128 + 0
+
+
+def test_bound_calls_fill_caller_arrays_like_the_plain_calls():
+    w = make_requests(1)
+    sh = _shape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"])
+    ctx = np.ascontiguousarray(w["ctx_len"], dtype=np.int32)
+    mode = np.ascontiguousarray(w["mode"], dtype=np.uint8)
+    owner = np.empty((w["n_req"], w["n_kv_heads"]), np.int32); dp = np.empty(w["n_req"], np.int32)
+    load = np.zeros(w["n_ranks"], np.int64)
+    place = fs.bind_build_placement(sh, ctx, mode, owner, dp, load)
+    place()
+    o2, d2, l2 = fs.fs_build_placement(sh, ctx, mode)
+    assert owner.tobytes() == o2.tobytes() and dp.tobytes() == d2.tobytes() and load.tobytes() == l2.tobytes()
+    load.fill(0); place()                       # reusable
+    assert load.tobytes() == l2.tobytes()
+    items, pairs, sched, indptr = fs.fs_build_worklist(sh, ctx, owner, 2, 512)
+    bufs = (np.empty(len(items) + 5, fs.ITEM_DTYPE), np.empty(len(pairs), fs.PAIR_DTYPE),
+            np.empty(len(items) + 5, np.int32), np.empty(len(pairs) + 1, np.int64))
+    wl = fs.bind_build_worklist(sh, ctx, owner, 2, 512, *bufs)
+    wl()
+    assert (wl.n_items.value, wl.n_pairs.value) == (len(items), len(pairs))
+    assert bufs[0][:len(items)].tobytes() == items.tobytes() and bufs[2][:len(items)].tobytes() == sched.tobytes()
+    assert bufs[3].tobytes() == indptr.tobytes()
+    with pytest.raises(TypeError):
+        fs.bind_build_placement(sh, ctx.astype(np.int64), mode, owner, dp, load)
