@@ -5,8 +5,11 @@
 // is exact algebra on the partial (out, lse) pairs:
 //     lse = ln sum_c exp(lse_c),   out = sum_c exp(lse_c - lse) * o_c.
 //
-// One wavefront per output row (pair, q-head); a lane owns two of the 128 columns, so a row of
-// a partial is one coalesced 512-byte read.  HBM traffic is under 1% of the attention sweep's.
+// One wavefront per output row (pair, q-head).  The row's chunk lse values are read 64 at a time,
+// one per lane, and reduced across the wavefront, so a pair cut into many chunks (a 131072-token
+// context in 1024-token chunks has 128) costs two wide loads instead of a serial chain.  For the
+// rows themselves a lane owns two of the 128 columns (one coalesced 512-byte read per chunk) and
+// four chunk rows are in flight at a time.  HBM traffic is under 1% of the attention sweep's.
 #include <hip/hip_runtime.h>
 
 #include "fs_internal.h"
@@ -14,6 +17,17 @@
 namespace {
 
 constexpr int kRowsPerBlock = 4;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
 
 __global__ void __launch_bounds__(kRowsPerBlock * 64)
 merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ part_lse,
@@ -25,20 +39,45 @@ merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ par
   if (row >= n_rows) return;
   const int64_t p = row / group;
   const int g = static_cast<int>(row - p * group);
-  const int64_t c0 = chunk_indptr[p], c1 = chunk_indptr[p + 1];
+  const int64_t c0 = chunk_indptr[p];
+  const int n = static_cast<int>(chunk_indptr[p + 1] - c0);
 
   float M = -INFINITY;
-  for (int64_t c = c0; c < c1; ++c) M = fmaxf(M, part_lse[c * group + g]);
+  for (int base = 0; base < n; base += 64) {
+    const int c = base + lane;
+    M = fmaxf(M, c < n ? part_lse[(c0 + c) * group + g] : -INFINITY);
+  }
+  M = wave_max(M);
+
   float sum = 0.f;
   float2 acc = make_float2(0.f, 0.f);
-  for (int64_t c = c0; c < c1; ++c) {
-    const int64_t r = c * group + g;
-    const float w = __expf(part_lse[r] - M);
-    const float2 o = reinterpret_cast<const float2*>(part_o + r * fs::kHeadDim)[lane];
-    sum += w;
-    acc.x = fmaf(w, o.x, acc.x);
-    acc.y = fmaf(w, o.y, acc.y);
+  for (int base = 0; base < n; base += 64) {
+    const int c = base + lane;
+    const float w = c < n ? __expf(part_lse[(c0 + c) * group + g] - M) : 0.f;
+    sum += w;                                   // per lane; reduced once at the end
+    const int cnt = min(64, n - base);
+    const float2* rows = reinterpret_cast<const float2*>(part_o + ((c0 + base) * group + g) * fs::kHeadDim) + lane;
+    const int64_t stride = static_cast<int64_t>(group) * (fs::kHeadDim / 2);   // float2 units between chunk rows
+    int j = 0;
+    for (; j + 4 <= cnt; j += 4) {
+      float2 o[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) o[u] = rows[(j + u) * stride];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j + u));
+        acc.x = fmaf(wj, o[u].x, acc.x);
+        acc.y = fmaf(wj, o[u].y, acc.y);
+      }
+    }
+    for (; j < cnt; ++j) {
+      const float2 o = rows[j * stride];
+      const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j));
+      acc.x = fmaf(wj, o.x, acc.x);
+      acc.y = fmaf(wj, o.y, acc.y);
+    }
   }
+  sum = wave_sum(sum);
   const float inv = 1.0f / sum;
   reinterpret_cast<float2*>(out + row * fs::kHeadDim)[lane] = make_float2(acc.x * inv, acc.y * inv);
   if (lane == 0) lse[row] = M + __logf(sum);
