@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying HIP graphs")
+    ap.add_argument("--cold", action="store_true", help="also time the kernels with L2 and the memory-side cache scrubbed before every launch")
+    ap.add_argument("--all-ranks", action="store_true", help="also time every rank's share in turn (kernels only) and report the spread")
     ap.add_argument("--force-tail", action="store_true", help="config 3: request 0 gets 131072 tokens")
     args = ap.parse_args()
 
@@ -279,6 +281,57 @@ def main() -> int:
         torch.cuda.synchronize()
         probe_gbs = nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
+    # ---- cold-cache kernel times: shares smaller than the 256 MB memory-side cache are otherwise
+    # served from it when the same pool is swept again and again
+    cold = None
+    if args.cold:
+        scrub = torch.empty(1 << 30, dtype=torch.uint8, device=dev)       # 1 GiB, read once before each launch
+        sink2 = torch.zeros(4, dtype=torch.int32, device=dev)
+        dts, mts = [], []
+        for _ in range(20):
+            fs.fs_stream_read_probe(scrub, scrub.numel(), sink2, sptr)
+            c0, c1, c2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            c0.record(stream)
+            call_decode[0]()
+            c1.record(stream)
+            call_merge[0]()
+            c2.record(stream)
+            torch.cuda.synchronize()
+            dts.append(c0.elapsed_time(c1)); mts.append(c1.elapsed_time(c2))
+        cold = {"decode_ms": round(float(np.mean(dts)), 5), "merge_ms": round(float(np.mean(mts)), 5),
+                "decode_gbs": round(decode_bytes / (float(np.mean(dts)) * 1e-3) / 1e9, 1)}
+        del scrub
+
+    # ---- every rank's share in turn (the straggler view of the skewed batch) -----------------------
+    per_rank = None
+    if args.all_ranks:
+        per_rank = []
+        for k in range(R):
+            it_k, pr_k, sc_k, ip_k = fs.fs_build_worklist(shape, ctx, owner, k, chunk)
+            if len(it_k) == 0:
+                per_rank.append({"rank": k, "kv_token_heads": 0, "n_items": 0, "kernels_us": 0.0, "gbs": 0.0})
+                continue
+            kv_k = make_kv_pool(w["seed"], np.stack([pr_k["req"], pr_k["kv_head"]], axis=1), ctx, kv_dtype=w["kv_dtype"])
+            ds_k = DeviceShare(shape, q_bits, kv_k, w["sm_scale"], interleave_kv=not args.separate_kv)
+            ds_k.set_worklist(it_k, pr_k, sc_k, ip_k)
+            for _ in range(5):
+                ds_k.run()
+            r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 30
+            r0.record(stream)
+            for _ in range(reps):
+                ds_k.run()
+            r1.record(stream)
+            torch.cuda.synchronize()
+            us = r0.elapsed_time(r1) * 1e3 / reps
+            th = int(rank_load[k])
+            per_rank.append({"rank": k, "kv_token_heads": th, "n_items": len(it_k), "kernels_us": round(us, 2),
+                             "gbs": round(th * 2 * w["head_dim"] * elt / (us * 1e-6) / 1e9, 1)})
+            del ds_k, kv_k
+        times = [p_["kernels_us"] for p_ in per_rank if p_["n_items"]]
+        rank_spread = {"min_us": min(times), "max_us": max(times), "mean_us": round(float(np.mean(times)), 2),
+                       "max_over_mean": round(max(times) / float(np.mean(times)), 3)}
+
     # ---- CPU baseline: the oracle on this machine's host cores ---------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -338,6 +391,11 @@ def main() -> int:
                      "traffic": MEASURED_TRAFFIC_BYTES.get(key)},
         "cpu_baseline": cpu,
     }
+    if cold is not None:
+        result["cold_cache"] = cold
+    if per_rank is not None:
+        result["per_rank"] = per_rank
+        result["rank_time_spread"] = rank_spread
     print(json.dumps(result))
     return 0
 
