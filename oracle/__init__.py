@@ -13,7 +13,7 @@ brute force, invariants, library routines); no function here is "parity
 unpinned".
 """
 from .formats import bf16_bits_to_f64, e4m3_bytes_to_f64, E4M3_TABLE  # noqa: F401
-from .placement import build_placement  # noqa: F401
+from .placement import build_placement, build_placement_hybrid_heads  # noqa: F401
 from .worklist import build_worklist, ITEM_FIELDS, PAIR_FIELDS  # noqa: F401
 from .attention import (  # noqa: F401
     attend,
