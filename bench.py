@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying HIP graphs")
+    ap.add_argument("--placement", choices=["requests", "heads"], default="requests",
+                    help="requests: the batch's TP/DP mix per request; heads: the paper's head-level hybrid (layer 0)")
     ap.add_argument("--cold", action="store_true", help="also time the kernels with L2 and the memory-side cache scrubbed before every launch")
     ap.add_argument("--all-ranks", action="store_true", help="also time every rank's share in turn (kernels only) and report the spread")
     ap.add_argument("--force-tail", action="store_true", help="config 3: request 0 gets 131072 tokens")
@@ -83,7 +85,10 @@ def main() -> int:
     shape = fs.FsShape(B, Hq, Hkv, w["head_dim"], w["page_tokens"], R)
     ctx, mode = w["ctx_len"], w["mode"]
     q_bits = make_q(w["seed"], B, Hq, w["head_dim"])
-    owner, dp_rank, rank_load = fs.fs_build_placement(shape, ctx, mode)
+    if args.placement == "heads":
+        owner, dp_rank, rank_load, _dp_load = fs.fs_build_placement_hybrid_heads(shape, ctx, layer=0)
+    else:
+        owner, dp_rank, rank_load = fs.fs_build_placement(shape, ctx, mode)
     items, pairs, sched, chunk_indptr = fs.fs_build_worklist(shape, ctx, owner, args.rank, chunk)
     n_items, n_pairs = len(items), len(pairs)
     if n_items == 0:
@@ -141,7 +146,12 @@ def main() -> int:
     load_buf = np.zeros(R, dtype=np.int64)
     ctx_c = np.ascontiguousarray(ctx, dtype=np.int32)
     mode_c = np.ascontiguousarray(mode, dtype=np.uint8)
-    call_place = fs.bind_build_placement(shape, ctx_c, mode_c, owner_buf, dp_buf, load_buf)
+    if args.placement == "heads":
+        dpl_buf = np.zeros(R, dtype=np.int64)
+        call_place = fs.bind_build_placement_hybrid_heads(shape, ctx_c, owner_buf, dp_buf, load_buf, dpl_buf)
+    else:
+        dpl_buf = None
+        call_place = fs.bind_build_placement(shape, ctx_c, mode_c, owner_buf, dp_buf, load_buf)
     call_list = [fs.bind_build_worklist(shape, ctx_c, owner_buf, args.rank, chunk, *hv) for hv in host_views]
 
     def bind_gpu_calls(stream_ptr):
@@ -158,6 +168,8 @@ def main() -> int:
 
     def build_host(slot: int):
         load_buf.fill(0)
+        if dpl_buf is not None:
+            dpl_buf.fill(0)
         call_place()                                        # S1 + S2
         call_list[slot]()                                   # S3
 
@@ -366,7 +378,8 @@ def main() -> int:
         "dtype": "bf16" if w["kv_dtype"] == "bf16" else "fp8_e4m3",
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {w['name']}: B={B}, Hq={Hq}, Hkv={Hkv}, d=128, page=16, "
-                               f"R={R}, rank {args.rank}, chunk={chunk}, seed={w['seed']}",
+                               f"R={R}, rank {args.rank}, chunk={chunk}, seed={w['seed']}"
+                               + (", head-level hybrid placement" if args.placement == "heads" else ""),
                    "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
                    "waves_per_group": fs.fs_get_option("waves_per_group"),

@@ -5,6 +5,7 @@
  * the KV heads of a model are spread over R surviving tensor-parallel ranks:
  *
  *   fs_build_placement   which rank owns each (request, KV head)        host
+ *   (fs_build_placement_hybrid_heads: the paper's head-level variant)   host
  *   fs_build_worklist    one rank's ragged (request, head, chunk) list  host
  *   fs_decode_attention  per-item partial attention (out, lse)          device
  *   fs_merge_lse         split-K partials -> final (out, lse)           device
@@ -104,6 +105,34 @@ typedef struct {
 FS_API fs_status fs_build_placement(const fs_shape* shape, const int32_t* ctx_len, const uint8_t* mode,
                              const int32_t* rot, int32_t layer,
                              int32_t* owner, int32_t* dp_rank, int64_t* rank_load);
+
+/* ---------------------------------------------------------------------------
+ * fs_build_placement_hybrid_heads - Section 3.1, Hybrid Attention exactly as the
+ * paper states it (Fig. 3), at head granularity, with Cyclic Placement's
+ * layer-by-layer rotation.
+ *
+ * Every tensor-parallel worker gets floor(H_kv/R) heads: heads [0, R*floor(H_kv/R))
+ * of every request go to rank (h + layer) mod R.  The remaining H_kv mod R heads
+ * are replicated and run data-parallel: all of a request's leftover heads go to
+ * the request's DP rank, which is route[r] when route is given, else the rank
+ * with the least pending DP work in token units (Load-Aware DP-Rank Routing:
+ * dp_load only, ties to the lowest rank, requests in index order).  When R divides
+ * H_kv nothing is left over and this is uniform TP (dp_rank = -1).
+ *
+ *  ctx_len   HOST in   [n_req]            each >= 1
+ *  route     HOST in   [n_req] or NULL    DP rank per request, each in [0, R)
+ *  owner     HOST out  [n_req*n_kv_heads]
+ *  dp_rank   HOST out  [n_req]
+ *  rank_load HOST in/out [n_ranks]        total load, KV tokens x KV heads
+ *  dp_load   HOST in/out [n_ranks]        the DP part of it (what the router balances)
+ *
+ * The result feeds fs_build_worklist unchanged.  FS_EINVAL: NULL pointer, bad
+ * shape, ctx_len < 1, route outside [0, R).
+ */
+FS_API fs_status fs_build_placement_hybrid_heads(const fs_shape* shape, const int32_t* ctx_len,
+                                                 int32_t layer, const int32_t* route,
+                                                 int32_t* owner, int32_t* dp_rank,
+                                                 int64_t* rank_load, int64_t* dp_load);
 
 /* ---------------------------------------------------------------------------
  * fs_build_worklist - the ragged per-(request, head) list that hybrid attention

@@ -9,8 +9,8 @@ from .binding import (  # noqa: F401
     FS_MODE_TP, FS_MODE_DP, FS_KV_BF16, FS_KV_FP8_E4M3,
     FsError, FsShape, FsKvView, ITEM_DTYPE, PAIR_DTYPE,
     library_path, load_library,
-    fs_build_placement, fs_build_worklist, fs_decode_attention, fs_merge_lse,
-    BoundCall, bind_build_placement, bind_build_worklist, bind_decode_attention, bind_merge_lse,
+    fs_build_placement, fs_build_placement_hybrid_heads, fs_build_worklist, fs_decode_attention, fs_merge_lse,
+    BoundCall, bind_build_placement, bind_build_placement_hybrid_heads, bind_build_worklist, bind_decode_attention, bind_merge_lse,
     fs_kv_elem_offset, fs_stream_read_probe, fs_set_option, fs_get_option, fs_last_error, fs_abi_version,
 )
 from .layout import slot_permutation, pack_slots  # noqa: F401

@@ -55,6 +55,8 @@ def load_library(path: str | None = None):
     i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
     lib.fs_build_placement.argtypes = [C.POINTER(FsShape), i32p, u8p, i32p, C.c_int32, i32p, i32p, i64p]
     lib.fs_build_placement.restype = C.c_int
+    lib.fs_build_placement_hybrid_heads.argtypes = [C.POINTER(FsShape), i32p, C.c_int32, i32p, i32p, i32p, i64p, i64p]
+    lib.fs_build_placement_hybrid_heads.restype = C.c_int
     lib.fs_build_worklist.argtypes = [C.POINTER(FsShape), i32p, i32p, C.c_int32, C.c_int32,
                                       C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_void_p, i64p, i64p]
@@ -131,6 +133,28 @@ def fs_build_placement(shape: FsShape, ctx_len, mode, rot=None, layer: int = 0, 
                                 owner.ctypes.data_as(i32p), dp.ctypes.data_as(i32p), load.ctypes.data_as(i64p))
     _check(st)
     return owner, dp, load
+
+
+def fs_build_placement_hybrid_heads(shape: FsShape, ctx_len, layer: int = 0, route=None, rank_load=None,
+                                    dp_load=None):
+    """-> (owner [B][H_kv] int32, dp_rank [B] int32, rank_load [R] int64, dp_load [R] int64)."""
+    lib = load_library()
+    B, H, R = shape.n_req, shape.n_kv_heads, shape.n_ranks
+    ctx = _host(ctx_len, np.int32)
+    if len(ctx) != B:
+        raise ValueError("ctx_len must have n_req entries")
+    rt = None if route is None else _host(route, np.int32)
+    owner = np.empty((max(B, 0), max(H, 0)), dtype=np.int32)
+    dp = np.empty(max(B, 0), dtype=np.int32)
+    load = np.zeros(max(R, 0), dtype=np.int64) if rank_load is None else np.array(rank_load, dtype=np.int64)
+    dload = np.zeros(max(R, 0), dtype=np.int64) if dp_load is None else np.array(dp_load, dtype=np.int64)
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    st = lib.fs_build_placement_hybrid_heads(C.byref(shape), ctx.ctypes.data_as(i32p), layer,
+                                             None if rt is None else rt.ctypes.data_as(i32p),
+                                             owner.ctypes.data_as(i32p), dp.ctypes.data_as(i32p),
+                                             load.ctypes.data_as(i64p), dload.ctypes.data_as(i64p))
+    _check(st)
+    return owner, dp, load, dload
 
 
 def fs_build_worklist(shape: FsShape, ctx_len, owner, rank: int, chunk_tokens: int, out=None):
@@ -218,6 +242,21 @@ def bind_build_placement(shape: FsShape, ctx_len: np.ndarray, mode: np.ndarray, 
             None if rot is None else rot.ctypes.data_as(i32p), C.c_int32(layer),
             owner.ctypes.data_as(i32p), dp_rank.ctypes.data_as(i32p), rank_load.ctypes.data_as(i64p))
     return BoundCall(lib.fs_build_placement, args, (shape, ctx_len, mode, rot, owner, dp_rank, rank_load))
+
+
+def bind_build_placement_hybrid_heads(shape: FsShape, ctx_len: np.ndarray, owner: np.ndarray, dp_rank: np.ndarray,
+                                      rank_load: np.ndarray, dp_load: np.ndarray, layer: int = 0, route=None) -> BoundCall:
+    """fs_build_placement_hybrid_heads on caller-held arrays; zero both load arrays for a fresh batch."""
+    lib = load_library()
+    for a, dt in ((ctx_len, np.int32), (owner, np.int32), (dp_rank, np.int32), (rank_load, np.int64), (dp_load, np.int64)):
+        if a.dtype != dt or not a.flags.c_contiguous:
+            raise TypeError("bind_build_placement_hybrid_heads needs contiguous arrays of the documented dtypes")
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    args = (C.byref(shape), ctx_len.ctypes.data_as(i32p), C.c_int32(layer),
+            None if route is None else route.ctypes.data_as(i32p),
+            owner.ctypes.data_as(i32p), dp_rank.ctypes.data_as(i32p),
+            rank_load.ctypes.data_as(i64p), dp_load.ctypes.data_as(i64p))
+    return BoundCall(lib.fs_build_placement_hybrid_heads, args, (shape, ctx_len, route, owner, dp_rank, rank_load, dp_load))
 
 
 def bind_build_worklist(shape: FsShape, ctx_len: np.ndarray, owner: np.ndarray, rank: int, chunk_tokens: int,

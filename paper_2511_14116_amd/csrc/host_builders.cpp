@@ -65,6 +65,50 @@ extern "C" fs_status fs_build_placement(const fs_shape* shape, const int32_t* ct
   return FS_OK;
 }
 
+extern "C" fs_status fs_build_placement_hybrid_heads(const fs_shape* shape, const int32_t* ctx_len,
+                                                     int32_t layer, const int32_t* route,
+                                                     int32_t* owner, int32_t* dp_rank,
+                                                     int64_t* rank_load, int64_t* dp_load) {
+  if (fs_status st = check_shape(shape, "fs_build_placement_hybrid_heads")) return st;
+  const int32_t B = shape->n_req, H = shape->n_kv_heads, R = shape->n_ranks;
+  if (!rank_load || !dp_load) return fs::fail(FS_EINVAL, "fs_build_placement_hybrid_heads: load arrays are NULL");
+  if (B > 0 && (!ctx_len || !owner || !dp_rank))
+    return fs::fail(FS_EINVAL, "fs_build_placement_hybrid_heads: NULL array with n_req %d", B);
+  const int32_t n_tp = (H / R) * R;     // heads every worker shares evenly
+  const int32_t n_dp = H - n_tp;        // leftover heads, replicated and run data-parallel
+  const int32_t first = floor_mod(layer, R);
+  for (int32_t r = 0; r < B; ++r) {
+    const int64_t L = ctx_len[r];
+    if (L < 1)
+      return fs::fail(FS_EINVAL, "fs_build_placement_hybrid_heads: ctx_len[%d] = %d < 1", r, ctx_len[r]);
+    int32_t* own = owner + static_cast<int64_t>(r) * H;
+    int32_t k = first;
+    for (int32_t h = 0; h < n_tp; ++h) {
+      own[h] = k;
+      rank_load[k] += L;
+      if (++k == R) k = 0;
+    }
+    if (n_dp == 0) {
+      dp_rank[r] = -1;
+      continue;
+    }
+    int32_t best = 0;
+    if (route) {
+      best = route[r];
+      if (best < 0 || best >= R)
+        return fs::fail(FS_EINVAL, "fs_build_placement_hybrid_heads: route[%d] = %d outside [0, %d)", r, best, R);
+    } else {
+      for (int32_t j = 1; j < R; ++j)
+        if (dp_load[j] < dp_load[best]) best = j;   // pending DP work only; equal loads keep the lowest rank
+    }
+    std::fill(own + n_tp, own + H, best);
+    dp_rank[r] = best;
+    rank_load[best] += n_dp * L;
+    dp_load[best] += n_dp * L;
+  }
+  return FS_OK;
+}
+
 extern "C" fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len,
                                        const int32_t* owner, int32_t rank, int32_t chunk_tokens,
                                        fs_work_item* items, int64_t items_cap,

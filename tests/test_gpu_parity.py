@@ -344,3 +344,35 @@ def test_hip_graph_replays_match_eager():
         assert torch.equal(ds.out, eager_o)
     ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
     check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, "graph replay vs oracle")
+
+
+def test_head_level_hybrid_every_rank_and_reassembly():
+    """The paper's literal hybrid attention (Section 3.1): 8 KV heads on 7 workers, one head each
+    tensor-parallel (rotated by layer), the eighth replicated and routed by least pending DP load.
+    Every rank's share against the oracle, then gathered against unsharded attention."""
+    w = make_requests(1, n_req=20, max_len=1200)
+    B, Hq, Hkv, R, G = w["n_req"], w["n_q_heads"], w["n_kv_heads"], 7, w["group"]
+    w["n_ranks"] = R
+    q = make_q(w["seed"], B, Hq, 128)
+    sh = shape_of(w)
+    layer = 3
+    owner, dp, load, dload = fs.fs_build_placement_hybrid_heads(sh, w["ctx_len"], layer=layer)
+    ref = oracle.build_placement_hybrid_heads(w["ctx_len"], R, Hkv, layer=layer)
+    for a, b in zip((owner, dp, load, dload), ref):
+        assert a.tobytes() == b.tobytes()
+    full_o = np.full((B, Hq, 128), np.nan); full_l = np.full((B, Hq), np.nan)
+    for k in range(R):
+        say(f"head-level hybrid rank {k}")
+        ds, kv, items, pairs, sched, indptr = run_rank(w, q, k, 256, owner)
+        pr = pairs_rows(pairs)
+        assert int(pr[:, 2].sum()) == load[k]
+        ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pr, Hq, G, w["sm_scale"])
+        out, lse = ds.out.cpu().numpy(), ds.lse.cpu().numpy()
+        check(out, lse, ref_o, ref_l, f"head-level rank {k}")
+        for p, (r, h, L, _n) in enumerate(pr):
+            full_o[r, h * G:(h + 1) * G] = out[p * G:(p + 1) * G]
+            full_l[r, h * G:(h + 1) * G] = lse[p * G:(p + 1) * G]
+    all_pairs = np.array([(r, h) for r in range(B) for h in range(Hkv)])
+    kv_all = make_kv_pool(w["seed"], all_pairs, w["ctx_len"])
+    un_o, un_l = oracle.unsharded_attention(q, kv_all, w["ctx_len"], Hq, Hkv, w["sm_scale"])
+    check(full_o, full_l, un_o, un_l, "head-level hybrid, all ranks gathered vs unsharded")

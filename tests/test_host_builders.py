@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "failsafe.h")) as f:
         header = f.read()
     declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
-    assert {"fs_build_placement", "fs_build_worklist", "fs_decode_attention", "fs_merge_lse",
+    assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_decode_attention", "fs_merge_lse",
             "fs_kv_elem_offset", "fs_stream_read_probe", "fs_set_option", "fs_get_option", "fs_last_error",
             "fs_abi_version"} <= declared
     lib = C.CDLL(fs.library_path())
@@ -197,3 +197,35 @@ def test_bound_calls_fill_caller_arrays_like_the_plain_calls():
     assert bufs[3].tobytes() == indptr.tobytes()
     with pytest.raises(TypeError):
         fs.bind_build_placement(sh, ctx.astype(np.int64), mode, owner, dp, load)
+
+
+def test_hybrid_heads_bit_exact_random_and_configs():
+    rng = np.random.default_rng(21)
+    for trial in range(300):
+        R = int(rng.integers(1, 9)); H = int(rng.integers(1, 12)); B = int(rng.integers(0, 14))
+        ctx = rng.integers(1, 5000, size=B).astype(np.int32)
+        layer = int(rng.integers(-3, 40))
+        route = rng.integers(0, R, size=B).astype(np.int32) if rng.random() < 0.4 else None
+        init = rng.integers(0, 1000, size=R); dinit = rng.integers(0, 1000, size=R)
+        sh = _shape(B, H, H, R)
+        got = fs.fs_build_placement_hybrid_heads(sh, ctx, layer=layer, route=route, rank_load=init, dp_load=dinit)
+        ref = oracle.build_placement_hybrid_heads(ctx, R, H, layer=layer, route=route, rank_load=init, dp_load=dinit)
+        for a, b in zip(got, ref):
+            assert a.tobytes() == b.tobytes()
+    for cfg_id in (1, 2, 3):
+        w = make_requests(cfg_id)
+        sh = _shape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"])
+        for layer in (0, 1, 5):
+            got = fs.fs_build_placement_hybrid_heads(sh, w["ctx_len"], layer=layer)
+            ref = oracle.build_placement_hybrid_heads(w["ctx_len"], w["n_ranks"], w["n_kv_heads"], layer=layer)
+            for a, b in zip(got, ref):
+                assert a.tobytes() == b.tobytes()
+            # the map feeds the ordinary work-list builder
+            items, pairs, sched, indptr = fs.fs_build_worklist(sh, w["ctx_len"], got[0], 0, w["chunk_tokens"])
+            oi, op, osch, oind = oracle.build_worklist(w["ctx_len"], ref[0], 0, w["chunk_tokens"], w["n_q_heads"], w["n_kv_heads"])
+            assert _items_as_rows(items).tobytes() == oi.tobytes() and sched.tobytes() == osch.tobytes()
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_placement_hybrid_heads(_shape(1, 4, 4, 3), [5], route=[3])
+    assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError):
+        fs.fs_build_placement_hybrid_heads(_shape(1, 4, 4, 3), [0])
