@@ -147,10 +147,13 @@ FS_API fs_status fs_build_placement_hybrid_heads(const fs_shape* shape, const in
  *
  *  owner        HOST in  [n_req*n_kv_heads]
  *  chunk_tokens 0 or a positive multiple of page_tokens
- *  items        HOST out [items_cap]   may be NULL with items_cap 0 (count only)
- *  pairs        HOST out [pairs_cap]   may be NULL with pairs_cap 0
- *  sched        HOST out [items_cap]   may be NULL iff items is NULL
- *  chunk_indptr HOST out [pairs_cap+1] may be NULL iff pairs is NULL
+ *  items        HOST out [items_cap]
+ *  pairs        HOST out [pairs_cap]
+ *  sched        HOST out [items_cap]
+ *  chunk_indptr HOST out [pairs_cap+1]
+ *               All four NULL (capacities 0): count only.  Otherwise all are filled; an
+ *               array with capacity 0 may be NULL (a rank that owns nothing), except
+ *               chunk_indptr, which always has at least one entry.
  *  n_items, n_pairs  HOST out  always written when the shape is valid
  *
  * FS_ECAPACITY: a non-NULL array is too small; nothing but the counts is valid.

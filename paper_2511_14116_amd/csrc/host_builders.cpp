@@ -128,9 +128,8 @@ extern "C" fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx
     return fs::fail(FS_EINVAL, "fs_build_worklist: chunk_tokens %d is not a multiple of page_tokens %d",
                     chunk_tokens, shape->page_tokens);
   if (B > 0 && (!ctx_len || !owner)) return fs::fail(FS_EINVAL, "fs_build_worklist: NULL input array");
-  if ((items == nullptr) != (sched == nullptr) || (pairs == nullptr) != (chunk_indptr == nullptr))
-    return fs::fail(FS_EINVAL, "fs_build_worklist: items/sched and pairs/chunk_indptr come in pairs");
-  if (items_cap < 0 || pairs_cap < 0 || (!items && items_cap) || (!pairs && pairs_cap))
+  const bool count_only = !items && !pairs && !sched && !chunk_indptr;
+  if (items_cap < 0 || pairs_cap < 0 || (!items && items_cap) || (!pairs && pairs_cap) || (!sched && items_cap))
     return fs::fail(FS_EINVAL, "fs_build_worklist: capacities do not match the arrays");
   const int32_t G = shape->n_q_heads / H;
   const int64_t C = chunk_tokens;
@@ -154,24 +153,24 @@ extern "C" fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx
       static_cast<int64_t>(B) * shape->n_q_heads > std::numeric_limits<int32_t>::max())
     return fs::fail(FS_EINVAL, "fs_build_worklist: row numbers exceed int32 (%lld items x G=%d)",
                     static_cast<long long>(ni), G);
-  if (!items && !pairs) return FS_OK;
-  if ((items && items_cap < ni) || (pairs && pairs_cap < np))
+  if (count_only) return FS_OK;
+  if (items_cap < ni || pairs_cap < np)
     return fs::fail(FS_ECAPACITY, "fs_build_worklist: need %lld items and %lld pairs, have room for %lld and %lld",
                     static_cast<long long>(ni), static_cast<long long>(np),
                     static_cast<long long>(items_cap), static_cast<long long>(pairs_cap));
 
-  // Pass 2: emit.
+  if (!chunk_indptr) return fs::fail(FS_EINVAL, "fs_build_worklist: chunk_indptr is NULL (it has n_pairs+1 entries)");
+
+  // Pass 2: emit.  (An array whose count is zero may be NULL: the capacity checks above cover it.)
   int64_t i = 0, p = 0;
   for (int32_t r = 0; r < B; ++r) {
     const int32_t L = ctx_len[r];
     const int32_t nc = static_cast<int32_t>(C ? (L + C - 1) / C : 1);
     for (int32_t h = 0; h < H; ++h) {
       if (owner[static_cast<int64_t>(r) * H + h] != rank) continue;
-      if (pairs) {
-        pairs[p] = fs_pair{r, h, L, nc};
-        chunk_indptr[p] = i;
-      }
-      if (items) {
+      pairs[p] = fs_pair{r, h, L, nc};
+      chunk_indptr[p] = i;
+      {
         for (int32_t c = 0; c < nc; ++c) {
           fs_work_item& it = items[i + c];
           it.req = r;
@@ -188,9 +187,9 @@ extern "C" fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx
       ++p;
     }
   }
-  if (pairs) chunk_indptr[np] = ni;
+  chunk_indptr[np] = ni;
 
-  if (items) {
+  if (ni > 0) {
     // Longest first; equal lengths keep index order.  Lengths are bounded by the chunk size (or
     // the longest context), so a counting sort keeps this linear for big batches.
     int32_t max_len = 0;

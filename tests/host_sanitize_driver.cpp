@@ -1,0 +1,91 @@
+// Host-side builders under AddressSanitizer + UBSan: random batches through the three host
+// entry points with exactly-sized output arrays (so any write past the end is caught) and a few
+// structural checks.  Built and run by tests/test_host_sanitizers.py; touches no GPU.
+#include <cstdio>
+#include <cstdlib>
+#include <random>
+#include <vector>
+
+#include "failsafe.h"
+
+#define REQUIRE(c)                                                        \
+  do {                                                                    \
+    if (!(c)) {                                                           \
+      std::fprintf(stderr, "FAILED %s at line %d (case %d)\n", #c, __LINE__, g_case); \
+      return 1;                                                           \
+    }                                                                     \
+  } while (0)
+
+static int g_case = 0;
+
+int main() {
+  std::mt19937 rng(12345);
+  for (g_case = 0; g_case < 400; ++g_case) {
+    const int R = 1 + rng() % 8, H = 1 + rng() % 9, G = 1 + rng() % 4, B = rng() % 20;
+    fs_shape sh{B, H * G, H, 128, 16, R};
+    std::vector<int32_t> ctx(B);
+    std::vector<uint8_t> mode(B);
+    for (int r = 0; r < B; ++r) {
+      ctx[r] = 1 + rng() % 5000;
+      mode[r] = rng() % 3 == 0;
+    }
+    std::vector<int32_t> owner(static_cast<size_t>(B) * H), dp(B);
+    std::vector<int64_t> load(R, 0), dload(R, 0);
+    if (g_case % 2 == 0) {
+      REQUIRE(fs_build_placement(&sh, ctx.data(), mode.data(), nullptr, static_cast<int32_t>(rng() % 50) - 10,
+                                 owner.data(), dp.data(), load.data()) == FS_OK);
+    } else {
+      REQUIRE(fs_build_placement_hybrid_heads(&sh, ctx.data(), static_cast<int32_t>(rng() % 50) - 10, nullptr,
+                                              owner.data(), dp.data(), load.data(), dload.data()) == FS_OK);
+    }
+    int64_t total = 0;
+    for (int r = 0; r < B; ++r) total += static_cast<int64_t>(ctx[r]) * H;
+    int64_t sum = 0;
+    for (int64_t x : load) sum += x;
+    REQUIRE(sum == total);
+    const int chunks[] = {0, 16, 64, 1024};
+    const int chunk = chunks[rng() % 4];
+    int64_t covered = 0;
+    for (int k = 0; k < R; ++k) {
+      int64_t ni = -1, np = -1;
+      REQUIRE(fs_build_worklist(&sh, ctx.data(), owner.data(), k, chunk, nullptr, 0, nullptr, 0, nullptr, nullptr,
+                                &ni, &np) == FS_OK);
+      std::vector<fs_work_item> items(ni);
+      std::vector<fs_pair> pairs(np);
+      std::vector<int32_t> sched(ni);
+      std::vector<int64_t> indptr(np + 1);
+      REQUIRE(fs_build_worklist(&sh, ctx.data(), owner.data(), k, chunk, items.data(), ni, pairs.data(), np,
+                                sched.data(), indptr.data(), &ni, &np) == FS_OK);
+      int64_t toks = 0;
+      for (const auto& it : items) toks += it.tok_end - it.tok_begin;
+      REQUIRE(toks == load[k]);
+      for (int64_t j = 1; j < ni; ++j) {
+        const auto& a = items[sched[j - 1]];
+        const auto& b = items[sched[j]];
+        REQUIRE(a.tok_end - a.tok_begin >= b.tok_end - b.tok_begin);
+      }
+      REQUIRE(indptr[np] == ni);
+      covered += np;
+      if (ni > 0) {   // one slot too few must be refused, not overrun
+        std::vector<fs_work_item> small(ni - 1);
+        std::vector<int32_t> ssched(ni - 1);
+        int64_t a = 0, b = 0;
+        REQUIRE(fs_build_worklist(&sh, ctx.data(), owner.data(), k, chunk, small.data(), ni - 1, pairs.data(), np,
+                                  ssched.data(), indptr.data(), &a, &b) == FS_ECAPACITY);
+        REQUIRE(a == ni && b == np);
+      }
+    }
+    REQUIRE(covered == static_cast<int64_t>(B) * H);
+  }
+  // error paths leave a message
+  fs_shape bad{1, 4, 2, 128, 16, 0};
+  int32_t one = 5;
+  uint8_t m = 0;
+  int32_t o[2], d;
+  int64_t l[1] = {0};
+  REQUIRE(fs_build_placement(&bad, &one, &m, nullptr, 0, o, &d, l) == FS_EINVAL);
+  REQUIRE(fs_last_error()[0] != 0);
+  REQUIRE(fs_kv_elem_offset(FS_KV_BF16, 0, 15, 127) == 2047 && fs_kv_elem_offset(FS_KV_BF16, 1, 16, 0) == -1);
+  std::puts("host sanitizer run: ok");
+  return 0;
+}
