@@ -10,6 +10,9 @@
  *   fs_decode_attention  per-item partial attention (out, lse)          device
  *   fs_merge_lse         split-K partials -> final (out, lse)           device
  *
+ * and, before the decode step, the host side of the paper's router and prefill
+ * scheduler: fs_route_request, fs_schedule_prefill.
+ *
  * The placement rules are those of the paper's Section 3.1 ("Memory and
  * Computation Balancer": Cyclic Placement, Hybrid Attention, Load-Aware DP-Rank
  * Routing); attention is the decode phase of Section 2.1.1 over KVCache blocks.
@@ -166,6 +169,58 @@ FS_API fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len
                             fs_pair* pairs, int64_t pairs_cap,
                             int32_t* sched, int64_t* chunk_indptr,
                             int64_t* n_items, int64_t* n_pairs);
+
+/* ---------------------------------------------------------------------------
+ * fs_route_request - Section 3.1, Load-Aware DP-Rank Routing: the incoming request
+ * goes to the rank whose pending DP work (token units) is smallest, the lowest rank
+ * among equals; `work` is added to that rank's pending work.
+ *
+ *  pending  HOST in/out [n_ranks]   pending work per rank
+ *  work     the request's work in token units, >= 0
+ *  rank     HOST out                the chosen rank
+ *
+ * FS_EINVAL: NULL pointer, n_ranks < 1, work < 0.
+ */
+FS_API fs_status fs_route_request(int32_t n_ranks, int64_t* pending, int64_t work, int32_t* rank);
+
+/* One waiting request of the prefill queue: n_new tokens wait behind n_done tokens
+ * that are already processed; rank is the request's DP rank. */
+typedef struct {
+  int32_t req, rank, n_done, n_new;
+} fs_prefill_entry;
+
+/* ---------------------------------------------------------------------------
+ * fs_schedule_prefill - Section 3.1, Algorithm 1 (DP-aware Adaptive Chunked
+ * Prefill): form the next prefill batch under a global token budget.
+ *
+ * S_r, the schedulable tokens of rank r, is the concatenation in array order of
+ * the waiting tokens of the entries with that rank.  While the batch holds fewer
+ * than `budget` tokens and some S_r is not empty: take the first token of S_r for
+ * the least-loaded such r (lowest rank among equals), add the token's cost to
+ * that rank's load, and remember the batch so far as a candidate.  Return the
+ * best candidate.  Fixed here where the paper is open:
+ *   cost of a token = tokens of its request before it + 1 (the keys it attends
+ *     to); a chunk of N tokens after L processed ones then costs
+ *     N*L + N*(N+1)/2, the paper's O(N^2 + N*L + N);
+ *   best candidate = among the candidates of at least min(min_tokens, all taken)
+ *     tokens, the one with the smallest (largest load)/(mean load); the larger
+ *     batch among equals;
+ *   loads start at init_load[r], or at 0 when init_load is NULL (the printed
+ *     initialisation; the algorithm lists per-rank workloads as an input).
+ *
+ *  entries   HOST in  [n_entries]
+ *  init_load HOST in  [n_ranks] or NULL
+ *  take      HOST out [n_entries]  leading waiting tokens of each entry in the batch
+ *  load      HOST out [n_ranks]    rank loads of the chosen batch (init_load included)
+ *  n_tokens  HOST out              tokens in the chosen batch (0 when nothing waits or budget is 0)
+ *
+ * FS_EINVAL: NULL pointer, n_ranks < 1, negative budget/min_tokens/n_entries,
+ * entry with rank outside [0, n_ranks) or negative counts.
+ */
+FS_API fs_status fs_schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens,
+                                     const fs_prefill_entry* entries, int32_t n_entries,
+                                     const int64_t* init_load, int32_t* take, int64_t* load,
+                                     int32_t* n_tokens);
 
 /* ---------------------------------------------------------------------------
  * The paged KVCache as the kernels read it.

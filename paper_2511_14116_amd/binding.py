@@ -36,6 +36,7 @@ class FsKvView(C.Structure):
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in
                        ("req", "kv_head", "tok_begin", "tok_end", "pair", "chunk", "q_row", "part_row")])
 PAIR_DTYPE = np.dtype([(n, np.int32) for n in ("req", "kv_head", "ctx_len", "n_chunks")])
+PREFILL_ENTRY_DTYPE = np.dtype([(n, np.int32) for n in ("req", "rank", "n_done", "n_new")])
 
 
 def library_path() -> str:
@@ -61,6 +62,10 @@ def load_library(path: str | None = None):
                                       C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_void_p, i64p, i64p]
     lib.fs_build_worklist.restype = C.c_int
+    lib.fs_route_request.argtypes = [C.c_int32, i64p, C.c_int64, i32p]
+    lib.fs_route_request.restype = C.c_int
+    lib.fs_schedule_prefill.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, i64p, i32p, i64p, i32p]
+    lib.fs_schedule_prefill.restype = C.c_int
     lib.fs_kv_elem_offset.argtypes = [C.c_int32] * 4
     lib.fs_kv_elem_offset.restype = C.c_int32
     lib.fs_decode_attention.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
@@ -183,6 +188,40 @@ def fs_build_worklist(shape: FsShape, ctx_len, owner, rank: int, chunk_tokens: i
     _check(st)
     n, m = n_items.value, n_pairs.value
     return items[:n], pairs[:m], sched[:n], indptr[:m + 1]
+
+
+def fs_route_request(pending: np.ndarray, work: int) -> int:
+    """Route one request; ``pending`` (int64, one entry per rank) is updated in place.  -> rank."""
+    if not isinstance(pending, np.ndarray) or pending.dtype != np.int64 or not pending.flags.c_contiguous:
+        raise TypeError("pending must be a contiguous int64 array (it is updated in place)")
+    rank = C.c_int32(-1)
+    st = load_library().fs_route_request(len(pending), pending.ctypes.data_as(C.POINTER(C.c_int64)), work,
+                                         C.byref(rank))
+    _check(st)
+    return rank.value
+
+
+def fs_schedule_prefill(n_ranks: int, budget: int, min_tokens: int, entries, init_load=None):
+    """-> (take [n_entries] int32, load [R] int64, n_tokens).  ``entries``: PREFILL_ENTRY_DTYPE array or
+    rows of (req, rank, n_done, n_new)."""
+    lib = load_library()
+    if isinstance(entries, np.ndarray) and entries.dtype == PREFILL_ENTRY_DTYPE:
+        ent = np.ascontiguousarray(entries)
+    else:
+        ent = np.ascontiguousarray(np.asarray(entries, dtype=np.int32).reshape(-1, 4)).view(PREFILL_ENTRY_DTYPE).reshape(-1)
+    n = len(ent)
+    take = np.zeros(n, dtype=np.int32)
+    load = np.zeros(max(n_ranks, 0), dtype=np.int64)
+    init = None if init_load is None else _host(init_load, np.int64)
+    if init is not None and len(init) != n_ranks:
+        raise ValueError("init_load must have one entry per rank")
+    n_tok = C.c_int32(0)
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    st = lib.fs_schedule_prefill(n_ranks, budget, min_tokens, ent.ctypes.data if n else None, n,
+                                 None if init is None else init.ctypes.data_as(i64p),
+                                 take.ctypes.data_as(i32p), load.ctypes.data_as(i64p), C.byref(n_tok))
+    _check(st)
+    return take, load, n_tok.value
 
 
 def fs_kv_elem_offset(kv_dtype: int, is_v: int, tok: int, d: int) -> int:

@@ -77,6 +77,33 @@ int main() {
     }
     REQUIRE(covered == static_cast<int64_t>(B) * H);
   }
+  // router and prefill scheduler: exactly-sized arrays, token conservation, budget respected
+  for (g_case = 1000; g_case < 1300; ++g_case) {
+    const int R = 1 + rng() % 8, n = rng() % 12;
+    std::vector<int64_t> pending(R, 0);
+    std::vector<fs_prefill_entry> ent(n);
+    int64_t waiting = 0;
+    for (int e = 0; e < n; ++e) {
+      const int32_t n_new = rng() % 50;
+      int32_t rank = -1;
+      REQUIRE(fs_route_request(R, pending.data(), n_new, &rank) == FS_OK);
+      REQUIRE(rank >= 0 && rank < R);
+      ent[e] = fs_prefill_entry{e, rank, static_cast<int32_t>(rng() % 100000), n_new};
+      waiting += n_new;
+    }
+    const int budget = rng() % 200, floor_tokens = rng() % 220;
+    std::vector<int32_t> take(n);
+    std::vector<int64_t> load(R);
+    int32_t n_tok = -1;
+    REQUIRE(fs_schedule_prefill(R, budget, floor_tokens, ent.data(), n, nullptr, take.data(), load.data(), &n_tok) == FS_OK);
+    int64_t sum = 0;
+    for (int e = 0; e < n; ++e) {
+      REQUIRE(take[e] >= 0 && take[e] <= ent[e].n_new);
+      sum += take[e];
+    }
+    REQUIRE(sum == n_tok && n_tok <= budget && n_tok <= waiting);
+    if (floor_tokens >= budget) REQUIRE(n_tok == (waiting < budget ? waiting : budget));
+  }
   // error paths leave a message
   fs_shape bad{1, 4, 2, 128, 16, 0};
   int32_t one = 5;

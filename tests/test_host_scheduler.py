@@ -1,0 +1,91 @@
+"""The C++ router and prefill scheduler against the oracle, value for value (no GPU needed)."""
+import json
+import os
+import time
+
+import numpy as np
+import pytest
+
+import paper_2511_14116_amd as fs
+from oracle.scheduler import adaptive_chunked_prefill, route_request
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(fs.library_path()):
+        from paper_2511_14116_amd.build import build
+        build(verbose=False)
+    return fs.load_library()
+
+
+def test_fig4_through_the_library():
+    with open(os.path.join(GOLD, "fig4_router_scheduler.json")) as f:
+        g = json.load(f)
+    R = g["n_ranks"]
+    pending = np.zeros(R, dtype=np.int64)
+    for _req, gpu, toks in g["queued"]:
+        pending[gpu] += toks
+    gpu3 = fs.fs_route_request(pending, g["new_request_tokens"])
+    assert gpu3 == g["load_aware_gpu_of_request_3"] and pending.tolist() == [4, 2, 1]
+    entries = [(req, gpu, 0, toks) for req, gpu, toks in g["queued"]] + [(3, gpu3, 0, 1)]
+    take, load, n = fs.fs_schedule_prefill(R, g["budget"], (g["budget"] + 1) // 2, entries)
+    assert take.tolist() == g["adaptive_batch_tokens_per_request"] and n == 3 and load.tolist() == [1, 1, 1]
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_scheduler_matches_oracle_on_random_queues(seed):
+    rng = np.random.default_rng(1000 + seed)
+    R = int(rng.integers(1, 9))
+    n = int(rng.integers(0, 14))
+    entries = [(i, int(rng.integers(0, R)), int(rng.integers(0, 3000)), int(rng.integers(0, 40))) for i in range(n)]
+    budget = int(rng.integers(0, 150))
+    min_tokens = int(rng.integers(0, budget + 3))
+    init = None if seed % 2 else [int(x) for x in rng.integers(0, 5000, size=R)]
+    want = adaptive_chunked_prefill(budget, R, entries, min_tokens, init)
+    take, load, n_tok = fs.fs_schedule_prefill(R, budget, min_tokens, entries, init)
+    assert take.tolist() == want[0] and load.tolist() == list(want[1]) and n_tok == want[2]
+
+
+def test_router_matches_oracle():
+    rng = np.random.default_rng(5)
+    for R in (1, 3, 7):
+        a = np.zeros(R, dtype=np.int64)
+        b = [0] * R
+        for w in rng.integers(0, 10000, size=300):
+            assert fs.fs_route_request(a, int(w)) == route_request(b, int(w))
+        assert a.tolist() == b
+
+
+def test_serving_sized_budget_is_fast_and_balanced():
+    # 7 ranks, 64 waiting prompts shaped like the paper's online trace (mean ~13.5K tokens), budget 8192
+    rng = np.random.default_rng(11)
+    R = 7
+    lens = np.clip(np.round(np.exp(rng.normal(np.log(8001), 0.9, size=64))), 1, 123192).astype(np.int64)
+    pending = np.zeros(R, dtype=np.int64)
+    entries = np.zeros(64, dtype=fs.PREFILL_ENTRY_DTYPE)
+    for i, L in enumerate(lens):
+        entries[i] = (i, fs.fs_route_request(pending, int(L)), 0, int(L))
+    assert pending.max() - pending.min() <= lens.max()
+    t0 = time.perf_counter()
+    take, load, n = fs.fs_schedule_prefill(R, 8192, 4096, entries)
+    dt = time.perf_counter() - t0
+    assert n >= 4096 and take.sum() == n
+    assert load.max() * R / load.sum() < 1.01          # a token budget spread evenly over the ranks
+    assert dt < 0.05
+
+
+def test_errors():
+    with pytest.raises(fs.FsError):
+        fs.fs_schedule_prefill(0, 4, 0, [])
+    with pytest.raises(fs.FsError):
+        fs.fs_schedule_prefill(2, 4, 0, [(0, 2, 0, 1)])
+    with pytest.raises(fs.FsError):
+        fs.fs_schedule_prefill(2, -1, 0, [(0, 1, 0, 1)])
+    with pytest.raises(fs.FsError):
+        fs.fs_route_request(np.zeros(3, dtype=np.int64), -5)
+    with pytest.raises(TypeError):
+        fs.fs_route_request([0, 0], 1)
+    take, load, n = fs.fs_schedule_prefill(3, 10, 5, [])
+    assert len(take) == 0 and n == 0 and load.tolist() == [0, 0, 0]
