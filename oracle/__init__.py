@@ -14,6 +14,7 @@ unpinned".
 """
 from .formats import bf16_bits_to_f64, e4m3_bytes_to_f64, E4M3_TABLE  # noqa: F401
 from .placement import build_placement, build_placement_hybrid_heads  # noqa: F401
+from .recovery import plan_ffn_reload, plan_kv_reload, replace_failed_gpu  # noqa: F401
 from .scheduler import adaptive_chunked_prefill, route_request, token_cost  # noqa: F401
 from .worklist import build_worklist, ITEM_FIELDS, PAIR_FIELDS  # noqa: F401
 from .attention import (  # noqa: F401
