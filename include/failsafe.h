@@ -11,7 +11,8 @@
  *   fs_merge_lse         split-K partials -> final (out, lse)           device
  *
  * and, before the decode step, the host side of the paper's router and prefill
- * scheduler: fs_route_request, fs_schedule_prefill.
+ * scheduler: fs_route_request, fs_schedule_prefill; after a fault, the recovery
+ * plans: fs_plan_kv_reload, fs_replace_failed_gpu, fs_plan_ffn_reload.
  *
  * The placement rules are those of the paper's Section 3.1 ("Memory and
  * Computation Balancer": Cyclic Placement, Hybrid Attention, Load-Aware DP-Rank
@@ -221,6 +222,60 @@ FS_API fs_status fs_schedule_prefill(int32_t n_ranks, int32_t budget, int32_t mi
                                      const fs_prefill_entry* entries, int32_t n_entries,
                                      const int64_t* init_load, int32_t* take, int64_t* load,
                                      int32_t* n_tokens);
+
+/* ---------------------------------------------------------------------------
+ * Recovery planning after a GPU fault - Section 3.2, "Lightning Recovery", as
+ * plans (what moves where); the transfers themselves are not part of this library.
+ * GPU ids are physical ids in [0, n_gpus); alive[g] != 0 marks the GPUs that live
+ * (HOST in [n_gpus], at least one), so a later fault is planned with the earlier
+ * dead GPUs still marked dead.
+ *
+ * fs_plan_kv_reload - Proactive KVCache Backup: a surviving GPU keeps the KVCache
+ * it holds and reloads from the host copy only what it newly needs.  For one layer
+ * and any two placements: slice (r, h) is reused when new_owner == old_owner and
+ * reloaded by new_owner otherwise.
+ *
+ *  ctx_len    HOST in  [n_req]             each >= 1
+ *  old_owner  HOST in  [n_req*n_kv_heads]  GPU holding (r, h) before the fault
+ *  new_owner  HOST in  [n_req*n_kv_heads]  GPU holding it afterwards, a live one
+ *  reload     HOST out [n_gpus]            KV tokens x KV heads each GPU reads from the host copy
+ *  reuse      HOST out [n_gpus]            KV tokens x KV heads each GPU keeps in place
+ *
+ * fs_replace_failed_gpu - the placement that moves nothing but the lost slices,
+ * the way hybrid attention (Section 3.1; Fig. 5) absorbs a lost worker: slices on
+ * surviving GPUs stay; the lost slices of request r become data-parallel work on
+ * r's DP rank; a request whose DP rank is -1 or dead is routed to the
+ * live GPU with the least dp_load (lowest id among equals), in request
+ * order; dp_load grows by (lost heads)*ctx_len[r].  Meant for the case where the
+ * tensor-parallel share per worker stays, floor(H/(R-1)) == floor(H/R); otherwise
+ * build a fresh placement and diff it with fs_plan_kv_reload.
+ *
+ *  old_dp_rank HOST in  [n_req]            -1 for a request without one
+ *  new_owner   HOST out [n_req*n_kv_heads]
+ *  new_dp_rank HOST out [n_req]
+ *  dp_load     HOST in/out [n_gpus]        pending DP work per GPU (entries of dead GPUs are ignored)
+ *
+ * fs_plan_ffn_reload - On-Demand Weight Recovery: FFN shards (slices along the
+ * intermediate dimension, whose order is free) stay where they are; each lost
+ * shard, in ascending index, goes to the live GPU that holds the fewest
+ * shards (lowest id among equals).
+ *
+ *  shard_owner HOST in  [n_shards]
+ *  new_owner   HOST out [n_shards]
+ *  n_load      HOST out [n_gpus]           shards each GPU reads from the host
+ *
+ * All three: FS_EINVAL for NULL pointers, n_gpus < 1, no live GPU, an owner
+ * outside [0, n_gpus), ctx_len < 1, a new owner that is dead.
+ */
+FS_API fs_status fs_plan_kv_reload(int32_t n_req, int32_t n_kv_heads, const int32_t* ctx_len,
+                                   const int32_t* old_owner, const int32_t* new_owner,
+                                   int32_t n_gpus, const uint8_t* alive, int64_t* reload, int64_t* reuse);
+FS_API fs_status fs_replace_failed_gpu(int32_t n_req, int32_t n_kv_heads, const int32_t* ctx_len,
+                                       const int32_t* old_owner, const int32_t* old_dp_rank,
+                                       int32_t n_gpus, const uint8_t* alive, int32_t* new_owner,
+                                       int32_t* new_dp_rank, int64_t* dp_load);
+FS_API fs_status fs_plan_ffn_reload(int32_t n_shards, const int32_t* shard_owner, int32_t n_gpus,
+                                    const uint8_t* alive, int32_t* new_owner, int32_t* n_load);
 
 /* ---------------------------------------------------------------------------
  * The paged KVCache as the kernels read it.

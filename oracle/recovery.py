@@ -22,19 +22,27 @@ where), not as transfers:
   lowest id).  ``plan_ffn_reload`` returns the new owner of every shard.
 
 GPU ids are physical: a placement over R-1 survivors is given in the ids of the
-GPUs that survive, so "same owner" means "same device".
+GPUs that survive, so "same owner" means "same device".  Which GPUs live is a mask
+over the ids, so a second fault is planned with the first GPU still marked dead.
 """
 import numpy as np
 
 
-def plan_kv_reload(ctx_len, old_owner, new_owner, n_gpus: int, failed: int):
+def _live(alive):
+    live = [g for g, a in enumerate(alive) if a]
+    if not live:
+        raise ValueError("no GPU survives")
+    return live
+
+
+def plan_kv_reload(ctx_len, old_owner, new_owner, alive):
     """-> (reload [n_gpus], reuse [n_gpus]) in KV tokens x KV heads per GPU, for one layer."""
     old_owner = np.asarray(old_owner)
     new_owner = np.asarray(new_owner)
     if old_owner.shape != new_owner.shape or old_owner.ndim != 2 or old_owner.shape[0] != len(ctx_len):
         raise ValueError("owner maps must both be [n_req][n_kv_heads]")
-    if not 0 <= failed < n_gpus:
-        raise ValueError("failed GPU outside [0, n_gpus)")
+    n_gpus = len(alive)
+    _live(alive)
     reload = [0] * n_gpus
     reuse = [0] * n_gpus
     for r in range(old_owner.shape[0]):
@@ -43,8 +51,8 @@ def plan_kv_reload(ctx_len, old_owner, new_owner, n_gpus: int, failed: int):
             raise ValueError("a request holds at least one token")
         for h in range(old_owner.shape[1]):
             a, b = int(old_owner[r, h]), int(new_owner[r, h])
-            if not (0 <= a < n_gpus and 0 <= b < n_gpus) or b == failed:
-                raise ValueError("owner outside the GPUs, or new owner is the failed GPU")
+            if not (0 <= a < n_gpus and 0 <= b < n_gpus) or not alive[b]:
+                raise ValueError("owner outside the GPUs, or new owner is a dead GPU")
             if a == b:
                 reuse[b] += L
             else:
@@ -52,22 +60,21 @@ def plan_kv_reload(ctx_len, old_owner, new_owner, n_gpus: int, failed: int):
     return np.array(reload, dtype=np.int64), np.array(reuse, dtype=np.int64)
 
 
-def replace_failed_gpu(ctx_len, old_owner, old_dp_rank, n_gpus: int, failed: int, dp_load=None):
+def replace_failed_gpu(ctx_len, old_owner, old_dp_rank, alive, dp_load=None):
     """-> (new_owner [B][H], new_dp_rank [B], dp_load [n_gpus]) moving only the lost slices."""
     old_owner = np.asarray(old_owner)
     B, H = old_owner.shape
-    if not 0 <= failed < n_gpus or n_gpus < 2:
-        raise ValueError("need a failed GPU inside [0, n_gpus) and at least one survivor")
+    n_gpus = len(alive)
+    survivors = _live(alive)
     load = [0] * n_gpus if dp_load is None else [int(x) for x in dp_load]
     new_owner = old_owner.astype(np.int32).copy()
     new_dp = np.asarray(old_dp_rank, dtype=np.int32).copy()
-    survivors = [g for g in range(n_gpus) if g != failed]
     for r in range(B):
-        lost = [h for h in range(H) if old_owner[r, h] == failed]
+        lost = [h for h in range(H) if not alive[old_owner[r, h]]]
         if not lost:
             continue
         d = int(new_dp[r])
-        if d < 0 or d == failed:
+        if d < 0 or not alive[d]:
             d = min(survivors, key=lambda g: (load[g], g))
             new_dp[r] = d
         for h in lost:
@@ -76,19 +83,18 @@ def replace_failed_gpu(ctx_len, old_owner, old_dp_rank, n_gpus: int, failed: int
     return new_owner, new_dp, np.array(load, dtype=np.int64)
 
 
-def plan_ffn_reload(shard_owner, n_gpus: int, failed: int):
+def plan_ffn_reload(shard_owner, alive):
     """-> (new_owner [n_shards], n_load [n_gpus]): survivors keep their shards, lost ones are dealt out."""
     owner = [int(x) for x in shard_owner]
-    if not 0 <= failed < n_gpus or n_gpus < 2:
-        raise ValueError("need a failed GPU inside [0, n_gpus) and at least one survivor")
+    n_gpus = len(alive)
+    survivors = _live(alive)
     if any(not 0 <= g < n_gpus for g in owner):
         raise ValueError("shard owner outside [0, n_gpus)")
     count = [sum(1 for g in owner if g == k) for k in range(n_gpus)]
     n_load = [0] * n_gpus
-    survivors = [g for g in range(n_gpus) if g != failed]
     new_owner = list(owner)
     for s, g in enumerate(owner):
-        if g != failed:
+        if alive[g]:
             continue
         k = min(survivors, key=lambda x: (count[x], x))
         new_owner[s] = k

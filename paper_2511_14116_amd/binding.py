@@ -66,6 +66,12 @@ def load_library(path: str | None = None):
     lib.fs_route_request.restype = C.c_int
     lib.fs_schedule_prefill.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, i64p, i32p, i64p, i32p]
     lib.fs_schedule_prefill.restype = C.c_int
+    lib.fs_plan_kv_reload.argtypes = [C.c_int32, C.c_int32, i32p, i32p, i32p, C.c_int32, u8p, i64p, i64p]
+    lib.fs_plan_kv_reload.restype = C.c_int
+    lib.fs_replace_failed_gpu.argtypes = [C.c_int32, C.c_int32, i32p, i32p, i32p, C.c_int32, u8p, i32p, i32p, i64p]
+    lib.fs_replace_failed_gpu.restype = C.c_int
+    lib.fs_plan_ffn_reload.argtypes = [C.c_int32, i32p, C.c_int32, u8p, i32p, i32p]
+    lib.fs_plan_ffn_reload.restype = C.c_int
     lib.fs_kv_elem_offset.argtypes = [C.c_int32] * 4
     lib.fs_kv_elem_offset.restype = C.c_int32
     lib.fs_decode_attention.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
@@ -222,6 +228,72 @@ def fs_schedule_prefill(n_ranks: int, budget: int, min_tokens: int, entries, ini
                                  take.ctypes.data_as(i32p), load.ctypes.data_as(i64p), C.byref(n_tok))
     _check(st)
     return take, load, n_tok.value
+
+
+def _owner2d(a, B):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    if a.ndim != 2 or a.shape[0] != B:
+        raise ValueError("owner maps must be [n_req][n_kv_heads]")
+    return a
+
+
+def _alive(alive):
+    return np.ascontiguousarray(np.asarray(alive) != 0, dtype=np.uint8)
+
+
+def fs_plan_kv_reload(ctx_len, old_owner, new_owner, alive):
+    """-> (reload [n_gpus] int64, reuse [n_gpus] int64), KV tokens x KV heads per GPU for one layer."""
+    ctx = _host(ctx_len, np.int32)
+    old, new = _owner2d(old_owner, len(ctx)), _owner2d(new_owner, len(ctx))
+    if old.shape != new.shape:
+        raise ValueError("owner maps differ in shape")
+    al = _alive(alive)
+    n_gpus = len(al)
+    reload = np.zeros(n_gpus, dtype=np.int64)
+    reuse = np.zeros(n_gpus, dtype=np.int64)
+    i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+    st = load_library().fs_plan_kv_reload(len(ctx), old.shape[1], ctx.ctypes.data_as(i32p), old.ctypes.data_as(i32p),
+                                          new.ctypes.data_as(i32p), n_gpus, al.ctypes.data_as(u8p),
+                                          reload.ctypes.data_as(i64p), reuse.ctypes.data_as(i64p))
+    _check(st)
+    return reload, reuse
+
+
+def fs_replace_failed_gpu(ctx_len, old_owner, old_dp_rank, alive, dp_load=None):
+    """-> (new_owner [B][H] int32, new_dp_rank [B] int32, dp_load [n_gpus] int64)."""
+    ctx = _host(ctx_len, np.int32)
+    old = _owner2d(old_owner, len(ctx))
+    odp = _host(old_dp_rank, np.int32)
+    if len(odp) != len(ctx):
+        raise ValueError("old_dp_rank must have n_req entries")
+    new = np.empty_like(old)
+    ndp = np.empty_like(odp)
+    al = _alive(alive)
+    n_gpus = len(al)
+    load = np.zeros(n_gpus, dtype=np.int64) if dp_load is None else np.array(dp_load, dtype=np.int64)
+    if len(load) != n_gpus:
+        raise ValueError("dp_load must have one entry per GPU")
+    i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+    st = load_library().fs_replace_failed_gpu(len(ctx), old.shape[1], ctx.ctypes.data_as(i32p),
+                                              old.ctypes.data_as(i32p), odp.ctypes.data_as(i32p), n_gpus, al.ctypes.data_as(u8p),
+                                              new.ctypes.data_as(i32p), ndp.ctypes.data_as(i32p),
+                                              load.ctypes.data_as(i64p))
+    _check(st)
+    return new, ndp, load
+
+
+def fs_plan_ffn_reload(shard_owner, alive):
+    """-> (new_owner [n_shards] int32, n_load [n_gpus] int32)."""
+    own = _host(shard_owner, np.int32)
+    new = np.empty_like(own)
+    al = _alive(alive)
+    n_gpus = len(al)
+    n_load = np.zeros(n_gpus, dtype=np.int32)
+    i32p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_uint8)
+    st = load_library().fs_plan_ffn_reload(len(own), own.ctypes.data_as(i32p), n_gpus, al.ctypes.data_as(u8p),
+                                           new.ctypes.data_as(i32p), n_load.ctypes.data_as(i32p))
+    _check(st)
+    return new, n_load
 
 
 def fs_kv_elem_offset(kv_dtype: int, is_v: int, tok: int, d: int) -> int:

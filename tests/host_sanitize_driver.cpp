@@ -104,6 +104,38 @@ int main() {
     REQUIRE(sum == n_tok && n_tok <= budget && n_tok <= waiting);
     if (floor_tokens >= budget) REQUIRE(n_tok == (waiting < budget ? waiting : budget));
   }
+  // recovery planner: exactly-sized arrays, conservation of slices and shards
+  for (g_case = 2000; g_case < 2300; ++g_case) {
+    const int n = 1 + rng() % 8, B = rng() % 16, H = 1 + rng() % 8, S = rng() % 40;
+    std::vector<uint8_t> alive(n);
+    for (auto& a : alive) a = rng() % 2;
+    alive[rng() % n] = 1;
+    std::vector<int32_t> ctx(B), old_owner(static_cast<size_t>(B) * H), old_dp(B), new_owner(old_owner.size()), new_dp(B);
+    for (auto& c : ctx) c = 1 + rng() % 3000;
+    for (auto& o : old_owner) o = rng() % n;
+    for (auto& d : old_dp) d = static_cast<int32_t>(rng() % (n + 1)) - 1;
+    std::vector<int64_t> dload(n, 0), reload(n), reuse(n);
+    REQUIRE(fs_replace_failed_gpu(B, H, ctx.data(), old_owner.data(), old_dp.data(), n, alive.data(), new_owner.data(),
+                                  new_dp.data(), dload.data()) == FS_OK);
+    REQUIRE(fs_plan_kv_reload(B, H, ctx.data(), old_owner.data(), new_owner.data(), n, alive.data(), reload.data(),
+                              reuse.data()) == FS_OK);
+    int64_t moved = 0, kept = 0, lost = 0, total = 0;
+    for (int g = 0; g < n; ++g) { moved += reload[g]; kept += reuse[g]; }
+    for (int r = 0; r < B; ++r)
+      for (int h = 0; h < H; ++h) {
+        total += ctx[r];
+        if (!alive[old_owner[static_cast<size_t>(r) * H + h]]) lost += ctx[r];
+        REQUIRE(alive[new_owner[static_cast<size_t>(r) * H + h]]);
+      }
+    REQUIRE(moved == lost && moved + kept == total);
+    std::vector<int32_t> shard_owner(S), shard_new(S), n_load(n);
+    for (auto& o : shard_owner) o = rng() % n;
+    REQUIRE(fs_plan_ffn_reload(S, shard_owner.data(), n, alive.data(), shard_new.data(), n_load.data()) == FS_OK);
+    int loaded = 0, dead = 0;
+    for (int g = 0; g < n; ++g) loaded += n_load[g];
+    for (int s = 0; s < S; ++s) { dead += !alive[shard_owner[s]]; REQUIRE(alive[shard_new[s]]); }
+    REQUIRE(loaded == dead);
+  }
   // error paths leave a message
   fs_shape bad{1, 4, 2, 128, 16, 0};
   int32_t one = 5;
