@@ -1,0 +1,100 @@
+"""Chunked-prefill attention over the paged KVCache, plain definition in fp64 (oracle side).
+
+Section 3.1 of the paper ("Fine-Grained Chunked Prefill") forms prefill batches that hold
+chunks of several requests: N new tokens of a request behind L tokens already processed.
+The prefill phase (Section 2.1.1) lets every prompt token attend to the tokens up to and
+including itself.  So new token i of a chunk (position L + i) of request r, for q-head j with
+KV head h = j // G, computes
+
+    s_t = sm_scale * <q[i][j], K[r][h][t]>        t in [0, L + i]
+    out = sum_t softmax(s)_t * V[r][h][t]
+    lse = ln sum_t exp(s_t)
+
+which is decode attention of that token over the first L + i + 1 cached tokens; the cache
+already holds the chunk's own K and V.  Test infrastructure only.
+
+Work list of one rank: (request, KV head) pairs the rank owns whose request has new tokens,
+in ascending (request, head); each pair's new tokens are cut into tiles of ``tile_tokens``
+query tokens (the last may be shorter).  Q is the ragged concatenation of the batch's new
+tokens in request order; output rows are per pair, token-major, q-head-minor.
+"""
+import numpy as np
+
+from .attention import attend, gather_pair_kv, _run
+from .formats import bf16_bits_to_f64
+
+PREFILL_ITEM_FIELDS = ("req", "kv_head", "pair", "q_begin", "q_end", "n_done", "q_row", "out_row")
+PREFILL_PAIR_FIELDS = ("req", "kv_head", "n_done", "n_new")
+
+
+def build_prefill_worklist(n_done, n_new, owner, rank: int, n_q_heads: int, tile_tokens: int):
+    """-> (items [n][8] int32, pairs [m][4] int32, sched [n] int32, out_indptr [m+1] int64)."""
+    owner = np.asarray(owner)
+    B, H = owner.shape
+    if n_q_heads % H or tile_tokens < 1:
+        raise ValueError("bad head counts or tile size")
+    G = n_q_heads // H
+    q_indptr = [0]
+    for r in range(B):
+        if n_done[r] < 0 or n_new[r] < 0:
+            raise ValueError("negative token count")
+        q_indptr.append(q_indptr[-1] + int(n_new[r]))
+    items, pairs, out_indptr = [], [], [0]
+    for r in range(B):
+        N, L = int(n_new[r]), int(n_done[r])
+        if N == 0:
+            continue
+        for h in range(H):
+            if owner[r, h] != rank:
+                continue
+            p = len(pairs)
+            pairs.append((r, h, L, N))
+            for b in range(0, N, tile_tokens):
+                e = min(N, b + tile_tokens)
+                items.append((r, h, p, b, e, L, (q_indptr[r] + b) * n_q_heads + h * G, out_indptr[p] + b * G))
+            out_indptr.append(out_indptr[p] + N * G)
+    # longest first: a tile streams the keys up to its last token
+    order = sorted(range(len(items)), key=lambda i: (-(items[i][5] + items[i][4]), i))
+    return (np.array(items, dtype=np.int32).reshape(-1, 8), np.array(pairs, dtype=np.int32).reshape(-1, 4),
+            np.array(order, dtype=np.int32), np.array(out_indptr, dtype=np.int64))
+
+
+def prefill_attention_pairs(q_bits, q_indptr, kv: dict, pairs, n_q_heads: int, group: int, sm_scale: float,
+                            workers: int = 1, only_pairs=None):
+    """Causal attention of every new token of every pair.  q_bits [T][H_q][d] bf16 bits,
+    q_indptr [B+1].  Returns (out [rows][d], lse [rows]) in fp64, rows as the work list orders
+    them (pair-major, then token, then q-head of the group)."""
+    d = kv["head_dim"]
+    qv = q_bits.reshape(-1, n_q_heads, d)
+    out_indptr = np.zeros(len(pairs) + 1, dtype=np.int64)
+    for p in range(len(pairs)):
+        out_indptr[p + 1] = out_indptr[p] + int(pairs[p][3]) * group
+    out = np.full((int(out_indptr[-1]), d), np.nan, dtype=np.float64)
+    lse = np.full(int(out_indptr[-1]), np.nan, dtype=np.float64)
+    todo = list(range(len(pairs))) if only_pairs is None else list(only_pairs)
+
+    def one(k):
+        p = todo[k]
+        r, h, L, N = (int(x) for x in pairs[p])
+        K, V = gather_pair_kv(kv, p, 0, L + N)
+        for i in range(N):
+            q = bf16_bits_to_f64(qv[int(q_indptr[r]) + i, h * group:(h + 1) * group])
+            o, l = attend(q, K[:L + i + 1], V[:L + i + 1], sm_scale)
+            row = int(out_indptr[p]) + i * group
+            out[row:row + group] = o
+            lse[row:row + group] = l
+
+    _run(one, len(todo), workers)
+    return out, lse
+
+
+def prefill_attention_row(q_bits, q_indptr, kv: dict, pairs, n_q_heads: int, group: int, sm_scale: float,
+                          pair: int, tok: int):
+    """One new token of one pair: (out [G][d], lse [G]).  For sampled checks at full size."""
+    d = kv["head_dim"]
+    r, h, L, N = (int(x) for x in pairs[pair])
+    if not 0 <= tok < N:
+        raise ValueError("token outside the chunk")
+    K, V = gather_pair_kv(kv, pair, 0, L + tok + 1)
+    q = bf16_bits_to_f64(q_bits.reshape(-1, n_q_heads, d)[int(q_indptr[r]) + tok, h * group:(h + 1) * group])
+    return attend(q, K, V, sm_scale)

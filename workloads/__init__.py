@@ -13,4 +13,6 @@ from .generate import (  # noqa: F401
     make_q,
     make_kv_pool,
     f32_to_bf16_bits,
+    make_prefill_queue,
+    make_prefill_q,
 )

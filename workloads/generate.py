@@ -183,3 +183,23 @@ def make_kv_pool(seed: int, pairs: np.ndarray, ctx_len: np.ndarray, head_dim: in
     return dict(k_pool=k_pool, v_pool=v_pool, k_scale=k_scale, v_scale=v_scale,
                 page_indptr=page_indptr, page_ids=page_ids, n_slots=n_slots,
                 kv_dtype=kv_dtype, head_dim=head_dim, page_tokens=page_tokens)
+
+
+def make_prefill_queue(seed: int, n_req: int, median: int = 8001, sigma: float = 0.9, cap: int = 123192,
+                       progress: float = 0.5) -> dict:
+    """Waiting prompts for a prefill batch: prompt length per request (lognormal with the median
+    and cap of the paper's online trace, Table 2) and how many of its tokens are already
+    processed (a multiple of 16; a fraction ``progress`` of the requests has made some progress).
+    Routing and batch forming are not done here."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 23])))
+    prompt = np.clip(np.rint(np.exp(rng.normal(np.log(median), sigma, size=n_req))), 1, cap).astype(np.int32)
+    started = rng.random(n_req) < progress
+    done = np.where(started, (rng.random(n_req) * prompt).astype(np.int64) // 16 * 16, 0).astype(np.int32)
+    done = np.minimum(done, prompt - 1).astype(np.int32) // 16 * 16
+    return dict(seed=seed, prompt_len=prompt, n_done=done.astype(np.int32))
+
+
+def make_prefill_q(seed: int, n_tokens: int, n_q_heads: int, head_dim: int) -> np.ndarray:
+    """Query rows of a prefill batch [n_tokens][n_q_heads][head_dim] as bf16 bit patterns, N(0,1)."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 29])))
+    return f32_to_bf16_bits(rng.standard_normal((n_tokens, n_q_heads, head_dim), dtype=np.float32))
