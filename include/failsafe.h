@@ -12,7 +12,8 @@
  *
  * and, before the decode step, the host side of the paper's router and prefill
  * scheduler: fs_route_request, fs_schedule_prefill; after a fault, the recovery
- * plans: fs_plan_kv_reload, fs_replace_failed_gpu, fs_plan_ffn_reload.
+ * plans: fs_plan_kv_reload, fs_replace_failed_gpu, fs_plan_ffn_reload; and the
+ * attention of the prefill batches: fs_build_prefill_worklist, fs_prefill_attention.
  *
  * The placement rules are those of the paper's Section 3.1 ("Memory and
  * Computation Balancer": Cyclic Placement, Hybrid Attention, Load-Aware DP-Rank
@@ -359,6 +360,83 @@ FS_API fs_status fs_merge_lse(const float* part_o, const float* part_lse, const 
                        float* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Chunked-prefill attention - the attention of the batches that the paper's
+ * fine-grained chunked prefill (Section 3.1) forms: n_new[r] new tokens of request
+ * r behind n_done[r] processed ones, chunks of several requests in one batch.
+ * New token i of the chunk sits at position n_done + i and attends to the cached
+ * tokens [0, n_done + i] (prefill phase, Section 2.1.1); the cache already holds
+ * the chunk's own K and V.
+ *
+ * Q of the batch is the ragged concatenation of the new tokens in request order:
+ * [sum n_new][n_q_heads][head_dim] bf16, passed as fs_kv_view.q.  The page table
+ * of fs_kv_view follows the pair order of the list built here and covers
+ * n_done + n_new tokens per pair.
+ *
+ * One unit of kernel work: query tokens [q_begin, q_end) of one pair's chunk. */
+typedef struct {
+  int32_t req;          /* request index                                          */
+  int32_t kv_head;      /* KV head index                                          */
+  int32_t pair;         /* index of the (request, head) pair in this rank's list  */
+  int32_t q_begin;      /* first new token of the tile, within the chunk          */
+  int32_t q_end;        /* one past the last                                      */
+  int32_t n_done;       /* tokens of the request before the chunk                 */
+  int32_t q_row;        /* Q row of (token q_begin, first q-head of the group)    */
+  int32_t out_row;      /* output row of (token q_begin, first q-head)            */
+} fs_prefill_item;
+
+typedef struct {
+  int32_t req, kv_head, n_done, n_new;
+} fs_prefill_pair;
+
+/* fs_build_prefill_worklist - pairs (r, h) with owner == rank and n_new[r] > 0, in
+ * ascending (r, h); pair p is cut into ceil(n_new/tile_tokens) items.  Output rows
+ * of pair p are [out_indptr[p], out_indptr[p+1]), token-major and q-head-minor:
+ * row(token i, group member g) = out_indptr[p] + i*G + g.  sched lists items by
+ * decreasing n_done + q_end (the keys the tile's last token sees), equal ones by
+ * increasing index.
+ *
+ *  n_done, n_new HOST in [n_req]      each >= 0
+ *  owner         HOST in [n_req*n_kv_heads]
+ *  tile_tokens   query tokens per item, >= 1 (fs_prefill_tile_tokens(G) is the kernel's size)
+ *  items, pairs, sched, out_indptr    HOST out, as for fs_build_worklist (all NULL = count only)
+ *
+ * FS_ECAPACITY / FS_EINVAL as for fs_build_worklist; also FS_EINVAL when the
+ * batch has more Q or output rows than int32 holds. */
+FS_API fs_status fs_build_prefill_worklist(const fs_shape* shape, const int32_t* n_done, const int32_t* n_new,
+                                           const int32_t* owner, int32_t rank, int32_t tile_tokens,
+                                           fs_prefill_item* items, int64_t items_cap,
+                                           fs_prefill_pair* pairs, int64_t pairs_cap,
+                                           int32_t* sched, int64_t* out_indptr,
+                                           int64_t* n_items, int64_t* n_pairs);
+
+/* Query tokens one kernel workgroup covers for a group of G q-heads per KV head
+ * (the natural tile_tokens; depends on the "prefill_col_tiles" option).  -1 for
+ * a group outside [1, 16]. */
+FS_API int32_t fs_prefill_tile_tokens(int32_t group);
+
+/* fs_prefill_attention - for every item, every token i in [q_begin, q_end) and g in
+ * [0, G), with q = Q row q_row + (i - q_begin)*n_q_heads + g and t over the cached
+ * tokens [0, n_done + i]:
+ *     s_t = sm_scale * <q, K_t>
+ *     lse[row] = ln sum_t exp(s_t),   out[row][:] = sum_t exp(s_t - lse) * V_t
+ * with row = out_row + (i - q_begin)*G + g.  fp32 scores, softmax and accumulation;
+ * the softmax weights enter P.V as a sum of two bf16 terms.
+ *
+ *  items_dev  DEVICE in  [n_items]   as built by fs_build_prefill_worklist
+ *  sched_dev  DEVICE in  [n_items]   launch order, or NULL for index order
+ *  tile_tokens  the value the list was built with, <= fs_prefill_tile_tokens(G)
+ *  out        DEVICE out [rows][head_dim] fp32, rows = out_indptr[n_pairs]
+ *  lse        DEVICE out [rows] fp32
+ *
+ * n_items == 0 is a no-op.  FS_EINVAL: NULL pointers, bad shape, G > 16,
+ * tile_tokens out of range, misaligned pools.  FS_EUNSUPPORTED: head_dim != 128,
+ * page_tokens != 16, K/V not bf16.  FS_EHIP: launch failure. */
+FS_API fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* kv,
+                                      const fs_prefill_item* items_dev, const int32_t* sched_dev,
+                                      int64_t n_items, int32_t tile_tokens, float* out, float* lse,
+                                      void* stream);
+
+/* ---------------------------------------------------------------------------
  * fs_stream_read_probe - measurement aid, not a step of the path: read `bytes`
  * bytes once with the access pattern of the attention sweep (16 bytes per lane,
  * contiguous per wavefront) and discard them.  Timing it gives the read rate this
@@ -371,7 +449,8 @@ FS_API fs_status fs_merge_lse(const float* part_o, const float* part_lse, const 
  */
 FS_API fs_status fs_stream_read_probe(const void* buf_dev, int64_t bytes, void* sink_dev, void* stream);
 
-/* Launch-shape knobs for measurement sweeps ("waves_per_group" in {1,2,4}, "prefetch_pages" in [1,3]).
+/* Launch-shape knobs for measurement sweeps ("waves_per_group" in {1,2,4}, "prefetch_pages" in [1,3],
+ * "prefill_col_tiles" in {1,2,4}, "prefill_waves" in {4,8}; the pair (8,4) has no kernel).
  * Unknown key or a value outside the documented range: FS_EINVAL, nothing changes. */
 FS_API fs_status fs_set_option(const char* key, int32_t value);
 FS_API int32_t   fs_get_option(const char* key);   /* -1 for an unknown key */

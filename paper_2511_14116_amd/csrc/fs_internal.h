@@ -18,6 +18,8 @@ constexpr int kMaxGroupFp8 = 8;
 struct Options {
   int waves_per_group;   // wavefronts cooperating on one work item (1, 2 or 4)
   int prefetch_pages;    // KV pages a wavefront keeps in flight ahead of the one it is consuming (1..3)
+  int prefill_col_tiles; // 16-row column tiles of query rows per prefill wavefront (1, 2 or 4)
+  int prefill_waves;     // wavefronts per prefill workgroup (4 or 8)
 };
 Options& options();
 

@@ -17,7 +17,7 @@ fs_status fail(fs_status st, const char* fmt, ...) {
 }
 
 Options& options() {
-  static Options o{4, 2};
+  static Options o{4, 2, 2, 4};
   return o;
 }
 
@@ -41,6 +41,18 @@ extern "C" fs_status fs_set_option(const char* key, int32_t value) {
     fs::options().prefetch_pages = value;
     return FS_OK;
   }
+  if (!strcmp(key, "prefill_col_tiles")) {
+    if (value != 1 && value != 2 && value != 4)
+      return fs::fail(FS_EINVAL, "prefill_col_tiles must be 1, 2 or 4 (got %d)", value);
+    fs::options().prefill_col_tiles = value;
+    return FS_OK;
+  }
+  if (!strcmp(key, "prefill_waves")) {
+    if (value != 4 && value != 8)
+      return fs::fail(FS_EINVAL, "prefill_waves must be 4 or 8 (got %d)", value);
+    fs::options().prefill_waves = value;
+    return FS_OK;
+  }
   return fs::fail(FS_EINVAL, "fs_set_option: unknown key '%s'", key);
 }
 
@@ -48,5 +60,7 @@ extern "C" int32_t fs_get_option(const char* key) {
   if (!key) return -1;
   if (!strcmp(key, "waves_per_group")) return fs::options().waves_per_group;
   if (!strcmp(key, "prefetch_pages")) return fs::options().prefetch_pages;
+  if (!strcmp(key, "prefill_col_tiles")) return fs::options().prefill_col_tiles;
+  if (!strcmp(key, "prefill_waves")) return fs::options().prefill_waves;
   return -1;
 }

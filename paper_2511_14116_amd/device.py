@@ -81,3 +81,20 @@ class DeviceShare:
     def run(self, use_sched: bool = True):
         self.decode(use_sched)
         self.merge()
+
+    # ---- chunked prefill: same Q / pool / page-table plumbing, another list and output shape ----
+    def set_prefill_worklist(self, items: np.ndarray, sched: np.ndarray, out_indptr: np.ndarray, tile_tokens: int):
+        """Upload a prefill tile list and size the output for it."""
+        dev = self.device
+        self.n_prefill_items = len(items)
+        self.prefill_tile_tokens = int(tile_tokens)
+        rows = int(out_indptr[-1])
+        self.prefill_items = torch.from_numpy(np.ascontiguousarray(items).view(np.int32).reshape(-1, 8)).to(dev)
+        self.prefill_sched = torch.from_numpy(np.ascontiguousarray(sched)).to(dev)
+        self.prefill_out = torch.full((rows, self.shape.head_dim), float("nan"), dtype=torch.float32, device=dev)
+        self.prefill_lse = torch.full((rows,), float("nan"), dtype=torch.float32, device=dev)
+
+    def prefill(self, use_sched: bool = True):
+        B.fs_prefill_attention(self.shape, self.view, self.prefill_items, self.prefill_sched if use_sched else None,
+                               self.n_prefill_items, self.prefill_tile_tokens, self.prefill_out, self.prefill_lse,
+                               torch.cuda.current_stream().cuda_stream)

@@ -1,0 +1,172 @@
+"""GPU parity of chunked-prefill attention (through the C ABI) against the CPU oracle.
+
+Bar: tile lists bit-exact; fp32 outputs within 2e-3 abs + 1e-2 rel of the fp64 oracle; LSE
+within 1e-3.  Every input is seeded and synthetic.
+"""
+import math
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_14116_amd as fs
+from paper_2511_14116_amd.device import DeviceShare
+from workloads import make_kv_pool, make_prefill_q, make_prefill_queue
+
+pytestmark = pytest.mark.gpu
+
+ABS_TOL, REL_TOL, LSE_TOL = 2e-3, 1e-2, 1e-3
+SCALE = 1.0 / math.sqrt(128.0)
+DEFAULT_WAVES, DEFAULT_CT = 4, 2
+
+
+def say(msg):
+    print(f"[prefill] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(fs.library_path()):
+        raise RuntimeError("libfailsafe.so is not built: GPU tests never fall back to anything else")
+    fs.load_library()
+    global DEFAULT_WAVES, DEFAULT_CT
+    DEFAULT_WAVES, DEFAULT_CT = fs.fs_get_option("prefill_waves"), fs.fs_get_option("prefill_col_tiles")
+    yield
+    fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
+    fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
+
+
+def check(out, lse, ref_o, ref_l, what):
+    out = np.asarray(out, dtype=np.float64); lse = np.asarray(lse, dtype=np.float64)
+    assert np.isfinite(out).all() and np.isfinite(lse).all(), f"{what}: non-finite output"
+    err = np.abs(out - ref_o)
+    tol = ABS_TOL + REL_TOL * np.abs(ref_o)
+    worst = float((err / tol).max()) if err.size else 0.0
+    lerr = float(np.abs(lse - ref_l).max()) if lse.size else 0.0
+    say(f"{what}: max err/tol {worst:.3f}, max |err| {float(err.max()) if err.size else 0:.2e}, lse err {lerr:.2e}")
+    assert worst <= 1.0, f"{what}: output outside 2e-3 + 1e-2*|ref| (worst ratio {worst})"
+    assert lerr <= LSE_TOL, f"{what}: lse off by {lerr}"
+
+
+def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched=True, interleave=True):
+    n_done = np.asarray(n_done, dtype=np.int32); n_new = np.asarray(n_new, dtype=np.int32)
+    B = len(n_done)
+    G = Hq // Hkv
+    sh = fs.FsShape(B, Hq, Hkv, 128, 16, R)
+    tile = fs.fs_prefill_tile_tokens(G) if tile is None else tile
+    items, pairs, sched, out_indptr = fs.fs_build_prefill_worklist(sh, n_done, n_new, owner, rank, tile)
+    w_items, w_pairs, w_sched, w_indptr = oracle.build_prefill_worklist(n_done, n_new, owner, rank, Hq, tile)
+    assert items.view(np.int32).reshape(-1, 8).tobytes() == w_items.tobytes()
+    assert sched.tobytes() == w_sched.tobytes() and out_indptr.tobytes() == w_indptr.tobytes()
+    ctx = (n_done + n_new).astype(np.int32)
+    kv = make_kv_pool(seed, w_pairs[:, :2], ctx)
+    q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    q = make_prefill_q(seed, int(q_indptr[-1]), Hq, 128)
+    ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave)
+    ds.set_prefill_worklist(items, sched, out_indptr, tile)
+    ds.prefill(use_sched=use_sched)
+    torch.cuda.synchronize()
+    return ds, kv, q, q_indptr, w_pairs, out_indptr
+
+
+def compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what):
+    ref_o, ref_l = oracle.prefill_attention_pairs(q, q_indptr, kv, pairs, Hq, G, SCALE, workers=8)
+    check(ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy(), ref_o, ref_l, what)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (12, 4), (32, 8), (64, 8), (32, 2), (10, 2)])
+def test_group_sizes_ragged_chunks(Hq, Hkv):
+    say(f"group sizes Hq={Hq} Hkv={Hkv}")
+    rng = np.random.default_rng(Hq * 100 + Hkv)
+    n_done = [0, 37, 160, 0, 511, 16]
+    n_new = [45, 1, 70, 0, 33, 129]
+    owner = rng.integers(0, 2, size=(6, Hkv)).astype(np.int32)
+    for rank in range(2):
+        ds, kv, q, q_indptr, pairs, _ = run_share(40 + Hq + Hkv, n_done, n_new, Hq, Hkv, owner, rank, 2)
+        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"Hq={Hq} Hkv={Hkv} rank {rank}")
+
+
+@pytest.mark.parametrize("waves,ct", [(4, 1), (4, 2), (4, 4), (8, 1), (8, 2)])
+def test_launch_shapes(waves, ct):
+    say(f"launch shape waves={waves} ct={ct}")
+    fs.fs_set_option("prefill_waves", waves)
+    fs.fs_set_option("prefill_col_tiles", ct)
+    try:
+        n_done = [0, 100, 1000, 31]
+        n_new = [97, 64, 200, 3]
+        owner = np.zeros((4, 2), dtype=np.int32)
+        ds, kv, q, q_indptr, pairs, _ = run_share(7, n_done, n_new, 16, 2, owner, 0, 1, use_sched=(waves == 4))
+        compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct}")
+        # a tile smaller than the kernel's natural one
+        ds, kv, q, q_indptr, pairs, _ = run_share(8, n_done, n_new, 16, 2, owner, 0, 1, tile=3)
+        compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct} tile=3")
+    finally:
+        fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
+        fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
+
+
+def test_first_token_closed_form_and_one_token_chunks():
+    say("closed forms")
+    owner = np.zeros((3, 1), dtype=np.int32)
+    ds, kv, q, q_indptr, pairs, out_indptr = run_share(9, [0, 0, 300], [1, 20, 1], 4, 1, owner, 0, 1)
+    out = ds.prefill_out.cpu().numpy()
+    for p in (0, 1):        # the first token of a fresh prompt sees only itself: out is its own V row, exactly
+        _, V = oracle.gather_pair_kv(kv, p, 0, 1)
+        for g in range(4):
+            assert np.array_equal(out[int(out_indptr[p]) + g].astype(np.float64), V[0])
+    compare_all(ds, kv, q, q_indptr, pairs, 4, 4, "one-token chunks")
+
+
+def test_chunked_prefill_feeds_from_the_scheduler():
+    """Router -> Algorithm 1 -> head-level hybrid placement -> tile list -> kernel, every rank in turn."""
+    say("scheduler-formed batch, every rank")
+    R, Hq, Hkv, budget = 3, 16, 4, 600
+    queue = make_prefill_queue(5, 10, median=300, sigma=0.8, cap=2000)
+    prompt, n_done = queue["prompt_len"], queue["n_done"]
+    pending = np.zeros(R, dtype=np.int64)
+    entries = np.zeros(len(prompt), dtype=fs.PREFILL_ENTRY_DTYPE)
+    for i in range(len(prompt)):
+        rank = fs.fs_route_request(pending, int(prompt[i] - n_done[i]))
+        entries[i] = (i, rank, int(n_done[i]), int(prompt[i] - n_done[i]))
+    take, load, n_tok = fs.fs_schedule_prefill(R, budget, budget // 2, entries)
+    assert n_tok > 0
+    ctx = np.maximum(n_done + take, 1).astype(np.int32)
+    sh = fs.FsShape(len(prompt), Hq, Hkv, 128, 16, R)
+    owner, dp, _, _ = fs.fs_build_placement_hybrid_heads(sh, ctx, layer=1, route=entries["rank"])
+    rows = 0
+    for rank in range(R):
+        ds, kv, q, q_indptr, pairs, out_indptr = run_share(11, n_done, take, Hq, Hkv, owner, rank, R)
+        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"scheduled batch rank {rank}")
+        rows += int(out_indptr[-1])
+    assert rows == int(take.sum()) * Hq        # every (token, q-head) of the batch is computed exactly once
+
+
+def test_unused_tails_and_spare_slots_are_never_used():
+    say("poisoned tails")
+    # contexts that end mid-page and mid-pair: the poisoned tail of the last page must not leak
+    owner = np.zeros((4, 2), dtype=np.int32)
+    ds, kv, q, q_indptr, pairs, _ = run_share(13, [1, 17, 30, 47], [14, 16, 19, 2], 8, 2, owner, 0, 1)
+    assert np.isfinite(ds.prefill_out.cpu().numpy()).all()
+    compare_all(ds, kv, q, q_indptr, pairs, 8, 4, "tails")
+
+
+def test_empty_share_and_bad_arguments():
+    say("empty share, errors")
+    sh = fs.FsShape(2, 8, 2, 128, 16, 2)
+    owner = np.zeros((2, 2), dtype=np.int32)
+    items, pairs, sched, out_indptr = fs.fs_build_prefill_worklist(sh, [5, 6], [3, 4], owner, 1, 4)
+    assert len(items) == 0
+    dummy = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    kvv = fs.FsKvView(q=dummy.data_ptr(), k_pool=dummy.data_ptr(), v_pool=dummy.data_ptr(), k_slot_stride=4096,
+                      v_slot_stride=4096, k_scale=None, v_scale=None, page_indptr=dummy.data_ptr(),
+                      page_ids=dummy.data_ptr(), kv_dtype=fs.FS_KV_BF16, sm_scale=SCALE)
+    fs.fs_prefill_attention(sh, kvv, None, None, 0, 4, dummy, dummy)          # no-op
+    with pytest.raises(fs.FsError):
+        fs.fs_prefill_attention(sh, kvv, dummy, None, 1, 10 ** 6, dummy, dummy)   # tile beyond the kernel's
+    kvv.kv_dtype = fs.FS_KV_FP8_E4M3
+    with pytest.raises(fs.FsError):
+        fs.fs_prefill_attention(sh, kvv, dummy, None, 1, 4, dummy, dummy)

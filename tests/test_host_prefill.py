@@ -1,0 +1,57 @@
+"""The C++ prefill tile-list builder against the oracle, bit for bit (no GPU needed)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2511_14116_amd as fs
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(fs.library_path()):
+        from paper_2511_14116_amd.build import build
+        build(verbose=False)
+    return fs.load_library()
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_prefill_worklist_matches_oracle(seed):
+    rng = np.random.default_rng(3000 + seed)
+    B, Hkv, G, R = int(rng.integers(0, 12)), int(rng.integers(1, 9)), int(rng.integers(1, 9)), int(rng.integers(1, 8))
+    n_done = rng.integers(0, 5000, size=B).astype(np.int32)
+    n_new = (rng.integers(0, 300, size=B) * (rng.random(B) < 0.7)).astype(np.int32)
+    owner = rng.integers(0, R, size=(B, Hkv)).astype(np.int32)
+    tile = int(rng.integers(1, 70))
+    shape = fs.FsShape(B, Hkv * G, Hkv, 128, 16, R)
+    for k in range(R):
+        w_items, w_pairs, w_sched, w_indptr = oracle.build_prefill_worklist(n_done, n_new, owner, k, Hkv * G, tile)
+        items, pairs, sched, indptr = fs.fs_build_prefill_worklist(shape, n_done, n_new, owner, k, tile)
+        assert items.view(np.int32).reshape(-1, 8).tobytes() == w_items.tobytes()
+        assert pairs.view(np.int32).reshape(-1, 4).tobytes() == w_pairs.tobytes()
+        assert sched.tobytes() == w_sched.tobytes() and indptr.tobytes() == w_indptr.tobytes()
+
+
+def test_field_names_follow_the_oracle():
+    assert fs.PREFILL_ITEM_DTYPE.names == oracle.PREFILL_ITEM_FIELDS
+    assert fs.PREFILL_PAIR_DTYPE.names == oracle.PREFILL_PAIR_FIELDS
+    assert fs.PREFILL_ITEM_DTYPE.itemsize == 32 and fs.PREFILL_PAIR_DTYPE.itemsize == 16
+
+
+def test_tile_tokens_and_errors():
+    assert fs.fs_prefill_tile_tokens(0) == -1 and fs.fs_prefill_tile_tokens(17) == -1
+    ct = fs.fs_get_option("prefill_col_tiles")
+    for G, per_tile in ((1, 16), (2, 8), (3, 4), (4, 4), (5, 2), (8, 2), (16, 1)):
+        assert fs.fs_prefill_tile_tokens(G) == fs.fs_get_option("prefill_waves") * ct * per_tile
+    shape = fs.FsShape(1, 4, 2, 128, 16, 2)
+    with pytest.raises(fs.FsError):
+        fs.fs_build_prefill_worklist(shape, [0], [5], [[0, 1]], 2, 4)        # rank outside
+    with pytest.raises(fs.FsError):
+        fs.fs_build_prefill_worklist(shape, [0], [5], [[0, 1]], 0, 0)        # tile size
+    with pytest.raises(fs.FsError):
+        fs.fs_build_prefill_worklist(shape, [-1], [5], [[0, 1]], 0, 4)
+    with pytest.raises(fs.FsError):
+        fs.fs_build_prefill_worklist(shape, [0], [5], [[0, 7]], 0, 4)
+    items, pairs, sched, indptr = fs.fs_build_prefill_worklist(shape, [9], [0], [[0, 1]], 0, 4)
+    assert len(items) == 0 and len(pairs) == 0 and indptr.tolist() == [0]
