@@ -52,12 +52,20 @@ def main() -> int:
     ap.add_argument("--cold", action="store_true", help="also time the kernels with L2 and the memory-side cache scrubbed before every launch")
     ap.add_argument("--all-ranks", action="store_true", help="also time every rank's share in turn (kernels only) and report the spread")
     ap.add_argument("--force-tail", action="store_true", help="config 3: request 0 gets 131072 tokens")
+    ap.add_argument("--path", choices=["decode", "prefill"], default="decode",
+                    help="decode: the measured decode-attention share (default); prefill: the chunked-prefill attention share")
+    ap.add_argument("--prefill-waves", type=int, default=None)
+    ap.add_argument("--prefill-col-tiles", type=int, default=None)
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (one rank's share at its real shape); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         return 2
+
+    if args.path == "prefill":
+        import bench_prefill
+        return bench_prefill.run(args)
 
     import torch
     import paper_2511_14116_amd as fs

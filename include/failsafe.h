@@ -372,16 +372,18 @@ FS_API fs_status fs_merge_lse(const float* part_o, const float* part_lse, const 
  * of fs_kv_view follows the pair order of the list built here and covers
  * n_done + n_new tokens per pair.
  *
- * One unit of kernel work: query tokens [q_begin, q_end) of one pair's chunk. */
+ * One unit of kernel work: query tokens [q_begin, q_end) of one pair's chunk (a
+ * tile) against the cached tokens [kv_begin, kv_end) (a split-K chunk of the keys
+ * the tile sees).  32 bytes, compared bit for bit against the oracle. */
 typedef struct {
-  int32_t req;          /* request index                                          */
-  int32_t kv_head;      /* KV head index                                          */
   int32_t pair;         /* index of the (request, head) pair in this rank's list  */
   int32_t q_begin;      /* first new token of the tile, within the chunk          */
   int32_t q_end;        /* one past the last                                      */
   int32_t n_done;       /* tokens of the request before the chunk                 */
+  int32_t kv_begin;     /* first cached token of this item, a multiple of 32      */
+  int32_t kv_end;       /* one past the last, <= n_done + q_end                   */
   int32_t q_row;        /* Q row of (token q_begin, first q-head of the group)    */
-  int32_t out_row;      /* output row of (token q_begin, first q-head)            */
+  int32_t part_row;     /* first partial-output row: item_index * T               */
 } fs_prefill_item;
 
 typedef struct {
@@ -389,51 +391,70 @@ typedef struct {
 } fs_prefill_pair;
 
 /* fs_build_prefill_worklist - pairs (r, h) with owner == rank and n_new[r] > 0, in
- * ascending (r, h); pair p is cut into ceil(n_new/tile_tokens) items.  Output rows
- * of pair p are [out_indptr[p], out_indptr[p+1]), token-major and q-head-minor:
- * row(token i, group member g) = out_indptr[p] + i*G + g.  sched lists items by
- * decreasing n_done + q_end (the keys the tile's last token sees), equal ones by
- * increasing index.
+ * ascending (r, h).  Pair p is cut into ceil(n_new/tile_tokens) tiles; a tile ending
+ * at token q_end sees the keys [0, n_done + q_end), cut into chunks of
+ * kv_chunk_tokens keys (0 = one chunk), one item each, consecutive per tile;
+ * chunk_indptr[k] is the first item of tile k (tiles numbered in list order).
+ * With T = tile_tokens*G rows per tile: item i writes partial rows [i*T, (i+1)*T),
+ * tile k owns final rows [k*T, (k+1)*T), both token-major and q-head-minor within
+ * the tile; so pair p's final rows are contiguous from out_indptr[p]:
+ * row(token i, group member g) = out_indptr[p] + i*G + g (rows between the end of a
+ * pair's short last tile and the next pair are padding).  sched lists items by
+ * decreasing kv_end - kv_begin, equal ones by increasing index.
  *
  *  n_done, n_new HOST in [n_req]      each >= 0
  *  owner         HOST in [n_req*n_kv_heads]
- *  tile_tokens   query tokens per item, >= 1 (fs_prefill_tile_tokens(G) is the kernel's size)
- *  items, pairs, sched, out_indptr    HOST out, as for fs_build_worklist (all NULL = count only)
+ *  tile_tokens   query tokens per tile, >= 1 (fs_prefill_tile_tokens(G) is the kernel's size)
+ *  kv_chunk_tokens  0 or a positive multiple of 32
+ *  items, sched  HOST out [items_cap]
+ *  pairs         HOST out [pairs_cap]
+ *  chunk_indptr  HOST out [tiles_cap+1]
+ *  out_indptr    HOST out [pairs_cap+1]
+ *                All five NULL (capacities 0): count only.
+ *  n_items, n_pairs, n_tiles  HOST out, always written when the arguments are valid
  *
- * FS_ECAPACITY / FS_EINVAL as for fs_build_worklist; also FS_EINVAL when the
- * batch has more Q or output rows than int32 holds. */
+ * FS_ECAPACITY: an array is too small (nothing but the counts is valid).
+ * FS_EINVAL: bad shape, rank, tile or chunk size, negative counts, owner outside
+ * [0, R), more Q or partial rows than int32 holds. */
 FS_API fs_status fs_build_prefill_worklist(const fs_shape* shape, const int32_t* n_done, const int32_t* n_new,
                                            const int32_t* owner, int32_t rank, int32_t tile_tokens,
+                                           int32_t kv_chunk_tokens,
                                            fs_prefill_item* items, int64_t items_cap,
                                            fs_prefill_pair* pairs, int64_t pairs_cap,
-                                           int32_t* sched, int64_t* out_indptr,
-                                           int64_t* n_items, int64_t* n_pairs);
+                                           int32_t* sched, int64_t* chunk_indptr, int64_t tiles_cap,
+                                           int64_t* out_indptr,
+                                           int64_t* n_items, int64_t* n_pairs, int64_t* n_tiles);
 
 /* Query tokens one kernel workgroup covers for a group of G q-heads per KV head
- * (the natural tile_tokens; depends on the "prefill_col_tiles" option).  -1 for
- * a group outside [1, 16]. */
+ * (the natural tile_tokens; depends on the "prefill_waves" and "prefill_col_tiles"
+ * options).  -1 for a group outside [1, 16]. */
 FS_API int32_t fs_prefill_tile_tokens(int32_t group);
 
 /* fs_prefill_attention - for every item, every token i in [q_begin, q_end) and g in
- * [0, G), with q = Q row q_row + (i - q_begin)*n_q_heads + g and t over the cached
- * tokens [0, n_done + i]:
+ * [0, G), with q = Q row q_row + (i - q_begin)*n_q_heads + g and t over the item's
+ * cached tokens the query may see, [kv_begin, min(kv_end, n_done + i + 1)):
  *     s_t = sm_scale * <q, K_t>
- *     lse[row] = ln sum_t exp(s_t),   out[row][:] = sum_t exp(s_t - lse) * V_t
- * with row = out_row + (i - q_begin)*G + g.  fp32 scores, softmax and accumulation;
- * the softmax weights enter P.V as a sum of two bf16 terms.
+ *     part_lse[row] = ln sum_t exp(s_t),   part_o[row][:] = sum_t exp(s_t - lse) * V_t
+ * with row = part_row + (i - q_begin)*G + g; a row that sees none of the item's keys
+ * gets part_o = 0 and part_lse = -inf.  Rows of a short last tile beyond its tokens
+ * are written as zeros (part_lse = 0).  fs_merge_lse(part_o, part_lse,
+ * chunk_indptr, n_tiles, T, head_dim, out, lse) then gives the final rows.  fp32
+ * scores, softmax and accumulation; the softmax weights enter P.V as a sum of two
+ * bf16 terms.
  *
  *  items_dev  DEVICE in  [n_items]   as built by fs_build_prefill_worklist
  *  sched_dev  DEVICE in  [n_items]   launch order, or NULL for index order
- *  tile_tokens  the value the list was built with, <= fs_prefill_tile_tokens(G)
- *  out        DEVICE out [rows][head_dim] fp32, rows = out_indptr[n_pairs]
- *  lse        DEVICE out [rows] fp32
+ *  tile_tokens  the value the list was built with, == fs_prefill_tile_tokens(G)
+ *               or smaller
+ *  part_o     DEVICE out [n_items*T][head_dim] fp32, T = tile_tokens*G
+ *  part_lse   DEVICE out [n_items*T] fp32
  *
  * n_items == 0 is a no-op.  FS_EINVAL: NULL pointers, bad shape, G > 16,
  * tile_tokens out of range, misaligned pools.  FS_EUNSUPPORTED: head_dim != 128,
  * page_tokens != 16, K/V not bf16.  FS_EHIP: launch failure. */
 FS_API fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* kv,
                                       const fs_prefill_item* items_dev, const int32_t* sched_dev,
-                                      int64_t n_items, int32_t tile_tokens, float* out, float* lse,
+                                      int64_t n_items, int32_t tile_tokens, float* part_o, float* part_lse,
                                       void* stream);
 
 /* ---------------------------------------------------------------------------

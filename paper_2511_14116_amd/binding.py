@@ -38,7 +38,7 @@ ITEM_DTYPE = np.dtype([(n, np.int32) for n in
 PAIR_DTYPE = np.dtype([(n, np.int32) for n in ("req", "kv_head", "ctx_len", "n_chunks")])
 PREFILL_ENTRY_DTYPE = np.dtype([(n, np.int32) for n in ("req", "rank", "n_done", "n_new")])
 PREFILL_ITEM_DTYPE = np.dtype([(n, np.int32) for n in
-                               ("req", "kv_head", "pair", "q_begin", "q_end", "n_done", "q_row", "out_row")])
+                               ("pair", "q_begin", "q_end", "n_done", "kv_begin", "kv_end", "q_row", "part_row")])
 PREFILL_PAIR_DTYPE = np.dtype([(n, np.int32) for n in ("req", "kv_head", "n_done", "n_new")])
 
 
@@ -75,9 +75,9 @@ def load_library(path: str | None = None):
     lib.fs_replace_failed_gpu.restype = C.c_int
     lib.fs_plan_ffn_reload.argtypes = [C.c_int32, i32p, C.c_int32, u8p, i32p, i32p]
     lib.fs_plan_ffn_reload.restype = C.c_int
-    lib.fs_build_prefill_worklist.argtypes = [C.POINTER(FsShape), i32p, i32p, i32p, C.c_int32, C.c_int32,
+    lib.fs_build_prefill_worklist.argtypes = [C.POINTER(FsShape), i32p, i32p, i32p, C.c_int32, C.c_int32, C.c_int32,
                                               C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
-                                              C.c_void_p, C.c_void_p, i64p, i64p]
+                                              C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, i64p, i64p, i64p]
     lib.fs_build_prefill_worklist.restype = C.c_int
     lib.fs_prefill_tile_tokens.argtypes = [C.c_int32]
     lib.fs_prefill_tile_tokens.restype = C.c_int32
@@ -312,29 +312,35 @@ def fs_prefill_tile_tokens(group: int) -> int:
     return load_library().fs_prefill_tile_tokens(group)
 
 
-def fs_build_prefill_worklist(shape: FsShape, n_done, n_new, owner, rank: int, tile_tokens: int):
-    """-> (items [n] PREFILL_ITEM_DTYPE, pairs [m] PREFILL_PAIR_DTYPE, sched [n] int32, out_indptr [m+1] int64)."""
+def fs_build_prefill_worklist(shape: FsShape, n_done, n_new, owner, rank: int, tile_tokens: int,
+                              kv_chunk_tokens: int = 0):
+    """-> (items [n] PREFILL_ITEM_DTYPE, pairs [m] PREFILL_PAIR_DTYPE, sched [n] int32,
+    chunk_indptr [n_tiles+1] int64, out_indptr [m+1] int64)."""
     lib = load_library()
     nd, nn, own = _host(n_done, np.int32), _host(n_new, np.int32), _host(owner, np.int32)
     if len(nd) != shape.n_req or len(nn) != shape.n_req or own.size != shape.n_req * shape.n_kv_heads:
         raise ValueError("n_done, n_new and owner must match the shape")
     i32p = C.POINTER(C.c_int32)
-    n_items, n_pairs = C.c_int64(0), C.c_int64(0)
-    args = (C.byref(shape), nd.ctypes.data_as(i32p), nn.ctypes.data_as(i32p), own.ctypes.data_as(i32p), rank, tile_tokens)
-    _check(lib.fs_build_prefill_worklist(*args, None, 0, None, 0, None, None, C.byref(n_items), C.byref(n_pairs)))
+    n_items, n_pairs, n_tiles = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    args = (C.byref(shape), nd.ctypes.data_as(i32p), nn.ctypes.data_as(i32p), own.ctypes.data_as(i32p), rank,
+            tile_tokens, kv_chunk_tokens)
+    counts = (C.byref(n_items), C.byref(n_pairs), C.byref(n_tiles))
+    _check(lib.fs_build_prefill_worklist(*args, None, 0, None, 0, None, None, 0, None, *counts))
     items = np.empty(n_items.value, dtype=PREFILL_ITEM_DTYPE)
     pairs = np.empty(n_pairs.value, dtype=PREFILL_PAIR_DTYPE)
     sched = np.empty(n_items.value, dtype=np.int32)
-    indptr = np.empty(n_pairs.value + 1, dtype=np.int64)
+    chunk_indptr = np.empty(n_tiles.value + 1, dtype=np.int64)
+    out_indptr = np.empty(n_pairs.value + 1, dtype=np.int64)
     _check(lib.fs_build_prefill_worklist(*args, items.ctypes.data, len(items), pairs.ctypes.data, len(pairs),
-                                         sched.ctypes.data, indptr.ctypes.data, C.byref(n_items), C.byref(n_pairs)))
-    return items, pairs, sched, indptr
+                                         sched.ctypes.data, chunk_indptr.ctypes.data, n_tiles.value,
+                                         out_indptr.ctypes.data, *counts))
+    return items, pairs, sched, chunk_indptr, out_indptr
 
 
 def fs_prefill_attention(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int, tile_tokens: int,
-                         out, lse, stream=None) -> None:
+                         part_o, part_lse, stream=None) -> None:
     st = load_library().fs_prefill_attention(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
-                                             n_items, tile_tokens, _ptr(out), _ptr(lse), _ptr(stream))
+                                             n_items, tile_tokens, _ptr(part_o), _ptr(part_lse), _ptr(stream))
     _check(st)
 
 

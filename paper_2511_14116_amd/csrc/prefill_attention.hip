@@ -3,21 +3,27 @@
 // The paper's fine-grained chunked prefill (Section 3.1) puts chunks of several requests into
 // one batch: N new tokens of a request behind L processed ones.  Every new token attends to the
 // cache up to and including itself (prefill phase, Section 2.1.1).  The paper describes no
-// kernel; this one is built on the decode kernel's slot layout, which already puts K and V
-// pages into matrix-core operand order.
+// kernel; this one is built on the decode kernel's slot layout, which already stores K and V
+// pages in matrix-core operand order.
 //
-// One workgroup per tile of query tokens of one (request, KV head) pair.  A query row is a
-// (token, q-head of the group) combination; 16 rows form a column tile of the transposed score
-// matrix, and every wavefront owns CT column tiles.  Per pair of KV pages (32 tokens) a
-// wavefront loads K and V once (16-byte loads straight into operand registers) and reuses them
-// for all its column tiles:
-//     S^T[tok][row] = K . Q^T        2 x 4 v_mfma_f32_16x16x32_bf16 per column tile
-//     online softmax in fp32, log2 domain, causal mask only on the pages that straddle a row's position
-//     O^T[d][row]  += V^T . P^T      8 x v_mfma_f32_16x16x32_bf16 over the 32 tokens, P as bf16 hi + lo
+// One workgroup per item: a tile of query tokens of one (request, KV head) pair against one
+// split-K chunk of the keys the tile sees.  A query row is a (token, q-head of the group)
+// combination; 16 rows form a column tile of the transposed score matrix and every wavefront
+// owns CT column tiles.  The workgroup walks the chunk in pairs of KV pages (32 tokens):
+//   * every wavefront fetches its share of the next pairs from global memory into registers (two
+//     pairs in flight) and copies it into a double-buffered LDS stage, so the whole workgroup
+//     reads each page from L2/HBM once;
+//   * from LDS every wavefront takes the K operands (16-byte reads, conflict-free), and for each
+//     of its column tiles
+//         S^T[tok][row] = K . Q^T        2 x 4 v_mfma_f32_16x16x32_bf16
+//     then the V operands and, per column tile, the online softmax (fp32, log2 domain, causal
+//     mask only on the pairs that straddle a row's position) and
+//         O^T[d][row]  += V^T . P^T      8 x v_mfma_f32_16x16x32_bf16 over the 32 tokens, P as bf16 hi + lo.
 // The S^T accumulators of the two pages are, lane by lane, the 8 reduction elements the second
-// product wants from P^T, and the V registers of the two pages pair up the same way, so nothing
-// crosses lanes except the running max.  This is a dense contraction (G*N rows against L+N
-// keys): the matrix cores bound it, not HBM.
+// product wants from P^T (4 tokens of the first page, the same 4 of the second); the copy into
+// LDS pairs the V rows of the two pages the same way, so nothing crosses lanes except the
+// running max.  This is a dense contraction (G*N rows against L+N keys): the matrix cores bound
+// it, not HBM.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -40,15 +46,19 @@ struct PrefillParams {
   const int32_t* __restrict__ page_ids;
   const fs_prefill_item* __restrict__ items;
   const int32_t* __restrict__ sched;
-  float* __restrict__ out;
-  float* __restrict__ lse;
+  float* __restrict__ part_o;
+  float* __restrict__ part_lse;
   int32_t group;        // G
   int32_t group_pad;    // G rounded up to a power of two (divides 16)
   int32_t n_q_heads;
+  int32_t tile_tokens;  // query tokens per tile as the list was built (rows per item = tile_tokens * G)
   float scale_log2;
 };
 
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kStageBytes = 16384;     // one pair of pages: K0, K1 (4 KiB each), then the paired V halves (2 x 4 KiB)
+constexpr int kVaOffset = 8192;        // V rows d = 32c + lane%16:      (page 0 tokens 4kb..+3 | page 1 tokens 4kb..+3)
+constexpr int kVbOffset = 12288;       // V rows d = 32c + 16 + lane%16: likewise
 
 __device__ __forceinline__ float xor16(float v, bool take_max) {
   const unsigned u = __builtin_bit_cast(unsigned, v);
@@ -63,56 +73,13 @@ __device__ __forceinline__ float xor32(float v, bool take_max) {
   return take_max ? fmaxf(__uint_as_float(a), __uint_as_float(b)) : __uint_as_float(a) + __uint_as_float(b);
 }
 
-// Two KV pages (32 tokens) in operand registers.  The second product reduces over the 32 tokens of
-// the pair, and a lane's 8 reduction elements are 4 tokens of the first page followed by the same 4
-// of the second, so each V operand is filled by one 8-byte load from either page.
-struct PagePair {
-  u32x4 k[2][4];   // [page][32-d block]: A operand of K.Q^T
-  u32x4 va[4];     // [32-d block], d = 32c + lane%16:      (page 0 tokens 4kb..4kb+3, page 1 tokens 4kb..4kb+3)
-  u32x4 vb[4];     // [32-d block], d = 32c + 16 + lane%16: likewise
+// A wavefront's share of one page pair on its way from global memory to LDS: NP (K block, V block)
+// couples of 1 KiB, each couple from one page h and one 32-d block c.
+template <int NP>
+struct InFlight {
+  u32x4 k[NP];
+  u32x4 v[NP];
 };
-
-__device__ __forceinline__ void load_pair(PagePair& r, const PrefillParams& P, const int32_t* __restrict__ ids,
-                                          int page0, int n_pages, int lane) {
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    if (page0 + h < n_pages) {
-      const int64_t slot = ids[page0 + h];
-      const u32x4* kp = reinterpret_cast<const u32x4*>(P.k_pool + slot * P.k_stride) + lane;
-      const uint2* vp = reinterpret_cast<const uint2*>(P.v_pool + slot * P.v_stride) + 2 * lane;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) r.k[h][s] = kp[s * 64];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint2 a = vp[s * 128], b = vp[s * 128 + 1];
-        if (h == 0) { r.va[s].x = a.x; r.va[s].y = a.y; r.vb[s].x = b.x; r.vb[s].y = b.y; }
-        else        { r.va[s].z = a.x; r.va[s].w = a.y; r.vb[s].z = b.x; r.vb[s].w = b.y; }
-      }
-    } else {   // no such page: its keys are masked, its values must be finite
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        r.k[h][s] = u32x4{0u, 0u, 0u, 0u};
-        if (h == 0) { r.va[s].x = 0u; r.va[s].y = 0u; r.vb[s].x = 0u; r.vb[s].y = 0u; }
-        else        { r.va[s].z = 0u; r.va[s].w = 0u; r.vb[s].z = 0u; r.vb[s].w = 0u; }
-      }
-    }
-  }
-}
-
-// Blank the value rows of tokens at or beyond valid0 (page 0) / valid1 (page 1), each 0..16: whatever
-// bits sit in the unused tail of a last page (NaN included) must not reach the product, where
-// 0 * NaN is NaN.
-__device__ __forceinline__ void blank_values(PagePair& r, int valid0, int valid1, int kb) {
-  const uint32_t a0 = (4 * kb + 0 < valid0 ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid0 ? 0xFFFF0000u : 0u);
-  const uint32_t a1 = (4 * kb + 2 < valid0 ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid0 ? 0xFFFF0000u : 0u);
-  const uint32_t b0 = (4 * kb + 0 < valid1 ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid1 ? 0xFFFF0000u : 0u);
-  const uint32_t b1 = (4 * kb + 2 < valid1 ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid1 ? 0xFFFF0000u : 0u);
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    r.va[c].x &= a0; r.va[c].y &= a1; r.va[c].z &= b0; r.va[c].w &= b1;
-    r.vb[c].x &= a0; r.vb[c].y &= a1; r.vb[c].z &= b0; r.vb[c].w &= b1;
-  }
-}
 
 struct TileState {
   float m;          // running max (log2 domain) of this lane's query row
@@ -120,67 +87,12 @@ struct TileState {
   f32x4 acc[8];     // O^T[d = 16b + 4*(lane/16) + r][row = lane%16]
 };
 
-// One column tile against one page pair.  `pos` is the last key this lane's row may see; `t0` the
-// first token of the pair.
-template <bool MASK>
-__device__ __forceinline__ void consume_pair(TileState& st, const PagePair& pg, const bf16x8 (&qreg)[4],
-                                             float scale_log2, int t0, int pos, int kb) {
-  f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pg.k[0][c]), qreg[c], sa, 0, 0, 0);
-    sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pg.k[1][c]), qreg[c], sb, 0, 0, 0);
-  }
-  float x[8];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    x[r] = sa[r] * scale_log2;
-    x[4 + r] = sb[r] * scale_log2;
-  }
-  if (MASK) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      if (t0 + 4 * kb + r > pos) x[r] = -INFINITY;
-      if (t0 + 16 + 4 * kb + r > pos) x[4 + r] = -INFINITY;
-    }
-  }
-  float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-  mx = xor32(xor16(mx, true), true);
-  const float m_new = fmaxf(st.m, mx);     // finite from the first pair on: token 0 is visible to every row
-  if (__any(m_new > st.m)) {
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // first pair: exp2(-inf) = 0
-    st.l *= alpha;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
-    st.m = m_new;
-  }
-  float p[8];
-  float ps = 0.f;
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    p[r] = __builtin_amdgcn_exp2f(x[r] - st.m);
-    ps += p[r];
-  }
-  st.l += ps;
-  // weights as bf16 hi + lo (16 significant bits), as in the decode kernel
-  bf16x8 ph, pl;
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    ph[r] = static_cast<__bf16>(p[r]);
-    pl[r] = static_cast<__bf16>(p[r] - static_cast<float>(ph[r]));
-  }
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const bf16x8 va = __builtin_bit_cast(bf16x8, pg.va[c]), vb = __builtin_bit_cast(bf16x8, pg.vb[c]);
-    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph, st.acc[2 * c], 0, 0, 0);
-    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, ph, st.acc[2 * c + 1], 0, 0, 0);
-    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl, st.acc[2 * c], 0, 0, 0);
-    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pl, st.acc[2 * c + 1], 0, 0, 0);
-  }
-}
-
 template <int WAVES, int CT>
 __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillParams P) {
+  constexpr int NP = 8 / WAVES;        // (K, V) block couples a wavefront moves per page pair
+  static_assert(NP >= 1, "at most 8 wavefronts");
+  __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
+
   const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
   const fs_prefill_item it = P.items[item_idx];
   const int lane = threadIdx.x & 63;
@@ -190,9 +102,13 @@ __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillP
   const int tpc = 16 / Gp;                       // query tokens per column tile
   const int n_tok = it.q_end - it.q_begin;       // query tokens of this item
   const int tok0 = wave * CT * tpc;              // first token (within the item) of this wavefront
-  if (tok0 >= n_tok) return;                     // nothing for this wavefront (short last tile); no barriers below
-  const int ctx = it.n_done + it.q_end;          // keys that exist as far as this item is concerned
+  const bool wave_live = tok0 < n_tok;           // a short last tile leaves some wavefronts without rows
   const int L0 = it.n_done + it.q_begin;         // position of the item's first token
+  const int last_key = it.n_done + it.q_end - 1; // last key any row of the tile may see
+  const int n_it = (it.kv_end - it.kv_begin + 31) / 32;       // page pairs of this item
+  const int page_begin = it.kv_begin / fs::kPageTokens;
+  const int page_end = (it.kv_end + fs::kPageTokens - 1) / fs::kPageTokens;
+  const int32_t* __restrict__ ids = P.page_ids + P.page_indptr[it.pair];
 
   // this lane's row of each column tile
   const int g = col % Gp, tl = col / Gp;
@@ -203,7 +119,7 @@ __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillP
   for (int t = 0; t < CT; ++t) {
     const int tok = tok0 + t * tpc + tl;                  // within the item
     live[t] = tok < n_tok && g < G;
-    pos[t] = min(L0 + tok, ctx - 1);                      // rows that do not exist look at valid keys only
+    pos[t] = min(L0 + tok, last_key);                     // rows that do not exist look at existing keys only
     const int64_t qrow = static_cast<int64_t>(it.q_row) + static_cast<int64_t>(min(tok, n_tok - 1)) * P.n_q_heads + min(g, G - 1);
     const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + qrow * fs::kHeadDim) + kb;
 #pragma unroll
@@ -222,49 +138,179 @@ __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillP
     for (int j = 0; j < 8; ++j) st[t].acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  const int tok_last = min(n_tok, tok0 + CT * tpc) - 1;   // last token of this wavefront
-  const int pos_last = L0 + tok_last;
-  const int n_pages = pos_last / fs::kPageTokens + 1;     // pages this wavefront needs
-  const int n_pairs = (n_pages + 1) / 2;
-  const int32_t* __restrict__ ids = P.page_ids + P.page_indptr[it.pair];
-
-  PagePair buf[2];
-  load_pair(buf[0], P, ids, 0, n_pages, lane);
-  for (int j = 0; j < n_pairs; j += 2) {
+  // ---- global -> registers: this wavefront's couples of pair jp ---------------------------------
+  auto fetch = [&](InFlight<NP>& r, int jp) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int jj = j + u;
-      if (jj < n_pairs) {
-        if (jj + 1 < n_pairs) load_pair(buf[u ^ 1], P, ids, 2 * (jj + 1), n_pages, lane);
-        PagePair& pg = buf[u];
-        const int t0 = 32 * jj;
-        if (t0 + 32 > ctx) {          // the cache ends inside this pair: blank what lies beyond it
-          blank_values(pg, min(16, max(0, ctx - t0)), min(16, max(0, ctx - t0 - 16)), kb);
-        }
+    for (int i = 0; i < NP; ++i) {
+      const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
+      const int page = page_begin + 2 * jp + h;
+      if (page < page_end) {
+        const int64_t slot = ids[page];
+        r.k[i] = reinterpret_cast<const u32x4*>(P.k_pool + slot * P.k_stride)[c * 64 + lane];
+        r.v[i] = reinterpret_cast<const u32x4*>(P.v_pool + slot * P.v_stride)[c * 64 + lane];
+      } else {   // the item ends with the first page of the pair
+        r.k[i] = u32x4{0u, 0u, 0u, 0u};
+        r.v[i] = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  };
+  // ---- registers -> LDS stage s ------------------------------------------------------------------
+  auto deposit = [&](int s, const InFlight<NP>& r, int jp) {
 #pragma unroll
-        for (int t = 0; t < CT; ++t) {
-          const int first_pos = L0 + tok0 + t * tpc;                       // smallest position in the column tile
-          const int last_pos = min(L0 + tok0 + t * tpc + tpc - 1, ctx - 1);  // largest
-          if (tok0 + t * tpc < n_tok && t0 <= last_pos) {
-            if (t0 + 31 <= first_pos) consume_pair<false>(st[t], pg, qreg[t], P.scale_log2, t0, pos[t], kb);
-            else consume_pair<true>(st[t], pg, qreg[t], P.scale_log2, t0, pos[t], kb);
+    for (int i = 0; i < NP; ++i) {
+      const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
+      // value rows of tokens at or beyond the item's end may hold anything (the unused tail of a last
+      // page is never initialised): blank them, 0 * NaN would be NaN in the product
+      const int valid = it.kv_end - (page_begin + 2 * jp + h) * fs::kPageTokens;    // tokens of this page inside the item
+      const uint32_t m0 = (4 * kb + 0 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid ? 0xFFFF0000u : 0u);
+      const uint32_t m1 = (4 * kb + 2 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid ? 0xFFFF0000u : 0u);
+      unsigned char* base = stage[s];
+      *reinterpret_cast<u32x4*>(base + ((h * 4 + c) * 64 + lane) * 16) = r.k[i];
+      *reinterpret_cast<uint2*>(base + kVaOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(r.v[i].x & m0, r.v[i].y & m1);
+      *reinterpret_cast<uint2*>(base + kVbOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(r.v[i].z & m0, r.v[i].w & m1);
+    }
+  };
+  // ---- one page pair from LDS stage s against this wavefront's column tiles -----------------------
+  auto compute = [&](int s, int jp) {
+    if (!wave_live) return;
+    const int t0 = it.kv_begin + 32 * jp;                 // first token of the pair
+    bool need[CT], full[CT];
+    bool any = false;
+#pragma unroll
+    for (int t = 0; t < CT; ++t) {
+      const int first_pos = L0 + tok0 + t * tpc;                              // smallest position in the column tile
+      const int last_pos = min(L0 + tok0 + t * tpc + tpc - 1, last_key);      // largest
+      need[t] = tok0 + t * tpc < n_tok && t0 <= last_pos;
+      full[t] = t0 + 31 <= first_pos;                                         // every row sees all 32 tokens
+      any |= need[t];
+    }
+    if (!any) return;
+    const unsigned char* base = stage[s];
+    f32x4 sa[CT], sb[CT];
+    {
+      u32x4 k0[4], k1[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        k0[c] = *reinterpret_cast<const u32x4*>(base + (c * 64 + lane) * 16);
+        k1[c] = *reinterpret_cast<const u32x4*>(base + ((4 + c) * 64 + lane) * 16);
+      }
+#pragma unroll
+      for (int t = 0; t < CT; ++t) {
+        sa[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        sb[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (need[t]) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            sa[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k0[c]), qreg[t][c], sa[t], 0, 0, 0);
+            sb[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k1[c]), qreg[t][c], sb[t], 0, 0, 0);
           }
         }
       }
     }
+    u32x4 va[4], vb[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      va[c] = *reinterpret_cast<const u32x4*>(base + kVaOffset + (c * 64 + lane) * 16);
+      vb[c] = *reinterpret_cast<const u32x4*>(base + kVbOffset + (c * 64 + lane) * 16);
+    }
+#pragma unroll
+    for (int t = 0; t < CT; ++t) {
+      if (!need[t]) continue;
+      float x[8];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        x[r] = sa[t][r] * P.scale_log2;
+        x[4 + r] = sb[t][r] * P.scale_log2;
+      }
+      if (!full[t]) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (t0 + 4 * kb + r > pos[t]) x[r] = -INFINITY;
+          if (t0 + 16 + 4 * kb + r > pos[t]) x[4 + r] = -INFINITY;
+        }
+      }
+      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      mx = xor32(xor16(mx, true), true);
+      const float m_new = fmaxf(st[t].m, mx);
+      // a row may see none of the item's keys so far (its position lies before the chunk): keep its state at zero
+      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+      if (__any(m_new > st[t].m)) {
+        const float alpha = __builtin_amdgcn_exp2f(st[t].m - m_ref);   // first keys of a row: exp2(-inf) = 0
+        st[t].l *= alpha;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st[t].acc[j] *= alpha;
+        st[t].m = m_new;
+      }
+      float p[8];
+      float ps = 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        p[r] = __builtin_amdgcn_exp2f(x[r] - m_ref);
+        ps += p[r];
+      }
+      st[t].l += ps;
+      // weights as bf16 hi + lo (16 significant bits), as in the decode kernel
+      bf16x8 ph, pl;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        ph[r] = static_cast<__bf16>(p[r]);
+        pl[r] = static_cast<__bf16>(p[r] - static_cast<float>(ph[r]));
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, va[c]), b = __builtin_bit_cast(bf16x8, vb[c]);
+        st[t].acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph, st[t].acc[2 * c], 0, 0, 0);
+        st[t].acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, ph, st[t].acc[2 * c + 1], 0, 0, 0);
+        st[t].acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, st[t].acc[2 * c], 0, 0, 0);
+        st[t].acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, pl, st[t].acc[2 * c + 1], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- the walk: pair j is computed from stage j%2 while pair j+1 is copied into the other stage and
+  // pairs j+2, j+3 are on their way from global memory.  One barrier per pair: after it, stage (j+1)%2 is
+  // complete and nobody reads stage j%2 any more.  Every wavefront takes every branch below (n_it is the
+  // workgroup's), so the barriers match.
+  InFlight<NP> r0, r1;
+  fetch(r0, 0);
+  if (n_it > 1) fetch(r1, 1);
+  deposit(0, r0, 0);
+  if (n_it > 2) fetch(r0, 2);
+  __syncthreads();
+  for (int j = 0; j < n_it; j += 2) {
+    if (j + 1 < n_it) {
+      deposit(1, r1, j + 1);
+      if (j + 3 < n_it) fetch(r1, j + 3);
+    }
+    compute(0, j);
+    __syncthreads();
+    if (j + 1 < n_it) {
+      if (j + 2 < n_it) {
+        deposit(0, r0, j + 2);
+        if (j + 4 < n_it) fetch(r0, j + 4);
+      }
+      compute(1, j + 1);
+      __syncthreads();
+    }
   }
 
+  // ---- write the item's partial rows --------------------------------------------------------------
 #pragma unroll
   for (int t = 0; t < CT; ++t) {
+    const int tok = tok0 + t * tpc + tl;
     const float l_tot = xor32(xor16(st[t].l, false), false);
-    if (live[t]) {
-      const int tok = tok0 + t * tpc + tl;
-      const int64_t row = static_cast<int64_t>(it.out_row) + static_cast<int64_t>(tok) * G + g;
-      const float inv = 1.0f / l_tot;
-      float* o = P.out + row * fs::kHeadDim + 4 * kb;
+    if (g >= G || tok >= P.tile_tokens) continue;          // no such row in the partial buffer
+    const int64_t row = static_cast<int64_t>(it.part_row) + static_cast<int64_t>(tok) * G + g;
+    float* o = P.part_o + row * fs::kHeadDim + 4 * kb;
+    if (tok < n_tok) {
+      const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;  // a row that saw none of the item's keys: out = 0, lse = -inf
 #pragma unroll
       for (int b = 0; b < 8; ++b) *reinterpret_cast<f32x4*>(o + 16 * b) = st[t].acc[b] * inv;
-      if (kb == 0) P.lse[row] = (st[t].m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+      if (kb == 0) P.part_lse[row] = l_tot > 0.f ? (st[t].m + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+    } else {                                               // padding row of a short last tile
+#pragma unroll
+      for (int b = 0; b < 8; ++b) *reinterpret_cast<f32x4*>(o + 16 * b) = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (kb == 0) P.part_lse[row] = 0.f;
     }
   }
 }
@@ -292,7 +338,7 @@ extern "C" int32_t fs_prefill_tile_tokens(int32_t group) {
 
 extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* kv,
                                           const fs_prefill_item* items_dev, const int32_t* sched_dev,
-                                          int64_t n_items, int32_t tile_tokens, float* out, float* lse,
+                                          int64_t n_items, int32_t tile_tokens, float* part_o, float* part_lse,
                                           void* stream) {
   if (!shape || !kv) return fs::fail(FS_EINVAL, "fs_prefill_attention: shape or kv is NULL");
   if (shape->n_kv_heads < 1 || shape->n_q_heads < shape->n_kv_heads || shape->n_q_heads % shape->n_kv_heads)
@@ -313,14 +359,14 @@ extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_vie
   if (tile_tokens < 1 || tile_tokens > cap)
     return fs::fail(FS_EINVAL, "fs_prefill_attention: tile_tokens %d outside [1, %d] for group %d", tile_tokens, cap, G);
   if (n_items == 0) return FS_OK;
-  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev || !out || !lse)
+  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev || !part_o || !part_lse)
     return fs::fail(FS_EINVAL, "fs_prefill_attention: NULL device pointer");
   const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * 2;
   if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
       (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
       (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
-      (reinterpret_cast<uintptr_t>(out) & 15))
-    return fs::fail(FS_EINVAL, "fs_prefill_attention: pools, strides, q and out must be 16-byte aligned and strides "
+      (reinterpret_cast<uintptr_t>(part_o) & 15))
+    return fs::fail(FS_EINVAL, "fs_prefill_attention: pools, strides, q and part_o must be 16-byte aligned and strides "
                                "at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
   if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "fs_prefill_attention: sm_scale is not finite");
 
@@ -334,11 +380,12 @@ extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_vie
   P.page_ids = kv->page_ids;
   P.items = items_dev;
   P.sched = sched_dev;
-  P.out = out;
-  P.lse = lse;
+  P.part_o = part_o;
+  P.part_lse = part_lse;
   P.group = G;
   P.group_pad = pad_group(G);
   P.n_q_heads = shape->n_q_heads;
+  P.tile_tokens = tile_tokens;
   P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (waves * 10 + ct) {

@@ -83,18 +83,27 @@ class DeviceShare:
         self.merge()
 
     # ---- chunked prefill: same Q / pool / page-table plumbing, another list and output shape ----
-    def set_prefill_worklist(self, items: np.ndarray, sched: np.ndarray, out_indptr: np.ndarray, tile_tokens: int):
-        """Upload a prefill tile list and size the output for it."""
+    def set_prefill_worklist(self, items: np.ndarray, sched: np.ndarray, chunk_indptr: np.ndarray, tile_tokens: int):
+        """Upload a prefill item list and size the partial and final outputs for it."""
         dev = self.device
         self.n_prefill_items = len(items)
+        self.n_prefill_tiles = len(chunk_indptr) - 1
         self.prefill_tile_tokens = int(tile_tokens)
-        rows = int(out_indptr[-1])
+        T = self.prefill_tile_rows = int(tile_tokens) * self.group
+        D = self.shape.head_dim
         self.prefill_items = torch.from_numpy(np.ascontiguousarray(items).view(np.int32).reshape(-1, 8)).to(dev)
         self.prefill_sched = torch.from_numpy(np.ascontiguousarray(sched)).to(dev)
-        self.prefill_out = torch.full((rows, self.shape.head_dim), float("nan"), dtype=torch.float32, device=dev)
-        self.prefill_lse = torch.full((rows,), float("nan"), dtype=torch.float32, device=dev)
+        self.prefill_chunk_indptr = torch.from_numpy(np.ascontiguousarray(chunk_indptr)).to(dev)
+        self.prefill_part_o = torch.full((self.n_prefill_items * T, D), float("nan"), dtype=torch.float32, device=dev)
+        self.prefill_part_lse = torch.full((self.n_prefill_items * T,), float("nan"), dtype=torch.float32, device=dev)
+        self.prefill_out = torch.full((self.n_prefill_tiles * T, D), float("nan"), dtype=torch.float32, device=dev)
+        self.prefill_lse = torch.full((self.n_prefill_tiles * T,), float("nan"), dtype=torch.float32, device=dev)
 
     def prefill(self, use_sched: bool = True):
+        """Per-item partials, then the split-K merge (the same fs_merge_lse the decode path uses)."""
+        s = torch.cuda.current_stream().cuda_stream
         B.fs_prefill_attention(self.shape, self.view, self.prefill_items, self.prefill_sched if use_sched else None,
-                               self.n_prefill_items, self.prefill_tile_tokens, self.prefill_out, self.prefill_lse,
-                               torch.cuda.current_stream().cuda_stream)
+                               self.n_prefill_items, self.prefill_tile_tokens, self.prefill_part_o,
+                               self.prefill_part_lse, s)
+        B.fs_merge_lse(self.prefill_part_o, self.prefill_part_lse, self.prefill_chunk_indptr, self.n_prefill_tiles,
+                       self.prefill_tile_rows, self.shape.head_dim, self.prefill_out, self.prefill_lse, s)

@@ -52,30 +52,39 @@ def check(out, lse, ref_o, ref_l, what):
     assert lerr <= LSE_TOL, f"{what}: lse off by {lerr}"
 
 
-def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched=True, interleave=True):
+def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched=True, interleave=True, chunk=0):
     n_done = np.asarray(n_done, dtype=np.int32); n_new = np.asarray(n_new, dtype=np.int32)
     B = len(n_done)
     G = Hq // Hkv
     sh = fs.FsShape(B, Hq, Hkv, 128, 16, R)
     tile = fs.fs_prefill_tile_tokens(G) if tile is None else tile
-    items, pairs, sched, out_indptr = fs.fs_build_prefill_worklist(sh, n_done, n_new, owner, rank, tile)
-    w_items, w_pairs, w_sched, w_indptr = oracle.build_prefill_worklist(n_done, n_new, owner, rank, Hq, tile)
+    items, pairs, sched, chunk_indptr, out_indptr = fs.fs_build_prefill_worklist(sh, n_done, n_new, owner, rank, tile, chunk)
+    w_items, w_pairs, w_sched, w_chunks, w_indptr = oracle.build_prefill_worklist(n_done, n_new, owner, rank, Hq, tile, chunk)
     assert items.view(np.int32).reshape(-1, 8).tobytes() == w_items.tobytes()
     assert sched.tobytes() == w_sched.tobytes() and out_indptr.tobytes() == w_indptr.tobytes()
+    assert chunk_indptr.tobytes() == w_chunks.tobytes()
     ctx = (n_done + n_new).astype(np.int32)
     kv = make_kv_pool(seed, w_pairs[:, :2], ctx)
     q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
     q = make_prefill_q(seed, int(q_indptr[-1]), Hq, 128)
     ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave)
-    ds.set_prefill_worklist(items, sched, out_indptr, tile)
+    ds.set_prefill_worklist(items, sched, chunk_indptr, tile)
     ds.prefill(use_sched=use_sched)
     torch.cuda.synchronize()
+    ds.w_items, ds.tile = w_items, tile
     return ds, kv, q, q_indptr, w_pairs, out_indptr
 
 
-def compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what):
-    ref_o, ref_l = oracle.prefill_attention_pairs(q, q_indptr, kv, pairs, Hq, G, SCALE, workers=8)
-    check(ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy(), ref_o, ref_l, what)
+def compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, out_indptr=None):
+    """Final rows (after the split-K merge) against the unsplit oracle; padding rows must be finite."""
+    if out_indptr is None:
+        _, _, _, _, out_indptr = oracle.build_prefill_worklist(*ds.list_args)
+    ref_o, ref_l = oracle.prefill_attention_pairs(q, q_indptr, kv, pairs, Hq, G, SCALE, workers=8, out_indptr=out_indptr)
+    out, lse = ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy()
+    assert np.isfinite(out).all() and np.isfinite(lse).all(), f"{what}: non-finite output (padding rows included)"
+    valid = np.isfinite(ref_l)
+    assert valid.sum() == int(pairs[:, 3].sum()) * G if len(pairs) else valid.sum() == 0
+    check(out[valid], lse[valid], ref_o[valid], ref_l[valid], what)
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (12, 4), (32, 8), (64, 8), (32, 2), (10, 2)])
@@ -86,8 +95,9 @@ def test_group_sizes_ragged_chunks(Hq, Hkv):
     n_new = [45, 1, 70, 0, 33, 129]
     owner = rng.integers(0, 2, size=(6, Hkv)).astype(np.int32)
     for rank in range(2):
-        ds, kv, q, q_indptr, pairs, _ = run_share(40 + Hq + Hkv, n_done, n_new, Hq, Hkv, owner, rank, 2)
-        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"Hq={Hq} Hkv={Hkv} rank {rank}")
+        ds, kv, q, q_indptr, pairs, oi = run_share(40 + Hq + Hkv, n_done, n_new, Hq, Hkv, owner, rank, 2,
+                                                   chunk=(0, 64)[rank])
+        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"Hq={Hq} Hkv={Hkv} rank {rank}", oi)
 
 
 @pytest.mark.parametrize("waves,ct", [(4, 1), (4, 2), (4, 4), (8, 1), (8, 2)])
@@ -99,11 +109,12 @@ def test_launch_shapes(waves, ct):
         n_done = [0, 100, 1000, 31]
         n_new = [97, 64, 200, 3]
         owner = np.zeros((4, 2), dtype=np.int32)
-        ds, kv, q, q_indptr, pairs, _ = run_share(7, n_done, n_new, 16, 2, owner, 0, 1, use_sched=(waves == 4))
-        compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct}")
+        for chunk in (0, 32, 256):
+            ds, kv, q, q_indptr, pairs, oi = run_share(7, n_done, n_new, 16, 2, owner, 0, 1, use_sched=(waves == 4), chunk=chunk)
+            compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct} chunk={chunk}", oi)
         # a tile smaller than the kernel's natural one
-        ds, kv, q, q_indptr, pairs, _ = run_share(8, n_done, n_new, 16, 2, owner, 0, 1, tile=3)
-        compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct} tile=3")
+        ds, kv, q, q_indptr, pairs, oi = run_share(8, n_done, n_new, 16, 2, owner, 0, 1, tile=3, chunk=96)
+        compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct} tile=3", oi)
     finally:
         fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
         fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
@@ -118,7 +129,7 @@ def test_first_token_closed_form_and_one_token_chunks():
         _, V = oracle.gather_pair_kv(kv, p, 0, 1)
         for g in range(4):
             assert np.array_equal(out[int(out_indptr[p]) + g].astype(np.float64), V[0])
-    compare_all(ds, kv, q, q_indptr, pairs, 4, 4, "one-token chunks")
+    compare_all(ds, kv, q, q_indptr, pairs, 4, 4, "one-token chunks", out_indptr)
 
 
 def test_chunked_prefill_feeds_from_the_scheduler():
@@ -139,9 +150,9 @@ def test_chunked_prefill_feeds_from_the_scheduler():
     owner, dp, _, _ = fs.fs_build_placement_hybrid_heads(sh, ctx, layer=1, route=entries["rank"])
     rows = 0
     for rank in range(R):
-        ds, kv, q, q_indptr, pairs, out_indptr = run_share(11, n_done, take, Hq, Hkv, owner, rank, R)
-        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"scheduled batch rank {rank}")
-        rows += int(out_indptr[-1])
+        ds, kv, q, q_indptr, pairs, out_indptr = run_share(11, n_done, take, Hq, Hkv, owner, rank, R, chunk=128)
+        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"scheduled batch rank {rank}", out_indptr)
+        rows += int(pairs[:, 3].sum()) * (Hq // Hkv) if len(pairs) else 0
     assert rows == int(take.sum()) * Hq        # every (token, q-head) of the batch is computed exactly once
 
 
@@ -149,16 +160,33 @@ def test_unused_tails_and_spare_slots_are_never_used():
     say("poisoned tails")
     # contexts that end mid-page and mid-pair: the poisoned tail of the last page must not leak
     owner = np.zeros((4, 2), dtype=np.int32)
-    ds, kv, q, q_indptr, pairs, _ = run_share(13, [1, 17, 30, 47], [14, 16, 19, 2], 8, 2, owner, 0, 1)
-    assert np.isfinite(ds.prefill_out.cpu().numpy()).all()
-    compare_all(ds, kv, q, q_indptr, pairs, 8, 4, "tails")
+    for chunk in (0, 32):
+        ds, kv, q, q_indptr, pairs, oi = run_share(13, [1, 17, 30, 47], [14, 16, 19, 2], 8, 2, owner, 0, 1, chunk=chunk)
+        compare_all(ds, kv, q, q_indptr, pairs, 8, 4, f"tails chunk={chunk}", oi)
+
+
+def test_partials_item_by_item():
+    say("partials")
+    # every item's partial rows against the oracle's, rows that see none of a chunk included
+    n_done, n_new, Hq, Hkv = [70, 0, 33], [50, 9, 40], 8, 2
+    owner = np.zeros((3, Hkv), dtype=np.int32)
+    ds, kv, q, q_indptr, pairs, oi = run_share(17, n_done, n_new, Hq, Hkv, owner, 0, 1, tile=8, chunk=64)
+    ref_o, ref_l = oracle.prefill_attention_items(q, kv, ds.w_items, pairs, Hq, 4, 8, SCALE)
+    part_o, part_l = ds.prefill_part_o.cpu().numpy().astype(np.float64), ds.prefill_part_lse.cpu().numpy().astype(np.float64)
+    unseen = np.isneginf(ref_l)
+    assert unseen.any() and np.array_equal(np.isneginf(part_l), unseen)
+    assert (part_o[unseen] == 0).all()
+    pad = np.isnan(ref_l)                       # rows a short last tile does not have: written as zeros
+    assert (part_o[pad] == 0).all() and (part_l[pad] == 0).all()
+    seen = ~unseen & ~pad
+    check(part_o[seen], part_l[seen], ref_o[seen], ref_l[seen], "partials")
 
 
 def test_empty_share_and_bad_arguments():
     say("empty share, errors")
     sh = fs.FsShape(2, 8, 2, 128, 16, 2)
     owner = np.zeros((2, 2), dtype=np.int32)
-    items, pairs, sched, out_indptr = fs.fs_build_prefill_worklist(sh, [5, 6], [3, 4], owner, 1, 4)
+    items, pairs, sched, chunk_indptr, out_indptr = fs.fs_build_prefill_worklist(sh, [5, 6], [3, 4], owner, 1, 4)
     assert len(items) == 0
     dummy = torch.zeros(64, dtype=torch.float32, device="cuda:0")
     kvv = fs.FsKvView(q=dummy.data_ptr(), k_pool=dummy.data_ptr(), v_pool=dummy.data_ptr(), k_slot_stride=4096,

@@ -24,13 +24,15 @@ def test_prefill_worklist_matches_oracle(seed):
     n_new = (rng.integers(0, 300, size=B) * (rng.random(B) < 0.7)).astype(np.int32)
     owner = rng.integers(0, R, size=(B, Hkv)).astype(np.int32)
     tile = int(rng.integers(1, 70))
+    chunk = int(rng.integers(0, 40)) * 32
     shape = fs.FsShape(B, Hkv * G, Hkv, 128, 16, R)
     for k in range(R):
-        w_items, w_pairs, w_sched, w_indptr = oracle.build_prefill_worklist(n_done, n_new, owner, k, Hkv * G, tile)
-        items, pairs, sched, indptr = fs.fs_build_prefill_worklist(shape, n_done, n_new, owner, k, tile)
+        w_items, w_pairs, w_sched, w_chunks, w_out = oracle.build_prefill_worklist(n_done, n_new, owner, k, Hkv * G, tile, chunk)
+        items, pairs, sched, chunks, out = fs.fs_build_prefill_worklist(shape, n_done, n_new, owner, k, tile, chunk)
         assert items.view(np.int32).reshape(-1, 8).tobytes() == w_items.tobytes()
         assert pairs.view(np.int32).reshape(-1, 4).tobytes() == w_pairs.tobytes()
-        assert sched.tobytes() == w_sched.tobytes() and indptr.tobytes() == w_indptr.tobytes()
+        assert sched.tobytes() == w_sched.tobytes() and chunks.tobytes() == w_chunks.tobytes()
+        assert out.tobytes() == w_out.tobytes()
 
 
 def test_field_names_follow_the_oracle():
@@ -53,5 +55,7 @@ def test_tile_tokens_and_errors():
         fs.fs_build_prefill_worklist(shape, [-1], [5], [[0, 1]], 0, 4)
     with pytest.raises(fs.FsError):
         fs.fs_build_prefill_worklist(shape, [0], [5], [[0, 7]], 0, 4)
-    items, pairs, sched, indptr = fs.fs_build_prefill_worklist(shape, [9], [0], [[0, 1]], 0, 4)
-    assert len(items) == 0 and len(pairs) == 0 and indptr.tolist() == [0]
+    with pytest.raises(fs.FsError):
+        fs.fs_build_prefill_worklist(shape, [0], [5], [[0, 1]], 0, 4, 48)    # chunk not a multiple of 32
+    items, pairs, sched, chunks, out = fs.fs_build_prefill_worklist(shape, [9], [0], [[0, 1]], 0, 4)
+    assert len(items) == 0 and len(pairs) == 0 and chunks.tolist() == [0] and out.tolist() == [0]

@@ -5,8 +5,8 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import (bf16_bits_to_f64, build_prefill_worklist, decode_attention_pairs, gather_pair_kv,
-                    prefill_attention_pairs, prefill_attention_row)
+from oracle import (bf16_bits_to_f64, build_prefill_worklist, decode_attention_pairs, gather_pair_kv, merge_lse,
+                    prefill_attention_items, prefill_attention_pairs, prefill_attention_row)
 from workloads import make_kv_pool, make_prefill_q
 
 SCALE = 1.0 / math.sqrt(128.0)
@@ -15,7 +15,9 @@ SCALE = 1.0 / math.sqrt(128.0)
 def _setup(seed, n_done, n_new, Hq, Hkv, owner=None, rank=0, tile=8):
     B = len(n_done)
     owner = np.zeros((B, Hkv), dtype=np.int32) if owner is None else np.asarray(owner)
-    items, pairs, sched, out_indptr = build_prefill_worklist(n_done, n_new, owner, rank, Hq, tile)
+    items, pairs, sched, chunk_indptr, _ = build_prefill_worklist(n_done, n_new, owner, rank, Hq, tile)
+    G = Hq // Hkv
+    out_indptr = np.concatenate([[0], np.cumsum(pairs[:, 3] * G)]).astype(np.int64) if len(pairs) else np.zeros(1, np.int64)
     ctx = (np.asarray(n_done) + np.asarray(n_new)).astype(np.int32)
     kv = make_kv_pool(seed, pairs[:, :2], ctx, threads=1)
     q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
@@ -97,15 +99,23 @@ def test_one_new_token_is_decode_attention():
 
 
 def test_worklist_by_hand():
-    # 2 requests, 2 KV heads, 4 q-heads; rank 1 owns head 1 of request 0 and both heads of request 1
+    # 2 requests, 2 KV heads, 4 q-heads (G = 2); rank 1 owns head 1 of request 0 and both heads of request 1
     owner = [[0, 1], [1, 1]]
-    items, pairs, sched, out_indptr = build_prefill_worklist([10, 0], [5, 3], owner, 1, 4, tile_tokens=4)
-    assert pairs.tolist() == [[0, 1, 10, 5], [1, 0, 0, 3], [1, 1, 0, 3]]
-    assert out_indptr.tolist() == [0, 10, 16, 22]
-    # (req, kv_head, pair, q_begin, q_end, n_done, q_row, out_row); Q rows: request 0 tokens 0..4, request 1 tokens 5..7
-    assert items.tolist() == [[0, 1, 0, 0, 4, 10, 0 * 4 + 2, 0], [0, 1, 0, 4, 5, 10, 4 * 4 + 2, 8],
-                              [1, 0, 1, 0, 3, 0, 5 * 4 + 0, 10], [1, 1, 2, 0, 3, 0, 5 * 4 + 2, 16]]
-    assert sched.tolist() == [1, 0, 2, 3]           # key counts 15, 14, 3, 3
+    items, pairs, sched, chunk_indptr, out_indptr = build_prefill_worklist([40, 0], [5, 3], owner, 1, 4, tile_tokens=4,
+                                                                           kv_chunk_tokens=32)
+    assert pairs.tolist() == [[0, 1, 40, 5], [1, 0, 0, 3], [1, 1, 0, 3]]
+    # tiles: pair 0 -> tokens [0,4) (keys 44: chunks [0,32) [32,44)) and [4,5) (keys 45: [0,32) [32,45)); pairs 1, 2 -> one tile, one chunk
+    # (pair, q_begin, q_end, n_done, kv_begin, kv_end, q_row, part_row); T = 4 tokens x 2 = 8 rows per item
+    assert items.tolist() == [[0, 0, 4, 40, 0, 32, 0 * 4 + 2, 0], [0, 0, 4, 40, 32, 44, 0 * 4 + 2, 8],
+                              [0, 4, 5, 40, 0, 32, 4 * 4 + 2, 16], [0, 4, 5, 40, 32, 45, 4 * 4 + 2, 24],
+                              [1, 0, 3, 0, 0, 3, 5 * 4 + 0, 32], [2, 0, 3, 0, 0, 3, 5 * 4 + 2, 40]]
+    assert chunk_indptr.tolist() == [0, 2, 4, 5, 6]
+    assert out_indptr.tolist() == [0, 16, 24, 32]          # pair 0 has two tiles of 8 rows, the others one
+    assert sched.tolist() == [0, 2, 3, 1, 4, 5]            # keys per item: 32, 12, 32, 13, 3, 3
+    # no split: one item per tile
+    items0, _, sched0, chunk0, out0 = build_prefill_worklist([40, 0], [5, 3], owner, 1, 4, tile_tokens=4)
+    assert items0[:, 4:6].tolist() == [[0, 44], [0, 45], [0, 3], [0, 3]] and chunk0.tolist() == [0, 1, 2, 3, 4]
+    assert out0.tolist() == out_indptr.tolist() and sched0.tolist() == [1, 0, 2, 3]
 
 
 @pytest.mark.parametrize("seed", range(10))
@@ -116,19 +126,50 @@ def test_worklist_invariants(seed):
     n_new = rng.integers(0, 40, size=B)
     owner = rng.integers(0, R, size=(B, Hkv))
     tile = int(rng.integers(1, 20))
+    chunk = int(rng.integers(0, 4)) * 32
+    T = tile * G
     seen = set()
     for k in range(R):
-        items, pairs, sched, out_indptr = build_prefill_worklist(n_done, n_new, owner, k, Hkv * G, tile)
+        items, pairs, sched, chunk_indptr, out_indptr = build_prefill_worklist(n_done, n_new, owner, k, Hkv * G, tile, chunk)
         assert sorted(sched.tolist()) == list(range(len(items)))
-        keys = [items[i][5] + items[i][4] for i in sched]
+        keys = [items[i][5] - items[i][4] for i in sched]
         assert keys == sorted(keys, reverse=True)
+        assert [it[7] for it in items] == [i * T for i in range(len(items))]
+        n_tiles = 0
         for p, (r, h, L, N) in enumerate(pairs):
             assert owner[r, h] == k and N == n_new[r] > 0 and L == n_done[r]
             seen.add((int(r), int(h)))
-            mine = [it for it in items if it[2] == p]
-            assert [it[3] for it in mine] == list(range(0, N, tile))
-            assert all(it[4] == min(N, it[3] + tile) for it in mine)
-            assert all(it[7] == out_indptr[p] + it[3] * G for it in mine)
-            assert all(it[6] == (int(n_new[:r].sum()) + it[3]) * Hkv * G + h * G for it in mine)
-        assert out_indptr[-1] == sum(int(p[3]) for p in pairs) * G
+            assert out_indptr[p] == n_tiles * T
+            for b in range(0, N, tile):
+                e = min(N, b + tile)
+                mine = items[chunk_indptr[n_tiles]:chunk_indptr[n_tiles + 1]]
+                assert all(it[0] == p and it[1] == b and it[2] == e and it[3] == L for it in mine)
+                assert all(it[6] == (int(n_new[:r].sum()) + b) * Hkv * G + h * G for it in mine)
+                # the chunks tile [0, L + e) without gap or overlap, all but the last of full size
+                assert mine[0][4] == 0 and mine[-1][5] == L + e
+                assert all(a[5] == c[4] for a, c in zip(mine[:-1], mine[1:]))
+                assert all(it[5] - it[4] == chunk for it in mine[:-1])
+                n_tiles += 1
+        assert chunk_indptr[-1] == len(items) and len(chunk_indptr) == n_tiles + 1 and out_indptr[-1] == n_tiles * T
     assert seen == {(r, h) for r in range(B) for h in range(Hkv) if n_new[r] > 0}
+
+
+@pytest.mark.parametrize("chunk", [32, 64, 96])
+def test_chunk_partials_merge_back_to_unsplit(chunk):
+    # split-K is exact algebra: merging the items' partials (rows that see none of a chunk included)
+    # gives the unsplit result
+    n_done, n_new, Hq, Hkv, G, tile = [70, 0, 33], [50, 9, 40], 4, 2, 2, 8
+    owner = np.zeros((3, Hkv), dtype=np.int32)
+    items, pairs, sched, chunk_indptr, out_indptr = build_prefill_worklist(n_done, n_new, owner, 0, Hq, tile, chunk)
+    ctx = (np.asarray(n_done) + np.asarray(n_new)).astype(np.int32)
+    kv = make_kv_pool(21, pairs[:, :2], ctx, threads=1)
+    q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    q = make_prefill_q(21, int(q_indptr[-1]), Hq, 128)
+    part_o, part_lse = prefill_attention_items(q, kv, items, pairs, Hq, G, tile, SCALE)
+    assert np.isinf(part_lse[np.isfinite(part_o).all(axis=1)]).any()      # the case of an unseen chunk occurs
+    with np.errstate(invalid="ignore"):
+        out, lse = merge_lse(part_o, part_lse, chunk_indptr, tile * G)
+    want_o, want_l = prefill_attention_pairs(q, q_indptr, kv, pairs, Hq, G, SCALE, out_indptr=out_indptr)
+    valid = np.isfinite(want_l)
+    assert valid.sum() == int(pairs[:, 3].sum()) * G
+    assert np.abs(out[valid] - want_o[valid]).max() < 1e-12 and np.abs(lse[valid] - want_l[valid]).max() < 1e-12
