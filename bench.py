@@ -56,6 +56,8 @@ def main() -> int:
                     help="decode: the measured decode-attention share (default); prefill: the chunked-prefill attention share")
     ap.add_argument("--prefill-waves", type=int, default=None)
     ap.add_argument("--prefill-col-tiles", type=int, default=None)
+    ap.add_argument("--prefill-budget", type=int, default=8192, help="prefill path: token budget of the batch")
+    ap.add_argument("--prefill-queue", type=int, default=64, help="prefill path: waiting prompts")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

@@ -19,7 +19,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 
 
 def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64, n_kv_heads=8, seed=20251120,
-                     median=8001, cap=123192):
+                     median=8001, cap=123192, kv_chunk=1024):
     """Queue -> router -> Algorithm 1 -> hybrid placement -> rank's tile list (library calls only)."""
     from workloads import make_prefill_queue
     queue = make_prefill_queue(seed, n_req, median=median, sigma=0.9, cap=cap)
@@ -39,11 +39,13 @@ def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64,
     owner, dp, rank_load, dp_load = fs.fs_build_placement_hybrid_heads(shape, ctx, layer=0, route=entries["rank"])
     G = n_q_heads // n_kv_heads
     tile = fs.fs_prefill_tile_tokens(G)
-    items, pairs, sched, out_indptr = fs.fs_build_prefill_worklist(shape, n_done, take, owner, rank, tile)
+    items, pairs, sched, chunk_indptr, out_indptr = fs.fs_build_prefill_worklist(shape, n_done, take, owner, rank, tile,
+                                                                                 kv_chunk)
     t3 = time.perf_counter()
     return dict(seed=seed, shape=shape, G=G, R=R, rank=rank, budget=budget, prompt=prompt, n_done=n_done,
                 n_new=take.astype(np.int32), entries=entries, rank_token_load=load, n_tokens=n_tok, owner=owner,
-                tile=tile, items=items, pairs=pairs, sched=sched, out_indptr=out_indptr,
+                tile=tile, kv_chunk=kv_chunk, items=items, pairs=pairs, sched=sched, chunk_indptr=chunk_indptr,
+                out_indptr=out_indptr,
                 host_us=dict(router=(t1 - t0) * 1e6, scheduler=(t2 - t1) * 1e6, placement_and_list=(t3 - t2) * 1e6))
 
 
@@ -78,7 +80,9 @@ def run(args) -> int:
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream()
 
-    w = prefill_workload(fs, rank=args.rank)
+    kv_chunk = 2048 if args.chunk is None else args.chunk
+    wl = dict(rank=args.rank, kv_chunk=kv_chunk, budget=args.prefill_budget, n_req=args.prefill_queue)
+    w = prefill_workload(fs, **wl)
     shape, G, pairs, items = w["shape"], w["G"], w["pairs"], w["items"]
     if len(items) == 0:
         print("bench.py: this rank's prefill share is empty", file=sys.stderr)
@@ -88,30 +92,37 @@ def run(args) -> int:
     q_indptr = np.concatenate([[0], np.cumsum(w["n_new"])]).astype(np.int64)
     q = make_prefill_q(w["seed"], int(q_indptr[-1]), shape.n_q_heads, 128)
     ds = DeviceShare(shape, q, kv, 1.0 / np.sqrt(128.0))
-    ds.set_prefill_worklist(items, w["sched"], w["out_indptr"], w["tile"])
+    ds.set_prefill_worklist(items, w["sched"], w["chunk_indptr"], w["tile"])
     flops = algorithmic_flops(pairs, G)
-    rows = int(w["out_indptr"][-1])
+    rows = int(sum(int(p["n_new"]) for p in pairs)) * G
     kv_tokens = int(sum(int(p["n_done"]) + int(p["n_new"]) for p in pairs))
 
     host_us = []
 
     def step(ev=None):
         t0 = time.perf_counter()
-        ww = prefill_workload(fs, rank=args.rank)                       # host side of the step (library calls)
+        ww = prefill_workload(fs, **wl)                                  # host side of the step (library calls)
         ds.prefill_items.copy_(torch.from_numpy(ww["items"].view(np.int32).reshape(-1, 8)), non_blocking=True)
         ds.prefill_sched.copy_(torch.from_numpy(ww["sched"]), non_blocking=True)
+        ds.prefill_chunk_indptr.copy_(torch.from_numpy(ww["chunk_indptr"]), non_blocking=True)
         host_us.append((time.perf_counter() - t0) * 1e6)
+        sp = stream.cuda_stream
         if ev is not None:
             ev[0].record(stream)
-        ds.prefill()
+        fs.fs_prefill_attention(ds.shape, ds.view, ds.prefill_items, ds.prefill_sched, ds.n_prefill_items,
+                                ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
         if ev is not None:
             ev[1].record(stream)
+        fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_chunk_indptr, ds.n_prefill_tiles,
+                        ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
+        if ev is not None:
+            ev[2].record(stream)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     host_us.clear()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -120,6 +131,7 @@ def run(args) -> int:
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     k_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
+    m_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
 
     out = ds.prefill_out.cpu().numpy()
     lse = ds.prefill_lse.cpu().numpy()
@@ -158,13 +170,14 @@ def run(args) -> int:
         "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"prefill batch: 64 waiting prompts (lognormal median 8001, cap 123192), budget 8192 tokens, "
+        "config": {"workload": f"prefill batch: {args.prefill_queue} waiting prompts (lognormal median 8001, cap 123192), budget {args.prefill_budget} tokens, "
                                f"Hq=64, Hkv=8, d=128, page=16, R=7 head-level hybrid, rank {args.rank}, seed={w['seed']}",
-                   "n_pairs": len(pairs), "n_items": len(items), "tile_tokens": w["tile"], "batch_tokens": int(w["n_tokens"]),
+                   "n_pairs": len(pairs), "n_tiles": ds.n_prefill_tiles, "n_items": len(items), "tile_tokens": w["tile"],
+                   "kv_chunk_tokens": kv_chunk, "batch_tokens": int(w["n_tokens"]),
                    "query_rows": rows, "kv_tokens_of_pairs": kv_tokens, "flops": flops,
                    "prefill_waves": fs.fs_get_option("prefill_waves"), "prefill_col_tiles": fs.fs_get_option("prefill_col_tiles")},
         "kernel_ms": {"prefill_avg": round(k_avg, 5), "prefill_p10": round(float(np.percentile(k_ms, 10)), 5),
-                      "prefill_p90": round(float(np.percentile(k_ms, 90)), 5)},
+                      "prefill_p90": round(float(np.percentile(k_ms, 90)), 5), "merge_avg": round(float(m_ms.mean()), 5)},
         "host_us_per_step": {"all_avg": round(float(np.mean(host_us)), 1), **{k: round(v, 1) for k, v in w["host_us"].items()}},
         "query_token_heads_per_s": round(rows / G / (ms_per_step * 1e-3), 1),
         "roofline": {"bound": "mfma", "kernel": "prefill_bf16_kernel", "achieved": round(flops / (k_avg * 1e-3) / 1e12, 2),

@@ -35,6 +35,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
 
 struct PrefillParams {
   const uint16_t* __restrict__ q;
@@ -86,6 +87,64 @@ struct TileState {
   float l;          // this lane's share of the running sum
   f32x4 acc[8];     // O^T[d = 16b + 4*(lane/16) + r][row = lane%16]
 };
+
+// Online softmax of one column tile over one page pair and its share of O^T += V^T . P^T.
+// sa/sb: raw scores of the tile against the two pages (this lane: tokens t0 + 4kb + r and
+// t0 + 16 + 4kb + r).  MASK: some of the 32 tokens lie beyond some row's position `pos`.
+template <bool MASK>
+__device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const f32x4 sb, const u32x4 (&va)[4],
+                                           const u32x4 (&vb)[4], float scale_log2, int t0, int pos, int kb) {
+  // no fused multiply-add here: a row's top key must get exp2(0) = 1 exactly, which needs the scaled
+  // score rounded the same way on both sides of the subtraction
+#pragma clang fp contract(off)
+  f32x8 s = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
+  if (MASK) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if (t0 + 4 * kb + r > pos) s[r] = -INFINITY;
+      if (t0 + 16 + 4 * kb + r > pos) s[4 + r] = -INFINITY;
+    }
+  }
+  // the softmax scale is positive, so the max of the raw scores is the max of the scaled ones
+  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  mx = xor32(xor16(mx, true), true) * scale_log2;
+  const float m_new = fmaxf(st.m, mx);
+  // MASK only: a row may have seen none of the item's keys so far (its position lies before the
+  // chunk); its state stays at zero.  Without a mask every score is finite and so is m_new.
+  const float m_ref = (MASK && m_new == -INFINITY) ? 0.f : m_new;
+  if (__any(m_new > st.m)) {
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);   // first keys of a row: exp2(-inf) = 0
+    st.l *= alpha;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
+    st.m = m_new;
+  }
+  f32x8 p;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * scale_log2 - m_ref);   // product rounded first: the row's top key gets exactly 1
+  st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+  // Weights as bf16 hi + lo (16 significant bits).  hi is p cut to its upper 16 bits (one byte
+  // permute packs two of them), lo = p - hi is exact in fp32 and is rounded to bf16.
+  u32x4 hi_packed;
+  f32x8 lo;
+#pragma unroll
+  for (int r = 0; r < 8; r += 2) {
+    const uint32_t b0 = __float_as_uint(p[r]), b1 = __float_as_uint(p[r + 1]);
+    hi_packed[r / 2] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);     // (b1 & 0xFFFF0000) | (b0 >> 16)
+    lo[r] = p[r] - __uint_as_float(b0 & 0xFFFF0000u);
+    lo[r + 1] = p[r + 1] - __uint_as_float(b1 & 0xFFFF0000u);
+  }
+  const bf16x8 ph = __builtin_bit_cast(bf16x8, hi_packed);
+  const bf16x8 pl = __builtin_convertvector(lo, bf16x8);
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const bf16x8 a = __builtin_bit_cast(bf16x8, va[c]), b = __builtin_bit_cast(bf16x8, vb[c]);
+    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph, st.acc[2 * c], 0, 0, 0);
+    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, ph, st.acc[2 * c + 1], 0, 0, 0);
+    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, st.acc[2 * c], 0, 0, 0);
+    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, pl, st.acc[2 * c + 1], 0, 0, 0);
+  }
+}
 
 template <int WAVES, int CT>
 __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillParams P) {
@@ -187,6 +246,7 @@ __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillP
     if (!any) return;
     const unsigned char* base = stage[s];
     f32x4 sa[CT], sb[CT];
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     {
       u32x4 k0[4], k1[4];
 #pragma unroll
@@ -196,11 +256,11 @@ __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillP
       }
 #pragma unroll
       for (int t = 0; t < CT; ++t) {
-        sa[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        sb[t] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (need[t]) {
+          sa[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k0[0]), qreg[t][0], zero4, 0, 0, 0);
+          sb[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k1[0]), qreg[t][0], zero4, 0, 0, 0);
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
+          for (int c = 1; c < 4; ++c) {
             sa[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k0[c]), qreg[t][c], sa[t], 0, 0, 0);
             sb[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k1[c]), qreg[t][c], sb[t], 0, 0, 0);
           }
@@ -216,54 +276,8 @@ __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillP
 #pragma unroll
     for (int t = 0; t < CT; ++t) {
       if (!need[t]) continue;
-      float x[8];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        x[r] = sa[t][r] * P.scale_log2;
-        x[4 + r] = sb[t][r] * P.scale_log2;
-      }
-      if (!full[t]) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (t0 + 4 * kb + r > pos[t]) x[r] = -INFINITY;
-          if (t0 + 16 + 4 * kb + r > pos[t]) x[4 + r] = -INFINITY;
-        }
-      }
-      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      mx = xor32(xor16(mx, true), true);
-      const float m_new = fmaxf(st[t].m, mx);
-      // a row may see none of the item's keys so far (its position lies before the chunk): keep its state at zero
-      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-      if (__any(m_new > st[t].m)) {
-        const float alpha = __builtin_amdgcn_exp2f(st[t].m - m_ref);   // first keys of a row: exp2(-inf) = 0
-        st[t].l *= alpha;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) st[t].acc[j] *= alpha;
-        st[t].m = m_new;
-      }
-      float p[8];
-      float ps = 0.f;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(x[r] - m_ref);
-        ps += p[r];
-      }
-      st[t].l += ps;
-      // weights as bf16 hi + lo (16 significant bits), as in the decode kernel
-      bf16x8 ph, pl;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        ph[r] = static_cast<__bf16>(p[r]);
-        pl[r] = static_cast<__bf16>(p[r] - static_cast<float>(ph[r]));
-      }
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, va[c]), b = __builtin_bit_cast(bf16x8, vb[c]);
-        st[t].acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph, st[t].acc[2 * c], 0, 0, 0);
-        st[t].acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, ph, st[t].acc[2 * c + 1], 0, 0, 0);
-        st[t].acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, st[t].acc[2 * c], 0, 0, 0);
-        st[t].acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, pl, st[t].acc[2 * c + 1], 0, 0, 0);
-      }
+      if (full[t]) softmax_pv<false>(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb);
+      else softmax_pv<true>(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb);
     }
   };
 
