@@ -145,9 +145,9 @@ def run(args) -> int:
         rng = np.random.default_rng(1)
         prs = oracle.PREFILL_PAIR_FIELDS
         pr_rows = np.stack([pairs[n] for n in prs], axis=1)
-        budget_flops, done_flops, n_rows, ok = 4e9, 0, 0, True
+        budget_flops, done_flops, n_rows, ok = 2e11, 0, 0, True
         t0 = time.perf_counter()
-        while done_flops < budget_flops and time.perf_counter() - t0 < 25:
+        while done_flops < budget_flops and time.perf_counter() - t0 < 20:
             p = int(rng.integers(0, len(pairs)))
             tok = int(rng.integers(0, int(pairs[p]["n_new"])))
             o, l = oracle.prefill_attention_row(q, q_indptr, kv, pr_rows, shape.n_q_heads, G, 1.0 / np.sqrt(128.0), p, tok)

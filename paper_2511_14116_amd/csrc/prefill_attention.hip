@@ -82,6 +82,14 @@ struct InFlight {
   u32x4 v[NP];
 };
 
+// max of three without the NaN-quieting moves the compiler puts around fmaxf (the inputs are matrix-core
+// outputs or -inf; a NaN can only come from a row that is never stored)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 struct TileState {
   float m;          // running max (log2 domain) of this lane's query row
   float l;          // this lane's share of the running sum
@@ -90,15 +98,16 @@ struct TileState {
 
 // Online softmax of one column tile over one page pair and its share of O^T += V^T . P^T.
 // sa/sb: raw scores of the tile against the two pages (this lane: tokens t0 + 4kb + r and
-// t0 + 16 + 4kb + r).  MASK: some of the 32 tokens lie beyond some row's position `pos`.
-template <bool MASK>
+// t0 + 16 + 4kb + r).  mask: some of the 32 tokens lie beyond some row's position `pos`.
 __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const f32x4 sb, const u32x4 (&va)[4],
-                                           const u32x4 (&vb)[4], float scale_log2, int t0, int pos, int kb) {
+                                           const u32x4 (&vb)[4], float scale_log2, int t0, int pos, int kb,
+                                           bool mask) {
   // no fused multiply-add here: a row's top key must get exp2(0) = 1 exactly, which needs the scaled
   // score rounded the same way on both sides of the subtraction
 #pragma clang fp contract(off)
   f32x8 s = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
-  if (MASK) {
+  if (mask) {   // wave-uniform; kept a real branch (the empty asm stops the compiler from turning it into 16 selects on every step)
+    asm volatile("");
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       if (t0 + 4 * kb + r > pos) s[r] = -INFINITY;
@@ -106,19 +115,19 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     }
   }
   // the softmax scale is positive, so the max of the raw scores is the max of the scaled ones
-  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  float mx = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), fmaxf(s[6], s[7]));
   mx = xor32(xor16(mx, true), true) * scale_log2;
   const float m_new = fmaxf(st.m, mx);
-  // MASK only: a row may have seen none of the item's keys so far (its position lies before the
-  // chunk); its state stays at zero.  Without a mask every score is finite and so is m_new.
-  const float m_ref = (MASK && m_new == -INFINITY) ? 0.f : m_new;
-  if (__any(m_new > st.m)) {
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);   // first keys of a row: exp2(-inf) = 0
-    st.l *= alpha;
+  // A row may have seen none of the item's keys so far (its position lies before the chunk): its
+  // state stays at zero.
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  // Rescale on every step (alpha is 1 when the max did not move): a branch around these 33 multiplies
+  // makes the compiler copy the whole accumulator instead, which costs the same on every step.
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);     // first keys of a row: exp2(-inf) = 0
+  st.l *= alpha;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
-    st.m = m_new;
-  }
+  for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
+  st.m = m_new;
   f32x8 p;
 #pragma unroll
   for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * scale_log2 - m_ref);   // product rounded first: the row's top key gets exactly 1
@@ -146,8 +155,10 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
   }
 }
 
+// The 8-wavefront, one-column-tile shape is held to 128 registers so that two workgroups (four
+// wavefronts per SIMD) share a CU: the softmax is a long dependent chain and needs the company.
 template <int WAVES, int CT>
-__global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillParams P) {
+__global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) prefill_bf16_kernel(const PrefillParams P) {
   constexpr int NP = 8 / WAVES;        // (K, V) block couples a wavefront moves per page pair
   static_assert(NP >= 1, "at most 8 wavefronts");
   __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
@@ -275,9 +286,7 @@ __global__ void __launch_bounds__(WAVES * 64) prefill_bf16_kernel(const PrefillP
     }
 #pragma unroll
     for (int t = 0; t < CT; ++t) {
-      if (!need[t]) continue;
-      if (full[t]) softmax_pv<false>(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb);
-      else softmax_pv<true>(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb);
+      if (need[t]) softmax_pv(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb, !full[t]);
     }
   };
 

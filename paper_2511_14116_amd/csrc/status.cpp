@@ -17,7 +17,7 @@ fs_status fail(fs_status st, const char* fmt, ...) {
 }
 
 Options& options() {
-  static Options o{4, 2, 2, 4};
+  static Options o{4, 2, 1, 8};
   return o;
 }
 
