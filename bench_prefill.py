@@ -16,10 +16,11 @@ import time
 import numpy as np
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
+KV_CHUNK_DEFAULT = 2048            # split-K chunk of the keys a tile sees
 
 
 def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64, n_kv_heads=8, seed=20251120,
-                     median=8001, cap=123192, kv_chunk=1024):
+                     median=8001, cap=123192, kv_chunk=KV_CHUNK_DEFAULT):
     """Queue -> router -> Algorithm 1 -> hybrid placement -> rank's tile list (library calls only)."""
     from workloads import make_prefill_queue
     queue = make_prefill_queue(seed, n_req, median=median, sigma=0.9, cap=cap)
@@ -80,7 +81,7 @@ def run(args) -> int:
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream()
 
-    kv_chunk = 2048 if args.chunk is None else args.chunk
+    kv_chunk = KV_CHUNK_DEFAULT if args.chunk is None else args.chunk
     wl = dict(rank=args.rank, kv_chunk=kv_chunk, budget=args.prefill_budget, n_req=args.prefill_queue)
     w = prefill_workload(fs, **wl)
     shape, G, pairs, items = w["shape"], w["G"], w["pairs"], w["items"]

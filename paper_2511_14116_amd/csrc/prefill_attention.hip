@@ -61,19 +61,6 @@ constexpr int kStageBytes = 16384;     // one pair of pages: K0, K1 (4 KiB each)
 constexpr int kVaOffset = 8192;        // V rows d = 32c + lane%16:      (page 0 tokens 4kb..+3 | page 1 tokens 4kb..+3)
 constexpr int kVbOffset = 12288;       // V rows d = 32c + 16 + lane%16: likewise
 
-__device__ __forceinline__ float xor16(float v, bool take_max) {
-  const unsigned u = __builtin_bit_cast(unsigned, v);
-  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const unsigned a = r[0], b = r[1];
-  return take_max ? fmaxf(__uint_as_float(a), __uint_as_float(b)) : __uint_as_float(a) + __uint_as_float(b);
-}
-__device__ __forceinline__ float xor32(float v, bool take_max) {
-  const unsigned u = __builtin_bit_cast(unsigned, v);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  const unsigned a = r[0], b = r[1];
-  return take_max ? fmaxf(__uint_as_float(a), __uint_as_float(b)) : __uint_as_float(a) + __uint_as_float(b);
-}
-
 // A wavefront's share of one page pair on its way from global memory to LDS: NP (K block, V block)
 // couples of 1 KiB, each couple from one page h and one 32-d block c.
 template <int NP>
@@ -90,11 +77,27 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
+__device__ __forceinline__ float max2(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+// x *= a in place.  As asm with a tied operand so that, inside a rarely taken branch, the accumulators
+// stay in their registers (with a plain multiply the compiler copies all of them on every step instead).
+#define FS_SCALE_IN_PLACE(vec, k, a)                                  \
+  do {                                                                \
+    float t_ = (vec)[k];                                              \
+    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(t_) : "v"(a));         \
+    (vec)[k] = t_;                                                    \
+  } while (0)
+
 struct TileState {
-  float m;          // running max (log2 domain) of this lane's query row
-  float l;          // this lane's share of the running sum
+  float m;          // reference max (log2 domain) of this lane's query row: within 2^8 below the true running max
+  f32x4 l;          // running sum of the row's weights, element 0 (kept on the matrix cores: a row of ones above V^T)
   f32x4 acc[8];     // O^T[d = 16b + 4*(lane/16) + r][row = lane%16]
 };
+
+constexpr float kLazy = 8.0f;   // the reference max follows the running max only when it falls 2^8 behind
 
 // Online softmax of one column tile over one page pair and its share of O^T += V^T . P^T.
 // sa/sb: raw scores of the tile against the two pages (this lane: tokens t0 + 4kb + r and
@@ -115,23 +118,40 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     }
   }
   // the softmax scale is positive, so the max of the raw scores is the max of the scaled ones
-  float mx = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), fmaxf(s[6], s[7]));
-  mx = xor32(xor16(mx, true), true) * scale_log2;
-  const float m_new = fmaxf(st.m, mx);
+  float mx = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max2(s[6], s[7]));
+  {
+    const unsigned u = __float_as_uint(mx);
+    const auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned a = r16[0], b = r16[1];
+    mx = max2(__uint_as_float(a), __uint_as_float(b));
+    const unsigned v = __float_as_uint(mx);
+    const auto r32 = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    const unsigned c = r32[0], d = r32[1];
+    mx = max2(__uint_as_float(c), __uint_as_float(d)) * scale_log2;
+  }
+  // Lazy reference max: the exponentials are taken against st.m, which moves up to the block's max only
+  // when that lies more than 2^8 above it (always on a row's first visible keys, where st.m is -inf, so
+  // a row's first top key still gets exactly 1; rarely afterwards).  Weights stay below 2^8, which costs
+  // fp32 sums and the bf16 hi/lo pair no precision, and the 33 rescale multiplies leave the common path.
+  const bool move = mx > st.m + kLazy;
+  if (__any(move)) {
+    const float alpha = move ? __builtin_amdgcn_exp2f(st.m - mx) : 1.0f;   // st.m = -inf: exp2(-inf) = 0
+    FS_SCALE_IN_PLACE(st.l, 0, alpha);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      FS_SCALE_IN_PLACE(st.acc[j], 0, alpha);
+      FS_SCALE_IN_PLACE(st.acc[j], 1, alpha);
+      FS_SCALE_IN_PLACE(st.acc[j], 2, alpha);
+      FS_SCALE_IN_PLACE(st.acc[j], 3, alpha);
+    }
+    st.m = move ? mx : st.m;
+  }
   // A row may have seen none of the item's keys so far (its position lies before the chunk): its
   // state stays at zero.
-  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-  // Rescale on every step (alpha is 1 when the max did not move): a branch around these 33 multiplies
-  // makes the compiler copy the whole accumulator instead, which costs the same on every step.
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);     // first keys of a row: exp2(-inf) = 0
-  st.l *= alpha;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
-  st.m = m_new;
+  const float m_ref = st.m == -INFINITY ? 0.f : st.m;
   f32x8 p;
 #pragma unroll
   for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * scale_log2 - m_ref);   // product rounded first: the row's top key gets exactly 1
-  st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
   // Weights as bf16 hi + lo (16 significant bits).  hi is p cut to its upper 16 bits (one byte
   // permute packs two of them), lo = p - hi is exact in fp32 and is rounded to bf16.
   u32x4 hi_packed;
@@ -153,6 +173,11 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, st.acc[2 * c], 0, 0, 0);
     st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, pl, st.acc[2 * c + 1], 0, 0, 0);
   }
+  // the row sums: a row of ones in place of V^T leaves sum_t p_t in every element of the result column
+  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, ph, st.l, 0, 0, 0);
+  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pl, st.l, 0, 0, 0);
 }
 
 // The 8-wavefront, one-column-tile shape is held to 128 registers so that two workgroups (four
@@ -203,7 +228,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
 #pragma unroll
   for (int t = 0; t < CT; ++t) {
     st[t].m = -INFINITY;
-    st[t].l = 0.f;
+    st[t].l = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 8; ++j) st[t].acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
@@ -321,7 +346,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
 #pragma unroll
   for (int t = 0; t < CT; ++t) {
     const int tok = tok0 + t * tpc + tl;
-    const float l_tot = xor32(xor16(st[t].l, false), false);
+    const float l_tot = st[t].l[0];
     if (g >= G || tok >= P.tile_tokens) continue;          // no such row in the partial buffer
     const int64_t row = static_cast<int64_t>(it.part_row) + static_cast<int64_t>(tok) * G + g;
     float* o = P.part_o + row * fs::kHeadDim + 4 * kb;

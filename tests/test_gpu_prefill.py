@@ -198,3 +198,35 @@ def test_empty_share_and_bad_arguments():
     kvv.kv_dtype = fs.FS_KV_FP8_E4M3
     with pytest.raises(fs.FsError):
         fs.fs_prefill_attention(sh, kvv, dummy, None, 1, 4, dummy, dummy)
+
+
+def test_bench_batch_full_size_sampled():
+    """The batch `bench.py --path prefill` times, in its launch configuration: sampled (pair, token)
+    rows against the oracle, one by one, plus finiteness of every row."""
+    say("bench batch, sampled rows")
+    import bench_prefill
+    w = bench_prefill.prefill_workload(fs)
+    shape, G, pairs, items = w["shape"], w["G"], w["pairs"], w["items"]
+    assert w["tile"] == fs.fs_prefill_tile_tokens(G) and w["kv_chunk"] == bench_prefill.KV_CHUNK_DEFAULT
+    ctx = (w["n_done"] + w["n_new"]).astype(np.int32)
+    kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx)
+    q_indptr = np.concatenate([[0], np.cumsum(w["n_new"])]).astype(np.int64)
+    q = make_prefill_q(w["seed"], int(q_indptr[-1]), shape.n_q_heads, 128)
+    ds = DeviceShare(shape, q, kv, SCALE)
+    ds.set_prefill_worklist(items, w["sched"], w["chunk_indptr"], w["tile"])
+    ds.prefill()
+    torch.cuda.synchronize()
+    out, lse = ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    pr = np.stack([pairs[n] for n in oracle.PREFILL_PAIR_FIELDS], axis=1)
+    rng = np.random.default_rng(3)
+    longest = int(np.argmax(pr[:, 2] + pr[:, 3]))
+    samples = [(longest, int(pr[longest, 3]) - 1), (longest, 0), (0, 0)]
+    samples += [(int(p), int(rng.integers(0, pr[p, 3]))) for p in rng.integers(0, len(pr), size=40)]
+    got_o, got_l, ref_o, ref_l = [], [], [], []
+    for p, tok in samples:
+        o, l = oracle.prefill_attention_row(q, q_indptr, kv, pr, shape.n_q_heads, G, SCALE, p, tok)
+        row = int(w["out_indptr"][p]) + tok * G
+        got_o.append(out[row:row + G]); got_l.append(lse[row:row + G]); ref_o.append(o); ref_l.append(l)
+    check(np.concatenate(got_o), np.concatenate(got_l), np.concatenate(ref_o), np.concatenate(ref_l),
+          f"bench batch, {len(samples)} sampled rows")
