@@ -6,6 +6,7 @@
 // least-loaded rank that still has schedulable tokens, then picks the best of the batches
 // it passed through.  What the paper leaves open (the token cost, the choice among the
 // candidates, the unused workload input) is fixed as the header states.
+#include <new>
 #include <vector>
 
 #include "fs_internal.h"
@@ -22,10 +23,10 @@ extern "C" fs_status fs_route_request(int32_t n_ranks, int64_t* pending, int64_t
   return FS_OK;
 }
 
-extern "C" fs_status fs_schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens,
-                                         const fs_prefill_entry* entries, int32_t n_entries,
-                                         const int64_t* init_load, int32_t* take, int64_t* load,
-                                         int32_t* n_tokens) {
+namespace {
+fs_status schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens, const fs_prefill_entry* entries,
+                           int32_t n_entries, const int64_t* init_load, int32_t* take, int64_t* load,
+                           int32_t* n_tokens) {
   const int32_t R = n_ranks;
   if (R < 1) return fs::fail(FS_EINVAL, "fs_schedule_prefill: n_ranks %d < 1", R);
   if (budget < 0 || min_tokens < 0 || n_entries < 0)
@@ -58,9 +59,12 @@ extern "C" fs_status fs_schedule_prefill(int32_t n_ranks, int32_t budget, int32_
   // took from plus the largest load and the load sum at that point.
   std::vector<int32_t> took_from;
   std::vector<int64_t> cand_max, cand_sum;
-  took_from.reserve(budget);
-  cand_max.reserve(budget);
-  cand_sum.reserve(budget);
+  int64_t waiting = 0;
+  for (int32_t e = 0; e < n_entries; ++e) waiting += entries[e].n_new;
+  const size_t most = static_cast<size_t>(waiting < budget ? waiting : budget);   // tokens the loop can take
+  took_from.reserve(most);
+  cand_max.reserve(most);
+  cand_sum.reserve(most);
   int64_t sum = 0, mx = 0;
   for (int32_t r = 0; r < R; ++r) { sum += L[r]; if (r == 0 || L[r] > mx) mx = L[r]; }
   while (static_cast<int32_t>(took_from.size()) < budget) {
@@ -109,4 +113,16 @@ extern "C" fs_status fs_schedule_prefill(int32_t n_ranks, int32_t budget, int32_
   for (int32_t r = 0; r < R; ++r) load[r] = L[r];
   *n_tokens = best + 1;
   return FS_OK;
+}
+}  // namespace
+
+extern "C" fs_status fs_schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens,
+                                         const fs_prefill_entry* entries, int32_t n_entries,
+                                         const int64_t* init_load, int32_t* take, int64_t* load,
+                                         int32_t* n_tokens) {
+  try {   // nothing may throw across the C boundary
+    return schedule_prefill(n_ranks, budget, min_tokens, entries, n_entries, init_load, take, load, n_tokens);
+  } catch (const std::bad_alloc&) {
+    return fs::fail(FS_ECAPACITY, "fs_schedule_prefill: out of host memory for a budget of %d tokens", budget);
+  }
 }
