@@ -6,6 +6,7 @@
 // least-loaded rank that still has schedulable tokens, then picks the best of the batches
 // it passed through.  What the paper leaves open (the token cost, the choice among the
 // candidates, the unused workload input) is fixed as the header states.
+#include <cstddef>
 #include <new>
 #include <vector>
 
