@@ -234,7 +234,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
   }
 
   // ---- global -> registers: this wavefront's couples of pair jp ---------------------------------
-  auto fetch = [&](InFlight<NP>& r, int jp) {
+  auto fetch = [&](InFlight<NP>& r, int jp) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
@@ -250,7 +250,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
     }
   };
   // ---- registers -> LDS stage s ------------------------------------------------------------------
-  auto deposit = [&](int s, const InFlight<NP>& r, int jp) {
+  auto deposit = [&](int s, const InFlight<NP>& r, int jp) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
@@ -266,7 +266,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
     }
   };
   // ---- one page pair from LDS stage s against this wavefront's column tiles -----------------------
-  auto compute = [&](int s, int jp) {
+  auto compute = [&](int s, int jp) __attribute__((always_inline)) {
     if (!wave_live) return;
     const int t0 = it.kv_begin + 32 * jp;                 // first token of the pair
     bool need[CT], full[CT];
