@@ -24,6 +24,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <type_traits>
 
 #include "fs_internal.h"
 
@@ -288,10 +289,17 @@ __device__ __forceinline__ void cvt16(const u32x4 raw, float (&f)[16]) {
   }
 }
 
+// Sum over the 8 lanes that share a token row (lanes 8k .. 8k+7), left in all of them: two quad
+// permutes and a half-row mirror, all as DPP operands of the add (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_read(float v) {
+  return __uint_as_float(static_cast<uint32_t>(
+      __builtin_amdgcn_update_dpp(0, static_cast<int>(__float_as_uint(v)), CTRL, 0xF, 0xF, true)));
+}
 __device__ __forceinline__ float sum_over_8_lanes(float v) {
-  v += __shfl_xor(v, 1, 64);
-  v += __shfl_xor(v, 2, 64);
-  v += __shfl_xor(v, 4, 64);
+  v += dpp_read<0xB1>(v);     // quad_perm [1,0,3,2]: lane ^ 1
+  v += dpp_read<0x4E>(v);     // quad_perm [2,3,0,1]: lane ^ 2
+  v += dpp_read<0x141>(v);    // row_half_mirror: lane i of a group of 8 reads lane 7 - i, the other quad
   return v;
 }
 
@@ -361,49 +369,74 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
     for (int i = 0; i < 16; ++i) o[g][i] = 0.f;
   }
 
+  // One page against the q rows of this lane's token subsets.  FULL: all 16 tokens exist (every page
+  // but the last of an item), so nothing is masked.  The exponentials are taken against a reference
+  // max m[g] that moves up to a token's score only when that lies more than 2^8 above it (always on a
+  // subset's first token, where m is -inf; rarely afterwards), so the 17 rescale multiplies leave the
+  // common path; weights stay below 2^8, which costs the fp32 sums nothing.
+  auto consume = [&](const Fp8Page& pg, int valid, auto full_tag) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {          // token ts + 8h of this page
+      const bool live = FULL || ts + 8 * h < valid;
+      float kf[16], vf[16];
+      cvt16(pg.k[h], kf);
+      cvt16(pg.v[h], vf);
+      if (!FULL) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) vf[e] = live ? vf[e] : 0.f;   // whatever bits sit there must not reach the sum
+      }
+#pragma unroll
+      for (int g = 0; g < GMAX; ++g) {
+        if (g < G) {
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) dot = fmaf(qf[g][e], kf[e], dot);
+          float x = sum_over_8_lanes(dot) * pg.ks;
+          if (!FULL) x = live ? x : -INFINITY;
+          const bool move = x > m[g] + 8.0f;
+          if (__any(move)) {
+            const float alpha = move ? __builtin_amdgcn_exp2f(m[g] - x) : 1.0f;   // m = -inf: exp2(-inf) = 0
+            l[g] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[g][e] *= alpha;
+            m[g] = move ? x : m[g];
+          }
+          // a subset that has seen no live token yet keeps its state at zero (m = -inf, x = -inf)
+          const float m_ref = (!FULL && m[g] == -INFINITY) ? 0.f : m[g];
+          const float p = __builtin_amdgcn_exp2f(x - m_ref);
+          l[g] += p;
+          const float pv = p * pg.vs;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[g][e] = fmaf(pv, vf[e], o[g][e]);
+        }
+      }
+    }
+  };
+
+  // NBUF register buffers; NBUF-1 pages are in flight while one is consumed.  The steady-state loop is
+  // branch-free (every prefetch is in range, every page is full); the ragged end is a second loop.
   Fp8Page buf[NBUF];
 #pragma unroll
   for (int u = 0; u < NBUF - 1; ++u)
     if (p0 + u < p1) load_page_fp8(buf[u], P, ids[p0 + u], lane);
-  int32_t slot_next = (p0 + NBUF - 1 < p1) ? ids[p0 + NBUF - 1] : 0;
 
-  for (int i = p0; i < p1; i += NBUF) {
+  int i = p0;
+  for (; i + 2 * NBUF - 2 < p1; i += NBUF) {
 #pragma unroll
     for (int u = 0; u < NBUF; ++u) {
-      const int pi = i + u;
-      if (pi < p1) {
-        const int pn = pi + NBUF - 1;
-        if (pn < p1) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, slot_next, lane);
-        slot_next = (pn + 1 < p1) ? ids[pn + 1] : 0;
-        const Fp8Page& pg = buf[u];
-        const int valid = min(fs::kPageTokens, n_tok - pi * fs::kPageTokens);
+      load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[i + u + NBUF - 1], lane);
+      consume(buf[u], fs::kPageTokens, std::true_type{});
+    }
+  }
+  // here pages i .. i+NBUF-2 (those below p1) are in flight in buf[0 .. NBUF-2]
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {          // token ts + 8h of this page
-          const bool live = ts + 8 * h < valid;
-          float kf[16], vf[16];
-          cvt16(pg.k[h], kf);
-          cvt16(pg.v[h], vf);
-#pragma unroll
-          for (int g = 0; g < GMAX; ++g) {
-            if (g < G) {
-              float dot = 0.f;
-#pragma unroll
-              for (int e = 0; e < 16; ++e) dot = fmaf(qf[g][e], kf[e], dot);
-              float x = sum_over_8_lanes(dot) * pg.ks;
-              x = live ? x : -INFINITY;
-              const float m_new = fmaxf(m[g], x);
-              // m_new = -inf only while this subset has seen no live token; keep the state at zero then
-              const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m[g] - m_new);
-              const float p = live ? __builtin_amdgcn_exp2f(x - m_new) : 0.f;
-              l[g] = l[g] * alpha + p;
-              const float pv = p * pg.vs;
-#pragma unroll
-              for (int e = 0; e < 16; ++e) o[g][e] = fmaf(o[g][e], alpha, live ? pv * vf[e] : 0.f);
-              m[g] = m_new;
-            }
-          }
-        }
-      }
+  for (int u = 0; u < 2 * NBUF - 2; ++u) {
+    const int pi = i + u;
+    if (pi < p1) {
+      const int pn = pi + NBUF - 1;
+      if (pn < p1) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[pn], lane);
+      consume(buf[u % NBUF], min(fs::kPageTokens, n_tok - pi * fs::kPageTokens), std::false_type{});
     }
   }
 
