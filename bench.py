@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # (see profiles/); None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
     "cfg2_rank0": 1972222620,    # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt
-    "cfg4_rank0": 1608679089,    # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
+    "cfg4_rank0": 1609662362,    # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
 }
 
 
