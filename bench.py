@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
 # (see profiles/); None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_rank0": 1972222620,    # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt
+    "cfg2_rank0": 1971483318,    # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
     "cfg4_rank0": 1609662362,    # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
 }
 
@@ -47,6 +47,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying HIP graphs")
+    ap.add_argument("--classic", action="store_true",
+                    help="bf16: one workgroup per item (fs_decode_attention) even for long lists")
+    ap.add_argument("--persistent", action="store_true",
+                    help="bf16: the persistent form of the sweep (fs_decode_attention_persistent: workgroups claim items, "
+                         "partial rows leave in bursts) even for short lists; by default it is used from 1024 items on")
     ap.add_argument("--placement", choices=["requests", "heads"], default="requests",
                     help="requests: the batch's TP/DP mix per request; heads: the paper's head-level hybrid (layer 0)")
     ap.add_argument("--cold", action="store_true", help="also time the kernels with L2 and the memory-side cache scrubbed before every launch")
@@ -136,10 +141,11 @@ def main() -> int:
     off_items = 0
     off_sched = up(off_items + n_items * 32)
     off_indptr = up(off_sched + n_items * 4)
-    blob_bytes = up(off_indptr + (n_pairs + 1) * 8)
+    off_claim = up(off_indptr + (n_pairs + 1) * 8)           # one zero int32: the persistent sweep's item counter
+    blob_bytes = up(off_claim + 4)
     N_SLOTS = 4
     dev_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, device=dev) for _ in range(N_SLOTS)]
-    host_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(N_SLOTS)]
+    host_blobs = [torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(N_SLOTS)]   # zeros: the counter word
     slot_done = [torch.cuda.Event() for _ in range(N_SLOTS)]     # the step that last used this slot finished
     host_views = []
     for hb in host_blobs:
@@ -167,12 +173,20 @@ def main() -> int:
         call_place = fs.bind_build_placement(shape, ctx_c, mode_c, owner_buf, dp_buf, load_buf)
     call_list = [fs.bind_build_worklist(shape, ctx_c, owner_buf, args.rank, chunk, *hv) for hv in host_views]
 
+    # The persistent form pays off once every workgroup walks several items (it saves the scattered stores
+    # and the relaunches); with one item or fewer per workgroup slot it is the same work plus a counter.
+    persistent = w["kv_dtype"] == "bf16" and not args.classic and (args.persistent or n_items >= 1024)
+
     def bind_gpu_calls(stream_ptr):
         dec, mrg = [], []
         for db in dev_blobs:
             base = db.data_ptr()
-            dec.append(fs.bind_decode_attention(shape, ds.view, base + off_items, base + off_sched, n_items,
-                                                part_o, part_lse, stream_ptr))
+            if persistent:
+                dec.append(fs.bind_decode_attention_persistent(shape, ds.view, base + off_items, base + off_sched,
+                                                               n_items, base + off_claim, part_o, part_lse, stream_ptr))
+            else:
+                dec.append(fs.bind_decode_attention(shape, ds.view, base + off_items, base + off_sched, n_items,
+                                                    part_o, part_lse, stream_ptr))
             mrg.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"],
                                          out, lse, stream_ptr))
         return dec, mrg
@@ -248,6 +262,8 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    build_host(0)                                           # the timed loop counts from 0 again: its first blob,
+    dev_blobs[0].copy_(host_blobs[0], non_blocking=True)    # with the item counter at zero
     host_us.clear(); wait_us.clear(); enqueue_us.clear()
     timed = [i for i in range(args.steps) if graphs is None or i % EVENT_EVERY == 0]
     events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(2)] for i in timed}
@@ -269,6 +285,7 @@ def main() -> int:
         torch.cuda.synchronize()
         g_out, g_lse = out.clone(), lse.clone()
         out.fill_(float("nan")); lse.fill_(float("nan"))
+        dev_blobs[0].copy_(host_blobs[0], non_blocking=True)      # the list again, with its item counter at zero
         enqueue_eager(0)
         torch.cuda.synchronize()
         if not (torch.equal(g_out, out) and torch.equal(g_lse, lse)):
@@ -315,6 +332,7 @@ def main() -> int:
         dts, mts = [], []
         for _ in range(20):
             fs.fs_stream_read_probe(scrub, scrub.numel(), sink2, sptr)
+            dev_blobs[0].copy_(host_blobs[0], non_blocking=True)  # the list with its item counter at zero
             c0, c1, c2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
             c0.record(stream)
             call_decode[0]()
@@ -340,12 +358,12 @@ def main() -> int:
             ds_k = DeviceShare(shape, q_bits, kv_k, w["sm_scale"], interleave_kv=not args.separate_kv)
             ds_k.set_worklist(it_k, pr_k, sc_k, ip_k)
             for _ in range(5):
-                ds_k.run()
+                ds_k.run(persistent=persistent)
             r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             reps = 30
             r0.record(stream)
             for _ in range(reps):
-                ds_k.run()
+                ds_k.run(persistent=persistent)
             r1.record(stream)
             torch.cuda.synchronize()
             us = r0.elapsed_time(r1) * 1e3 / reps
@@ -395,6 +413,7 @@ def main() -> int:
                                + (", head-level hybrid placement" if args.placement == "heads" else ""),
                    "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
+                   "sweep": "persistent (fs_decode_attention_persistent)" if persistent else "one workgroup per item (fs_decode_attention)",
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),
                    "kv_layout": "separate" if args.separate_kv else "interleaved",
@@ -410,7 +429,8 @@ def main() -> int:
                              "enqueue_avg": round(float(np.mean(enqueue_us)), 1),
                              "wait_for_gpu_avg": round(float(np.mean(wait_us)), 1)},
         "stream_read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
-        "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else "decode_bf16_kernel",
+        "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else
+                     ("decode_bf16_persistent_kernel" if persistent else "decode_bf16_kernel"),
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "algorithmic_bytes_per_launch": decode_bytes,

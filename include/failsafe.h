@@ -342,6 +342,23 @@ FS_API fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv
                               int64_t n_items, float* part_o, float* part_lse, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * fs_decode_attention_persistent - the same computation and the same outputs as
+ * fs_decode_attention for bf16 K/V, by a fixed set of workgroups (two per CU) that
+ * claim items from a counter in list order and write their partial rows in bursts
+ * (decode phase, Section 2.1.1; the ragged list of Section 3.1).
+ *
+ *  claim_dev  DEVICE in/out  one int32, 4-byte aligned; must be 0 when the launch
+ *             starts (e.g. uploaded together with the list) and is left non-zero.
+ *             Two launches that overlap in time need two counters.
+ *
+ * Everything else as for fs_decode_attention.  FS_EUNSUPPORTED: fp8 K/V.
+ */
+FS_API fs_status fs_decode_attention_persistent(const fs_shape* shape, const fs_kv_view* kv,
+                                                const fs_work_item* items_dev, const int32_t* sched_dev,
+                                                int64_t n_items, int32_t* claim_dev, float* part_o,
+                                                float* part_lse, void* stream);
+
+/* ---------------------------------------------------------------------------
  * fs_merge_lse - combine the chunk partials of each pair (split-K merge):
  *     lse = ln sum_c exp(lse_c),   out = sum_c exp(lse_c - lse) * o_c
  * Rows [p*G, p*G+G) of out/lse belong to pair p; its partial rows are

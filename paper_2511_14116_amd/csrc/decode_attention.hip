@@ -23,6 +23,7 @@
 // one q-head per KV head there is no dense contraction to give the matrix cores.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <type_traits>
 
@@ -272,6 +273,194 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
 }
 
 // ---------------------------------------------------------------------------------------------
+// Persistent form of the bf16 sweep.  A fixed set of workgroups (two per CU) walks the list: the
+// first gridDim.x items go one to each workgroup, every further item is claimed from a counter
+// in the list's longest-first order at the moment a workgroup has streamed its current item
+// (list scheduling, as the hardware dispatcher does for one workgroup per item).  Finished
+// partial rows wait in LDS and leave in one burst when the staging area is full or the
+// workgroup is done: writes scattered through the launch slow the read stream far more than
+// their bytes explain, writes at the end of a workgroup's life mostly do not.  The next item's
+// descriptor, query rows and first pages are fetched while the current item's rows are merged,
+// and the barriers around that merge wait for LDS traffic only, so those loads stay in flight
+// across them.
+// ---------------------------------------------------------------------------------------------
+
+constexpr int kStageRows = 64;    // partial rows a workgroup keeps in LDS before it writes them (64 x 512 B)
+
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// The page table is read-only for the whole launch, but the persistent kernel also writes to global
+// memory inside its item loop, so the compiler no longer takes its word for that and would fetch the
+// page ids with vector loads, which queue up behind the page loads.  Reading them through the
+// constant address space keeps them on the scalar path.
+typedef const int32_t __attribute__((address_space(4))) * const_ids_ptr;
+
+struct ItemDesc {
+  const_ids_ptr ids;    // page ids of the item's first page onwards
+  int n_tok;            // tokens of the item
+  int p0, p1;           // this wavefront's pages [p0, p1) of the item
+  int part_row;
+  bf16x8 q[4];          // Q^T operand of this lane
+  bool valid;
+};
+
+template <int WAVES>
+__device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int n_items, int wave, int lane, int G) {
+  ItemDesc d;
+  d.valid = k < n_items;
+  d.ids = (const_ids_ptr)(uintptr_t)0;
+  d.n_tok = 0;
+  d.p0 = d.p1 = 0;
+  d.part_row = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) d.q[c] = bf16x8{};
+  if (d.valid) {
+    // k is the same in every lane (it comes from LDS, which the compiler cannot see): saying so keeps the
+    // descriptor and, above all, the page ids on the scalar path, where their loads do not queue up behind
+    // the page loads
+    const int item_idx = __builtin_amdgcn_readfirstlane(P.sched ? P.sched[k] : k);
+    fs_work_item it = P.items[item_idx];
+    it.pair = __builtin_amdgcn_readfirstlane(it.pair);
+    it.tok_begin = __builtin_amdgcn_readfirstlane(it.tok_begin);
+    it.tok_end = __builtin_amdgcn_readfirstlane(it.tok_end);
+    it.q_row = __builtin_amdgcn_readfirstlane(it.q_row);
+    it.part_row = __builtin_amdgcn_readfirstlane(it.part_row);
+    d.n_tok = it.tok_end - it.tok_begin;
+    const int n_pages = (d.n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
+    const int64_t first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+    const int32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page));
+    const int32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page >> 32));
+    d.ids = (const_ids_ptr)(reinterpret_cast<uintptr_t>(P.page_ids + ((static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo))));
+    const int per = (n_pages + WAVES - 1) / WAVES;
+    d.p0 = wave * per;
+    d.p1 = min(n_pages, d.p0 + per);
+    d.part_row = it.part_row;
+    const int qi = lane & 15, kb = lane >> 4;
+    const int qrow = it.q_row + min(qi, G - 1);
+    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      u32x4 v = qp[4 * c];
+      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
+      d.q[c] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+  return d;
+}
+
+template <int WAVES, int NBUF>
+__global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(const DecodeParams P, int n_items,
+                                                                            int* __restrict__ claim) {
+  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
+  __shared__ float sm_m[WAVES * 16];
+  __shared__ float sm_l[WAVES * 16];
+  __shared__ __attribute__((aligned(16))) float st_o[kStageRows * fs::kHeadDim];
+  __shared__ float st_lse[kStageRows];
+  __shared__ int st_row[kStageRows];
+  __shared__ int s_next;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qi = lane & 15, kb = lane >> 4;
+  const int G = P.group;
+  const int n_groups = gridDim.x;
+
+  ItemDesc cur = load_desc<WAVES>(P, blockIdx.x, n_items, wave, lane, G);   // blockIdx.x < n_items by the launch
+
+  PageRegs buf[NBUF];
+  auto prologue = [&](const ItemDesc& d) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u)
+      if (d.p0 + u < d.p1) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.ids[d.p0 + u], lane);
+  };
+  prologue(cur);
+
+  int staged = 0;
+  for (;;) {
+    SoftmaxState st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    int i = cur.p0;
+    for (; i + 2 * NBUF - 2 < cur.p1; i += NBUF) {
+#pragma unroll
+      for (int u = 0; u < NBUF; ++u) {
+        load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[i + u + NBUF - 1], lane);
+        consume_page<true>(st, buf[u], cur.q, P.scale_log2, fs::kPageTokens, kb);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * NBUF - 2; ++u) {
+      const int pi = i + u;
+      if (pi < cur.p1) {
+        const int pn = pi + NBUF - 1;
+        if (pn < cur.p1) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[pn], lane);
+        consume_page<false>(st, buf[u % NBUF], cur.q, P.scale_log2, min(fs::kPageTokens, cur.n_tok - pi * fs::kPageTokens), kb);
+      }
+    }
+    // merge the wavefronts through LDS into the staging rows
+    const float l_total = sum_xor32(sum_xor16(st.l));
+    if (lane < 16) {
+      sm_m[wave * 16 + lane] = st.m;
+      sm_l[wave * 16 + lane] = l_total;
+    }
+    {
+      float* row = sm_o + (wave * 16 + qi) * kORow + 4 * kb;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + 16 * j) = st.acc[j];
+    }
+    // The next item is claimed only now.  Claiming it earlier would hide the counter's round trip, but a
+    // workgroup would then sit on an item another could have started: claiming at the start of the current
+    // item cost 11 us of the launch on the 70B-shaped batch, two items ahead 20 us, four pages early 4 us.
+    if (threadIdx.x == 0) s_next = atomicAdd(claim, 1) + n_groups;
+    lds_barrier();
+    // every page of the current item is consumed: fetch the next item's descriptor and first pages now,
+    // so that they travel while the rows are merged
+    ItemDesc nxt = load_desc<WAVES>(P, __builtin_amdgcn_readfirstlane(s_next), n_items, wave, lane, G);
+    prologue(nxt);
+    for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
+      const int q = idx >> 5, d4 = idx & 31;
+      float M = sm_m[q];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sm_m[w * 16 + q]);
+      float L = 0.f;
+      f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) {
+        const float wgt = __builtin_amdgcn_exp2f(sm_m[w * 16 + q] - M);   // a wave with no pages has m = -inf
+        L += wgt * sm_l[w * 16 + q];
+        o += wgt * *reinterpret_cast<const f32x4*>(sm_o + (w * 16 + q) * kORow + 4 * d4);
+      }
+      const float inv = 1.0f / L;
+      *reinterpret_cast<f32x4*>(st_o + (staged + q) * fs::kHeadDim + 4 * d4) = o * inv;
+      if (d4 == 0) {
+        st_lse[staged + q] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+        st_row[staged + q] = cur.part_row + q;
+      }
+    }
+    staged += G;
+    lds_barrier();                     // staging rows complete; the merge buffers may be reused
+    const bool last = !nxt.valid;
+    if (last || staged + G > kStageRows) {
+      for (int idx = threadIdx.x; idx < staged * 32; idx += WAVES * 64) {
+        const int r = idx >> 5, d4 = idx & 31;
+        __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(st_o + r * fs::kHeadDim + 4 * d4),
+                                    reinterpret_cast<f32x4*>(P.part_o + static_cast<int64_t>(st_row[r]) * fs::kHeadDim + 4 * d4));
+      }
+      for (int r = threadIdx.x; r < staged; r += WAVES * 64) __builtin_nontemporal_store(st_lse[r], P.part_lse + st_row[r]);
+      staged = 0;
+      // the next write into the staging rows comes after the next item's first barrier, which every
+      // thread reaches only when it is done reading them here
+    }
+    if (last) break;
+    cur = nxt;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // fp8 e4m3 path.  Slots are token-major (128 bytes per token).  Lane (c = lane%8, ts = lane/8)
 // owns d in [16c, 16c+16) and the tokens ts and ts+8 of every page, so one wave-wide 16-byte
 // load covers eight whole token rows (1 KiB contiguous).  The 8 lanes of a token row add their
@@ -482,6 +671,69 @@ fs_status launch(K kernel, int threads, const DecodeParams& P, int64_t n_items, 
 }
 
 }  // namespace
+
+extern "C" fs_status fs_decode_attention_persistent(const fs_shape* shape, const fs_kv_view* kv,
+                                                    const fs_work_item* items_dev, const int32_t* sched_dev,
+                                                    int64_t n_items, int32_t* claim_dev, float* part_o,
+                                                    float* part_lse, void* stream) {
+  if (!shape || !kv) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: shape or kv is NULL");
+  if (shape->n_kv_heads < 1 || shape->n_q_heads < shape->n_kv_heads || shape->n_q_heads % shape->n_kv_heads)
+    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: n_q_heads %d is not a multiple of n_kv_heads %d",
+                    shape->n_q_heads, shape->n_kv_heads);
+  if (shape->head_dim != fs::kHeadDim || shape->page_tokens != fs::kPageTokens)
+    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention_persistent: head_dim %d, page_tokens %d (only %d and %d are built)",
+                    shape->head_dim, shape->page_tokens, fs::kHeadDim, fs::kPageTokens);
+  const int G = shape->n_q_heads / shape->n_kv_heads;
+  if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: group %d > %d", G, fs::kMaxGroup);
+  if (kv->kv_dtype != FS_KV_BF16)
+    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention_persistent: only bf16 K/V is built (kv_dtype %d)", kv->kv_dtype);
+  if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: n_items out of range");
+  if (n_items == 0) return FS_OK;
+  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev || !claim_dev || !part_o ||
+      !part_lse)
+    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: NULL device pointer");
+  const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * 2;
+  if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
+      (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
+      (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
+      (reinterpret_cast<uintptr_t>(part_o) & 15) || (reinterpret_cast<uintptr_t>(claim_dev) & 3))
+    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: pools, strides, q and part_o must be 16-byte aligned, "
+                               "strides at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
+  if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: sm_scale is not finite");
+  // CU count of the current device, asked once per device (the query is a runtime call on the launch path)
+  static int cu_of_device[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    return fs::fail(FS_EHIP, "fs_decode_attention_persistent: cannot identify the current device");
+  int n_cu = cu_of_device[dev];
+  if (n_cu == 0) {
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+      return fs::fail(FS_EHIP, "fs_decode_attention_persistent: cannot read the device's CU count");
+    cu_of_device[dev] = n_cu;      // racing first calls write the same value
+  }
+  DecodeParams P;
+  P.q = static_cast<const uint16_t*>(kv->q);
+  P.k_pool = static_cast<const char*>(kv->k_pool);
+  P.v_pool = static_cast<const char*>(kv->v_pool);
+  P.k_stride = kv->k_slot_stride;
+  P.v_stride = kv->v_slot_stride;
+  P.k_scale = nullptr;
+  P.v_scale = nullptr;
+  P.page_indptr = kv->page_indptr;
+  P.page_ids = kv->page_ids;
+  P.items = items_dev;
+  P.sched = sched_dev;
+  P.part_o = part_o;
+  P.part_lse = part_lse;
+  P.group = G;
+  P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
+  const int64_t groups = std::min<int64_t>(n_items, 2ll * n_cu);      // two resident workgroups per CU
+  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3>), dim3(static_cast<unsigned>(groups)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), P, static_cast<int>(n_items), claim_dev);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_decode_attention_persistent: launch failed: %s", hipGetErrorString(e));
+  return FS_OK;
+}
 
 extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv,
                                          const fs_work_item* items_dev, const int32_t* sched_dev,

@@ -74,12 +74,24 @@ class DeviceShare:
         B.fs_decode_attention(self.shape, self.view, self.items, self.sched if use_sched else None,
                               self.n_items, self.part_o, self.part_lse, torch.cuda.current_stream().cuda_stream)
 
+    def decode_persistent(self, use_sched: bool = True):
+        """The same partials by the persistent form of the sweep (bf16 K/V only)."""
+        if not hasattr(self, "claim"):
+            self.claim = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.claim.zero_()
+        B.fs_decode_attention_persistent(self.shape, self.view, self.items, self.sched if use_sched else None,
+                                         self.n_items, self.claim, self.part_o, self.part_lse,
+                                         torch.cuda.current_stream().cuda_stream)
+
     def merge(self):
         B.fs_merge_lse(self.part_o, self.part_lse, self.chunk_indptr, self.n_pairs, self.group,
                        self.shape.head_dim, self.out, self.lse, torch.cuda.current_stream().cuda_stream)
 
-    def run(self, use_sched: bool = True):
-        self.decode(use_sched)
+    def run(self, use_sched: bool = True, persistent: bool = False):
+        if persistent:
+            self.decode_persistent(use_sched)
+        else:
+            self.decode(use_sched)
         self.merge()
 
     # ---- chunked prefill: same Q / pool / page-table plumbing, another list and output shape ----

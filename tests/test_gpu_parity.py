@@ -376,3 +376,45 @@ def test_head_level_hybrid_every_rank_and_reassembly():
     kv_all = make_kv_pool(w["seed"], all_pairs, w["ctx_len"])
     un_o, un_l = oracle.unsharded_attention(q, kv_all, w["ctx_len"], Hq, Hkv, w["sm_scale"])
     check(full_o, full_l, un_o, un_l, "head-level hybrid, all ranks gathered vs unsharded")
+
+
+def test_persistent_sweep_small_batches_against_oracle():
+    """The persistent form of the sweep: every rank of the tiny batch and a ragged split-K batch,
+    element by element against the oracle, and bit for bit against the one-workgroup-per-item form
+    (same wavefront split, same page order, same merge)."""
+    say("persistent sweep, small batches")
+    for cfg_id, kw, chunk in ((0, {}, 0), (0, {}, 64), (1, dict(n_req=48, max_len=3000), 256)):
+        w = make_requests(cfg_id, **kw)
+        q = make_q(w["seed"], w["n_req"], w["n_q_heads"], 128)
+        owner, dp, load = fs.fs_build_placement(shape_of(w), w["ctx_len"], w["mode"])
+        for rank in range(w["n_ranks"]):
+            ds, kv, items, pairs, sched, indptr = run_rank(w, q, rank, chunk, owner)
+            if len(items) == 0:
+                continue
+            ref_part_o, ref_part_l = ds.part_o.clone(), ds.part_lse.clone()
+            ds.part_o.fill_(float("nan")); ds.part_lse.fill_(float("nan"))
+            ds.out.fill_(float("nan")); ds.lse.fill_(float("nan"))
+            ds.decode_persistent()
+            ds.merge()
+            torch.cuda.synchronize()
+            assert torch.equal(ds.part_o, ref_part_o) and torch.equal(ds.part_lse, ref_part_l)
+            ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
+            check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l,
+                  f"persistent cfg{cfg_id} chunk={chunk} rank {rank} ({len(items)} items)")
+            # a second launch on the same counter without clearing it must be refused by nothing: the
+            # binding clears it; launching twice in a row gives the same bits
+            ds.decode_persistent()
+            torch.cuda.synchronize()
+            assert torch.equal(ds.part_o, ref_part_o)
+
+
+def test_persistent_sweep_config2_full_size():
+    say("persistent sweep, config 2 full size")
+    ds = _full_config(2, 0, 4)            # the regular form, sampled against the oracle
+    ref_out, ref_lse = ds.out.clone(), ds.lse.clone()
+    ds.out.fill_(float("nan")); ds.lse.fill_(float("nan"))
+    ds.part_o.fill_(float("nan")); ds.part_lse.fill_(float("nan"))
+    ds.decode_persistent()
+    ds.merge()
+    torch.cuda.synchronize()
+    assert torch.equal(ds.out, ref_out) and torch.equal(ds.lse, ref_lse)
