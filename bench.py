@@ -61,6 +61,8 @@ def main() -> int:
                     help="decode: the measured decode-attention share (default); prefill: the chunked-prefill attention share")
     ap.add_argument("--prefill-waves", type=int, default=None)
     ap.add_argument("--prefill-col-tiles", type=int, default=None)
+    ap.add_argument("--prefill-wide-v", action="store_true",
+                    help="prefill: keep V in bf16 and feed the weights as bf16 hi + lo (for values beyond fp16's range)")
     ap.add_argument("--prefill-budget", type=int, default=8192, help="prefill path: token budget of the batch")
     ap.add_argument("--prefill-queue", type=int, default=64, help="prefill path: waiting prompts")
     args = ap.parse_args()

@@ -488,7 +488,12 @@ FS_API fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* k
 FS_API fs_status fs_stream_read_probe(const void* buf_dev, int64_t bytes, void* sink_dev, void* stream);
 
 /* Launch-shape knobs for measurement sweeps ("waves_per_group" in {1,2,4}, "prefetch_pages" in [1,3],
- * "prefill_col_tiles" in {1,2,4}, "prefill_waves" in {4,8}; the pair (8,4) has no kernel).
+ * "prefill_col_tiles" in {1,2,4}, "prefill_waves" in {4,8}; the pair (8,4) has no kernel), and one
+ * numeric switch: "prefill_wide_v" in {0,1}.  With 0 (default) fs_prefill_attention multiplies fp16
+ * weights with V converted to fp16 on its way into LDS: exact for |v| in [2^-14, 65504], |v| above
+ * 65504 counts as 65504, smaller magnitudes land on fp16's subnormal grid (absolute error < 2^-24).
+ * With 1, V stays bf16 and the weights enter as bf16 hi + lo (two products, ~20% slower), for caches
+ * whose values leave fp16's range.
  * Unknown key or a value outside the documented range: FS_EINVAL, nothing changes. */
 FS_API fs_status fs_set_option(const char* key, int32_t value);
 FS_API int32_t   fs_get_option(const char* key);   /* -1 for an unknown key */

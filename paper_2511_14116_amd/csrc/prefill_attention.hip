@@ -18,7 +18,9 @@
 //         S^T[tok][row] = K . Q^T        2 x 4 v_mfma_f32_16x16x32_bf16
 //     then the V operands and, per column tile, the online softmax (fp32, log2 domain, causal
 //     mask only on the pairs that straddle a row's position) and
-//         O^T[d][row]  += V^T . P^T      8 x v_mfma_f32_16x16x32_bf16 over the 32 tokens, P as bf16 hi + lo.
+//         O^T[d][row]  += V^T . P^T      8 x v_mfma_f32_16x16x32_f16 over the 32 tokens: the weights as fp16,
+//                                         V converted bf16 -> fp16 on its way into LDS (or, option
+//                                         "prefill_wide_v", V as bf16 and the weights as bf16 hi + lo).
 // The S^T accumulators of the two pages are, lane by lane, the 8 reduction elements the second
 // product wants from P^T (4 tokens of the first page, the same 4 of the second); the copy into
 // LDS pairs the V rows of the two pages the same way, so nothing crosses lanes except the
@@ -36,6 +38,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 struct PrefillParams {
   const uint16_t* __restrict__ q;
@@ -93,6 +97,7 @@ __device__ __forceinline__ float max2(float a, float b) {
 
 struct TileState {
   float m;          // reference max (log2 domain) of this lane's query row: within 2^8 below the true running max
+  float neg_ref;    // -m, or -0 while the row has seen no key (m = -inf)
   f32x4 l;          // running sum of the row's weights, element 0 (kept on the matrix cores: a row of ones above V^T)
   f32x4 acc[8];     // O^T[d = 16b + 4*(lane/16) + r][row = lane%16]
 };
@@ -102,11 +107,16 @@ constexpr float kLazy = 8.0f;   // the reference max follows the running max onl
 // Online softmax of one column tile over one page pair and its share of O^T += V^T . P^T.
 // sa/sb: raw scores of the tile against the two pages (this lane: tokens t0 + 4kb + r and
 // t0 + 16 + 4kb + r).  mask: some of the 32 tokens lie beyond some row's position `pos`.
+// WIDE = false: the weights and the V operands enter the second product as fp16 (V is converted on its
+// way into LDS, exactly for magnitudes from 2^-14 to 65504; smaller ones land on fp16's subnormal grid,
+// larger ones enter as +-65504).  WIDE = true: V stays bf16 and the weights go in as bf16 hi + lo, two
+// products, for caches whose values leave fp16's range.
+template <bool WIDE>
 __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const f32x4 sb, const u32x4 (&va)[4],
                                            const u32x4 (&vb)[4], float scale_log2, int t0, int pos, int kb,
                                            bool mask) {
-  // no fused multiply-add here: a row's top key must get exp2(0) = 1 exactly, which needs the scaled
-  // score rounded the same way on both sides of the subtraction
+  // no fused multiply-add on the wide path: there a row's top key must get exp2(0) = 1 exactly, which needs
+  // the scaled score rounded the same way on both sides of the subtraction
 #pragma clang fp contract(off)
   f32x8 s = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
   if (mask) {   // wave-uniform; kept a real branch (the empty asm stops the compiler from turning it into 16 selects on every step)
@@ -117,9 +127,16 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
       if (t0 + 16 + 4 * kb + r > pos) s[4 + r] = -INFINITY;
     }
   }
-  // the softmax scale is positive, so the max of the raw scores is the max of the scaled ones
-  float mx = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max2(s[6], s[7]));
-  {
+  // Lazy reference max: the exponentials are taken against st.m, which moves up to the row's max only
+  // when that lies more than 2^8 above it (always on a row's first visible keys, where st.m is -inf, so
+  // a row's first top key still gets exactly 1; rarely afterwards).  Weights stay below 2^8, which costs
+  // fp32 sums and 16-bit weights no precision, and the rescale multiplies leave the common path.  The
+  // common path does not even form the row's max: every lane checks its own 8 scores (the softmax scale
+  // is positive, so the max of the raw scores is the max of the scaled ones), and only if some lane of the
+  // wavefront is out of range are the four lanes of each row combined.
+  const float mx_lane = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max2(s[6], s[7]));
+  if (__any(mx_lane * scale_log2 > st.m + kLazy)) {
+    float mx = mx_lane;
     const unsigned u = __float_as_uint(mx);
     const auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
     const unsigned a = r16[0], b = r16[1];
@@ -128,13 +145,7 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     const auto r32 = __builtin_amdgcn_permlane32_swap(v, v, false, false);
     const unsigned c = r32[0], d = r32[1];
     mx = max2(__uint_as_float(c), __uint_as_float(d)) * scale_log2;
-  }
-  // Lazy reference max: the exponentials are taken against st.m, which moves up to the block's max only
-  // when that lies more than 2^8 above it (always on a row's first visible keys, where st.m is -inf, so
-  // a row's first top key still gets exactly 1; rarely afterwards).  Weights stay below 2^8, which costs
-  // fp32 sums and the bf16 hi/lo pair no precision, and the 33 rescale multiplies leave the common path.
-  const bool move = mx > st.m + kLazy;
-  if (__any(move)) {
+    const bool move = mx > st.m + kLazy;
     const float alpha = move ? __builtin_amdgcn_exp2f(st.m - mx) : 1.0f;   // st.m = -inf: exp2(-inf) = 0
     FS_SCALE_IN_PLACE(st.l, 0, alpha);
 #pragma unroll
@@ -145,44 +156,78 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
       FS_SCALE_IN_PLACE(st.acc[j], 3, alpha);
     }
     st.m = move ? mx : st.m;
+    // A row may have seen none of the item's keys so far (its position lies before the chunk): its
+    // state stays at zero and its reference is 0.
+    st.neg_ref = st.m == -INFINITY ? -0.f : -st.m;
   }
-  // A row may have seen none of the item's keys so far (its position lies before the chunk): its
-  // state stays at zero.
-  const float m_ref = st.m == -INFINITY ? 0.f : st.m;
+  const float m_ref = -st.neg_ref;
   f32x8 p;
+  if constexpr (!WIDE) {
+    // One fused multiply-add per score: the top key's weight may miss 1 by an ulp of fp32, which the
+    // rounding to fp16 below takes back, so a row's first key still weighs exactly 1.
 #pragma unroll
-  for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * scale_log2 - m_ref);   // product rounded first: the row's top key gets exactly 1
-  // Weights as bf16 hi + lo (16 significant bits).  hi is p cut to its upper 16 bits (one byte
-  // permute packs two of them), lo = p - hi is exact in fp32 and is rounded to bf16.
-  u32x4 hi_packed;
-  f32x8 lo;
+    for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, st.neg_ref));
+    const f16x8 ph = __builtin_convertvector(p, f16x8);          // weights are below 2^8: no overflow
 #pragma unroll
-  for (int r = 0; r < 8; r += 2) {
-    const uint32_t b0 = __float_as_uint(p[r]), b1 = __float_as_uint(p[r + 1]);
-    hi_packed[r / 2] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);     // (b1 & 0xFFFF0000) | (b0 >> 16)
-    lo[r] = p[r] - __uint_as_float(b0 & 0xFFFF0000u);
-    lo[r + 1] = p[r + 1] - __uint_as_float(b1 & 0xFFFF0000u);
+    for (int c = 0; c < 4; ++c) {
+      const f16x8 a = __builtin_bit_cast(f16x8, va[c]), b = __builtin_bit_cast(f16x8, vb[c]);
+      st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, ph, st.acc[2 * c], 0, 0, 0);
+      st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(b, ph, st.acc[2 * c + 1], 0, 0, 0);
+    }
+    // the row sums: a row of ones in place of V^T leaves sum_t p_t in every element of the result column
+    const u32x4 ones_bits = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
+    st.l = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones_bits), ph, st.l, 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * scale_log2 - m_ref);   // product rounded first: the row's top key gets exactly 1
+    // Weights as bf16 hi + lo (16 significant bits).  hi is p cut to its upper 16 bits (one byte
+    // permute packs two of them), lo = p - hi is exact in fp32 and is rounded to bf16.
+    u32x4 hi_packed;
+    f32x8 lo;
+#pragma unroll
+    for (int r = 0; r < 8; r += 2) {
+      const uint32_t b0 = __float_as_uint(p[r]), b1 = __float_as_uint(p[r + 1]);
+      hi_packed[r / 2] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);     // (b1 & 0xFFFF0000) | (b0 >> 16)
+      lo[r] = p[r] - __uint_as_float(b0 & 0xFFFF0000u);
+      lo[r + 1] = p[r + 1] - __uint_as_float(b1 & 0xFFFF0000u);
+    }
+    const bf16x8 ph = __builtin_bit_cast(bf16x8, hi_packed);
+    const bf16x8 pl = __builtin_convertvector(lo, bf16x8);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, va[c]), b = __builtin_bit_cast(bf16x8, vb[c]);
+      st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph, st.acc[2 * c], 0, 0, 0);
+      st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, ph, st.acc[2 * c + 1], 0, 0, 0);
+      st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, st.acc[2 * c], 0, 0, 0);
+      st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, pl, st.acc[2 * c + 1], 0, 0, 0);
+    }
+    // the row sums: a row of ones in place of V^T leaves sum_t p_t in every element of the result column
+    const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+    st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, ph, st.l, 0, 0, 0);
+    st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pl, st.l, 0, 0, 0);
   }
-  const bf16x8 ph = __builtin_bit_cast(bf16x8, hi_packed);
-  const bf16x8 pl = __builtin_convertvector(lo, bf16x8);
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const bf16x8 a = __builtin_bit_cast(bf16x8, va[c]), b = __builtin_bit_cast(bf16x8, vb[c]);
-    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ph, st.acc[2 * c], 0, 0, 0);
-    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, ph, st.acc[2 * c + 1], 0, 0, 0);
-    st.acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, st.acc[2 * c], 0, 0, 0);
-    st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, pl, st.acc[2 * c + 1], 0, 0, 0);
-  }
-  // the row sums: a row of ones in place of V^T leaves sum_t p_t in every element of the result column
-  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
-  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, ph, st.l, 0, 0, 0);
-  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pl, st.l, 0, 0, 0);
+}
+
+// One 4 KiB slot of a pool as a raw buffer resource (base in scalar registers).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slot_buffer(const char* base) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>((static_cast<uint64_t>(hi) << 32) | lo), 0, 4096,
+                                           0x00020000 /* raw 32-bit data format */);
+}
+
+// Two bf16 values (one 32-bit word) as two fp16 values, same order.  Round-toward-zero conversion: exact
+// inside fp16's normal range, and a magnitude above 65504 becomes 65504, not infinity.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
+  const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xFFFF0000u);
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
 // The 8-wavefront, one-column-tile shape is held to 128 registers so that two workgroups (four
 // wavefronts per SIMD) share a CU: the softmax is a long dependent chain and needs the company.
-template <int WAVES, int CT>
+template <int WAVES, int CT, bool WIDE>
 __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) prefill_bf16_kernel(const PrefillParams P) {
   constexpr int NP = 8 / WAVES;        // (K, V) block couples a wavefront moves per page pair
   static_assert(NP >= 1, "at most 8 wavefronts");
@@ -203,7 +248,10 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
   const int n_it = (it.kv_end - it.kv_begin + 31) / 32;       // page pairs of this item
   const int page_begin = it.kv_begin / fs::kPageTokens;
   const int page_end = (it.kv_end + fs::kPageTokens - 1) / fs::kPageTokens;
-  const int32_t* __restrict__ ids = P.page_ids + P.page_indptr[it.pair];
+  // The page table is read through the constant address space: the kernel also stores to global memory, so
+  // the compiler would otherwise fetch the ids with vector loads and do the slot arithmetic per lane.
+  typedef const int32_t __attribute__((address_space(4))) * const_ids_ptr;
+  const const_ids_ptr ids = (const_ids_ptr)(reinterpret_cast<uintptr_t>(P.page_ids + P.page_indptr[it.pair]));
 
   // this lane's row of each column tile
   const int g = col % Gp, tl = col / Gp;
@@ -228,6 +276,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
 #pragma unroll
   for (int t = 0; t < CT; ++t) {
     st[t].m = -INFINITY;
+    st[t].neg_ref = -0.f;
     st[t].l = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 8; ++j) st[t].acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -240,9 +289,11 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
       const int page = page_begin + 2 * jp + h;
       if (page < page_end) {
+        // a slot as a raw buffer: its base stays in scalar registers, the lane's place in it is one 32-bit
+        // offset (64-bit vector addresses cost this kernel registers it does not have)
         const int64_t slot = ids[page];
-        r.k[i] = reinterpret_cast<const u32x4*>(P.k_pool + slot * P.k_stride)[c * 64 + lane];
-        r.v[i] = reinterpret_cast<const u32x4*>(P.v_pool + slot * P.v_stride)[c * 64 + lane];
+        r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.k_pool + slot * P.k_stride), (c * 64 + lane) * 16, 0, 0);
+        r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.v_pool + slot * P.v_stride), (c * 64 + lane) * 16, 0, 0);
       } else {   // the item ends with the first page of the pair
         r.k[i] = u32x4{0u, 0u, 0u, 0u};
         r.v[i] = u32x4{0u, 0u, 0u, 0u};
@@ -254,15 +305,20 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
+      unsigned char* base = stage[s];
+      *reinterpret_cast<u32x4*>(base + ((h * 4 + c) * 64 + lane) * 16) = r.k[i];
+      u32x4 v = r.v[i];
+      if constexpr (!WIDE) v = u32x4{bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w)};
       // value rows of tokens at or beyond the item's end may hold anything (the unused tail of a last
       // page is never initialised): blank them, 0 * NaN would be NaN in the product
       const int valid = it.kv_end - (page_begin + 2 * jp + h) * fs::kPageTokens;    // tokens of this page inside the item
-      const uint32_t m0 = (4 * kb + 0 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid ? 0xFFFF0000u : 0u);
-      const uint32_t m1 = (4 * kb + 2 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid ? 0xFFFF0000u : 0u);
-      unsigned char* base = stage[s];
-      *reinterpret_cast<u32x4*>(base + ((h * 4 + c) * 64 + lane) * 16) = r.k[i];
-      *reinterpret_cast<uint2*>(base + kVaOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(r.v[i].x & m0, r.v[i].y & m1);
-      *reinterpret_cast<uint2*>(base + kVbOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(r.v[i].z & m0, r.v[i].w & m1);
+      if (valid < fs::kPageTokens) {          // same for the whole wavefront: only an item's last page
+        const uint32_t m0 = (4 * kb + 0 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid ? 0xFFFF0000u : 0u);
+        const uint32_t m1 = (4 * kb + 2 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid ? 0xFFFF0000u : 0u);
+        v = u32x4{v.x & m0, v.y & m1, v.z & m0, v.w & m1};
+      }
+      *reinterpret_cast<uint2*>(base + kVaOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(v.x, v.y);
+      *reinterpret_cast<uint2*>(base + kVbOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(v.z, v.w);
     }
   };
   // ---- one page pair from LDS stage s against this wavefront's column tiles -----------------------
@@ -311,7 +367,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
     }
 #pragma unroll
     for (int t = 0; t < CT; ++t) {
-      if (need[t]) softmax_pv(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb, !full[t]);
+      if (need[t]) softmax_pv<WIDE>(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb, !full[t]);
     }
   };
 
@@ -436,12 +492,18 @@ extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_vie
   P.tile_tokens = tile_tokens;
   P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool wide = fs::options().prefill_wide_v != 0;
+#define FS_PREFILL_CASE(W, C)                                                                     \
+  case W * 10 + C:                                                                                \
+    return wide ? launch(prefill_bf16_kernel<W, C, true>, W * 64, P, n_items, s)                  \
+                : launch(prefill_bf16_kernel<W, C, false>, W * 64, P, n_items, s)
   switch (waves * 10 + ct) {
-    case 41: return launch(prefill_bf16_kernel<4, 1>, 256, P, n_items, s);
-    case 42: return launch(prefill_bf16_kernel<4, 2>, 256, P, n_items, s);
-    case 44: return launch(prefill_bf16_kernel<4, 4>, 256, P, n_items, s);
-    case 81: return launch(prefill_bf16_kernel<8, 1>, 512, P, n_items, s);
-    case 82: return launch(prefill_bf16_kernel<8, 2>, 512, P, n_items, s);
+    FS_PREFILL_CASE(4, 1);
+    FS_PREFILL_CASE(4, 2);
+    FS_PREFILL_CASE(4, 4);
+    FS_PREFILL_CASE(8, 1);
+    FS_PREFILL_CASE(8, 2);
     default: return fs::fail(FS_EINVAL, "fs_prefill_attention: no kernel for prefill_waves %d, prefill_col_tiles %d", waves, ct);
   }
+#undef FS_PREFILL_CASE
 }

@@ -38,6 +38,7 @@ def _lib():
     yield
     fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
     fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
+    fs.fs_set_option("prefill_wide_v", 0)
 
 
 def check(out, lse, ref_o, ref_l, what):
@@ -52,7 +53,8 @@ def check(out, lse, ref_o, ref_l, what):
     assert lerr <= LSE_TOL, f"{what}: lse off by {lerr}"
 
 
-def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched=True, interleave=True, chunk=0):
+def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched=True, interleave=True, chunk=0,
+              kv_edit=None):
     n_done = np.asarray(n_done, dtype=np.int32); n_new = np.asarray(n_new, dtype=np.int32)
     B = len(n_done)
     G = Hq // Hkv
@@ -65,6 +67,8 @@ def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched
     assert chunk_indptr.tobytes() == w_chunks.tobytes()
     ctx = (n_done + n_new).astype(np.int32)
     kv = make_kv_pool(seed, w_pairs[:, :2], ctx)
+    if kv_edit is not None:
+        kv_edit(kv)
     q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
     q = make_prefill_q(seed, int(q_indptr[-1]), Hq, 128)
     ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave)
@@ -130,6 +134,71 @@ def test_first_token_closed_form_and_one_token_chunks():
         for g in range(4):
             assert np.array_equal(out[int(out_indptr[p]) + g].astype(np.float64), V[0])
     compare_all(ds, kv, q, q_indptr, pairs, 4, 4, "one-token chunks", out_indptr)
+
+
+@pytest.mark.parametrize("waves,ct", [(8, 1), (4, 2)])
+def test_wide_value_path(waves, ct):
+    """The bf16 hi + lo form of the second product (option prefill_wide_v = 1): same bar, and the first token
+    of a prompt still returns its own V row exactly."""
+    say(f"wide V path waves={waves} ct={ct}")
+    fs.fs_set_option("prefill_wide_v", 1)
+    fs.fs_set_option("prefill_waves", waves)
+    fs.fs_set_option("prefill_col_tiles", ct)
+    try:
+        n_done, n_new = [0, 100, 1000, 31, 0], [97, 64, 200, 3, 1]
+        owner = np.zeros((5, 2), dtype=np.int32)
+        for chunk in (0, 256):
+            ds, kv, q, q_indptr, pairs, oi = run_share(21, n_done, n_new, 16, 2, owner, 0, 1, chunk=chunk)
+            compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"wide V, waves={waves} ct={ct} chunk={chunk}", oi)
+        out = ds.prefill_out.cpu().numpy()
+        for p in range(len(pairs)):
+            if pairs[p, 2] == 0:                    # a fresh prompt: its first token sees only itself
+                _, V = oracle.gather_pair_kv(kv, p, 0, 1)
+                for g in range(8):
+                    assert np.array_equal(out[int(oi[p]) + g].astype(np.float64), V[0])
+    finally:
+        fs.fs_set_option("prefill_wide_v", 0)
+        fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
+        fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
+
+
+def test_value_range_of_the_second_product():
+    """Values of V outside fp16's range: by default they enter the second product as +-65504 (and tiny ones on
+    fp16's subnormal grid, an absolute error below 2^-24); with prefill_wide_v = 1 they count in full."""
+    say("V range")
+    BIG, NEG_BIG, TINY = 0x47C3, 0xC7C3, 0x3580      # bf16 bits of 99840, -99840, 2^-20
+
+    def edit(kv):
+        for p in range(len(kv["page_indptr"]) - 1):
+            slot = int(kv["page_ids"][int(kv["page_indptr"][p])])       # first page of the pair: token 0 always exists
+            kv["v_pool"][slot, 0, 3] = BIG
+            kv["v_pool"][slot, 0, 64] = NEG_BIG
+            kv["v_pool"][slot, 0, 127] = TINY
+
+    n_done, n_new = [0, 40, 7], [33, 20, 1]
+    owner = np.zeros((3, 2), dtype=np.int32)
+    Hq, G = 8, 4
+    for wide in (0, 1):
+        fs.fs_set_option("prefill_wide_v", wide)
+        try:
+            ds, kv, q, q_indptr, pairs, oi = run_share(23, n_done, n_new, Hq, 2, owner, 0, 1, chunk=32, kv_edit=edit)
+        finally:
+            fs.fs_set_option("prefill_wide_v", 0)
+        out, lse = ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy()
+        got_o, got_l, ref_o, ref_l = [], [], [], []
+        qf = oracle.bf16_bits_to_f64(q.reshape(-1, Hq, 128))
+        for p in range(len(pairs)):
+            r, h, L, N = (int(x) for x in pairs[p])
+            for tok in range(N):
+                K, V = oracle.gather_pair_kv(kv, p, 0, L + tok + 1)
+                assert abs(V[0, 3]) > 65504 and abs(V[0, 64]) > 65504
+                if not wide:
+                    V = np.clip(V, -65504.0, 65504.0)
+                o, l = oracle.attend(qf[int(q_indptr[r]) + tok, h * G:(h + 1) * G], K, V, SCALE)
+                row = int(oi[p]) + tok * G
+                got_o.append(out[row:row + G]); got_l.append(lse[row:row + G]); ref_o.append(o); ref_l.append(l)
+        check(np.concatenate(got_o), np.concatenate(got_l), np.concatenate(ref_o), np.concatenate(ref_l),
+              f"V beyond fp16, wide={wide}")
 
 
 def test_chunked_prefill_feeds_from_the_scheduler():
