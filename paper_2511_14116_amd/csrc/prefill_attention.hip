@@ -287,17 +287,15 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
-      const int page = page_begin + 2 * jp + h;
-      if (page < page_end) {
-        // a slot as a raw buffer: its base stays in scalar registers, the lane's place in it is one 32-bit
-        // offset (64-bit vector addresses cost this kernel registers it does not have)
-        const int64_t slot = ids[page];
-        r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.k_pool + slot * P.k_stride), (c * 64 + lane) * 16, 0, 0);
-        r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.v_pool + slot * P.v_stride), (c * 64 + lane) * 16, 0, 0);
-      } else {   // the item ends with the first page of the pair
-        r.k[i] = u32x4{0u, 0u, 0u, 0u};
-        r.v[i] = u32x4{0u, 0u, 0u, 0u};
-      }
+      // Always a load, beyond the item's last page that page again (its keys are masked by position and
+      // its values blanked on the way into LDS): with the same number of loads in flight on every path
+      // the wait before a copy into LDS leaves the younger loads in flight.
+      const int page = min(page_begin + 2 * jp + h, page_end - 1);
+      // a slot as a raw buffer: its base stays in scalar registers, the lane's place in it is one 32-bit
+      // offset (64-bit vector addresses cost this kernel registers it does not have)
+      const int64_t slot = ids[page];
+      r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.k_pool + slot * P.k_stride), (c * 64 + lane) * 16, 0, 0);
+      r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.v_pool + slot * P.v_stride), (c * 64 + lane) * 16, 0, 0);
     }
   };
   // ---- registers -> LDS stage s ------------------------------------------------------------------
@@ -375,27 +373,25 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : 1) p
   // pairs j+2, j+3 are on their way from global memory.  One barrier per pair: after it, stage (j+1)%2 is
   // complete and nobody reads stage j%2 any more.  Every wavefront takes every branch below (n_it is the
   // workgroup's), so the barriers match.
+  if (n_it < 1) return;        // not produced by the list builder (an item sees at least one key)
   InFlight<NP> r0, r1;
   fetch(r0, 0);
-  if (n_it > 1) fetch(r1, 1);
+  fetch(r1, 1);
   deposit(0, r0, 0);
-  if (n_it > 2) fetch(r0, 2);
+  fetch(r0, 2);
   __syncthreads();
   for (int j = 0; j < n_it; j += 2) {
-    if (j + 1 < n_it) {
-      deposit(1, r1, j + 1);
-      if (j + 3 < n_it) fetch(r1, j + 3);
-    }
+    // Copies and fetches run for pairs beyond the item's end too (into a stage nobody reads, from the last
+    // page again): one shape of loop body, so every wait for a copy's data leaves exactly the two younger
+    // loads in flight.
+    deposit(1, r1, j + 1);
+    fetch(r1, j + 3);
     compute(0, j);
     __syncthreads();
-    if (j + 1 < n_it) {
-      if (j + 2 < n_it) {
-        deposit(0, r0, j + 2);
-        if (j + 4 < n_it) fetch(r0, j + 4);
-      }
-      compute(1, j + 1);
-      __syncthreads();
-    }
+    deposit(0, r0, j + 2);
+    fetch(r0, j + 4);
+    if (j + 1 < n_it) compute(1, j + 1);
+    __syncthreads();
   }
 
   // ---- write the item's partial rows --------------------------------------------------------------
