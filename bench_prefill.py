@@ -29,9 +29,10 @@ def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64,
     t0 = time.perf_counter()
     pending = np.zeros(R, dtype=np.int64)
     entries = np.zeros(n_req, dtype=fs.PREFILL_ENTRY_DTYPE)
-    for i in range(n_req):
-        waiting = int(prompt[i] - n_done[i])
-        entries[i] = (i, fs.fs_route_request(pending, waiting), int(n_done[i]), waiting)
+    entries["req"] = np.arange(n_req)
+    entries["n_done"] = n_done
+    entries["n_new"] = prompt - n_done
+    entries["rank"] = fs.fs_route_requests(pending, prompt - n_done)        # the waiting queue in arrival order
     t1 = time.perf_counter()
     take, load, n_tok = fs.fs_schedule_prefill(R, budget, budget // 2, entries)
     t2 = time.perf_counter()

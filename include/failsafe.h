@@ -11,7 +11,7 @@
  *   fs_merge_lse         split-K partials -> final (out, lse)           device
  *
  * and, before the decode step, the host side of the paper's router and prefill
- * scheduler: fs_route_request, fs_schedule_prefill; after a fault, the recovery
+ * scheduler: fs_route_request(s), fs_schedule_prefill; after a fault, the recovery
  * plans: fs_plan_kv_reload, fs_replace_failed_gpu, fs_plan_ffn_reload; and the
  * attention of the prefill batches: fs_build_prefill_worklist, fs_prefill_attention.
  *
@@ -184,6 +184,19 @@ FS_API fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len
  * FS_EINVAL: NULL pointer, n_ranks < 1, work < 0.
  */
 FS_API fs_status fs_route_request(int32_t n_ranks, int64_t* pending, int64_t work, int32_t* rank);
+
+/* fs_route_requests - the same rule (Section 3.1, Load-Aware DP-Rank Routing) for a queue of
+ * requests in arrival order, one call: request i goes to the rank with the least pending work
+ * after requests 0..i-1 were placed (lowest rank among equals), exactly as n calls of
+ * fs_route_request would place them.
+ *
+ *  pending  HOST in/out [n_ranks]   pending work per rank
+ *  work     HOST in     [n]         work of each request in token units, >= 0
+ *  rank     HOST out    [n]         the chosen ranks
+ *
+ * FS_EINVAL: NULL pointer (with n > 0), n_ranks < 1, n < 0, a negative work (nothing is changed).
+ */
+FS_API fs_status fs_route_requests(int32_t n_ranks, int64_t* pending, const int64_t* work, int32_t n, int32_t* rank);
 
 /* One waiting request of the prefill queue: n_new tokens wait behind n_done tokens
  * that are already processed; rank is the request's DP rank. */

@@ -67,6 +67,8 @@ def load_library(path: str | None = None):
     lib.fs_build_worklist.restype = C.c_int
     lib.fs_route_request.argtypes = [C.c_int32, i64p, C.c_int64, i32p]
     lib.fs_route_request.restype = C.c_int
+    lib.fs_route_requests.argtypes = [C.c_int32, i64p, i64p, C.c_int32, i32p]
+    lib.fs_route_requests.restype = C.c_int
     lib.fs_schedule_prefill.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, i64p, i32p, i64p, i32p]
     lib.fs_schedule_prefill.restype = C.c_int
     lib.fs_plan_kv_reload.argtypes = [C.c_int32, C.c_int32, i32p, i32p, i32p, C.c_int32, u8p, i64p, i64p]
@@ -220,6 +222,22 @@ def fs_route_request(pending: np.ndarray, work: int) -> int:
                                          C.byref(rank))
     _check(st)
     return rank.value
+
+
+def fs_route_requests(pending: np.ndarray, work) -> np.ndarray:
+    """Route a queue of requests in arrival order; ``pending`` (int64, one entry per rank) is updated in
+    place.  -> ranks [n] int32."""
+    if not isinstance(pending, np.ndarray) or pending.dtype != np.int64 or not pending.flags.c_contiguous:
+        raise TypeError("pending must be a contiguous int64 array (it is updated in place)")
+    work = np.ascontiguousarray(work, dtype=np.int64)
+    if work.ndim != 1:
+        raise ValueError("work must be one-dimensional")
+    rank = np.full(len(work), -1, dtype=np.int32)
+    st = load_library().fs_route_requests(len(pending), pending.ctypes.data_as(C.POINTER(C.c_int64)),
+                                          work.ctypes.data_as(C.POINTER(C.c_int64)), len(work),
+                                          rank.ctypes.data_as(C.POINTER(C.c_int32)))
+    _check(st)
+    return rank
 
 
 def fs_schedule_prefill(n_ranks: int, budget: int, min_tokens: int, entries, init_load=None):

@@ -24,6 +24,23 @@ extern "C" fs_status fs_route_request(int32_t n_ranks, int64_t* pending, int64_t
   return FS_OK;
 }
 
+extern "C" fs_status fs_route_requests(int32_t n_ranks, int64_t* pending, const int64_t* work, int32_t n, int32_t* rank) {
+  if (n_ranks < 1) return fs::fail(FS_EINVAL, "fs_route_requests: n_ranks %d < 1", n_ranks);
+  if (n < 0) return fs::fail(FS_EINVAL, "fs_route_requests: n %d < 0", n);
+  if (!pending || (n > 0 && (!work || !rank))) return fs::fail(FS_EINVAL, "fs_route_requests: NULL pointer");
+  for (int32_t i = 0; i < n; ++i)
+    if (work[i] < 0)
+      return fs::fail(FS_EINVAL, "fs_route_requests: work[%d] = %lld < 0", i, static_cast<long long>(work[i]));
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t best = 0;
+    for (int32_t k = 1; k < n_ranks; ++k)
+      if (pending[k] < pending[best]) best = k;   // strict: equal loads keep the lowest rank
+    pending[best] += work[i];
+    rank[i] = best;
+  }
+  return FS_OK;
+}
+
 namespace {
 fs_status schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens, const fs_prefill_entry* entries,
                            int32_t n_entries, const int64_t* init_load, int32_t* take, int64_t* load,

@@ -91,6 +91,14 @@ int main() {
       ent[e] = fs_prefill_entry{e, rank, static_cast<int32_t>(rng() % 100000), n_new};
       waiting += n_new;
     }
+    {   // the queue form places the same requests the same way
+      std::vector<int64_t> pending2(R, 0), work(n);
+      std::vector<int32_t> ranks(n);
+      for (int e = 0; e < n; ++e) work[e] = ent[e].n_new;
+      REQUIRE(fs_route_requests(R, pending2.data(), work.data(), n, ranks.data()) == FS_OK);
+      for (int e = 0; e < n; ++e) REQUIRE(ranks[e] == ent[e].rank);
+      REQUIRE(pending2 == pending);
+    }
     const int budget = rng() % 200, floor_tokens = rng() % 220;
     std::vector<int32_t> take(n);
     std::vector<int64_t> load(R);

@@ -58,6 +58,27 @@ def test_router_matches_oracle():
         assert a.tolist() == b
 
 
+def test_queue_router_matches_oracle_and_single_calls():
+    rng = np.random.default_rng(6)
+    for R in (1, 2, 7):
+        work = rng.integers(0, 10000, size=257)
+        work[::9] = 0                                   # zero-work requests still take the lowest least-loaded rank
+        start = rng.integers(0, 3000, size=R).astype(np.int64)
+        a, b, c = start.copy(), [int(x) for x in start], start.copy()
+        ranks = fs.fs_route_requests(a, work)
+        assert ranks.dtype == np.int32
+        assert ranks.tolist() == [route_request(b, int(w)) for w in work]
+        assert ranks.tolist() == [fs.fs_route_request(c, int(w)) for w in work]
+        assert a.tolist() == b == c.tolist()
+    assert len(fs.fs_route_requests(np.zeros(3, dtype=np.int64), [])) == 0
+    keep = np.array([5, 1, 9], dtype=np.int64)
+    with pytest.raises(fs.FsError):
+        fs.fs_route_requests(keep, [4, -1, 2])          # a negative work: nothing is placed
+    assert keep.tolist() == [5, 1, 9]
+    with pytest.raises(TypeError):
+        fs.fs_route_requests([0, 0], [1])
+
+
 def test_serving_sized_budget_is_fast_and_balanced():
     # 7 ranks, 64 waiting prompts shaped like the paper's online trace (mean ~13.5K tokens), budget 8192
     rng = np.random.default_rng(11)
