@@ -469,8 +469,9 @@ FS_API int32_t fs_prefill_tile_tokens(int32_t group);
  * gets part_o = 0 and part_lse = -inf.  Rows of a short last tile beyond its tokens
  * are written as zeros (part_lse = 0).  fs_merge_lse(part_o, part_lse,
  * chunk_indptr, n_tiles, T, head_dim, out, lse) then gives the final rows.  fp32
- * scores, softmax and accumulation; the softmax weights enter P.V as a sum of two
- * bf16 terms.
+ * scores, softmax and accumulation; in P.V the softmax weights and V enter as fp16
+ * (V beyond +-65504 as +-65504), or, with option "prefill_wide_v" = 1, V as bf16 and
+ * the weights as a sum of two bf16 terms (see fs_set_option).
  *
  *  items_dev  DEVICE in  [n_items]   as built by fs_build_prefill_worklist
  *  sched_dev  DEVICE in  [n_items]   launch order, or NULL for index order
