@@ -286,6 +286,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
 // ---------------------------------------------------------------------------------------------
 
 constexpr int kStageRows = 64;    // partial rows a workgroup keeps in LDS before it writes them (64 x 512 B)
+constexpr int kSecondShare = 4;   // a CU's second workgroup claims only within the first 1/kSecondShare of the list
 
 __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -377,6 +378,14 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
   };
   prologue(cur);
 
+  // Two workgroups share a CU, and the one launched second streams at about half the rate of the first (the
+  // issue arbiter prefers the older wavefront) while the CU's total stays the same.  A late item in its hands
+  // takes twice as long and ends the launch late, so the second half of the grid - by launch order the
+  // second workgroup of every CU - stops claiming once a quarter of the list is handed out; it is there to
+  // fill the CU while the list is long, and leaves the rest to its sibling.  (Where launch order does not map
+  // to CUs like that, half of the workgroups retire early just the same, which costs nothing measurable.)
+  const bool second_on_cu = blockIdx.x >= (gridDim.x + 1) / 2;
+  bool keep_claiming = true;
   int staged = 0;
   for (;;) {
     SoftmaxState st;
@@ -415,11 +424,13 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
     // The next item is claimed only now.  Claiming it earlier would hide the counter's round trip, but a
     // workgroup would then sit on an item another could have started: claiming at the start of the current
     // item cost 11 us of the launch on the 70B-shaped batch, two items ahead 20 us, four pages early 4 us.
-    if (threadIdx.x == 0) s_next = atomicAdd(claim, 1) + n_groups;
+    if (threadIdx.x == 0) s_next = keep_claiming ? atomicAdd(claim, 1) + n_groups : n_items;
     lds_barrier();
     // every page of the current item is consumed: fetch the next item's descriptor and first pages now,
     // so that they travel while the rows are merged
-    ItemDesc nxt = load_desc<WAVES>(P, __builtin_amdgcn_readfirstlane(s_next), n_items, wave, lane, G);
+    const int next_k = __builtin_amdgcn_readfirstlane(s_next);
+    ItemDesc nxt = load_desc<WAVES>(P, next_k, n_items, wave, lane, G);
+    if (second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
     prologue(nxt);
     for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
       const int q = idx >> 5, d4 = idx & 31;
