@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
 # (see profiles/); None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_rank0": 1971483318,    # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
+    "cfg2_rank0": 1971402660,    # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
     "cfg4_rank0": 1609662362,    # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
 }
 
