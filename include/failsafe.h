@@ -360,9 +360,11 @@ FS_API fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv
  * claim items from a counter in list order and write their partial rows in bursts
  * (decode phase, Section 2.1.1; the ragged list of Section 3.1).
  *
- *  claim_dev  DEVICE in/out  one int32, 4-byte aligned; must be 0 when the launch
- *             starts (e.g. uploaded together with the list) and is left non-zero.
- *             Two launches that overlap in time need two counters.
+ *  claim_dev  DEVICE in/out  two int32 (8-byte aligned): the item counter and the count
+ *             of workgroups that have left.  Both must be 0 before the first launch that
+ *             uses them; every launch leaves them at 0 again, so launches that follow
+ *             one another on a stream (or replays of a captured graph) share one pair
+ *             without clearing it.  Two launches that overlap in time need two pairs.
  *
  * Everything else as for fs_decode_attention.  FS_EUNSUPPORTED: fp8 K/V.
  */

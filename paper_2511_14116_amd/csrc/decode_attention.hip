@@ -469,6 +469,12 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
     if (last) break;
     cur = nxt;
   }
+  // The last workgroup to leave puts both counters back to zero for the next launch (every other
+  // workgroup has made its last claim by then).
+  if (threadIdx.x == 0 && atomicAdd(claim + 1, 1) == static_cast<int>(gridDim.x) - 1) {
+    __atomic_store_n(claim, 0, __ATOMIC_RELAXED);
+    __atomic_store_n(claim + 1, 0, __ATOMIC_RELAXED);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -707,8 +713,8 @@ extern "C" fs_status fs_decode_attention_persistent(const fs_shape* shape, const
   if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
       (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
       (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
-      (reinterpret_cast<uintptr_t>(part_o) & 15) || (reinterpret_cast<uintptr_t>(claim_dev) & 3))
-    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: pools, strides, q and part_o must be 16-byte aligned, "
+      (reinterpret_cast<uintptr_t>(part_o) & 15) || (reinterpret_cast<uintptr_t>(claim_dev) & 7))
+    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: pools, strides, q and part_o must be 16-byte aligned, claim_dev 8-byte, "
                                "strides at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
   if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: sm_scale is not finite");
   // CU count of the current device, asked once per device (the query is a runtime call on the launch path)

@@ -77,8 +77,7 @@ class DeviceShare:
     def decode_persistent(self, use_sched: bool = True):
         """The same partials by the persistent form of the sweep (bf16 K/V only)."""
         if not hasattr(self, "claim"):
-            self.claim = torch.zeros(1, dtype=torch.int32, device=self.device)
-        self.claim.zero_()
+            self.claim = torch.zeros(2, dtype=torch.int32, device=self.device)   # every launch leaves them at zero
         B.fs_decode_attention_persistent(self.shape, self.view, self.items, self.sched if use_sched else None,
                                          self.n_items, self.claim, self.part_o, self.part_lse,
                                          torch.cuda.current_stream().cuda_stream)

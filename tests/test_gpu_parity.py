@@ -401,11 +401,14 @@ def test_persistent_sweep_small_batches_against_oracle():
             ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
             check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l,
                   f"persistent cfg{cfg_id} chunk={chunk} rank {rank} ({len(items)} items)")
-            # a second launch on the same counter without clearing it must be refused by nothing: the
-            # binding clears it; launching twice in a row gives the same bits
+            # every launch leaves its two counters at zero, so a second launch on the same pair, with
+            # nothing cleared in between, gives the same bits
+            assert ds.claim.cpu().tolist() == [0, 0]
+            ds.part_o.fill_(float("nan")); ds.part_lse.fill_(float("nan"))
             ds.decode_persistent()
             torch.cuda.synchronize()
-            assert torch.equal(ds.part_o, ref_part_o)
+            assert torch.equal(ds.part_o, ref_part_o) and torch.equal(ds.part_lse, ref_part_l)
+            assert ds.claim.cpu().tolist() == [0, 0]
 
 
 def test_persistent_sweep_config2_full_size():
@@ -414,7 +417,9 @@ def test_persistent_sweep_config2_full_size():
     ref_out, ref_lse = ds.out.clone(), ds.lse.clone()
     ds.out.fill_(float("nan")); ds.lse.fill_(float("nan"))
     ds.part_o.fill_(float("nan")); ds.part_lse.fill_(float("nan"))
-    ds.decode_persistent()
+    for _ in range(3):                    # back to back on one pair of counters that nobody clears
+        ds.decode_persistent()
     ds.merge()
     torch.cuda.synchronize()
     assert torch.equal(ds.out, ref_out) and torch.equal(ds.lse, ref_lse)
+    assert ds.claim.cpu().tolist() == [0, 0]
