@@ -100,7 +100,7 @@ def main() -> int:
     # ---- synthetic batch ---------------------------------------------------------------------
     kw = dict(force_first_len=131072) if (args.config == 3 and args.force_tail) else {}
     w = make_requests(args.config, **kw)
-    chunk = w["chunk_tokens"] if args.chunk is None else args.chunk
+    MIN_CHUNK = 256          # floor of the adaptive split-K chunk (tokens)
     B, Hq, Hkv, R, G = w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"], w["group"]
     shape = fs.FsShape(B, Hq, Hkv, w["head_dim"], w["page_tokens"], R)
     ctx, mode = w["ctx_len"], w["mode"]
@@ -109,6 +109,17 @@ def main() -> int:
         owner, dp_rank, rank_load, _dp_load = fs.fs_build_placement_hybrid_heads(shape, ctx, layer=0)
     else:
         owner, dp_rank, rank_load = fs.fs_build_placement(shape, ctx, mode)
+    n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+
+    def chunk_for(rank):
+        """The config's chunk; where it is the builder's choice, halved until the rank's list has an item per CU."""
+        if args.chunk is not None:
+            return args.chunk
+        if w.get("chunk_adaptive") and w["chunk_tokens"] > MIN_CHUNK:
+            return fs.fs_choose_chunk_tokens(shape, ctx, owner, rank, w["chunk_tokens"], MIN_CHUNK, n_cu)[0]
+        return w["chunk_tokens"]
+
+    chunk = chunk_for(args.rank)
     items, pairs, sched, chunk_indptr = fs.fs_build_worklist(shape, ctx, owner, args.rank, chunk)
     n_items, n_pairs = len(items), len(pairs)
     if n_items == 0:
@@ -348,7 +359,7 @@ def main() -> int:
     if args.all_ranks:
         per_rank = []
         for k in range(R):
-            it_k, pr_k, sc_k, ip_k = fs.fs_build_worklist(shape, ctx, owner, k, chunk)
+            it_k, pr_k, sc_k, ip_k = fs.fs_build_worklist(shape, ctx, owner, k, chunk_for(k))
             if len(it_k) == 0:
                 per_rank.append({"rank": k, "kv_token_heads": 0, "n_items": 0, "kernels_us": 0.0, "gbs": 0.0})
                 continue

@@ -173,6 +173,26 @@ FS_API fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len
                             int64_t* n_items, int64_t* n_pairs);
 
 /* ---------------------------------------------------------------------------
+ * fs_choose_chunk_tokens - a split-K chunk size for one rank's share.  The ragged share of
+ * Section 3.1 can be a handful of very long contexts (the skew the paper's load-aware routing is
+ * there for); a list with fewer items than the GPU has compute units leaves most of it idle, so
+ * the chunk is halved, from max_chunk down (rounded down to whole pages), until rank's list, as
+ * fs_build_worklist would build it, has at least min_items items or the next halving would go
+ * below min_chunk.
+ *
+ *  ctx_len, owner   HOST in   as for fs_build_worklist
+ *  max_chunk, min_chunk       multiples of page_tokens, page_tokens <= min_chunk <= max_chunk
+ *  min_items        the length the list should reach (e.g. the number of compute units)
+ *  chunk_tokens     HOST out  the chosen chunk
+ *  n_items          HOST out  the list's length with it
+ *
+ * FS_EINVAL: bad shape, rank, chunk bounds, min_items < 0, owner outside [0, R), ctx_len < 1.
+ */
+FS_API fs_status fs_choose_chunk_tokens(const fs_shape* shape, const int32_t* ctx_len, const int32_t* owner,
+                                        int32_t rank, int32_t max_chunk, int32_t min_chunk, int64_t min_items,
+                                        int32_t* chunk_tokens, int64_t* n_items);
+
+/* ---------------------------------------------------------------------------
  * fs_route_request - Section 3.1, Load-Aware DP-Rank Routing: the incoming request
  * goes to the rank whose pending DP work (token units) is smallest, the lowest rank
  * among equals; `work` is added to that rank's pending work.

@@ -50,3 +50,21 @@ def build_worklist(ctx_len, owner, rank: int, chunk_tokens: int, n_q_heads: int,
     length = items[:, 3] - items[:, 2]
     sched = sorted(range(len(items)), key=lambda i: (-int(length[i]), i))
     return items, pairs, np.array(sched, dtype=np.int32), np.array(indptr, dtype=np.int64)
+
+
+def choose_chunk_tokens(ctx_len, owner, rank: int, max_chunk: int, min_chunk: int, min_items: int,
+                        n_kv_heads: int, page_tokens: int = 16):
+    """Halve the split-K chunk from ``max_chunk`` down (whole pages) until ``rank``'s list has at least
+    ``min_items`` items or the next halving would fall below ``min_chunk``.  -> (chunk, n_items).
+    The chunk is this build's device for long contexts, not the paper's; the item count is that of
+    ``build_worklist`` with the same chunk."""
+    if min_chunk < page_tokens or min_chunk % page_tokens or max_chunk < min_chunk or max_chunk % page_tokens:
+        raise ValueError("chunk bounds must be whole pages, min <= max")
+    lens = [int(ctx_len[r]) for r in range(len(ctx_len)) for h in range(n_kv_heads) if int(owner[r][h]) == rank]
+    C = int(max_chunk)
+    while True:
+        n = sum(-(-L // C) for L in lens)
+        nxt = (C // 2) // page_tokens * page_tokens
+        if n >= min_items or nxt < min_chunk:
+            return C, n
+        C = nxt

@@ -65,6 +65,9 @@ def load_library(path: str | None = None):
                                       C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_void_p, i64p, i64p]
     lib.fs_build_worklist.restype = C.c_int
+    lib.fs_choose_chunk_tokens.argtypes = [C.POINTER(FsShape), i32p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                           i32p, i64p]
+    lib.fs_choose_chunk_tokens.restype = C.c_int
     lib.fs_route_request.argtypes = [C.c_int32, i64p, C.c_int64, i32p]
     lib.fs_route_request.restype = C.c_int
     lib.fs_route_requests.argtypes = [C.c_int32, i64p, i64p, C.c_int32, i32p]
@@ -211,6 +214,20 @@ def fs_build_worklist(shape: FsShape, ctx_len, owner, rank: int, chunk_tokens: i
     _check(st)
     n, m = n_items.value, n_pairs.value
     return items[:n], pairs[:m], sched[:n], indptr[:m + 1]
+
+
+def fs_choose_chunk_tokens(shape: FsShape, ctx_len, owner, rank: int, max_chunk: int, min_chunk: int,
+                           min_items: int):
+    """-> (chunk_tokens, n_items): the split-K chunk, halved from ``max_chunk`` down to at least ``min_chunk``,
+    with which ``rank``'s list reaches ``min_items`` items."""
+    lib = load_library()
+    ctx = _host(ctx_len, np.int32)
+    own = _host(owner, np.int32)
+    i32p = C.POINTER(C.c_int32)
+    chunk, n_items = C.c_int32(0), C.c_int64(0)
+    _check(lib.fs_choose_chunk_tokens(C.byref(shape), ctx.ctypes.data_as(i32p), own.ctypes.data_as(i32p), rank,
+                                      max_chunk, min_chunk, min_items, C.byref(chunk), C.byref(n_items)))
+    return chunk.value, n_items.value
 
 
 def fs_route_request(pending: np.ndarray, work: int) -> int:

@@ -277,9 +277,15 @@ def _full_config(cfg_id, rank, n_sample, **req_kw):
     owner, dp, load = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
     o_owner, _, o_load = oracle.build_placement(w["ctx_len"], w["mode"], w["n_ranks"], w["n_kv_heads"])
     assert owner.tobytes() == o_owner.tobytes() and load.tobytes() == o_load.tobytes()
-    say(f"config {cfg_id} rank {rank}: generating pool")
-    ds, kv, items, pairs, sched, indptr = run_rank(w, q, rank, w["chunk_tokens"], owner)
-    oi, op, osch, oind = oracle.build_worklist(w["ctx_len"], o_owner, rank, w["chunk_tokens"], w["n_q_heads"], w["n_kv_heads"])
+    chunk = w["chunk_tokens"]
+    if w.get("chunk_adaptive"):           # the builder's choice, as bench.py makes it: an item per compute unit
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        chunk, n_chosen = fs.fs_choose_chunk_tokens(sh, w["ctx_len"], owner, rank, w["chunk_tokens"], 256, n_cu)
+        assert (chunk, n_chosen) == oracle.choose_chunk_tokens(w["ctx_len"], o_owner, rank, w["chunk_tokens"], 256, n_cu,
+                                                               w["n_kv_heads"])
+    say(f"config {cfg_id} rank {rank}: generating pool (chunk {chunk})")
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, rank, chunk, owner)
+    oi, op, osch, oind = oracle.build_worklist(w["ctx_len"], o_owner, rank, chunk, w["n_q_heads"], w["n_kv_heads"])
     assert items_rows(items).tobytes() == oi.tobytes() and sched.tobytes() == osch.tobytes() and indptr.tobytes() == oind.tobytes()
     say(f"config {cfg_id} rank {rank}: {len(pairs)} pairs, {len(items)} items, {ds.kv_bytes / 1e6:.1f} MB of K+V")
     out = ds.out.cpu().numpy(); lse = ds.lse.cpu().numpy()

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "failsafe.h")) as f:
         header = f.read()
     declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
-    assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_decode_attention",
+    assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_choose_chunk_tokens", "fs_decode_attention",
             "fs_decode_attention_persistent", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
             "fs_route_request", "fs_route_requests", "fs_schedule_prefill", "fs_plan_kv_reload", "fs_replace_failed_gpu", "fs_plan_ffn_reload", "fs_kv_elem_offset", "fs_stream_read_probe", "fs_set_option", "fs_get_option", "fs_last_error",
             "fs_abi_version"} <= declared
@@ -230,3 +230,27 @@ def test_hybrid_heads_bit_exact_random_and_configs():
     assert e.value.status == fs.FS_EINVAL
     with pytest.raises(fs.FsError):
         fs.fs_build_placement_hybrid_heads(_shape(1, 4, 4, 3), [0])
+
+
+def test_chunk_choice_matches_oracle():
+    rng = np.random.default_rng(11)
+    for case in range(40):
+        B, H, R = int(rng.integers(1, 30)), int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        ctx = rng.integers(1, 40000, size=B).astype(np.int32)
+        owner = rng.integers(0, R, size=(B, H)).astype(np.int32)
+        sh = _shape(B, 2 * H, H, R)
+        for rank in range(R):
+            for max_c, min_c, want in ((2048, 256, 256), (4096, 16, 37), (512, 512, 10 ** 5), (2048, 48, 0), (48, 16, 9)):
+                got = fs.fs_choose_chunk_tokens(sh, ctx, owner, rank, max_c, min_c, want)
+                assert got == oracle.choose_chunk_tokens(ctx, owner, rank, max_c, min_c, want, H)
+                items, _, _, _ = fs.fs_build_worklist(sh, ctx, owner, rank, got[0])
+                assert len(items) == got[1]
+    sh = _shape(2, 4, 2, 2)
+    ctx, owner = np.array([5, 9], dtype=np.int32), np.zeros((2, 2), dtype=np.int32)
+    for bad in ((64, 24, 1), (16, 32, 1), (64, 8, 1), (64, 16, -1)):
+        with pytest.raises(fs.FsError):
+            fs.fs_choose_chunk_tokens(sh, ctx, owner, 0, *bad)
+    with pytest.raises(fs.FsError):
+        fs.fs_choose_chunk_tokens(sh, ctx, owner, 2, 64, 16, 1)
+    with pytest.raises(fs.FsError):
+        fs.fs_choose_chunk_tokens(sh, np.array([5, 0], dtype=np.int32), owner, 0, 64, 16, 1)

@@ -2,7 +2,7 @@
 import numpy as np
 import pytest
 
-from oracle import build_placement, build_worklist
+from oracle import build_placement, build_worklist, choose_chunk_tokens
 
 
 def _case(seed, B, R, H, frac_dp, lo=1, hi=9000):
@@ -81,3 +81,35 @@ def test_rejects_bad_chunk_and_heads():
         build_worklist(ctx, owner, 0, 24, 4, 2)
     with pytest.raises(ValueError):
         build_worklist(ctx, owner, 0, 16, 5, 2)
+
+
+def test_chunk_choice_by_hand():
+    # rank 0 holds three pairs of 40, 20 and 20 tokens (the tiny list above)
+    ctx = np.array([40, 20], dtype=np.int32)
+    owner, _, _ = build_placement(ctx, [0, 1], 2, 2)
+    # chunk 64: 3 items; 32: 2+1+1 = 4; 16: 3+2+2 = 7
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 3, 2) == (64, 3)
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 4, 2) == (32, 4)
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 5, 2) == (16, 7)
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 100, 2) == (16, 7)      # never below min_chunk
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 32, 100, 2) == (32, 4)
+    assert choose_chunk_tokens(ctx, owner, 0, 48, 16, 4, 2) == (16, 7)        # 48 -> 24 rounds down to one page
+    assert choose_chunk_tokens(ctx, owner, 1, 64, 16, 0, 2) == (64, 1)        # nothing asked for: the largest chunk
+    with pytest.raises(ValueError):
+        choose_chunk_tokens(ctx, owner, 0, 64, 24, 1, 2)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_chunk_choice_properties(seed):
+    ctx, owner, _ = _case(seed, 40, 3, 4, 0.3, lo=1, hi=30000)
+    for rank in range(3):
+        for min_items in (0, 1, 50, 256, 10 ** 6):
+            C, n = choose_chunk_tokens(ctx, owner, rank, 2048, 256, min_items, 4)
+            assert C in (2048, 1024, 512, 256)
+            items, _, _, _ = build_worklist(ctx, owner, rank, C, 8, 4)
+            assert n == len(items)                              # the count is the real list's
+            if C < 2048:                                        # every larger candidate was too short
+                bigger, _, _, _ = build_worklist(ctx, owner, rank, 2 * C, 8, 4)
+                assert len(bigger) < min_items
+            if n < min_items:
+                assert C == 256

@@ -29,13 +29,13 @@ CONFIGS = {
             dp=("fraction", 0.0), chunk_tokens=0),
     1: dict(name="8b-hybrid", n_req=256, n_q_heads=32, n_kv_heads=8, head_dim=128,
             page_tokens=16, n_ranks=7, kv_dtype="bf16", lengths=("lognormal", 2048, 0.8, 8192),
-            dp=("fraction", 0.25), chunk_tokens=2048),
+            dp=("fraction", 0.25), chunk_tokens=2048, chunk_adaptive=True),
     2: dict(name="70b-gqa", n_req=512, n_q_heads=64, n_kv_heads=8, head_dim=128,
             page_tokens=16, n_ranks=6, kv_dtype="bf16", lengths=("lognormal", 4096, 0.7, 32768),
             dp=("fraction", 0.20), chunk_tokens=2048),
     3: dict(name="long-context-skew", n_req=64, n_q_heads=32, n_kv_heads=8, head_dim=128,
             page_tokens=16, n_ranks=5, kv_dtype="bf16", lengths=("pareto", 1.2, 512, 131072),
-            dp=("shorter_than", 16384), chunk_tokens=2048),
+            dp=("shorter_than", 16384), chunk_tokens=2048, chunk_adaptive=True),
     4: dict(name="mha-fp8", n_req=1024, n_q_heads=32, n_kv_heads=32, head_dim=128,
             page_tokens=16, n_ranks=7, kv_dtype="fp8", lengths=("uniform", 512, 2048),
             dp=("fraction", 0.0), chunk_tokens=0),
