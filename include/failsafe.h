@@ -7,6 +7,7 @@
  *   fs_build_placement   which rank owns each (request, KV head)        host
  *   (fs_build_placement_hybrid_heads: the paper's head-level variant)   host
  *   fs_build_worklist    one rank's ragged (request, head, chunk) list  host
+ *   (fs_choose_chunk_tokens: a chunk size where the caller leaves it open) host
  *   fs_decode_attention  per-item partial attention (out, lse)          device
  *   fs_merge_lse         split-K partials -> final (out, lse)           device
  *
