@@ -20,10 +20,12 @@ KV_CHUNK_DEFAULT = 2048            # split-K chunk of the keys a tile sees
 
 
 def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64, n_kv_heads=8, seed=20251120,
-                     median=8001, cap=123192, kv_chunk=KV_CHUNK_DEFAULT):
-    """Queue -> router -> Algorithm 1 -> hybrid placement -> rank's tile list (library calls only)."""
-    from workloads import make_prefill_queue
-    queue = make_prefill_queue(seed, n_req, median=median, sigma=0.9, cap=cap)
+                     median=8001, cap=123192, kv_chunk=KV_CHUNK_DEFAULT, queue=None):
+    """Queue -> router -> Algorithm 1 -> hybrid placement -> rank's tile list (library calls only).
+    ``queue``: the waiting prompts if already drawn (the draw is the synthetic input, not part of a step)."""
+    if queue is None:
+        from workloads import make_prefill_queue
+        queue = make_prefill_queue(seed, n_req, median=median, sigma=0.9, cap=cap)
     prompt, n_done = queue["prompt_len"], queue["n_done"]
     R = n_ranks
     t0 = time.perf_counter()
@@ -44,7 +46,7 @@ def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64,
     items, pairs, sched, chunk_indptr, out_indptr = fs.fs_build_prefill_worklist(shape, n_done, take, owner, rank, tile,
                                                                                  kv_chunk)
     t3 = time.perf_counter()
-    return dict(seed=seed, shape=shape, G=G, R=R, rank=rank, budget=budget, prompt=prompt, n_done=n_done,
+    return dict(seed=seed, queue=queue, shape=shape, G=G, R=R, rank=rank, budget=budget, prompt=prompt, n_done=n_done,
                 n_new=take.astype(np.int32), entries=entries, rank_token_load=load, n_tokens=n_tok, owner=owner,
                 tile=tile, kv_chunk=kv_chunk, items=items, pairs=pairs, sched=sched, chunk_indptr=chunk_indptr,
                 out_indptr=out_indptr,
@@ -102,13 +104,30 @@ def run(args) -> int:
     kv_tokens = int(sum(int(p["n_done"]) + int(p["n_new"]) for p in pairs))
 
     host_us = []
+    # The step's list goes to the GPU through pinned staging buffers (a copy from pageable memory would make the
+    # host wait for it); three sets, and a set is reused only once the upload that read it is done.
+    N_STAGE = 3
+    staging = [dict(items=torch.empty((len(items), 8), dtype=torch.int32, pin_memory=True),
+                    sched=torch.empty(len(items), dtype=torch.int32, pin_memory=True),
+                    indptr=torch.empty(len(w["chunk_indptr"]), dtype=torch.int64, pin_memory=True),
+                    done=None) for _ in range(N_STAGE)]
+    n_step = [0]
 
     def step(ev=None):
         t0 = time.perf_counter()
-        ww = prefill_workload(fs, **wl)                                  # host side of the step (library calls)
-        ds.prefill_items.copy_(torch.from_numpy(ww["items"].view(np.int32).reshape(-1, 8)), non_blocking=True)
-        ds.prefill_sched.copy_(torch.from_numpy(ww["sched"]), non_blocking=True)
-        ds.prefill_chunk_indptr.copy_(torch.from_numpy(ww["chunk_indptr"]), non_blocking=True)
+        ww = prefill_workload(fs, queue=w["queue"], **wl)                # host side of the step (library calls)
+        st = staging[n_step[0] % N_STAGE]
+        n_step[0] += 1
+        if st["done"] is not None:
+            st["done"].synchronize()
+        st["items"].numpy()[...] = ww["items"].view(np.int32).reshape(-1, 8)
+        st["sched"].numpy()[...] = ww["sched"]
+        st["indptr"].numpy()[...] = ww["chunk_indptr"]
+        ds.prefill_items.copy_(st["items"], non_blocking=True)
+        ds.prefill_sched.copy_(st["sched"], non_blocking=True)
+        ds.prefill_chunk_indptr.copy_(st["indptr"], non_blocking=True)
+        st["done"] = torch.cuda.Event()
+        st["done"].record(stream)
         host_us.append((time.perf_counter() - t0) * 1e6)
         sp = stream.cuda_stream
         if ev is not None:

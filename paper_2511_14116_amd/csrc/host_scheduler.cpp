@@ -7,6 +7,8 @@
 // it passed through.  What the paper leaves open (the token cost, the choice among the
 // candidates, the unused workload input) is fixed as the header states.
 #include <cstddef>
+#include <cstdint>
+#include <limits>
 #include <new>
 #include <vector>
 
@@ -73,60 +75,76 @@ fs_status schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens, 
   std::vector<int64_t> L(R);
   for (int32_t r = 0; r < R; ++r) L[r] = init_load ? init_load[r] : 0;
 
-  // The loop of Algorithm 1.  Candidate i (the batch after i+1 tokens) is remembered as the rank it
-  // took from plus the largest load and the load sum at that point.
-  std::vector<int32_t> took_from;
-  std::vector<int64_t> cand_max, cand_sum;
+  // The loop of Algorithm 1.
+  // Candidate i (the batch after i+1 tokens) is remembered as the rank it took from; from the first batch
+  // choose_best_batch may pick on (min(min_tokens, all) tokens), also the largest load and the load sum.
   int64_t waiting = 0;
   for (int32_t e = 0; e < n_entries; ++e) waiting += entries[e].n_new;
   const size_t most = static_cast<size_t>(waiting < budget ? waiting : budget);   // tokens the loop can take
-  took_from.reserve(most);
-  cand_max.reserve(most);
-  cand_sum.reserve(most);
+  if (most == 0) {
+    for (int32_t r = 0; r < R; ++r) load[r] = L[r];
+    *n_tokens = 0;
+    return FS_OK;
+  }
+  const size_t lo = static_cast<size_t>(min_tokens) < most ? static_cast<size_t>(min_tokens) : most;
+  const size_t first_cand = lo > 0 ? lo - 1 : 0;
+  std::vector<uint8_t> took_from8;
+  std::vector<int32_t> took_from32;
+  const bool small_r = R <= 256;
+  if (small_r) took_from8.resize(most); else took_from32.resize(most);
+  std::vector<int64_t> cand_max(most - first_cand), cand_sum(most - first_cand);
   int64_t sum = 0, mx = 0;
   for (int32_t r = 0; r < R; ++r) { sum += L[r]; if (r == 0 || L[r] > mx) mx = L[r]; }
-  while (static_cast<int32_t>(took_from.size()) < budget) {
-    int32_t rs = -1;
-    for (int32_t r = 0; r < R; ++r)
-      if (cur[r] >= 0 && (rs < 0 || L[r] < L[rs])) rs = r;
-    if (rs < 0) break;                                    // every S_r is empty
+  // A rank whose S_r is empty is priced at the largest load so that the search below needs no test per
+  // rank; the loop ends after `most` tokens, which is exactly when every S_r is empty or the budget is spent.
+  constexpr int64_t kEmpty = std::numeric_limits<int64_t>::max();
+  std::vector<int64_t> key(R);
+  for (int32_t r = 0; r < R; ++r) key[r] = cur[r] >= 0 ? L[r] : kEmpty;
+  for (size_t n_taken = 0; n_taken < most; ++n_taken) {
+    int32_t rs = 0;
+    int64_t least = key[0];
+    for (int32_t r = 1; r < R; ++r) {          // strict: equal loads keep the lowest rank
+      const bool lt = key[r] < least;
+      least = lt ? key[r] : least;
+      rs = lt ? r : rs;
+    }
     const fs_prefill_entry& q = entries[cur[rs]];
     const int64_t cost = static_cast<int64_t>(q.n_done) + cur_taken[rs] + 1;   // keys this token attends to
     L[rs] += cost;
     sum += cost;
     if (L[rs] > mx) mx = L[rs];
     if (++cur_taken[rs] == q.n_new) { cur[rs] = next[cur[rs]]; cur_taken[rs] = 0; }
-    took_from.push_back(rs);
-    cand_max.push_back(mx);
-    cand_sum.push_back(sum);
+    key[rs] = cur[rs] >= 0 ? L[rs] : kEmpty;
+    if (small_r) took_from8[n_taken] = static_cast<uint8_t>(rs); else took_from32[n_taken] = rs;
+    if (n_taken >= first_cand) {
+      cand_max[n_taken - first_cand] = mx;
+      cand_sum[n_taken - first_cand] = sum;
+    }
   }
 
-  const int32_t n_all = static_cast<int32_t>(took_from.size());
-  if (n_all == 0) {
-    for (int32_t r = 0; r < R; ++r) load[r] = L[r];
-    *n_tokens = 0;
-    return FS_OK;
+  // choose_best_batch: smallest max/mean among the eligible candidates, the larger batch among equals.
+  // max_i/sum_i <= max_b/sum_b  <=>  max_i*sum_b <= max_b*sum_i.
+  size_t best_c = 0;
+  for (size_t c = 1; c < cand_max.size(); ++c) {
+    const unsigned __int128 a = static_cast<unsigned __int128>(cand_max[c]) * static_cast<unsigned __int128>(cand_sum[best_c]);
+    const unsigned __int128 b = static_cast<unsigned __int128>(cand_max[best_c]) * static_cast<unsigned __int128>(cand_sum[c]);
+    if (a <= b) best_c = c;
   }
-  // choose_best_batch: smallest max/mean among the candidates of at least min(min_tokens, n_all) tokens,
-  // the larger batch among equals.  max_i/sum_i <= max_b/sum_b  <=>  max_i*sum_b <= max_b*sum_i.
-  const int32_t lo = min_tokens < n_all ? min_tokens : n_all;
-  int32_t best = -1;
-  for (int32_t i = (lo > 0 ? lo - 1 : 0); i < n_all; ++i) {
-    if (best < 0) { best = i; continue; }
-    const unsigned __int128 a = static_cast<unsigned __int128>(cand_max[i]) * static_cast<unsigned __int128>(cand_sum[best]);
-    const unsigned __int128 b = static_cast<unsigned __int128>(cand_max[best]) * static_cast<unsigned __int128>(cand_sum[i]);
-    if (a <= b) best = i;
-  }
+  const int32_t best = static_cast<int32_t>(first_cand + best_c);
 
-  // Replay the first best+1 steps to get the per-entry counts and the loads of the chosen batch.
-  cur = first;
-  for (int32_t r = 0; r < R; ++r) { cur_taken[r] = 0; L[r] = init_load ? init_load[r] : 0; }
-  for (int32_t i = 0; i <= best; ++i) {
-    const int32_t r = took_from[i];
-    const int32_t e = cur[r];
-    L[r] += static_cast<int64_t>(entries[e].n_done) + cur_taken[r] + 1;
-    ++take[e];
-    if (++cur_taken[r] == entries[e].n_new) { cur[r] = next[e]; cur_taken[r] = 0; }
+  // The chosen batch: how many of its tokens came from each rank, dealt out over that rank's entries in
+  // order; a rank's load grows by the costs n_done+1 .. n_done+t of the t tokens taken from an entry.
+  std::vector<int64_t> from_rank(R, 0);
+  for (int32_t i = 0; i <= best; ++i) ++from_rank[small_r ? took_from8[i] : took_from32[i]];
+  for (int32_t r = 0; r < R; ++r) {
+    L[r] = init_load ? init_load[r] : 0;
+    int64_t left = from_rank[r];
+    for (int32_t e = first[r]; e >= 0 && left > 0; e = next[e]) {
+      const int64_t t = left < entries[e].n_new ? left : entries[e].n_new;
+      take[e] = static_cast<int32_t>(t);
+      L[r] += t * entries[e].n_done + t * (t + 1) / 2;
+      left -= t;
+    }
   }
   for (int32_t r = 0; r < R; ++r) load[r] = L[r];
   *n_tokens = best + 1;
