@@ -282,7 +282,8 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
 // their bytes explain, writes at the end of a workgroup's life mostly do not.  The next item's
 // descriptor, query rows and first pages are fetched while the current item's rows are merged,
 // and the barriers around that merge wait for LDS traffic only, so those loads stay in flight
-// across them.
+// across them.  claim[0] counts the items handed out beyond the first gridDim.x, claim[1] the workgroups
+// that have left; both are zero between launches.
 // ---------------------------------------------------------------------------------------------
 
 constexpr int kStageRows = 64;    // partial rows a workgroup keeps in LDS before it writes them (64 x 512 B)
