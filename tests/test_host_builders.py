@@ -145,6 +145,23 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention(_shape(1, 34, 2, 3), kv, None, None, 3, None, None)
     assert e.value.status == fs.FS_EINVAL
+    # the persistent form of the sweep checks the same things, plus its counters and the K/V type
+    fs.fs_decode_attention_persistent(sh, kv, None, None, 0, None, None, None)       # empty list: no-op
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention_persistent(sh, kv, None, None, 3, None, None, None)
+    assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention_persistent(_shape(1, 4, 2, 3, d=64), kv, None, None, 3, None, None, None)
+    assert e.value.status == fs.FS_EUNSUPPORTED
+    kv8 = fs.FsKvView(kv_dtype=fs.FS_KV_FP8_E4M3)
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention_persistent(sh, kv8, None, None, 3, None, None, None)
+    assert e.value.status == fs.FS_EUNSUPPORTED
+    # prefill: empty list is a no-op; a tile beyond the kernel's is refused before any launch
+    fs.fs_prefill_attention(sh, kv, None, None, 0, 1, None, None)
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_prefill_attention(sh, kv, None, None, 1, 10 ** 6, None, None)
+    assert e.value.status == fs.FS_EINVAL
     with pytest.raises(fs.FsError) as e:
         fs.fs_merge_lse(None, None, None, 4, 2, 64, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
