@@ -7,9 +7,11 @@
 //
 // One wavefront per output row (pair, q-head).  The row's chunk lse values are read 64 at a time,
 // one per lane, and reduced across the wavefront, so a pair cut into many chunks (a 131072-token
-// context in 1024-token chunks has 128) costs two wide loads instead of a serial chain.  For the
-// rows themselves a lane owns two of the 128 columns (one coalesced 512-byte read per chunk) and
-// four chunk rows are in flight at a time.  HBM traffic is under 1% of the attention sweep's.
+// context in 1024-token chunks has 128) costs a wide load per 64 chunks instead of a serial chain.
+// For the rows themselves a lane owns two of the 128 columns (one coalesced 512-byte read per
+// chunk), four chunk rows are in flight at a time, and the first four are requested together with
+// the lse values, before the weights are known.  For decode the traffic is under 1% of the
+// attention sweep's; for chunked prefill (a tile's rows per chunk) it is a sixth of the kernel time.
 #include <hip/hip_runtime.h>
 
 #include "fs_internal.h"
@@ -42,25 +44,37 @@ merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ par
   const int64_t c0 = chunk_indptr[p];
   const int n = static_cast<int>(chunk_indptr[p + 1] - c0);
 
+  // Chunks are taken 64 at a time (one lse per lane).  The first rows of a batch are requested before
+  // its weights are known, so the two reads travel together; across batches (more than 64 chunks) the
+  // running maximum moves and what has been summed is rescaled, as in an online softmax.
   float M = -INFINITY;
-  for (int base = 0; base < n; base += 64) {
-    const int c = base + lane;
-    M = fmaxf(M, c < n ? part_lse[(c0 + c) * group + g] : -INFINITY);
-  }
-  M = wave_max(M);
-
   float sum = 0.f;
   float2 acc = make_float2(0.f, 0.f);
+  const int64_t stride = static_cast<int64_t>(group) * (fs::kHeadDim / 2);   // float2 units between chunk rows
   for (int base = 0; base < n; base += 64) {
     const int c = base + lane;
-    const float w = c < n ? __expf(part_lse[(c0 + c) * group + g] - M) : 0.f;
-    sum += w;                                   // per lane; reduced once at the end
     const int cnt = min(64, n - base);
+    const float lv = c < n ? part_lse[(c0 + c) * group + g] : -INFINITY;
     const float2* rows = reinterpret_cast<const float2*>(part_o + ((c0 + base) * group + g) * fs::kHeadDim) + lane;
-    const int64_t stride = static_cast<int64_t>(group) * (fs::kHeadDim / 2);   // float2 units between chunk rows
-    int j = 0;
+    float2 o[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) o[u] = rows[min(u, cnt - 1) * stride];        // the batch's first rows (repeats if it has fewer)
+    const float Mb = fmaxf(M, wave_max(lv));
+    const float rescale = __expf(M - Mb);              // first batch: exp(-inf) = 0 times zero sums
+    M = Mb;
+    sum *= rescale;
+    acc.x *= rescale;
+    acc.y *= rescale;
+    const float w = c < n ? __expf(lv - M) : 0.f;
+    sum += w;                                   // per lane; reduced once at the end
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wj = u < cnt ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), u)) : 0.f;
+      acc.x = fmaf(wj, o[u].x, acc.x);
+      acc.y = fmaf(wj, o[u].y, acc.y);
+    }
+    int j = 4;
     for (; j + 4 <= cnt; j += 4) {
-      float2 o[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) o[u] = rows[(j + u) * stride];
 #pragma unroll
@@ -71,10 +85,10 @@ merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ par
       }
     }
     for (; j < cnt; ++j) {
-      const float2 o = rows[j * stride];
+      const float2 oj = rows[j * stride];
       const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j));
-      acc.x = fmaf(wj, o.x, acc.x);
-      acc.y = fmaf(wj, o.y, acc.y);
+      acc.x = fmaf(wj, oj.x, acc.x);
+      acc.y = fmaf(wj, oj.y, acc.y);
     }
   }
   sum = wave_sum(sum);
