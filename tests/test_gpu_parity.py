@@ -417,6 +417,54 @@ def test_persistent_sweep_small_batches_against_oracle():
             assert ds.claim.cpu().tolist() == [0, 0]
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_persistent_sweep_random_lists_match_the_plain_sweep(seed):
+    """Random shares with many small items (lists several times longer than the resident workgroups, every
+    group size, ragged chunks): the persistent sweep leaves the same bits as one workgroup per item, its
+    counters at zero, and the merged rows within tolerance of the oracle on a sample of pairs."""
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8, 16]))
+    R = int(rng.integers(1, 4))
+    B = int(rng.integers(20, 100))
+    chunk = int(rng.choice([16, 32, 48, 128]))
+    if seed % 2:                          # every other case: one rank, small chunks -> thousands of items
+        R, chunk, B = 1, int(rng.choice([16, 32])), max(B, 60)
+    ctx = rng.integers(1, 500, size=B).astype(np.int32)
+    mode = (rng.random(B) < 0.3).astype(np.uint8)
+    sh = fs.FsShape(B, Hkv * G, Hkv, 128, 16, R)
+    owner, dp, load = fs.fs_build_placement(sh, ctx, mode)
+    rank = int(rng.integers(0, R))
+    items, pairs, sched, indptr = fs.fs_build_worklist(sh, ctx, owner, rank, chunk)
+    say(f"random persistent seed {seed}: B={B} Hkv={Hkv} G={G} R={R} chunk={chunk} -> {len(items)} items")
+    if len(items) == 0:
+        pytest.skip("empty share")
+    q = make_q(77 + seed, B, Hkv * G, 128)
+    kv = make_kv_pool(77 + seed, np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx)
+    ds = DeviceShare(sh, q, kv, 1.0 / np.sqrt(128.0))
+    ds.set_worklist(items, pairs, sched, indptr)
+    ds.run()
+    torch.cuda.synchronize()
+    ref_part_o, ref_part_l = ds.part_o.clone(), ds.part_lse.clone()
+    ref_out, ref_lse = ds.out.clone(), ds.lse.clone()
+    for use_sched in (True, False):
+        ds.part_o.fill_(float("nan")); ds.part_lse.fill_(float("nan"))
+        ds.out.fill_(float("nan")); ds.lse.fill_(float("nan"))
+        ds.run(use_sched=use_sched, persistent=True)
+        torch.cuda.synchronize()
+        assert torch.equal(ds.part_o, ref_part_o) and torch.equal(ds.part_lse, ref_part_l)
+        assert torch.equal(ds.out, ref_out) and torch.equal(ds.lse, ref_lse)
+        assert ds.claim.cpu().tolist() == [0, 0]
+    pick = rng.choice(len(pairs), size=min(6, len(pairs)), replace=False)
+    pr = pairs_rows(pairs)
+    out, lse = ds.out.cpu().numpy(), ds.lse.cpu().numpy()
+    for p in sorted(int(x) for x in pick):
+        view = dict(kv, page_indptr=np.array([0, kv["page_indptr"][p + 1] - kv["page_indptr"][p]]),
+                    page_ids=kv["page_ids"][kv["page_indptr"][p]:kv["page_indptr"][p + 1]])
+        ref_o, ref_l = oracle.decode_attention_pairs(q, view, pr[p:p + 1], Hkv * G, G, 1.0 / np.sqrt(128.0))
+        check(out[p * G:(p + 1) * G], lse[p * G:(p + 1) * G], ref_o, ref_l, f"random persistent seed {seed} pair {p}")
+
+
 def test_persistent_sweep_config2_full_size():
     say("persistent sweep, config 2 full size")
     ds = _full_config(2, 0, 4)            # the regular form, sampled against the oracle
