@@ -354,7 +354,7 @@ __device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int 
 
 template <int WAVES, int NBUF>
 __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(const DecodeParams P, int n_items,
-                                                                            int* __restrict__ claim) {
+                                                                            int* __restrict__ claim, int n_first) {
   __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
   __shared__ float sm_m[WAVES * 16];
   __shared__ float sm_l[WAVES * 16];
@@ -381,11 +381,12 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
 
   // Two workgroups share a CU, and the one launched second streams at about half the rate of the first (the
   // issue arbiter prefers the older wavefront) while the CU's total stays the same.  A late item in its hands
-  // takes twice as long and ends the launch late, so the second half of the grid - by launch order the
-  // second workgroup of every CU - stops claiming once a quarter of the list is handed out; it is there to
-  // fill the CU while the list is long, and leaves the rest to its sibling.  (Where launch order does not map
-  // to CUs like that, half of the workgroups retire early just the same, which costs nothing measurable.)
-  const bool second_on_cu = blockIdx.x >= (gridDim.x + 1) / 2;
+  // takes twice as long and ends the launch late, so the workgroups beyond the first n_first (one per CU) -
+  // by launch order the second workgroup of a CU - stop claiming once a quarter of the list is handed out;
+  // they are there to fill the CU while the list is long, and leave the rest to their siblings.  (Where launch
+  // order does not map to CUs like that, as many workgroups retire early just the same, which costs nothing
+  // measurable.)
+  const bool second_on_cu = static_cast<int>(blockIdx.x) >= n_first;
   bool keep_claiming = true;
   int staged = 0;
   for (;;) {
@@ -747,7 +748,7 @@ extern "C" fs_status fs_decode_attention_persistent(const fs_shape* shape, const
   P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
   const int64_t groups = std::min<int64_t>(n_items, 2ll * n_cu);      // two resident workgroups per CU
   hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3>), dim3(static_cast<unsigned>(groups)), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), P, static_cast<int>(n_items), claim_dev);
+                     static_cast<hipStream_t>(stream), P, static_cast<int>(n_items), claim_dev, n_cu);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_decode_attention_persistent: launch failed: %s", hipGetErrorString(e));
   return FS_OK;
