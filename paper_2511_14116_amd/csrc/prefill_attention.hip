@@ -228,7 +228,7 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
 // The 8-wavefront, one-column-tile shape is held to 128 registers so that two workgroups (four
 // wavefronts per SIMD) share a CU: the softmax is a long dependent chain and needs the company.
 template <int WAVES, int CT, bool WIDE>
-__global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAVES == 4 && CT == 2) ? 2 : 1) prefill_bf16_kernel(const PrefillParams P) {
+__global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAVES == 4 && CT == 2) ? 2 : (WAVES == 4 && CT == 1) ? 3 : 1) prefill_bf16_kernel(const PrefillParams P) {
   constexpr int NP = 8 / WAVES;        // (K, V) block couples a wavefront moves per page pair
   static_assert(NP >= 1, "at most 8 wavefronts");
   __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
