@@ -393,16 +393,22 @@ def main() -> int:
         budget = 12_000_000                      # tok.heads: keeps this leg to some tens of seconds
         csum = np.cumsum(pr[:, 2].astype(np.int64))
         n_s = int(min(len(pr), max(1, np.searchsorted(csum, budget) + 1)))
-        t1 = time.perf_counter()
-        oo, ol = oracle.decode_attention_pairs(q_bits, kv, pr[:n_s], Hq, G, w["sm_scale"], workers=cores)
-        dt = time.perf_counter() - t1
+        times = []
+        t_leg = time.perf_counter()
+        while len(times) < 9 and (len(times) < 3 or time.perf_counter() - t_leg < 10.0):   # short samples: repeat, take the median
+            t1 = time.perf_counter()
+            oo, ol = oracle.decode_attention_pairs(q_bits, kv, pr[:n_s], Hq, G, w["sm_scale"], workers=cores)
+            times.append(time.perf_counter() - t1)
+            if times[-1] > 5.0:
+                break
+        dt = float(np.median(times))
         s_tok = int(csum[n_s - 1])
         got = out[: n_s * G].cpu().numpy().astype(np.float64)
         err_ok = bool((np.abs(got - oo) <= 2e-3 + 1e-2 * np.abs(oo)).all()
                       and (np.abs(lse[: n_s * G].cpu().numpy() - ol) <= 1e-3).all())
         cpu = {"value": round(s_tok * 2 * w["head_dim"] * elt / dt / 1e9, 4), "unit": "GB/s", "cores": cores,
                "kind": "oracle", "sample": f"first {n_s} of {n_pairs} pairs of rank {args.rank} "
-               f"({s_tok} KV-token-heads), fp64 numpy, {dt:.2f} s",
+               f"({s_tok} KV-token-heads), fp64 numpy, median of {len(times)} runs: {dt:.2f} s",
                "kv_token_heads_per_s": round(s_tok / dt, 1), "gpu_matches_oracle_on_sample": err_ok}
 
     dec_avg_ms = float(dec_ms.mean())
