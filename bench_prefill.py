@@ -16,6 +16,9 @@ import time
 import numpy as np
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
+# HBM-side bytes of one prefill_bf16_kernel launch on the default batch (rocprofv3 --pmc FETCH_SIZE x 2.000 +
+# WRITE_SIZE, see profiles/prefill_bf16_kernel_hybrid_batch_rank0.txt); other batches: not measured
+MEASURED_TRAFFIC_DEFAULT_BATCH = 217260032
 KV_CHUNK_DEFAULT = 2048            # split-K chunk of the keys a tile sees
 
 
@@ -207,7 +210,10 @@ def run(args) -> int:
         "roofline": {"bound": "mfma", "kernel": "prefill_bf16_kernel", "achieved": round(flops / (k_avg * 1e-3) / 1e12, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(flops / (k_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "algorithmic_flops_per_launch": flops, "traffic": None},
+                     "algorithmic_flops_per_launch": flops,
+                     "traffic": MEASURED_TRAFFIC_DEFAULT_BATCH if (args.prefill_queue, args.prefill_budget, args.rank, kv_chunk)
+                     == (64, 8192, 0, KV_CHUNK_DEFAULT) and fs.fs_get_option("prefill_waves") == 8
+                     and fs.fs_get_option("prefill_col_tiles") == 1 else None},
     }
     if cpu is not None:
         res["cpu_baseline"] = cpu
