@@ -8,6 +8,7 @@ attention kernel against the dense bf16 matrix-core peak.
 """
 from __future__ import annotations
 
+import gc
 import json
 import os
 import sys
@@ -107,57 +108,121 @@ def run(args) -> int:
     kv_tokens = int(sum(int(p["n_done"]) + int(p["n_new"]) for p in pairs))
 
     host_us = []
-    # The step's list goes to the GPU through pinned staging buffers (a copy from pageable memory would make the
-    # host wait for it); three sets, and a set is reused only once the upload that read it is done.
+    # The step's list is built by the library straight into pinned memory (items | sched | chunk_indptr in one
+    # blob, three blobs in rotation; a blob is reused only once the upload that read it is done) and goes
+    # to the GPU as one copy; the kernels read it from the device blob.
+    n_cap, t_cap, p_cap = len(items), len(w["chunk_indptr"]) - 1, len(pairs)
+
+    def up(x):
+        return (x + 255) & ~255
+    off_sched = up(n_cap * 32)
+    off_indptr = up(off_sched + n_cap * 4)
+    blob_bytes = up(off_indptr + (t_cap + 1) * 8)
+    dev_blob = torch.empty(blob_bytes, dtype=torch.uint8, device=dev)
     N_STAGE = 3
-    staging = [dict(items=torch.empty((len(items), 8), dtype=torch.int32, pin_memory=True),
-                    sched=torch.empty(len(items), dtype=torch.int32, pin_memory=True),
-                    indptr=torch.empty(len(w["chunk_indptr"]), dtype=torch.int64, pin_memory=True),
-                    done=None) for _ in range(N_STAGE)]
+    n_done_buf = np.ascontiguousarray(w["n_done"], dtype=np.int32)
+    n_new_buf = np.zeros(len(n_done_buf), dtype=np.int32)
+    owner_buf = np.zeros((shape.n_req, shape.n_kv_heads), dtype=np.int32)
+    staging = []
+    for _ in range(N_STAGE):
+        hb = torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True)
+        a = hb.numpy()
+        views = dict(items=a[:n_cap * 32].view(fs.PREFILL_ITEM_DTYPE), sched=a[off_sched:off_sched + n_cap * 4].view(np.int32),
+                     indptr=a[off_indptr:off_indptr + (t_cap + 1) * 8].view(np.int64),
+                     pairs=np.empty(p_cap, dtype=fs.PREFILL_PAIR_DTYPE), out_indptr=np.empty(p_cap + 1, dtype=np.int64))
+        call = fs.bind_build_prefill_worklist(shape, n_done_buf, n_new_buf, owner_buf, args.rank, w["tile"], kv_chunk,
+                                              views["items"], views["pairs"], views["sched"], views["indptr"],
+                                              views["out_indptr"])
+        staging.append(dict(host=hb, build=call))
     n_step = [0]
+    base = dev_blob.data_ptr()
+    R = w["R"]
+    entries = w["entries"].copy()
+    work = (w["prompt"] - w["n_done"]).astype(np.int64)
 
     def step(ev=None):
         t0 = time.perf_counter()
-        ww = prefill_workload(fs, queue=w["queue"], **wl)                # host side of the step (library calls)
+        # host side of the step (library calls): router, Algorithm 1, head-level placement, rank's tile list
+        entries["rank"] = fs.fs_route_requests(np.zeros(R, dtype=np.int64), work)
+        t1 = time.perf_counter()
+        take, _, _ = fs.fs_schedule_prefill(R, args.prefill_budget, args.prefill_budget // 2, entries)
+        t2 = time.perf_counter()
+        n_new_buf[...] = take
+        owner_buf[...] = fs.fs_build_placement_hybrid_heads(shape, np.maximum(n_done_buf + n_new_buf, 1), layer=0,
+                                                           route=entries["rank"])[0]
+        t3 = time.perf_counter()
         st = staging[n_step[0] % N_STAGE]
         n_step[0] += 1
-        if st["done"] is not None:
-            st["done"].synchronize()
-        st["items"].numpy()[...] = ww["items"].view(np.int32).reshape(-1, 8)
-        st["sched"].numpy()[...] = ww["sched"]
-        st["indptr"].numpy()[...] = ww["chunk_indptr"]
-        ds.prefill_items.copy_(st["items"], non_blocking=True)
-        ds.prefill_sched.copy_(st["sched"], non_blocking=True)
-        ds.prefill_chunk_indptr.copy_(st["indptr"], non_blocking=True)
-        st["done"] = torch.cuda.Event()
-        st["done"].record(stream)
-        host_us.append((time.perf_counter() - t0) * 1e6)
-        sp = stream.cuda_stream
+        st["done"].synchronize()                 # the upload that last read this blob is done
+        t4 = time.perf_counter()
+        st["build"]()
+        n_it, n_ti = st["build"].n_items.value, st["build"].n_tiles.value
+        t5 = time.perf_counter()
+        if ev is None and st["graph"] is not None and (n_it, n_ti) == st["counts"]:
+            st["graph"].replay()                 # upload, attention, merge: one launch
+            st["done"].record(stream)
+        else:
+            enqueue(st, n_it, n_ti, stream, ev)
+        t6 = time.perf_counter()
+        host_us.append([(b - a) * 1e6 for a, b in ((t0, t6), (t0, t1), (t1, t2), (t2, t3), (t3, t4), (t4, t5), (t5, t6))])
+
+    def enqueue(st, n_it, n_ti, on, ev=None):
+        sp = on.cuda_stream
+        dev_blob.copy_(st["host"], non_blocking=True)
+        st["done"].record(on)
         if ev is not None:
-            ev[0].record(stream)
-        fs.fs_prefill_attention(ds.shape, ds.view, ds.prefill_items, ds.prefill_sched, ds.n_prefill_items,
+            ev[0].record(on)
+        fs.fs_prefill_attention(ds.shape, ds.view, base, base + off_sched, n_it,
                                 ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
         if ev is not None:
-            ev[1].record(stream)
-        fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_chunk_indptr, ds.n_prefill_tiles,
+            ev[1].record(on)
+        fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, base + off_indptr, n_ti,
                         ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
         if ev is not None:
-            ev[2].record(stream)
+            ev[2].record(on)
 
-    for _ in range(args.warmup):
+    for st in staging:
+        st["done"] = torch.cuda.Event()
+        st["done"].record(stream)
+        st["graph"], st["counts"] = None, None
+    for _ in range(max(args.warmup, N_STAGE)):
         step()
     torch.cuda.synchronize()
+    # The GPU side of a step - upload of the blob, attention, merge - as one HIP graph per staging blob (the list's
+    # sizes are launch arguments, so a step whose list has other sizes than the captured one is launched eagerly).
+    if not args.no_graph:
+        cap_stream = torch.cuda.Stream()
+        for st in staging:
+            counts = (st["build"].n_items.value, st["build"].n_tiles.value)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=cap_stream):
+                dev_blob.copy_(st["host"], non_blocking=True)
+                sp = cap_stream.cuda_stream
+                fs.fs_prefill_attention(ds.shape, ds.view, base, base + off_sched, counts[0],
+                                        ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
+                fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, base + off_indptr, counts[1],
+                                ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
+            st["graph"], st["counts"] = g, counts
+        torch.cuda.synchronize()
+        for _ in range(N_STAGE):
+            step()
+        torch.cuda.synchronize()
     host_us.clear()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    EVENT_EVERY = 8          # every 8th step runs eagerly with HIP events around the kernels
+    timed = [i for i in range(args.steps) if args.no_graph or i % EVENT_EVERY == 0]
+    events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for i in timed}
     torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()             # as timeit does: a full collection in the middle of the loop is a 40 ms stall
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(events[i])
+        step(events.get(i))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    gc.enable()
     ms_per_step = wall * 1e3 / args.steps
-    k_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
-    m_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
+    k_ms = np.array([e[0].elapsed_time(e[1]) for e in events.values()])
+    m_ms = np.array([e[1].elapsed_time(e[2]) for e in events.values()])
 
     out = ds.prefill_out.cpu().numpy()
     lse = ds.prefill_lse.cpu().numpy()
@@ -202,10 +267,12 @@ def run(args) -> int:
                    "kv_chunk_tokens": kv_chunk, "batch_tokens": int(w["n_tokens"]),
                    "query_rows": rows, "kv_tokens_of_pairs": kv_tokens, "flops": flops,
                    "prefill_waves": fs.fs_get_option("prefill_waves"), "prefill_col_tiles": fs.fs_get_option("prefill_col_tiles"),
-                   "second_product": "bf16 V, weights bf16 hi+lo" if fs.fs_get_option("prefill_wide_v") else "fp16 V and weights"},
+                   "second_product": "bf16 V, weights bf16 hi+lo" if fs.fs_get_option("prefill_wide_v") else "fp16 V and weights",
+                   "launch": "eager" if args.no_graph else f"hip graph per staging blob (upload, attention, merge); every {EVENT_EVERY}th step eager with events"},
         "kernel_ms": {"prefill_avg": round(k_avg, 5), "prefill_p10": round(float(np.percentile(k_ms, 10)), 5),
                       "prefill_p90": round(float(np.percentile(k_ms, 90)), 5), "merge_avg": round(float(m_ms.mean()), 5)},
-        "host_us_per_step": {"all_avg": round(float(np.mean(host_us)), 1), **{k: round(v, 1) for k, v in w["host_us"].items()}},
+        "host_us_per_step": dict(zip(("all", "router", "scheduler", "placement", "wait_for_staging", "tile_list", "upload_enqueue"),
+                                     (round(float(v), 1) for v in np.mean(np.array(host_us), axis=0)))),
         "query_token_heads_per_s": round(rows / G / (ms_per_step * 1e-3), 1),
         "roofline": {"bound": "mfma", "kernel": "prefill_bf16_kernel", "achieved": round(flops / (k_avg * 1e-3) / 1e12, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -417,11 +417,11 @@ class BoundCall:
     same call on the same buffers every step pays only the foreign call itself afterwards.
     The arrays the pointers refer to are kept alive by the object."""
 
-    __slots__ = ("_fn", "_args", "_keep", "n_items", "n_pairs")
+    __slots__ = ("_fn", "_args", "_keep", "n_items", "n_pairs", "n_tiles")
 
-    def __init__(self, fn, args, keep, n_items=None, n_pairs=None):
+    def __init__(self, fn, args, keep, n_items=None, n_pairs=None, n_tiles=None):
         self._fn, self._args, self._keep = fn, args, keep
-        self.n_items, self.n_pairs = n_items, n_pairs
+        self.n_items, self.n_pairs, self.n_tiles = n_items, n_pairs, n_tiles
 
     def __call__(self) -> None:
         st = self._fn(*self._args)
@@ -477,6 +477,34 @@ def bind_build_worklist(shape: FsShape, ctx_len: np.ndarray, owner: np.ndarray, 
             C.c_void_p(chunk_indptr.ctypes.data), C.byref(n_items), C.byref(n_pairs))
     return BoundCall(lib.fs_build_worklist, args, (shape, ctx_len, owner, items, pairs, sched, chunk_indptr),
                      n_items, n_pairs)
+
+
+def bind_build_prefill_worklist(shape: FsShape, n_done: np.ndarray, n_new: np.ndarray, owner: np.ndarray, rank: int,
+                                tile_tokens: int, kv_chunk_tokens: int, items: np.ndarray, pairs: np.ndarray,
+                                sched: np.ndarray, chunk_indptr: np.ndarray, out_indptr: np.ndarray) -> BoundCall:
+    """fs_build_prefill_worklist into caller-held arrays (e.g. views of pinned memory); the inputs are read
+    from the given arrays at every call.  After a call the counts are in .n_items.value, .n_pairs.value
+    and .n_tiles.value; a list that outgrows the arrays raises FsError (FS_ECAPACITY)."""
+    lib = load_library()
+    for a in (n_done, n_new, owner, sched):
+        if a.dtype != np.int32 or not a.flags.c_contiguous:
+            raise TypeError("bind_build_prefill_worklist needs contiguous int32 n_done, n_new, owner and sched")
+    for a in (chunk_indptr, out_indptr):
+        if a.dtype != np.int64 or not a.flags.c_contiguous:
+            raise TypeError("bind_build_prefill_worklist needs contiguous int64 chunk_indptr and out_indptr")
+    if items.dtype != PREFILL_ITEM_DTYPE or pairs.dtype != PREFILL_PAIR_DTYPE or len(sched) != len(items):
+        raise TypeError("bind_build_prefill_worklist: items, pairs and sched do not match the documented layouts")
+    if len(out_indptr) != len(pairs) + 1 or len(chunk_indptr) < 1:
+        raise ValueError("bind_build_prefill_worklist: out_indptr needs len(pairs)+1 entries, chunk_indptr at least one")
+    i32p = C.POINTER(C.c_int32)
+    n_items, n_pairs, n_tiles = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    args = (C.byref(shape), n_done.ctypes.data_as(i32p), n_new.ctypes.data_as(i32p), owner.ctypes.data_as(i32p),
+            C.c_int32(rank), C.c_int32(tile_tokens), C.c_int32(kv_chunk_tokens),
+            C.c_void_p(items.ctypes.data), C.c_int64(len(items)), C.c_void_p(pairs.ctypes.data), C.c_int64(len(pairs)),
+            C.c_void_p(sched.ctypes.data), C.c_void_p(chunk_indptr.ctypes.data), C.c_int64(len(chunk_indptr) - 1),
+            C.c_void_p(out_indptr.ctypes.data), C.byref(n_items), C.byref(n_pairs), C.byref(n_tiles))
+    return BoundCall(lib.fs_build_prefill_worklist, args,
+                     (shape, n_done, n_new, owner, items, pairs, sched, chunk_indptr, out_indptr), n_items, n_pairs, n_tiles)
 
 
 def bind_decode_attention(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int,

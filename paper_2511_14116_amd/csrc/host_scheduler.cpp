@@ -6,6 +6,7 @@
 // least-loaded rank that still has schedulable tokens, then picks the best of the batches
 // it passed through.  What the paper leaves open (the token cost, the choice among the
 // candidates, the unused workload input) is fixed as the header states.
+#include <algorithm>
 #include <cstddef>
 #include <cstdint>
 #include <limits>
@@ -98,27 +99,74 @@ fs_status schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens, 
   // A rank whose S_r is empty is priced at the largest load so that the search below needs no test per
   // rank; the loop ends after `most` tokens, which is exactly when every S_r is empty or the budget is spent.
   constexpr int64_t kEmpty = std::numeric_limits<int64_t>::max();
-  std::vector<int64_t> key(R);
-  for (int32_t r = 0; r < R; ++r) key[r] = cur[r] >= 0 ? L[r] : kEmpty;
-  for (size_t n_taken = 0; n_taken < most; ++n_taken) {
-    int32_t rs = 0;
-    int64_t least = key[0];
-    for (int32_t r = 1; r < R; ++r) {          // strict: equal loads keep the lowest rank
-      const bool lt = key[r] < least;
-      least = lt ? key[r] : least;
-      rs = lt ? r : rs;
-    }
-    const fs_prefill_entry& q = entries[cur[rs]];
-    const int64_t cost = static_cast<int64_t>(q.n_done) + cur_taken[rs] + 1;   // keys this token attends to
-    L[rs] += cost;
-    sum += cost;
-    if (L[rs] > mx) mx = L[rs];
-    if (++cur_taken[rs] == q.n_new) { cur[rs] = next[cur[rs]]; cur_taken[rs] = 0; }
-    key[rs] = cur[rs] >= 0 ? L[rs] : kEmpty;
+  auto record = [&](size_t n_taken, int32_t rs) {
     if (small_r) took_from8[n_taken] = static_cast<uint8_t>(rs); else took_from32[n_taken] = rs;
     if (n_taken >= first_cand) {
       cand_max[n_taken - first_cand] = mx;
       cand_sum[n_taken - first_cand] = sum;
+    }
+  };
+  // Up to 8 ranks (a node) with loads that leave three bits to spare: load and rank travel as one key,
+  // load*8 + rank, so the least key is the least load and, among equals, the lowest rank; the eight keys
+  // stay in registers and the search is a tree of seven minima.  Same picks as the general loop below.
+  constexpr int kPack = 8;
+  bool packed = R <= kPack;
+  if (packed) {
+    int64_t top = 0, dearest = 0;
+    for (int32_t r = 0; r < R; ++r) { if (L[r] < 0) packed = false; if (L[r] > top) top = L[r]; }
+    for (int32_t e = 0; e < n_entries; ++e)
+      dearest = std::max<int64_t>(dearest, static_cast<int64_t>(entries[e].n_done) + entries[e].n_new);
+    // no load can pass top + most * dearest
+    if (dearest > 0 && static_cast<int64_t>(most) > ((int64_t{1} << 59) - top) / dearest) packed = false;
+  }
+  if (packed) {
+    int64_t k[kPack], cost[kPack], left[kPack];
+    for (int32_t r = 0; r < kPack; ++r) {
+      const bool has = r < R && cur[r] >= 0;
+      k[r] = has ? L[r] * kPack + r : kEmpty;
+      cost[r] = has ? static_cast<int64_t>(entries[cur[r]].n_done) + 1 : 0;   // keys the rank's next token attends to
+      left[r] = has ? entries[cur[r]].n_new : 0;                             // tokens left in the entry at the head of S_r
+    }
+    for (size_t n_taken = 0; n_taken < most; ++n_taken) {
+      const int64_t a = std::min(std::min(k[0], k[1]), std::min(k[2], k[3]));
+      const int64_t b = std::min(std::min(k[4], k[5]), std::min(k[6], k[7]));
+      const int64_t least = std::min(a, b);
+      const int32_t rs = static_cast<int32_t>(least & (kPack - 1));
+      const int64_t c = cost[rs];
+      const int64_t grown = least / kPack + c;
+      sum += c;
+      if (grown > mx) mx = grown;
+      cost[rs] = c + 1;
+      bool has = true;
+      if (--left[rs] == 0) {                      // the entry is used up: S_r goes on with the rank's next one
+        const int32_t e = next[cur[rs]];
+        cur[rs] = e;
+        has = e >= 0;
+        if (has) { cost[rs] = static_cast<int64_t>(entries[e].n_done) + 1; left[rs] = entries[e].n_new; }
+      }
+      const int64_t key_now = has ? grown * kPack + rs : kEmpty;
+      for (int32_t r = 0; r < kPack; ++r) k[r] = r == rs ? key_now : k[r];
+      record(n_taken, rs);
+    }
+  } else {
+    std::vector<int64_t> key(R);
+    for (int32_t r = 0; r < R; ++r) key[r] = cur[r] >= 0 ? L[r] : kEmpty;
+    for (size_t n_taken = 0; n_taken < most; ++n_taken) {
+      int32_t rs = 0;
+      int64_t least = key[0];
+      for (int32_t r = 1; r < R; ++r) {          // strict: equal loads keep the lowest rank
+        const bool lt = key[r] < least;
+        least = lt ? key[r] : least;
+        rs = lt ? r : rs;
+      }
+      const fs_prefill_entry& q = entries[cur[rs]];
+      const int64_t cost = static_cast<int64_t>(q.n_done) + cur_taken[rs] + 1;   // keys this token attends to
+      L[rs] += cost;
+      sum += cost;
+      if (L[rs] > mx) mx = L[rs];
+      if (++cur_taken[rs] == q.n_new) { cur[rs] = next[cur[rs]]; cur_taken[rs] = 0; }
+      key[rs] = cur[rs] >= 0 ? L[rs] : kEmpty;
+      record(n_taken, rs);
     }
   }
 

@@ -5,20 +5,21 @@
 // is exact algebra on the partial (out, lse) pairs:
 //     lse = ln sum_c exp(lse_c),   out = sum_c exp(lse_c - lse) * o_c.
 //
-// One wavefront per output row (pair, q-head).  The row's chunk lse values are read 64 at a time,
-// one per lane, and reduced across the wavefront, so a pair cut into many chunks (a 131072-token
-// context in 1024-token chunks has 128) costs a wide load per 64 chunks instead of a serial chain.
-// For the rows themselves a lane owns two of the 128 columns (one coalesced 512-byte read per
-// chunk), four chunk rows are in flight at a time, and the first four are requested together with
-// the lse values, before the weights are known.  For decode the traffic is under 1% of the
-// attention sweep's; for chunked prefill (a tile's rows per chunk) it is a sixth of the kernel time.
+// One wavefront per output row (pair, q-head), or per four consecutive rows of a pair when the group
+// is a multiple of four.  A row's chunk lse values are read 64 at a time, one per lane, and reduced
+// across the wavefront, so a pair cut into many chunks (a 131072-token context in 1024-token chunks
+// has 128) costs a wide load per 64 chunks instead of a serial chain.  For the rows themselves a lane
+// owns two of the 128 columns (one coalesced 512-byte read per chunk row), four chunk rows (two per
+// output row in the four-row form: eight) are in flight at a time, and the first ones are requested
+// together with the lse values, before the weights are known.  For decode the traffic is under 1% of
+// the attention sweep's; for chunked prefill (a tile's rows per chunk) it is a sixth of the kernel time.
 #include <hip/hip_runtime.h>
 
 #include "fs_internal.h"
 
 namespace {
 
-constexpr int kRowsPerBlock = 4;
+constexpr int kWavesPerBlock = 4;
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -31,70 +32,100 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-__global__ void __launch_bounds__(kRowsPerBlock * 64)
+// RW output rows per wavefront (consecutive rows of one pair, so group must be a multiple of RW): with many
+// rows of few chunks each (a prefill tile's 128 rows, most tiles a single chunk) a wavefront with one row is
+// a chain of three dependent loads and nothing else; four rows side by side keep four times the bytes in flight.
+// The arithmetic of a row is the same for every RW, operation for operation.
+template <int RW>
+__global__ void __launch_bounds__(kWavesPerBlock * 64)
 merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ part_lse,
                  const int64_t* __restrict__ chunk_indptr, int64_t n_rows, int group,
                  float* __restrict__ out, float* __restrict__ lse) {
+  constexpr int U = RW == 1 ? 4 : 2;               // chunk rows in flight per output row
   const int lane = threadIdx.x & 63;
-  const int64_t row = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock +
-                      __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  if (row >= n_rows) return;
-  const int64_t p = row / group;
-  const int g = static_cast<int>(row - p * group);
+  const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock +
+                        __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * RW;
+  if (row0 >= n_rows) return;
+  const int64_t p = row0 / group;
+  const int g0 = static_cast<int>(row0 - p * group);
   const int64_t c0 = chunk_indptr[p];
   const int n = static_cast<int>(chunk_indptr[p + 1] - c0);
 
   // Chunks are taken 64 at a time (one lse per lane).  The first rows of a batch are requested before
   // its weights are known, so the two reads travel together; across batches (more than 64 chunks) the
   // running maximum moves and what has been summed is rescaled, as in an online softmax.
-  float M = -INFINITY;
-  float sum = 0.f;
-  float2 acc = make_float2(0.f, 0.f);
+  float M[RW], sum[RW];
+  float2 acc[RW];
+#pragma unroll
+  for (int r = 0; r < RW; ++r) { M[r] = -INFINITY; sum[r] = 0.f; acc[r] = make_float2(0.f, 0.f); }
   const int64_t stride = static_cast<int64_t>(group) * (fs::kHeadDim / 2);   // float2 units between chunk rows
   for (int base = 0; base < n; base += 64) {
     const int c = base + lane;
     const int cnt = min(64, n - base);
-    const float lv = c < n ? part_lse[(c0 + c) * group + g] : -INFINITY;
-    const float2* rows = reinterpret_cast<const float2*>(part_o + ((c0 + base) * group + g) * fs::kHeadDim) + lane;
-    float2 o[4];
+    float lv[RW];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) o[u] = rows[min(u, cnt - 1) * stride];        // the batch's first rows (repeats if it has fewer)
-    const float Mb = fmaxf(M, wave_max(lv));
-    const float rescale = __expf(M - Mb);              // first batch: exp(-inf) = 0 times zero sums
-    M = Mb;
-    sum *= rescale;
-    acc.x *= rescale;
-    acc.y *= rescale;
-    const float w = c < n ? __expf(lv - M) : 0.f;
-    sum += w;                                   // per lane; reduced once at the end
+    for (int r = 0; r < RW; ++r) lv[r] = c < n ? part_lse[(c0 + c) * group + g0 + r] : -INFINITY;
+    // row r of chunk base+j: rows[j * stride + r * 64]
+    const float2* rows = reinterpret_cast<const float2*>(part_o + ((c0 + base) * group + g0) * fs::kHeadDim) + lane;
+    float2 o[U][RW];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const float wj = u < cnt ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), u)) : 0.f;
-      acc.x = fmaf(wj, o[u].x, acc.x);
-      acc.y = fmaf(wj, o[u].y, acc.y);
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int r = 0; r < RW; ++r) o[u][r] = rows[min(u, cnt - 1) * stride + r * 64];   // the batch's first rows (repeats if it has fewer)
+    float w[RW];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+      const float Mb = fmaxf(M[r], wave_max(lv[r]));
+      const float rescale = __expf(M[r] - Mb);          // first batch: exp(-inf) = 0 times zero sums
+      M[r] = Mb;
+      sum[r] *= rescale;
+      acc[r].x *= rescale;
+      acc[r].y *= rescale;
+      w[r] = c < n ? __expf(lv[r] - Mb) : 0.f;
+      sum[r] += w[r];                             // per lane; reduced once at the end
     }
-    int j = 4;
-    for (; j + 4 <= cnt; j += 4) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) o[u] = rows[(j + u) * stride];
+    for (int u = 0; u < U; ++u) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j + u));
-        acc.x = fmaf(wj, o[u].x, acc.x);
-        acc.y = fmaf(wj, o[u].y, acc.y);
+      for (int r = 0; r < RW; ++r) {
+        const float wj = u < cnt ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w[r]), u)) : 0.f;
+        acc[r].x = fmaf(wj, o[u][r].x, acc[r].x);
+        acc[r].y = fmaf(wj, o[u][r].y, acc[r].y);
+      }
+    }
+    int j = U;
+    for (; j + U <= cnt; j += U) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < RW; ++r) o[u][r] = rows[(j + u) * stride + r * 64];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+          const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w[r]), j + u));
+          acc[r].x = fmaf(wj, o[u][r].x, acc[r].x);
+          acc[r].y = fmaf(wj, o[u][r].y, acc[r].y);
+        }
       }
     }
     for (; j < cnt; ++j) {
-      const float2 oj = rows[j * stride];
-      const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j));
-      acc.x = fmaf(wj, oj.x, acc.x);
-      acc.y = fmaf(wj, oj.y, acc.y);
+#pragma unroll
+      for (int r = 0; r < RW; ++r) {
+        const float2 oj = rows[j * stride + r * 64];
+        const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w[r]), j));
+        acc[r].x = fmaf(wj, oj.x, acc[r].x);
+        acc[r].y = fmaf(wj, oj.y, acc[r].y);
+      }
     }
   }
-  sum = wave_sum(sum);
-  const float inv = 1.0f / sum;
-  reinterpret_cast<float2*>(out + row * fs::kHeadDim)[lane] = make_float2(acc.x * inv, acc.y * inv);
-  if (lane == 0) lse[row] = M + __logf(sum);
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const float total = wave_sum(sum[r]);
+    const float inv = 1.0f / total;
+    reinterpret_cast<float2*>(out + (row0 + r) * fs::kHeadDim)[lane] = make_float2(acc[r].x * inv, acc[r].y * inv);
+    if (lane == 0) lse[row0 + r] = M[r] + __logf(total);
+  }
 }
 
 }  // namespace
@@ -111,9 +142,17 @@ extern "C" fs_status fs_merge_lse(const float* part_o, const float* part_lse, co
   if (!part_o || !part_lse || !chunk_indptr_dev || !out || !lse)
     return fs::fail(FS_EINVAL, "fs_merge_lse: NULL device pointer");
   const int64_t n_rows = n_pairs * group;
-  const unsigned blocks = static_cast<unsigned>((n_rows + kRowsPerBlock - 1) / kRowsPerBlock);
-  hipLaunchKernelGGL(merge_lse_kernel, dim3(blocks), dim3(kRowsPerBlock * 64), 0,
-                     static_cast<hipStream_t>(stream), part_o, part_lse, chunk_indptr_dev, n_rows, group, out, lse);
+  // Output rows per wavefront (within one pair): four once one row each would be more wavefronts than the
+  // chip holds at a time (256 CUs x 32); below that, more wavefronts is what hides the latency.
+  const int rw = group % 4 == 0 && n_rows > 8192 ? 4 : 1;
+  const int64_t per_block = static_cast<int64_t>(kWavesPerBlock) * rw;
+  const unsigned blocks = static_cast<unsigned>((n_rows + per_block - 1) / per_block);
+  if (rw == 4)
+    hipLaunchKernelGGL(merge_lse_kernel<4>, dim3(blocks), dim3(kWavesPerBlock * 64), 0,
+                       static_cast<hipStream_t>(stream), part_o, part_lse, chunk_indptr_dev, n_rows, group, out, lse);
+  else
+    hipLaunchKernelGGL(merge_lse_kernel<1>, dim3(blocks), dim3(kWavesPerBlock * 64), 0,
+                       static_cast<hipStream_t>(stream), part_o, part_lse, chunk_indptr_dev, n_rows, group, out, lse);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_merge_lse: launch failed: %s", hipGetErrorString(e));
   return FS_OK;

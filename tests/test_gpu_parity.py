@@ -182,6 +182,26 @@ def test_merge_with_widely_spread_lse():
     check(out.cpu().numpy(), lse.cpu().numpy(), mo, ml, "merge, spread lse")
 
 
+@pytest.mark.parametrize("G,n_pairs", [(8, 1100), (4, 2100), (128, 70), (6, 1500)])
+def test_merge_of_many_rows(G, n_pairs):
+    """More rows than the chip holds wavefronts: groups that are a multiple of four go four rows to a
+    wavefront (the others one), with pairs of one chunk, of a few, and of more than 64."""
+    rng = np.random.default_rng(600 + G)
+    counts = rng.choice([1, 1, 1, 2, 3, 7], size=n_pairs)
+    counts[rng.integers(0, n_pairs, size=3)] = [65, 70, 130]
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    n_items = int(indptr[-1])
+    assert n_pairs * G > 8192
+    po = rng.standard_normal((n_items * G, 128)).astype(np.float32)
+    pl = (rng.standard_normal(n_items * G) * 6).astype(np.float32)
+    out = torch.empty((n_pairs * G, 128), dtype=torch.float32, device="cuda"); lse = torch.empty(n_pairs * G, dtype=torch.float32, device="cuda")
+    fs.fs_merge_lse(torch.from_numpy(po).cuda(), torch.from_numpy(pl).cuda(), torch.from_numpy(indptr).cuda(),
+                    n_pairs, G, 128, out, lse, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    mo, ml = oracle.merge_lse(po.astype(np.float64), pl.astype(np.float64), indptr, G)
+    check(out.cpu().numpy(), lse.cpu().numpy(), mo, ml, f"merge, many rows, G={G}")
+
+
 def test_single_key_closed_form_and_layout_variants():
     """L = 1: out is the V row exactly (weight 1.0 is exact in bf16) and lse is the score; the same
     share gives the same bits with K/V interleaved or in two pools, scheduled or in index order."""

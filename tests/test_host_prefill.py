@@ -66,3 +66,37 @@ def test_tile_tokens_and_errors():
         fs.fs_build_prefill_worklist(shape, [0], [5], [[0, 1]], 0, 4, 48)    # chunk not a multiple of 32
     items, pairs, sched, chunks, out = fs.fs_build_prefill_worklist(shape, [9], [0], [[0, 1]], 0, 4)
     assert len(items) == 0 and len(pairs) == 0 and chunks.tolist() == [0] and out.tolist() == [0]
+
+
+def test_bound_builder_fills_caller_arrays_and_follows_its_inputs():
+    """The pre-marshalled call writes the same list into caller-held arrays, reads its inputs anew at every
+    call, and reports a list that outgrows the arrays."""
+    rng = np.random.default_rng(77)
+    B, Hkv, G, R, tile, chunk = 6, 4, 2, 3, 8, 64
+    shape = fs.FsShape(B, Hkv * G, Hkv, 128, 16, R)
+    n_done = rng.integers(0, 400, size=B).astype(np.int32)
+    n_new = rng.integers(1, 60, size=B).astype(np.int32)
+    owner = rng.integers(0, R, size=(B, Hkv)).astype(np.int32)
+    ref = fs.fs_build_prefill_worklist(shape, n_done, n_new, owner, 1, tile, chunk)
+    cap_i, cap_p, cap_t = len(ref[0]) + 5, len(ref[1]) + 2, len(ref[3]) - 1 + 3
+    items = np.zeros(cap_i, dtype=fs.PREFILL_ITEM_DTYPE)
+    pairs = np.zeros(cap_p, dtype=fs.PREFILL_PAIR_DTYPE)
+    sched = np.zeros(cap_i, dtype=np.int32)
+    chunks = np.zeros(cap_t + 1, dtype=np.int64)
+    out = np.zeros(cap_p + 1, dtype=np.int64)
+    call = fs.bind_build_prefill_worklist(shape, n_done, n_new, owner, 1, tile, chunk, items, pairs, sched, chunks, out)
+    for _ in range(2):
+        call()
+        ni, npairs, nt = call.n_items.value, call.n_pairs.value, call.n_tiles.value
+        assert (ni, npairs, nt) == (len(ref[0]), len(ref[1]), len(ref[3]) - 1)
+        assert items[:ni].tobytes() == ref[0].tobytes() and pairs[:npairs].tobytes() == ref[1].tobytes()
+        assert sched[:ni].tobytes() == ref[2].tobytes() and chunks[:nt + 1].tobytes() == ref[3].tobytes()
+        assert out[:npairs + 1].tobytes() == ref[4].tobytes()
+        n_new[0] += 3                                        # the next call sees the changed input
+        ref = fs.fs_build_prefill_worklist(shape, n_done, n_new, owner, 1, tile, chunk)
+    n_new[:] = 5000                                          # far more tiles than the arrays hold
+    with pytest.raises(fs.FsError) as e:
+        call()
+    assert e.value.status == fs.FS_ECAPACITY
+    with pytest.raises(TypeError):
+        fs.bind_build_prefill_worklist(shape, n_done.astype(np.int64), n_new, owner, 1, tile, chunk, items, pairs, sched, chunks, out)
