@@ -89,7 +89,7 @@ int main() {
   }
   // router and prefill scheduler: exactly-sized arrays, token conservation, budget respected
   for (g_case = 1000; g_case < 1300; ++g_case) {
-    const int R = 1 + rng() % 8, n = rng() % 12;
+    const int R = 1 + rng() % 12, n = rng() % 12;   // up to 8 ranks: packed keys; beyond: the linear search
     std::vector<int64_t> pending(R, 0);
     std::vector<fs_prefill_entry> ent(n);
     int64_t waiting = 0;

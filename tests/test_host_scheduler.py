@@ -48,6 +48,30 @@ def test_scheduler_matches_oracle_on_random_queues(seed):
     assert take.tolist() == want[0] and load.tolist() == list(want[1]) and n_tok == want[2]
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_scheduler_search_forms_agree_with_the_oracle(seed):
+    """Up to 8 ranks with modest non-negative loads the library searches packed (load, rank) keys; more
+    ranks, a negative starting load or loads near 2^59 take the linear search.  Both against the oracle,
+    on queues full of equal loads (ties go to the lowest rank) and of ranks that run dry."""
+    rng = np.random.default_rng(7000 + seed)
+    kind = seed % 4
+    R = int(rng.integers(9, 21)) if kind == 0 else int(rng.integers(1, 9))
+    n = int(rng.integers(1, 20))
+    entries = [(i, int(rng.integers(0, R)), int(rng.choice([0, 0, 7, 512])), int(rng.integers(0, 12))) for i in range(n)]
+    budget = int(rng.integers(1, 120))
+    min_tokens = int(rng.integers(0, budget + 1))
+    init = None
+    if kind == 1:
+        init = [int(x) for x in rng.integers(-50, 50, size=R)]            # a negative load: linear search
+    elif kind == 2:
+        init = [int(x) for x in (1 << 59) + rng.integers(0, 3, size=R)]   # no room for the rank bits: linear search
+    elif kind == 3:
+        init = [int(x) for x in rng.integers(0, 2, size=R)]               # packed keys, nearly all equal
+    want = adaptive_chunked_prefill(budget, R, entries, min_tokens, init)
+    take, load, n_tok = fs.fs_schedule_prefill(R, budget, min_tokens, entries, init)
+    assert take.tolist() == want[0] and load.tolist() == list(want[1]) and n_tok == want[2]
+
+
 def test_router_matches_oracle():
     rng = np.random.default_rng(5)
     for R in (1, 3, 7):
