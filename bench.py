@@ -57,6 +57,7 @@ def main() -> int:
     ap.add_argument("--cold", action="store_true", help="also time the kernels with L2 and the memory-side cache scrubbed before every launch")
     ap.add_argument("--all-ranks", action="store_true", help="also time every rank's share in turn (kernels only) and report the spread")
     ap.add_argument("--force-tail", action="store_true", help="config 3: request 0 gets 131072 tokens")
+    ap.add_argument("--seed", type=int, default=None, help="draw the batch from this seed instead of the config's own")
     ap.add_argument("--path", choices=["decode", "prefill"], default="decode",
                     help="decode: the measured decode-attention share (default); prefill: the chunked-prefill attention share")
     ap.add_argument("--prefill-waves", type=int, default=None)
@@ -99,7 +100,7 @@ def main() -> int:
 
     # ---- synthetic batch ---------------------------------------------------------------------
     kw = dict(force_first_len=131072) if (args.config == 3 and args.force_tail) else {}
-    w = make_requests(args.config, **kw)
+    w = make_requests(args.config, seed=args.seed, **kw)
     MIN_CHUNK = 256          # floor of the adaptive split-K chunk (tokens)
     B, Hq, Hkv, R, G = w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"], w["group"]
     shape = fs.FsShape(B, Hq, Hkv, w["head_dim"], w["page_tokens"], R)
