@@ -404,13 +404,20 @@ def main() -> int:
                 break
         dt = float(np.median(times))
         s_tok = int(csum[n_s - 1])
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):        # the same sample on one core: one worker, single-threaded BLAS
+            t1 = time.perf_counter()
+            oracle.decode_attention_pairs(q_bits, kv, pr[:n_s], Hq, G, w["sm_scale"], workers=1)
+            dt_one = time.perf_counter() - t1
         got = out[: n_s * G].cpu().numpy().astype(np.float64)
         err_ok = bool((np.abs(got - oo) <= 2e-3 + 1e-2 * np.abs(oo)).all()
                       and (np.abs(lse[: n_s * G].cpu().numpy() - ol) <= 1e-3).all())
         cpu = {"value": round(s_tok * 2 * w["head_dim"] * elt / dt / 1e9, 4), "unit": "GB/s", "cores": cores,
                "kind": "oracle", "sample": f"first {n_s} of {n_pairs} pairs of rank {args.rank} "
                f"({s_tok} KV-token-heads), fp64 numpy, median of {len(times)} runs: {dt:.2f} s",
-               "kv_token_heads_per_s": round(s_tok / dt, 1), "gpu_matches_oracle_on_sample": err_ok}
+               "kv_token_heads_per_s": round(s_tok / dt, 1), "gpu_matches_oracle_on_sample": err_ok,
+               "one_core": {"value": round(s_tok * 2 * w["head_dim"] * elt / dt_one / 1e9, 4), "unit": "GB/s",
+                            "seconds": round(dt_one, 2)}}
 
     dec_avg_ms = float(dec_ms.mean())
     achieved = decode_bytes / (dec_avg_ms * 1e-3) / 1e9
