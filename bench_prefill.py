@@ -19,7 +19,7 @@ import numpy as np
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # HBM-side bytes of one prefill_bf16_kernel launch on the default batch (rocprofv3 --pmc FETCH_SIZE x 2.000 +
 # WRITE_SIZE, see profiles/prefill_bf16_kernel_hybrid_batch_rank0.txt); other batches: not measured
-MEASURED_TRAFFIC_DEFAULT_BATCH = 208407450
+MEASURED_TRAFFIC_DEFAULT_BATCH = 217260032
 KV_CHUNK_DEFAULT = 2048            # split-K chunk of the keys a tile sees
 
 

@@ -10,10 +10,9 @@
 // split-K chunk of the keys the tile sees.  A query row is a (token, q-head of the group)
 // combination; 16 rows form a column tile of the transposed score matrix and every wavefront
 // owns CT column tiles.  The workgroup walks the chunk in pairs of KV pages (32 tokens):
-//   * every wavefront fetches its share of the next pairs from global memory, so the whole workgroup
-//     reads each page from L2/HBM once: K straight into one of four LDS stages (`buffer_load ... lds`,
-//     no registers, three pairs ahead), V into registers (two pairs in flight) and from there, converted,
-//     into a double-buffered LDS stage;
+//   * every wavefront fetches its share of the next pairs from global memory into registers (two
+//     pairs in flight) and copies it into a double-buffered LDS stage, so the whole workgroup
+//     reads each page from L2/HBM once;
 //   * from LDS every wavefront takes the K operands (16-byte reads, conflict-free), and for each
 //     of its column tiles
 //         S^T[tok][row] = K . Q^T        2 x 4 v_mfma_f32_16x16x32_bf16
@@ -62,16 +61,15 @@ struct PrefillParams {
 };
 
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kKStageBytes = 8192;     // K of one pair of pages: K0, K1 (4 KiB each), in slot order
-constexpr int kKStages = 4;            // pair j computes from stage j%4 while pairs j+1..j+3 land in the others
-constexpr int kVStageBytes = 8192;     // V of one pair of pages: the paired halves (2 x 4 KiB)
-constexpr int kVaOffset = 0;           // V rows d = 32c + lane%16:      (page 0 tokens 4kb..+3 | page 1 tokens 4kb..+3)
-constexpr int kVbOffset = 4096;        // V rows d = 32c + 16 + lane%16: likewise
+constexpr int kStageBytes = 16384;     // one pair of pages: K0, K1 (4 KiB each), then the paired V halves (2 x 4 KiB)
+constexpr int kVaOffset = 8192;        // V rows d = 32c + lane%16:      (page 0 tokens 4kb..+3 | page 1 tokens 4kb..+3)
+constexpr int kVbOffset = 12288;       // V rows d = 32c + 16 + lane%16: likewise
 
-// A wavefront's share of the V of one page pair on its way from global memory to LDS: NP blocks of
-// 1 KiB, each from one page h and one 32-d block c (the K block of the same (h, c) goes to LDS directly).
+// A wavefront's share of one page pair on its way from global memory to LDS: NP (K block, V block)
+// couples of 1 KiB, each couple from one page h and one 32-d block c.
 template <int NP>
 struct InFlight {
+  u32x4 k[NP];
   u32x4 v[NP];
 };
 
@@ -233,8 +231,7 @@ template <int WAVES, int CT, bool WIDE>
 __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAVES == 4 && CT == 2) ? 2 : (WAVES == 4 && CT == 1) ? 3 : 1) prefill_bf16_kernel(const PrefillParams P) {
   constexpr int NP = 8 / WAVES;        // (K, V) block couples a wavefront moves per page pair
   static_assert(NP >= 1, "at most 8 wavefronts");
-  __shared__ __attribute__((aligned(16))) unsigned char kst[kKStages][kKStageBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char vst[2][kVStageBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
 
   const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
   const fs_prefill_item it = P.items[item_idx];
@@ -285,7 +282,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     for (int j = 0; j < 8; ++j) st[t].acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // ---- global -> LDS (K) and registers (V): this wavefront's blocks of pair jp ------------------
+  // ---- global -> registers: this wavefront's couples of pair jp ---------------------------------
   auto fetch = [&](InFlight<NP>& r, int jp) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
@@ -297,32 +294,17 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
       // a slot as a raw buffer: its base stays in scalar registers, the lane's place in it is one 32-bit
       // offset (64-bit vector addresses cost this kernel registers it does not have)
       const int64_t slot = ids[page];
-      {
-        // K block (h, c) straight into its place in stage jp%4: the hardware writes lane l's 16 bytes at
-        // m0 + 16*l, which is the slot's own order.  Issued as text: the compiler would tie a load into
-        // LDS to every later LDS read and barrier through its wait counters; here the wait for the V
-        // block below, which is issued after it and counted in order, covers it.
-        const uint64_t a = reinterpret_cast<uint64_t>(P.k_pool + slot * P.k_stride);
-        const u32x4 rsrc = {static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a))),
-                            static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32))),
-                            4096u, 0x00020000u /* raw 32-bit data format */};
-        const uint32_t lds_at = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(
-            reinterpret_cast<uintptr_t>(kst[jp % kKStages] + (h * 4 + c) * 1024)));
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"   // m0 is a reserved register; naming it is the point
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                     :: "s"(lds_at), "v"((c * 64 + lane) * 16), "s"(rsrc) : "memory", "m0");
-#pragma clang diagnostic pop
-      }
+      r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.k_pool + slot * P.k_stride), (c * 64 + lane) * 16, 0, 0);
       r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.v_pool + slot * P.v_stride), (c * 64 + lane) * 16, 0, 0);
     }
   };
-  // ---- V: registers -> LDS stage s ---------------------------------------------------------------
+  // ---- registers -> LDS stage s ------------------------------------------------------------------
   auto deposit = [&](int s, const InFlight<NP>& r, int jp) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
-      unsigned char* base = vst[s];
+      unsigned char* base = stage[s];
+      *reinterpret_cast<u32x4*>(base + ((h * 4 + c) * 64 + lane) * 16) = r.k[i];
       u32x4 v = r.v[i];
       if constexpr (!WIDE) v = u32x4{bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w)};
       // value rows of tokens at or beyond the item's end may hold anything (the unused tail of a last
@@ -337,7 +319,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
       *reinterpret_cast<uint2*>(base + kVbOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(v.z, v.w);
     }
   };
-  // ---- page pair jp (K in stage jp%4, V in stage s) against this wavefront's column tiles ---------
+  // ---- one page pair from LDS stage s against this wavefront's column tiles -----------------------
   auto compute = [&](int s, int jp) __attribute__((always_inline)) {
     if (!wave_live) return;
     const int t0 = it.kv_begin + 32 * jp;                 // first token of the pair
@@ -352,16 +334,15 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
       any |= need[t];
     }
     if (!any) return;
-    const unsigned char* base = vst[s];
-    const unsigned char* kbase = kst[jp % kKStages];
+    const unsigned char* base = stage[s];
     f32x4 sa[CT], sb[CT];
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     {
       u32x4 k0[4], k1[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        k0[c] = *reinterpret_cast<const u32x4*>(kbase + (c * 64 + lane) * 16);
-        k1[c] = *reinterpret_cast<const u32x4*>(kbase + ((4 + c) * 64 + lane) * 16);
+        k0[c] = *reinterpret_cast<const u32x4*>(base + (c * 64 + lane) * 16);
+        k1[c] = *reinterpret_cast<const u32x4*>(base + ((4 + c) * 64 + lane) * 16);
       }
 #pragma unroll
       for (int t = 0; t < CT; ++t) {
@@ -388,11 +369,9 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     }
   };
 
-  // ---- the walk: pair j is computed from V stage j%2 and K stage j%4 while the V of pair j+1 is copied
-  // into the other V stage and pairs j+2, j+3 are on their way from global memory (their K into the K
-  // stages that pairs j-2 and j-1 have left).  One barrier per pair: after it, pair j+1 is complete in LDS
-  // (a wavefront's wait for its V block of pair j+1 also covers its K block, issued before it) and nobody
-  // reads the stages of pair j any more.  Every wavefront takes every branch below (n_it is the
+  // ---- the walk: pair j is computed from stage j%2 while pair j+1 is copied into the other stage and
+  // pairs j+2, j+3 are on their way from global memory.  One barrier per pair: after it, stage (j+1)%2 is
+  // complete and nobody reads stage j%2 any more.  Every wavefront takes every branch below (n_it is the
   // workgroup's), so the barriers match.
   if (n_it < 1) return;        // not produced by the list builder (an item sees at least one key)
   InFlight<NP> r0, r1;
@@ -414,8 +393,6 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     if (j + 1 < n_it) compute(1, j + 1);
     __syncthreads();
   }
-  // no load into LDS may outlive the workgroup's hold on it (the walk fetches past the item's end)
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- write the item's partial rows --------------------------------------------------------------
 #pragma unroll

@@ -287,6 +287,25 @@ def test_fp8_small(G, Hkv):
             check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"fp8 G={G} rank {k} chunk {chunk}")
 
 
+@pytest.mark.parametrize("cfg_id", [1, 4])
+def test_repeated_launches_agree_bit_for_bit(cfg_id):
+    """The kernels have no atomics on data and a fixed order of sums: launches on the same inputs must leave
+    the same bits (partials and merged rows), whichever form of the sweep runs.  A difference means a race."""
+    w = make_requests(cfg_id, n_req=96)
+    q = make_q(w["seed"], 96, w["n_q_heads"], 128)
+    owner, _, _ = fs.fs_build_placement(shape_of(w), w["ctx_len"], w["mode"])
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 512, owner)
+    first = [t.clone() for t in (ds.part_o, ds.part_lse, ds.out, ds.lse)]
+    forms = [False] * 3 + ([True] * 3 if w["kv_dtype"] == "bf16" else [])
+    for rep, persistent in enumerate(forms):
+        for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
+            t.fill_(float("nan"))
+        ds.run(persistent=persistent)
+        torch.cuda.synchronize()
+        for name, a, b in zip(("part_o", "part_lse", "out", "lse"), first, (ds.part_o, ds.part_lse, ds.out, ds.lse)):
+            assert torch.equal(a, b), f"launch {rep} (persistent={persistent}): {name} differs from the first launch"
+
+
 # ------------------------------------------------------------------------------------------------
 def _full_config(cfg_id, rank, n_sample, **req_kw):
     """A config at its full size in the launch shape the benchmark times; the oracle checks a sample

@@ -225,6 +225,66 @@ def test_chunked_prefill_feeds_from_the_scheduler():
     assert rows == int(take.sum()) * Hq        # every (token, q-head) of the batch is computed exactly once
 
 
+def test_hip_graph_replays_match_eager():
+    """The prefill benchmark replays upload, attention and merge as one HIP graph.  Captured once and
+    replayed several times with eager work and synchronisation in between, every replay must leave the
+    bits of the eager launch (the kernels are deterministic), from the list the upload brought."""
+    say("prefill: graph replays")
+    rng = np.random.default_rng(91)
+    Hq, Hkv, R = 32, 8, 2
+    n_done, n_new = [0, 200, 1030, 48], [150, 40, 90, 700]
+    owner = rng.integers(0, R, size=(4, Hkv)).astype(np.int32)
+    ds, kv, q, q_indptr, pairs, oi = run_share(77, n_done, n_new, Hq, Hkv, owner, 1, R, chunk=256)
+    eager_o, eager_l = ds.prefill_out.clone(), ds.prefill_lse.clone()
+    host_items = ds.prefill_items.cpu().pin_memory()
+    cap = torch.cuda.Stream()
+    sp = cap.cuda_stream
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=cap):
+        ds.prefill_items.copy_(host_items, non_blocking=True)
+        fs.fs_prefill_attention(ds.shape, ds.view, ds.prefill_items, ds.prefill_sched, ds.n_prefill_items,
+                                ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
+        fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_chunk_indptr, ds.n_prefill_tiles,
+                        ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
+    for rep in range(4):
+        ds.prefill_out.fill_(float("nan")); ds.prefill_lse.fill_(float("nan")); ds.prefill_part_o.fill_(float("nan"))
+        ds.prefill_items.zero_()                   # the replayed upload has to bring the list back
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ds.prefill_out, eager_o) and torch.equal(ds.prefill_lse, eager_l), f"replay {rep} differs"
+        ds.prefill()                               # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(ds.prefill_out, eager_o)
+    compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, "graph replay vs oracle", oi)
+
+
+@pytest.mark.parametrize("waves,ct,wide", [(8, 1, 0), (4, 2, 0), (8, 1, 1)])
+def test_repeated_launches_agree_bit_for_bit(waves, ct, wide):
+    """Launches on the same inputs must leave the same bits in every launch shape (fixed order of sums, no
+    atomics on data): a difference means a race between the workgroup's stages."""
+    say(f"prefill: repeated launches, waves={waves} ct={ct} wide={wide}")
+    fs.fs_set_option("prefill_waves", waves); fs.fs_set_option("prefill_col_tiles", ct); fs.fs_set_option("prefill_wide_v", wide)
+    try:
+        rng = np.random.default_rng(92)
+        Hq, Hkv, R = 64, 8, 2
+        n_done, n_new = [0, 300, 2100, 16], [260, 70, 130, 900]
+        owner = rng.integers(0, R, size=(4, Hkv)).astype(np.int32)
+        ds, kv, q, q_indptr, pairs, oi = run_share(78, n_done, n_new, Hq, Hkv, owner, 0, R, chunk=512)
+        first = [t.clone() for t in (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse)]
+        for rep in range(5):
+            for t in (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse):
+                t.fill_(float("nan"))
+            ds.prefill()
+            torch.cuda.synchronize()
+            for name, a, b in zip(("part_o", "part_lse", "out", "lse"), first,
+                                  (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse)):
+                assert torch.equal(a, b), f"launch {rep}: {name} differs from the first launch"
+    finally:
+        fs.fs_set_option("prefill_waves", 8); fs.fs_set_option("prefill_col_tiles", 1); fs.fs_set_option("prefill_wide_v", 0)
+
+
 def test_unused_tails_and_spare_slots_are_never_used():
     say("poisoned tails")
     # contexts that end mid-page and mid-pair: the poisoned tail of the last page must not leak
