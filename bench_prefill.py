@@ -68,7 +68,6 @@ def algorithmic_flops(pairs, G, d=128):
 
 def run(args) -> int:
     import torch
-    import oracle
     import paper_2511_14116_amd as fs
     from paper_2511_14116_amd.device import DeviceShare
     from workloads import make_kv_pool, make_prefill_q
@@ -233,6 +232,7 @@ def run(args) -> int:
     # ---- CPU baseline: the oracle on a bounded sample of (pair, token) rows ------------------------
     cpu = None
     if not args.no_cpu_baseline:
+        import oracle                    # only this leg touches the oracle
         rng = np.random.default_rng(1)
         prs = oracle.PREFILL_PAIR_FIELDS
         pr_rows = np.stack([pairs[n] for n in prs], axis=1)
