@@ -250,7 +250,7 @@ def main() -> int:
         torch.cuda.synchronize()
 
     host_us, wait_us, enqueue_us = [], [], []
-    EVENT_EVERY = 8          # every 8th step runs eagerly with HIP events around the attention kernel
+    EVENT_EVERY = 16         # every 16th step runs eagerly with HIP events around the attention kernel (an eager step costs ~25 us more)
 
     def step(i: int, ev=None):
         # on entry the blob of step i is built and its upload is enqueued; build the one of step i+1
