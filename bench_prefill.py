@@ -32,16 +32,13 @@ def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64,
         queue = make_prefill_queue(seed, n_req, median=median, sigma=0.9, cap=cap)
     prompt, n_done = queue["prompt_len"], queue["n_done"]
     R = n_ranks
-    t0 = time.perf_counter()
     pending = np.zeros(R, dtype=np.int64)
     entries = np.zeros(n_req, dtype=fs.PREFILL_ENTRY_DTYPE)
     entries["req"] = np.arange(n_req)
     entries["n_done"] = n_done
     entries["n_new"] = prompt - n_done
     entries["rank"] = fs.fs_route_requests(pending, prompt - n_done)        # the waiting queue in arrival order
-    t1 = time.perf_counter()
     take, load, n_tok = fs.fs_schedule_prefill(R, budget, budget // 2, entries)
-    t2 = time.perf_counter()
     shape = fs.FsShape(n_req, n_q_heads, n_kv_heads, 128, 16, R)
     ctx = np.maximum(n_done + take, 1).astype(np.int32)
     owner, dp, rank_load, dp_load = fs.fs_build_placement_hybrid_heads(shape, ctx, layer=0, route=entries["rank"])
@@ -49,12 +46,10 @@ def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64,
     tile = fs.fs_prefill_tile_tokens(G)
     items, pairs, sched, chunk_indptr, out_indptr = fs.fs_build_prefill_worklist(shape, n_done, take, owner, rank, tile,
                                                                                  kv_chunk)
-    t3 = time.perf_counter()
     return dict(seed=seed, queue=queue, shape=shape, G=G, R=R, rank=rank, budget=budget, prompt=prompt, n_done=n_done,
                 n_new=take.astype(np.int32), entries=entries, rank_token_load=load, n_tokens=n_tok, owner=owner,
                 tile=tile, kv_chunk=kv_chunk, items=items, pairs=pairs, sched=sched, chunk_indptr=chunk_indptr,
-                out_indptr=out_indptr,
-                host_us=dict(router=(t1 - t0) * 1e6, scheduler=(t2 - t1) * 1e6, placement_and_list=(t3 - t2) * 1e6))
+                out_indptr=out_indptr)
 
 
 def algorithmic_flops(pairs, G, d=128):
