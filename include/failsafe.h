@@ -245,13 +245,13 @@ typedef struct {
  *     initialisation; the algorithm lists per-rank workloads as an input).
  *
  *  entries   HOST in  [n_entries]
- *  init_load HOST in  [n_ranks] or NULL
+ *  init_load HOST in  [n_ranks] or NULL   each >= 0
  *  take      HOST out [n_entries]  leading waiting tokens of each entry in the batch
  *  load      HOST out [n_ranks]    rank loads of the chosen batch (init_load included)
  *  n_tokens  HOST out              tokens in the chosen batch (0 when nothing waits or budget is 0)
  *
  * FS_EINVAL: NULL pointer, n_ranks < 1, negative budget/min_tokens/n_entries,
- * entry with rank outside [0, n_ranks) or negative counts.
+ * entry with rank outside [0, n_ranks) or negative counts, a negative init_load.
  */
 FS_API fs_status fs_schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens,
                                      const fs_prefill_entry* entries, int32_t n_entries,

@@ -68,6 +68,8 @@ def adaptive_chunked_prefill(budget: int, n_ranks: int, entries, min_tokens: int
     L = [0] * R if init_load is None else [int(x) for x in init_load]
     if len(L) != R:
         raise ValueError("init_load must have one entry per rank")
+    if any(x < 0 for x in L):
+        raise ValueError("a rank's load is work in token units: it cannot be negative")
     B = []                     # tokens in the order taken
     H = []                     # candidates: (size, loads) after every token
     while len(B) < budget and any(S[r] for r in range(R)):

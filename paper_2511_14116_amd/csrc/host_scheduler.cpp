@@ -62,6 +62,12 @@ fs_status schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens, 
                       q.rank, q.n_done, q.n_new);
   }
 
+  if (init_load)
+    for (int32_t r = 0; r < R; ++r)
+      if (init_load[r] < 0)
+        return fs::fail(FS_EINVAL, "fs_schedule_prefill: init_load[%d] = %lld < 0 (a load is work in token units)", r,
+                        static_cast<long long>(init_load[r]));
+
   // S_r: per rank, the entries routed to it in arrival order, and a cursor (entry, tokens taken).
   std::vector<int32_t> first(R, -1), next(n_entries > 0 ? n_entries : 1, -1), last(R, -1);
   for (int32_t e = 0; e < n_entries; ++e) {
@@ -106,14 +112,14 @@ fs_status schedule_prefill(int32_t n_ranks, int32_t budget, int32_t min_tokens, 
       cand_sum[n_taken - first_cand] = sum;
     }
   };
-  // Up to 8 ranks (a node) with loads that leave three bits to spare: load and rank travel as one key,
+  // Up to 8 ranks (a node) with loads (never negative) that leave three bits to spare: load and rank travel as one key,
   // load*8 + rank, so the least key is the least load and, among equals, the lowest rank; the eight keys
   // stay in registers and the search is a tree of seven minima.  Same picks as the general loop below.
   constexpr int kPack = 8;
   bool packed = R <= kPack;
   if (packed) {
     int64_t top = 0, dearest = 0;
-    for (int32_t r = 0; r < R; ++r) { if (L[r] < 0) packed = false; if (L[r] > top) top = L[r]; }
+    for (int32_t r = 0; r < R; ++r) if (L[r] > top) top = L[r];
     for (int32_t e = 0; e < n_entries; ++e)
       dearest = std::max<int64_t>(dearest, static_cast<int64_t>(entries[e].n_done) + entries[e].n_new);
     // no load can pass top + most * dearest

@@ -50,9 +50,9 @@ def test_scheduler_matches_oracle_on_random_queues(seed):
 
 @pytest.mark.parametrize("seed", range(40))
 def test_scheduler_search_forms_agree_with_the_oracle(seed):
-    """Up to 8 ranks with modest non-negative loads the library searches packed (load, rank) keys; more
-    ranks, a negative starting load or loads near 2^59 take the linear search.  Both against the oracle,
-    on queues full of equal loads (ties go to the lowest rank) and of ranks that run dry."""
+    """Up to 8 ranks with modest loads the library searches packed (load, rank) keys; more ranks or loads
+    near 2^59 take the linear search.  Both against the oracle, on queues full of equal loads (ties go to the
+    lowest rank) and of ranks that run dry.  A negative starting load is an error on both sides."""
     rng = np.random.default_rng(7000 + seed)
     kind = seed % 4
     R = int(rng.integers(9, 21)) if kind == 0 else int(rng.integers(1, 9))
@@ -62,7 +62,12 @@ def test_scheduler_search_forms_agree_with_the_oracle(seed):
     min_tokens = int(rng.integers(0, budget + 1))
     init = None
     if kind == 1:
-        init = [int(x) for x in rng.integers(-50, 50, size=R)]            # a negative load: linear search
+        init = [int(x) for x in rng.integers(0, 50, size=R)]
+        bad = list(init); bad[int(rng.integers(0, R))] = -1 - int(rng.integers(0, 40))
+        with pytest.raises(ValueError):
+            adaptive_chunked_prefill(budget, R, entries, min_tokens, bad)
+        with pytest.raises(fs.FsError):
+            fs.fs_schedule_prefill(R, budget, min_tokens, entries, bad)
     elif kind == 2:
         init = [int(x) for x in (1 << 59) + rng.integers(0, 3, size=R)]   # no room for the rank bits: linear search
     elif kind == 3:
