@@ -376,10 +376,13 @@ FS_API fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv
                               int64_t n_items, float* part_o, float* part_lse, void* stream);
 
 /* ---------------------------------------------------------------------------
- * fs_decode_attention_persistent - the same computation and the same outputs as
- * fs_decode_attention for bf16 K/V, by a fixed set of workgroups (two per CU) that
- * claim items from a counter in list order and write their partial rows in bursts
- * (decode phase, Section 2.1.1; the ragged list of Section 3.1).
+ * fs_decode_attention_persistent - the same computation as fs_decode_attention for
+ * bf16 K/V, by a fixed set of workgroups (two per CU) that claim items from a counter
+ * in list order and write their partial rows in bursts (decode phase, Section 2.1.1;
+ * the ragged list of Section 3.1).  An item's pages are split over four wavefronts as
+ * in fs_decode_attention's default launch shape ("waves_per_group" = 4), so the two
+ * give the same bits there; with another "waves_per_group" the plain call sums in
+ * another order and agrees only within rounding.
  *
  *  claim_dev  DEVICE in/out  two int32 (8-byte aligned): the item counter and the count
  *             of workgroups that have left.  Both must be 0 before the first launch that
