@@ -25,7 +25,13 @@ def _lib():
         raise RuntimeError("libfailsafe.so is not built: GPU tests never fall back to anything else")
     fs.load_library()
     yield
-    fs.fs_set_option("prefill_wide_v", 0)
+    _defaults()
+
+
+def _defaults():
+    for key, value in (("prefill_wide_v", 0), ("prefill_waves", 8), ("prefill_col_tiles", 1), ("waves_per_group", 4),
+                       ("prefetch_pages", 2)):
+        fs.fs_set_option(key, value)
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -80,3 +86,47 @@ def test_decode_on_drawn_shapes(seed):
             ds.run(persistent=True)
             torch.cuda.synchronize()
             assert torch.equal(plain, ds.out), f"{what}: the persistent sweep differs from the plain one"
+
+
+@pytest.mark.parametrize("seed", range(2))
+def test_drawn_launch_shapes(seed):
+    """The same draws under drawn launch shapes of both kernels (wavefronts per item, pages prefetched, prefill
+    wavefronts x column tiles): every shape against the oracle; the persistent sweep matches the plain one bit
+    for bit where the plain one splits an item over four wavefronts as it does."""
+    rng = np.random.default_rng(8300 + seed)
+    try:
+        for case in range(25):
+            pw, pc = [(8, 1), (8, 2), (4, 1), (4, 2), (4, 4)][int(rng.integers(0, 5))]
+            fs.fs_set_option("prefill_waves", pw); fs.fs_set_option("prefill_col_tiles", pc)
+            fs.fs_set_option("prefill_wide_v", int(rng.random() < 0.25))
+            fs.fs_set_option("waves_per_group", int(rng.choice([1, 2, 4]))); fs.fs_set_option("prefetch_pages", int(rng.integers(1, 4)))
+            Hkv = int(rng.choice([1, 2, 8])); G = int(rng.choice([1, 2, 4, 8, 16])); Hq = Hkv * G
+            R = int(rng.integers(1, 4)); B = int(rng.integers(1, 5))
+            n_done = (rng.integers(0, 600, size=B) * (rng.random(B) < 0.7)).astype(np.int32)
+            n_new = rng.choice([1, 16, 17, 33, 100, 257], size=B).astype(np.int32)
+            owner = rng.integers(0, R, size=(B, Hkv)).astype(np.int32)
+            chunk = int(rng.choice([0, 64, 256]))
+            what = f"shapes seed {seed} case {case}: prefill {pw}x{pc} Hkv={Hkv} G={G} n_done={n_done.tolist()} n_new={n_new.tolist()} chunk={chunk}"
+            TP.say(what)
+            ds, kv, q, q_indptr, pairs, oi = TP.run_share(9500 + 100 * seed + case, n_done, n_new, Hq, Hkv, owner,
+                                                          int(rng.integers(0, R)), R, chunk=chunk)
+            if len(pairs):
+                TP.compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, oi)
+            n_req = int(rng.integers(1, 30))
+            w = make_requests(1, seed=7700 + 100 * seed + case, n_req=n_req, max_len=int(rng.choice([300, 3000])))
+            w.update(n_q_heads=Hq, n_kv_heads=Hkv, group=G, n_ranks=int(rng.integers(1, 6)))
+            qd = make_q(w["seed"], n_req, Hq, 128)
+            owner_d, _, _ = fs.fs_build_placement(TD.shape_of(w), w["ctx_len"], w["mode"])
+            what = f"shapes seed {seed} case {case}: decode waves {fs.fs_get_option('waves_per_group')} prefetch {fs.fs_get_option('prefetch_pages')} B={n_req} Hkv={Hkv} G={G}"
+            dd, kvd, items, prs, sched, indptr = TD.run_rank(w, qd, 0, int(rng.choice([0, 64, 512])), owner_d)
+            if not len(prs):
+                continue
+            ref_o, ref_l = oracle.decode_attention_pairs(qd, kvd, TD.pairs_rows(prs), Hq, G, w["sm_scale"])
+            TD.check(dd.out.cpu().numpy(), dd.lse.cpu().numpy(), ref_o, ref_l, what)
+            if fs.fs_get_option("waves_per_group") == 4:
+                plain = dd.out.clone()
+                dd.run(persistent=True)
+                torch.cuda.synchronize()
+                assert torch.equal(plain, dd.out), f"{what}: the persistent sweep differs from the plain one"
+    finally:
+        _defaults()
