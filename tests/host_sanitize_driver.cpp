@@ -1,4 +1,4 @@
-// Host-side builders under AddressSanitizer + UBSan: random batches through the three host
+// Host-side builders under AddressSanitizer + UBSan: random batches through the host
 // entry points with exactly-sized output arrays (so any write past the end is caught) and a few
 // structural checks.  Built and run by tests/test_host_sanitizers.py; touches no GPU.
 #include <cstdio>
@@ -153,6 +153,56 @@ int main() {
     for (int g = 0; g < n; ++g) loaded += n_load[g];
     for (int s = 0; s < S; ++s) { dead += !alive[shard_owner[s]]; REQUIRE(alive[shard_new[s]]); }
     REQUIRE(loaded == dead);
+  }
+  // prefill tile list: exactly-sized arrays, every new token of every owned pair in exactly one tile,
+  // every tile's keys tiled by its chunks without gap or overlap
+  for (g_case = 3000; g_case < 3300; ++g_case) {
+    const int R = 1 + rng() % 5, H = 1 + rng() % 6, G = 1 + rng() % 8, B = rng() % 10;
+    fs_shape sh{B, H * G, H, 128, 16, R};
+    std::vector<int32_t> n_done(B), n_new(B), owner(static_cast<size_t>(B) * H);
+    for (int r = 0; r < B; ++r) {
+      n_done[r] = rng() % 3 ? static_cast<int32_t>(rng() % 2000) : 0;
+      n_new[r] = rng() % 4 ? static_cast<int32_t>(rng() % 300) : 0;
+    }
+    for (auto& o : owner) o = rng() % R;
+    const int32_t rank = rng() % R, tile = 1 + rng() % 40, chunk = 32 * (rng() % 9);
+    int64_t ni = -1, np = -1, nt = -1;
+    REQUIRE(fs_build_prefill_worklist(&sh, n_done.data(), n_new.data(), owner.data(), rank, tile, chunk, nullptr, 0,
+                                      nullptr, 0, nullptr, nullptr, 0, nullptr, &ni, &np, &nt) == FS_OK);
+    std::vector<fs_prefill_item> items(ni);
+    std::vector<fs_prefill_pair> pairs(np);
+    std::vector<int32_t> sched(ni);
+    std::vector<int64_t> chunk_indptr(nt + 1), out_indptr(np + 1);
+    int64_t ni2 = -1, np2 = -1, nt2 = -1;
+    REQUIRE(fs_build_prefill_worklist(&sh, n_done.data(), n_new.data(), owner.data(), rank, tile, chunk, items.data(), ni,
+                                      pairs.data(), np, sched.data(), chunk_indptr.data(), nt, out_indptr.data(), &ni2,
+                                      &np2, &nt2) == FS_OK);
+    REQUIRE(ni2 == ni && np2 == np && nt2 == nt && chunk_indptr[0] == 0 && chunk_indptr[nt] == ni);
+    int64_t tokens = 0, want = 0;
+    for (int r = 0; r < B; ++r)
+      for (int h = 0; h < H; ++h)
+        if (owner[static_cast<size_t>(r) * H + h] == rank) want += n_new[r];
+    for (int64_t t = 0; t < nt; ++t) {
+      const int64_t a = chunk_indptr[t], b = chunk_indptr[t + 1];
+      REQUIRE(b > a);
+      const fs_prefill_item& first = items[a];
+      tokens += first.q_end - first.q_begin;
+      REQUIRE(first.kv_begin == 0 && items[b - 1].kv_end == first.n_done + first.q_end);
+      for (int64_t i = a + 1; i < b; ++i) REQUIRE(items[i].kv_begin == items[i - 1].kv_end && items[i].pair == first.pair);
+    }
+    REQUIRE(tokens == want);
+    std::vector<char> seen(ni, 0);
+    for (int64_t i = 0; i < ni; ++i) {
+      REQUIRE(sched[i] >= 0 && sched[i] < ni && !seen[sched[i]]);
+      seen[sched[i]] = 1;
+    }
+    if (ni > 1) {   // one item short: the call must refuse, not write past the end
+      std::vector<fs_prefill_item> small(ni - 1);
+      std::vector<int32_t> sched_small(ni - 1);
+      REQUIRE(fs_build_prefill_worklist(&sh, n_done.data(), n_new.data(), owner.data(), rank, tile, chunk, small.data(),
+                                        ni - 1, pairs.data(), np, sched_small.data(), chunk_indptr.data(), nt,
+                                        out_indptr.data(), &ni2, &np2, &nt2) == FS_ECAPACITY);
+    }
   }
   // error paths leave a message
   fs_shape bad{1, 4, 2, 128, 16, 0};

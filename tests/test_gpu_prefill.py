@@ -79,10 +79,8 @@ def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched
     return ds, kv, q, q_indptr, w_pairs, out_indptr
 
 
-def compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, out_indptr=None):
+def compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, out_indptr):
     """Final rows (after the split-K merge) against the unsplit oracle; padding rows must be finite."""
-    if out_indptr is None:
-        _, _, _, _, out_indptr = oracle.build_prefill_worklist(*ds.list_args)
     ref_o, ref_l = oracle.prefill_attention_pairs(q, q_indptr, kv, pairs, Hq, G, SCALE, workers=8, out_indptr=out_indptr)
     out, lse = ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy()
     assert np.isfinite(out).all() and np.isfinite(lse).all(), f"{what}: non-finite output (padding rows included)"

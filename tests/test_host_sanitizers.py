@@ -15,7 +15,7 @@ def test_host_builders_under_asan_ubsan(tmp_path):
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            os.path.join(ROOT, "tests", "host_sanitize_driver.cpp"),
-           os.path.join(CSRC, "host_builders.cpp"), os.path.join(CSRC, "host_scheduler.cpp"), os.path.join(CSRC, "host_recovery.cpp"),
+           os.path.join(CSRC, "host_builders.cpp"), os.path.join(CSRC, "host_scheduler.cpp"), os.path.join(CSRC, "host_recovery.cpp"), os.path.join(CSRC, "host_prefill.cpp"),
            os.path.join(CSRC, "status.cpp"), "-o", exe]
     build = subprocess.run(cmd, capture_output=True, text=True)
     if build.returncode != 0 and "sanitize" in build.stderr and "cannot find" in build.stderr:
