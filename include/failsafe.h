@@ -10,6 +10,7 @@
  *   (fs_choose_chunk_tokens: a chunk size where the caller leaves it open) host
  *   fs_decode_attention  per-item partial attention (out, lse)          device
  *   fs_merge_lse         split-K partials -> final (out, lse)           device
+ *   (fs_decode_attention_fused: the last two in one call, unsplit pairs unmerged) device
  *
  * and, before the decode step, the host side of the paper's router and prefill
  * scheduler: fs_route_request(s), fs_schedule_prefill; after a fault, the recovery
@@ -396,6 +397,32 @@ FS_API fs_status fs_decode_attention_persistent(const fs_shape* shape, const fs_
                                                 const fs_work_item* items_dev, const int32_t* sched_dev,
                                                 int64_t n_items, int32_t* claim_dev, float* part_o,
                                                 float* part_lse, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * fs_decode_attention_fused - the decode attention of the whole list (Section 2.1.1) and the
+ * split-K merge of its partials in one call: what fs_decode_attention (or
+ * fs_decode_attention_persistent) followed by fs_merge_lse leave in out/lse, bit for bit, for
+ * the ragged list of Section 3.1.  A pair that is a single item (chunk_indptr[p+1] -
+ * chunk_indptr[p] == 1) gets its final rows [p*G, p*G+G) straight from the sweep and writes no
+ * partial rows; the merge runs only for the pairs that are split, and is not launched at all when
+ * n_items == n_pairs.
+ *
+ *  chunk_indptr_dev  DEVICE in   [n_pairs+1]  as built by fs_build_worklist
+ *  part_o, part_lse  DEVICE scratch, sized and indexed as for fs_decode_attention (rows of
+ *                    unsplit pairs stay untouched); may be NULL when n_items == n_pairs
+ *  claim_dev         DEVICE in/out, as for fs_decode_attention_persistent, or NULL.  With bf16
+ *                    K/V, a non-NULL claim_dev and at least 1024 items the persistent sweep runs,
+ *                    otherwise one workgroup per item
+ *  out, lse          DEVICE out  [n_pairs*G][head_dim], [n_pairs*G] fp32
+ *
+ * n_items == 0 is a no-op.  Errors as for fs_decode_attention, and FS_EINVAL for n_pairs
+ * outside [1, n_items] or a NULL chunk_indptr_dev, out or lse.
+ */
+FS_API fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_kv_view* kv,
+                                           const fs_work_item* items_dev, const int32_t* sched_dev,
+                                           int64_t n_items, const int64_t* chunk_indptr_dev, int64_t n_pairs,
+                                           float* part_o, float* part_lse, int32_t* claim_dev,
+                                           float* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------
  * fs_merge_lse - combine the chunk partials of each pair (split-K merge):

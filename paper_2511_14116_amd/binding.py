@@ -97,6 +97,10 @@ def load_library(path: str | None = None):
     lib.fs_decode_attention_persistent.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
                                                    C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_decode_attention_persistent.restype = C.c_int
+    lib.fs_decode_attention_fused.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
+                                              C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fs_decode_attention_fused.restype = C.c_int
     lib.fs_merge_lse.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                  C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_merge_lse.restype = C.c_int
@@ -401,6 +405,14 @@ def fs_decode_attention_persistent(shape: FsShape, kv: FsKvView, items_dev, sche
     _check(st)
 
 
+def fs_decode_attention_fused(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int, chunk_indptr_dev,
+                              n_pairs: int, part_o, part_lse, claim_dev, out, lse, stream=None) -> None:
+    st = load_library().fs_decode_attention_fused(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
+                                                  n_items, _ptr(chunk_indptr_dev), n_pairs, _ptr(part_o),
+                                                  _ptr(part_lse), _ptr(claim_dev), _ptr(out), _ptr(lse), _ptr(stream))
+    _check(st)
+
+
 def fs_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,
                  out, lse, stream=None) -> None:
     st = load_library().fs_merge_lse(_ptr(part_o), _ptr(part_lse), _ptr(chunk_indptr_dev), n_pairs, group,
@@ -521,6 +533,15 @@ def bind_decode_attention_persistent(shape: FsShape, kv: FsKvView, items_dev, sc
     args = (C.byref(shape), C.byref(kv), _vp(items_dev), _vp(sched_dev), C.c_int64(n_items), _vp(claim_dev),
             _vp(part_o), _vp(part_lse), _vp(stream))
     return BoundCall(lib.fs_decode_attention_persistent, args, (shape, kv, items_dev, sched_dev, claim_dev, part_o, part_lse))
+
+
+def bind_decode_attention_fused(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int, chunk_indptr_dev,
+                                n_pairs: int, part_o, part_lse, claim_dev, out, lse, stream=None) -> BoundCall:
+    lib = load_library()
+    args = (C.byref(shape), C.byref(kv), _vp(items_dev), _vp(sched_dev), C.c_int64(n_items), _vp(chunk_indptr_dev),
+            C.c_int64(n_pairs), _vp(part_o), _vp(part_lse), _vp(claim_dev), _vp(out), _vp(lse), _vp(stream))
+    return BoundCall(lib.fs_decode_attention_fused, args,
+                     (shape, kv, items_dev, sched_dev, chunk_indptr_dev, part_o, part_lse, claim_dev, out, lse))
 
 
 def bind_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,

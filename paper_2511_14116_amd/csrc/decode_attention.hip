@@ -53,6 +53,11 @@ struct DecodeParams {
   const int32_t* __restrict__ sched;
   float* __restrict__ part_o;
   float* __restrict__ part_lse;
+  // Fused form only (else NULL): a pair that is a single item writes its rows straight to the final
+  // arrays, rows [pair*G, pair*G+G), and needs no merge.
+  const int64_t* __restrict__ chunk_indptr;
+  float* __restrict__ out;
+  float* __restrict__ lse;
   int32_t group;
   float scale_log2;   // sm_scale * log2(e): scores live in the log2 domain
 };
@@ -166,6 +171,18 @@ __device__ __forceinline__ void consume_page(SoftmaxState& st, PageRegs& pg, con
 }
 
 // Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.
+// Where an item's G rows go: its partial rows, or - in the fused form, when the item is all of its pair -
+// the pair's final rows.
+struct RowDest {
+  float* o;
+  float* lse;
+  int row;
+};
+__device__ __forceinline__ RowDest row_dest(const DecodeParams& P, int pair, int part_row) {
+  if (P.chunk_indptr && P.chunk_indptr[pair + 1] - P.chunk_indptr[pair] == 1) return RowDest{P.out, P.lse, pair * P.group};
+  return RowDest{P.part_o, P.part_lse, part_row};
+}
+
 template <int WAVES>
 __device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_total, int wave, int lane,
                                                 int G, float* __restrict__ part_o,
@@ -209,6 +226,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
 
   const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
   const fs_work_item it = P.items[item_idx];
+  const RowDest dst = row_dest(P, it.pair, it.part_row);   // asked for now, needed when the item ends
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int qi = lane & 15, kb = lane >> 4;
@@ -269,7 +287,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
   }
 
   const float l_total = sum_xor32(sum_xor16(st.l));
-  merge_and_store<WAVES>(st, l_total, wave, lane, G, P.part_o, P.part_lse, it.part_row, sm_o, sm_m, sm_l);
+  merge_and_store<WAVES>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -303,7 +321,7 @@ struct ItemDesc {
   const_ids_ptr ids;    // page ids of the item's first page onwards
   int n_tok;            // tokens of the item
   int p0, p1;           // this wavefront's pages [p0, p1) of the item
-  int part_row;
+  int row;              // first partial row of the item, or -(first final row) - 1 when the item is all of its pair (fused form)
   bf16x8 q[4];          // Q^T operand of this lane
   bool valid;
 };
@@ -315,7 +333,7 @@ __device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int 
   d.ids = (const_ids_ptr)(uintptr_t)0;
   d.n_tok = 0;
   d.p0 = d.p1 = 0;
-  d.part_row = 0;
+  d.row = 0;
 #pragma unroll
   for (int c = 0; c < 4; ++c) d.q[c] = bf16x8{};
   if (d.valid) {
@@ -338,7 +356,11 @@ __device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int 
     const int per = (n_pages + WAVES - 1) / WAVES;
     d.p0 = wave * per;
     d.p1 = min(n_pages, d.p0 + per);
-    d.part_row = it.part_row;
+    d.row = it.part_row;
+    if (P.chunk_indptr) {
+      const int32_t n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - P.chunk_indptr[it.pair]));
+      if (n_chunks == 1) d.row = -(it.pair * G) - 1;
+    }
     const int qi = lane & 15, kb = lane >> 4;
     const int qrow = it.q_row + min(qi, G - 1);
     const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
@@ -451,7 +473,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
       *reinterpret_cast<f32x4*>(st_o + (staged + q) * fs::kHeadDim + 4 * d4) = o * inv;
       if (d4 == 0) {
         st_lse[staged + q] = (M + __builtin_amdgcn_logf(L)) * kLn2;
-        st_row[staged + q] = cur.part_row + q;
+        st_row[staged + q] = cur.row >= 0 ? cur.row + q : cur.row - q;
       }
     }
     staged += G;
@@ -460,10 +482,14 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
     if (last || staged + G > kStageRows) {
       for (int idx = threadIdx.x; idx < staged * 32; idx += WAVES * 64) {
         const int r = idx >> 5, d4 = idx & 31;
-        __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(st_o + r * fs::kHeadDim + 4 * d4),
-                                    reinterpret_cast<f32x4*>(P.part_o + static_cast<int64_t>(st_row[r]) * fs::kHeadDim + 4 * d4));
+        const int row = st_row[r];
+        float* dst = row >= 0 ? P.part_o + static_cast<int64_t>(row) * fs::kHeadDim : P.out + static_cast<int64_t>(-row - 1) * fs::kHeadDim;
+        __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(st_o + r * fs::kHeadDim + 4 * d4), reinterpret_cast<f32x4*>(dst + 4 * d4));
       }
-      for (int r = threadIdx.x; r < staged; r += WAVES * 64) __builtin_nontemporal_store(st_lse[r], P.part_lse + st_row[r]);
+      for (int r = threadIdx.x; r < staged; r += WAVES * 64) {
+        const int row = st_row[r];
+        __builtin_nontemporal_store(st_lse[r], row >= 0 ? P.part_lse + row : P.lse + (-row - 1));
+      }
       staged = 0;
       // the next write into the staging rows comes after the next item's first barrier, which every
       // thread reaches only when it is done reading them here
@@ -537,6 +563,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
 
   const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
   const fs_work_item it = P.items[item_idx];
+  const RowDest dst = row_dest(P, it.pair, it.part_row);   // asked for now, needed when the item ends
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 7, ts = lane >> 3;
@@ -676,154 +703,115 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
       }
     }
     const float inv = 1.0f / L;
-    __builtin_nontemporal_store(acc * inv, reinterpret_cast<f32x4*>(P.part_o + static_cast<int64_t>(it.part_row + g) * fs::kHeadDim + 4 * d4));
-    if (d4 == 0) __builtin_nontemporal_store((M + __builtin_amdgcn_logf(L)) * kLn2, P.part_lse + it.part_row + g);
+    __builtin_nontemporal_store(acc * inv, reinterpret_cast<f32x4*>(dst.o + static_cast<int64_t>(dst.row + g) * fs::kHeadDim + 4 * d4));
+    if (d4 == 0) __builtin_nontemporal_store((M + __builtin_amdgcn_logf(L)) * kLn2, dst.lse + dst.row + g);
   }
 }
 
 template <typename K>
-fs_status launch(K kernel, int threads, const DecodeParams& P, int64_t n_items, hipStream_t stream) {
+fs_status launch(const char* who, K kernel, int threads, const DecodeParams& P, int64_t n_items, hipStream_t stream) {
   hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(n_items)), dim3(threads), 0, stream, P);
   const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_decode_attention: launch failed: %s", hipGetErrorString(e));
+  if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
   return FS_OK;
 }
 
-}  // namespace
+// ---- host side -------------------------------------------------------------------------------
 
-extern "C" fs_status fs_decode_attention_persistent(const fs_shape* shape, const fs_kv_view* kv,
-                                                    const fs_work_item* items_dev, const int32_t* sched_dev,
-                                                    int64_t n_items, int32_t* claim_dev, float* part_o,
-                                                    float* part_lse, void* stream) {
-  if (!shape || !kv) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: shape or kv is NULL");
+// Argument checks shared by the entry points.  `who` names the call in messages.  On FS_OK with
+// n_items > 0, *P is ready for a launch (the fused fields are left NULL).
+fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, const fs_work_item* items_dev,
+                  const int32_t* sched_dev, int64_t n_items, float* part_o, float* part_lse, bool partials_needed,
+                  bool bf16_only, DecodeParams* P) {
+  if (!shape || !kv) return fs::fail(FS_EINVAL, "%s: shape or kv is NULL", who);
   if (shape->n_kv_heads < 1 || shape->n_q_heads < shape->n_kv_heads || shape->n_q_heads % shape->n_kv_heads)
-    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: n_q_heads %d is not a multiple of n_kv_heads %d",
-                    shape->n_q_heads, shape->n_kv_heads);
-  if (shape->head_dim != fs::kHeadDim || shape->page_tokens != fs::kPageTokens)
-    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention_persistent: head_dim %d, page_tokens %d (only %d and %d are built)",
-                    shape->head_dim, shape->page_tokens, fs::kHeadDim, fs::kPageTokens);
-  const int G = shape->n_q_heads / shape->n_kv_heads;
-  if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: group %d > %d", G, fs::kMaxGroup);
-  if (kv->kv_dtype != FS_KV_BF16)
-    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention_persistent: only bf16 K/V is built (kv_dtype %d)", kv->kv_dtype);
-  if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: n_items out of range");
-  if (n_items == 0) return FS_OK;
-  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev || !claim_dev || !part_o ||
-      !part_lse)
-    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: NULL device pointer");
-  const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * 2;
-  if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
-      (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
-      (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
-      (reinterpret_cast<uintptr_t>(part_o) & 15) || (reinterpret_cast<uintptr_t>(claim_dev) & 7))
-    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: pools, strides, q and part_o must be 16-byte aligned, claim_dev 8-byte, "
-                               "strides at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
-  if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: sm_scale is not finite");
-  // CU count of the current device, asked once per device (the query is a runtime call on the launch path)
-  static int cu_of_device[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
-    return fs::fail(FS_EHIP, "fs_decode_attention_persistent: cannot identify the current device");
-  int n_cu = cu_of_device[dev];
-  if (n_cu == 0) {
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
-      return fs::fail(FS_EHIP, "fs_decode_attention_persistent: cannot read the device's CU count");
-    cu_of_device[dev] = n_cu;      // racing first calls write the same value
-  }
-  DecodeParams P;
-  P.q = static_cast<const uint16_t*>(kv->q);
-  P.k_pool = static_cast<const char*>(kv->k_pool);
-  P.v_pool = static_cast<const char*>(kv->v_pool);
-  P.k_stride = kv->k_slot_stride;
-  P.v_stride = kv->v_slot_stride;
-  P.k_scale = nullptr;
-  P.v_scale = nullptr;
-  P.page_indptr = kv->page_indptr;
-  P.page_ids = kv->page_ids;
-  P.items = items_dev;
-  P.sched = sched_dev;
-  P.part_o = part_o;
-  P.part_lse = part_lse;
-  P.group = G;
-  P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
-  const int64_t groups = std::min<int64_t>(n_items, 2ll * n_cu);      // two resident workgroups per CU
-  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3>), dim3(static_cast<unsigned>(groups)), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), P, static_cast<int>(n_items), claim_dev, n_cu);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_decode_attention_persistent: launch failed: %s", hipGetErrorString(e));
-  return FS_OK;
-}
-
-extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv,
-                                         const fs_work_item* items_dev, const int32_t* sched_dev,
-                                         int64_t n_items, float* part_o, float* part_lse, void* stream) {
-  if (!shape || !kv) return fs::fail(FS_EINVAL, "fs_decode_attention: shape or kv is NULL");
-  if (shape->n_kv_heads < 1 || shape->n_q_heads < shape->n_kv_heads || shape->n_q_heads % shape->n_kv_heads)
-    return fs::fail(FS_EINVAL, "fs_decode_attention: n_q_heads %d is not a multiple of n_kv_heads %d",
-                    shape->n_q_heads, shape->n_kv_heads);
+    return fs::fail(FS_EINVAL, "%s: n_q_heads %d is not a multiple of n_kv_heads %d", who, shape->n_q_heads,
+                    shape->n_kv_heads);
   if (shape->head_dim != fs::kHeadDim)
-    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention: head_dim %d (only %d is built)", shape->head_dim, fs::kHeadDim);
+    return fs::fail(FS_EUNSUPPORTED, "%s: head_dim %d (only %d is built)", who, shape->head_dim, fs::kHeadDim);
   if (shape->page_tokens != fs::kPageTokens)
-    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention: page_tokens %d (only %d is built)", shape->page_tokens,
-                    fs::kPageTokens);
+    return fs::fail(FS_EUNSUPPORTED, "%s: page_tokens %d (only %d is built)", who, shape->page_tokens, fs::kPageTokens);
   const int G = shape->n_q_heads / shape->n_kv_heads;
-  if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "fs_decode_attention: group %d > %d", G, fs::kMaxGroup);
-  if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "fs_decode_attention: n_items out of range");
+  if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "%s: group %d > %d", who, G, fs::kMaxGroup);
+  if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "%s: n_items out of range", who);
   if (kv->kv_dtype != FS_KV_BF16 && kv->kv_dtype != FS_KV_FP8_E4M3)
-    return fs::fail(FS_EINVAL, "fs_decode_attention: unknown kv_dtype %d", kv->kv_dtype);
+    return fs::fail(FS_EINVAL, "%s: unknown kv_dtype %d", who, kv->kv_dtype);
+  if (bf16_only && kv->kv_dtype != FS_KV_BF16)
+    return fs::fail(FS_EUNSUPPORTED, "%s: only bf16 K/V is built (kv_dtype %d)", who, kv->kv_dtype);
   if (kv->kv_dtype == FS_KV_FP8_E4M3 && G > fs::kMaxGroupFp8)
-    return fs::fail(FS_EUNSUPPORTED, "fs_decode_attention: fp8 KV with group %d > %d", G, fs::kMaxGroupFp8);
+    return fs::fail(FS_EUNSUPPORTED, "%s: fp8 KV with group %d > %d", who, G, fs::kMaxGroupFp8);
   if (n_items == 0) return FS_OK;
-  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev || !part_o || !part_lse)
-    return fs::fail(FS_EINVAL, "fs_decode_attention: NULL device pointer");
+  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev ||
+      (partials_needed && (!part_o || !part_lse)))
+    return fs::fail(FS_EINVAL, "%s: NULL device pointer", who);
   if (kv->kv_dtype == FS_KV_FP8_E4M3 && (!kv->k_scale || !kv->v_scale))
-    return fs::fail(FS_EINVAL, "fs_decode_attention: fp8 KV needs k_scale and v_scale");
+    return fs::fail(FS_EINVAL, "%s: fp8 KV needs k_scale and v_scale", who);
   const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * (kv->kv_dtype == FS_KV_BF16 ? 2 : 1);
   if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
       (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
       (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
       (reinterpret_cast<uintptr_t>(part_o) & 15))
-    return fs::fail(FS_EINVAL, "fs_decode_attention: pools, strides, q and part_o must be 16-byte aligned and "
-                               "strides at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
-  if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "fs_decode_attention: sm_scale is not finite");
+    return fs::fail(FS_EINVAL, "%s: pools, strides, q and part_o must be 16-byte aligned and strides at least one slot "
+                               "(%lld bytes)", who, static_cast<long long>(slot_bytes));
+  if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "%s: sm_scale is not finite", who);
+  P->q = static_cast<const uint16_t*>(kv->q);
+  P->k_pool = static_cast<const char*>(kv->k_pool);
+  P->v_pool = static_cast<const char*>(kv->v_pool);
+  P->k_stride = kv->k_slot_stride;
+  P->v_stride = kv->v_slot_stride;
+  P->k_scale = kv->k_scale;
+  P->v_scale = kv->v_scale;
+  P->page_indptr = kv->page_indptr;
+  P->page_ids = kv->page_ids;
+  P->items = items_dev;
+  P->sched = sched_dev;
+  P->part_o = part_o;
+  P->part_lse = part_lse;
+  P->chunk_indptr = nullptr;
+  P->out = nullptr;
+  P->lse = nullptr;
+  P->group = G;
+  P->scale_log2 = kv->sm_scale * 1.4426950408889634f;
+  return FS_OK;
+}
 
-  DecodeParams P;
-  P.q = static_cast<const uint16_t*>(kv->q);
-  P.k_pool = static_cast<const char*>(kv->k_pool);
-  P.v_pool = static_cast<const char*>(kv->v_pool);
-  P.k_stride = kv->k_slot_stride;
-  P.v_stride = kv->v_slot_stride;
-  P.k_scale = kv->k_scale;
-  P.v_scale = kv->v_scale;
-  P.page_indptr = kv->page_indptr;
-  P.page_ids = kv->page_ids;
-  P.items = items_dev;
-  P.sched = sched_dev;
-  P.part_o = part_o;
-  P.part_lse = part_lse;
-  P.group = G;
-  P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
-  hipStream_t s = static_cast<hipStream_t>(stream);
+// CU count of the current device, asked once per device (the query is a runtime call on the launch path).
+fs_status device_cu_count(const char* who, int* n_cu_out) {
+  static int cu_of_device[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    return fs::fail(FS_EHIP, "%s: cannot identify the current device", who);
+  int n_cu = cu_of_device[dev];
+  if (n_cu == 0) {
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+      return fs::fail(FS_EHIP, "%s: cannot read the device's CU count", who);
+    cu_of_device[dev] = n_cu;      // racing first calls write the same value
+  }
+  *n_cu_out = n_cu;
+  return FS_OK;
+}
+
+// One workgroup per item, in the launch shape the options select.
+fs_status launch_plain(const char* who, const DecodeParams& P, int kv_dtype, int64_t n_items, hipStream_t s) {
   const int waves = fs::options().waves_per_group;
-
   const int nbuf = fs::options().prefetch_pages + 1;
+  const int G = P.group;
 
 #define FS_PICK(KERNEL, ...)                                                             \
   switch (waves * 10 + nbuf) {                                                           \
-    case 12: return launch(KERNEL<1, 2 __VA_ARGS__>, 64, P, n_items, s);                 \
-    case 13: return launch(KERNEL<1, 3 __VA_ARGS__>, 64, P, n_items, s);                 \
-    case 14: return launch(KERNEL<1, 4 __VA_ARGS__>, 64, P, n_items, s);                 \
-    case 22: return launch(KERNEL<2, 2 __VA_ARGS__>, 128, P, n_items, s);                \
-    case 23: return launch(KERNEL<2, 3 __VA_ARGS__>, 128, P, n_items, s);                \
-    case 24: return launch(KERNEL<2, 4 __VA_ARGS__>, 128, P, n_items, s);                \
-    case 42: return launch(KERNEL<4, 2 __VA_ARGS__>, 256, P, n_items, s);                \
-    case 43: return launch(KERNEL<4, 3 __VA_ARGS__>, 256, P, n_items, s);                \
-    case 44: return launch(KERNEL<4, 4 __VA_ARGS__>, 256, P, n_items, s);                \
-    default: return fs::fail(FS_EINVAL, "fs_decode_attention: no kernel for waves_per_group %d, prefetch_pages %d", \
-                             waves, nbuf - 1);                                           \
+    case 12: return launch(who, KERNEL<1, 2 __VA_ARGS__>, 64, P, n_items, s);            \
+    case 13: return launch(who, KERNEL<1, 3 __VA_ARGS__>, 64, P, n_items, s);            \
+    case 14: return launch(who, KERNEL<1, 4 __VA_ARGS__>, 64, P, n_items, s);            \
+    case 22: return launch(who, KERNEL<2, 2 __VA_ARGS__>, 128, P, n_items, s);           \
+    case 23: return launch(who, KERNEL<2, 3 __VA_ARGS__>, 128, P, n_items, s);           \
+    case 24: return launch(who, KERNEL<2, 4 __VA_ARGS__>, 128, P, n_items, s);           \
+    case 42: return launch(who, KERNEL<4, 2 __VA_ARGS__>, 256, P, n_items, s);           \
+    case 43: return launch(who, KERNEL<4, 3 __VA_ARGS__>, 256, P, n_items, s);           \
+    case 44: return launch(who, KERNEL<4, 4 __VA_ARGS__>, 256, P, n_items, s);           \
+    default: return fs::fail(FS_EINVAL, "%s: no kernel for waves_per_group %d, prefetch_pages %d", who, waves, nbuf - 1); \
   }
 
-  if (kv->kv_dtype == FS_KV_BF16) {
+  if (kv_dtype == FS_KV_BF16) {
     FS_PICK(decode_bf16_kernel)
   }
   if (G == 1) {
@@ -832,6 +820,74 @@ extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view
 #undef FS_COMMA_ONE
   }
 #undef FS_PICK
-  if (G <= 4) return launch(decode_fp8_kernel<2, 2, 4>, 128, P, n_items, s);
-  return launch(decode_fp8_kernel<1, 2, 8>, 64, P, n_items, s);
+  if (G <= 4) return launch(who, decode_fp8_kernel<2, 2, 4>, 128, P, n_items, s);
+  return launch(who, decode_fp8_kernel<1, 2, 8>, 64, P, n_items, s);
+}
+
+// The persistent form: two resident workgroups per CU claim items from claim_dev.
+fs_status launch_persistent(const char* who, const DecodeParams& P, int64_t n_items, int32_t* claim_dev, hipStream_t s) {
+  int n_cu = 0;
+  if (const fs_status st = device_cu_count(who, &n_cu); st != FS_OK) return st;
+  const int64_t groups = std::min<int64_t>(n_items, 2ll * n_cu);
+  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3>), dim3(static_cast<unsigned>(groups)), dim3(256), 0, s, P,
+                     static_cast<int>(n_items), claim_dev, n_cu);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+  return FS_OK;
+}
+
+}  // namespace
+
+extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv,
+                                         const fs_work_item* items_dev, const int32_t* sched_dev,
+                                         int64_t n_items, float* part_o, float* part_lse, void* stream) {
+  DecodeParams P;
+  if (const fs_status st = prepare("fs_decode_attention", shape, kv, items_dev, sched_dev, n_items, part_o, part_lse,
+                                   true, false, &P); st != FS_OK || n_items == 0)
+    return st;
+  return launch_plain("fs_decode_attention", P, kv->kv_dtype, n_items, static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_decode_attention_persistent(const fs_shape* shape, const fs_kv_view* kv,
+                                                    const fs_work_item* items_dev, const int32_t* sched_dev,
+                                                    int64_t n_items, int32_t* claim_dev, float* part_o,
+                                                    float* part_lse, void* stream) {
+  DecodeParams P;
+  if (const fs_status st = prepare("fs_decode_attention_persistent", shape, kv, items_dev, sched_dev, n_items, part_o,
+                                   part_lse, true, true, &P); st != FS_OK || n_items == 0)
+    return st;
+  if (!claim_dev || (reinterpret_cast<uintptr_t>(claim_dev) & 7))
+    return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: claim_dev is NULL or not 8-byte aligned");
+  return launch_persistent("fs_decode_attention_persistent", P, n_items, claim_dev, static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_kv_view* kv,
+                                               const fs_work_item* items_dev, const int32_t* sched_dev, int64_t n_items,
+                                               const int64_t* chunk_indptr_dev, int64_t n_pairs, float* part_o,
+                                               float* part_lse, int32_t* claim_dev, float* out, float* lse,
+                                               void* stream) {
+  const char* who = "fs_decode_attention_fused";
+  if (n_pairs < 0 || n_pairs > n_items) return fs::fail(FS_EINVAL, "%s: n_pairs %lld outside [0, n_items]", who,
+                                                        static_cast<long long>(n_pairs));
+  const bool split = n_items > n_pairs;            // some pair has more than one item: partial rows and a merge
+  DecodeParams P;
+  if (const fs_status st = prepare(who, shape, kv, items_dev, sched_dev, n_items, part_o, part_lse, split, false, &P);
+      st != FS_OK || n_items == 0)
+    return st;
+  if (n_pairs == 0) return fs::fail(FS_EINVAL, "%s: %lld items but no pairs", who, static_cast<long long>(n_items));
+  if (!chunk_indptr_dev || !out || !lse || (reinterpret_cast<uintptr_t>(out) & 15))
+    return fs::fail(FS_EINVAL, "%s: chunk_indptr_dev, out or lse is NULL, or out is not 16-byte aligned", who);
+  if (claim_dev && (reinterpret_cast<uintptr_t>(claim_dev) & 7))
+    return fs::fail(FS_EINVAL, "%s: claim_dev is not 8-byte aligned", who);
+  P.chunk_indptr = chunk_indptr_dev;
+  P.out = out;
+  P.lse = lse;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // The persistent form pays once every resident workgroup walks several items; below that it is the same
+  // work plus a counter.
+  const bool persistent = claim_dev && kv->kv_dtype == FS_KV_BF16 && n_items >= fs::kPersistentMinItems;
+  const fs_status st = persistent ? launch_persistent(who, P, n_items, claim_dev, s)
+                                  : launch_plain(who, P, kv->kv_dtype, n_items, s);
+  if (st != FS_OK || !split) return st;
+  return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
 }

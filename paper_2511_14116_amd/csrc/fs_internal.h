@@ -14,6 +14,7 @@ constexpr int kHeadDim = 128;
 constexpr int kPageTokens = 16;
 constexpr int kMaxGroup = 16;       // q-heads per KV head that fit one MFMA tile column set
 constexpr int kMaxGroupFp8 = 8;
+constexpr int kPersistentMinItems = 1024;   // list length from which the fused decode call takes the persistent sweep
 
 struct Options {
   int waves_per_group;   // wavefronts cooperating on one work item (1, 2 or 4)
@@ -23,5 +24,10 @@ struct Options {
   int prefill_wide_v;    // 0: prefill multiplies fp16 weights with V taken to fp16; 1: bf16 V, weights as bf16 hi + lo
 };
 Options& options();
+
+// The split-K merge as the fused decode call launches it (arguments already checked).  skip_single: pairs
+// of one chunk are left alone (their final rows are already written).
+fs_status merge_lse_launch(const char* who, const float* part_o, const float* part_lse, const int64_t* chunk_indptr_dev,
+                           int64_t n_pairs, int32_t group, float* out, float* lse, bool skip_single, void* stream);
 
 }  // namespace fs

@@ -40,7 +40,7 @@ template <int RW>
 __global__ void __launch_bounds__(kWavesPerBlock * 64)
 merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ part_lse,
                  const int64_t* __restrict__ chunk_indptr, int64_t n_rows, int group,
-                 float* __restrict__ out, float* __restrict__ lse) {
+                 float* __restrict__ out, float* __restrict__ lse, int skip_single) {
   constexpr int U = RW == 1 ? 4 : 2;               // chunk rows in flight per output row
   const int lane = threadIdx.x & 63;
   const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock +
@@ -50,6 +50,7 @@ merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ par
   const int g0 = static_cast<int>(row0 - p * group);
   const int64_t c0 = chunk_indptr[p];
   const int n = static_cast<int>(chunk_indptr[p + 1] - c0);
+  if (skip_single && n == 1) return;   // fused decode: the sweep has already written this pair's final rows
 
   // Chunks are taken 64 at a time (one lse per lane).  The first rows of a batch are requested before
   // its weights are known, so the two reads travel together; across batches (more than 64 chunks) the
@@ -149,6 +150,30 @@ merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ par
 
 }  // namespace
 
+namespace fs {
+
+fs_status merge_lse_launch(const char* who, const float* part_o, const float* part_lse, const int64_t* chunk_indptr_dev,
+                           int64_t n_pairs, int32_t group, float* out, float* lse, bool skip_single, void* stream_ptr) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
+  const int64_t n_rows = n_pairs * group;
+  // Output rows per wavefront (within one pair): four once one row each would be more wavefronts than the
+  // chip holds at a time (256 CUs x 32); below that, more wavefronts is what hides the latency.
+  const int rw = group % 4 == 0 && n_rows > 8192 ? 4 : 1;
+  const int64_t per_block = static_cast<int64_t>(kWavesPerBlock) * rw;
+  const unsigned blocks = static_cast<unsigned>((n_rows + per_block - 1) / per_block);
+  if (rw == 4)
+    hipLaunchKernelGGL(merge_lse_kernel<4>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, stream, part_o, part_lse,
+                       chunk_indptr_dev, n_rows, group, out, lse, skip_single ? 1 : 0);
+  else
+    hipLaunchKernelGGL(merge_lse_kernel<1>, dim3(blocks), dim3(kWavesPerBlock * 64), 0, stream, part_o, part_lse,
+                       chunk_indptr_dev, n_rows, group, out, lse, skip_single ? 1 : 0);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch of the merge failed: %s", who, hipGetErrorString(e));
+  return FS_OK;
+}
+
+}  // namespace fs
+
 extern "C" fs_status fs_merge_lse(const float* part_o, const float* part_lse, const int64_t* chunk_indptr_dev,
                                   int64_t n_pairs, int32_t group, int32_t head_dim,
                                   float* out, float* lse, void* stream) {
@@ -160,19 +185,5 @@ extern "C" fs_status fs_merge_lse(const float* part_o, const float* part_lse, co
   if (n_pairs == 0) return FS_OK;
   if (!part_o || !part_lse || !chunk_indptr_dev || !out || !lse)
     return fs::fail(FS_EINVAL, "fs_merge_lse: NULL device pointer");
-  const int64_t n_rows = n_pairs * group;
-  // Output rows per wavefront (within one pair): four once one row each would be more wavefronts than the
-  // chip holds at a time (256 CUs x 32); below that, more wavefronts is what hides the latency.
-  const int rw = group % 4 == 0 && n_rows > 8192 ? 4 : 1;
-  const int64_t per_block = static_cast<int64_t>(kWavesPerBlock) * rw;
-  const unsigned blocks = static_cast<unsigned>((n_rows + per_block - 1) / per_block);
-  if (rw == 4)
-    hipLaunchKernelGGL(merge_lse_kernel<4>, dim3(blocks), dim3(kWavesPerBlock * 64), 0,
-                       static_cast<hipStream_t>(stream), part_o, part_lse, chunk_indptr_dev, n_rows, group, out, lse);
-  else
-    hipLaunchKernelGGL(merge_lse_kernel<1>, dim3(blocks), dim3(kWavesPerBlock * 64), 0,
-                       static_cast<hipStream_t>(stream), part_o, part_lse, chunk_indptr_dev, n_rows, group, out, lse);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_merge_lse: launch failed: %s", hipGetErrorString(e));
-  return FS_OK;
+  return fs::merge_lse_launch("fs_merge_lse", part_o, part_lse, chunk_indptr_dev, n_pairs, group, out, lse, false, stream);
 }

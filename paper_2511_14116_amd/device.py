@@ -86,6 +86,16 @@ class DeviceShare:
         B.fs_merge_lse(self.part_o, self.part_lse, self.chunk_indptr, self.n_pairs, self.group,
                        self.shape.head_dim, self.out, self.lse, torch.cuda.current_stream().cuda_stream)
 
+    def run_fused(self, use_sched: bool = True, persistent: bool = True):
+        """Sweep and merge in one library call; unsplit pairs get their final rows from the sweep.  With
+        ``persistent`` the counters are handed over and the library takes the persistent sweep for long bf16 lists."""
+        if persistent and not hasattr(self, "claim"):
+            self.claim = torch.zeros(2, dtype=torch.int32, device=self.device)
+        B.fs_decode_attention_fused(self.shape, self.view, self.items, self.sched if use_sched else None, self.n_items,
+                                    self.chunk_indptr, self.n_pairs, self.part_o, self.part_lse,
+                                    self.claim if persistent else None, self.out, self.lse,
+                                    torch.cuda.current_stream().cuda_stream)
+
     def run(self, use_sched: bool = True, persistent: bool = False):
         if persistent:
             self.decode_persistent(use_sched)

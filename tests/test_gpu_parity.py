@@ -306,6 +306,27 @@ def test_repeated_launches_agree_bit_for_bit(cfg_id):
             assert torch.equal(a, b), f"launch {rep} (persistent={persistent}): {name} differs from the first launch"
 
 
+def check_fused(ds, indptr, what):
+    """fs_decode_attention_fused on the share that ``ds`` has just run the two-call way: the same final bits,
+    the same partial rows for split pairs, no partial row written for a pair that is one item."""
+    want = [t.clone() for t in (ds.part_o, ds.part_lse, ds.out, ds.lse)]
+    G = ds.group
+    counts = np.diff(indptr)
+    split_rows = torch.from_numpy(np.repeat(np.repeat(counts > 1, counts), G)).to(ds.device)   # per partial row
+    forms = (False, True) if ds.kv_dtype == fs.FS_KV_BF16 else (False,)
+    for persistent in forms:
+        for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
+            t.fill_(float("nan"))
+        ds.run_fused(persistent=persistent)
+        torch.cuda.synchronize()
+        assert torch.equal(ds.out, want[2]) and torch.equal(ds.lse, want[3]), f"{what}: fused call (persistent={persistent}) leaves other final rows"
+        assert torch.equal(ds.part_o[split_rows], want[0][split_rows]) and torch.equal(ds.part_lse[split_rows], want[1][split_rows])
+        assert torch.isnan(ds.part_lse[~split_rows]).all() and torch.isnan(ds.part_o[~split_rows]).all(), \
+            f"{what}: the fused call wrote partial rows of an unsplit pair"
+        if persistent:
+            assert ds.claim.cpu().tolist() == [0, 0]
+
+
 # ------------------------------------------------------------------------------------------------
 def _full_config(cfg_id, rank, **req_kw):
     """A config at its full size in the launch shape the benchmark times: every pair of the share against
@@ -348,6 +369,7 @@ def _full_config(cfg_id, rank, **req_kw):
         for name, a, b in zip(("part_o", "part_lse", "out", "lse"), first, (ds.part_o, ds.part_lse, ds.out, ds.lse)):
             assert torch.equal(a, b), f"{what}: persistent sweep leaves other bits in {name}"
         assert ds.claim.cpu().tolist() == [0, 0]
+    check_fused(ds, indptr, what)
     return ds
 
 
@@ -510,3 +532,28 @@ def test_persistent_sweep_random_lists_match_the_plain_sweep(seed):
     pr = pairs_rows(pairs)
     ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pr, Hkv * G, G, 1.0 / np.sqrt(128.0), workers=8)
     check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"random persistent seed {seed}, all {len(pr)} pairs")
+    check_fused(ds, indptr, f"random persistent seed {seed}")
+
+
+@pytest.mark.parametrize("cfg_id,kw,chunk", [(0, {}, 0), (0, {}, 64), (1, dict(n_req=40, max_len=2500), 512),
+                                             (4, dict(n_req=30), 0), (4, dict(n_req=30), 1024)])
+def test_fused_call_small_batches(cfg_id, kw, chunk):
+    """The one-call form on lists with no split pair (no merge is launched and no partial buffer is needed),
+    with some, and with fp8 K/V: element by element against the oracle and bit for bit against the two calls."""
+    w = make_requests(cfg_id, **kw)
+    q = make_q(w["seed"], w["n_req"], w["n_q_heads"], 128)
+    owner, _, _ = fs.fs_build_placement(shape_of(w), w["ctx_len"], w["mode"])
+    for rank in (0, w["n_ranks"] - 1):
+        ds, kv, items, pairs, sched, indptr = run_rank(w, q, rank, chunk, owner)
+        if len(items) == 0:
+            continue
+        say(f"fused cfg{cfg_id} chunk {chunk} rank {rank}: {len(items)} items, {len(pairs)} pairs")
+        check_fused(ds, indptr, f"fused cfg{cfg_id} chunk {chunk} rank {rank}")
+        ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
+        check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"fused cfg{cfg_id} chunk {chunk} rank {rank}")
+        if len(items) == len(pairs):      # nothing is split: the call takes no partial buffers at all
+            ds.out.fill_(float("nan")); ds.lse.fill_(float("nan"))
+            fs.fs_decode_attention_fused(ds.shape, ds.view, ds.items, ds.sched, ds.n_items, ds.chunk_indptr, ds.n_pairs,
+                                         None, None, None, ds.out, ds.lse, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"fused, no partial buffers, cfg{cfg_id} rank {rank}")

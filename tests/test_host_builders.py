@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
         header = f.read()
     declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
     assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_choose_chunk_tokens", "fs_decode_attention",
-            "fs_decode_attention_persistent", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
+            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
             "fs_route_request", "fs_route_requests", "fs_schedule_prefill", "fs_plan_kv_reload", "fs_replace_failed_gpu", "fs_plan_ffn_reload", "fs_kv_elem_offset", "fs_stream_read_probe", "fs_set_option", "fs_get_option", "fs_last_error",
             "fs_abi_version"} <= declared
     lib = C.CDLL(fs.library_path())
@@ -156,6 +156,15 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     kv8 = fs.FsKvView(kv_dtype=fs.FS_KV_FP8_E4M3)
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_persistent(sh, kv8, None, None, 3, None, None, None)
+    assert e.value.status == fs.FS_EUNSUPPORTED
+    # the fused call: the same checks, and the pair count must fit the list
+    fs.fs_decode_attention_fused(sh, kv, None, None, 0, None, 0, None, None, None, None, None)   # empty list: no-op
+    for n_items, n_pairs in ((3, 4), (3, -1), (3, 0), (3, 2)):          # too many pairs, negative, none, NULL pointers
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_decode_attention_fused(sh, kv, None, None, n_items, None, n_pairs, None, None, None, None, None)
+        assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention_fused(_shape(1, 4, 2, 3, d=64), kv, None, None, 3, None, 3, None, None, None, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
     # prefill: empty list is a no-op; a tile beyond the kernel's is refused before any launch
     fs.fs_prefill_attention(sh, kv, None, None, 0, 1, None, None)
