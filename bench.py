@@ -5,7 +5,8 @@
 
 A step is one pass of the whole hot path over one synthetic batch: placement (S1+S2) and the
 rank's work list (S3) built on the host by the library, the list copied to the GPU, the
-attention sweep (S4) and the split-K merge (S5).  Q, the paged K/V pool and the page table are
+attention sweep (S4) and the split-K merge (S5) - the last two as one library call
+(fs_decode_attention_fused: pairs that are a single item need no merge).  Q, the paged K/V pool and the page table are
 resident in HBM before the timed region starts.  Host work for step t+1 overlaps the GPU work
 of step t (nothing synchronises inside the timed region), as it would in a serving loop.
 
@@ -25,12 +26,14 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
-# (see profiles/); None until measured for that workload.
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (see
+# profiles/).  A figure belongs to one kernel on one list: the key is (config, rank, seed, chunk, placement,
+# kernel); any other run reports null.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_rank0": 1971402660,    # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
-    "cfg4_rank0": 1609662362,    # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
+    (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971402660,   # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
+    (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1609662362,                  # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
 }
+KERNEL_LAUNCHES = 30       # launches of the attention kernel timed one by one for the roofline figure
 
 
 def main() -> int:
@@ -52,6 +55,8 @@ def main() -> int:
     ap.add_argument("--persistent", action="store_true",
                     help="bf16: the persistent form of the sweep (fs_decode_attention_persistent: workgroups claim items, "
                          "partial rows leave in bursts) even for short lists; by default it is used from 1024 items on")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="the step calls fs_decode_attention[_persistent] and fs_merge_lse instead of fs_decode_attention_fused")
     ap.add_argument("--placement", choices=["requests", "heads"], default="requests",
                     help="requests: the batch's TP/DP mix per request; heads: the paper's head-level hybrid (layer 0)")
     ap.add_argument("--cold", action="store_true", help="also time the kernels with L2 and the memory-side cache scrubbed before every launch")
@@ -139,10 +144,18 @@ def main() -> int:
     scale_bytes = n_pages * 8 if w["kv_dtype"] == "fp8" else 0
     q_bytes = n_pairs * G * w["head_dim"] * 2
     table_bytes = n_pages * 4 + n_items * 32 + n_items * 4
-    part_bytes = n_items * G * (w["head_dim"] * 4 + 4)
-    out_bytes = n_pairs * G * (w["head_dim"] * 4 + 4)
-    decode_bytes = kv_bytes + scale_bytes + q_bytes + table_bytes + part_bytes
-    merge_bytes = part_bytes + out_bytes + (n_pairs + 1) * 8
+    row_bytes = w["head_dim"] * 4 + 4                       # one fp32 output row and its lse
+    counts = np.diff(chunk_indptr)
+    if args.two_calls:                                      # every item writes partial rows, the merge reads them all
+        n_part_items, n_direct_pairs = n_items, 0
+    else:                                                   # fused: only split pairs go through partial rows
+        n_part_items, n_direct_pairs = int(counts[counts > 1].sum()), int((counts == 1).sum())
+    part_bytes = n_part_items * G * row_bytes
+    decode_bytes = (kv_bytes + scale_bytes + q_bytes + table_bytes + part_bytes + n_direct_pairs * G * row_bytes
+                    + (0 if args.two_calls else (n_pairs + 1) * 8))
+    merge_bytes = part_bytes + (n_pairs - n_direct_pairs) * G * row_bytes + (n_pairs + 1) * 8
+    if not args.two_calls and n_part_items == 0:
+        merge_bytes = 0                                     # nothing is split: no merge is launched
     step_bytes = decode_bytes + merge_bytes
 
     # ---- device buffers for the per-step work list -----------------------------------------------
@@ -189,10 +202,15 @@ def main() -> int:
     # The persistent form pays off once every workgroup walks several items (it saves the scattered stores
     # and the relaunches); with one item or fewer per workgroup slot it is the same work plus a counter.
     persistent = w["kv_dtype"] == "bf16" and not args.classic and (args.persistent or n_items >= 1024)
+    if args.persistent and n_items < 1024 and not args.two_calls:
+        print("bench.py: --persistent below 1024 items needs --two-calls (the fused call picks the sweep by list length)",
+              file=sys.stderr)
+        return 2
     claim = torch.zeros(2, dtype=torch.int32, device=dev)    # the persistent sweep's counters; every launch leaves them at zero
 
     def bind_gpu_calls(stream_ptr):
-        dec, mrg = [], []
+        """Per blob: the sweep alone, the merge alone, and the one-call form of both."""
+        dec, mrg, fused = [], [], []
         for db in dev_blobs:
             base = db.data_ptr()
             if persistent:
@@ -203,9 +221,12 @@ def main() -> int:
                                                     part_o, part_lse, stream_ptr))
             mrg.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"],
                                          out, lse, stream_ptr))
-        return dec, mrg
+            fused.append(fs.bind_decode_attention_fused(shape, ds.view, base + off_items, base + off_sched, n_items,
+                                                        base + off_indptr, n_pairs, part_o, part_lse,
+                                                        claim if persistent else None, out, lse, stream_ptr))
+        return dec, mrg, fused
 
-    call_decode, call_merge = bind_gpu_calls(sptr)
+    call_decode, call_merge, call_fused = bind_gpu_calls(sptr)
 
     def build_host(slot: int):
         load_buf.fill(0)
@@ -216,13 +237,15 @@ def main() -> int:
 
     # The GPU side of step i reads device blob i % N_SLOTS and, next to it, uploads the blob of
     # step i+1 (which the host has built by then), so the upload never sits between two sweeps.
-    def enqueue_eager(slot: int, ev=None):
-        if ev is not None:
-            ev[0].record(stream)
-        call_decode[slot]()                                 # S4
-        if ev is not None:
-            ev[1].record(stream)
-        call_merge[slot]()                                  # S5
+    def gpu_side(dec, mrg, fused, slot: int):
+        if args.two_calls:
+            dec[slot]()                                     # S4
+            mrg[slot]()                                     # S5
+        else:
+            fused[slot]()                                   # S4 + S5
+
+    def enqueue_eager(slot: int):
+        gpu_side(call_decode, call_merge, call_fused, slot)
         nxt = (slot + 1) % N_SLOTS
         dev_blobs[nxt].copy_(host_blobs[nxt], non_blocking=True)
 
@@ -237,22 +260,20 @@ def main() -> int:
     graphs = None
     if not args.no_graph:
         cap_stream = torch.cuda.Stream()
-        cap_decode, cap_merge = bind_gpu_calls(cap_stream.cuda_stream)
+        cap_decode, cap_merge, cap_fused = bind_gpu_calls(cap_stream.cuda_stream)
         graphs = []
         for slot in range(N_SLOTS):
             g = torch.cuda.CUDAGraph()
             nxt = (slot + 1) % N_SLOTS
             with torch.cuda.graph(g, stream=cap_stream):
-                cap_decode[slot]()
-                cap_merge[slot]()
+                gpu_side(cap_decode, cap_merge, cap_fused, slot)
                 dev_blobs[nxt].copy_(host_blobs[nxt], non_blocking=True)
             graphs.append(g)
         torch.cuda.synchronize()
 
     host_us, wait_us, enqueue_us = [], [], []
-    EVENT_EVERY = 16         # every 16th step runs eagerly with HIP events around the attention kernel (an eager step costs ~25 us more)
 
-    def step(i: int, ev=None):
+    def step(i: int):
         # on entry the blob of step i is built and its upload is enqueued; build the one of step i+1
         t0 = time.perf_counter()
         slot, nxt = i % N_SLOTS, (i + 1) % N_SLOTS
@@ -261,8 +282,8 @@ def main() -> int:
         t1 = time.perf_counter()
         build_host(nxt)
         t2 = time.perf_counter()
-        if graphs is None or ev is not None:
-            enqueue_eager(slot, ev)
+        if graphs is None:
+            enqueue_eager(slot)
         else:
             graphs[slot].replay()
         slot_done[slot].record(stream)
@@ -277,16 +298,33 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
     host_us.clear(); wait_us.clear(); enqueue_us.clear()
-    timed = [i for i in range(args.steps) if graphs is None or i % EVENT_EVERY == 0]
-    events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(2)] for i in timed}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, events.get(i))
+        step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    dec_ms = np.array([e[0].elapsed_time(e[1]) for e in events.values()])
+
+    # The attention kernel alone, after the region (events inside it would only add gaps): KERNEL_LAUNCHES launches
+    # whatever --steps is, each between its own pair of HIP events on the stream it is launched on.  It is the sweep the
+    # step runs (same kernel, same list); in the fused step the rows of unsplit pairs go to out instead of part_o.
+    def time_each(call, n):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n)]
+        for a, b in evs:
+            a.record(stream)
+            call()
+            b.record(stream)
+        torch.cuda.synchronize()
+        return np.array([a.elapsed_time(b) for a, b in evs])
+
+    build_host(0)
+    dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
+    for _ in range(3):
+        call_decode[0]()
+    torch.cuda.synchronize()
+    dec_ms = time_each(call_decode[0], KERNEL_LAUNCHES)
+    fused_ms = time_each(call_fused[0], KERNEL_LAUNCHES)       # sweep + merge of the split pairs, as the step runs them
 
     # a graph step and an eager step must leave the same bits behind
     if graphs is not None:
@@ -301,6 +339,12 @@ def main() -> int:
         torch.cuda.synchronize()
         if not (torch.equal(g_out, out) and torch.equal(g_lse, lse)):
             print("bench.py: graph replay and eager launch disagree", file=sys.stderr)
+            return 1
+        out.fill_(float("nan")); lse.fill_(float("nan"))        # and so must the two-call and the one-call form
+        call_decode[0](); call_merge[0]()
+        torch.cuda.synchronize()
+        if not (torch.equal(g_out, out) and torch.equal(g_lse, lse)):
+            print("bench.py: fs_decode_attention_fused and the two calls disagree", file=sys.stderr)
             return 1
 
     # the merge kernel alone, timed after the region (its events would only add gaps inside it)
@@ -367,13 +411,14 @@ def main() -> int:
             kv_k = make_kv_pool(w["seed"], np.stack([pr_k["req"], pr_k["kv_head"]], axis=1), ctx, kv_dtype=w["kv_dtype"])
             ds_k = DeviceShare(shape, q_bits, kv_k, w["sm_scale"], interleave_kv=not args.separate_kv)
             ds_k.set_worklist(it_k, pr_k, sc_k, ip_k)
+            run_k = (lambda: ds_k.run(persistent=persistent)) if args.two_calls else (lambda: ds_k.run_fused(persistent=persistent))
             for _ in range(5):
-                ds_k.run(persistent=persistent)
+                run_k()
             r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             reps = 30
             r0.record(stream)
             for _ in range(reps):
-                ds_k.run(persistent=persistent)
+                run_k()
             r1.record(stream)
             torch.cuda.synchronize()
             us = r0.elapsed_time(r1) * 1e3 / reps
@@ -421,7 +466,11 @@ def main() -> int:
 
     dec_avg_ms = float(dec_ms.mean())
     achieved = decode_bytes / (dec_avg_ms * 1e-3) / 1e9
-    key = f"cfg{args.config}_rank{args.rank}"
+    kernel_name = "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else ("decode_bf16_persistent_kernel" if persistent
+                                                                        else "decode_bf16_kernel")
+    default_shape = (args.waves in (None, 4) and args.prefetch in (None, 2) and not args.separate_kv
+                     and not (args.config == 3 and args.force_tail))
+    key = (args.config, args.rank, w["seed"], chunk, args.placement, kernel_name) if default_shape else None
     result = {
         "metric": "achieved HBM GB/s (% of peak) and KV-token-heads/s, rank-0 share, 1 MI355X",
         "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 2),
@@ -436,24 +485,27 @@ def main() -> int:
                                + (", head-level hybrid placement" if args.placement == "heads" else ""),
                    "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
-                   "sweep": "persistent (fs_decode_attention_persistent)" if persistent else "one workgroup per item (fs_decode_attention)",
+                   "sweep": "persistent" if persistent else "one workgroup per item",
+                   "step_calls": "fs_decode_attention[_persistent] + fs_merge_lse" if args.two_calls else "fs_decode_attention_fused",
+                   "merge_launched": bool(args.two_calls or n_items > n_pairs),
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),
                    "kv_layout": "separate" if args.separate_kv else "interleaved",
-                   "launch": "eager" if graphs is None else f"hip graph per slot; every {EVENT_EVERY}th step eager with events"},
+                   "launch": "eager" if graphs is None else "hip graph per slot"},
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "kv_token_heads_per_s": round(tok_heads / (ms_per_step * 1e-3), 1),
         "kernel_ms": {"decode_avg": round(dec_avg_ms, 5), "decode_p50": round(float(np.median(dec_ms)), 5),
                       "decode_p10": round(float(np.percentile(dec_ms, 10)), 5),
                       "decode_p90": round(float(np.percentile(dec_ms, 90)), 5),
-                      "merge_avg": round(float(mrg_ms.mean()), 5)},
+                      "decode_launches": int(len(dec_ms)),
+                      "sweep_plus_merge_avg": round(float(fused_ms.mean()), 5),
+                      "merge_alone_avg": round(float(mrg_ms.mean()), 5)},
         "host_us_per_step": {"builders_avg": round(float(np.mean(host_us)), 1),
                              "builders_p90": round(float(np.percentile(host_us, 90)), 1),
                              "enqueue_avg": round(float(np.mean(enqueue_us)), 1),
                              "wait_for_gpu_avg": round(float(np.mean(wait_us)), 1)},
         "stream_read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
-        "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else
-                     ("decode_bf16_persistent_kernel" if persistent else "decode_bf16_kernel"),
+        "roofline": {"bound": "hbm", "kernel": kernel_name,
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "algorithmic_bytes_per_launch": decode_bytes,

@@ -425,6 +425,32 @@ FS_API fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_kv_vi
                                            float* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * fs_decode_attention_fused_static - fs_decode_attention_fused for callers that cannot allocate
+ * device memory or hand over a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The counters of the persistent sweep and the partial rows of
+ * split pairs live in a fixed array inside the library (16 MiB + 128 KiB + 256 B of device memory,
+ * held on every GPU the library runs on until the process ends) instead of in part_o, part_lse and
+ * claim_dev; the call allocates and frees nothing.  The sweep is the persistent one for bf16 K/V
+ * from 1024 items on, one workgroup per item otherwise; out/lse are, bit for bit, what
+ * fs_decode_attention_fused leaves with the same sweep.
+ *
+ *  Limit: a list with a split pair (n_items > n_pairs) may have at most 32768 partial rows,
+ *  n_items * G <= 32768, else FS_ECAPACITY and nothing is launched.  A list without a split pair
+ *  has no such limit.
+ *  Every call on one GPU uses that GPU's one array: calls that may overlap in time on one GPU
+ *  (two streams, two threads) race and must be serialised by the caller.  The array keeps the last
+ *  call's contents; the call clears the counters it needs at zero itself (a fill kernel).
+ *  The first call on a device looks up the array's address (not a stream operation): make one
+ *  call on each device before capturing a graph that contains this call.
+ *
+ * Everything else (arguments, errors) as for fs_decode_attention_fused.
+ */
+FS_API fs_status fs_decode_attention_fused_static(const fs_shape* shape, const fs_kv_view* kv,
+                                                  const fs_work_item* items_dev, const int32_t* sched_dev,
+                                                  int64_t n_items, const int64_t* chunk_indptr_dev,
+                                                  int64_t n_pairs, float* out, float* lse, void* stream);
+
+/* ---------------------------------------------------------------------------
  * fs_merge_lse - combine the chunk partials of each pair (split-K merge):
  *     lse = ln sum_c exp(lse_c),   out = sum_c exp(lse_c - lse) * o_c
  * Rows [p*G, p*G+G) of out/lse belong to pair p; its partial rows are

@@ -52,6 +52,12 @@ def load_library(path: str | None = None):
     if _LIB is not None and path is None:
         return _LIB
     p = path or library_path()
+    try:
+        # PyTorch ships a HIP runtime of its own.  If this library were loaded first it would bring in the system's,
+        # and a process with both finds no device for this library's kernels; loading torch first makes both use one.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(p):
         raise FileNotFoundError(
             f"{p} is not built; run `python -m paper_2511_14116_amd.build` (needs hipcc) first")
@@ -101,6 +107,9 @@ def load_library(path: str | None = None):
                                               C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_decode_attention_fused.restype = C.c_int
+    lib.fs_decode_attention_fused_static.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
+                                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fs_decode_attention_fused_static.restype = C.c_int
     lib.fs_merge_lse.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                  C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_merge_lse.restype = C.c_int
@@ -410,6 +419,14 @@ def fs_decode_attention_fused(shape: FsShape, kv: FsKvView, items_dev, sched_dev
     st = load_library().fs_decode_attention_fused(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
                                                   n_items, _ptr(chunk_indptr_dev), n_pairs, _ptr(part_o),
                                                   _ptr(part_lse), _ptr(claim_dev), _ptr(out), _ptr(lse), _ptr(stream))
+    _check(st)
+
+
+def fs_decode_attention_fused_static(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int,
+                                     chunk_indptr_dev, n_pairs: int, out, lse, stream=None) -> None:
+    st = load_library().fs_decode_attention_fused_static(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
+                                                         n_items, _ptr(chunk_indptr_dev), n_pairs, _ptr(out), _ptr(lse),
+                                                         _ptr(stream))
     _check(st)
 
 

@@ -25,6 +25,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <type_traits>
 
 #include "fs_internal.h"
@@ -716,6 +717,24 @@ fs_status launch(const char* who, K kernel, int threads, const DecodeParams& P, 
   return FS_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Device memory of the entry point that allocates nothing (fs_decode_attention_fused_static): the
+// persistent sweep's two counters and the partial rows of split pairs live in this array instead of
+// in buffers the caller brings.  Every GPU the library runs on holds its own copy, at its own
+// address, until the process ends.  Layout: [0, 256) counters | partial rows | their lse values.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the address
+// that call returns.
+// ---------------------------------------------------------------------------------------------
+constexpr int64_t kStaticRows = 32768;                                            // partial rows it holds
+constexpr int64_t kStaticOffO = 256;
+constexpr int64_t kStaticOffLse = kStaticOffO + kStaticRows * fs::kHeadDim * 4;
+constexpr int64_t kStaticBytes = kStaticOffLse + kStaticRows * 4;                 // 16 MiB + 128 KiB + 256 B
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+__global__ void zero_counters_kernel(int* __restrict__ claim) {
+  if (threadIdx.x < 2) claim[threadIdx.x] = 0;
+}
+
 // ---- host side -------------------------------------------------------------------------------
 
 // Argument checks shared by the entry points.  `who` names the call in messages.  On FS_OK with
@@ -890,4 +909,66 @@ extern "C" fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_k
                                   : launch_plain(who, P, kv->kv_dtype, n_items, s);
   if (st != FS_OK || !split) return st;
   return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
+}
+
+extern "C" fs_status fs_decode_attention_fused_static(const fs_shape* shape, const fs_kv_view* kv,
+                                                      const fs_work_item* items_dev, const int32_t* sched_dev,
+                                                      int64_t n_items, const int64_t* chunk_indptr_dev,
+                                                      int64_t n_pairs, float* out, float* lse, void* stream) {
+  const char* who = "fs_decode_attention_fused_static";
+  if (n_pairs < 0 || n_pairs > n_items) return fs::fail(FS_EINVAL, "%s: n_pairs %lld outside [0, n_items]", who,
+                                                        static_cast<long long>(n_pairs));
+  const bool split = n_items > n_pairs;
+  DecodeParams P;
+  if (const fs_status st = prepare(who, shape, kv, items_dev, sched_dev, n_items, nullptr, nullptr, false, false, &P);
+      st != FS_OK || n_items == 0)
+    return st;
+  if (n_pairs == 0) return fs::fail(FS_EINVAL, "%s: %lld items but no pairs", who, static_cast<long long>(n_items));
+  if (!chunk_indptr_dev || !out || !lse || (reinterpret_cast<uintptr_t>(out) & 15))
+    return fs::fail(FS_EINVAL, "%s: chunk_indptr_dev, out or lse is NULL, or out is not 16-byte aligned", who);
+  if (split && n_items * P.group > kStaticRows)
+    return fs::fail(FS_ECAPACITY, "%s: a split list of %lld items x %d q-heads needs %lld partial rows, the static "
+                                  "array holds %lld; use fs_decode_attention_fused with buffers of your own", who,
+                    static_cast<long long>(n_items), P.group, static_cast<long long>(n_items * P.group),
+                    static_cast<long long>(kStaticRows));
+  // The array's address on the current device, asked once per device with that device current.
+  static unsigned char* base_of_device[64] = {};
+  static std::mutex lock;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    return fs::fail(FS_EHIP, "%s: cannot identify the current device", who);
+  unsigned char* base = nullptr;
+  {
+    std::lock_guard<std::mutex> hold(lock);
+    base = base_of_device[dev];
+    if (!base) {
+      void* p = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return fs::fail(FS_EHIP, "%s: cannot resolve the static array on device %d: %s", who, dev, hipGetErrorString(e));
+      base = base_of_device[dev] = static_cast<unsigned char*>(p);
+    }
+  }
+  int32_t* claim = reinterpret_cast<int32_t*>(base);
+  P.part_o = reinterpret_cast<float*>(base + kStaticOffO);
+  P.part_lse = reinterpret_cast<float*>(base + kStaticOffLse);
+  P.chunk_indptr = chunk_indptr_dev;
+  P.out = out;
+  P.lse = lse;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool persistent = kv->kv_dtype == FS_KV_BF16 && n_items >= fs::kPersistentMinItems;
+  fs_status st;
+  if (persistent) {
+    // The array keeps what the last call left.  A completed sweep leaves its counters at zero, but this
+    // call does not rest on that: it clears them itself (a fill kernel, which a captured graph replays
+    // faithfully).
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, claim);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    st = launch_persistent(who, P, n_items, claim, s);
+  } else {
+    st = launch_plain(who, P, kv->kv_dtype, n_items, s);
+  }
+  if (st != FS_OK || !split) return st;
+  return fs::merge_lse_launch(who, P.part_o, P.part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
 }
