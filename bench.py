@@ -47,9 +47,17 @@ def main() -> int:
     ap.add_argument("--waves", type=int, default=None)
     ap.add_argument("--prefetch", type=int, default=None)
     ap.add_argument("--separate-kv", action="store_true", help="K and V in two pools instead of interleaved")
+    ap.add_argument("--scales-by-slot", action="store_true",
+                    help="fp8: the kernels gather the scales from the by-slot arrays instead of reading them in page-table order")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-graph", action="store_true", help="prefill path: launch every step eagerly instead of replaying HIP graphs")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the GPU side of a step as a HIP graph per slot instead of launching it eagerly (measured "
+                         "slower here: ~14 us pass between the end of one graph and the first kernel of the next)")
+    ap.add_argument("--list", choices=["host", "device"], default="host",
+                    help="where the kernels read the step's work list: host = in place from the pinned host memory the "
+                         "builder writes (no upload; default); device = a copy uploaded every step")
     ap.add_argument("--classic", action="store_true",
                     help="bf16: one workgroup per item (fs_decode_attention) even for long lists")
     ap.add_argument("--persistent", action="store_true",
@@ -134,7 +142,8 @@ def main() -> int:
     kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx, kv_dtype=w["kv_dtype"])
 
     from paper_2511_14116_amd.device import DeviceShare
-    ds = DeviceShare(shape, q_bits, kv, w["sm_scale"], interleave_kv=not args.separate_kv)
+    ds = DeviceShare(shape, q_bits, kv, w["sm_scale"], interleave_kv=not args.separate_kv,
+                     scales_by_page=not args.scales_by_slot)
 
     # ---- algorithmic bytes ---------------------------------------------------------------------
     tok_heads = int(rank_load[args.rank])
@@ -158,11 +167,12 @@ def main() -> int:
         merge_bytes = 0                                     # nothing is split: no merge is launched
     step_bytes = decode_bytes + merge_bytes
 
-    # ---- device buffers for the per-step work list -----------------------------------------------
-    # One blob per step holds items | sched | chunk_indptr.  The host writes it into pinned memory
-    # (N_SLOTS buffers in rotation, each with its own device blob).  The GPU side of a step - copy
-    # the blob, sweep, merge - is captured once per slot as a HIP graph, so a step costs the host
-    # one graph launch and the GPU sees the three nodes back to back.
+    # ---- buffers for the per-step work list --------------------------------------------------------
+    # One blob per step holds items | sched | chunk_indptr.  The host builds it in pinned memory (N_SLOTS
+    # buffers in rotation), which is mapped into the GPU's address space: by default the kernels read the
+    # list in place (85 KB per step on the 70B-shaped batch, fetched once per item while the previous item's
+    # rows are merged), so a step is one library call, launched eagerly.  --list device uploads the blob
+    # into HBM every step instead; --graph replays sweep, merge (and upload) as one HIP graph per slot.
     def up(x):
         return (x + 255) & ~255
     off_items = 0
@@ -211,8 +221,8 @@ def main() -> int:
     def bind_gpu_calls(stream_ptr):
         """Per blob: the sweep alone, the merge alone, and the one-call form of both."""
         dec, mrg, fused = [], [], []
-        for db in dev_blobs:
-            base = db.data_ptr()
+        for db in (host_blobs if host_list else dev_blobs):
+            base = db.data_ptr()        # a pinned host blob is mapped into the GPU's address space at the same address
             if persistent:
                 dec.append(fs.bind_decode_attention_persistent(shape, ds.view, base + off_items, base + off_sched,
                                                                n_items, claim, part_o, part_lse, stream_ptr))
@@ -226,7 +236,12 @@ def main() -> int:
                                                         claim if persistent else None, out, lse, stream_ptr))
         return dec, mrg, fused
 
+    host_list = args.list == "host"
     call_decode, call_merge, call_fused = bind_gpu_calls(sptr)
+
+    def upload(slot: int):
+        if not host_list:
+            dev_blobs[slot].copy_(host_blobs[slot], non_blocking=True)
 
     def build_host(slot: int):
         load_buf.fill(0)
@@ -246,19 +261,18 @@ def main() -> int:
 
     def enqueue_eager(slot: int):
         gpu_side(call_decode, call_merge, call_fused, slot)
-        nxt = (slot + 1) % N_SLOTS
-        dev_blobs[nxt].copy_(host_blobs[nxt], non_blocking=True)
+        upload((slot + 1) % N_SLOTS)
 
     for slot in range(N_SLOTS):                             # warm everything up eagerly once
         build_host(slot)
-    dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
+    upload(0)
     for slot in range(N_SLOTS):
         enqueue_eager(slot)
     torch.cuda.synchronize()
 
     # one HIP graph per slot: sweep -> merge -> upload of the next step's blob
     graphs = None
-    if not args.no_graph:
+    if args.graph:
         cap_stream = torch.cuda.Stream()
         cap_decode, cap_merge, cap_fused = bind_gpu_calls(cap_stream.cuda_stream)
         graphs = []
@@ -267,7 +281,7 @@ def main() -> int:
             nxt = (slot + 1) % N_SLOTS
             with torch.cuda.graph(g, stream=cap_stream):
                 gpu_side(cap_decode, cap_merge, cap_fused, slot)
-                dev_blobs[nxt].copy_(host_blobs[nxt], non_blocking=True)
+                upload(nxt)
             graphs.append(g)
         torch.cuda.synchronize()
 
@@ -277,8 +291,10 @@ def main() -> int:
         # on entry the blob of step i is built and its upload is enqueued; build the one of step i+1
         t0 = time.perf_counter()
         slot, nxt = i % N_SLOTS, (i + 1) % N_SLOTS
-        while not slot_done[slot].query():                  # step i-N_SLOTS, the last reader of pinned blob nxt,
-            pass                                            # is done (busy poll: a blocking wait costs a timer tick)
+        # the last reader of pinned blob nxt must be done: the upload in step i-N_SLOTS, or, when the kernels read the
+        # list in place, step i+1-N_SLOTS itself (busy poll: a blocking wait costs a timer tick)
+        while not slot_done[nxt if host_list else slot].query():
+            pass
         t1 = time.perf_counter()
         build_host(nxt)
         t2 = time.perf_counter()
@@ -293,7 +309,7 @@ def main() -> int:
         enqueue_us.append((t3 - t2) * 1e6)
 
     build_host(0)
-    dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
+    upload(0)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -319,7 +335,7 @@ def main() -> int:
         return np.array([a.elapsed_time(b) for a, b in evs])
 
     build_host(0)
-    dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
+    upload(0)
     for _ in range(3):
         call_decode[0]()
     torch.cuda.synchronize()
@@ -330,7 +346,7 @@ def main() -> int:
     if graphs is not None:
         build_host(0)
         build_host(1)
-        dev_blobs[0].copy_(host_blobs[0], non_blocking=True)
+        upload(0)
         graphs[0].replay()
         torch.cuda.synchronize()
         g_out, g_lse = out.clone(), lse.clone()
@@ -469,7 +485,7 @@ def main() -> int:
     kernel_name = "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else ("decode_bf16_persistent_kernel" if persistent
                                                                         else "decode_bf16_kernel")
     default_shape = (args.waves in (None, 4) and args.prefetch in (None, 2) and not args.separate_kv
-                     and not (args.config == 3 and args.force_tail))
+                     and not args.scales_by_slot and not (args.config == 3 and args.force_tail))
     key = (args.config, args.rank, w["seed"], chunk, args.placement, kernel_name) if default_shape else None
     result = {
         "metric": "achieved HBM GB/s (% of peak) and KV-token-heads/s, rank-0 share, 1 MI355X",
@@ -491,7 +507,9 @@ def main() -> int:
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),
                    "kv_layout": "separate" if args.separate_kv else "interleaved",
-                   "launch": "eager" if graphs is None else "hip graph per slot"},
+                   "fp8_scales": None if w["kv_dtype"] != "fp8" else ("by slot" if args.scales_by_slot else "page-table order"),
+                   "launch": "eager" if graphs is None else "hip graph per slot",
+                   "work_list": "read in place from pinned host memory" if host_list else "uploaded every step"},
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "kv_token_heads_per_s": round(tok_heads / (ms_per_step * 1e-3), 1),
         "kernel_ms": {"decode_avg": round(dec_avg_ms, 5), "decode_p50": round(float(np.median(dec_ms)), 5),

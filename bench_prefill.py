@@ -78,8 +78,7 @@ def run(args) -> int:
         fs.fs_set_option("prefill_waves", args.prefill_waves)
     if args.prefill_col_tiles:
         fs.fs_set_option("prefill_col_tiles", args.prefill_col_tiles)
-    if args.prefill_wide_v:
-        fs.fs_set_option("prefill_wide_v", 1)
+    v_range = fs.FS_V_ANY if args.prefill_wide_v else fs.FS_V_FP16_RANGE     # the batch's V is N(0,1): exact in fp16
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream()
@@ -95,7 +94,7 @@ def run(args) -> int:
     kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx)
     q_indptr = np.concatenate([[0], np.cumsum(w["n_new"])]).astype(np.int64)
     q = make_prefill_q(w["seed"], int(q_indptr[-1]), shape.n_q_heads, 128)
-    ds = DeviceShare(shape, q, kv, 1.0 / np.sqrt(128.0))
+    ds = DeviceShare(shape, q, kv, 1.0 / np.sqrt(128.0), v_range=v_range)
     ds.set_prefill_worklist(items, w["sched"], w["chunk_indptr"], w["tile"])
     flops = algorithmic_flops(pairs, G)
     rows = int(sum(int(p["n_new"]) for p in pairs)) * G
@@ -255,14 +254,14 @@ def run(args) -> int:
         "metric": "chunked-prefill attention TFLOP/s (% of bf16 MFMA peak) and query-token-heads/s, rank-0 share, 1 MI355X",
         "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 (second product in fp16)" if not fs.fs_get_option("prefill_wide_v") else "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 (second product in fp16)" if not args.prefill_wide_v else "bf16", "data": "synthetic",
         "config": {"workload": f"prefill batch: {args.prefill_queue} waiting prompts (lognormal median 8001, cap 123192), budget {args.prefill_budget} tokens, "
                                f"Hq=64, Hkv=8, d=128, page=16, R=7 head-level hybrid, rank {args.rank}, seed={w['seed']}",
                    "n_pairs": len(pairs), "n_tiles": ds.n_prefill_tiles, "n_items": len(items), "tile_tokens": w["tile"],
                    "kv_chunk_tokens": kv_chunk, "batch_tokens": int(w["n_tokens"]),
                    "query_rows": rows, "kv_tokens_of_pairs": kv_tokens, "flops": flops,
                    "prefill_waves": fs.fs_get_option("prefill_waves"), "prefill_col_tiles": fs.fs_get_option("prefill_col_tiles"),
-                   "second_product": "bf16 V, weights bf16 hi+lo" if fs.fs_get_option("prefill_wide_v") else "fp16 V and weights",
+                   "second_product": "bf16 V, weights bf16 hi+lo (v_range FS_V_ANY)" if args.prefill_wide_v else "fp16 V and weights (v_range FS_V_FP16_RANGE)",
                    "launch": "eager" if args.no_graph else f"hip graph per staging blob (upload, attention, merge); every {EVENT_EVERY}th step eager with events"},
         "kernel_ms": {"prefill_avg": round(k_avg, 5), "prefill_p10": round(float(np.percentile(k_ms, 10)), 5),
                       "prefill_p90": round(float(np.percentile(k_ms, 90)), 5), "merge_avg": round(float(m_ms.mean()), 5)},

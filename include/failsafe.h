@@ -40,7 +40,7 @@
 extern "C" {
 #endif
 
-#define FS_ABI_VERSION 1
+#define FS_ABI_VERSION 2
 
 #if defined(__GNUC__)
 #define FS_API __attribute__((visibility("default")))
@@ -58,6 +58,15 @@ typedef enum {
 
 enum { FS_MODE_TP = 0, FS_MODE_DP = 1 };          /* per request                  */
 enum { FS_KV_BF16 = 0, FS_KV_FP8_E4M3 = 1 };      /* storage type of K and V      */
+/* What the caller states about the V values a call can read (fs_kv_view.v_range; used by
+ * fs_prefill_attention, ignored by the decode calls):
+ *   FS_V_ANY         nothing: any finite bf16 value.  V stays bf16 in the P.V product and the
+ *                    softmax weights enter as a sum of two bf16 terms.
+ *   FS_V_FP16_RANGE  every V value is 0 or has a magnitude in [2^-14, 65504], i.e. converts to
+ *                    fp16 exactly.  The product then runs on fp16 weights and fp16 V (~20% faster).
+ *                    A value that breaks the statement is not detected: a larger magnitude counts
+ *                    as 65504, a smaller one is rounded toward zero on fp16's subnormal grid. */
+enum { FS_V_ANY = 0, FS_V_FP16_RANGE = 1 };
 
 /* Shape of one decode batch. */
 typedef struct {
@@ -345,6 +354,12 @@ typedef struct {
   const int32_t* page_ids;     /* DEVICE [page_indptr[n_pairs]]                   */
   int32_t kv_dtype;            /* FS_KV_BF16 or FS_KV_FP8_E4M3                    */
   float sm_scale;              /* softmax scale, 1/sqrt(head_dim) in the paper's models */
+  const float* page_scales;    /* DEVICE [page_indptr[n_pairs]][2] or NULL: fp8 only, the same scales in
+                                  page-table order, entry j = (K scale, V scale) of slot page_ids[j].  When
+                                  given, the decode kernels read these (a contiguous run along an item,
+                                  0.2% of the K/V bytes) and k_scale/v_scale may be NULL; the by-slot
+                                  arrays cost one memory line per slot and scale, ~4% of the bytes.      */
+  int32_t v_range;             /* FS_V_ANY (0) or FS_V_FP16_RANGE: see the enum                           */
 } fs_kv_view;
 
 /* Element offset (in elements) of (tok, d) inside a slot; is_v selects the V
@@ -548,9 +563,8 @@ FS_API int32_t fs_prefill_tile_tokens(int32_t group);
  * gets part_o = 0 and part_lse = -inf.  Rows of a short last tile beyond its tokens
  * are written as zeros (part_lse = 0).  fs_merge_lse(part_o, part_lse,
  * chunk_indptr, n_tiles, T, head_dim, out, lse) then gives the final rows.  fp32
- * scores, softmax and accumulation; in P.V the softmax weights and V enter as fp16
- * (V beyond +-65504 as +-65504), or, with option "prefill_wide_v" = 1, V as bf16 and
- * the weights as a sum of two bf16 terms (see fs_set_option).
+ * scores, softmax and accumulation; in P.V, V enters as bf16 and the softmax weights as
+ * a sum of two bf16 terms, or, when kv->v_range == FS_V_FP16_RANGE, both as fp16.
  *
  *  items_dev  DEVICE in  [n_items]   as built by fs_build_prefill_worklist
  *  sched_dev  DEVICE in  [n_items]   launch order, or NULL for index order
@@ -560,7 +574,8 @@ FS_API int32_t fs_prefill_tile_tokens(int32_t group);
  *  part_lse   DEVICE out [n_items*T] fp32
  *
  * n_items == 0 is a no-op.  FS_EINVAL: NULL pointers, bad shape, G > 16,
- * tile_tokens out of range, misaligned pools.  FS_EUNSUPPORTED: head_dim != 128,
+ * tile_tokens out of range, misaligned pools, sm_scale not finite or <= 0 (the kernel's
+ * lazy running maximum is taken on the raw scores), unknown v_range.  FS_EUNSUPPORTED: head_dim != 128,
  * page_tokens != 16, K/V not bf16.  FS_EHIP: launch failure. */
 FS_API fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* kv,
                                       const fs_prefill_item* items_dev, const int32_t* sched_dev,
@@ -580,13 +595,11 @@ FS_API fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* k
  */
 FS_API fs_status fs_stream_read_probe(const void* buf_dev, int64_t bytes, void* sink_dev, void* stream);
 
-/* Launch-shape knobs for measurement sweeps ("waves_per_group" in {1,2,4}, "prefetch_pages" in [1,3],
- * "prefill_col_tiles" in {1,2,4}, "prefill_waves" in {4,8}; the pair (8,4) has no kernel), and one
- * numeric switch: "prefill_wide_v" in {0,1}.  With 0 (default) fs_prefill_attention multiplies fp16
- * weights with V converted to fp16 on its way into LDS: exact for |v| in [2^-14, 65504], |v| above
- * 65504 counts as 65504, smaller magnitudes land on fp16's subnormal grid (absolute error < 2^-24).
- * With 1, V stays bf16 and the weights enter as bf16 hi + lo (two products, ~20% slower), for caches
- * whose values leave fp16's range.
+/* Launch-shape knobs for measurement sweeps: "waves_per_group" in {1,2,4}, "prefetch_pages" in [1,3],
+ * "prefill_col_tiles" in {1,2,4}, "prefill_waves" in {4,8} (the pair (8,4) has no kernel).  They select
+ * among kernels that compute the same thing (sums in another order); nothing numeric is an option.
+ * The table is process-wide and not synchronised: set it before launching from several threads, not
+ * while another thread is inside a call.
  * Unknown key or a value outside the documented range: FS_EINVAL, nothing changes. */
 FS_API fs_status fs_set_option(const char* key, int32_t value);
 FS_API int32_t   fs_get_option(const char* key);   /* -1 for an unknown key */

@@ -68,3 +68,54 @@ def choose_chunk_tokens(ctx_len, owner, rank: int, max_chunk: int, min_chunk: in
         if n >= min_items or nxt < min_chunk:
             return C, n
         C = nxt
+
+
+def build_worklist_units(ctx_len, owner, rank: int, n_units: int, n_q_heads: int, n_kv_heads: int,
+                         page_tokens: int = 16):
+    """The same ragged share (Section 3.1) cut for a launch without stragglers: the rank's pairs, in
+    (request, head) order, are laid end to end as one stream of KVCache pages, and the stream is cut
+    into ``n_units`` runs of equal length (to within one page), one per resident workgroup.  Where a
+    run crosses from one pair into the next it is cut there too, so an item is still tokens
+    [tok_begin, tok_end) of one pair, and a pair that lies inside one run is a single item.
+
+    With P pages in the stream and U = min(n_units, P) units, unit u holds stream pages
+    [floor(u*P/U), floor((u+1)*P/U)).  Items are numbered in stream order, so the items of a unit
+    and the items of a pair are both consecutive.  Returns (items [n_items][8], pairs [n_pairs][4],
+    unit_indptr int64 [U+1], chunk_indptr int64 [n_pairs+1]); item and pair fields as in
+    ``build_worklist`` (chunk = the item's index within its pair, n_chunks = the pair's item count).
+    The cut is this build's device, not the paper's.
+    """
+    H = int(n_kv_heads)
+    if n_q_heads % H:
+        raise ValueError("q heads must be a multiple of KV heads")
+    if n_units < 1:
+        raise ValueError("at least one unit")
+    G = n_q_heads // H
+    T = int(page_tokens)
+    mine = [(r, h, int(ctx_len[r])) for r in range(len(ctx_len)) for h in range(H) if int(owner[r][h]) == rank]
+    n_pages = [-(-L // T) for (_, _, L) in mine]
+    P = sum(n_pages)
+    U = min(int(n_units), P)
+    cuts = [(u * P) // U for u in range(U + 1)] if U else [0]
+    items, pairs, chunk_indptr, unit_indptr = [], [], [0], [0]
+    start = 0                      # stream position of the current pair's first page
+    u = 0                          # unit that holds the next page to place
+    for p, (r, h, L) in enumerate(mine):
+        done = 0                   # pages of this pair already placed
+        c = 0
+        while done < n_pages[p]:
+            while start + done >= cuts[u + 1]:          # the stream position has left unit u
+                u += 1
+                unit_indptr.append(len(items))
+            take = min(n_pages[p] - done, cuts[u + 1] - (start + done))
+            i = len(items)
+            items.append((r, h, done * T, min(L, (done + take) * T), p, c, r * n_q_heads + h * G, i * G))
+            done += take
+            c += 1
+        pairs.append((r, h, L, c))
+        chunk_indptr.append(len(items))
+        start += n_pages[p]
+    while len(unit_indptr) < U + 1:
+        unit_indptr.append(len(items))
+    return (np.array(items, dtype=np.int32).reshape(-1, 8), np.array(pairs, dtype=np.int32).reshape(-1, 4),
+            np.array(unit_indptr, dtype=np.int64), np.array(chunk_indptr, dtype=np.int64))

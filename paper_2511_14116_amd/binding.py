@@ -9,6 +9,7 @@ import numpy as np
 FS_OK, FS_EINVAL, FS_ECAPACITY, FS_EHIP, FS_EUNSUPPORTED = 0, -1, -2, -3, -4
 FS_MODE_TP, FS_MODE_DP = 0, 1
 FS_KV_BF16, FS_KV_FP8_E4M3 = 0, 1
+FS_V_ANY, FS_V_FP16_RANGE = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -30,7 +31,7 @@ class FsKvView(C.Structure):
                 ("k_slot_stride", C.c_int64), ("v_slot_stride", C.c_int64),
                 ("k_scale", C.c_void_p), ("v_scale", C.c_void_p),
                 ("page_indptr", C.c_void_p), ("page_ids", C.c_void_p),
-                ("kv_dtype", C.c_int32), ("sm_scale", C.c_float)]
+                ("kv_dtype", C.c_int32), ("sm_scale", C.c_float), ("page_scales", C.c_void_p), ("v_range", C.c_int32)]
 
 
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in

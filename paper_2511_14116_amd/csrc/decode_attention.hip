@@ -46,8 +46,9 @@ struct DecodeParams {
   const char* __restrict__ v_pool;
   int64_t k_stride;
   int64_t v_stride;
-  const float* __restrict__ k_scale;
-  const float* __restrict__ v_scale;
+  const float* __restrict__ k_scale;      // fp8: by slot, or (page_scales given) the (K, V) pairs in page-table order
+  const float* __restrict__ v_scale;      //      by slot, or page_scales + 1
+  int32_t scale_by_page;                  // 1: scale of page i of the table sits at k_scale[2i] / v_scale[2i]
   const int64_t* __restrict__ page_indptr;
   const int32_t* __restrict__ page_ids;
   const fs_work_item* __restrict__ items;
@@ -544,15 +545,18 @@ struct Fp8Page {
   float ks, vs;
 };
 
-__device__ __forceinline__ void load_page_fp8(Fp8Page& r, const DecodeParams& P, int32_t slot, int lane) {
+// `page` is the page's position in the whole page table (scales kept in page-table order are read as a
+// contiguous run along an item, eight pages to a 64-byte line, instead of one line per slot).
+__device__ __forceinline__ void load_page_fp8(Fp8Page& r, const DecodeParams& P, int32_t slot, int64_t page, int lane) {
   const u32x4* kp = reinterpret_cast<const u32x4*>(P.k_pool + slot * P.k_stride) + lane;
   const u32x4* vp = reinterpret_cast<const u32x4*>(P.v_pool + slot * P.v_stride) + lane;
   r.k[0] = __builtin_nontemporal_load(kp);
   r.k[1] = __builtin_nontemporal_load(kp + 64);
   r.v[0] = __builtin_nontemporal_load(vp);
   r.v[1] = __builtin_nontemporal_load(vp + 64);
-  r.ks = P.k_scale[slot];
-  r.vs = P.v_scale[slot];
+  const int64_t si = P.scale_by_page ? 2 * page : static_cast<int64_t>(slot);
+  r.ks = P.k_scale[si];
+  r.vs = P.v_scale[si];
 }
 
 template <int WAVES, int NBUF, int GMAX>
@@ -572,7 +576,8 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
 
   const int n_tok = it.tok_end - it.tok_begin;
   const int n_pages = (n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
-  const int32_t* __restrict__ ids = P.page_ids + P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+  const int64_t first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+  const int32_t* __restrict__ ids = P.page_ids + first_page;
   const int per = (n_pages + WAVES - 1) / WAVES;
   const int p0 = wave * per;
   const int p1 = min(n_pages, p0 + per);
@@ -655,13 +660,13 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
   Fp8Page buf[NBUF];
 #pragma unroll
   for (int u = 0; u < NBUF - 1; ++u)
-    if (p0 + u < p1) load_page_fp8(buf[u], P, ids[p0 + u], lane);
+    if (p0 + u < p1) load_page_fp8(buf[u], P, ids[p0 + u], first_page + p0 + u, lane);
 
   int i = p0;
   for (; i + 2 * NBUF - 2 < p1; i += NBUF) {
 #pragma unroll
     for (int u = 0; u < NBUF; ++u) {
-      load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[i + u + NBUF - 1], lane);
+      load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[i + u + NBUF - 1], first_page + i + u + NBUF - 1, lane);
       consume(buf[u], fs::kPageTokens, std::true_type{});
     }
   }
@@ -671,7 +676,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
     const int pi = i + u;
     if (pi < p1) {
       const int pn = pi + NBUF - 1;
-      if (pn < p1) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[pn], lane);
+      if (pn < p1) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[pn], first_page + pn, lane);
       consume(buf[u % NBUF], min(fs::kPageTokens, n_tok - pi * fs::kPageTokens), std::false_type{});
     }
   }
@@ -763,8 +768,8 @@ fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, 
   if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev ||
       (partials_needed && (!part_o || !part_lse)))
     return fs::fail(FS_EINVAL, "%s: NULL device pointer", who);
-  if (kv->kv_dtype == FS_KV_FP8_E4M3 && (!kv->k_scale || !kv->v_scale))
-    return fs::fail(FS_EINVAL, "%s: fp8 KV needs k_scale and v_scale", who);
+  if (kv->kv_dtype == FS_KV_FP8_E4M3 && !kv->page_scales && (!kv->k_scale || !kv->v_scale))
+    return fs::fail(FS_EINVAL, "%s: fp8 KV needs page_scales, or k_scale and v_scale", who);
   const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * (kv->kv_dtype == FS_KV_BF16 ? 2 : 1);
   if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
       (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
@@ -778,8 +783,9 @@ fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, 
   P->v_pool = static_cast<const char*>(kv->v_pool);
   P->k_stride = kv->k_slot_stride;
   P->v_stride = kv->v_slot_stride;
-  P->k_scale = kv->k_scale;
-  P->v_scale = kv->v_scale;
+  P->k_scale = kv->page_scales ? kv->page_scales : kv->k_scale;
+  P->v_scale = kv->page_scales ? kv->page_scales + 1 : kv->v_scale;
+  P->scale_by_page = kv->page_scales ? 1 : 0;
   P->page_indptr = kv->page_indptr;
   P->page_ids = kv->page_ids;
   P->items = items_dev;

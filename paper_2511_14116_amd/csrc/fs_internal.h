@@ -21,7 +21,6 @@ struct Options {
   int prefetch_pages;    // KV pages a wavefront keeps in flight ahead of the one it is consuming (1..3)
   int prefill_col_tiles; // 16-row column tiles of query rows per prefill wavefront (1, 2 or 4)
   int prefill_waves;     // wavefronts per prefill workgroup (4 or 8)
-  int prefill_wide_v;    // 0: prefill multiplies fp16 weights with V taken to fp16; 1: bf16 V, weights as bf16 hi + lo
 };
 Options& options();
 

@@ -19,8 +19,8 @@
 //     then the V operands and, per column tile, the online softmax (fp32, log2 domain, causal
 //     mask only on the pairs that straddle a row's position) and
 //         O^T[d][row]  += V^T . P^T      8 x v_mfma_f32_16x16x32_f16 over the 32 tokens: the weights as fp16,
-//                                         V converted bf16 -> fp16 on its way into LDS (or, option
-//                                         "prefill_wide_v", V as bf16 and the weights as bf16 hi + lo).
+//                                         V converted bf16 -> fp16 on its way into LDS (when the caller
+//                                         states FS_V_FP16_RANGE; else V as bf16 and the weights as bf16 hi + lo).
 // The S^T accumulators of the two pages are, lane by lane, the 8 reduction elements the second
 // product wants from P^T (4 tokens of the first page, the same 4 of the second); the copy into
 // LDS pairs the V rows of the two pages the same way, so nothing crosses lanes except the
@@ -468,7 +468,12 @@ extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_vie
       (reinterpret_cast<uintptr_t>(part_o) & 15))
     return fs::fail(FS_EINVAL, "fs_prefill_attention: pools, strides, q and part_o must be 16-byte aligned and strides "
                                "at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
-  if (!std::isfinite(kv->sm_scale)) return fs::fail(FS_EINVAL, "fs_prefill_attention: sm_scale is not finite");
+  // The kernel's lazy running maximum is taken on the raw scores and scaled afterwards, which orders them
+  // correctly only for a positive scale.
+  if (!std::isfinite(kv->sm_scale) || kv->sm_scale <= 0.f)
+    return fs::fail(FS_EINVAL, "fs_prefill_attention: sm_scale %g is not finite and positive", static_cast<double>(kv->sm_scale));
+  if (kv->v_range != FS_V_ANY && kv->v_range != FS_V_FP16_RANGE)
+    return fs::fail(FS_EINVAL, "fs_prefill_attention: unknown v_range %d", kv->v_range);
 
   PrefillParams P;
   P.q = static_cast<const uint16_t*>(kv->q);
@@ -488,7 +493,7 @@ extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_vie
   P.tile_tokens = tile_tokens;
   P.scale_log2 = kv->sm_scale * 1.4426950408889634f;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool wide = fs::options().prefill_wide_v != 0;
+  const bool wide = kv->v_range != FS_V_FP16_RANGE;   // no statement about V: keep it in bf16
 #define FS_PREFILL_CASE(W, C)                                                                     \
   case W * 10 + C:                                                                                \
     return wide ? launch(prefill_bf16_kernel<W, C, true>, W * 64, P, n_items, s)                  \

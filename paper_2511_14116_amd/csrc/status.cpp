@@ -17,7 +17,7 @@ fs_status fail(fs_status st, const char* fmt, ...) {
 }
 
 Options& options() {
-  static Options o{4, 2, 1, 8, 0};
+  static Options o{4, 2, 1, 8};
   return o;
 }
 
@@ -53,12 +53,6 @@ extern "C" fs_status fs_set_option(const char* key, int32_t value) {
     fs::options().prefill_waves = value;
     return FS_OK;
   }
-  if (!strcmp(key, "prefill_wide_v")) {
-    if (value != 0 && value != 1)
-      return fs::fail(FS_EINVAL, "prefill_wide_v must be 0 or 1 (got %d)", value);
-    fs::options().prefill_wide_v = value;
-    return FS_OK;
-  }
   return fs::fail(FS_EINVAL, "fs_set_option: unknown key '%s'", key);
 }
 
@@ -68,6 +62,5 @@ extern "C" int32_t fs_get_option(const char* key) {
   if (!strcmp(key, "prefetch_pages")) return fs::options().prefetch_pages;
   if (!strcmp(key, "prefill_col_tiles")) return fs::options().prefill_col_tiles;
   if (!strcmp(key, "prefill_waves")) return fs::options().prefill_waves;
-  if (!strcmp(key, "prefill_wide_v")) return fs::options().prefill_wide_v;
   return -1;
 }

@@ -15,7 +15,8 @@ class DeviceShare:
     """Q, the paged K/V pool (repacked into kernel order) and the page table on the GPU."""
 
     def __init__(self, shape: B.FsShape, q_bits: np.ndarray, kv: dict, sm_scale: float,
-                 interleave_kv: bool = True, device: str = "cuda:0"):
+                 interleave_kv: bool = True, device: str = "cuda:0", v_range: int = B.FS_V_ANY,
+                 scales_by_page: bool = True):
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceShare needs a GPU; there is no CPU fallback")
         self.shape = shape
@@ -42,18 +43,23 @@ class DeviceShare:
             self._pool = (k, v)
             k_ptr, v_ptr = k.data_ptr(), v.data_ptr()
             k_stride = v_stride = slot_bytes
-        self.k_scale = self.v_scale = None
+        self.page_indptr = torch.from_numpy(kv["page_indptr"]).to(self.device)
+        self.page_ids = torch.from_numpy(kv["page_ids"]).to(self.device)
+        self.k_scale = self.v_scale = self.page_scales = None
         if kv["k_scale"] is not None:
             self.k_scale = torch.from_numpy(kv["k_scale"]).to(self.device)
             self.v_scale = torch.from_numpy(kv["v_scale"]).to(self.device)
-        self.page_indptr = torch.from_numpy(kv["page_indptr"]).to(self.device)
-        self.page_ids = torch.from_numpy(kv["page_ids"]).to(self.device)
+            if scales_by_page:
+                # the same scales in page-table order, (K, V) per page: what an engine keeps next to its page ids
+                idx = self.page_ids.long()
+                self.page_scales = torch.stack([self.k_scale[idx], self.v_scale[idx]], dim=1).contiguous()
         self.view = B.FsKvView(
             q=self.q.data_ptr(), k_pool=k_ptr, v_pool=v_ptr, k_slot_stride=k_stride, v_slot_stride=v_stride,
             k_scale=None if self.k_scale is None else self.k_scale.data_ptr(),
             v_scale=None if self.v_scale is None else self.v_scale.data_ptr(),
             page_indptr=self.page_indptr.data_ptr(), page_ids=self.page_ids.data_ptr(),
-            kv_dtype=self.kv_dtype, sm_scale=float(sm_scale))
+            kv_dtype=self.kv_dtype, sm_scale=float(sm_scale),
+            page_scales=None if self.page_scales is None else self.page_scales.data_ptr(), v_range=int(v_range))
         self.kv_bytes = int(kv["page_indptr"][-1]) * 2 * slot_bytes
         self.n_items = self.n_pairs = 0
 

@@ -51,13 +51,13 @@ def shape_of(w):
     return fs.FsShape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["head_dim"], w["page_tokens"], w["n_ranks"])
 
 
-def run_rank(w, q, rank, chunk, owner, interleave=True, use_sched=True, pairs_subset=None):
+def run_rank(w, q, rank, chunk, owner, interleave=True, use_sched=True, pairs_subset=None, scales_by_page=True):
     """Build rank's list with the library, run the kernels, return everything needed to compare."""
     sh = shape_of(w)
     items, pairs, sched, indptr = fs.fs_build_worklist(sh, w["ctx_len"], owner, rank, chunk)
     kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1) if len(pairs) else np.zeros((0, 2)),
                       w["ctx_len"], kv_dtype=w["kv_dtype"])
-    ds = DeviceShare(sh, q, kv, w["sm_scale"], interleave_kv=interleave)
+    ds = DeviceShare(sh, q, kv, w["sm_scale"], interleave_kv=interleave, scales_by_page=scales_by_page)
     ds.set_worklist(items, pairs, sched, indptr)
     ds.run(use_sched=use_sched)
     torch.cuda.synchronize()
@@ -285,6 +285,10 @@ def test_fp8_small(G, Hkv):
             ds, kv, items, pairs, sched, indptr = run_rank(w, q, k, chunk, owner)
             ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), G * Hkv, G, w["sm_scale"])
             check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"fp8 G={G} rank {k} chunk {chunk}")
+            # the scales gathered by slot instead of read in page-table order: the same numbers, the same bits
+            ds2, *_ = run_rank(w, q, k, chunk, owner, scales_by_page=False)
+            assert ds.page_scales is not None and ds2.page_scales is None
+            assert torch.equal(ds.out, ds2.out) and torch.equal(ds.lse, ds2.lse)
 
 
 @pytest.mark.parametrize("cfg_id", [1, 4])

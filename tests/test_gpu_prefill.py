@@ -38,7 +38,6 @@ def _lib():
     yield
     fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
     fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
-    fs.fs_set_option("prefill_wide_v", 0)
 
 
 def check(out, lse, ref_o, ref_l, what):
@@ -54,7 +53,9 @@ def check(out, lse, ref_o, ref_l, what):
 
 
 def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched=True, interleave=True, chunk=0,
-              kv_edit=None):
+              kv_edit=None, v_range=fs.FS_V_FP16_RANGE):
+    """``v_range``: what the call is told about V.  The generator draws N(0,1) values, which convert to fp16
+    exactly, so the statement FS_V_FP16_RANGE is true unless ``kv_edit`` plants something else."""
     n_done = np.asarray(n_done, dtype=np.int32); n_new = np.asarray(n_new, dtype=np.int32)
     B = len(n_done)
     G = Hq // Hkv
@@ -71,7 +72,7 @@ def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched
         kv_edit(kv)
     q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
     q = make_prefill_q(seed, int(q_indptr[-1]), Hq, 128)
-    ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave)
+    ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave, v_range=v_range)
     ds.set_prefill_worklist(items, sched, chunk_indptr, tile)
     ds.prefill(use_sched=use_sched)
     torch.cuda.synchronize()
@@ -136,17 +137,16 @@ def test_first_token_closed_form_and_one_token_chunks():
 
 @pytest.mark.parametrize("waves,ct", [(8, 1), (4, 2)])
 def test_wide_value_path(waves, ct):
-    """The bf16 hi + lo form of the second product (option prefill_wide_v = 1): same bar, and the first token
+    """The bf16 hi + lo form of the second product (v_range = FS_V_ANY): same bar, and the first token
     of a prompt still returns its own V row exactly."""
     say(f"wide V path waves={waves} ct={ct}")
-    fs.fs_set_option("prefill_wide_v", 1)
     fs.fs_set_option("prefill_waves", waves)
     fs.fs_set_option("prefill_col_tiles", ct)
     try:
         n_done, n_new = [0, 100, 1000, 31, 0], [97, 64, 200, 3, 1]
         owner = np.zeros((5, 2), dtype=np.int32)
         for chunk in (0, 256):
-            ds, kv, q, q_indptr, pairs, oi = run_share(21, n_done, n_new, 16, 2, owner, 0, 1, chunk=chunk)
+            ds, kv, q, q_indptr, pairs, oi = run_share(21, n_done, n_new, 16, 2, owner, 0, 1, chunk=chunk, v_range=fs.FS_V_ANY)
             compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"wide V, waves={waves} ct={ct} chunk={chunk}", oi)
         out = ds.prefill_out.cpu().numpy()
         for p in range(len(pairs)):
@@ -155,48 +155,52 @@ def test_wide_value_path(waves, ct):
                 for g in range(8):
                     assert np.array_equal(out[int(oi[p]) + g].astype(np.float64), V[0])
     finally:
-        fs.fs_set_option("prefill_wide_v", 0)
         fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
         fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
 
 
 def test_value_range_of_the_second_product():
-    """Values of V outside fp16's range: by default they enter the second product as +-65504 (and tiny ones on
-    fp16's subnormal grid, an absolute error below 2^-24); with prefill_wide_v = 1 they count in full."""
+    """V values at and beyond the edges of fp16's range.  With no statement about V (FS_V_ANY) magnitudes of 1e5
+    and 1e-6 count in full; with FS_V_FP16_RANGE the values at the very edges of the stated range (65504 and
+    2^-14) are exact.  Both against the oracle as it stands.  A caller whose statement is false gets finite
+    rows (the header says how such values enter); nothing more is claimed for that case."""
     say("V range")
-    BIG, NEG_BIG, TINY = 0x47C3, 0xC7C3, 0x3580      # bf16 bits of 99840, -99840, 2^-20
 
-    def edit(kv):
-        for p in range(len(kv["page_indptr"]) - 1):
-            slot = int(kv["page_ids"][int(kv["page_indptr"][p])])       # first page of the pair: token 0 always exists
-            kv["v_pool"][slot, 0, 3] = BIG
-            kv["v_pool"][slot, 0, 64] = NEG_BIG
-            kv["v_pool"][slot, 0, 127] = TINY
+    def planter(big, neg_big, tiny):
+        def edit(kv):
+            for p in range(len(kv["page_indptr"]) - 1):
+                slot = int(kv["page_ids"][int(kv["page_indptr"][p])])       # first page of the pair: token 0 always exists
+                kv["v_pool"][slot, 0, 3] = big
+                kv["v_pool"][slot, 0, 64] = neg_big
+                kv["v_pool"][slot, 0, 127] = tiny
+        return edit
 
+    beyond = planter(0x47C3, 0xC7C3, 0x3586)         # bf16 bits of 99840, -99840, 9.98e-7
+    edge = planter(0x477F, 0xC77F, 0x3880)           # 65280 (the largest bf16 below 65504), -65280, 2^-14
     n_done, n_new = [0, 40, 7], [33, 20, 1]
     owner = np.zeros((3, 2), dtype=np.int32)
     Hq, G = 8, 4
-    for wide in (0, 1):
-        fs.fs_set_option("prefill_wide_v", wide)
-        try:
-            ds, kv, q, q_indptr, pairs, oi = run_share(23, n_done, n_new, Hq, 2, owner, 0, 1, chunk=32, kv_edit=edit)
-        finally:
-            fs.fs_set_option("prefill_wide_v", 0)
+    for name, edit, v_range, compare in (("beyond fp16, no statement", beyond, fs.FS_V_ANY, True),
+                                         ("edges of fp16, stated", edge, fs.FS_V_FP16_RANGE, True),
+                                         ("beyond fp16, false statement", beyond, fs.FS_V_FP16_RANGE, False)):
+        ds, kv, q, q_indptr, pairs, oi = run_share(23, n_done, n_new, Hq, 2, owner, 0, 1, chunk=32, kv_edit=edit,
+                                                   v_range=v_range)
         out, lse = ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy()
+        assert np.isfinite(out).all() and np.isfinite(lse).all(), name
+        if not compare:
+            continue
         got_o, got_l, ref_o, ref_l = [], [], [], []
         qf = oracle.bf16_bits_to_f64(q.reshape(-1, Hq, 128))
         for p in range(len(pairs)):
             r, h, L, N = (int(x) for x in pairs[p])
             for tok in range(N):
                 K, V = oracle.gather_pair_kv(kv, p, 0, L + tok + 1)
-                assert abs(V[0, 3]) > 65504 and abs(V[0, 64]) > 65504
-                if not wide:
-                    V = np.clip(V, -65504.0, 65504.0)
+                if v_range == fs.FS_V_ANY:
+                    assert abs(V[0, 3]) > 65504 and abs(V[0, 64]) > 65504 and 0 < abs(V[0, 127]) < 2.0 ** -14
                 o, l = oracle.attend(qf[int(q_indptr[r]) + tok, h * G:(h + 1) * G], K, V, SCALE)
                 row = int(oi[p]) + tok * G
                 got_o.append(out[row:row + G]); got_l.append(lse[row:row + G]); ref_o.append(o); ref_l.append(l)
-        check(np.concatenate(got_o), np.concatenate(got_l), np.concatenate(ref_o), np.concatenate(ref_l),
-              f"V beyond fp16, wide={wide}")
+        check(np.concatenate(got_o), np.concatenate(got_l), np.concatenate(ref_o), np.concatenate(ref_l), f"V {name}")
 
 
 def test_chunked_prefill_feeds_from_the_scheduler():
@@ -263,13 +267,14 @@ def test_repeated_launches_agree_bit_for_bit(waves, ct, wide):
     """Launches on the same inputs must leave the same bits in every launch shape (fixed order of sums, no
     atomics on data): a difference means a race between the workgroup's stages."""
     say(f"prefill: repeated launches, waves={waves} ct={ct} wide={wide}")
-    fs.fs_set_option("prefill_waves", waves); fs.fs_set_option("prefill_col_tiles", ct); fs.fs_set_option("prefill_wide_v", wide)
+    fs.fs_set_option("prefill_waves", waves); fs.fs_set_option("prefill_col_tiles", ct)
     try:
         rng = np.random.default_rng(92)
         Hq, Hkv, R = 64, 8, 2
         n_done, n_new = [0, 300, 2100, 16], [260, 70, 130, 900]
         owner = rng.integers(0, R, size=(4, Hkv)).astype(np.int32)
-        ds, kv, q, q_indptr, pairs, oi = run_share(78, n_done, n_new, Hq, Hkv, owner, 0, R, chunk=512)
+        ds, kv, q, q_indptr, pairs, oi = run_share(78, n_done, n_new, Hq, Hkv, owner, 0, R, chunk=512,
+                                                   v_range=fs.FS_V_ANY if wide else fs.FS_V_FP16_RANGE)
         first = [t.clone() for t in (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse)]
         for rep in range(5):
             for t in (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse):
@@ -280,7 +285,7 @@ def test_repeated_launches_agree_bit_for_bit(waves, ct, wide):
                                   (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse)):
                 assert torch.equal(a, b), f"launch {rep}: {name} differs from the first launch"
     finally:
-        fs.fs_set_option("prefill_waves", 8); fs.fs_set_option("prefill_col_tiles", 1); fs.fs_set_option("prefill_wide_v", 0)
+        fs.fs_set_option("prefill_waves", 8); fs.fs_set_option("prefill_col_tiles", 1)
 
 
 def test_unused_tails_and_spare_slots_are_never_used():

@@ -29,7 +29,7 @@ def _lib():
 
 
 def _defaults():
-    for key, value in (("prefill_wide_v", 0), ("prefill_waves", 8), ("prefill_col_tiles", 1), ("waves_per_group", 4),
+    for key, value in (("prefill_waves", 8), ("prefill_col_tiles", 1), ("waves_per_group", 4),
                        ("prefetch_pages", 2)):
         fs.fs_set_option(key, value)
 
@@ -50,15 +50,12 @@ def test_prefill_on_drawn_shapes(seed):
         wide = int(rng.random() < 0.25)
         what = f"prefill seed {seed} case {case}: Hkv={Hkv} G={G} R={R} n_done={n_done.tolist()} n_new={n_new.tolist()} chunk={chunk} tile={tile} wide={wide}"
         TP.say(what)
-        fs.fs_set_option("prefill_wide_v", wide)
-        try:
-            ds, kv, q, q_indptr, pairs, oi = TP.run_share(9000 + 100 * seed + case, n_done, n_new, Hq, Hkv, owner,
-                                                          int(rng.integers(0, R)), R, tile=tile, chunk=chunk,
-                                                          use_sched=bool(rng.random() < 0.8), interleave=bool(rng.random() < 0.7))
-            if len(pairs):
-                TP.compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, oi)
-        finally:
-            fs.fs_set_option("prefill_wide_v", 0)
+        ds, kv, q, q_indptr, pairs, oi = TP.run_share(9000 + 100 * seed + case, n_done, n_new, Hq, Hkv, owner,
+                                                      int(rng.integers(0, R)), R, tile=tile, chunk=chunk,
+                                                      use_sched=bool(rng.random() < 0.8), interleave=bool(rng.random() < 0.7),
+                                                      v_range=fs.FS_V_ANY if wide else fs.FS_V_FP16_RANGE)
+        if len(pairs):
+            TP.compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, oi)
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -98,7 +95,7 @@ def test_drawn_launch_shapes(seed):
         for case in range(25):
             pw, pc = [(8, 1), (8, 2), (4, 1), (4, 2), (4, 4)][int(rng.integers(0, 5))]
             fs.fs_set_option("prefill_waves", pw); fs.fs_set_option("prefill_col_tiles", pc)
-            fs.fs_set_option("prefill_wide_v", int(rng.random() < 0.25))
+            wide = bool(rng.random() < 0.25)
             fs.fs_set_option("waves_per_group", int(rng.choice([1, 2, 4]))); fs.fs_set_option("prefetch_pages", int(rng.integers(1, 4)))
             Hkv = int(rng.choice([1, 2, 8])); G = int(rng.choice([1, 2, 4, 8, 16])); Hq = Hkv * G
             R = int(rng.integers(1, 4)); B = int(rng.integers(1, 5))
@@ -109,7 +106,8 @@ def test_drawn_launch_shapes(seed):
             what = f"shapes seed {seed} case {case}: prefill {pw}x{pc} Hkv={Hkv} G={G} n_done={n_done.tolist()} n_new={n_new.tolist()} chunk={chunk}"
             TP.say(what)
             ds, kv, q, q_indptr, pairs, oi = TP.run_share(9500 + 100 * seed + case, n_done, n_new, Hq, Hkv, owner,
-                                                          int(rng.integers(0, R)), R, chunk=chunk)
+                                                          int(rng.integers(0, R)), R, chunk=chunk,
+                                                          v_range=fs.FS_V_ANY if wide else fs.FS_V_FP16_RANGE)
             if len(pairs):
                 TP.compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, oi)
             n_req = int(rng.integers(1, 30))

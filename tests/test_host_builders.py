@@ -40,12 +40,12 @@ def test_library_exports_every_declared_symbol():
     lib = C.CDLL(fs.library_path())
     for name in declared:
         assert hasattr(lib, name), name
-    assert fs.fs_abi_version() == 1
+    assert fs.fs_abi_version() == 2
 
 
 def test_struct_sizes_match_the_header():
     assert C.sizeof(fs.FsShape) == 24 and fs.ITEM_DTYPE.itemsize == 32 and fs.PAIR_DTYPE.itemsize == 16
-    assert C.sizeof(fs.FsKvView) == 80
+    assert C.sizeof(fs.FsKvView) == 96
 
 
 @pytest.mark.parametrize("cfg_id", sorted(CONFIGS))
@@ -171,6 +171,16 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     with pytest.raises(fs.FsError) as e:
         fs.fs_prefill_attention(sh, kv, None, None, 1, 10 ** 6, None, None)
     assert e.value.status == fs.FS_EINVAL
+    # a softmax scale that is not positive, or an unknown statement about V, is refused before any launch
+    import torch
+    dummy = torch.zeros(64, dtype=torch.uint8).data_ptr()      # any non-NULL, 16-byte aligned address: nothing is launched
+    for field, value in (("sm_scale", 0.0), ("sm_scale", -0.1), ("v_range", 7)):
+        bad = fs.FsKvView(q=dummy, k_pool=dummy, v_pool=dummy, k_slot_stride=4096, v_slot_stride=4096, page_indptr=dummy,
+                          page_ids=dummy, kv_dtype=fs.FS_KV_BF16, sm_scale=0.1)
+        setattr(bad, field, value)
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_prefill_attention(sh, bad, dummy, None, 1, 1, dummy, dummy)
+        assert e.value.status == fs.FS_EINVAL and field in str(e.value)
     with pytest.raises(fs.FsError) as e:
         fs.fs_merge_lse(None, None, None, 4, 2, 64, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED

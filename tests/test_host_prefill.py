@@ -45,12 +45,9 @@ def test_tile_tokens_and_errors():
     assert fs.fs_prefill_tile_tokens(0) == -1 and fs.fs_prefill_tile_tokens(17) == -1
     ct = fs.fs_get_option("prefill_col_tiles")
     assert (fs.fs_get_option("prefill_waves"), ct) == (8, 1)
-    assert fs.fs_get_option("prefill_wide_v") == 0
+    assert fs.fs_get_option("prefill_wide_v") == -1          # nothing numeric is a process-wide option
     with pytest.raises(fs.FsError):
-        fs.fs_set_option("prefill_wide_v", 2)
-    fs.fs_set_option("prefill_wide_v", 1)
-    assert fs.fs_get_option("prefill_wide_v") == 1
-    fs.fs_set_option("prefill_wide_v", 0)
+        fs.fs_set_option("prefill_wide_v", 1)
     for G, per_tile in ((1, 16), (2, 8), (3, 4), (4, 4), (5, 2), (8, 2), (16, 1)):
         assert fs.fs_prefill_tile_tokens(G) == fs.fs_get_option("prefill_waves") * ct * per_tile
     shape = fs.FsShape(1, 4, 2, 128, 16, 2)

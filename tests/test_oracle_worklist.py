@@ -113,3 +113,82 @@ def test_chunk_choice_properties(seed):
                 assert len(bigger) < min_items
             if n < min_items:
                 assert C == 256
+
+
+# ---- the list cut into equal runs of pages (one per resident workgroup) ---------------------------------
+from oracle import build_worklist_units
+
+
+def test_units_by_hand():
+    # Same share as test_tiny_list_by_hand: rank 0 holds (r0,h0) L=40 (3 pages), (r1,h0) and (r1,h1) L=20 (2 pages
+    # each): a stream of 7 pages.  Three units: cuts at floor(u*7/3) = 0, 2, 4, 7.
+    #   unit 0 = pages 0-1          -> pair 0 tokens [0, 32)
+    #   unit 1 = pages 2-3          -> pair 0 [32, 40) and pair 1 [0, 16)
+    #   unit 2 = pages 4-6          -> pair 1 [16, 20) and pair 2 [0, 20)
+    ctx = np.array([40, 20], dtype=np.int32)
+    owner, _, _ = build_placement(ctx, [0, 1], 2, 2)
+    items, pairs, unit_indptr, chunk_indptr = build_worklist_units(ctx, owner, 0, 3, 4, 2)
+    assert items.tolist() == [
+        [0, 0, 0, 32, 0, 0, 0, 0], [0, 0, 32, 40, 0, 1, 0, 2],
+        [1, 0, 0, 16, 1, 0, 4, 4], [1, 0, 16, 20, 1, 1, 4, 6],
+        [1, 1, 0, 20, 2, 0, 6, 8]]
+    assert pairs.tolist() == [[0, 0, 40, 2], [1, 0, 20, 2], [1, 1, 20, 1]]
+    assert unit_indptr.tolist() == [0, 1, 3, 5] and chunk_indptr.tolist() == [0, 2, 4, 5]
+    # four units: cuts 0, 1, 3, 5, 7 -> [0,16) | [16,40) | pair 1 whole | pair 2 whole
+    items, pairs, unit_indptr, chunk_indptr = build_worklist_units(ctx, owner, 0, 4, 4, 2)
+    assert [it[2:6] for it in items.tolist()] == [[0, 16, 0, 0], [16, 40, 0, 1], [0, 20, 1, 0], [0, 20, 2, 0]]
+    assert unit_indptr.tolist() == [0, 1, 2, 3, 4] and chunk_indptr.tolist() == [0, 2, 3, 4]
+    # one unit: every pair is one item; more units than pages: one page per unit
+    items, pairs, unit_indptr, _ = build_worklist_units(ctx, owner, 0, 1, 4, 2)
+    assert [it[2:4] for it in items.tolist()] == [[0, 40], [0, 20], [0, 20]] and unit_indptr.tolist() == [0, 3]
+    items, pairs, unit_indptr, _ = build_worklist_units(ctx, owner, 0, 50, 4, 2)
+    assert len(items) == 7 and unit_indptr.tolist() == list(range(8)) and pairs[:, 3].tolist() == [3, 2, 2]
+    # a rank with nothing
+    items, pairs, unit_indptr, chunk_indptr = build_worklist_units(np.array([5], np.int32), np.zeros((1, 2), np.int32), 1, 4, 2, 2)
+    assert items.shape == (0, 8) and pairs.shape == (0, 4) and unit_indptr.tolist() == [0] and chunk_indptr.tolist() == [0]
+
+
+@pytest.mark.parametrize("n_units", [1, 2, 7, 64, 512, 100000])
+def test_units_against_a_page_by_page_partition(n_units):
+    """Second style: write out every page of the stream, give page k of P the unit u with
+    floor(u*P/U) <= k < floor((u+1)*P/U) (the textbook equal partition of a sequence), and collect runs of
+    pages with the same (unit, pair).  Then the invariants the kernels rely on."""
+    R, H, Hq = 5, 8, 32
+    G = Hq // H
+    for seed in range(6):
+        ctx, owner, load = _case(40 + seed, 30 + 9 * seed, R, H, 0.3, lo=1, hi=3000 if seed % 2 else 200)
+        seen = set()
+        for k in range(R):
+            items, pairs, unit_indptr, chunk_indptr = build_worklist_units(ctx, owner, k, n_units, Hq, H)
+            stream = [(p, j) for p, (r, h, L, _n) in enumerate(pairs) for j in range(-(-int(L) // 16))]
+            P = len(stream)
+            U = min(n_units, P)
+            assert len(unit_indptr) == U + 1 and unit_indptr[0] == 0 and unit_indptr[-1] == len(items)
+            cuts = np.array([(u * P) // U for u in range(U + 1)]) if U else np.array([0])
+            unit_of_page = np.searchsorted(cuts, np.arange(P), side="right") - 1
+            want = []          # (unit, pair, first page, last page + 1)
+            for kpage, (p, j) in enumerate(stream):
+                u = int(unit_of_page[kpage])
+                if want and want[-1][0] == u and want[-1][1] == p:
+                    want[-1][3] = j + 1
+                else:
+                    want.append([u, p, j, j + 1])
+            assert len(want) == len(items)
+            unit_of_item = np.searchsorted(unit_indptr, np.arange(len(items)), side="right") - 1
+            for i, (u, p, a, b) in enumerate(want):
+                r, h, L, _n = (int(x) for x in pairs[p])
+                assert items[i].tolist()[:5] == [r, h, 16 * a, min(L, 16 * b), p] and unit_of_item[i] == u
+            # what the kernels rely on
+            assert int((items[:, 3] - items[:, 2]).sum()) == load[k]
+            sizes = np.diff(cuts)
+            assert U == 0 or (sizes.max() - sizes.min() <= 1 and sizes.min() >= 1)     # equal runs, none empty
+            assert chunk_indptr[0] == 0 and chunk_indptr[-1] == len(items)
+            for p, (r, h, L, n) in enumerate(pairs):
+                its = items[chunk_indptr[p]:chunk_indptr[p + 1]]
+                assert len(its) == n >= 1 and its[0, 2] == 0 and its[-1, 3] == L and (its[1:, 2] == its[:-1, 3]).all()
+                assert (its[:-1, 3] % 16 == 0).all() and its[:, 5].tolist() == list(range(n))
+                assert (its[:, 6] == r * Hq + h * G).all() and owner[r, h] == k
+                seen.add((int(r), int(h)))
+            assert items[:, 7].tolist() == [i * G for i in range(len(items))]
+            assert len(items) <= len(pairs) + max(U - 1, 0)       # a cut adds at most one item
+        assert len(seen) == len(ctx) * H
