@@ -63,6 +63,9 @@ def main() -> int:
     ap.add_argument("--persistent", action="store_true",
                     help="bf16: the persistent form of the sweep (fs_decode_attention_persistent: workgroups claim items, "
                          "partial rows leave in bursts) even for short lists; by default it is used from 1024 items on")
+    ap.add_argument("--units", type=int, default=None, metavar="N",
+                    help="bf16: cut the share into N equal runs of pages (0 = two per compute unit) and sweep them with one "
+                         "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units)")
     ap.add_argument("--two-calls", action="store_true",
                     help="the step calls fs_decode_attention[_persistent] and fs_merge_lse instead of fs_decode_attention_fused")
     ap.add_argument("--placement", choices=["requests", "heads"], default="requests",
@@ -134,7 +137,26 @@ def main() -> int:
         return w["chunk_tokens"]
 
     chunk = chunk_for(args.rank)
-    items, pairs, sched, chunk_indptr = fs.fs_build_worklist(shape, ctx, owner, args.rank, chunk)
+    units = args.units is not None
+    if units and w["kv_dtype"] != "bf16":
+        print("bench.py: --units is built for bf16 K/V", file=sys.stderr)
+        return 2
+
+    def units_for(rank):
+        """Two resident workgroups per compute unit, but at least 16 pages (256 tokens) to a run."""
+        if args.units:
+            return args.units
+        pages = sum(-(-int(ctx[r]) // w["page_tokens"]) for r in range(B) for h in range(Hkv) if owner[r, h] == rank)
+        return max(1, min(2 * n_cu, pages // 16))
+
+    if units:
+        n_units_req = units_for(args.rank)
+        items, pairs, unit_indptr, chunk_indptr = fs.fs_build_worklist_units(shape, ctx, owner, args.rank, n_units_req)
+        n_units = len(unit_indptr) - 1
+        sched = None
+        chunk = 0
+    else:
+        items, pairs, sched, chunk_indptr = fs.fs_build_worklist(shape, ctx, owner, args.rank, chunk)
     n_items, n_pairs = len(items), len(pairs)
     if n_items == 0:
         print("bench.py: this rank's share is empty", file=sys.stderr)
@@ -152,7 +174,7 @@ def main() -> int:
     kv_bytes = tok_heads * 2 * w["head_dim"] * elt          # K and V rows actually attended
     scale_bytes = n_pages * 8 if w["kv_dtype"] == "fp8" else 0
     q_bytes = n_pairs * G * w["head_dim"] * 2
-    table_bytes = n_pages * 4 + n_items * 32 + n_items * 4
+    table_bytes = n_pages * 4 + n_items * 32 + ((n_units + 1) * 8 if units else n_items * 4)
     row_bytes = w["head_dim"] * 4 + 4                       # one fp32 output row and its lse
     counts = np.diff(chunk_indptr)
     if args.two_calls:                                      # every item writes partial rows, the merge reads them all
@@ -177,7 +199,7 @@ def main() -> int:
         return (x + 255) & ~255
     off_items = 0
     off_sched = up(off_items + n_items * 32)
-    off_indptr = up(off_sched + n_items * 4)
+    off_indptr = up(off_sched + ((n_units + 1) * 8 if units else n_items * 4))      # units: unit_indptr sits where sched would
     blob_bytes = up(off_indptr + (n_pairs + 1) * 8)
     N_SLOTS = 4
     dev_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, device=dev) for _ in range(N_SLOTS)]
@@ -188,6 +210,7 @@ def main() -> int:
         a = hb.numpy()
         host_views.append((a[off_items:off_items + n_items * 32].view(fs.ITEM_DTYPE),
                            np.empty(n_pairs, dtype=fs.PAIR_DTYPE),
+                           a[off_sched:off_sched + (n_units + 1) * 8].view(np.int64) if units else
                            a[off_sched:off_sched + n_items * 4].view(np.int32),
                            a[off_indptr:off_indptr + (n_pairs + 1) * 8].view(np.int64)))
     part_o = torch.empty((n_items * G, w["head_dim"]), dtype=torch.float32, device=dev)
@@ -207,11 +230,14 @@ def main() -> int:
     else:
         dpl_buf = None
         call_place = fs.bind_build_placement(shape, ctx_c, mode_c, owner_buf, dp_buf, load_buf)
-    call_list = [fs.bind_build_worklist(shape, ctx_c, owner_buf, args.rank, chunk, *hv) for hv in host_views]
+    if units:
+        call_list = [fs.bind_build_worklist_units(shape, ctx_c, owner_buf, args.rank, n_units_req, *hv) for hv in host_views]
+    else:
+        call_list = [fs.bind_build_worklist(shape, ctx_c, owner_buf, args.rank, chunk, *hv) for hv in host_views]
 
     # The persistent form pays off once every workgroup walks several items (it saves the scattered stores
     # and the relaunches); with one item or fewer per workgroup slot it is the same work plus a counter.
-    persistent = w["kv_dtype"] == "bf16" and not args.classic and (args.persistent or n_items >= 1024)
+    persistent = w["kv_dtype"] == "bf16" and not args.classic and not units and (args.persistent or n_items >= 1024)
     if args.persistent and n_items < 1024 and not args.two_calls:
         print("bench.py: --persistent below 1024 items needs --two-calls (the fused call picks the sweep by list length)",
               file=sys.stderr)
@@ -223,6 +249,13 @@ def main() -> int:
         dec, mrg, fused = [], [], []
         for db in (host_blobs if host_list else dev_blobs):
             base = db.data_ptr()        # a pinned host blob is mapped into the GPU's address space at the same address
+            if units:
+                dec.append(fs.bind_decode_attention_units(shape, ds.view, base + off_items, n_items, base + off_sched, n_units,
+                                                          None, 0, part_o, part_lse, None, None, stream_ptr))
+                mrg.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"], out, lse, stream_ptr))
+                fused.append(fs.bind_decode_attention_units(shape, ds.view, base + off_items, n_items, base + off_sched, n_units,
+                                                            base + off_indptr, n_pairs, part_o, part_lse, out, lse, stream_ptr))
+                continue
             if persistent:
                 dec.append(fs.bind_decode_attention_persistent(shape, ds.view, base + off_items, base + off_sched,
                                                                n_items, claim, part_o, part_lse, stream_ptr))
@@ -420,14 +453,21 @@ def main() -> int:
     if args.all_ranks:
         per_rank = []
         for k in range(R):
-            it_k, pr_k, sc_k, ip_k = fs.fs_build_worklist(shape, ctx, owner, k, chunk_for(k))
+            if units:
+                it_k, pr_k, ui_k, ip_k = fs.fs_build_worklist_units(shape, ctx, owner, k, units_for(k))
+            else:
+                it_k, pr_k, sc_k, ip_k = fs.fs_build_worklist(shape, ctx, owner, k, chunk_for(k))
             if len(it_k) == 0:
                 per_rank.append({"rank": k, "kv_token_heads": 0, "n_items": 0, "kernels_us": 0.0, "gbs": 0.0})
                 continue
             kv_k = make_kv_pool(w["seed"], np.stack([pr_k["req"], pr_k["kv_head"]], axis=1), ctx, kv_dtype=w["kv_dtype"])
             ds_k = DeviceShare(shape, q_bits, kv_k, w["sm_scale"], interleave_kv=not args.separate_kv)
-            ds_k.set_worklist(it_k, pr_k, sc_k, ip_k)
-            run_k = (lambda: ds_k.run(persistent=persistent)) if args.two_calls else (lambda: ds_k.run_fused(persistent=persistent))
+            if units:
+                ds_k.set_worklist_units(it_k, pr_k, ui_k, ip_k)
+                run_k = ds_k.run_units
+            else:
+                ds_k.set_worklist(it_k, pr_k, sc_k, ip_k)
+                run_k = (lambda: ds_k.run(persistent=persistent)) if args.two_calls else (lambda: ds_k.run_fused(persistent=persistent))
             for _ in range(5):
                 run_k()
             r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -482,11 +522,11 @@ def main() -> int:
 
     dec_avg_ms = float(dec_ms.mean())
     achieved = decode_bytes / (dec_avg_ms * 1e-3) / 1e9
-    kernel_name = "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else ("decode_bf16_persistent_kernel" if persistent
+    kernel_name = "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else ("decode_bf16_persistent_kernel" if persistent or units
                                                                         else "decode_bf16_kernel")
     default_shape = (args.waves in (None, 4) and args.prefetch in (None, 2) and not args.separate_kv
                      and not args.scales_by_slot and not (args.config == 3 and args.force_tail))
-    key = (args.config, args.rank, w["seed"], chunk, args.placement, kernel_name) if default_shape else None
+    key = (args.config, args.rank, w["seed"], f"{n_units} units" if units else chunk, args.placement, kernel_name) if default_shape else None
     result = {
         "metric": "achieved HBM GB/s (% of peak) and KV-token-heads/s, rank-0 share, 1 MI355X",
         "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 2),
@@ -497,12 +537,13 @@ def main() -> int:
         "dtype": "bf16" if w["kv_dtype"] == "bf16" else "fp8_e4m3",
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {w['name']}: B={B}, Hq={Hq}, Hkv={Hkv}, d=128, page=16, "
-                               f"R={R}, rank {args.rank}, chunk={chunk}, seed={w['seed']}"
+                               f"R={R}, rank {args.rank}, " + (f"{n_units} equal runs of pages" if units else f"chunk={chunk}") + f", seed={w['seed']}"
                                + (", head-level hybrid placement" if args.placement == "heads" else ""),
                    "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
-                   "sweep": "persistent" if persistent else "one workgroup per item",
-                   "step_calls": "fs_decode_attention[_persistent] + fs_merge_lse" if args.two_calls else "fs_decode_attention_fused",
+                   "sweep": "one resident workgroup per run of pages" if units else ("persistent" if persistent else "one workgroup per item"),
+                   "step_calls": ("fs_decode_attention_units" + (" (sweep alone) + fs_merge_lse" if args.two_calls else "")) if units else
+                                 ("fs_decode_attention[_persistent] + fs_merge_lse" if args.two_calls else "fs_decode_attention_fused"),
                    "merge_launched": bool(args.two_calls or n_items > n_pairs),
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),

@@ -184,6 +184,35 @@ FS_API fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len
                             int64_t* n_items, int64_t* n_pairs);
 
 /* ---------------------------------------------------------------------------
+ * fs_build_worklist_units - the same ragged share (Section 3.1) cut for a launch without
+ * stragglers.  The rank's pairs, in ascending (r, h), are laid end to end as one stream of
+ * KVCache pages and the stream is cut into n_units runs of equal length (to within one page), one
+ * per resident workgroup of fs_decode_attention_units: with P pages in all and U = min(n_units, P)
+ * units, unit u holds stream pages [floor(u*P/U), floor((u+1)*P/U)).  Where a run crosses from
+ * one pair into the next it is cut there too, so an item is still tokens [tok_begin, tok_end) of
+ * one pair, a pair inside one run is a single item, and the list has at most n_pairs + U - 1 items.
+ * Items are numbered in stream order: the items of a unit are consecutive (unit_indptr[u] is the
+ * first of unit u) and so are the items of a pair (chunk_indptr[p]); fs_work_item.chunk is the
+ * item's index within its pair and fs_pair.n_chunks the pair's item count.
+ *
+ *  items        HOST out [items_cap]
+ *  pairs        HOST out [pairs_cap]
+ *  unit_indptr  HOST out [units_cap+1]
+ *  chunk_indptr HOST out [pairs_cap+1]
+ *               All four NULL (capacities 0): count only.
+ *  n_items, n_pairs, n_units_out  HOST out  always written when the arguments are valid (n_units_out = U)
+ *
+ * FS_ECAPACITY: an array is too small; nothing but the counts is valid.  FS_EINVAL: bad shape,
+ * rank outside [0, R), n_units < 1, owner outside [0, R), ctx_len < 1, counts beyond int32 rows.
+ */
+FS_API fs_status fs_build_worklist_units(const fs_shape* shape, const int32_t* ctx_len, const int32_t* owner,
+                                         int32_t rank, int32_t n_units,
+                                         fs_work_item* items, int64_t items_cap,
+                                         fs_pair* pairs, int64_t pairs_cap,
+                                         int64_t* unit_indptr, int64_t units_cap, int64_t* chunk_indptr,
+                                         int64_t* n_items, int64_t* n_pairs, int64_t* n_units_out);
+
+/* ---------------------------------------------------------------------------
  * fs_choose_chunk_tokens - a split-K chunk size for one rank's share.  The ragged share of
  * Section 3.1 can be a handful of very long contexts (the skew the paper's load-aware routing is
  * there for); a list with fewer items than the GPU has compute units leaves most of it idle, so
@@ -438,6 +467,32 @@ FS_API fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_kv_vi
                                            int64_t n_items, const int64_t* chunk_indptr_dev, int64_t n_pairs,
                                            float* part_o, float* part_lse, int32_t* claim_dev,
                                            float* out, float* lse, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * fs_decode_attention_units - decode attention (Section 2.1.1) and split-K merge of a list that
+ * fs_build_worklist_units has cut into equal runs, bf16 K/V: one resident workgroup per unit
+ * walks its unit's items in order (no counter, nothing handed out at run time: every workgroup
+ * streams the same number of pages), a pair that is one item gets its final rows from the sweep,
+ * the others are merged as by fs_merge_lse.  out/lse hold, to rounding (another order of sums
+ * wherever the cuts differ), what fs_decode_attention + fs_merge_lse give for the same pairs.
+ * Choose n_units as the number of workgroups the GPU holds at once (two per compute unit).
+ *
+ *  items_dev         DEVICE in   [n_items]     as built by fs_build_worklist_units
+ *  unit_indptr_dev   DEVICE in   [n_units+1]
+ *  chunk_indptr_dev  DEVICE in   [n_pairs+1], or NULL: the sweep alone - every item's rows go to
+ *                    part_o/part_lse as in fs_decode_attention, nothing is merged, n_pairs, out
+ *                    and lse are ignored (fs_merge_lse can follow)
+ *  part_o, part_lse  DEVICE scratch [n_items*G][head_dim], [n_items*G]; may be NULL when n_items == n_pairs
+ *  out, lse          DEVICE out  [n_pairs*G][head_dim], [n_pairs*G] fp32
+ *
+ * n_items == 0 is a no-op.  Errors as for fs_decode_attention_fused; FS_EUNSUPPORTED for fp8 K/V.
+ * List contents are trusted (device memory): no unit may be empty.
+ */
+FS_API fs_status fs_decode_attention_units(const fs_shape* shape, const fs_kv_view* kv,
+                                           const fs_work_item* items_dev, int64_t n_items,
+                                           const int64_t* unit_indptr_dev, int64_t n_units,
+                                           const int64_t* chunk_indptr_dev, int64_t n_pairs,
+                                           float* part_o, float* part_lse, float* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------
  * fs_decode_attention_fused_static - fs_decode_attention_fused for callers that cannot allocate

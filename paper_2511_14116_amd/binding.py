@@ -72,6 +72,14 @@ def load_library(path: str | None = None):
                                       C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_void_p, i64p, i64p]
     lib.fs_build_worklist.restype = C.c_int
+    lib.fs_build_worklist_units.argtypes = [C.POINTER(FsShape), i32p, i32p, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                            C.c_void_p, C.c_int64, C.c_void_p, i64p, i64p, i64p]
+    lib.fs_build_worklist_units.restype = C.c_int
+    lib.fs_decode_attention_units.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_int64,
+                                              C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fs_decode_attention_units.restype = C.c_int
     lib.fs_choose_chunk_tokens.argtypes = [C.POINTER(FsShape), i32p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                            i32p, i64p]
     lib.fs_choose_chunk_tokens.restype = C.c_int
@@ -228,6 +236,26 @@ def fs_build_worklist(shape: FsShape, ctx_len, owner, rank: int, chunk_tokens: i
     _check(st)
     n, m = n_items.value, n_pairs.value
     return items[:n], pairs[:m], sched[:n], indptr[:m + 1]
+
+
+def fs_build_worklist_units(shape: FsShape, ctx_len, owner, rank: int, n_units: int):
+    """-> (items [n] ITEM_DTYPE, pairs [m] PAIR_DTYPE, unit_indptr [U+1] int64, chunk_indptr [m+1] int64):
+    the rank's share cut into U = min(n_units, pages) equal runs of pages."""
+    lib = load_library()
+    ctx = _host(ctx_len, np.int32)
+    own = _host(owner, np.int32)
+    i32p = C.POINTER(C.c_int32)
+    n_items, n_pairs, n_u = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    args = (C.byref(shape), ctx.ctypes.data_as(i32p), own.ctypes.data_as(i32p), rank, n_units)
+    counts = (C.byref(n_items), C.byref(n_pairs), C.byref(n_u))
+    _check(lib.fs_build_worklist_units(*args, None, 0, None, 0, None, 0, None, *counts))
+    items = np.empty(n_items.value, dtype=ITEM_DTYPE)
+    pairs = np.empty(n_pairs.value, dtype=PAIR_DTYPE)
+    unit_indptr = np.empty(n_u.value + 1, dtype=np.int64)
+    chunk_indptr = np.empty(n_pairs.value + 1, dtype=np.int64)
+    _check(lib.fs_build_worklist_units(*args, items.ctypes.data, len(items), pairs.ctypes.data, len(pairs),
+                                       unit_indptr.ctypes.data, n_u.value, chunk_indptr.ctypes.data, *counts))
+    return items, pairs, unit_indptr, chunk_indptr
 
 
 def fs_choose_chunk_tokens(shape: FsShape, ctx_len, owner, rank: int, max_chunk: int, min_chunk: int,
@@ -431,6 +459,14 @@ def fs_decode_attention_fused_static(shape: FsShape, kv: FsKvView, items_dev, sc
     _check(st)
 
 
+def fs_decode_attention_units(shape: FsShape, kv: FsKvView, items_dev, n_items: int, unit_indptr_dev, n_units: int,
+                              chunk_indptr_dev, n_pairs: int, part_o, part_lse, out, lse, stream=None) -> None:
+    st = load_library().fs_decode_attention_units(C.byref(shape), C.byref(kv), _ptr(items_dev), n_items,
+                                                  _ptr(unit_indptr_dev), n_units, _ptr(chunk_indptr_dev), n_pairs,
+                                                  _ptr(part_o), _ptr(part_lse), _ptr(out), _ptr(lse), _ptr(stream))
+    _check(st)
+
+
 def fs_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,
                  out, lse, stream=None) -> None:
     st = load_library().fs_merge_lse(_ptr(part_o), _ptr(part_lse), _ptr(chunk_indptr_dev), n_pairs, group,
@@ -509,6 +545,22 @@ def bind_build_worklist(shape: FsShape, ctx_len: np.ndarray, owner: np.ndarray, 
                      n_items, n_pairs)
 
 
+def bind_build_worklist_units(shape: FsShape, ctx_len: np.ndarray, owner: np.ndarray, rank: int, n_units: int,
+                              items: np.ndarray, pairs: np.ndarray, unit_indptr: np.ndarray,
+                              chunk_indptr: np.ndarray) -> BoundCall:
+    """fs_build_worklist_units into caller-held arrays (e.g. views of pinned memory).  After a call the counts
+    are in .n_items.value, .n_pairs.value and .n_tiles.value (the number of units)."""
+    lib = load_library()
+    i32p = C.POINTER(C.c_int32)
+    n_items, n_pairs, n_u = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    args = (C.byref(shape), ctx_len.ctypes.data_as(i32p), owner.ctypes.data_as(i32p), C.c_int32(rank), C.c_int32(n_units),
+            C.c_void_p(items.ctypes.data), C.c_int64(len(items)), C.c_void_p(pairs.ctypes.data), C.c_int64(len(pairs)),
+            C.c_void_p(unit_indptr.ctypes.data), C.c_int64(len(unit_indptr) - 1), C.c_void_p(chunk_indptr.ctypes.data),
+            C.byref(n_items), C.byref(n_pairs), C.byref(n_u))
+    return BoundCall(lib.fs_build_worklist_units, args, (shape, ctx_len, owner, items, pairs, unit_indptr, chunk_indptr),
+                     n_items, n_pairs, n_u)
+
+
 def bind_build_prefill_worklist(shape: FsShape, n_done: np.ndarray, n_new: np.ndarray, owner: np.ndarray, rank: int,
                                 tile_tokens: int, kv_chunk_tokens: int, items: np.ndarray, pairs: np.ndarray,
                                 sched: np.ndarray, chunk_indptr: np.ndarray, out_indptr: np.ndarray) -> BoundCall:
@@ -560,6 +612,15 @@ def bind_decode_attention_fused(shape: FsShape, kv: FsKvView, items_dev, sched_d
             C.c_int64(n_pairs), _vp(part_o), _vp(part_lse), _vp(claim_dev), _vp(out), _vp(lse), _vp(stream))
     return BoundCall(lib.fs_decode_attention_fused, args,
                      (shape, kv, items_dev, sched_dev, chunk_indptr_dev, part_o, part_lse, claim_dev, out, lse))
+
+
+def bind_decode_attention_units(shape: FsShape, kv: FsKvView, items_dev, n_items: int, unit_indptr_dev, n_units: int,
+                                chunk_indptr_dev, n_pairs: int, part_o, part_lse, out, lse, stream=None) -> BoundCall:
+    lib = load_library()
+    args = (C.byref(shape), C.byref(kv), _vp(items_dev), C.c_int64(n_items), _vp(unit_indptr_dev), C.c_int64(n_units),
+            _vp(chunk_indptr_dev), C.c_int64(n_pairs), _vp(part_o), _vp(part_lse), _vp(out), _vp(lse), _vp(stream))
+    return BoundCall(lib.fs_decode_attention_units, args,
+                     (shape, kv, items_dev, unit_indptr_dev, chunk_indptr_dev, part_o, part_lse, out, lse))
 
 
 def bind_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,

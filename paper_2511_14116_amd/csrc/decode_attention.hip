@@ -376,9 +376,13 @@ __device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int 
   return d;
 }
 
-template <int WAVES, int NBUF>
+// UNITS = true is the form without a counter: workgroup u walks the items [unit_indptr[u], unit_indptr[u+1]) of a
+// list that the host has cut into equal runs of pages (fs_build_worklist_units), so every workgroup streams
+// the same number of bytes and nothing is handed out at run time; `claim` then carries nothing.
+template <int WAVES, int NBUF, bool UNITS>
 __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(const DecodeParams P, int n_items,
-                                                                            int* __restrict__ claim, int n_first) {
+                                                                            int* __restrict__ claim, int n_first,
+                                                                            const int64_t* __restrict__ unit_indptr) {
   __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
   __shared__ float sm_m[WAVES * 16];
   __shared__ float sm_l[WAVES * 16];
@@ -393,7 +397,12 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
   const int G = P.group;
   const int n_groups = gridDim.x;
 
-  ItemDesc cur = load_desc<WAVES>(P, blockIdx.x, n_items, wave, lane, G);   // blockIdx.x < n_items by the launch
+  int unit_end = 0, cur_k = static_cast<int>(blockIdx.x);
+  if constexpr (UNITS) {
+    cur_k = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x]));
+    unit_end = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x + 1]));   // > cur_k: no unit is empty
+  }
+  ItemDesc cur = load_desc<WAVES>(P, cur_k, n_items, wave, lane, G);   // a valid item by the launch
 
   PageRegs buf[NBUF];
   auto prologue = [&](const ItemDesc& d) __attribute__((always_inline)) {
@@ -450,13 +459,21 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
     // The next item is claimed only now.  Claiming it earlier would hide the counter's round trip, but a
     // workgroup would then sit on an item another could have started: claiming at the start of the current
     // item cost 11 us of the launch on the 70B-shaped batch, two items ahead 20 us, four pages early 4 us.
-    if (threadIdx.x == 0) s_next = keep_claiming ? atomicAdd(claim, 1) + n_groups : n_items;
+    if constexpr (!UNITS) {
+      if (threadIdx.x == 0) s_next = keep_claiming ? atomicAdd(claim, 1) + n_groups : n_items;
+    }
     lds_barrier();
     // every page of the current item is consumed: fetch the next item's descriptor and first pages now,
     // so that they travel while the rows are merged
-    const int next_k = __builtin_amdgcn_readfirstlane(s_next);
+    int next_k;
+    if constexpr (UNITS) {
+      ++cur_k;
+      next_k = cur_k < unit_end ? cur_k : n_items;
+    } else {
+      next_k = __builtin_amdgcn_readfirstlane(s_next);
+    }
     ItemDesc nxt = load_desc<WAVES>(P, next_k, n_items, wave, lane, G);
-    if (second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
+    if (!UNITS && second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
     prologue(nxt);
     for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
       const int q = idx >> 5, d4 = idx & 31;
@@ -501,9 +518,11 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
   }
   // The last workgroup to leave puts both counters back to zero for the next launch (every other
   // workgroup has made its last claim by then).
-  if (threadIdx.x == 0 && atomicAdd(claim + 1, 1) == static_cast<int>(gridDim.x) - 1) {
-    __atomic_store_n(claim, 0, __ATOMIC_RELAXED);
-    __atomic_store_n(claim + 1, 0, __ATOMIC_RELAXED);
+  if constexpr (!UNITS) {
+    if (threadIdx.x == 0 && atomicAdd(claim + 1, 1) == static_cast<int>(gridDim.x) - 1) {
+      __atomic_store_n(claim, 0, __ATOMIC_RELAXED);
+      __atomic_store_n(claim + 1, 0, __ATOMIC_RELAXED);
+    }
   }
 }
 
@@ -854,8 +873,8 @@ fs_status launch_persistent(const char* who, const DecodeParams& P, int64_t n_it
   int n_cu = 0;
   if (const fs_status st = device_cu_count(who, &n_cu); st != FS_OK) return st;
   const int64_t groups = std::min<int64_t>(n_items, 2ll * n_cu);
-  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3>), dim3(static_cast<unsigned>(groups)), dim3(256), 0, s, P,
-                     static_cast<int>(n_items), claim_dev, n_cu);
+  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, false>), dim3(static_cast<unsigned>(groups)), dim3(256), 0, s, P,
+                     static_cast<int>(n_items), claim_dev, n_cu, static_cast<const int64_t*>(nullptr));
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
   return FS_OK;
@@ -914,6 +933,41 @@ extern "C" fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_k
   const fs_status st = persistent ? launch_persistent(who, P, n_items, claim_dev, s)
                                   : launch_plain(who, P, kv->kv_dtype, n_items, s);
   if (st != FS_OK || !split) return st;
+  return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
+}
+
+extern "C" fs_status fs_decode_attention_units(const fs_shape* shape, const fs_kv_view* kv,
+                                               const fs_work_item* items_dev, int64_t n_items,
+                                               const int64_t* unit_indptr_dev, int64_t n_units,
+                                               const int64_t* chunk_indptr_dev, int64_t n_pairs,
+                                               float* part_o, float* part_lse, float* out, float* lse, void* stream) {
+  const char* who = "fs_decode_attention_units";
+  const bool partials_only = chunk_indptr_dev == nullptr;      // every item's rows to part_o / part_lse, no merge
+  if (!partials_only && (n_pairs < 0 || n_pairs > n_items))
+    return fs::fail(FS_EINVAL, "%s: n_pairs %lld outside [0, n_items]", who, static_cast<long long>(n_pairs));
+  if (n_units < 0 || n_units > n_items) return fs::fail(FS_EINVAL, "%s: n_units %lld outside [0, n_items]", who,
+                                                        static_cast<long long>(n_units));
+  const bool split = partials_only || n_items > n_pairs;
+  DecodeParams P;
+  if (const fs_status st = prepare(who, shape, kv, items_dev, nullptr, n_items, part_o, part_lse, split, true, &P);
+      st != FS_OK || n_items == 0)
+    return st;
+  if (n_units == 0 || (!partials_only && n_pairs == 0))
+    return fs::fail(FS_EINVAL, "%s: %lld items but no pairs or no units", who, static_cast<long long>(n_items));
+  if (!unit_indptr_dev) return fs::fail(FS_EINVAL, "%s: unit_indptr_dev is NULL", who);
+  if (!partials_only && (!out || !lse || (reinterpret_cast<uintptr_t>(out) & 15)))
+    return fs::fail(FS_EINVAL, "%s: out or lse is NULL, or out is not 16-byte aligned", who);
+  if (!partials_only) {
+    P.chunk_indptr = chunk_indptr_dev;
+    P.out = out;
+    P.lse = lse;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, true>), dim3(static_cast<unsigned>(n_units)), dim3(256), 0, s, P,
+                     static_cast<int>(n_items), static_cast<int*>(nullptr), 0, unit_indptr_dev);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+  if (partials_only || n_items == n_pairs) return FS_OK;
   return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
 }
 

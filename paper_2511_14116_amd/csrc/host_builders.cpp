@@ -250,6 +250,104 @@ extern "C" fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx
   return FS_OK;
 }
 
+extern "C" fs_status fs_build_worklist_units(const fs_shape* shape, const int32_t* ctx_len, const int32_t* owner,
+                                             int32_t rank, int32_t n_units,
+                                             fs_work_item* items, int64_t items_cap,
+                                             fs_pair* pairs, int64_t pairs_cap,
+                                             int64_t* unit_indptr, int64_t units_cap, int64_t* chunk_indptr,
+                                             int64_t* n_items, int64_t* n_pairs, int64_t* n_units_out) {
+  const char* who = "fs_build_worklist_units";
+  if (fs_status st = check_shape(shape, who)) return st;
+  const int32_t B = shape->n_req, H = shape->n_kv_heads, R = shape->n_ranks, T = shape->page_tokens;
+  if (!n_items || !n_pairs || !n_units_out) return fs::fail(FS_EINVAL, "%s: count outputs are NULL", who);
+  if (T < 1) return fs::fail(FS_EINVAL, "%s: page_tokens %d < 1", who, T);
+  if (shape->n_q_heads < H || shape->n_q_heads % H)
+    return fs::fail(FS_EINVAL, "%s: n_q_heads %d is not a multiple of n_kv_heads %d", who, shape->n_q_heads, H);
+  if (rank < 0 || rank >= R) return fs::fail(FS_EINVAL, "%s: rank %d outside [0, %d)", who, rank, R);
+  if (n_units < 1) return fs::fail(FS_EINVAL, "%s: n_units %d < 1", who, n_units);
+  if (B > 0 && (!ctx_len || !owner)) return fs::fail(FS_EINVAL, "%s: NULL input array", who);
+  const bool count_only = !items && !pairs && !unit_indptr && !chunk_indptr;
+  if (items_cap < 0 || pairs_cap < 0 || units_cap < 0 || (!items && items_cap) || (!pairs && pairs_cap))
+    return fs::fail(FS_EINVAL, "%s: capacities do not match the arrays", who);
+  const int32_t G = shape->n_q_heads / H;
+
+  // Pass 1: validate, count the pairs and the pages of the stream.
+  int64_t np = 0, P = 0;
+  for (int32_t r = 0; r < B; ++r) {
+    if (ctx_len[r] < 1) return fs::fail(FS_EINVAL, "%s: ctx_len[%d] = %d < 1", who, r, ctx_len[r]);
+    const int64_t pages = (static_cast<int64_t>(ctx_len[r]) + T - 1) / T;
+    for (int32_t h = 0; h < H; ++h) {
+      const int32_t k = owner[static_cast<int64_t>(r) * H + h];
+      if (k < 0 || k >= R) return fs::fail(FS_EINVAL, "%s: owner[%d][%d] = %d outside [0, %d)", who, r, h, k, R);
+      if (k == rank) { ++np; P += pages; }
+    }
+  }
+  const int64_t U = std::min<int64_t>(n_units, P);
+  // Unit u holds stream pages [cut(u), cut(u+1)), cut(u) = floor(u*P/U): equal runs to within one page.
+  auto cut = [&](int64_t u) { return U ? u * P / U : 0; };
+
+  // One walk serves the count and the emission: pairs in (request, head) order, each cut where a unit ends.
+  auto walk = [&](auto&& on_item, auto&& on_pair, auto&& on_unit) {
+    int64_t start = 0, u = 0, next_cut = cut(1), i = 0, p = 0;
+    for (int32_t r = 0; r < B; ++r) {
+      const int32_t L = ctx_len[r];
+      const int64_t pages = (static_cast<int64_t>(L) + T - 1) / T;
+      for (int32_t h = 0; h < H; ++h) {
+        if (owner[static_cast<int64_t>(r) * H + h] != rank) continue;
+        int64_t done = 0;
+        int32_t c = 0;
+        const int64_t first_item = i;
+        while (done < pages) {
+          while (start + done >= next_cut) {      // the stream has left unit u
+            ++u;
+            on_unit(u, i);
+            next_cut = cut(u + 1);
+          }
+          const int64_t take = std::min(pages - done, next_cut - (start + done));
+          on_item(i, r, h, p, c, static_cast<int32_t>(done * T),
+                  static_cast<int32_t>(std::min<int64_t>(L, (done + take) * T)));
+          done += take;
+          ++c;
+          ++i;
+        }
+        on_pair(p, r, h, L, c, first_item);
+        start += pages;
+        ++p;
+      }
+    }
+    return i;
+  };
+  const int64_t ni = walk([](auto...) {}, [](auto...) {}, [](auto...) {});
+  *n_items = ni;
+  *n_pairs = np;
+  *n_units_out = U;
+  if (ni * G > std::numeric_limits<int32_t>::max() ||
+      static_cast<int64_t>(B) * shape->n_q_heads > std::numeric_limits<int32_t>::max())
+    return fs::fail(FS_EINVAL, "%s: row numbers exceed int32 (%lld items x G=%d)", who, static_cast<long long>(ni), G);
+  if (count_only) return FS_OK;
+  if (items_cap < ni || pairs_cap < np || units_cap < U)
+    return fs::fail(FS_ECAPACITY, "%s: need %lld items, %lld pairs and %lld units, have room for %lld, %lld and %lld", who,
+                    static_cast<long long>(ni), static_cast<long long>(np), static_cast<long long>(U),
+                    static_cast<long long>(items_cap), static_cast<long long>(pairs_cap), static_cast<long long>(units_cap));
+  if (!unit_indptr || !chunk_indptr)
+    return fs::fail(FS_EINVAL, "%s: unit_indptr (n_units+1 entries) or chunk_indptr (n_pairs+1 entries) is NULL", who);
+
+  unit_indptr[0] = 0;
+  walk(
+      [&](int64_t i, int32_t r, int32_t h, int64_t p, int32_t c, int32_t tok_begin, int32_t tok_end) {
+        items[i] = fs_work_item{r, h, tok_begin, tok_end, static_cast<int32_t>(p), c,
+                                r * shape->n_q_heads + h * G, static_cast<int32_t>(i * G)};
+      },
+      [&](int64_t p, int32_t r, int32_t h, int32_t L, int32_t c, int64_t first_item) {
+        pairs[p] = fs_pair{r, h, L, c};
+        chunk_indptr[p] = first_item;
+      },
+      [&](int64_t u, int64_t i) { unit_indptr[u] = i; });
+  chunk_indptr[np] = ni;
+  unit_indptr[U] = ni;
+  return FS_OK;
+}
+
 extern "C" int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, int32_t d) {
   if (tok < 0 || tok >= fs::kPageTokens || d < 0 || d >= fs::kHeadDim) return -1;
   if (kv_dtype == FS_KV_FP8_E4M3) return tok * fs::kHeadDim + d;

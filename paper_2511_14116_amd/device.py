@@ -76,6 +76,17 @@ class DeviceShare:
         self.out = torch.full((self.n_pairs * G, D), float("nan"), dtype=torch.float32, device=dev)
         self.lse = torch.full((self.n_pairs * G,), float("nan"), dtype=torch.float32, device=dev)
 
+    def set_worklist_units(self, items: np.ndarray, pairs: np.ndarray, unit_indptr: np.ndarray, chunk_indptr: np.ndarray):
+        """Upload a list cut into equal runs (fs_build_worklist_units) and size the outputs for it."""
+        self.set_worklist(items, pairs, np.zeros(0, dtype=np.int32), chunk_indptr)
+        self.n_units = len(unit_indptr) - 1
+        self.unit_indptr = torch.from_numpy(np.ascontiguousarray(unit_indptr)).to(self.device)
+
+    def run_units(self):
+        B.fs_decode_attention_units(self.shape, self.view, self.items, self.n_items, self.unit_indptr, self.n_units,
+                                    self.chunk_indptr, self.n_pairs, self.part_o, self.part_lse, self.out, self.lse,
+                                    torch.cuda.current_stream().cuda_stream)
+
     def decode(self, use_sched: bool = True):
         B.fs_decode_attention(self.shape, self.view, self.items, self.sched if use_sched else None,
                               self.n_items, self.part_o, self.part_lse, torch.cuda.current_stream().cuda_stream)

@@ -1,6 +1,7 @@
 // Host-side builders under AddressSanitizer + UBSan: random batches through the host
 // entry points with exactly-sized output arrays (so any write past the end is caught) and a few
 // structural checks.  Built and run by tests/test_host_sanitizers.py; touches no GPU.
+#include <cstdint>
 #include <cstdio>
 #include <cstdlib>
 #include <random>
@@ -86,6 +87,44 @@ int main() {
       }
     }
     REQUIRE(covered == static_cast<int64_t>(B) * H);
+  }
+  // the list cut into equal runs: exactly-sized arrays, runs equal to within a page, every pair tiled
+  for (g_case = 500; g_case < 900; ++g_case) {
+    const int R = 1 + rng() % 5, H = 1 + rng() % 8, G = 1 + rng() % 4, B = rng() % 14;
+    fs_shape sh{B, H * G, H, 128, 16, R};
+    std::vector<int32_t> ctx(B), owner(static_cast<size_t>(B) * H);
+    for (auto& c : ctx) c = 1 + rng() % (rng() % 2 ? 60 : 3000);
+    for (auto& o : owner) o = rng() % R;
+    const int32_t rank = rng() % R, n_units = 1 + rng() % (rng() % 2 ? 8 : 700);
+    int64_t ni = -1, np = -1, nu = -1;
+    REQUIRE(fs_build_worklist_units(&sh, ctx.data(), owner.data(), rank, n_units, nullptr, 0, nullptr, 0, nullptr, 0,
+                                    nullptr, &ni, &np, &nu) == FS_OK);
+    std::vector<fs_work_item> items(ni);
+    std::vector<fs_pair> pairs(np);
+    std::vector<int64_t> unit_indptr(nu + 1), chunk_indptr(np + 1);
+    int64_t ni2 = -1, np2 = -1, nu2 = -1;
+    REQUIRE(fs_build_worklist_units(&sh, ctx.data(), owner.data(), rank, n_units, items.data(), ni, pairs.data(), np,
+                                    unit_indptr.data(), nu, chunk_indptr.data(), &ni2, &np2, &nu2) == FS_OK);
+    REQUIRE(ni2 == ni && np2 == np && nu2 == nu && unit_indptr[0] == 0 && unit_indptr[nu] == ni && chunk_indptr[np] == ni);
+    REQUIRE(ni <= np + (nu > 0 ? nu - 1 : 0));
+    int64_t lo = INT64_MAX, hi = 0;
+    for (int64_t u = 0; u < nu; ++u) {
+      int64_t pages = 0;
+      REQUIRE(unit_indptr[u + 1] > unit_indptr[u]);
+      for (int64_t i = unit_indptr[u]; i < unit_indptr[u + 1]; ++i) pages += (items[i].tok_end - items[i].tok_begin + 15) / 16;
+      lo = pages < lo ? pages : lo;
+      hi = pages > hi ? pages : hi;
+    }
+    REQUIRE(nu == 0 || hi - lo <= 1);
+    for (int64_t p = 0; p < np; ++p) {
+      REQUIRE(items[chunk_indptr[p]].tok_begin == 0 && items[chunk_indptr[p + 1] - 1].tok_end == pairs[p].ctx_len);
+      for (int64_t i = chunk_indptr[p] + 1; i < chunk_indptr[p + 1]; ++i) REQUIRE(items[i].tok_begin == items[i - 1].tok_end);
+    }
+    if (ni > 1) {
+      std::vector<fs_work_item> small(ni - 1);
+      REQUIRE(fs_build_worklist_units(&sh, ctx.data(), owner.data(), rank, n_units, small.data(), ni - 1, pairs.data(), np,
+                                      unit_indptr.data(), nu, chunk_indptr.data(), &ni2, &np2, &nu2) == FS_ECAPACITY);
+    }
   }
   // router and prefill scheduler: exactly-sized arrays, token conservation, budget respected
   for (g_case = 1000; g_case < 1300; ++g_case) {

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
         header = f.read()
     declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
     assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_choose_chunk_tokens", "fs_decode_attention",
-            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
+            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_decode_attention_units", "fs_build_worklist_units", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
             "fs_route_request", "fs_route_requests", "fs_schedule_prefill", "fs_plan_kv_reload", "fs_replace_failed_gpu", "fs_plan_ffn_reload", "fs_kv_elem_offset", "fs_stream_read_probe", "fs_set_option", "fs_get_option", "fs_last_error",
             "fs_abi_version"} <= declared
     lib = C.CDLL(fs.library_path())
@@ -87,6 +87,50 @@ def test_random_small_cases_bit_exact():
         assert _items_as_rows(items).tobytes() == oi.tobytes()
         assert pairs.view(np.int32).reshape(-1, 4).tobytes() == op.tobytes()
         assert sched.tobytes() == osch.tobytes() and indptr.tobytes() == oind.tobytes()
+
+
+def _units_equal(got, want):
+    items, pairs, unit_indptr, chunk_indptr = got
+    oi, op, ou, oc = want
+    return (_items_as_rows(items).tobytes() == oi.tobytes() and pairs.view(np.int32).reshape(-1, 4).tobytes() == op.tobytes()
+            and unit_indptr.tobytes() == ou.tobytes() and chunk_indptr.tobytes() == oc.tobytes())
+
+
+def test_units_list_bit_exact_configs_and_random():
+    """fs_build_worklist_units against the oracle's cut, byte for byte: the five batches at full size and drawn
+    small cases with every relation of units to pages (one unit, fewer than pairs, more than pages)."""
+    for cfg_id in range(5):
+        w = make_requests(cfg_id)
+        sh = _shape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"])
+        owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+        for k in (range(w["n_ranks"]) if cfg_id in (0, 3) else [0]):
+            for n_units in (1, 37, 512, 10 ** 7):
+                assert _units_equal(fs.fs_build_worklist_units(sh, w["ctx_len"], owner, k, n_units),
+                                    oracle.build_worklist_units(w["ctx_len"], owner, k, n_units, w["n_q_heads"], w["n_kv_heads"]))
+    rng = np.random.default_rng(12)
+    for _ in range(400):
+        R = int(rng.integers(1, 6)); H = int(rng.integers(1, 9)); G = int(rng.integers(1, 5)); B = int(rng.integers(0, 12))
+        ctx = rng.integers(1, int(rng.choice([20, 400, 5000])), size=B).astype(np.int32)
+        owner = rng.integers(0, R, size=(B, H)).astype(np.int32)
+        k = int(rng.integers(0, R)); n_units = int(rng.choice([1, 2, 3, 5, 8, 64, 1000]))
+        sh = _shape(B, H * G, H, R)
+        assert _units_equal(fs.fs_build_worklist_units(sh, ctx, owner, k, n_units),
+                            oracle.build_worklist_units(ctx, owner, k, n_units, H * G, H))
+    # errors: no units, a short array
+    sh = _shape(2, 4, 2, 2)
+    ctx = np.array([40, 20], dtype=np.int32); owner = np.zeros((2, 2), dtype=np.int32)
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_build_worklist_units(sh, ctx, owner, 0, 0)
+    assert e.value.status == fs.FS_EINVAL
+    lib = fs.load_library()
+    ni, npairs, nu = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    items = np.empty(3, dtype=fs.ITEM_DTYPE); pairs = np.empty(4, dtype=fs.PAIR_DTYPE)
+    ui = np.empty(5, dtype=np.int64); ci = np.empty(5, dtype=np.int64)
+    i32p = C.POINTER(C.c_int32)
+    st = lib.fs_build_worklist_units(C.byref(sh), ctx.ctypes.data_as(i32p), owner.ctypes.data_as(i32p), 0, 4,
+                                     items.ctypes.data, 3, pairs.ctypes.data, 4, ui.ctypes.data, 4, ci.ctypes.data,
+                                     C.byref(ni), C.byref(npairs), C.byref(nu))
+    assert st == fs.FS_ECAPACITY and (ni.value, npairs.value, nu.value) == (7, 4, 4)   # 10 pages in 4 runs of 2-3: three of the cuts fall inside a pair
 
 
 def test_sched_sort_fallback_path_matches():
@@ -165,6 +209,14 @@ def test_device_entry_points_validate_before_touching_the_gpu():
         assert e.value.status == fs.FS_EINVAL
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_fused(_shape(1, 4, 2, 3, d=64), kv, None, None, 3, None, 3, None, None, None, None, None)
+    assert e.value.status == fs.FS_EUNSUPPORTED
+    fs.fs_decode_attention_units(sh, kv, None, 0, None, 0, None, 0, None, None, None, None)          # empty list: no-op
+    for n_items, n_units, n_pairs in ((3, 4, 3), (3, 2, 4), (3, 0, 2), (3, 2, 2)):        # counts that cannot be; NULL pointers
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_decode_attention_units(sh, kv, None, n_items, None, n_units, None, n_pairs, None, None, None, None)
+        assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_decode_attention_units(sh, kv8, None, 3, None, 2, None, 2, None, None, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
     # prefill: empty list is a no-op; a tile beyond the kernel's is refused before any launch
     fs.fs_prefill_attention(sh, kv, None, None, 0, 1, None, None)
