@@ -65,7 +65,9 @@ def main() -> int:
                          "partial rows leave in bursts) even for short lists; by default it is used from 1024 items on")
     ap.add_argument("--units", type=int, default=None, metavar="N",
                     help="bf16: cut the share into N equal runs of pages (0 = two per compute unit) and sweep them with one "
-                         "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units)")
+                         "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units).  Default: that form, "
+                         "two runs per compute unit, once a run would hold 64 pages or more; else the chunked list")
+    ap.add_argument("--chunked", action="store_true", help="the chunked list (fs_build_worklist) whatever the share's size")
     ap.add_argument("--two-calls", action="store_true",
                     help="the step calls fs_decode_attention[_persistent] and fs_merge_lse instead of fs_decode_attention_fused")
     ap.add_argument("--placement", choices=["requests", "heads"], default="requests",
@@ -137,17 +139,22 @@ def main() -> int:
         return w["chunk_tokens"]
 
     chunk = chunk_for(args.rank)
-    units = args.units is not None
-    if units and w["kv_dtype"] != "bf16":
+    if args.units is not None and w["kv_dtype"] != "bf16":
         print("bench.py: --units is built for bf16 K/V", file=sys.stderr)
         return 2
+    UNIT_MIN_PAGES = 64      # below this a run is too short to pay for its start: the chunked list measures faster
+
+    def pages_of(rank):
+        return sum(-(-int(ctx[r]) // w["page_tokens"]) for r in range(B) for h in range(Hkv) if owner[r, h] == rank)
 
     def units_for(rank):
         """Two resident workgroups per compute unit, but at least 16 pages (256 tokens) to a run."""
         if args.units:
             return args.units
-        pages = sum(-(-int(ctx[r]) // w["page_tokens"]) for r in range(B) for h in range(Hkv) if owner[r, h] == rank)
-        return max(1, min(2 * n_cu, pages // 16))
+        return max(1, min(2 * n_cu, pages_of(rank) // 16))
+
+    units = args.units is not None or (w["kv_dtype"] == "bf16" and not args.chunked and not args.classic and not args.persistent
+                                       and args.chunk is None and pages_of(args.rank) >= UNIT_MIN_PAGES * 2 * n_cu)
 
     if units:
         n_units_req = units_for(args.rank)
@@ -375,6 +382,19 @@ def main() -> int:
     dec_ms = time_each(call_decode[0], KERNEL_LAUNCHES)
     fused_ms = time_each(call_fused[0], KERNEL_LAUNCHES)       # sweep + merge of the split pairs, as the step runs them
 
+    def time_batch(call, n):
+        """n launches back to back between one pair of events: the launch-to-launch period, without the few
+        microseconds an event pair adds around a single launch."""
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(n):
+            call()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    dec_batch_ms = time_batch(call_decode[0], KERNEL_LAUNCHES)
+
     # a graph step and an eager step must leave the same bits behind
     if graphs is not None:
         build_host(0)
@@ -520,7 +540,7 @@ def main() -> int:
                "one_core": {"value": round(s_tok * 2 * w["head_dim"] * elt / dt_one / 1e9, 4), "unit": "GB/s",
                             "seconds": round(dt_one, 2)}}
 
-    dec_avg_ms = float(dec_ms.mean())
+    dec_avg_ms = float(dec_batch_ms)
     achieved = decode_bytes / (dec_avg_ms * 1e-3) / 1e9
     kernel_name = "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else ("decode_bf16_persistent_kernel" if persistent or units
                                                                         else "decode_bf16_kernel")
@@ -553,7 +573,8 @@ def main() -> int:
                    "work_list": "read in place from pinned host memory" if host_list else "uploaded every step"},
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "kv_token_heads_per_s": round(tok_heads / (ms_per_step * 1e-3), 1),
-        "kernel_ms": {"decode_avg": round(dec_avg_ms, 5), "decode_p50": round(float(np.median(dec_ms)), 5),
+        "kernel_ms": {"decode_avg": round(dec_avg_ms, 5), "decode_avg_is": f"{KERNEL_LAUNCHES} launches back to back between one pair of events",
+                      "decode_each_avg": round(float(dec_ms.mean()), 5), "decode_p50": round(float(np.median(dec_ms)), 5),
                       "decode_p10": round(float(np.percentile(dec_ms, 10)), 5),
                       "decode_p90": round(float(np.percentile(dec_ms, 90)), 5),
                       "decode_launches": int(len(dec_ms)),

@@ -44,7 +44,8 @@ PREFILL_PAIR_DTYPE = np.dtype([(n, np.int32) for n in ("req", "kv_head", "n_done
 
 
 def library_path() -> str:
-    return os.path.join(_PKG, "libfailsafe.so")
+    """The in-tree library, or the build named by FAILSAFE_LIBRARY (for comparing two builds on one GPU)."""
+    return os.environ.get("FAILSAFE_LIBRARY") or os.path.join(_PKG, "libfailsafe.so")
 
 
 def load_library(path: str | None = None):

@@ -21,15 +21,22 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra: list[str] | None = None) -> str:
+def build(verbose: bool = True, extra: list[str] | None = None, out: str | None = None) -> str:
+    """Compile every source into one shared library (``out``, default the in-tree libfailsafe.so)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    lib = out or LIB
     cmd = [hipcc, *FLAGS, *(extra or []), "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+           "-o", lib, *[os.path.join(CSRC, s) for s in SOURCES]]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    build(extra=sys.argv[1:])
+    # python -m paper_2511_14116_amd.build [-o other.so] [extra hipcc flags...]
+    argv = sys.argv[1:]
+    out = None
+    if argv[:1] == ["-o"]:
+        out, argv = argv[1], argv[2:]
+    build(extra=argv, out=out)

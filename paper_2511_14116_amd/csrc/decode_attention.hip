@@ -324,18 +324,25 @@ struct ItemDesc {
   int n_tok;            // tokens of the item
   int p0, p1;           // this wavefront's pages [p0, p1) of the item
   int row;              // first partial row of the item, or -(first final row) - 1 when the item is all of its pair (fused form)
-  bf16x8 q[4];          // Q^T operand of this lane
+  int q_row;            // first query row of the item's group
+  int32_t first_ids[3]; // slots of this wavefront's first pages (those the prologue fetches), asked for with the rest
+  bf16x8 q[4];          // Q^T operand of this lane (load_desc_q)
   bool valid;
 };
 
-template <int WAVES>
-__device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int n_items, int wave, int lane, int G) {
+// The scalar part of item k's descriptor: everything but the query rows.  All of it stays in scalar registers.
+template <int WAVES, int NBUF>
+__device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k, int n_items, int wave, int G) {
+  static_assert(NBUF - 1 <= 3, "first_ids holds three slots");
   ItemDesc d;
   d.valid = k < n_items;
   d.ids = (const_ids_ptr)(uintptr_t)0;
   d.n_tok = 0;
   d.p0 = d.p1 = 0;
   d.row = 0;
+  d.q_row = 0;
+#pragma unroll
+  for (int u = 0; u < 3; ++u) d.first_ids[u] = 0;
 #pragma unroll
   for (int c = 0; c < 4; ++c) d.q[c] = bf16x8{};
   if (d.valid) {
@@ -358,13 +365,24 @@ __device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int 
     const int per = (n_pages + WAVES - 1) / WAVES;
     d.p0 = wave * per;
     d.p1 = min(n_pages, d.p0 + per);
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u)
+      if (d.p0 + u < d.p1) d.first_ids[u] = d.ids[d.p0 + u];
     d.row = it.part_row;
+    d.q_row = it.q_row;
     if (P.chunk_indptr) {
       const int32_t n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - P.chunk_indptr[it.pair]));
       if (n_chunks == 1) d.row = -(it.pair * G) - 1;
     }
+  }
+  return d;
+}
+
+// The query rows of the item, as the Q^T operand of this lane.
+__device__ __forceinline__ void load_desc_q(ItemDesc& d, const DecodeParams& P, int lane, int G) {
+  if (d.valid) {
     const int qi = lane & 15, kb = lane >> 4;
-    const int qrow = it.q_row + min(qi, G - 1);
+    const int qrow = d.q_row + min(qi, G - 1);
     const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -373,7 +391,6 @@ __device__ __forceinline__ ItemDesc load_desc(const DecodeParams& P, int k, int 
       d.q[c] = __builtin_bit_cast(bf16x8, v);
     }
   }
-  return d;
 }
 
 // UNITS = true is the form without a counter: workgroup u walks the items [unit_indptr[u], unit_indptr[u+1]) of a
@@ -402,13 +419,14 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
     cur_k = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x]));
     unit_end = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x + 1]));   // > cur_k: no unit is empty
   }
-  ItemDesc cur = load_desc<WAVES>(P, cur_k, n_items, wave, lane, G);   // a valid item by the launch
+  ItemDesc cur = load_desc_head<WAVES, NBUF>(P, cur_k, n_items, wave, G);   // a valid item by the launch
+  load_desc_q(cur, P, lane, G);
 
   PageRegs buf[NBUF];
   auto prologue = [&](const ItemDesc& d) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < NBUF - 1; ++u)
-      if (d.p0 + u < d.p1) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.ids[d.p0 + u], lane);
+      if (d.p0 + u < d.p1) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.first_ids[u], lane);
   };
   prologue(cur);
 
@@ -423,6 +441,16 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
   bool keep_claiming = true;
   int staged = 0;
   for (;;) {
+    // With equal runs the next item is known from the start: its descriptor and the slots of its first pages are
+    // asked for now and travel while the current item streams, so that at the item's end the next pages can be
+    // requested at once.  With a counter the next item is only known after the claim (below).
+    ItemDesc nxt;
+#ifndef FS_EXP_LATE_DESC
+    if constexpr (UNITS) {
+      ++cur_k;
+      nxt = load_desc_head<WAVES, NBUF>(P, cur_k < unit_end ? cur_k : n_items, n_items, wave, G);
+    }
+#endif
     SoftmaxState st;
     st.m = -INFINITY;
     st.l = 0.f;
@@ -465,15 +493,18 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
     lds_barrier();
     // every page of the current item is consumed: fetch the next item's descriptor and first pages now,
     // so that they travel while the rows are merged
-    int next_k;
+    if constexpr (!UNITS) {
+      const int next_k = __builtin_amdgcn_readfirstlane(s_next);
+      nxt = load_desc_head<WAVES, NBUF>(P, next_k, n_items, wave, G);
+      if (second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
+    }
+#ifdef FS_EXP_LATE_DESC
     if constexpr (UNITS) {
       ++cur_k;
-      next_k = cur_k < unit_end ? cur_k : n_items;
-    } else {
-      next_k = __builtin_amdgcn_readfirstlane(s_next);
+      nxt = load_desc_head<WAVES, NBUF>(P, cur_k < unit_end ? cur_k : n_items, n_items, wave, G);
     }
-    ItemDesc nxt = load_desc<WAVES>(P, next_k, n_items, wave, lane, G);
-    if (!UNITS && second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
+#endif
+    load_desc_q(nxt, P, lane, G);
     prologue(nxt);
     for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
       const int q = idx >> 5, d4 = idx & 31;
