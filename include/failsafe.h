@@ -395,6 +395,21 @@ typedef struct {
  * order.  Returns -1 for arguments out of range or an unknown kv_dtype. */
 FS_API int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, int32_t d);
 
+/* fs_pack_kv_slots - KVCache blocks (Section 2.1.1) from token-major order [tok][d] into the element order
+ * above, on the device: slot s is read at src_dev + s*src_slot_stride and written at dst_dev +
+ * s*dst_slot_stride (so the destination may be the K or the V half of an interleaved pool).  fp8 slots
+ * are token-major in both orders and are copied.  The stand-in for an engine's KV-append step, which
+ * would write the kernels' order directly.
+ *
+ *  src_dev  DEVICE in   n_slots slots of 16 x 128 elements, token-major
+ *  dst_dev  DEVICE out  the same slots in kernel order; the two pools must not overlap
+ *  is_v     0: the K order, else the V order
+ *
+ * n_slots == 0 is a no-op.  FS_EINVAL: NULL or misaligned (16 bytes) pointers or strides, a stride below one
+ * slot, overlapping pools, unknown kv_dtype.  FS_EHIP: launch failure. */
+FS_API fs_status fs_pack_kv_slots(const void* src_dev, int64_t src_slot_stride, void* dst_dev, int64_t dst_slot_stride,
+                                  int64_t n_slots, int32_t kv_dtype, int32_t is_v, void* stream);
+
 /* ---------------------------------------------------------------------------
  * fs_decode_attention - decode-phase attention (Section 2.1.1) for every item
  * of the list, one launch.  For item i and g in [0, G), with q = query row

@@ -123,6 +123,8 @@ def load_library(path: str | None = None):
     lib.fs_merge_lse.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                  C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_merge_lse.restype = C.c_int
+    lib.fs_pack_kv_slots.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
+    lib.fs_pack_kv_slots.restype = C.c_int
     lib.fs_stream_read_probe.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     lib.fs_stream_read_probe.restype = C.c_int
     lib.fs_set_option.argtypes = [C.c_char_p, C.c_int32]
@@ -473,6 +475,12 @@ def fs_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, h
     st = load_library().fs_merge_lse(_ptr(part_o), _ptr(part_lse), _ptr(chunk_indptr_dev), n_pairs, group,
                                      head_dim, _ptr(out), _ptr(lse), _ptr(stream))
     _check(st)
+
+
+def fs_pack_kv_slots(src_dev, src_slot_stride: int, dst_dev, dst_slot_stride: int, n_slots: int, kv_dtype: int,
+                     is_v: bool, stream=None) -> None:
+    _check(load_library().fs_pack_kv_slots(_ptr(src_dev), src_slot_stride, _ptr(dst_dev), dst_slot_stride, n_slots,
+                                           kv_dtype, int(bool(is_v)), _ptr(stream)))
 
 
 def fs_stream_read_probe(buf_dev, nbytes: int, sink_dev, stream=None) -> None:

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfailsafe.so")
 
-SOURCES = ["status.cpp", "host_builders.cpp", "host_scheduler.cpp", "host_recovery.cpp", "host_prefill.cpp", "decode_attention.hip", "merge_lse.hip", "prefill_attention.hip", "stream_probe.hip"]
+SOURCES = ["status.cpp", "host_builders.cpp", "host_scheduler.cpp", "host_recovery.cpp", "host_prefill.cpp", "decode_attention.hip", "merge_lse.hip", "prefill_attention.hip", "stream_probe.hip", "pack_slots.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -6,7 +6,6 @@ import numpy as np
 import torch
 
 from . import binding as B
-from .layout import pack_slots
 
 _KV_CODE = {"bf16": B.FS_KV_BF16, "fp8": B.FS_KV_FP8_E4M3}
 
@@ -26,23 +25,25 @@ class DeviceShare:
         self.q = torch.from_numpy(q_bits.view(np.int16)).to(self.device)
         tdt = torch.int16 if self.kv_dtype == B.FS_KV_BF16 else torch.uint8
         view = (lambda a: a.view(np.int16)) if self.kv_dtype == B.FS_KV_BF16 else (lambda a: a)
-        k = pack_slots(torch.from_numpy(view(kv["k_pool"])).to(self.device), self.kv_dtype, False)
-        v = pack_slots(torch.from_numpy(view(kv["v_pool"])).to(self.device), self.kv_dtype, True)
-        n_slots, T, D = k.shape
-        slot_bytes = T * D * k.element_size()
+        n_slots, T, D = kv["k_pool"].shape
+        slot_bytes = T * D * (2 if self.kv_dtype == B.FS_KV_BF16 else 1)
+        stream = torch.cuda.current_stream().cuda_stream
         if interleave_kv:
             # K and V of a slot side by side: one 2*slot_bytes run per (page, head)
-            both = torch.empty((n_slots, 2, T * D), dtype=tdt, device=self.device)
-            both[:, 0] = k.reshape(n_slots, -1)
-            both[:, 1] = v.reshape(n_slots, -1)
-            del k, v
-            self._pool = both
-            k_ptr, v_ptr = both.data_ptr(), both.data_ptr() + slot_bytes
+            self._pool = torch.empty((n_slots, 2, T * D), dtype=tdt, device=self.device)
+            k_ptr, v_ptr = self._pool.data_ptr(), self._pool.data_ptr() + slot_bytes
             k_stride = v_stride = 2 * slot_bytes
         else:
-            self._pool = (k, v)
-            k_ptr, v_ptr = k.data_ptr(), v.data_ptr()
+            self._pool = (torch.empty((n_slots, T * D), dtype=tdt, device=self.device),
+                          torch.empty((n_slots, T * D), dtype=tdt, device=self.device))
+            k_ptr, v_ptr = self._pool[0].data_ptr(), self._pool[1].data_ptr()
             k_stride = v_stride = slot_bytes
+        # the generator's pools are token-major; the library puts every slot into the order its kernels read
+        for host, dst, is_v in ((kv["k_pool"], k_ptr, False), (kv["v_pool"], v_ptr, True)):
+            src = torch.from_numpy(view(host)).to(self.device)
+            B.fs_pack_kv_slots(src, slot_bytes, dst, k_stride, n_slots, self.kv_dtype, is_v, stream)
+            torch.cuda.current_stream().synchronize()
+            del src
         self.page_indptr = torch.from_numpy(kv["page_indptr"]).to(self.device)
         self.page_ids = torch.from_numpy(kv["page_ids"]).to(self.device)
         self.k_scale = self.v_scale = self.page_scales = None

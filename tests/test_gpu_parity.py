@@ -257,6 +257,33 @@ def test_large_scores_stay_finite():
         check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"large scores, chunk {chunk}")
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_device_slot_packing_matches_the_layout_definition(kv_dtype):
+    """fs_pack_kv_slots on the device against the gather that fs_kv_elem_offset defines (applied on the host),
+    byte for byte, into separate pools and into the two halves of an interleaved pool."""
+    from paper_2511_14116_amd.layout import pack_slots
+    rng = np.random.default_rng(3)
+    code = fs.FS_KV_BF16 if kv_dtype == "bf16" else fs.FS_KV_FP8_E4M3
+    n_slots, elt = 37, (np.uint16 if kv_dtype == "bf16" else np.uint8)
+    slot_bytes = 2048 * np.dtype(elt).itemsize
+    stream = torch.cuda.current_stream().cuda_stream
+    for is_v in (False, True):
+        host = rng.integers(0, np.iinfo(elt).max, size=(n_slots, 16, 128), dtype=elt)
+        want = pack_slots(host, code, is_v).reshape(n_slots, -1)
+        src = torch.from_numpy(host.view(np.int16 if kv_dtype == "bf16" else np.uint8)).cuda()
+        dst = torch.zeros((n_slots, 2048), dtype=src.dtype, device="cuda")
+        fs.fs_pack_kv_slots(src, slot_bytes, dst, slot_bytes, n_slots, code, is_v, stream)
+        both = torch.zeros((n_slots, 2, 2048), dtype=src.dtype, device="cuda")
+        fs.fs_pack_kv_slots(src, slot_bytes, both.data_ptr() + (slot_bytes if is_v else 0), 2 * slot_bytes, n_slots, code, is_v, stream)
+        torch.cuda.synchronize()
+        assert dst.cpu().numpy().view(elt).tobytes() == want.tobytes()
+        half = both[:, 1 if is_v else 0].cpu().numpy().view(elt)
+        assert half.tobytes() == want.tobytes() and not both[:, 0 if is_v else 1].any()
+    with pytest.raises(fs.FsError) as e:          # in place is refused
+        fs.fs_pack_kv_slots(src, slot_bytes, src, slot_bytes, n_slots, code, False, stream)
+    assert e.value.status == fs.FS_EINVAL
+
+
 def test_empty_rank_is_a_no_op():
     w = make_requests(0, n_req=1)
     w["ctx_len"] = np.array([40], dtype=np.int32); w["mode"] = np.array([1], np.uint8)

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
         header = f.read()
     declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
     assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_choose_chunk_tokens", "fs_decode_attention",
-            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_decode_attention_units", "fs_build_worklist_units", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
+            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_decode_attention_units", "fs_build_worklist_units", "fs_pack_kv_slots", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
             "fs_route_request", "fs_route_requests", "fs_schedule_prefill", "fs_plan_kv_reload", "fs_replace_failed_gpu", "fs_plan_ffn_reload", "fs_kv_elem_offset", "fs_stream_read_probe", "fs_set_option", "fs_get_option", "fs_last_error",
             "fs_abi_version"} <= declared
     lib = C.CDLL(fs.library_path())
@@ -218,6 +218,11 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_units(sh, kv8, None, 3, None, 2, None, 2, None, None, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
+    fs.fs_pack_kv_slots(None, 4096, None, 4096, 0, fs.FS_KV_BF16, False)                            # no slots: no-op
+    for args in ((None, 4096, None, 4096, 3, fs.FS_KV_BF16), (64, 4096, 8192, 100, 3, fs.FS_KV_BF16), (64, 4096, 8192, 4096, 3, 9)):
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_pack_kv_slots(*args, False)
+        assert e.value.status == fs.FS_EINVAL
     # prefill: empty list is a no-op; a tile beyond the kernel's is refused before any launch
     fs.fs_prefill_attention(sh, kv, None, None, 0, 1, None, None)
     with pytest.raises(fs.FsError) as e:
