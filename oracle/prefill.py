@@ -39,7 +39,7 @@ def build_prefill_worklist(n_done, n_new, owner, rank: int, n_q_heads: int, tile
     out_indptr [m+1] int64)."""
     owner = np.asarray(owner)
     B, H = owner.shape
-    if n_q_heads % H or tile_tokens < 1 or kv_chunk_tokens < 0 or kv_chunk_tokens % 32:
+    if n_q_heads % H or tile_tokens < 1 or kv_chunk_tokens < 0:
         raise ValueError("bad head counts, tile size or chunk size")
     G = n_q_heads // H
     T = tile_tokens * G
