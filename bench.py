@@ -72,6 +72,8 @@ def main() -> int:
                          "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units).  Default: that form, "
                          "two runs per compute unit, once a run would hold 64 pages or more; else the chunked list")
     ap.add_argument("--chunked", action="store_true", help="the chunked list (fs_build_worklist) whatever the share's size")
+    ap.add_argument("--no-records", action="store_true",
+                    help="hand the kernels the items (they look each one up themselves) instead of launch records")
     ap.add_argument("--two-calls", action="store_true",
                     help="the step calls fs_decode_attention[_persistent] and fs_merge_lse instead of fs_decode_attention_fused")
     ap.add_argument("--placement", choices=["requests", "heads"], default="requests",
@@ -185,7 +187,9 @@ def main() -> int:
     kv_bytes = tok_heads * 2 * w["head_dim"] * elt          # K and V rows actually attended
     scale_bytes = n_pages * 8 if w["kv_dtype"] == "fp8" else 0
     q_bytes = n_pairs * G * w["head_dim"] * 2
-    table_bytes = n_pages * 4 + n_items * 32 + ((n_units + 1) * 8 if units else n_items * 4)
+    # list bytes the sweep reads: 64-byte records, or 32-byte items + launch order; run boundaries for equal runs
+    table_bytes = n_pages * 4 + (n_items * 64 if not (args.no_records or args.two_calls) else n_items * 32 + (0 if units else n_items * 4)) \
+        + ((n_units + 1) * 8 if units else 0)
     row_bytes = w["head_dim"] * 4 + 4                       # one fp32 output row and its lse
     counts = np.diff(chunk_indptr)
     if args.two_calls:                                      # every item writes partial rows, the merge reads them all
@@ -211,7 +215,9 @@ def main() -> int:
     off_items = 0
     off_sched = up(off_items + n_items * 32)
     off_indptr = up(off_sched + ((n_units + 1) * 8 if units else n_items * 4))      # units: unit_indptr sits where sched would
-    blob_bytes = up(off_indptr + (n_pairs + 1) * 8)
+    off_records = up(off_indptr + (n_pairs + 1) * 8)          # launch records of the step's list (one-call form)
+    off_records2 = up(off_records + n_items * 64)             # and records that send every row to part_o (the sweep timed alone)
+    blob_bytes = up(off_records2 + n_items * 64)
     N_SLOTS = 4
     dev_blobs = [torch.empty(blob_bytes, dtype=torch.uint8, device=dev) for _ in range(N_SLOTS)]
     host_blobs = [torch.zeros(blob_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(N_SLOTS)]
@@ -224,6 +230,8 @@ def main() -> int:
                            a[off_sched:off_sched + (n_units + 1) * 8].view(np.int64) if units else
                            a[off_sched:off_sched + n_items * 4].view(np.int32),
                            a[off_indptr:off_indptr + (n_pairs + 1) * 8].view(np.int64)))
+    host_rec = [hb.numpy()[off_records:off_records + n_items * 64].view(fs.RECORD_DTYPE) for hb in host_blobs]
+    host_rec2 = [hb.numpy()[off_records2:off_records2 + n_items * 64].view(fs.RECORD_DTYPE) for hb in host_blobs]
     part_o = torch.empty((n_items * G, w["head_dim"]), dtype=torch.float32, device=dev)
     part_lse = torch.empty(n_items * G, dtype=torch.float32, device=dev)
     out = torch.empty((n_pairs * G, w["head_dim"]), dtype=torch.float32, device=dev)
@@ -254,12 +262,27 @@ def main() -> int:
               file=sys.stderr)
         return 2
     claim = torch.zeros(2, dtype=torch.int32, device=dev)    # the persistent sweep's counters; every launch leaves them at zero
+    # Launch records: the host resolves every item (page-table offset, chunk count, first slots) while it builds the
+    # list, so a workgroup starts with one read instead of four dependent ones.  The counter form takes items only.
+    use_records = not args.no_records and not persistent and not args.two_calls
+    page_indptr_h = np.ascontiguousarray(kv["page_indptr"], dtype=np.int64)
+    page_ids_h = np.ascontiguousarray(kv["page_ids"], dtype=np.int32)
+    call_records = [fs.bind_build_launch_records(shape, hv[0], None if units else hv[2], hv[3], n_pairs, page_indptr_h,
+                                                 page_ids_h, host_rec[s_]) for s_, hv in enumerate(host_views)]
 
     def bind_gpu_calls(stream_ptr):
         """Per blob: the sweep alone, the merge alone, and the one-call form of both."""
         dec, mrg, fused = [], [], []
         for db in (host_blobs if host_list else dev_blobs):
             base = db.data_ptr()        # a pinned host blob is mapped into the GPU's address space at the same address
+            if use_records:
+                ui = (base + off_sched) if units else None
+                dec.append(fs.bind_decode_attention_records(shape, ds.view, base + off_records2, n_items, ui, n_units if units else 0,
+                                                            None, 0, part_o, part_lse, out, lse, stream_ptr))
+                mrg.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"], out, lse, stream_ptr))
+                fused.append(fs.bind_decode_attention_records(shape, ds.view, base + off_records, n_items, ui, n_units if units else 0,
+                                                              base + off_indptr, n_pairs, part_o, part_lse, out, lse, stream_ptr))
+                continue
             if units:
                 dec.append(fs.bind_decode_attention_units(shape, ds.view, base + off_items, n_items, base + off_sched, n_units,
                                                           None, 0, part_o, part_lse, None, None, stream_ptr))
@@ -293,6 +316,8 @@ def main() -> int:
             dpl_buf.fill(0)
         call_place()                                        # S1 + S2
         call_list[slot]()                                   # S3
+        if use_records:
+            call_records[slot]()                            # S3, written out for the kernels
 
     # The GPU side of step i reads device blob i % N_SLOTS and, next to it, uploads the blob of
     # step i+1 (which the host has built by then), so the upload never sits between two sweeps.
@@ -379,6 +404,10 @@ def main() -> int:
         return np.array([a.elapsed_time(b) for a, b in evs])
 
     build_host(0)
+    if use_records:     # for the sweep timed alone: records that send every item's rows to part_o
+        hv0 = host_views[0]
+        fs.fs_build_launch_records(shape, hv0[0], None if units else hv0[2], hv0[3], page_indptr_h, page_ids_h,
+                                   direct_rows=False, out=host_rec2[0])
     upload(0)
     for _ in range(3):
         call_decode[0]()
@@ -566,7 +595,8 @@ def main() -> int:
                    "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
                    "sweep": "one resident workgroup per run of pages" if units else ("persistent" if persistent else "one workgroup per item"),
-                   "step_calls": ("fs_decode_attention_units" + (" (sweep alone) + fs_merge_lse" if args.two_calls else "")) if units else
+                   "step_calls": "fs_build_launch_records + fs_decode_attention_records" if use_records else
+                                 ("fs_decode_attention_units" + (" (sweep alone) + fs_merge_lse" if args.two_calls else "")) if units else
                                  ("fs_decode_attention[_persistent] + fs_merge_lse" if args.two_calls else "fs_decode_attention_fused"),
                    "merge_launched": bool(args.two_calls or n_items > n_pairs),
                    "waves_per_group": fs.fs_get_option("waves_per_group"),

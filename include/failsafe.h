@@ -510,6 +510,67 @@ FS_API fs_status fs_decode_attention_units(const fs_shape* shape, const fs_kv_vi
                                            float* part_o, float* part_lse, float* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Launch records - a work list written out the way a kernel wants to find it.  A kernel that is
+ * handed items looks each one up itself: the list entry, the item, the pair's offset in the page
+ * table and its chunk count, then the page ids - four dependent reads before the first page of
+ * K/V can be asked for, at the start of every workgroup.  A record holds all of that for one item,
+ * resolved on the host, with the slots of the item's first eight pages: one 64-byte read.
+ * (The ragged list is Section 3.1's; the record is this library's device.) */
+typedef struct {
+  int64_t first_page;      /* index into page_ids of the item's first page:
+                              page_indptr[pair] + tok_begin / page_tokens                    */
+  int32_t n_tok;           /* tok_end - tok_begin                                            */
+  int32_t q_row;           /* first query row, as in the item                                */
+  int32_t row;             /* first partial row (part_row); or, for an item that is all of
+                              its pair, -(pair*G) - 1: its rows are the pair's final rows    */
+  int32_t reserved0;       /* 0                                                              */
+  int32_t first_slots[8];  /* page_ids[first_page + j], j = 0..7 (0 beyond the last page)    */
+  int32_t reserved1[2];    /* 0                                                              */
+} fs_launch_record;        /* 64 bytes; arrays of these are compared bit for bit             */
+
+/* fs_build_launch_records - record k describes item order[k] (order == NULL: item k).
+ *
+ *  items        HOST in  [n_items]    from fs_build_worklist or fs_build_worklist_units
+ *  order        HOST in  [n_items] or NULL   launch order (fs_build_worklist's sched)
+ *  chunk_indptr HOST in  [n_pairs+1]
+ *  page_indptr  HOST in  [n_pairs+1]  the page table the kernels will be given, host copy
+ *  page_ids     HOST in  [n_page_ids]
+ *  direct_rows  nonzero: an item that is all of its pair gets row = -(pair*G) - 1 (what
+ *               fs_decode_attention_records expects); 0: every row is the item's part_row
+ *  records      HOST out [n_items]
+ *
+ * FS_EINVAL: NULL pointer, negative counts, an order entry or a pair outside its range, an item
+ * whose pages do not lie inside its pair's part of the page table. */
+FS_API fs_status fs_build_launch_records(const fs_shape* shape, const fs_work_item* items, const int32_t* order,
+                                         int64_t n_items, const int64_t* chunk_indptr, int64_t n_pairs,
+                                         const int64_t* page_indptr, const int32_t* page_ids, int64_t n_page_ids,
+                                         int32_t direct_rows, fs_launch_record* records);
+
+/* fs_decode_attention_records - decode attention (Section 2.1.1) and split-K merge in one call,
+ * from launch records built with direct_rows != 0.  unit_indptr_dev == NULL: one workgroup per
+ * record, in the order of the array (bf16 or fp8 K/V).  unit_indptr_dev given: records of a list
+ * from fs_build_worklist_units in item order, one resident workgroup per unit (bf16 K/V), as
+ * fs_decode_attention_units.  Rows of unsplit pairs come final from the sweep; the merge runs for
+ * split pairs and is not launched when n_items == n_pairs.  out/lse hold what the calls that take
+ * items leave for the same list, bit for bit.
+ *
+ *  records_dev       DEVICE in   [n_items]
+ *  unit_indptr_dev   DEVICE in   [n_units+1] or NULL
+ *  chunk_indptr_dev  DEVICE in   [n_pairs+1]  (read by the merge only), or NULL: the sweep alone - no merge is
+ *                    launched, n_pairs is ignored and every row goes where its record says (records built
+ *                    with direct_rows == 0 send all of them to part_o/part_lse)
+ *  part_o, part_lse  DEVICE scratch [n_items*G][head_dim], [n_items*G]; may be NULL when n_items == n_pairs
+ *  out, lse          DEVICE out
+ *
+ * The page table of kv must be the one the records were built from.  Errors as for
+ * fs_decode_attention_fused. */
+FS_API fs_status fs_decode_attention_records(const fs_shape* shape, const fs_kv_view* kv,
+                                             const fs_launch_record* records_dev, int64_t n_items,
+                                             const int64_t* unit_indptr_dev, int64_t n_units,
+                                             const int64_t* chunk_indptr_dev, int64_t n_pairs,
+                                             float* part_o, float* part_lse, float* out, float* lse, void* stream);
+
+/* ---------------------------------------------------------------------------
  * fs_decode_attention_fused_static - fs_decode_attention_fused for callers that cannot allocate
  * device memory or hand over a workspace: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  The counters of the persistent sweep and the partial rows of

@@ -20,7 +20,7 @@ from .prefill import (  # noqa: F401
 )
 from .recovery import plan_ffn_reload, plan_kv_reload, replace_failed_gpu  # noqa: F401
 from .scheduler import adaptive_chunked_prefill, route_request, token_cost  # noqa: F401
-from .worklist import build_worklist, build_worklist_units, choose_chunk_tokens, ITEM_FIELDS, PAIR_FIELDS  # noqa: F401
+from .worklist import build_worklist, build_worklist_units, build_launch_records, choose_chunk_tokens, ITEM_FIELDS, PAIR_FIELDS  # noqa: F401
 from .attention import (  # noqa: F401
     attend,
     gather_pair_kv,

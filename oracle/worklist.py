@@ -119,3 +119,40 @@ def build_worklist_units(ctx_len, owner, rank: int, n_units: int, n_q_heads: int
         unit_indptr.append(len(items))
     return (np.array(items, dtype=np.int32).reshape(-1, 8), np.array(pairs, dtype=np.int32).reshape(-1, 4),
             np.array(unit_indptr, dtype=np.int64), np.array(chunk_indptr, dtype=np.int64))
+
+
+RECORD_WORDS = 16       # a launch record is 16 int32 words (64 bytes)
+
+
+def build_launch_records(items, order, chunk_indptr, page_indptr, page_ids, group: int, direct_rows: bool = True,
+                         page_tokens: int = 16):
+    """A work list written out the way a kernel wants to find it: one 64-byte record per item, in launch
+    order, with everything the item's first memory requests depend on already looked up (this build's
+    device; the paper describes no kernel).  ``order`` lists item indices in launch order (None: index
+    order).  Record k, for item i = order[k], as 16 int32 words:
+
+        0-1   first_page  index into page_ids of the item's first page (int64, low word first):
+                          page_indptr[pair] + tok_begin / page_tokens
+        2     n_tok       tok_end - tok_begin
+        3     q_row       as in the item
+        4     row         part_row; or, with ``direct_rows`` and a pair that is this one item,
+                          -(pair*group) - 1: the item's rows are the pair's final rows
+        5     0
+        6-13  page_ids[first_page + j] for j = 0..7 (0 beyond the item's last page)
+        14-15 0
+    """
+    n = len(items)
+    order = range(n) if order is None else [int(i) for i in order]
+    rec = np.zeros((len(order), RECORD_WORDS), dtype=np.int32)
+    for k, i in enumerate(order):
+        r, h, tb, te, pair, c, q_row, part_row = (int(x) for x in items[i])
+        first_page = int(page_indptr[pair]) + tb // page_tokens
+        n_pages = -(-(te - tb) // page_tokens)
+        rec[k, 0:2] = np.array([first_page], dtype=np.int64).view(np.int32)
+        rec[k, 2] = te - tb
+        rec[k, 3] = q_row
+        single = int(chunk_indptr[pair + 1]) - int(chunk_indptr[pair]) == 1
+        rec[k, 4] = -(pair * group) - 1 if (direct_rows and single) else part_row
+        for j in range(min(8, n_pages)):
+            rec[k, 6 + j] = int(page_ids[first_page + j])
+    return rec

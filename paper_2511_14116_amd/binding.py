@@ -37,6 +37,8 @@ class FsKvView(C.Structure):
 ITEM_DTYPE = np.dtype([(n, np.int32) for n in
                        ("req", "kv_head", "tok_begin", "tok_end", "pair", "chunk", "q_row", "part_row")])
 PAIR_DTYPE = np.dtype([(n, np.int32) for n in ("req", "kv_head", "ctx_len", "n_chunks")])
+RECORD_DTYPE = np.dtype([("first_page", np.int64), ("n_tok", np.int32), ("q_row", np.int32), ("row", np.int32),
+                         ("reserved0", np.int32), ("first_slots", np.int32, (8,)), ("reserved1", np.int32, (2,))])
 PREFILL_ENTRY_DTYPE = np.dtype([(n, np.int32) for n in ("req", "rank", "n_done", "n_new")])
 PREFILL_ITEM_DTYPE = np.dtype([(n, np.int32) for n in
                                ("pair", "q_begin", "q_end", "n_done", "kv_begin", "kv_end", "q_row", "part_row")])
@@ -81,6 +83,13 @@ def load_library(path: str | None = None):
                                               C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_decode_attention_units.restype = C.c_int
+    lib.fs_build_launch_records.argtypes = [C.POINTER(FsShape), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                            C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+    lib.fs_build_launch_records.restype = C.c_int
+    lib.fs_decode_attention_records.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_int64,
+                                                C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fs_decode_attention_records.restype = C.c_int
     lib.fs_choose_chunk_tokens.argtypes = [C.POINTER(FsShape), i32p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                            i32p, i64p]
     lib.fs_choose_chunk_tokens.restype = C.c_int
@@ -259,6 +268,30 @@ def fs_build_worklist_units(shape: FsShape, ctx_len, owner, rank: int, n_units: 
     _check(lib.fs_build_worklist_units(*args, items.ctypes.data, len(items), pairs.ctypes.data, len(pairs),
                                        unit_indptr.ctypes.data, n_u.value, chunk_indptr.ctypes.data, *counts))
     return items, pairs, unit_indptr, chunk_indptr
+
+
+def fs_build_launch_records(shape: FsShape, items, order, chunk_indptr, page_indptr, page_ids, direct_rows: bool = True,
+                            out=None):
+    """-> records [n_items] RECORD_DTYPE: record k describes item order[k] (order None: item k).  ``out``: a
+    preallocated RECORD_DTYPE array (e.g. a view of pinned memory) to fill instead."""
+    lib = load_library()
+    it = np.ascontiguousarray(items)
+    if it.dtype != ITEM_DTYPE:
+        raise TypeError("items must be an ITEM_DTYPE array")
+    od = None if order is None else _host(order, np.int32)
+    ci, pi, ids = _host(chunk_indptr, np.int64), _host(page_indptr, np.int64), _host(page_ids, np.int32)
+    if od is not None and len(od) != len(it):
+        raise ValueError("order must have one entry per item")
+    if len(pi) != len(ci):
+        raise ValueError("chunk_indptr and page_indptr must both have n_pairs+1 entries")
+    rec = np.zeros(len(it), dtype=RECORD_DTYPE) if out is None else out
+    if rec.dtype != RECORD_DTYPE or len(rec) < len(it):
+        raise TypeError("out must be a RECORD_DTYPE array with room for every item")
+    st = lib.fs_build_launch_records(C.byref(shape), it.ctypes.data, None if od is None else od.ctypes.data, len(it),
+                                     ci.ctypes.data, len(ci) - 1, pi.ctypes.data, ids.ctypes.data, len(ids),
+                                     int(bool(direct_rows)), rec.ctypes.data)
+    _check(st)
+    return rec[:len(it)]
 
 
 def fs_choose_chunk_tokens(shape: FsShape, ctx_len, owner, rank: int, max_chunk: int, min_chunk: int,
@@ -470,6 +503,14 @@ def fs_decode_attention_units(shape: FsShape, kv: FsKvView, items_dev, n_items: 
     _check(st)
 
 
+def fs_decode_attention_records(shape: FsShape, kv: FsKvView, records_dev, n_items: int, unit_indptr_dev, n_units: int,
+                                chunk_indptr_dev, n_pairs: int, part_o, part_lse, out, lse, stream=None) -> None:
+    st = load_library().fs_decode_attention_records(C.byref(shape), C.byref(kv), _ptr(records_dev), n_items,
+                                                    _ptr(unit_indptr_dev), n_units, _ptr(chunk_indptr_dev), n_pairs,
+                                                    _ptr(part_o), _ptr(part_lse), _ptr(out), _ptr(lse), _ptr(stream))
+    _check(st)
+
+
 def fs_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,
                  out, lse, stream=None) -> None:
     st = load_library().fs_merge_lse(_ptr(part_o), _ptr(part_lse), _ptr(chunk_indptr_dev), n_pairs, group,
@@ -630,6 +671,30 @@ def bind_decode_attention_units(shape: FsShape, kv: FsKvView, items_dev, n_items
             _vp(chunk_indptr_dev), C.c_int64(n_pairs), _vp(part_o), _vp(part_lse), _vp(out), _vp(lse), _vp(stream))
     return BoundCall(lib.fs_decode_attention_units, args,
                      (shape, kv, items_dev, unit_indptr_dev, chunk_indptr_dev, part_o, part_lse, out, lse))
+
+
+def bind_build_launch_records(shape: FsShape, items: np.ndarray, order, chunk_indptr: np.ndarray, n_pairs: int,
+                              page_indptr: np.ndarray, page_ids: np.ndarray, records: np.ndarray,
+                              direct_rows: bool = True) -> BoundCall:
+    """fs_build_launch_records on caller-held arrays (items and records e.g. views of pinned memory); reads all of
+    ``items`` (its length is the item count)."""
+    lib = load_library()
+    if items.dtype != ITEM_DTYPE or records.dtype != RECORD_DTYPE or len(records) < len(items):
+        raise TypeError("bind_build_launch_records: items / records do not match the documented layouts")
+    args = (C.byref(shape), C.c_void_p(items.ctypes.data), None if order is None else C.c_void_p(order.ctypes.data),
+            C.c_int64(len(items)), C.c_void_p(chunk_indptr.ctypes.data), C.c_int64(n_pairs),
+            C.c_void_p(page_indptr.ctypes.data), C.c_void_p(page_ids.ctypes.data), C.c_int64(len(page_ids)),
+            C.c_int32(int(bool(direct_rows))), C.c_void_p(records.ctypes.data))
+    return BoundCall(lib.fs_build_launch_records, args, (shape, items, order, chunk_indptr, page_indptr, page_ids, records))
+
+
+def bind_decode_attention_records(shape: FsShape, kv: FsKvView, records_dev, n_items: int, unit_indptr_dev, n_units: int,
+                                  chunk_indptr_dev, n_pairs: int, part_o, part_lse, out, lse, stream=None) -> BoundCall:
+    lib = load_library()
+    args = (C.byref(shape), C.byref(kv), _vp(records_dev), C.c_int64(n_items), _vp(unit_indptr_dev), C.c_int64(n_units),
+            _vp(chunk_indptr_dev), C.c_int64(n_pairs), _vp(part_o), _vp(part_lse), _vp(out), _vp(lse), _vp(stream))
+    return BoundCall(lib.fs_decode_attention_records, args,
+                     (shape, kv, records_dev, unit_indptr_dev, chunk_indptr_dev, part_o, part_lse, out, lse))
 
 
 def bind_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,

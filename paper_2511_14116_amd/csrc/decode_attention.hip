@@ -53,6 +53,10 @@ struct DecodeParams {
   const int32_t* __restrict__ page_ids;
   const fs_work_item* __restrict__ items;
   const int32_t* __restrict__ sched;
+  // Instead of items + sched: one record per item in launch order with everything already looked up
+  // (fs_build_launch_records); NULL: the kernels look an item up themselves (list entry, item, page-table
+  // offset, chunk count - four dependent reads before the first page can be asked for).
+  const fs_launch_record* __restrict__ records;
   float* __restrict__ part_o;
   float* __restrict__ part_lse;
   // Fused form only (else NULL): a pair that is a single item writes its rows straight to the final
@@ -172,19 +176,114 @@ __device__ __forceinline__ void consume_page(SoftmaxState& st, PageRegs& pg, con
   }
 }
 
-// Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.
-// Where an item's G rows go: its partial rows, or - in the fused form, when the item is all of its pair -
-// the pair's final rows.
+// The page table is read-only for the whole launch, but the kernels also write to global memory, so the
+// compiler does not take its word for that and would fetch the page ids with vector loads, which queue up
+// behind the page loads.  Reading them through the constant address space keeps them on the scalar path.
+typedef const int32_t __attribute__((address_space(4))) * const_ids_ptr;
+
+// What a wavefront needs to know of an item.  The item's pages are dealt to the workgroup's wavefronts in
+// turn: wavefront w of W takes pages w, w + W, w + 2W, ... of the item, `n_mine` of them.
+struct ItemDesc {
+  const_ids_ptr ids;    // page ids of the item's first page onwards
+  int32_t page_lo, page_hi;   // position of the item's first page in the whole page table (fp8 scales in page order)
+  int n_tok;            // tokens of the item
+  int n_mine;           // pages of the item this wavefront takes
+  int row;              // first partial row of the item, or -(first final row) - 1 when the item is all of its pair (one-call forms)
+  int q_row;            // first query row of the item's group
+  int32_t first_ids[3]; // slots of this wavefront's first pages (those the prologue fetches), asked for with the rest
+  bf16x8 q[4];          // Q^T operand of this lane (load_desc_q; bf16 kernels)
+  bool valid;
+};
+
+// The scalar part of the descriptor of the item at launch position k: everything but the query rows.  All of
+// it stays in scalar registers.  With launch records that is one 64-byte read (and the first slots come out of
+// the same record, asked for at the same time); without, the list entry, the item, the page-table offset and
+// chunk count, and the page ids are read one after the other.
+template <int WAVES, int NBUF>
+__device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k, int n_items, int wave, int G) {
+  static_assert(NBUF - 1 <= 3, "first_ids holds three slots");
+  ItemDesc d;
+  d.valid = k < n_items;
+  d.ids = (const_ids_ptr)(uintptr_t)0;
+  d.page_lo = d.page_hi = 0;
+  d.n_tok = 0;
+  d.n_mine = 0;
+  d.row = 0;
+  d.q_row = 0;
+#pragma unroll
+  for (int u = 0; u < 3; ++u) d.first_ids[u] = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) d.q[c] = bf16x8{};
+  if (d.valid) {
+    int64_t first_page;
+    int32_t rec_slot[3] = {0, 0, 0};
+    if (P.records) {
+      // k is the same in every lane (it may come from LDS, which the compiler cannot see): saying so keeps
+      // the descriptor and, above all, the page ids on the scalar path
+      const fs_launch_record* rec = P.records + __builtin_amdgcn_readfirstlane(k);
+      first_page = rec->first_page;
+      d.n_tok = __builtin_amdgcn_readfirstlane(rec->n_tok);
+      d.q_row = __builtin_amdgcn_readfirstlane(rec->q_row);
+      d.row = __builtin_amdgcn_readfirstlane(rec->row);
+#pragma unroll
+      for (int u = 0; u < NBUF - 1; ++u)           // the record holds the item's first eight slots
+        if (wave + u * WAVES < 8) rec_slot[u] = __builtin_amdgcn_readfirstlane(rec->first_slots[wave + u * WAVES]);
+    } else {
+      const int item_idx = __builtin_amdgcn_readfirstlane(P.sched ? P.sched[k] : k);
+      fs_work_item it = P.items[item_idx];
+      it.pair = __builtin_amdgcn_readfirstlane(it.pair);
+      it.tok_begin = __builtin_amdgcn_readfirstlane(it.tok_begin);
+      it.tok_end = __builtin_amdgcn_readfirstlane(it.tok_end);
+      d.n_tok = it.tok_end - it.tok_begin;
+      d.q_row = __builtin_amdgcn_readfirstlane(it.q_row);
+      d.row = __builtin_amdgcn_readfirstlane(it.part_row);
+      first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+      if (P.chunk_indptr) {
+        const int32_t n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - P.chunk_indptr[it.pair]));
+        if (n_chunks == 1) d.row = -(it.pair * G) - 1;
+      }
+    }
+    d.page_lo = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page));
+    d.page_hi = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page >> 32));
+    d.ids = (const_ids_ptr)(reinterpret_cast<uintptr_t>(P.page_ids + ((static_cast<int64_t>(d.page_hi) << 32) | static_cast<uint32_t>(d.page_lo))));
+    const int n_pages = (d.n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
+    d.n_mine = n_pages > wave ? (n_pages - wave + WAVES - 1) / WAVES : 0;
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) {
+      if (u < d.n_mine) d.first_ids[u] = (P.records && wave + u * WAVES < 8) ? rec_slot[u] : d.ids[wave + u * WAVES];
+    }
+  }
+  return d;
+}
+
+// The query rows of the item, as the Q^T operand of this lane: lane (q = lane%16, kb = lane/16) holds
+// Q[q][32c + 8kb .. +8) for c = 0..3; rows beyond the group are zero (read from a row that exists, then blanked).
+__device__ __forceinline__ void load_desc_q(ItemDesc& d, const DecodeParams& P, int lane, int G) {
+  if (d.valid) {
+    const int qi = lane & 15, kb = lane >> 4;
+    const int qrow = d.q_row + min(qi, G - 1);
+    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      u32x4 v = qp[4 * c];
+      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
+      d.q[c] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+}
+
+// Where an item's G rows go, from the descriptor's row.
 struct RowDest {
   float* o;
   float* lse;
   int row;
 };
-__device__ __forceinline__ RowDest row_dest(const DecodeParams& P, int pair, int part_row) {
-  if (P.chunk_indptr && P.chunk_indptr[pair + 1] - P.chunk_indptr[pair] == 1) return RowDest{P.out, P.lse, pair * P.group};
-  return RowDest{P.part_o, P.part_lse, part_row};
+__device__ __forceinline__ RowDest row_dest(const DecodeParams& P, int row) {
+  if (row < 0) return RowDest{P.out, P.lse, -row - 1};
+  return RowDest{P.part_o, P.part_lse, row};
 }
 
+// Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.
 template <int WAVES>
 __device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_total, int wave, int lane,
                                                 int G, float* __restrict__ part_o,
@@ -226,34 +325,12 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
   __shared__ float sm_m[WAVES * 16];
   __shared__ float sm_l[WAVES * 16];
 
-  const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
-  const fs_work_item it = P.items[item_idx];
-  const RowDest dst = row_dest(P, it.pair, it.part_row);   // asked for now, needed when the item ends
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qi = lane & 15, kb = lane >> 4;
+  const int kb = lane >> 4;
   const int G = P.group;
-
-  const int n_tok = it.tok_end - it.tok_begin;
-  const int n_pages = (n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
-  const int32_t* __restrict__ ids = P.page_ids + P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
-  const int per = (n_pages + WAVES - 1) / WAVES;
-  const int p0 = wave * per;
-  const int p1 = min(n_pages, p0 + per);
-
-  // Q^T as the B operand: lane (q = lane%16, kb = lane/16) holds Q[q][32c + 8kb .. +8) for c = 0..3.
-  bf16x8 qreg[4];
-  {
-    // rows beyond the group are zero; they are read from a row that exists and then blanked
-    const int qrow = it.q_row + min(qi, G - 1);
-    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      u32x4 v = qp[4 * c];
-      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
-      qreg[c] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
+  ItemDesc d = load_desc_head<WAVES, NBUF>(P, static_cast<int>(blockIdx.x), 0x7FFFFFFF, wave, G);
+  load_desc_q(d, P, lane, G);
 
   SoftmaxState st;
   st.m = -INFINITY;
@@ -264,30 +341,32 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
   // NBUF register buffers; NBUF-1 pages are in flight while one is consumed.  The steady-state
   // loop is branch-free (every prefetch is in range, every page is full), so the loads of
   // pages i+1.. stay outstanding while page i is consumed; the ragged end is a second loop.
+  // Index i counts this wavefront's pages; its i-th page is page wave + i*WAVES of the item.
   PageRegs buf[NBUF];
 #pragma unroll
   for (int u = 0; u < NBUF - 1; ++u)
-    if (p0 + u < p1) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, ids[p0 + u], lane);
+    if (u < d.n_mine) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.first_ids[u], lane);
 
-  int i = p0;
-  for (; i + 2 * NBUF - 2 < p1; i += NBUF) {
+  int i = 0;
+  for (; i + 2 * NBUF - 2 < d.n_mine; i += NBUF) {
 #pragma unroll
     for (int u = 0; u < NBUF; ++u) {
-      load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, ids[i + u + NBUF - 1], lane);
-      consume_page<true>(st, buf[u], qreg, P.scale_log2, fs::kPageTokens, kb);
+      load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.ids[wave + (i + u + NBUF - 1) * WAVES], lane);
+      consume_page<true>(st, buf[u], d.q, P.scale_log2, fs::kPageTokens, kb);
     }
   }
-  // here pages i .. i+NBUF-2 (those below p1) are in flight in buf[0 .. NBUF-2]
+  // here pages i .. i+NBUF-2 (those below n_mine) are in flight in buf[0 .. NBUF-2]
 #pragma unroll
   for (int u = 0; u < 2 * NBUF - 2; ++u) {
     const int pi = i + u;
-    if (pi < p1) {
+    if (pi < d.n_mine) {
       const int pn = pi + NBUF - 1;
-      if (pn < p1) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, ids[pn], lane);
-      consume_page<false>(st, buf[u % NBUF], qreg, P.scale_log2, min(fs::kPageTokens, n_tok - pi * fs::kPageTokens), kb);
+      if (pn < d.n_mine) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.ids[wave + pn * WAVES], lane);
+      consume_page<false>(st, buf[u % NBUF], d.q, P.scale_log2, min(fs::kPageTokens, d.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
     }
   }
 
+  const RowDest dst = row_dest(P, d.row);
   const float l_total = sum_xor32(sum_xor16(st.l));
   merge_and_store<WAVES>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l);
 }
@@ -311,86 +390,6 @@ constexpr int kSecondShare = 4;   // a CU's second workgroup claims only within 
 
 __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// The page table is read-only for the whole launch, but the persistent kernel also writes to global
-// memory inside its item loop, so the compiler no longer takes its word for that and would fetch the
-// page ids with vector loads, which queue up behind the page loads.  Reading them through the
-// constant address space keeps them on the scalar path.
-typedef const int32_t __attribute__((address_space(4))) * const_ids_ptr;
-
-struct ItemDesc {
-  const_ids_ptr ids;    // page ids of the item's first page onwards
-  int n_tok;            // tokens of the item
-  int p0, p1;           // this wavefront's pages [p0, p1) of the item
-  int row;              // first partial row of the item, or -(first final row) - 1 when the item is all of its pair (fused form)
-  int q_row;            // first query row of the item's group
-  int32_t first_ids[3]; // slots of this wavefront's first pages (those the prologue fetches), asked for with the rest
-  bf16x8 q[4];          // Q^T operand of this lane (load_desc_q)
-  bool valid;
-};
-
-// The scalar part of item k's descriptor: everything but the query rows.  All of it stays in scalar registers.
-template <int WAVES, int NBUF>
-__device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k, int n_items, int wave, int G) {
-  static_assert(NBUF - 1 <= 3, "first_ids holds three slots");
-  ItemDesc d;
-  d.valid = k < n_items;
-  d.ids = (const_ids_ptr)(uintptr_t)0;
-  d.n_tok = 0;
-  d.p0 = d.p1 = 0;
-  d.row = 0;
-  d.q_row = 0;
-#pragma unroll
-  for (int u = 0; u < 3; ++u) d.first_ids[u] = 0;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) d.q[c] = bf16x8{};
-  if (d.valid) {
-    // k is the same in every lane (it comes from LDS, which the compiler cannot see): saying so keeps the
-    // descriptor and, above all, the page ids on the scalar path, where their loads do not queue up behind
-    // the page loads
-    const int item_idx = __builtin_amdgcn_readfirstlane(P.sched ? P.sched[k] : k);
-    fs_work_item it = P.items[item_idx];
-    it.pair = __builtin_amdgcn_readfirstlane(it.pair);
-    it.tok_begin = __builtin_amdgcn_readfirstlane(it.tok_begin);
-    it.tok_end = __builtin_amdgcn_readfirstlane(it.tok_end);
-    it.q_row = __builtin_amdgcn_readfirstlane(it.q_row);
-    it.part_row = __builtin_amdgcn_readfirstlane(it.part_row);
-    d.n_tok = it.tok_end - it.tok_begin;
-    const int n_pages = (d.n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
-    const int64_t first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
-    const int32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page));
-    const int32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page >> 32));
-    d.ids = (const_ids_ptr)(reinterpret_cast<uintptr_t>(P.page_ids + ((static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo))));
-    const int per = (n_pages + WAVES - 1) / WAVES;
-    d.p0 = wave * per;
-    d.p1 = min(n_pages, d.p0 + per);
-#pragma unroll
-    for (int u = 0; u < NBUF - 1; ++u)
-      if (d.p0 + u < d.p1) d.first_ids[u] = d.ids[d.p0 + u];
-    d.row = it.part_row;
-    d.q_row = it.q_row;
-    if (P.chunk_indptr) {
-      const int32_t n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - P.chunk_indptr[it.pair]));
-      if (n_chunks == 1) d.row = -(it.pair * G) - 1;
-    }
-  }
-  return d;
-}
-
-// The query rows of the item, as the Q^T operand of this lane.
-__device__ __forceinline__ void load_desc_q(ItemDesc& d, const DecodeParams& P, int lane, int G) {
-  if (d.valid) {
-    const int qi = lane & 15, kb = lane >> 4;
-    const int qrow = d.q_row + min(qi, G - 1);
-    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      u32x4 v = qp[4 * c];
-      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
-      d.q[c] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
 }
 
 // UNITS = true is the form without a counter: workgroup u walks the items [unit_indptr[u], unit_indptr[u+1]) of a
@@ -426,7 +425,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
   auto prologue = [&](const ItemDesc& d) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < NBUF - 1; ++u)
-      if (d.p0 + u < d.p1) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.first_ids[u], lane);
+      if (u < d.n_mine) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.first_ids[u], lane);
   };
   prologue(cur);
 
@@ -456,21 +455,21 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
     st.l = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    int i = cur.p0;
-    for (; i + 2 * NBUF - 2 < cur.p1; i += NBUF) {
+    int i = 0;          // counts this wavefront's pages of the item: its i-th page is page wave + i*WAVES
+    for (; i + 2 * NBUF - 2 < cur.n_mine; i += NBUF) {
 #pragma unroll
       for (int u = 0; u < NBUF; ++u) {
-        load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[i + u + NBUF - 1], lane);
+        load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[wave + (i + u + NBUF - 1) * WAVES], lane);
         consume_page<true>(st, buf[u], cur.q, P.scale_log2, fs::kPageTokens, kb);
       }
     }
 #pragma unroll
     for (int u = 0; u < 2 * NBUF - 2; ++u) {
       const int pi = i + u;
-      if (pi < cur.p1) {
+      if (pi < cur.n_mine) {
         const int pn = pi + NBUF - 1;
-        if (pn < cur.p1) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[pn], lane);
-        consume_page<false>(st, buf[u % NBUF], cur.q, P.scale_log2, min(fs::kPageTokens, cur.n_tok - pi * fs::kPageTokens), kb);
+        if (pn < cur.n_mine) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[wave + pn * WAVES], lane);
+        consume_page<false>(st, buf[u % NBUF], cur.q, P.scale_log2, min(fs::kPageTokens, cur.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
       }
     }
     // merge the wavefronts through LDS into the staging rows
@@ -616,28 +615,20 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
   __shared__ float sm_m[WAVES * 8 * GMAX];
   __shared__ float sm_l[WAVES * 8 * GMAX];
 
-  const int item_idx = P.sched ? P.sched[blockIdx.x] : static_cast<int>(blockIdx.x);
-  const fs_work_item it = P.items[item_idx];
-  const RowDest dst = row_dest(P, it.pair, it.part_row);   // asked for now, needed when the item ends
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 7, ts = lane >> 3;
   const int G = P.group;
-
-  const int n_tok = it.tok_end - it.tok_begin;
-  const int n_pages = (n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
-  const int64_t first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
-  const int32_t* __restrict__ ids = P.page_ids + first_page;
-  const int per = (n_pages + WAVES - 1) / WAVES;
-  const int p0 = wave * per;
-  const int p1 = min(n_pages, p0 + per);
+  const ItemDesc d = load_desc_head<WAVES, NBUF>(P, static_cast<int>(blockIdx.x), 0x7FFFFFFF, wave, G);
+  const int n_tok = d.n_tok;
+  const int64_t first_page = (static_cast<int64_t>(d.page_hi) << 32) | static_cast<uint32_t>(d.page_lo);
 
   // this lane's 16 d of every q row, pre-multiplied by the softmax scale (fp32)
   float qf[GMAX][16];
 #pragma unroll
   for (int g = 0; g < GMAX; ++g) {
     if (g < G) {
-      const uint4* qp = reinterpret_cast<const uint4*>(P.q + static_cast<int64_t>(it.q_row + g) * fs::kHeadDim + 16 * c);
+      const uint4* qp = reinterpret_cast<const uint4*>(P.q + static_cast<int64_t>(d.q_row + g) * fs::kHeadDim + 16 * c);
       const uint4 a = qp[0], b = qp[1];
       const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
@@ -707,27 +698,29 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
 
   // NBUF register buffers; NBUF-1 pages are in flight while one is consumed.  The steady-state loop is
   // branch-free (every prefetch is in range, every page is full); the ragged end is a second loop.
+  // Index i counts this wavefront's pages; its i-th page is page wave + i*WAVES of the item.
   Fp8Page buf[NBUF];
 #pragma unroll
   for (int u = 0; u < NBUF - 1; ++u)
-    if (p0 + u < p1) load_page_fp8(buf[u], P, ids[p0 + u], first_page + p0 + u, lane);
+    if (u < d.n_mine) load_page_fp8(buf[u], P, d.first_ids[u], first_page + wave + u * WAVES, lane);
 
-  int i = p0;
-  for (; i + 2 * NBUF - 2 < p1; i += NBUF) {
+  int i = 0;
+  for (; i + 2 * NBUF - 2 < d.n_mine; i += NBUF) {
 #pragma unroll
     for (int u = 0; u < NBUF; ++u) {
-      load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[i + u + NBUF - 1], first_page + i + u + NBUF - 1, lane);
+      const int pg = wave + (i + u + NBUF - 1) * WAVES;
+      load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, d.ids[pg], first_page + pg, lane);
       consume(buf[u], fs::kPageTokens, std::true_type{});
     }
   }
-  // here pages i .. i+NBUF-2 (those below p1) are in flight in buf[0 .. NBUF-2]
+  // here pages i .. i+NBUF-2 (those below n_mine) are in flight in buf[0 .. NBUF-2]
 #pragma unroll
   for (int u = 0; u < 2 * NBUF - 2; ++u) {
     const int pi = i + u;
-    if (pi < p1) {
+    if (pi < d.n_mine) {
       const int pn = pi + NBUF - 1;
-      if (pn < p1) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, ids[pn], first_page + pn, lane);
-      consume(buf[u % NBUF], min(fs::kPageTokens, n_tok - pi * fs::kPageTokens), std::false_type{});
+      if (pn < d.n_mine) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, d.ids[wave + pn * WAVES], first_page + wave + pn * WAVES, lane);
+      consume(buf[u % NBUF], min(fs::kPageTokens, n_tok - (wave + pi * WAVES) * fs::kPageTokens), std::false_type{});
     }
   }
 
@@ -744,6 +737,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
     }
   }
   __syncthreads();
+  const RowDest dst = row_dest(P, d.row);
   for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
     const int g = idx >> 5, d4 = idx & 31;
     float M = -INFINITY;
@@ -794,7 +788,7 @@ __global__ void zero_counters_kernel(int* __restrict__ claim) {
 
 // Argument checks shared by the entry points.  `who` names the call in messages.  On FS_OK with
 // n_items > 0, *P is ready for a launch (the fused fields are left NULL).
-fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, const fs_work_item* items_dev,
+fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, const void* items_dev,
                   const int32_t* sched_dev, int64_t n_items, float* part_o, float* part_lse, bool partials_needed,
                   bool bf16_only, DecodeParams* P) {
   if (!shape || !kv) return fs::fail(FS_EINVAL, "%s: shape or kv is NULL", who);
@@ -838,8 +832,9 @@ fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, 
   P->scale_by_page = kv->page_scales ? 1 : 0;
   P->page_indptr = kv->page_indptr;
   P->page_ids = kv->page_ids;
-  P->items = items_dev;
+  P->items = static_cast<const fs_work_item*>(items_dev);   // the records call puts its list into P->records afterwards
   P->sched = sched_dev;
+  P->records = nullptr;
   P->part_o = part_o;
   P->part_lse = part_lse;
   P->chunk_indptr = nullptr;
@@ -999,6 +994,45 @@ extern "C" fs_status fs_decode_attention_units(const fs_shape* shape, const fs_k
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
   if (partials_only || n_items == n_pairs) return FS_OK;
+  return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
+}
+
+extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs_kv_view* kv,
+                                                 const fs_launch_record* records_dev, int64_t n_items,
+                                                 const int64_t* unit_indptr_dev, int64_t n_units,
+                                                 const int64_t* chunk_indptr_dev, int64_t n_pairs,
+                                                 float* part_o, float* part_lse, float* out, float* lse, void* stream) {
+  const char* who = "fs_decode_attention_records";
+  const bool sweep_only = chunk_indptr_dev == nullptr;     // no merge: the rows go where the records say
+  if (!sweep_only && (n_pairs < 0 || n_pairs > n_items))
+    return fs::fail(FS_EINVAL, "%s: n_pairs %lld outside [0, n_items]", who, static_cast<long long>(n_pairs));
+  const bool units = unit_indptr_dev != nullptr;
+  if (units && (n_units < 0 || n_units > n_items))
+    return fs::fail(FS_EINVAL, "%s: n_units %lld outside [0, n_items]", who, static_cast<long long>(n_units));
+  const bool split = sweep_only || n_items > n_pairs;
+  DecodeParams P;
+  if (const fs_status st = prepare(who, shape, kv, records_dev, nullptr, n_items, part_o, part_lse, split, units, &P);
+      st != FS_OK || n_items == 0)
+    return st;
+  if ((!sweep_only && n_pairs == 0) || (units && n_units == 0))
+    return fs::fail(FS_EINVAL, "%s: %lld items but no pairs or no units", who, static_cast<long long>(n_items));
+  if (!out || !lse || (reinterpret_cast<uintptr_t>(out) & 15) || (reinterpret_cast<uintptr_t>(records_dev) & 7))
+    return fs::fail(FS_EINVAL, "%s: out or lse is NULL, out is not 16-byte or records_dev not 8-byte aligned", who);
+  P.items = nullptr;
+  P.records = records_dev;
+  P.out = out;
+  P.lse = lse;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  fs_status st = FS_OK;
+  if (units) {
+    hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, true>), dim3(static_cast<unsigned>(n_units)), dim3(256), 0, s, P,
+                       static_cast<int>(n_items), static_cast<int*>(nullptr), 0, unit_indptr_dev);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) st = fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+  } else {
+    st = launch_plain(who, P, kv->kv_dtype, n_items, s);
+  }
+  if (st != FS_OK || sweep_only || n_items == n_pairs) return st;
   return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
 }
 

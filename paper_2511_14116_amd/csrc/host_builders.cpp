@@ -348,6 +348,46 @@ extern "C" fs_status fs_build_worklist_units(const fs_shape* shape, const int32_
   return FS_OK;
 }
 
+extern "C" fs_status fs_build_launch_records(const fs_shape* shape, const fs_work_item* items, const int32_t* order,
+                                             int64_t n_items, const int64_t* chunk_indptr, int64_t n_pairs,
+                                             const int64_t* page_indptr, const int32_t* page_ids, int64_t n_page_ids,
+                                             int32_t direct_rows, fs_launch_record* records) {
+  const char* who = "fs_build_launch_records";
+  if (fs_status st = check_shape(shape, who)) return st;
+  const int32_t H = shape->n_kv_heads, T = shape->page_tokens;
+  if (T < 1 || shape->n_q_heads < H || shape->n_q_heads % H)
+    return fs::fail(FS_EINVAL, "%s: bad page_tokens %d or head counts %d/%d", who, T, shape->n_q_heads, H);
+  if (n_items < 0 || n_pairs < 0 || n_page_ids < 0) return fs::fail(FS_EINVAL, "%s: negative count", who);
+  if (n_items == 0) return FS_OK;
+  if (!items || !chunk_indptr || !page_indptr || !page_ids || !records)
+    return fs::fail(FS_EINVAL, "%s: NULL pointer", who);
+  const int32_t G = shape->n_q_heads / H;
+  for (int64_t k = 0; k < n_items; ++k) {
+    const int64_t i = order ? order[k] : k;
+    if (i < 0 || i >= n_items) return fs::fail(FS_EINVAL, "%s: order[%lld] = %lld outside [0, %lld)", who,
+                                               static_cast<long long>(k), static_cast<long long>(i), static_cast<long long>(n_items));
+    const fs_work_item& it = items[i];
+    if (it.pair < 0 || it.pair >= n_pairs || it.tok_begin < 0 || it.tok_end <= it.tok_begin || it.tok_begin % T)
+      return fs::fail(FS_EINVAL, "%s: item %lld is malformed (pair %d, tokens [%d, %d))", who, static_cast<long long>(i),
+                      it.pair, it.tok_begin, it.tok_end);
+    const int64_t first_page = page_indptr[it.pair] + it.tok_begin / T;
+    const int64_t n_pages = (static_cast<int64_t>(it.tok_end) - it.tok_begin + T - 1) / T;
+    if (first_page < 0 || first_page + n_pages > page_indptr[it.pair + 1] || page_indptr[it.pair + 1] > n_page_ids)
+      return fs::fail(FS_EINVAL, "%s: item %lld's pages [%lld, %lld) leave its pair's part of the page table", who,
+                      static_cast<long long>(i), static_cast<long long>(first_page), static_cast<long long>(first_page + n_pages));
+    fs_launch_record& r = records[k];
+    r.first_page = first_page;
+    r.n_tok = it.tok_end - it.tok_begin;
+    r.q_row = it.q_row;
+    const bool single = chunk_indptr[it.pair + 1] - chunk_indptr[it.pair] == 1;
+    r.row = (direct_rows && single) ? -(it.pair * G) - 1 : it.part_row;
+    r.reserved0 = 0;
+    for (int j = 0; j < 8; ++j) r.first_slots[j] = j < n_pages ? page_ids[first_page + j] : 0;
+    r.reserved1[0] = r.reserved1[1] = 0;
+  }
+  return FS_OK;
+}
+
 extern "C" int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, int32_t d) {
   if (tok < 0 || tok >= fs::kPageTokens || d < 0 || d >= fs::kHeadDim) return -1;
   if (kv_dtype == FS_KV_FP8_E4M3) return tok * fs::kHeadDim + d;

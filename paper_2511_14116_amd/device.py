@@ -88,6 +88,18 @@ class DeviceShare:
                                     self.chunk_indptr, self.n_pairs, self.part_o, self.part_lse, self.out, self.lse,
                                     torch.cuda.current_stream().cuda_stream)
 
+    def set_records(self, records: np.ndarray):
+        """Upload launch records of the list that set_worklist / set_worklist_units brought."""
+        assert len(records) == self.n_items
+        self.records = torch.from_numpy(np.ascontiguousarray(records).view(np.int32).reshape(-1, 16)).to(self.device)
+
+    def run_records(self, units: bool = False):
+        """Sweep and merge in one call from launch records (one workgroup per record, or per unit)."""
+        B.fs_decode_attention_records(self.shape, self.view, self.records, self.n_items,
+                                      self.unit_indptr if units else None, self.n_units if units else 0,
+                                      self.chunk_indptr, self.n_pairs, self.part_o, self.part_lse, self.out, self.lse,
+                                      torch.cuda.current_stream().cuda_stream)
+
     def decode(self, use_sched: bool = True):
         B.fs_decode_attention(self.shape, self.view, self.items, self.sched if use_sched else None,
                               self.n_items, self.part_o, self.part_lse, torch.cuda.current_stream().cuda_stream)

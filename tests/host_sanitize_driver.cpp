@@ -120,6 +120,22 @@ int main() {
       REQUIRE(items[chunk_indptr[p]].tok_begin == 0 && items[chunk_indptr[p + 1] - 1].tok_end == pairs[p].ctx_len);
       for (int64_t i = chunk_indptr[p] + 1; i < chunk_indptr[p + 1]; ++i) REQUIRE(items[i].tok_begin == items[i - 1].tok_end);
     }
+    {   // launch records of the same list: exactly-sized output, every record restates its item
+      std::vector<int64_t> page_indptr(np + 1, 0);
+      for (int64_t p = 0; p < np; ++p) page_indptr[p + 1] = page_indptr[p] + (pairs[p].ctx_len + 15) / 16;
+      std::vector<int32_t> page_ids(page_indptr[np]);
+      for (size_t j = 0; j < page_ids.size(); ++j) page_ids[j] = static_cast<int32_t>(1000 + j);
+      std::vector<fs_launch_record> rec(ni);
+      REQUIRE(fs_build_launch_records(&sh, items.data(), nullptr, ni, chunk_indptr.data(), np, page_indptr.data(),
+                                      page_ids.data(), static_cast<int64_t>(page_ids.size()), 1, rec.data()) == FS_OK);
+      for (int64_t i = 0; i < ni; ++i) {
+        REQUIRE(rec[i].n_tok == items[i].tok_end - items[i].tok_begin && rec[i].q_row == items[i].q_row);
+        REQUIRE(rec[i].first_page == page_indptr[items[i].pair] + items[i].tok_begin / 16);
+        REQUIRE(rec[i].first_slots[0] == 1000 + rec[i].first_page);
+        const bool single = chunk_indptr[items[i].pair + 1] - chunk_indptr[items[i].pair] == 1;
+        REQUIRE(rec[i].row == (single ? -(items[i].pair * G) - 1 : items[i].part_row));
+      }
+    }
     if (ni > 1) {
       std::vector<fs_work_item> small(ni - 1);
       REQUIRE(fs_build_worklist_units(&sh, ctx.data(), owner.data(), rank, n_units, small.data(), ni - 1, pairs.data(), np,

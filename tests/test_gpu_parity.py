@@ -337,6 +337,22 @@ def test_repeated_launches_agree_bit_for_bit(cfg_id):
             assert torch.equal(a, b), f"launch {rep} (persistent={persistent}): {name} differs from the first launch"
 
 
+def check_records(ds, kv, items, sched, indptr, what):
+    """fs_decode_attention_records (one workgroup per record, launch order) on the share that ``ds`` has just run
+    from items: the library's records equal the oracle's byte for byte, and the call leaves the same final rows."""
+    G = ds.group
+    rec = fs.fs_build_launch_records(ds.shape, items, sched, indptr, kv["page_indptr"], kv["page_ids"])
+    want = oracle.build_launch_records(items_rows(items), sched, indptr, kv["page_indptr"], kv["page_ids"], G)
+    assert rec.view(np.int32).reshape(-1, 16).tobytes() == want.tobytes(), f"{what}: launch records differ from the oracle's"
+    ref = [ds.out.clone(), ds.lse.clone()]
+    ds.set_records(rec)
+    for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
+        t.fill_(float("nan"))
+    ds.run_records()
+    torch.cuda.synchronize()
+    assert torch.equal(ds.out, ref[0]) and torch.equal(ds.lse, ref[1]), f"{what}: the records call leaves other final rows"
+
+
 def check_fused(ds, indptr, what):
     """fs_decode_attention_fused on the share that ``ds`` has just run the two-call way: the same final bits,
     the same partial rows for split pairs, no partial row written for a pair that is one item."""
@@ -401,6 +417,7 @@ def _full_config(cfg_id, rank, **req_kw):
             assert torch.equal(a, b), f"{what}: persistent sweep leaves other bits in {name}"
         assert ds.claim.cpu().tolist() == [0, 0]
     check_fused(ds, indptr, what)
+    check_records(ds, kv, items, sched, indptr, what)
     return ds
 
 
@@ -580,6 +597,7 @@ def test_fused_call_small_batches(cfg_id, kw, chunk):
             continue
         say(f"fused cfg{cfg_id} chunk {chunk} rank {rank}: {len(items)} items, {len(pairs)} pairs")
         check_fused(ds, indptr, f"fused cfg{cfg_id} chunk {chunk} rank {rank}")
+        check_records(ds, kv, items, sched, indptr, f"records cfg{cfg_id} chunk {chunk} rank {rank}")
         ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
         check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"fused cfg{cfg_id} chunk {chunk} rank {rank}")
         if len(items) == len(pairs):      # nothing is split: the call takes no partial buffers at all

@@ -56,8 +56,23 @@ def run_units(w, q, rank, n_units, owner, o_owner=None):
     kv = make_kv_pool(w["seed"], op[:, :2] if len(op) else np.zeros((0, 2)), w["ctx_len"])
     ds = DeviceShare(sh, q, kv, w["sm_scale"])
     ds.set_worklist_units(items, pairs, unit_indptr, chunk_indptr)
+    # from launch records first (item order, one workgroup per unit), then from the items: the same bits
+    rec = fs.fs_build_launch_records(sh, items, None, chunk_indptr, kv["page_indptr"], kv["page_ids"])
+    want = oracle.build_launch_records(oi, None, oc, kv["page_indptr"], kv["page_ids"], w["n_q_heads"] // w["n_kv_heads"])
+    assert rec.view(np.int32).reshape(-1, 16).tobytes() == want.tobytes()
+    if len(items):
+        ds.set_records(rec)
+        ds.run_records(units=True)
+        torch.cuda.synchronize()
+        from_records = [ds.out.clone(), ds.lse.clone(), ds.part_o.clone(), ds.part_lse.clone()]
+        for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
+            t.fill_(float("nan"))
     ds.run_units()
     torch.cuda.synchronize()
+    if len(items):
+        for a, b in zip(from_records, (ds.out, ds.lse, ds.part_o, ds.part_lse)):
+            assert torch.equal(a, b, ) or (torch.isnan(a) == torch.isnan(b)).all() and torch.equal(torch.nan_to_num(a), torch.nan_to_num(b)), \
+                "the records call and the items call differ"
     return ds, kv, op, oi, chunk_indptr
 
 

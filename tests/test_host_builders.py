@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
         header = f.read()
     declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
     assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_choose_chunk_tokens", "fs_decode_attention",
-            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_decode_attention_units", "fs_build_worklist_units", "fs_pack_kv_slots", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
+            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_decode_attention_units", "fs_build_worklist_units", "fs_build_launch_records", "fs_decode_attention_records", "fs_pack_kv_slots", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
             "fs_route_request", "fs_route_requests", "fs_schedule_prefill", "fs_plan_kv_reload", "fs_replace_failed_gpu", "fs_plan_ffn_reload", "fs_kv_elem_offset", "fs_stream_read_probe", "fs_set_option", "fs_get_option", "fs_last_error",
             "fs_abi_version"} <= declared
     lib = C.CDLL(fs.library_path())
@@ -133,6 +133,43 @@ def test_units_list_bit_exact_configs_and_random():
     assert st == fs.FS_ECAPACITY and (ni.value, npairs.value, nu.value) == (7, 4, 4)   # 10 pages in 4 runs of 2-3: three of the cuts fall inside a pair
 
 
+def test_launch_records_bit_exact_and_errors():
+    """fs_build_launch_records against the oracle's records, byte for byte, for chunked lists in launch order and
+    equal-run lists in item order; malformed inputs are refused."""
+    rng = np.random.default_rng(13)
+    assert fs.RECORD_DTYPE.itemsize == 64
+    for case in range(120):
+        R = int(rng.integers(1, 5)); H = int(rng.integers(1, 9)); G = int(rng.integers(1, 5)); B = int(rng.integers(1, 12))
+        ctx = rng.integers(1, int(rng.choice([20, 400, 3000])), size=B).astype(np.int32)
+        owner = rng.integers(0, R, size=(B, H)).astype(np.int32)
+        k = int(rng.integers(0, R))
+        sh = _shape(B, H * G, H, R)
+        if case % 2:
+            items, pairs, order, ci = fs.fs_build_worklist(sh, ctx, owner, k, int(rng.choice([0, 16, 64, 256])))
+        else:
+            items, pairs, _u, ci = fs.fs_build_worklist_units(sh, ctx, owner, k, int(rng.choice([1, 3, 9, 200])))
+            order = None
+        n_pages = -(-pairs["ctx_len"].astype(np.int64) // 16)
+        page_indptr = np.concatenate([[0], np.cumsum(n_pages)]).astype(np.int64)
+        total = int(page_indptr[-1])
+        page_ids = rng.permutation(total + 3)[:total].astype(np.int32)
+        for direct in (True, False):
+            rec = fs.fs_build_launch_records(sh, items, order, ci, page_indptr, page_ids, direct_rows=direct)
+            want = oracle.build_launch_records(_items_as_rows(items), order, ci, page_indptr, page_ids, G, direct_rows=direct)
+            assert rec.view(np.int32).reshape(-1, 16).tobytes() == want.tobytes()
+    # errors: an order entry out of range, a page table too short for the item
+    sh = _shape(2, 4, 2, 1)
+    ctx = np.array([40, 20], dtype=np.int32); owner = np.zeros((2, 2), dtype=np.int32)
+    items, pairs, sched, ci = fs.fs_build_worklist(sh, ctx, owner, 0, 16)
+    page_indptr = np.array([0, 3, 6, 8, 10], dtype=np.int64); page_ids = np.arange(10, dtype=np.int32)
+    fs.fs_build_launch_records(sh, items, sched, ci, page_indptr, page_ids)
+    bad_order = sched.copy(); bad_order[0] = len(items)
+    for args in ((bad_order, page_indptr, page_ids), (sched, page_indptr - np.array([0, 1, 1, 1, 1]), page_ids), (sched, page_indptr, page_ids[:9])):
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_build_launch_records(sh, items, args[0], ci, args[1], args[2])
+        assert e.value.status == fs.FS_EINVAL
+
+
 def test_sched_sort_fallback_path_matches():
     # few items with very different lengths take the comparison sort instead of the counting sort
     ctx = np.array([100000, 7, 100000, 50000], dtype=np.int32)
@@ -218,6 +255,11 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_units(sh, kv8, None, 3, None, 2, None, 2, None, None, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
+    fs.fs_decode_attention_records(sh, kv, None, 0, None, 0, None, 0, None, None, None, None)        # empty list: no-op
+    for n_items, n_units, n_pairs in ((3, 0, 4), (3, 0, 0), (3, 0, 2)):
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_decode_attention_records(sh, kv, None, n_items, None, n_units, None, n_pairs, None, None, None, None)
+        assert e.value.status == fs.FS_EINVAL
     fs.fs_pack_kv_slots(None, 4096, None, 4096, 0, fs.FS_KV_BF16, False)                            # no slots: no-op
     for args in ((None, 4096, None, 4096, 3, fs.FS_KV_BF16), (64, 4096, 8192, 100, 3, fs.FS_KV_BF16), (64, 4096, 8192, 4096, 3, 9)):
         with pytest.raises(fs.FsError) as e:

@@ -192,3 +192,61 @@ def test_units_against_a_page_by_page_partition(n_units):
             assert items[:, 7].tolist() == [i * G for i in range(len(items))]
             assert len(items) <= len(pairs) + max(U - 1, 0)       # a cut adds at most one item
         assert len(seen) == len(ctx) * H
+
+
+# ---- launch records -------------------------------------------------------------------------------------
+from oracle import build_launch_records
+
+
+def test_launch_records_by_hand():
+    # The hand-worked list of test_tiny_list_by_hand (rank 0, chunk 16): pairs (r0,h0) L=40 -> 3 pages at 0..2,
+    # (r1,h0) L=20 -> pages 3..4, (r1,h1) L=20 -> pages 5..6 of a 7-entry page table with slots 10, 11, ..., 16.
+    ctx = np.array([40, 20], dtype=np.int32)
+    owner, _, _ = build_placement(ctx, [0, 1], 2, 2)
+    items, pairs, sched, indptr = build_worklist(ctx, owner, 0, 16, 4, 2)
+    page_indptr = np.array([0, 3, 5, 7]); page_ids = np.arange(10, 17, dtype=np.int32)
+    rec = build_launch_records(items, sched, indptr, page_indptr, page_ids, 2)
+    assert sched.tolist() == [0, 1, 3, 5, 2, 4, 6]
+    # launch position 2 is item 3 = (r1,h0) tokens [0,16): first page 3 -> slot 13, one page, part row 6
+    assert rec[2].tolist() == [3, 0, 16, 4, 6, 0, 13, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    # launch position 4 is item 2 = (r0,h0) tokens [32,40): first page 2 -> slot 12, 8 tokens, part row 4
+    assert rec[4].tolist() == [2, 0, 8, 0, 4, 0, 12, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    # unsplit list, index order: every pair is one item, so every record points at final rows -(p*G) - 1
+    items1, pairs1, _, indptr1 = build_worklist(ctx, owner, 0, 0, 4, 2)
+    rec1 = build_launch_records(items1, None, indptr1, page_indptr, page_ids, 2)
+    assert rec1[:, 4].tolist() == [-1, -3, -5] and rec1[0, 6:14].tolist() == [10, 11, 12, 0, 0, 0, 0, 0]
+    assert build_launch_records(items1, None, indptr1, page_indptr, page_ids, 2, direct_rows=False)[:, 4].tolist() == [0, 2, 4]
+    # a first page beyond 2^31 entries keeps its high word
+    big = build_launch_records(items1[:1], None, indptr1, np.array([2 ** 33 + 5, 2 ** 33 + 8]), {2 ** 33 + 5 + j: 7 + j for j in range(3)}, 2)
+    assert big[0, :2].view(np.int64)[0] == 2 ** 33 + 5 and big[0, 6:9].tolist() == [7, 8, 9]
+
+
+def test_launch_records_invariants():
+    """Every record restates its item: the page range it names is the item's, the slots are the page table's,
+    the row is the partial row or the pair's final rows, on chunked and equal-run lists."""
+    rng = np.random.default_rng(5)
+    R, H, Hq = 3, 4, 16
+    G = Hq // H
+    ctx, owner, load = _case(77, 40, R, H, 0.3, lo=1, hi=700)
+    for k in range(R):
+        for items, order, indptr in ((lambda t: (t[0], t[2], t[3]))(build_worklist(ctx, owner, k, 64, Hq, H)),
+                                     (lambda t: (t[0], None, t[3]))(build_worklist_units(ctx, owner, k, 9, Hq, H))):
+            pairs_L = {}
+            for it in items:
+                pairs_L[int(it[4])] = max(pairs_L.get(int(it[4]), 0), int(it[3]))
+            n_pages = [-(-pairs_L[p] // 16) for p in range(len(pairs_L))]
+            page_indptr = np.concatenate([[0], np.cumsum(n_pages)])
+            page_ids = rng.permutation(int(page_indptr[-1]) + 5)[: int(page_indptr[-1])].astype(np.int32)
+            rec = build_launch_records(items, order, indptr, page_indptr, page_ids, G)
+            seq = range(len(items)) if order is None else order
+            assert len(rec) == len(items)
+            for kk, i in enumerate(seq):
+                it = items[i]
+                fp = int(rec[kk, :2].view(np.int64)[0])
+                assert fp == page_indptr[it[4]] + it[2] // 16 and rec[kk, 2] == it[3] - it[2] and rec[kk, 3] == it[6]
+                npg = -(-int(rec[kk, 2]) // 16)
+                assert fp + npg <= page_indptr[it[4] + 1]
+                assert rec[kk, 6:6 + min(8, npg)].tolist() == page_ids[fp: fp + min(8, npg)].tolist()
+                assert not rec[kk, 6 + min(8, npg):].any() and rec[kk, 5] == 0
+                single = indptr[it[4] + 1] - indptr[it[4]] == 1
+                assert rec[kk, 4] == (-(int(it[4]) * G) - 1 if single else it[7])
