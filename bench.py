@@ -55,7 +55,6 @@ def main() -> int:
                     help="fp8: the kernels gather the scales from the by-slot arrays instead of reading them in page-table order")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="prefill path: launch every step eagerly instead of replaying HIP graphs")
     ap.add_argument("--graph", action="store_true",
                     help="replay the GPU side of a step as a HIP graph per slot instead of launching it eagerly (measured "
                          "slower here: ~14 us pass between the end of one graph and the first kernel of the next)")

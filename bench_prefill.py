@@ -20,11 +20,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # HBM-side bytes of one prefill_bf16_kernel launch on the default batch (rocprofv3 --pmc FETCH_SIZE x 2.000 +
 # WRITE_SIZE, see profiles/prefill_bf16_kernel_hybrid_batch_rank0.txt); other batches: not measured
 MEASURED_TRAFFIC_DEFAULT_BATCH = 217260032
-KV_CHUNK_DEFAULT = 2048            # split-K chunk of the keys a tile sees
+KV_CHUNK_MAX, KV_CHUNK_MIN = 32768, 512    # the split-K chunk of the keys a tile sees is halved from MAX down to MIN ...
+ITEMS_PER_CU = 2.5                         # ... until the list has this many items per compute unit (fs_choose_prefill_chunk)
+N_CU = 256                                 # compute units of an MI355X (the list is a host matter: no device query here)
 
 
 def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64, n_kv_heads=8, seed=20251120,
-                     median=8001, cap=123192, kv_chunk=KV_CHUNK_DEFAULT, queue=None):
+                     median=8001, cap=123192, kv_chunk=None, queue=None):
     """Queue -> router -> Algorithm 1 -> hybrid placement -> rank's tile list (library calls only).
     ``queue``: the waiting prompts if already drawn (the draw is the synthetic input, not part of a step)."""
     if queue is None:
@@ -44,6 +46,9 @@ def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64,
     owner, dp, rank_load, dp_load = fs.fs_build_placement_hybrid_heads(shape, ctx, layer=0, route=entries["rank"])
     G = n_q_heads // n_kv_heads
     tile = fs.fs_prefill_tile_tokens(G)
+    if kv_chunk is None:      # a small batch is cut finer so that every compute unit has work, a large one not at all
+        kv_chunk, _ = fs.fs_choose_prefill_chunk(shape, n_done, take, owner, rank, tile, KV_CHUNK_MAX, KV_CHUNK_MIN,
+                                                 int(ITEMS_PER_CU * N_CU))
     items, pairs, sched, chunk_indptr, out_indptr = fs.fs_build_prefill_worklist(shape, n_done, take, owner, rank, tile,
                                                                                  kv_chunk)
     return dict(seed=seed, queue=queue, shape=shape, G=G, R=R, rank=rank, budget=budget, prompt=prompt, n_done=n_done,
@@ -83,9 +88,9 @@ def run(args) -> int:
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream()
 
-    kv_chunk = KV_CHUNK_DEFAULT if args.chunk is None else args.chunk
-    wl = dict(rank=args.rank, kv_chunk=kv_chunk, budget=args.prefill_budget, n_req=args.prefill_queue)
+    wl = dict(rank=args.rank, kv_chunk=args.chunk, budget=args.prefill_budget, n_req=args.prefill_queue)
     w = prefill_workload(fs, **wl)
+    kv_chunk = w["kv_chunk"]
     shape, G, pairs, items = w["shape"], w["G"], w["pairs"], w["items"]
     if len(items) == 0:
         print("bench.py: this rank's prefill share is empty", file=sys.stderr)
@@ -102,8 +107,9 @@ def run(args) -> int:
 
     host_us = []
     # The step's list is built by the library straight into pinned memory (items | sched | chunk_indptr in one
-    # blob, three blobs in rotation; a blob is reused only once the upload that read it is done) and goes
-    # to the GPU as one copy; the kernels read it from the device blob.
+    # blob, three blobs in rotation).  By default the kernels read it in place and are launched eagerly (a blob is
+    # reused only once the kernels that read it are done); --list device --graph uploads it as one copy and replays
+    # upload, attention and merge as one HIP graph.
     n_cap, t_cap, p_cap = len(items), len(w["chunk_indptr"]) - 1, len(pairs)
 
     def up(x):
@@ -127,7 +133,11 @@ def run(args) -> int:
                                               views["items"], views["pairs"], views["sched"], views["indptr"],
                                               views["out_indptr"])
         staging.append(dict(host=hb, build=call))
+    call_chunk = fs.bind_choose_prefill_chunk(shape, n_done_buf, n_new_buf, owner_buf, args.rank, w["tile"], KV_CHUNK_MAX,
+                                              KV_CHUNK_MIN, int(ITEMS_PER_CU * N_CU))
     n_step = [0]
+    in_place = args.list == "host"
+    use_graph = args.graph and not in_place
     base = dev_blob.data_ptr()
     R = w["R"]
     entries = w["entries"].copy()
@@ -148,6 +158,10 @@ def run(args) -> int:
         n_step[0] += 1
         st["done"].synchronize()                 # the upload that last read this blob is done
         t4 = time.perf_counter()
+        if args.chunk is None:                   # the split-K chunk is part of the step's host work (same batch, same choice)
+            call_chunk()
+            if call_chunk.n_tiles.value != kv_chunk:
+                raise RuntimeError("the step's batch changed under the benchmark")
         st["build"]()
         n_it, n_ti = st["build"].n_items.value, st["build"].n_tiles.value
         t5 = time.perf_counter()
@@ -161,18 +175,24 @@ def run(args) -> int:
 
     def enqueue(st, n_it, n_ti, on, ev=None):
         sp = on.cuda_stream
-        dev_blob.copy_(st["host"], non_blocking=True)
-        st["done"].record(on)
+        if in_place:              # the kernels read the list where the host built it (pinned, mapped into the GPU's address space)
+            b = st["host"].data_ptr()
+        else:
+            b = base
+            dev_blob.copy_(st["host"], non_blocking=True)
+            st["done"].record(on)
         if ev is not None:
             ev[0].record(on)
-        fs.fs_prefill_attention(ds.shape, ds.view, base, base + off_sched, n_it,
+        fs.fs_prefill_attention(ds.shape, ds.view, b, b + off_sched, n_it,
                                 ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
         if ev is not None:
             ev[1].record(on)
-        fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, base + off_indptr, n_ti,
+        fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, b + off_indptr, n_ti,
                         ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
         if ev is not None:
             ev[2].record(on)
+        if in_place:
+            st["done"].record(on)     # the blob is free again once the kernels that read it are done
 
     for st in staging:
         st["done"] = torch.cuda.Event()
@@ -183,7 +203,7 @@ def run(args) -> int:
     torch.cuda.synchronize()
     # The GPU side of a step - upload of the blob, attention, merge - as one HIP graph per staging blob (the list's
     # sizes are launch arguments, so a step whose list has other sizes than the captured one is launched eagerly).
-    if not args.no_graph:
+    if use_graph:
         cap_stream = torch.cuda.Stream()
         for st in staging:
             counts = (st["build"].n_items.value, st["build"].n_tiles.value)
@@ -202,7 +222,7 @@ def run(args) -> int:
         torch.cuda.synchronize()
     host_us.clear()
     EVENT_EVERY = 8          # every 8th step runs eagerly with HIP events around the kernels
-    timed = [i for i in range(args.steps) if args.no_graph or i % EVENT_EVERY == 0]
+    timed = [i for i in range(args.steps) if i % EVENT_EVERY == 0]
     events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for i in timed}
     torch.cuda.synchronize()
     gc.collect()
@@ -262,7 +282,9 @@ def run(args) -> int:
                    "query_rows": rows, "kv_tokens_of_pairs": kv_tokens, "flops": flops,
                    "prefill_waves": fs.fs_get_option("prefill_waves"), "prefill_col_tiles": fs.fs_get_option("prefill_col_tiles"),
                    "second_product": "bf16 V, weights bf16 hi+lo (v_range FS_V_ANY)" if args.prefill_wide_v else "fp16 V and weights (v_range FS_V_FP16_RANGE)",
-                   "launch": "eager" if args.no_graph else f"hip graph per staging blob (upload, attention, merge); every {EVENT_EVERY}th step eager with events"},
+                   "work_list": "read in place from pinned host memory" if in_place else "uploaded every step",
+                   "launch": f"hip graph per staging blob (upload, attention, merge); every {EVENT_EVERY}th step eager with events" if use_graph
+                             else f"eager; every {EVENT_EVERY}th step with events around the kernels"},
         "kernel_ms": {"prefill_avg": round(k_avg, 5), "prefill_p10": round(float(np.percentile(k_ms, 10)), 5),
                       "prefill_p90": round(float(np.percentile(k_ms, 90)), 5), "merge_avg": round(float(m_ms.mean()), 5)},
         "host_us_per_step": dict(zip(("all", "router", "scheduler", "placement", "wait_for_staging", "tile_list", "upload_enqueue"),
@@ -273,7 +295,7 @@ def run(args) -> int:
                      "frac": round(flops / (k_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "algorithmic_flops_per_launch": flops,
                      "traffic": MEASURED_TRAFFIC_DEFAULT_BATCH if (args.prefill_queue, args.prefill_budget, args.rank, kv_chunk)
-                     == (64, 8192, 0, KV_CHUNK_DEFAULT) and fs.fs_get_option("prefill_waves") == 8
+                     == (64, 8192, 0, 2048) and fs.fs_get_option("prefill_waves") == 8
                      and fs.fs_get_option("prefill_col_tiles") == 1 else None},
     }
     if cpu is not None:

@@ -15,7 +15,7 @@ unpinned".
 from .formats import bf16_bits_to_f64, e4m3_bytes_to_f64, E4M3_TABLE  # noqa: F401
 from .placement import build_placement, build_placement_hybrid_heads  # noqa: F401
 from .prefill import (  # noqa: F401
-    build_prefill_worklist, prefill_attention_items, prefill_attention_pairs, prefill_attention_row,
+    build_prefill_worklist, choose_prefill_chunk, prefill_attention_items, prefill_attention_pairs, prefill_attention_row,
     PREFILL_ITEM_FIELDS, PREFILL_PAIR_FIELDS,
 )
 from .recovery import plan_ffn_reload, plan_kv_reload, replace_failed_gpu  # noqa: F401

@@ -74,6 +74,24 @@ def build_prefill_worklist(n_done, n_new, owner, rank: int, n_q_heads: int, tile
             np.array(out_indptr, dtype=np.int64))
 
 
+def choose_prefill_chunk(n_done, n_new, owner, rank: int, n_q_heads: int, tile_tokens: int, max_chunk: int,
+                         min_chunk: int, min_items: int):
+    """Halve the split-K chunk of the keys from ``max_chunk`` down (staying a multiple of ``min_chunk``'s
+    granule, 32 keys) until ``rank``'s tile list has at least ``min_items`` items or the next halving would
+    fall below ``min_chunk``.  -> (chunk, n_items).  Split-K is this build's device, not the paper's: a
+    batch with few long chunks (Section 3.1's fine-grained chunked prefill forms such batches when little
+    is waiting) would otherwise leave most of the GPU idle, while a large batch needs no split at all."""
+    if min_chunk < 32 or min_chunk % 32 or max_chunk < min_chunk or max_chunk % 32:
+        raise ValueError("chunk bounds must be multiples of 32, min <= max")
+    C = int(max_chunk)
+    while True:
+        n = len(build_prefill_worklist(n_done, n_new, owner, rank, n_q_heads, tile_tokens, C)[0])
+        nxt = (C // 2) // 32 * 32
+        if n >= min_items or nxt < min_chunk:
+            return C, n
+        C = nxt
+
+
 def prefill_attention_items(q_bits, kv: dict, items, pairs, n_q_heads: int, group: int, tile_tokens: int,
                             sm_scale: float):
     """Partial result of every item: rows [i*T, (i+1)*T); rows of tokens a short tile does not have

@@ -109,6 +109,9 @@ def load_library(path: str | None = None):
                                               C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                               C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, i64p, i64p, i64p]
     lib.fs_build_prefill_worklist.restype = C.c_int
+    lib.fs_choose_prefill_chunk.argtypes = [C.POINTER(FsShape), i32p, i32p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_int64, i32p, i64p]
+    lib.fs_choose_prefill_chunk.restype = C.c_int
     lib.fs_prefill_tile_tokens.argtypes = [C.c_int32]
     lib.fs_prefill_tile_tokens.restype = C.c_int32
     lib.fs_prefill_attention.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
@@ -453,6 +456,21 @@ def fs_build_prefill_worklist(shape: FsShape, n_done, n_new, owner, rank: int, t
     return items, pairs, sched, chunk_indptr, out_indptr
 
 
+def fs_choose_prefill_chunk(shape: FsShape, n_done, n_new, owner, rank: int, tile_tokens: int, max_chunk: int,
+                            min_chunk: int, min_items: int):
+    """-> (kv_chunk_tokens, n_items): the split-K chunk, halved from ``max_chunk`` down to at least ``min_chunk``,
+    with which ``rank``'s tile list reaches ``min_items`` items."""
+    nd, nn, own = _host(n_done, np.int32), _host(n_new, np.int32), _host(owner, np.int32)
+    if len(nd) != shape.n_req or len(nn) != shape.n_req or own.size != shape.n_req * shape.n_kv_heads:
+        raise ValueError("n_done, n_new and owner must match the shape")
+    i32p = C.POINTER(C.c_int32)
+    chunk, n_items = C.c_int32(0), C.c_int64(0)
+    _check(load_library().fs_choose_prefill_chunk(C.byref(shape), nd.ctypes.data_as(i32p), nn.ctypes.data_as(i32p),
+                                                  own.ctypes.data_as(i32p), rank, tile_tokens, max_chunk, min_chunk,
+                                                  min_items, C.byref(chunk), C.byref(n_items)))
+    return chunk.value, n_items.value
+
+
 def fs_prefill_attention(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int, tile_tokens: int,
                          part_o, part_lse, stream=None) -> None:
     st = load_library().fs_prefill_attention(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
@@ -637,6 +655,22 @@ def bind_build_prefill_worklist(shape: FsShape, n_done: np.ndarray, n_new: np.nd
             C.c_void_p(out_indptr.ctypes.data), C.byref(n_items), C.byref(n_pairs), C.byref(n_tiles))
     return BoundCall(lib.fs_build_prefill_worklist, args,
                      (shape, n_done, n_new, owner, items, pairs, sched, chunk_indptr, out_indptr), n_items, n_pairs, n_tiles)
+
+
+def bind_choose_prefill_chunk(shape: FsShape, n_done: np.ndarray, n_new: np.ndarray, owner: np.ndarray, rank: int,
+                              tile_tokens: int, max_chunk: int, min_chunk: int, min_items: int) -> BoundCall:
+    """fs_choose_prefill_chunk on caller-held int32 arrays, read at every call.  After a call the chunk is in
+    .n_tiles.value and the list's length in .n_items.value."""
+    lib = load_library()
+    for a in (n_done, n_new, owner):
+        if a.dtype != np.int32 or not a.flags.c_contiguous:
+            raise TypeError("bind_choose_prefill_chunk needs contiguous int32 n_done, n_new and owner")
+    i32p = C.POINTER(C.c_int32)
+    chunk, n_items = C.c_int32(0), C.c_int64(0)
+    args = (C.byref(shape), n_done.ctypes.data_as(i32p), n_new.ctypes.data_as(i32p), owner.ctypes.data_as(i32p),
+            C.c_int32(rank), C.c_int32(tile_tokens), C.c_int32(max_chunk), C.c_int32(min_chunk), C.c_int64(min_items),
+            C.byref(chunk), C.byref(n_items))
+    return BoundCall(lib.fs_choose_prefill_chunk, args, (shape, n_done, n_new, owner), n_items, None, chunk)
 
 
 def bind_decode_attention(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int,

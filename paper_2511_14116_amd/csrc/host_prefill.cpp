@@ -111,3 +111,43 @@ extern "C" fs_status fs_build_prefill_worklist(const fs_shape* shape, const int3
   });
   return FS_OK;
 }
+
+extern "C" fs_status fs_choose_prefill_chunk(const fs_shape* shape, const int32_t* n_done, const int32_t* n_new,
+                                             const int32_t* owner, int32_t rank, int32_t tile_tokens,
+                                             int32_t max_chunk, int32_t min_chunk, int64_t min_items,
+                                             int32_t* kv_chunk_tokens, int64_t* n_items) {
+  if (!kv_chunk_tokens || !n_items) return fs::fail(FS_EINVAL, "fs_choose_prefill_chunk: output pointers are NULL");
+  if (min_chunk < 32 || min_chunk % 32 || max_chunk < min_chunk || max_chunk % 32)
+    return fs::fail(FS_EINVAL, "fs_choose_prefill_chunk: chunks [%d, %d] must be multiples of 32, min <= max", min_chunk,
+                    max_chunk);
+  if (min_items < 0) return fs::fail(FS_EINVAL, "fs_choose_prefill_chunk: min_items %lld < 0", static_cast<long long>(min_items));
+  // The candidates: max_chunk halved (keeping multiples of 32 keys) down to min_chunk.
+  int32_t cand[32];
+  int n_cand = 0;
+  for (int32_t C = max_chunk; C >= min_chunk && n_cand < 32; C = (C / 2) / 32 * 32) cand[n_cand++] = C;
+  // The list builder checks the arguments and counts the first candidate's list; the other candidates are
+  // counted in one more walk over the tiles (an item per chunk of the keys a tile sees).
+  int64_t count[32] = {}, np = 0, nt = 0;
+  if (const fs_status st = fs_build_prefill_worklist(shape, n_done, n_new, owner, rank, tile_tokens, cand[0], nullptr, 0, nullptr,
+                                                     0, nullptr, nullptr, 0, nullptr, &count[0], &np, &nt); st != FS_OK)
+    return st;
+  if (count[0] < min_items && n_cand > 1) {
+    const int32_t B = shape->n_req, H = shape->n_kv_heads;
+    for (int c = 1; c < n_cand; ++c) count[c] = 0;
+    for (int32_t r = 0; r < B; ++r) {
+      if (n_new[r] == 0) continue;
+      int64_t mine = 0;
+      for (int32_t h = 0; h < H; ++h) mine += owner[static_cast<int64_t>(r) * H + h] == rank;
+      if (mine == 0) continue;
+      for (int64_t b = 0; b < n_new[r]; b += tile_tokens) {
+        const int64_t keys = n_done[r] + std::min<int64_t>(n_new[r], b + tile_tokens);
+        for (int c = 1; c < n_cand; ++c) count[c] += mine * ((keys + cand[c] - 1) / cand[c]);
+      }
+    }
+  }
+  int pick = 0;
+  while (count[pick] < min_items && pick + 1 < n_cand) ++pick;
+  *kv_chunk_tokens = cand[pick];
+  *n_items = count[pick];
+  return FS_OK;
+}

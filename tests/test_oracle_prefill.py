@@ -173,3 +173,34 @@ def test_chunk_partials_merge_back_to_unsplit(chunk):
     valid = np.isfinite(want_l)
     assert valid.sum() == int(pairs[:, 3].sum()) * G
     assert np.abs(out[valid] - want_o[valid]).max() < 1e-12 and np.abs(lse[valid] - want_l[valid]).max() < 1e-12
+
+
+def test_chunk_choice_by_hand_and_on_drawn_batches():
+    """choose_prefill_chunk: a hand-worked case per branch, and on drawn batches that the count is the real
+    list's and every larger candidate was too short."""
+    import oracle
+    from oracle import choose_prefill_chunk
+    owner = np.zeros((2, 1), dtype=np.int32)
+    # one pair, 100 processed + 28 new tokens, tiles of 16: tile 0 sees 116 keys, tile 1 sees 128.
+    n_done, n_new = [100, 0], [28, 0]
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 2) == (256, 2)       # long enough at once
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 3) == (64, 4)        # 128: 2 items, 64: 2 + 2
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 100) == (32, 8)      # down to the floor: 4 + 4
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 96, 32, 5) == (32, 8)         # 96 -> 48 is no multiple of 32: 32
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 0) == (256, 2)       # nothing asked for
+    with pytest.raises(ValueError):
+        choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 100, 32, 1)
+    rng = np.random.default_rng(21)
+    for _ in range(40):
+        B, H, R = int(rng.integers(1, 6)), int(rng.integers(1, 4)), int(rng.integers(1, 3))
+        n_done = rng.integers(0, 3000, size=B); n_new = rng.integers(0, 200, size=B)
+        owner = rng.integers(0, R, size=(B, H)).astype(np.int32)
+        tile = int(rng.integers(1, 33)); want_items = int(rng.integers(0, 60))
+        mx = 32 * int(rng.integers(1, 65)); mn = 32 * int(rng.integers(1, mx // 32 + 1))
+        C, n = choose_prefill_chunk(n_done, n_new, owner, 0, 2 * H, tile, mx, mn, want_items)
+        assert n == len(oracle.build_prefill_worklist(n_done, n_new, owner, 0, 2 * H, tile, C)[0]) and mn <= C <= mx and C % 32 == 0
+        c = mx
+        while c != C:                      # every larger candidate was too short
+            assert len(oracle.build_prefill_worklist(n_done, n_new, owner, 0, 2 * H, tile, c)[0]) < want_items
+            c = (c // 2) // 32 * 32
+        assert n >= want_items or (C // 2) // 32 * 32 < mn
