@@ -116,7 +116,8 @@ def run(args) -> int:
         return (x + 255) & ~255
     off_sched = up(n_cap * 32)
     off_indptr = up(off_sched + n_cap * 4)
-    blob_bytes = up(off_indptr + (t_cap + 1) * 8)
+    off_out_indptr = up(off_indptr + (t_cap + 1) * 8)
+    blob_bytes = up(off_out_indptr + (p_cap + 1) * 8)
     dev_blob = torch.empty(blob_bytes, dtype=torch.uint8, device=dev)
     N_STAGE = 3
     n_done_buf = np.ascontiguousarray(w["n_done"], dtype=np.int32)
@@ -128,7 +129,8 @@ def run(args) -> int:
         a = hb.numpy()
         views = dict(items=a[:n_cap * 32].view(fs.PREFILL_ITEM_DTYPE), sched=a[off_sched:off_sched + n_cap * 4].view(np.int32),
                      indptr=a[off_indptr:off_indptr + (t_cap + 1) * 8].view(np.int64),
-                     pairs=np.empty(p_cap, dtype=fs.PREFILL_PAIR_DTYPE), out_indptr=np.empty(p_cap + 1, dtype=np.int64))
+                     pairs=np.empty(p_cap, dtype=fs.PREFILL_PAIR_DTYPE),
+                     out_indptr=a[off_out_indptr:off_out_indptr + (p_cap + 1) * 8].view(np.int64))
         call = fs.bind_build_prefill_worklist(shape, n_done_buf, n_new_buf, owner_buf, args.rank, w["tile"], kv_chunk,
                                               views["items"], views["pairs"], views["sched"], views["indptr"],
                                               views["out_indptr"])
@@ -183,14 +185,19 @@ def run(args) -> int:
             st["done"].record(on)
         if ev is not None:
             ev[0].record(on)
-        fs.fs_prefill_attention(ds.shape, ds.view, b, b + off_sched, n_it,
-                                ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
-        if ev is not None:
-            ev[1].record(on)
-        fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, b + off_indptr, n_ti,
-                        ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
-        if ev is not None:
-            ev[2].record(on)
+        if ev is not None or args.two_calls:   # the two calls, so that the attention kernel can be timed on its own
+            fs.fs_prefill_attention(ds.shape, ds.view, b, b + off_sched, n_it,
+                                    ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
+            if ev is not None:
+                ev[1].record(on)
+            fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, b + off_indptr, n_ti,
+                            ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
+            if ev is not None:
+                ev[2].record(on)
+        else:                                  # one call: tiles of one chunk are final from the kernel, the rest is merged
+            fs.fs_prefill_attention_fused(ds.shape, ds.view, b, b + off_sched, n_it, ds.prefill_tile_tokens, b + off_indptr,
+                                          n_ti, b + off_out_indptr, ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out,
+                                          ds.prefill_lse, sp)
         if in_place:
             st["done"].record(on)     # the blob is free again once the kernels that read it are done
 
@@ -211,10 +218,9 @@ def run(args) -> int:
             with torch.cuda.graph(g, stream=cap_stream):
                 dev_blob.copy_(st["host"], non_blocking=True)
                 sp = cap_stream.cuda_stream
-                fs.fs_prefill_attention(ds.shape, ds.view, base, base + off_sched, counts[0],
-                                        ds.prefill_tile_tokens, ds.prefill_part_o, ds.prefill_part_lse, sp)
-                fs.fs_merge_lse(ds.prefill_part_o, ds.prefill_part_lse, base + off_indptr, counts[1],
-                                ds.prefill_tile_rows, 128, ds.prefill_out, ds.prefill_lse, sp)
+                fs.fs_prefill_attention_fused(ds.shape, ds.view, base, base + off_sched, counts[0], ds.prefill_tile_tokens,
+                                              base + off_indptr, counts[1], base + off_out_indptr, ds.prefill_part_o,
+                                              ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse, sp)
             st["graph"], st["counts"] = g, counts
         torch.cuda.synchronize()
         for _ in range(N_STAGE):
@@ -283,6 +289,8 @@ def run(args) -> int:
                    "prefill_waves": fs.fs_get_option("prefill_waves"), "prefill_col_tiles": fs.fs_get_option("prefill_col_tiles"),
                    "second_product": "bf16 V, weights bf16 hi+lo (v_range FS_V_ANY)" if args.prefill_wide_v else "fp16 V and weights (v_range FS_V_FP16_RANGE)",
                    "work_list": "read in place from pinned host memory" if in_place else "uploaded every step",
+                   "step_calls": "fs_prefill_attention + fs_merge_lse" if args.two_calls else "fs_prefill_attention_fused",
+                   "single_chunk_tiles": int((np.diff(w["chunk_indptr"]) == 1).sum()),
                    "launch": f"hip graph per staging blob (upload, attention, merge); every {EVENT_EVERY}th step eager with events" if use_graph
                              else f"eager; every {EVENT_EVERY}th step with events around the kernels"},
         "kernel_ms": {"prefill_avg": round(k_avg, 5), "prefill_p10": round(float(np.percentile(k_ms, 10)), 5),

@@ -730,6 +730,28 @@ FS_API fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* k
                                       int64_t n_items, int32_t tile_tokens, float* part_o, float* part_lse,
                                       void* stream);
 
+/* fs_prefill_attention_fused - fs_prefill_attention and the split-K merge in one call (prefill phase,
+ * Section 2.1.1; the batches of Section 3.1's chunked prefill).  An item that is all of its tile (kv_begin
+ * == 0 and kv_end == n_done + q_end) writes the tile's final rows, out_indptr[pair] + token*G + g,
+ * straight from the kernel; the merge runs for the tiles that are split and is not launched when n_items ==
+ * n_tiles.  out/lse hold, bit for bit, what fs_prefill_attention followed by fs_merge_lse over all tiles
+ * leaves.
+ *
+ *  chunk_indptr_dev  DEVICE in   [n_tiles+1]   as built by fs_build_prefill_worklist
+ *  out_indptr_dev    DEVICE in   [n_pairs+1]   likewise
+ *  part_o, part_lse  DEVICE scratch, sized and indexed as for fs_prefill_attention (rows of unsplit tiles stay
+ *                    untouched); may be NULL when n_items == n_tiles
+ *  out, lse          DEVICE out  [n_tiles*T][head_dim], [n_tiles*T] fp32
+ *
+ * Errors as for fs_prefill_attention, and FS_EINVAL for n_tiles outside [1, n_items] or a NULL
+ * chunk_indptr_dev, out_indptr_dev, out or lse. */
+FS_API fs_status fs_prefill_attention_fused(const fs_shape* shape, const fs_kv_view* kv,
+                                            const fs_prefill_item* items_dev, const int32_t* sched_dev,
+                                            int64_t n_items, int32_t tile_tokens,
+                                            const int64_t* chunk_indptr_dev, int64_t n_tiles,
+                                            const int64_t* out_indptr_dev, float* part_o, float* part_lse,
+                                            float* out, float* lse, void* stream);
+
 /* ---------------------------------------------------------------------------
  * fs_stream_read_probe - measurement aid, not a step of the path: read `bytes`
  * bytes once with the access pattern of the attention sweep (16 bytes per lane,

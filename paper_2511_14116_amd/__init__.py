@@ -8,7 +8,7 @@ from .binding import (  # noqa: F401
     FS_OK, FS_EINVAL, FS_ECAPACITY, FS_EHIP, FS_EUNSUPPORTED,
     FS_MODE_TP, FS_MODE_DP, FS_KV_BF16, FS_KV_FP8_E4M3, FS_V_ANY, FS_V_FP16_RANGE,
     FsError, FsShape, FsKvView, ITEM_DTYPE, PAIR_DTYPE, RECORD_DTYPE, PREFILL_ENTRY_DTYPE, PREFILL_ITEM_DTYPE, PREFILL_PAIR_DTYPE,
-    fs_build_prefill_worklist, fs_choose_prefill_chunk, fs_prefill_attention, fs_prefill_tile_tokens,
+    fs_build_prefill_worklist, fs_choose_prefill_chunk, fs_prefill_attention, fs_prefill_attention_fused, fs_prefill_tile_tokens,
     fs_route_request, fs_route_requests, fs_schedule_prefill, fs_plan_kv_reload, fs_replace_failed_gpu, fs_plan_ffn_reload,
     library_path, load_library,
     fs_build_placement, fs_build_placement_hybrid_heads, fs_build_worklist, fs_build_worklist_units, fs_build_launch_records, fs_choose_chunk_tokens, fs_decode_attention, fs_decode_attention_persistent, fs_decode_attention_fused, fs_decode_attention_fused_static, fs_decode_attention_units, fs_decode_attention_records, fs_merge_lse,

@@ -117,6 +117,10 @@ def load_library(path: str | None = None):
     lib.fs_prefill_attention.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
                                          C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_prefill_attention.restype = C.c_int
+    lib.fs_prefill_attention_fused.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
+                                               C.c_int64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
+                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fs_prefill_attention_fused.restype = C.c_int
     lib.fs_kv_elem_offset.argtypes = [C.c_int32] * 4
     lib.fs_kv_elem_offset.restype = C.c_int32
     lib.fs_decode_attention.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_void_p,
@@ -475,6 +479,16 @@ def fs_prefill_attention(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_i
                          part_o, part_lse, stream=None) -> None:
     st = load_library().fs_prefill_attention(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
                                              n_items, tile_tokens, _ptr(part_o), _ptr(part_lse), _ptr(stream))
+    _check(st)
+
+
+def fs_prefill_attention_fused(shape: FsShape, kv: FsKvView, items_dev, sched_dev, n_items: int, tile_tokens: int,
+                               chunk_indptr_dev, n_tiles: int, out_indptr_dev, part_o, part_lse, out, lse,
+                               stream=None) -> None:
+    st = load_library().fs_prefill_attention_fused(C.byref(shape), C.byref(kv), _ptr(items_dev), _ptr(sched_dev),
+                                                   n_items, tile_tokens, _ptr(chunk_indptr_dev), n_tiles,
+                                                   _ptr(out_indptr_dev), _ptr(part_o), _ptr(part_lse), _ptr(out),
+                                                   _ptr(lse), _ptr(stream))
     _check(st)
 
 

@@ -53,6 +53,11 @@ struct PrefillParams {
   const int32_t* __restrict__ sched;
   float* __restrict__ part_o;
   float* __restrict__ part_lse;
+  // One-call form only (else NULL): an item that is all of its tile writes the tile's final rows,
+  // out_indptr[pair] + token*G + g, and needs no merge.
+  const int64_t* __restrict__ out_indptr;
+  float* __restrict__ out;
+  float* __restrict__ lse;
   int32_t group;        // G
   int32_t group_pad;    // G rounded up to a power of two (divides 16)
   int32_t n_q_heads;
@@ -73,21 +78,21 @@ struct InFlight {
   u32x4 v[NP];
 };
 
-// max of three without the NaN-quieting moves the compiler puts around fmaxf (the inputs are matrix-core
-// outputs or -inf; a NaN can only come from a row that is never stored)
+// max of three / of two as IEEE-754 maximum (v_maximum3_f32): no NaN-quieting moves around it, unlike fmaxf,
+// and, being an instruction the compiler knows, it gets the wait states that a read of a matrix-core result
+// needs.  (An asm statement does not: the compiler cannot see that it reads registers a matrix instruction has
+// just written, and the hardware does not interlock, so it would read what the registers held before.)
+// The inputs are matrix-core outputs or -inf; a NaN can only come from a row that is never stored.
 __device__ __forceinline__ float max3(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
+  return __builtin_elementwise_maximum(__builtin_elementwise_maximum(a, b), c);
 }
 
-__device__ __forceinline__ float max2(float a, float b) {
-  float r;
-  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
+__device__ __forceinline__ float max2(float a, float b) { return __builtin_elementwise_maximum(a, b); }
 // x *= a in place.  As asm with a tied operand so that, inside a rarely taken branch, the accumulators
 // stay in their registers (with a plain multiply the compiler copies all of them on every step instead).
+// The compiler does not see that these statements read and write registers of matrix instructions, so the
+// branch that holds them opens and closes with the wait states itself (FS_MATRIX_RESULT_WAIT).
+#define FS_MATRIX_RESULT_WAIT() asm volatile("s_nop 7\n\ts_nop 4" ::: "memory")   // 13 wait states: above the 12 of an 8-pass result
 #define FS_SCALE_IN_PLACE(vec, k, a)                                  \
   do {                                                                \
     float t_ = (vec)[k];                                              \
@@ -147,6 +152,7 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     mx = max2(__uint_as_float(c), __uint_as_float(d)) * scale_log2;
     const bool move = mx > st.m + kLazy;
     const float alpha = move ? __builtin_amdgcn_exp2f(st.m - mx) : 1.0f;   // st.m = -inf: exp2(-inf) = 0
+    FS_MATRIX_RESULT_WAIT();
     FS_SCALE_IN_PLACE(st.l, 0, alpha);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -155,6 +161,7 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
       FS_SCALE_IN_PLACE(st.acc[j], 2, alpha);
       FS_SCALE_IN_PLACE(st.acc[j], 3, alpha);
     }
+    FS_MATRIX_RESULT_WAIT();
     st.m = move ? mx : st.m;
     // A row may have seen none of the item's keys so far (its position lies before the chunk): its
     // state stays at zero and its reference is 0.
@@ -394,23 +401,28 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     __syncthreads();
   }
 
-  // ---- write the item's partial rows --------------------------------------------------------------
+  // ---- write the item's rows: partial rows, or the tile's final rows when the item is all of its tile ----
+  // (an item that starts at key 0 and ends at the last key its tile may see is the tile's only chunk)
+  const bool direct = P.out_indptr != nullptr && it.kv_begin == 0 && it.kv_end == it.n_done + it.q_end;
+  float* const dst_o = direct ? P.out : P.part_o;
+  float* const dst_lse = direct ? P.lse : P.part_lse;
+  const int64_t row0 = direct ? P.out_indptr[it.pair] + static_cast<int64_t>(it.q_begin) * G : static_cast<int64_t>(it.part_row);
 #pragma unroll
   for (int t = 0; t < CT; ++t) {
     const int tok = tok0 + t * tpc + tl;
     const float l_tot = st[t].l[0];
-    if (g >= G || tok >= P.tile_tokens) continue;          // no such row in the partial buffer
-    const int64_t row = static_cast<int64_t>(it.part_row) + static_cast<int64_t>(tok) * G + g;
-    float* o = P.part_o + row * fs::kHeadDim + 4 * kb;
+    if (g >= G || tok >= P.tile_tokens) continue;          // no such row in the buffers
+    const int64_t row = row0 + static_cast<int64_t>(tok) * G + g;
+    float* o = dst_o + row * fs::kHeadDim + 4 * kb;
     if (tok < n_tok) {
       const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;  // a row that saw none of the item's keys: out = 0, lse = -inf
 #pragma unroll
       for (int b = 0; b < 8; ++b) *reinterpret_cast<f32x4*>(o + 16 * b) = st[t].acc[b] * inv;
-      if (kb == 0) P.part_lse[row] = l_tot > 0.f ? (st[t].m + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      if (kb == 0) dst_lse[row] = l_tot > 0.f ? (st[t].m + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
     } else {                                               // padding row of a short last tile
 #pragma unroll
       for (int b = 0; b < 8; ++b) *reinterpret_cast<f32x4*>(o + 16 * b) = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (kb == 0) P.part_lse[row] = 0.f;
+      if (kb == 0) dst_lse[row] = 0.f;
     }
   }
 }
@@ -436,44 +448,48 @@ extern "C" int32_t fs_prefill_tile_tokens(int32_t group) {
   return fs::options().prefill_waves * fs::options().prefill_col_tiles * (16 / pad_group(group));
 }
 
-extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* kv,
-                                          const fs_prefill_item* items_dev, const int32_t* sched_dev,
-                                          int64_t n_items, int32_t tile_tokens, float* part_o, float* part_lse,
-                                          void* stream) {
-  if (!shape || !kv) return fs::fail(FS_EINVAL, "fs_prefill_attention: shape or kv is NULL");
+namespace {
+
+// Argument checks and launch shared by the two entry points.  direct_* non-NULL: single-chunk tiles write final rows.
+fs_status prefill_launch(const char* who, const fs_shape* shape, const fs_kv_view* kv,
+                         const fs_prefill_item* items_dev, const int32_t* sched_dev,
+                         int64_t n_items, int32_t tile_tokens, float* part_o, float* part_lse, bool partials_needed,
+                         const int64_t* out_indptr_dev, float* out, float* lse, void* stream) {
+  if (!shape || !kv) return fs::fail(FS_EINVAL, "%s: shape or kv is NULL", who);
   if (shape->n_kv_heads < 1 || shape->n_q_heads < shape->n_kv_heads || shape->n_q_heads % shape->n_kv_heads)
-    return fs::fail(FS_EINVAL, "fs_prefill_attention: n_q_heads %d is not a multiple of n_kv_heads %d",
+    return fs::fail(FS_EINVAL, "%s: n_q_heads %d is not a multiple of n_kv_heads %d", who,
                     shape->n_q_heads, shape->n_kv_heads);
   if (shape->head_dim != fs::kHeadDim)
-    return fs::fail(FS_EUNSUPPORTED, "fs_prefill_attention: head_dim %d (only %d is built)", shape->head_dim, fs::kHeadDim);
+    return fs::fail(FS_EUNSUPPORTED, "%s: head_dim %d (only %d is built)", who, shape->head_dim, fs::kHeadDim);
   if (shape->page_tokens != fs::kPageTokens)
-    return fs::fail(FS_EUNSUPPORTED, "fs_prefill_attention: page_tokens %d (only %d is built)", shape->page_tokens,
+    return fs::fail(FS_EUNSUPPORTED, "%s: page_tokens %d (only %d is built)", who, shape->page_tokens,
                     fs::kPageTokens);
   const int G = shape->n_q_heads / shape->n_kv_heads;
-  if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "fs_prefill_attention: group %d > %d", G, fs::kMaxGroup);
+  if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "%s: group %d > %d", who, G, fs::kMaxGroup);
   if (kv->kv_dtype != FS_KV_BF16)
-    return fs::fail(FS_EUNSUPPORTED, "fs_prefill_attention: only bf16 K/V is built (kv_dtype %d)", kv->kv_dtype);
-  if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "fs_prefill_attention: n_items out of range");
+    return fs::fail(FS_EUNSUPPORTED, "%s: only bf16 K/V is built (kv_dtype %d)", who, kv->kv_dtype);
+  if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "%s: n_items out of range", who);
   const int ct = fs::options().prefill_col_tiles, waves = fs::options().prefill_waves;
   const int cap = waves * ct * (16 / pad_group(G));
   if (tile_tokens < 1 || tile_tokens > cap)
-    return fs::fail(FS_EINVAL, "fs_prefill_attention: tile_tokens %d outside [1, %d] for group %d", tile_tokens, cap, G);
+    return fs::fail(FS_EINVAL, "%s: tile_tokens %d outside [1, %d] for group %d", who, tile_tokens, cap, G);
   if (n_items == 0) return FS_OK;
-  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev || !part_o || !part_lse)
-    return fs::fail(FS_EINVAL, "fs_prefill_attention: NULL device pointer");
+  if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev ||
+      (partials_needed && (!part_o || !part_lse)))
+    return fs::fail(FS_EINVAL, "%s: NULL device pointer", who);
   const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * 2;
   if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
       (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
       (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
       (reinterpret_cast<uintptr_t>(part_o) & 15))
-    return fs::fail(FS_EINVAL, "fs_prefill_attention: pools, strides, q and part_o must be 16-byte aligned and strides "
-                               "at least one slot (%lld bytes)", static_cast<long long>(slot_bytes));
+    return fs::fail(FS_EINVAL, "%s: pools, strides, q and part_o must be 16-byte aligned and strides "
+                               "at least one slot (%lld bytes)", who, static_cast<long long>(slot_bytes));
   // The kernel's lazy running maximum is taken on the raw scores and scaled afterwards, which orders them
   // correctly only for a positive scale.
   if (!std::isfinite(kv->sm_scale) || kv->sm_scale <= 0.f)
-    return fs::fail(FS_EINVAL, "fs_prefill_attention: sm_scale %g is not finite and positive", static_cast<double>(kv->sm_scale));
+    return fs::fail(FS_EINVAL, "%s: sm_scale %g is not finite and positive", who, static_cast<double>(kv->sm_scale));
   if (kv->v_range != FS_V_ANY && kv->v_range != FS_V_FP16_RANGE)
-    return fs::fail(FS_EINVAL, "fs_prefill_attention: unknown v_range %d", kv->v_range);
+    return fs::fail(FS_EINVAL, "%s: unknown v_range %d", who, kv->v_range);
 
   PrefillParams P;
   P.q = static_cast<const uint16_t*>(kv->q);
@@ -487,6 +503,9 @@ extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_vie
   P.sched = sched_dev;
   P.part_o = part_o;
   P.part_lse = part_lse;
+  P.out_indptr = out_indptr_dev;
+  P.out = out;
+  P.lse = lse;
   P.group = G;
   P.group_pad = pad_group(G);
   P.n_q_heads = shape->n_q_heads;
@@ -504,7 +523,38 @@ extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_vie
     FS_PREFILL_CASE(4, 4);
     FS_PREFILL_CASE(8, 1);
     FS_PREFILL_CASE(8, 2);
-    default: return fs::fail(FS_EINVAL, "fs_prefill_attention: no kernel for prefill_waves %d, prefill_col_tiles %d", waves, ct);
+    default: return fs::fail(FS_EINVAL, "%s: no kernel for prefill_waves %d, prefill_col_tiles %d", who, waves, ct);
   }
 #undef FS_PREFILL_CASE
 }
+
+}  // namespace
+
+extern "C" fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* kv,
+                                          const fs_prefill_item* items_dev, const int32_t* sched_dev,
+                                          int64_t n_items, int32_t tile_tokens, float* part_o, float* part_lse,
+                                          void* stream) {
+  return prefill_launch("fs_prefill_attention", shape, kv, items_dev, sched_dev, n_items, tile_tokens, part_o, part_lse, true,
+                        nullptr, nullptr, nullptr, stream);
+}
+
+extern "C" fs_status fs_prefill_attention_fused(const fs_shape* shape, const fs_kv_view* kv,
+                                                const fs_prefill_item* items_dev, const int32_t* sched_dev,
+                                                int64_t n_items, int32_t tile_tokens,
+                                                const int64_t* chunk_indptr_dev, int64_t n_tiles,
+                                                const int64_t* out_indptr_dev, float* part_o, float* part_lse,
+                                                float* out, float* lse, void* stream) {
+  const char* who = "fs_prefill_attention_fused";
+  if (n_tiles < 0 || n_tiles > n_items) return fs::fail(FS_EINVAL, "%s: n_tiles %lld outside [0, n_items]", who,
+                                                        static_cast<long long>(n_tiles));
+  if (n_items > 0 && (n_tiles == 0 || !chunk_indptr_dev || !out_indptr_dev || !out || !lse || (reinterpret_cast<uintptr_t>(out) & 15)))
+    return fs::fail(FS_EINVAL, "%s: no tiles, or chunk_indptr_dev, out_indptr_dev, out or lse is NULL, or out is not 16-byte aligned", who);
+  const bool split = n_items > n_tiles;          // some tile has more than one chunk: partial rows and a merge
+  const fs_status st = prefill_launch(who, shape, kv, items_dev, sched_dev, n_items, tile_tokens, part_o, part_lse, split,
+                                      out_indptr_dev, out, lse, stream);
+  if (st != FS_OK || n_items == 0 || !split) return st;
+  const int G = shape->n_q_heads / shape->n_kv_heads;
+  return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_tiles, tile_tokens * G, out, lse, /*skip_single=*/true,
+                              stream);
+}
+

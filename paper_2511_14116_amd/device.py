@@ -134,8 +134,12 @@ class DeviceShare:
         self.merge()
 
     # ---- chunked prefill: same Q / pool / page-table plumbing, another list and output shape ----
-    def set_prefill_worklist(self, items: np.ndarray, sched: np.ndarray, chunk_indptr: np.ndarray, tile_tokens: int):
-        """Upload a prefill item list and size the partial and final outputs for it."""
+    def set_prefill_worklist(self, items: np.ndarray, sched: np.ndarray, chunk_indptr: np.ndarray, tile_tokens: int,
+                             out_indptr: np.ndarray | None = None):
+        """Upload a prefill item list and size the partial and final outputs for it.  ``out_indptr`` (first final
+        row of every pair) is what the one-call form needs on top."""
+        if out_indptr is not None:
+            self.prefill_out_indptr = torch.from_numpy(np.ascontiguousarray(out_indptr)).to(self.device)
         dev = self.device
         self.n_prefill_items = len(items)
         self.n_prefill_tiles = len(chunk_indptr) - 1
@@ -149,6 +153,14 @@ class DeviceShare:
         self.prefill_part_lse = torch.full((self.n_prefill_items * T,), float("nan"), dtype=torch.float32, device=dev)
         self.prefill_out = torch.full((self.n_prefill_tiles * T, D), float("nan"), dtype=torch.float32, device=dev)
         self.prefill_lse = torch.full((self.n_prefill_tiles * T,), float("nan"), dtype=torch.float32, device=dev)
+
+    def prefill_fused(self, use_sched: bool = True):
+        """Attention and merge in one call; tiles of one chunk get their final rows from the kernel."""
+        B.fs_prefill_attention_fused(self.shape, self.view, self.prefill_items, self.prefill_sched if use_sched else None,
+                                     self.n_prefill_items, self.prefill_tile_tokens, self.prefill_chunk_indptr,
+                                     self.n_prefill_tiles, self.prefill_out_indptr, self.prefill_part_o,
+                                     self.prefill_part_lse, self.prefill_out, self.prefill_lse,
+                                     torch.cuda.current_stream().cuda_stream)
 
     def prefill(self, use_sched: bool = True):
         """Per-item partials, then the split-K merge (the same fs_merge_lse the decode path uses)."""

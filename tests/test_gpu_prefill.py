@@ -73,11 +73,37 @@ def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched
     q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
     q = make_prefill_q(seed, int(q_indptr[-1]), Hq, 128)
     ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave, v_range=v_range)
-    ds.set_prefill_worklist(items, sched, chunk_indptr, tile)
+    ds.set_prefill_worklist(items, sched, chunk_indptr, tile, out_indptr)
     ds.prefill(use_sched=use_sched)
     torch.cuda.synchronize()
     ds.w_items, ds.tile = w_items, tile
+    if len(items):
+        check_one_call_form(ds, chunk_indptr, use_sched)
     return ds, kv, q, q_indptr, w_pairs, out_indptr
+
+
+def check_one_call_form(ds, chunk_indptr, use_sched=True):
+    """fs_prefill_attention_fused on the list that ``ds`` has just run the two-call way: the same final bits, the
+    same partial rows for split tiles, none written for a tile that is one chunk."""
+    want = [t.clone() for t in (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse)]
+    counts = np.diff(chunk_indptr)
+    split_rows = torch.from_numpy(np.repeat(np.repeat(counts > 1, counts), ds.prefill_tile_rows)).to(ds.device)
+    for t in (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse):
+        t.fill_(float("nan"))
+    ds.prefill_fused(use_sched=use_sched)
+    torch.cuda.synchronize()
+    bad = (~((ds.prefill_out == want[2]).all(dim=1) & (ds.prefill_lse == want[3]))).nonzero().flatten().cpu().numpy()
+    if len(bad):
+        T = ds.prefill_tile_rows
+        r = int(bad[0])
+        raise AssertionError(f"the one-call form leaves other final rows: {len(bad)} rows, first {r} (tile {r // T} of "
+                             f"{counts[r // T]} chunks, row {r % T} of {T}); lse {float(ds.prefill_lse[r])} vs "
+                             f"{float(want[3][r])}; out[:4] {ds.prefill_out[r, :4].tolist()} vs {want[2][r, :4].tolist()}; "
+                             f"tiles hit {sorted(set((bad // T).tolist()))[:12]}")
+    assert torch.equal(ds.prefill_part_lse[split_rows], want[1][split_rows]) and torch.equal(ds.prefill_part_o[split_rows], want[0][split_rows])
+    assert torch.isnan(ds.prefill_part_lse[~split_rows]).all(), "the one-call form wrote partial rows of an unsplit tile"
+    ds.prefill(use_sched=use_sched)            # leave the buffers as the two calls leave them (callers look at partial rows)
+    torch.cuda.synchronize()
 
 
 def compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, out_indptr):
@@ -265,7 +291,9 @@ def test_hip_graph_replays_match_eager():
 @pytest.mark.parametrize("waves,ct,wide", [(8, 1, 0), (4, 2, 0), (8, 1, 1)])
 def test_repeated_launches_agree_bit_for_bit(waves, ct, wide):
     """Launches on the same inputs must leave the same bits in every launch shape (fixed order of sums, no
-    atomics on data): a difference means a race between the workgroup's stages."""
+    atomics on data): a difference means a race between the workgroup's stages, or a matrix-core result read
+    before the instruction that writes it has finished (the running reference maximum then comes out of
+    whatever the registers held, which moves the rounding of a whole row)."""
     say(f"prefill: repeated launches, waves={waves} ct={ct} wide={wide}")
     fs.fs_set_option("prefill_waves", waves); fs.fs_set_option("prefill_col_tiles", ct)
     try:
@@ -284,6 +312,28 @@ def test_repeated_launches_agree_bit_for_bit(waves, ct, wide):
             for name, a, b in zip(("part_o", "part_lse", "out", "lse"), first,
                                   (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse)):
                 assert torch.equal(a, b), f"launch {rep}: {name} differs from the first launch"
+    finally:
+        fs.fs_set_option("prefill_waves", 8); fs.fs_set_option("prefill_col_tiles", 1)
+
+
+@pytest.mark.parametrize("waves,ct", [(8, 1), (4, 1), (4, 2)])
+def test_scores_that_jump_far_above_the_reference_maximum(waves, ct):
+    """The kernel keeps a row's reference maximum lazily (it follows the running maximum only when that gets
+    2^8 ahead).  Keys 96..127 of every pair are 32 times larger than the rest, so their scores lie tens of
+    powers of two above everything seen before them: the reference must move there, or the weights overflow."""
+    say(f"prefill: score jump, waves={waves} ct={ct}")
+    fs.fs_set_option("prefill_waves", waves); fs.fs_set_option("prefill_col_tiles", ct)
+    try:
+        def louder_keys(kv):
+            for p in range(len(kv["page_indptr"]) - 1):
+                first = int(kv["page_indptr"][p])
+                slots = kv["page_ids"][first + 6:first + 8]
+                kv["k_pool"][slots] += np.uint16(5 << 7)          # bf16 exponent + 5
+        owner = np.zeros((3, 2), dtype=np.int32)
+        for chunk in (0, 64):
+            ds, kv, q, q_indptr, pairs, oi = run_share(321, [200, 128, 90], [40, 3, 70], 16, 2, owner, 0, 1, chunk=chunk,
+                                                       kv_edit=louder_keys)
+            compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"score jump {waves}x{ct} chunk={chunk}", oi)
     finally:
         fs.fs_set_option("prefill_waves", 8); fs.fs_set_option("prefill_col_tiles", 1)
 
@@ -345,9 +395,10 @@ def test_bench_batch_full_size_sampled():
     q_indptr = np.concatenate([[0], np.cumsum(w["n_new"])]).astype(np.int64)
     q = make_prefill_q(w["seed"], int(q_indptr[-1]), shape.n_q_heads, 128)
     ds = DeviceShare(shape, q, kv, SCALE)
-    ds.set_prefill_worklist(items, w["sched"], w["chunk_indptr"], w["tile"])
+    ds.set_prefill_worklist(items, w["sched"], w["chunk_indptr"], w["tile"], w["out_indptr"])
     ds.prefill()
     torch.cuda.synchronize()
+    check_one_call_form(ds, w["chunk_indptr"])
     out, lse = ds.prefill_out.cpu().numpy(), ds.prefill_lse.cpu().numpy()
     assert np.isfinite(out).all() and np.isfinite(lse).all()
     pr = np.stack([pairs[n] for n in oracle.PREFILL_PAIR_FIELDS], axis=1)

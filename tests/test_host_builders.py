@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
         header = f.read()
     declared = set(re.findall(r"FS_API[^;(]*?\b(fs_[a-z_0-9]+)\s*\(", header))
     assert {"fs_build_placement", "fs_build_placement_hybrid_heads", "fs_build_worklist", "fs_choose_chunk_tokens", "fs_decode_attention",
-            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_decode_attention_units", "fs_build_worklist_units", "fs_build_launch_records", "fs_decode_attention_records", "fs_pack_kv_slots", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention",
+            "fs_decode_attention_persistent", "fs_decode_attention_fused", "fs_decode_attention_units", "fs_build_worklist_units", "fs_build_launch_records", "fs_decode_attention_records", "fs_pack_kv_slots", "fs_merge_lse", "fs_build_prefill_worklist", "fs_prefill_attention", "fs_prefill_attention_fused", "fs_choose_prefill_chunk",
             "fs_route_request", "fs_route_requests", "fs_schedule_prefill", "fs_plan_kv_reload", "fs_replace_failed_gpu", "fs_plan_ffn_reload", "fs_kv_elem_offset", "fs_stream_read_probe", "fs_set_option", "fs_get_option", "fs_last_error",
             "fs_abi_version"} <= declared
     lib = C.CDLL(fs.library_path())
@@ -280,6 +280,11 @@ def test_device_entry_points_validate_before_touching_the_gpu():
         with pytest.raises(fs.FsError) as e:
             fs.fs_prefill_attention(sh, bad, dummy, None, 1, 1, dummy, dummy)
         assert e.value.status == fs.FS_EINVAL and field in str(e.value)
+    fs.fs_prefill_attention_fused(sh, kv, None, None, 0, 1, None, 0, None, None, None, None, None)     # empty list: no-op
+    for n_items, n_tiles in ((3, 4), (3, 0), (3, 2)):
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_prefill_attention_fused(sh, kv, None, None, n_items, 1, None, n_tiles, None, None, None, None, None)
+        assert e.value.status == fs.FS_EINVAL
     with pytest.raises(fs.FsError) as e:
         fs.fs_merge_lse(None, None, None, 4, 2, 64, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
