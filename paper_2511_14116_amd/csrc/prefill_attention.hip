@@ -407,22 +407,27 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
   float* const dst_o = direct ? P.out : P.part_o;
   float* const dst_lse = direct ? P.lse : P.part_lse;
   const int64_t row0 = direct ? P.out_indptr[it.pair] + static_cast<int64_t>(it.q_begin) * G : static_cast<int64_t>(it.part_row);
+  // The lane's place is worked out again, from the lane counter: values derived from threadIdx before the walk
+  // would be kept alive across it, in registers the walk does not have (they went to scratch memory).
+  const int lane_w = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int col_w = lane_w & 15, kb_w = lane_w >> 4;
+  const int g_w = col_w % Gp, tl_w = col_w / Gp;
 #pragma unroll
   for (int t = 0; t < CT; ++t) {
-    const int tok = tok0 + t * tpc + tl;
+    const int tok = tok0 + t * tpc + tl_w;
     const float l_tot = st[t].l[0];
-    if (g >= G || tok >= P.tile_tokens) continue;          // no such row in the buffers
-    const int64_t row = row0 + static_cast<int64_t>(tok) * G + g;
-    float* o = dst_o + row * fs::kHeadDim + 4 * kb;
+    if (g_w >= G || tok >= P.tile_tokens) continue;          // no such row in the buffers
+    const int64_t row = row0 + static_cast<int64_t>(tok) * G + g_w;
+    float* o = dst_o + row * fs::kHeadDim + 4 * kb_w;
     if (tok < n_tok) {
       const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;  // a row that saw none of the item's keys: out = 0, lse = -inf
 #pragma unroll
       for (int b = 0; b < 8; ++b) *reinterpret_cast<f32x4*>(o + 16 * b) = st[t].acc[b] * inv;
-      if (kb == 0) dst_lse[row] = l_tot > 0.f ? (st[t].m + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      if (kb_w == 0) dst_lse[row] = l_tot > 0.f ? (st[t].m + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
     } else {                                               // padding row of a short last tile
 #pragma unroll
       for (int b = 0; b < 8; ++b) *reinterpret_cast<f32x4*>(o + 16 * b) = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (kb == 0) dst_lse[row] = 0.f;
+      if (kb_w == 0) dst_lse[row] = 0.f;
     }
   }
 }
