@@ -74,6 +74,10 @@ def main() -> int:
     ap.add_argument("--chunked", action="store_true", help="the chunked list (fs_build_worklist) whatever the share's size")
     ap.add_argument("--no-records", action="store_true",
                     help="hand the kernels the items (they look each one up themselves) instead of launch records")
+    ap.add_argument("--merge-kernel", action="store_true",
+                    help="launch records: merge split pairs with a second kernel also where the default merges inside the sweep")
+    ap.add_argument("--merge-in-sweep", action="store_true",
+                    help="launch records: merge split pairs inside the sweep also on equal runs (default there: a second kernel)")
     ap.add_argument("--two-calls", action="store_true",
                     help="the step calls fs_decode_attention[_persistent] and fs_merge_lse instead of fs_decode_attention_fused")
     ap.add_argument("--placement", choices=["requests", "heads"], default="requests",
@@ -262,6 +266,11 @@ def main() -> int:
               file=sys.stderr)
         return 2
     claim = torch.zeros(2, dtype=torch.int32, device=dev)    # the persistent sweep's counters; every launch leaves them at zero
+    pair_counters = torch.zeros(n_pairs, dtype=torch.int32, device=dev)   # one per pair for the merge inside the sweep; likewise
+    # Split pairs merged by the sweep itself (no second kernel): pays on a short launch (config 3: 21.9 -> 18.9 us per
+    # step), where the merge kernel's launch is a third of the time; on the equal-run sweeps of the large shares the
+    # hand-over at the end of every workgroup's life costs what the second launch cost (config 2: 313.8 against 312.9).
+    merge_in_sweep = args.merge_in_sweep or (not units and not args.merge_kernel)
     # Launch records: the host resolves every item (page-table offset, chunk count, first slots) while it builds the
     # list, so a workgroup starts with one read instead of four dependent ones.  The counter form takes items only.
     use_records = not args.no_records and not persistent and not args.two_calls
@@ -278,10 +287,11 @@ def main() -> int:
             if use_records:
                 ui = (base + off_sched) if units else None
                 dec.append(fs.bind_decode_attention_records(shape, ds.view, base + off_records2, n_items, ui, n_units if units else 0,
-                                                            None, 0, part_o, part_lse, out, lse, stream_ptr))
+                                                            None, 0, part_o, part_lse, out, lse, None, stream_ptr))
                 mrg.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"], out, lse, stream_ptr))
                 fused.append(fs.bind_decode_attention_records(shape, ds.view, base + off_records, n_items, ui, n_units if units else 0,
-                                                              base + off_indptr, n_pairs, part_o, part_lse, out, lse, stream_ptr))
+                                                              base + off_indptr, n_pairs, part_o, part_lse, out, lse,
+                                                              pair_counters if merge_in_sweep else None, stream_ptr))
                 continue
             if units:
                 dec.append(fs.bind_decode_attention_units(shape, ds.view, base + off_items, n_items, base + off_sched, n_units,
@@ -598,7 +608,9 @@ def main() -> int:
                    "step_calls": "fs_build_launch_records + fs_decode_attention_records" if use_records else
                                  ("fs_decode_attention_units" + (" (sweep alone) + fs_merge_lse" if args.two_calls else "")) if units else
                                  ("fs_decode_attention[_persistent] + fs_merge_lse" if args.two_calls else "fs_decode_attention_fused"),
-                   "merge_launched": bool(args.two_calls or n_items > n_pairs),
+                   "merge_launched": bool(args.two_calls or (n_items > n_pairs and not (use_records and merge_in_sweep))),
+                   "split_pairs_merged": "by a merge kernel" if (args.two_calls or not use_records or not merge_in_sweep) else
+                                         "inside the sweep, by the workgroup that writes a pair's last partial rows",
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),
                    "kv_layout": "separate" if args.separate_kv else "interleaved",

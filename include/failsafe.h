@@ -523,9 +523,11 @@ typedef struct {
   int32_t q_row;           /* first query row, as in the item                                */
   int32_t row;             /* first partial row (part_row); or, for an item that is all of
                               its pair, -(pair*G) - 1: its rows are the pair's final rows    */
-  int32_t reserved0;       /* 0                                                              */
+  int32_t n_chunks;        /* chunks (items) of the item's pair                              */
   int32_t first_slots[8];  /* page_ids[first_page + j], j = 0..7 (0 beyond the last page)    */
-  int32_t reserved1[2];    /* 0                                                              */
+  int32_t pair;            /* the item's pair                                                */
+  int32_t pair_row;        /* first partial row of the pair's first chunk:
+                              chunk_indptr[pair] * G (chunk c's rows start G*c further on)   */
 } fs_launch_record;        /* 64 bytes; arrays of these are compared bit for bit             */
 
 /* fs_build_launch_records - record k describes item order[k] (order == NULL: item k).
@@ -540,7 +542,8 @@ typedef struct {
  *  records      HOST out [n_items]
  *
  * FS_EINVAL: NULL pointer, negative counts, an order entry or a pair outside its range, an item
- * whose pages do not lie inside its pair's part of the page table. */
+ * whose pages do not lie inside its pair's part of the page table, or whose part_row is not
+ * (chunk_indptr[pair] + chunk) * G (the rows the merge reads). */
 FS_API fs_status fs_build_launch_records(const fs_shape* shape, const fs_work_item* items, const int32_t* order,
                                          int64_t n_items, const int64_t* chunk_indptr, int64_t n_pairs,
                                          const int64_t* page_indptr, const int32_t* page_ids, int64_t n_page_ids,
@@ -561,14 +564,22 @@ FS_API fs_status fs_build_launch_records(const fs_shape* shape, const fs_work_it
  *                    with direct_rows == 0 send all of them to part_o/part_lse)
  *  part_o, part_lse  DEVICE scratch [n_items*G][head_dim], [n_items*G]; may be NULL when n_items == n_pairs
  *  out, lse          DEVICE out
+ *  pair_counters_dev DEVICE scratch [n_pairs] int32, or NULL.  Given (with chunk_indptr_dev): split pairs are
+ *                    merged inside the sweep and no merge kernel is launched - every workgroup that has
+ *                    written partial rows of a split pair counts itself in on the pair's counter, and the one
+ *                    that completes the count merges the pair's chunks into its final rows (nobody waits).
+ *                    The counters must all be zero when the call is made; every call leaves them zero
+ *                    (a launch that did not run to its end may not).  Calls that share counters must not
+ *                    overlap.  Same bits in out/lse as with NULL.
  *
  * The page table of kv must be the one the records were built from.  Errors as for
- * fs_decode_attention_fused. */
+ * fs_decode_attention_fused; FS_EINVAL also for pair_counters_dev without chunk_indptr_dev. */
 FS_API fs_status fs_decode_attention_records(const fs_shape* shape, const fs_kv_view* kv,
                                              const fs_launch_record* records_dev, int64_t n_items,
                                              const int64_t* unit_indptr_dev, int64_t n_units,
                                              const int64_t* chunk_indptr_dev, int64_t n_pairs,
-                                             float* part_o, float* part_lse, float* out, float* lse, void* stream);
+                                             float* part_o, float* part_lse, float* out, float* lse,
+                                             int32_t* pair_counters_dev, void* stream);
 
 /* ---------------------------------------------------------------------------
  * fs_decode_attention_fused_static - fs_decode_attention_fused for callers that cannot allocate

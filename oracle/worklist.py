@@ -137,9 +137,13 @@ def build_launch_records(items, order, chunk_indptr, page_indptr, page_ids, grou
         3     q_row       as in the item
         4     row         part_row; or, with ``direct_rows`` and a pair that is this one item,
                           -(pair*group) - 1: the item's rows are the pair's final rows
-        5     0
+        5     n_chunks    chunks (items) of the item's pair
         6-13  page_ids[first_page + j] for j = 0..7 (0 beyond the item's last page)
-        14-15 0
+        14    pair
+        15    pair_row    first partial row of the pair's first chunk, chunk_indptr[pair] * group (what a
+                          kernel that merges a pair itself needs to find the other chunks' rows)
+
+    An item must sit where the merge will look for it: part_row = (chunk_indptr[pair] + chunk) * group.
     """
     n = len(items)
     order = range(n) if order is None else [int(i) for i in order]
@@ -151,8 +155,14 @@ def build_launch_records(items, order, chunk_indptr, page_indptr, page_ids, grou
         rec[k, 0:2] = np.array([first_page], dtype=np.int64).view(np.int32)
         rec[k, 2] = te - tb
         rec[k, 3] = q_row
-        single = int(chunk_indptr[pair + 1]) - int(chunk_indptr[pair]) == 1
-        rec[k, 4] = -(pair * group) - 1 if (direct_rows and single) else part_row
+        c0 = int(chunk_indptr[pair])
+        n_chunks = int(chunk_indptr[pair + 1]) - c0
+        if not 0 <= c < n_chunks or part_row != (c0 + c) * group:
+            raise ValueError("item is not at row (chunk_indptr[pair] + chunk) * group")
+        rec[k, 4] = -(pair * group) - 1 if (direct_rows and n_chunks == 1) else part_row
+        rec[k, 5] = n_chunks
+        rec[k, 14] = pair
+        rec[k, 15] = c0 * group
         for j in range(min(8, n_pages)):
             rec[k, 6 + j] = int(page_ids[first_page + j])
     return rec

@@ -29,6 +29,7 @@
 #include <type_traits>
 
 #include "fs_internal.h"
+#include "merge_row.h"
 
 namespace {
 
@@ -64,6 +65,10 @@ struct DecodeParams {
   const int64_t* __restrict__ chunk_indptr;
   float* __restrict__ out;
   float* __restrict__ lse;
+  // One counter per pair, zero between launches (else NULL): a workgroup that has written partial rows of a
+  // split pair counts itself in, and the one that completes the pair merges it on the spot (arrive_and_merge),
+  // so that no merge kernel has to follow the sweep.
+  int32_t* pair_counters;
   int32_t group;
   float scale_log2;   // sm_scale * log2(e): scores live in the log2 domain
 };
@@ -190,6 +195,7 @@ struct ItemDesc {
   int n_mine;           // pages of the item this wavefront takes
   int row;              // first partial row of the item, or -(first final row) - 1 when the item is all of its pair (one-call forms)
   int q_row;            // first query row of the item's group
+  int pair, n_chunks, pair_row;   // the item's pair, its chunk count and the first partial row of its first chunk (n_chunks = 1 when unknown)
   int32_t first_ids[3]; // slots of this wavefront's first pages (those the prologue fetches), asked for with the rest
   bf16x8 q[4];          // Q^T operand of this lane (load_desc_q; bf16 kernels)
   bool valid;
@@ -210,6 +216,9 @@ __device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k,
   d.n_mine = 0;
   d.row = 0;
   d.q_row = 0;
+  d.pair = 0;
+  d.n_chunks = 1;
+  d.pair_row = 0;
 #pragma unroll
   for (int u = 0; u < 3; ++u) d.first_ids[u] = 0;
 #pragma unroll
@@ -225,6 +234,9 @@ __device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k,
       d.n_tok = __builtin_amdgcn_readfirstlane(rec->n_tok);
       d.q_row = __builtin_amdgcn_readfirstlane(rec->q_row);
       d.row = __builtin_amdgcn_readfirstlane(rec->row);
+      d.pair = __builtin_amdgcn_readfirstlane(rec->pair);
+      d.n_chunks = __builtin_amdgcn_readfirstlane(rec->n_chunks);
+      d.pair_row = __builtin_amdgcn_readfirstlane(rec->pair_row);
 #pragma unroll
       for (int u = 0; u < NBUF - 1; ++u)           // the record holds the item's first eight slots
         if (wave + u * WAVES < 8) rec_slot[u] = __builtin_amdgcn_readfirstlane(rec->first_slots[wave + u * WAVES]);
@@ -238,9 +250,12 @@ __device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k,
       d.q_row = __builtin_amdgcn_readfirstlane(it.q_row);
       d.row = __builtin_amdgcn_readfirstlane(it.part_row);
       first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+      d.pair = it.pair;
       if (P.chunk_indptr) {
-        const int32_t n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - P.chunk_indptr[it.pair]));
-        if (n_chunks == 1) d.row = -(it.pair * G) - 1;
+        const int64_t c0 = P.chunk_indptr[it.pair];
+        d.n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - c0));
+        d.pair_row = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(c0) * G);
+        if (d.n_chunks == 1) d.row = -(it.pair * G) - 1;
       }
     }
     d.page_lo = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page));
@@ -283,12 +298,76 @@ __device__ __forceinline__ RowDest row_dest(const DecodeParams& P, int row) {
   return RowDest{P.part_o, P.part_lse, row};
 }
 
+// A partial row on its way to the workgroup that will merge its pair inside the same launch: relaxed atomic stores
+// at device scope, which are written through to memory instead of waiting in this XCD's L2 (the other workgroup
+// may run on another XCD, whose L2 is not this one's).
+__device__ __forceinline__ void store_f32_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_f32x4_coherent(float* p, const f32x4 v) {
+  auto* q = reinterpret_cast<unsigned long long*>(p);
+  const unsigned long long lo = (static_cast<unsigned long long>(__float_as_uint(v[1])) << 32) | __float_as_uint(v[0]);
+  const unsigned long long hi = (static_cast<unsigned long long>(__float_as_uint(v[3])) << 32) | __float_as_uint(v[2]);
+  __hip_atomic_store(q, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(q + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Split pairs merged inside the sweep.  The workgroup has just issued the stores of the partial rows of `n` items
+// (s_pair/s_chunks/s_prow[j]: pair, chunk count and first partial row of the pair of item j; s_chunks[j] = 1: not
+// split, nothing to do).  One thread per item counts the workgroup in on the pair's counter; the workgroup that
+// brings a counter to the pair's chunk count is the last writer of that pair: it puts the counter back to zero for
+// the next launch and merges the pair's chunks into its final rows, one wavefront per q-head, with the routine of
+// the merge kernel (same bits).  Nobody waits for anybody.
+// What makes the other workgroups' rows visible, without fences (a device-scope fence writes back and invalidates
+// the whole L2 of the XCD, which on the 70B-shaped batch cost the sweep 150 us): partial rows are stored
+// (store_f32*_coherent) and read (merge_rows<.., COHERENT>) as relaxed device-scope atomics, which go to memory
+// past the caches, as the counter's atomic does; a thread counts in only after all the workgroup's stores have been
+// acknowledged (vmcnt(0) in every thread, then the barrier), and the merging workgroup reads only after its atomic
+// has returned the full count, i.e. after every other writer's atomic, each issued after its own stores were done.
+// Takes the workgroup's barriers: every thread must call it.
+template <int WAVES>
+__device__ __forceinline__ void arrive_and_merge(const DecodeParams& P, int n, const int* s_pair, const int* s_chunks,
+                                                 const int* s_prow, int* s_done, int G, int wave, int lane) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this thread's stores have reached memory
+  __syncthreads();
+  for (int j = threadIdx.x; j < n; j += WAVES * 64) {
+    const int c = s_chunks[j];
+    s_done[j] = c > 1 && __hip_atomic_fetch_add(P.pair_counters + s_pair[j], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == c - 1;
+  }
+  __syncthreads();
+  for (int j = 0; j < n; ++j) {
+    if (!__builtin_amdgcn_readfirstlane(s_done[j])) continue;
+    const int pair = __builtin_amdgcn_readfirstlane(s_pair[j]);
+    const int chunks = __builtin_amdgcn_readfirstlane(s_chunks[j]);
+    const int prow = __builtin_amdgcn_readfirstlane(s_prow[j]);
+    if (threadIdx.x == 0) __hip_atomic_store(P.pair_counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float* po = P.part_o;
+    const float* pl = P.part_lse;
+    for (int g = wave; g < G; g += WAVES)
+      fs_merge::merge_rows<1, true, true>(po, pl, prow / G, chunks, G, g, P.out + (static_cast<int64_t>(pair) * G + g) * fs::kHeadDim,
+                              P.lse + static_cast<int64_t>(pair) * G + g, lane);
+  }
+}
+
+// The same for the one item of a workgroup that has no more than that.
+template <int WAVES>
+__device__ __forceinline__ void arrive_and_merge_one(const DecodeParams& P, const ItemDesc& d, int* s_meta, int G, int wave,
+                                                     int lane) {
+  if (P.pair_counters == nullptr || d.n_chunks <= 1) return;     // the same for the whole workgroup
+  if (threadIdx.x == 0) {
+    s_meta[0] = d.pair;
+    s_meta[1] = d.n_chunks;
+    s_meta[2] = d.pair_row;
+  }
+  arrive_and_merge<WAVES>(P, 1, s_meta, s_meta + 1, s_meta + 2, s_meta + 3, G, wave, lane);
+}
+
 // Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.
 template <int WAVES>
 __device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_total, int wave, int lane,
                                                 int G, float* __restrict__ part_o,
                                                 float* __restrict__ part_lse, int part_row,
-                                                float* sm_o, float* sm_m, float* sm_l) {
+                                                float* sm_o, float* sm_m, float* sm_l, bool coherent) {
   const int qi = lane & 15, kb = lane >> 4;
   if (lane < 16) {
     sm_m[wave * 16 + lane] = st.m;
@@ -314,8 +393,15 @@ __device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_
     const float inv = 1.0f / L;
     // Streaming stores: the partial rows are read once, by the merge.  Measured on the 70B-shaped
     // batch, plain stores of these 9 MB cost the 2 GB read stream about 20 us, non-temporal ones 13.
-    __builtin_nontemporal_store(o * inv, reinterpret_cast<f32x4*>(part_o + static_cast<int64_t>(part_row + q) * fs::kHeadDim + 4 * d4));
-    if (d4 == 0) __builtin_nontemporal_store((M + __builtin_amdgcn_logf(L)) * kLn2, part_lse + part_row + q);
+    float* dst = part_o + static_cast<int64_t>(part_row + q) * fs::kHeadDim + 4 * d4;
+    const float lse_q = (M + __builtin_amdgcn_logf(L)) * kLn2;
+    if (coherent) {      // rows another workgroup of this launch will merge (arrive_and_merge)
+      store_f32x4_coherent(dst, o * inv);
+      if (d4 == 0) store_f32_coherent(part_lse + part_row + q, lse_q);
+    } else {
+      __builtin_nontemporal_store(o * inv, reinterpret_cast<f32x4*>(dst));
+      if (d4 == 0) __builtin_nontemporal_store(lse_q, part_lse + part_row + q);
+    }
   }
 }
 
@@ -324,6 +410,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
   __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
   __shared__ float sm_m[WAVES * 16];
   __shared__ float sm_l[WAVES * 16];
+  __shared__ int s_meta[4];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -368,7 +455,9 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodePar
 
   const RowDest dst = row_dest(P, d.row);
   const float l_total = sum_xor32(sum_xor16(st.l));
-  merge_and_store<WAVES>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l);
+  merge_and_store<WAVES>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l,
+                         P.pair_counters != nullptr && d.n_chunks > 1);
+  arrive_and_merge_one<WAVES>(P, d, s_meta, G, wave, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -395,8 +484,9 @@ __device__ __forceinline__ void lds_barrier() {
 // UNITS = true is the form without a counter: workgroup u walks the items [unit_indptr[u], unit_indptr[u+1]) of a
 // list that the host has cut into equal runs of pages (fs_build_worklist_units), so every workgroup streams
 // the same number of bytes and nothing is handed out at run time; `claim` then carries nothing.
+// (two wavefronts per SIMD - two workgroups per CU - is what the launch counts on: at most 256 registers)
 template <int WAVES, int NBUF, bool UNITS>
-__global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(const DecodeParams P, int n_items,
+__global__ void __launch_bounds__(WAVES * 64, 2) decode_bf16_persistent_kernel(const DecodeParams P, int n_items,
                                                                             int* __restrict__ claim, int n_first,
                                                                             const int64_t* __restrict__ unit_indptr) {
   __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
@@ -406,6 +496,8 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
   __shared__ float st_lse[kStageRows];
   __shared__ int st_row[kStageRows];
   __shared__ int s_next;
+  // what arrive_and_merge needs to know of the items whose rows are staged (at most kStageRows items: G >= 1)
+  __shared__ int st_pair[kStageRows], st_chunks[kStageRows], st_prow[kStageRows], st_done[kStageRows];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -438,7 +530,8 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
   // measurable.)
   const bool second_on_cu = static_cast<int>(blockIdx.x) >= n_first;
   bool keep_claiming = true;
-  int staged = 0;
+  int staged = 0, staged_items = 0;
+  bool staged_split = false;       // some staged item belongs to a split pair
   for (;;) {
     // With equal runs the next item is known from the start: its descriptor and the slots of its first pages are
     // asked for now and travel while the current item streams, so that at the item's end the next pages can be
@@ -525,6 +618,15 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
         st_row[staged + q] = cur.row >= 0 ? cur.row + q : cur.row - q;
       }
     }
+    if (P.pair_counters != nullptr) {
+      if (threadIdx.x == 0) {
+        st_pair[staged_items] = cur.pair;
+        st_chunks[staged_items] = cur.n_chunks;
+        st_prow[staged_items] = cur.pair_row;
+      }
+      staged_split |= cur.n_chunks > 1;
+    }
+    ++staged_items;
     staged += G;
     lds_barrier();                     // staging rows complete; the merge buffers may be reused
     const bool last = !nxt.valid;
@@ -533,13 +635,19 @@ __global__ void __launch_bounds__(WAVES * 64) decode_bf16_persistent_kernel(cons
         const int r = idx >> 5, d4 = idx & 31;
         const int row = st_row[r];
         float* dst = row >= 0 ? P.part_o + static_cast<int64_t>(row) * fs::kHeadDim : P.out + static_cast<int64_t>(-row - 1) * fs::kHeadDim;
-        __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(st_o + r * fs::kHeadDim + 4 * d4), reinterpret_cast<f32x4*>(dst + 4 * d4));
+        const f32x4 v = *reinterpret_cast<const f32x4*>(st_o + r * fs::kHeadDim + 4 * d4);
+        if (row >= 0 && P.pair_counters != nullptr) store_f32x4_coherent(dst + 4 * d4, v);     // rows for arrive_and_merge
+        else __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + 4 * d4));
       }
       for (int r = threadIdx.x; r < staged; r += WAVES * 64) {
         const int row = st_row[r];
-        __builtin_nontemporal_store(st_lse[r], row >= 0 ? P.part_lse + row : P.lse + (-row - 1));
+        if (row >= 0 && P.pair_counters != nullptr) store_f32_coherent(P.part_lse + row, st_lse[r]);
+        else __builtin_nontemporal_store(st_lse[r], row >= 0 ? P.part_lse + row : P.lse + (-row - 1));
       }
+      if (staged_split) arrive_and_merge<WAVES>(P, staged_items, st_pair, st_chunks, st_prow, st_done, G, wave, lane);
       staged = 0;
+      staged_items = 0;
+      staged_split = false;
       // the next write into the staging rows comes after the next item's first barrier, which every
       // thread reaches only when it is done reading them here
     }
@@ -614,6 +722,7 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
   __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 8 * GMAX * kORow];
   __shared__ float sm_m[WAVES * 8 * GMAX];
   __shared__ float sm_l[WAVES * 8 * GMAX];
+  __shared__ int s_meta[4];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -753,9 +862,17 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
       }
     }
     const float inv = 1.0f / L;
-    __builtin_nontemporal_store(acc * inv, reinterpret_cast<f32x4*>(dst.o + static_cast<int64_t>(dst.row + g) * fs::kHeadDim + 4 * d4));
-    if (d4 == 0) __builtin_nontemporal_store((M + __builtin_amdgcn_logf(L)) * kLn2, dst.lse + dst.row + g);
+    float* to = dst.o + static_cast<int64_t>(dst.row + g) * fs::kHeadDim + 4 * d4;
+    const float lse_g = (M + __builtin_amdgcn_logf(L)) * kLn2;
+    if (P.pair_counters != nullptr && d.n_chunks > 1) {      // rows another workgroup of this launch will merge
+      store_f32x4_coherent(to, acc * inv);
+      if (d4 == 0) store_f32_coherent(dst.lse + dst.row + g, lse_g);
+    } else {
+      __builtin_nontemporal_store(acc * inv, reinterpret_cast<f32x4*>(to));
+      if (d4 == 0) __builtin_nontemporal_store(lse_g, dst.lse + dst.row + g);
+    }
   }
+  arrive_and_merge_one<WAVES>(P, d, s_meta, G, wave, lane);
 }
 
 template <typename K>
@@ -838,6 +955,7 @@ fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, 
   P->part_o = part_o;
   P->part_lse = part_lse;
   P->chunk_indptr = nullptr;
+  P->pair_counters = nullptr;
   P->out = nullptr;
   P->lse = nullptr;
   P->group = G;
@@ -1001,9 +1119,12 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
                                                  const fs_launch_record* records_dev, int64_t n_items,
                                                  const int64_t* unit_indptr_dev, int64_t n_units,
                                                  const int64_t* chunk_indptr_dev, int64_t n_pairs,
-                                                 float* part_o, float* part_lse, float* out, float* lse, void* stream) {
+                                                 float* part_o, float* part_lse, float* out, float* lse,
+                                                 int32_t* pair_counters_dev, void* stream) {
   const char* who = "fs_decode_attention_records";
   const bool sweep_only = chunk_indptr_dev == nullptr;     // no merge: the rows go where the records say
+  if (sweep_only && pair_counters_dev)
+    return fs::fail(FS_EINVAL, "%s: pair_counters_dev without chunk_indptr_dev (a sweep that merges nothing needs no counters)", who);
   if (!sweep_only && (n_pairs < 0 || n_pairs > n_items))
     return fs::fail(FS_EINVAL, "%s: n_pairs %lld outside [0, n_items]", who, static_cast<long long>(n_pairs));
   const bool units = unit_indptr_dev != nullptr;
@@ -1022,6 +1143,13 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
   P.records = records_dev;
   P.out = out;
   P.lse = lse;
+  const bool merge_in_sweep = pair_counters_dev != nullptr && n_items > n_pairs;
+  if (merge_in_sweep) {
+    if (reinterpret_cast<uintptr_t>(pair_counters_dev) & 3)
+      return fs::fail(FS_EINVAL, "%s: pair_counters_dev is not 4-byte aligned", who);
+    if (n_pairs * P.group > 0x7FFFFFFFll) return fs::fail(FS_EINVAL, "%s: n_pairs out of range", who);
+    P.pair_counters = pair_counters_dev;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   fs_status st = FS_OK;
   if (units) {
@@ -1032,7 +1160,7 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
   } else {
     st = launch_plain(who, P, kv->kv_dtype, n_items, s);
   }
-  if (st != FS_OK || sweep_only || n_items == n_pairs) return st;
+  if (st != FS_OK || sweep_only || n_items == n_pairs || merge_in_sweep) return st;
   return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
 }
 

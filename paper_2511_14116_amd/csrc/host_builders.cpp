@@ -375,15 +375,21 @@ extern "C" fs_status fs_build_launch_records(const fs_shape* shape, const fs_wor
     if (first_page < 0 || first_page + n_pages > page_indptr[it.pair + 1] || page_indptr[it.pair + 1] > n_page_ids)
       return fs::fail(FS_EINVAL, "%s: item %lld's pages [%lld, %lld) leave its pair's part of the page table", who,
                       static_cast<long long>(i), static_cast<long long>(first_page), static_cast<long long>(first_page + n_pages));
+    const int64_t c0 = chunk_indptr[it.pair], n_chunks = chunk_indptr[it.pair + 1] - c0;
+    if (n_chunks < 1 || it.chunk < 0 || it.chunk >= n_chunks || (c0 + n_chunks) * G > 0x7FFFFFFFll ||
+        it.part_row != (c0 + it.chunk) * G)
+      return fs::fail(FS_EINVAL, "%s: item %lld (pair %d, chunk %d, part_row %d) does not sit at row (chunk_indptr[pair] + chunk) * G "
+                      "of its pair's %lld chunks", who, static_cast<long long>(i), it.pair, it.chunk, it.part_row,
+                      static_cast<long long>(n_chunks));
     fs_launch_record& r = records[k];
     r.first_page = first_page;
     r.n_tok = it.tok_end - it.tok_begin;
     r.q_row = it.q_row;
-    const bool single = chunk_indptr[it.pair + 1] - chunk_indptr[it.pair] == 1;
-    r.row = (direct_rows && single) ? -(it.pair * G) - 1 : it.part_row;
-    r.reserved0 = 0;
+    r.row = (direct_rows && n_chunks == 1) ? -(it.pair * G) - 1 : it.part_row;
+    r.n_chunks = static_cast<int32_t>(n_chunks);
     for (int j = 0; j < 8; ++j) r.first_slots[j] = j < n_pages ? page_ids[first_page + j] : 0;
-    r.reserved1[0] = r.reserved1[1] = 0;
+    r.pair = it.pair;
+    r.pair_row = static_cast<int32_t>(c0 * G);
   }
   return FS_OK;
 }

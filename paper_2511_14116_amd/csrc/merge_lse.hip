@@ -16,21 +16,11 @@
 #include <hip/hip_runtime.h>
 
 #include "fs_internal.h"
+#include "merge_row.h"
 
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
 
 // RW output rows per wavefront (consecutive rows of one pair, so group must be a multiple of RW): with many
 // rows of few chunks each (a prefill tile's 128 rows, most tiles a single chunk) a wavefront with one row is
@@ -41,7 +31,6 @@ __global__ void __launch_bounds__(kWavesPerBlock * 64)
 merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ part_lse,
                  const int64_t* __restrict__ chunk_indptr, int64_t n_rows, int group,
                  float* __restrict__ out, float* __restrict__ lse, int skip_single) {
-  constexpr int U = RW == 1 ? 4 : 2;               // chunk rows in flight per output row
   const int lane = threadIdx.x & 63;
   const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock +
                         __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * RW;
@@ -51,101 +40,7 @@ merge_lse_kernel(const float* __restrict__ part_o, const float* __restrict__ par
   const int64_t c0 = chunk_indptr[p];
   const int n = static_cast<int>(chunk_indptr[p + 1] - c0);
   if (skip_single && n == 1) return;   // fused decode: the sweep has already written this pair's final rows
-
-  // Chunks are taken 64 at a time (one lse per lane).  The first rows of a batch are requested before
-  // its weights are known, so the two reads travel together; across batches (more than 64 chunks) the
-  // running maximum moves and what has been summed is rescaled, as in an online softmax.
-  float M[RW], sum[RW];
-  float2 acc[RW];
-#pragma unroll
-  for (int r = 0; r < RW; ++r) { M[r] = -INFINITY; sum[r] = 0.f; acc[r] = make_float2(0.f, 0.f); }
-  const int64_t stride = static_cast<int64_t>(group) * (fs::kHeadDim / 2);   // float2 units between chunk rows
-  for (int base = 0; base < n; base += 64) {
-    const int c = base + lane;
-    const int cnt = min(64, n - base);
-    float lv[RW];
-#pragma unroll
-    for (int r = 0; r < RW; ++r) lv[r] = c < n ? part_lse[(c0 + c) * group + g0 + r] : -INFINITY;
-    // row r of chunk base+j: rows[j * stride + r * 64]
-    const float2* rows = reinterpret_cast<const float2*>(part_o + ((c0 + base) * group + g0) * fs::kHeadDim) + lane;
-    float2 o[U][RW];
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int r = 0; r < RW; ++r) o[u][r] = rows[min(u, cnt - 1) * stride + r * 64];   // the batch's first rows (repeats if it has fewer)
-    float w[RW];
-#pragma unroll
-    for (int r = 0; r < RW; ++r) {
-      const float Mb = fmaxf(M[r], wave_max(lv[r]));
-      const float rescale = __expf(M[r] - Mb);          // first batch: exp(-inf) = 0 times zero sums
-      M[r] = Mb;
-      sum[r] *= rescale;
-      acc[r].x *= rescale;
-      acc[r].y *= rescale;
-      w[r] = c < n ? __expf(lv[r] - Mb) : 0.f;
-      sum[r] += w[r];                             // per lane; reduced once at the end
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-#pragma unroll
-      for (int r = 0; r < RW; ++r) {
-        const float wj = u < cnt ? __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w[r]), u)) : 0.f;
-        acc[r].x = fmaf(wj, o[u][r].x, acc[r].x);
-        acc[r].y = fmaf(wj, o[u][r].y, acc[r].y);
-      }
-    }
-    int j = U;
-    // A pair cut into many chunks (a 131072-token context in 1024-token chunks: 128) is one wavefront's
-    // serial walk; sixteen rows in flight instead of four turn its 32 round trips into 8.  Same order of sums.
-    constexpr int D = 16 / RW;
-    for (; j + D <= cnt; j += D) {
-      float2 od[D][RW];
-#pragma unroll
-      for (int u = 0; u < D; ++u)
-#pragma unroll
-        for (int r = 0; r < RW; ++r) od[u][r] = rows[(j + u) * stride + r * 64];
-#pragma unroll
-      for (int u = 0; u < D; ++u) {
-#pragma unroll
-        for (int r = 0; r < RW; ++r) {
-          const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w[r]), j + u));
-          acc[r].x = fmaf(wj, od[u][r].x, acc[r].x);
-          acc[r].y = fmaf(wj, od[u][r].y, acc[r].y);
-        }
-      }
-    }
-    for (; j + U <= cnt; j += U) {
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int r = 0; r < RW; ++r) o[u][r] = rows[(j + u) * stride + r * 64];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int r = 0; r < RW; ++r) {
-          const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w[r]), j + u));
-          acc[r].x = fmaf(wj, o[u][r].x, acc[r].x);
-          acc[r].y = fmaf(wj, o[u][r].y, acc[r].y);
-        }
-      }
-    }
-    for (; j < cnt; ++j) {
-#pragma unroll
-      for (int r = 0; r < RW; ++r) {
-        const float2 oj = rows[j * stride + r * 64];
-        const float wj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w[r]), j));
-        acc[r].x = fmaf(wj, oj.x, acc[r].x);
-        acc[r].y = fmaf(wj, oj.y, acc[r].y);
-      }
-    }
-  }
-#pragma unroll
-  for (int r = 0; r < RW; ++r) {
-    const float total = wave_sum(sum[r]);
-    const float inv = 1.0f / total;
-    reinterpret_cast<float2*>(out + (row0 + r) * fs::kHeadDim)[lane] = make_float2(acc[r].x * inv, acc[r].y * inv);
-    if (lane == 0) lse[row0 + r] = M[r] + __logf(total);
-  }
+  fs_merge::merge_rows<RW>(part_o, part_lse, c0, n, group, g0, out + row0 * fs::kHeadDim, lse + row0, lane);
 }
 
 }  // namespace

@@ -351,6 +351,21 @@ def check_records(ds, kv, items, sched, indptr, what):
     ds.run_records()
     torch.cuda.synchronize()
     assert torch.equal(ds.out, ref[0]) and torch.equal(ds.lse, ref[1]), f"{what}: the records call leaves other final rows"
+    check_merge_in_sweep(ds, ref, False, what)
+
+
+def check_merge_in_sweep(ds, ref, units, what):
+    """The same call with pair counters: split pairs are merged by the workgroup that writes their last partial rows,
+    no merge kernel runs.  Twice in a row (the counters must be back at zero), same bits as ``ref`` = [out, lse]."""
+    for rep in range(2):
+        for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
+            t.fill_(float("nan"))
+        ds.run_records(units=units, merge_in_sweep=True)
+        torch.cuda.synchronize()
+        bad = (~((ds.out == ref[0]).all(dim=1) & (ds.lse == ref[1]))).nonzero().flatten().cpu().numpy()
+        assert len(bad) == 0, (f"{what}: merge inside the sweep (units={units}, call {rep}) leaves other final rows: {len(bad)} rows, "
+                               f"first {int(bad[0])} (pair {int(bad[0]) // ds.group}), lse {float(ds.lse[int(bad[0])])} vs {float(ref[1][int(bad[0])])}")
+        assert int(ds.pair_counters.abs().sum()) == 0, f"{what}: the pair counters are not back at zero after call {rep}"
 
 
 def check_fused(ds, indptr, what):
@@ -472,6 +487,38 @@ def test_hip_graph_replays_match_eager():
         assert torch.equal(ds.out, eager_o)
     ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), w["n_q_heads"], w["group"], w["sm_scale"])
     check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, "graph replay vs oracle")
+
+
+def test_hip_graph_replays_of_the_sweep_that_merges():
+    """fs_decode_attention_records with pair counters (split pairs merged inside the sweep) captured as a HIP
+    graph: the counters go back to zero inside every launch, so replays need nothing cleared between them; every
+    replay, with eager launches of the same call and of the two-call form in between, gives the eager bits."""
+    w = make_requests(1, n_req=24, max_len=2500)
+    q = make_q(w["seed"], 24, w["n_q_heads"], 128)
+    sh = shape_of(w)
+    owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
+    ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 256, owner)
+    eager_o, eager_l = ds.out.clone(), ds.lse.clone()
+    assert ds.n_items > ds.n_pairs
+    ds.set_records(fs.fs_build_launch_records(sh, items, sched, indptr, kv["page_indptr"], kv["page_ids"]))
+    counters = torch.zeros(ds.n_pairs, dtype=torch.int32, device=ds.device)
+    cap = torch.cuda.Stream()
+    call = fs.bind_decode_attention_records(sh, ds.view, ds.records, ds.n_items, None, 0, ds.chunk_indptr, ds.n_pairs,
+                                            ds.part_o, ds.part_lse, ds.out, ds.lse, counters, cap.cuda_stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=cap):
+        call()
+    for rep in range(4):
+        ds.out.fill_(float("nan")); ds.lse.fill_(float("nan")); ds.part_o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ds.out, eager_o) and torch.equal(ds.lse, eager_l), f"replay {rep} differs"
+        assert int(counters.abs().sum()) == 0, f"replay {rep} left a pair counter standing"
+        ds.run()                       # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(ds.out, eager_o)
 
 
 def test_head_level_hybrid_every_rank_and_reassembly():

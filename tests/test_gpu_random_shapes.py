@@ -78,6 +78,8 @@ def test_decode_on_drawn_shapes(seed):
             continue
         ref_o, ref_l = oracle.decode_attention_pairs(q, kv, TD.pairs_rows(pairs), G * Hkv, G, w["sm_scale"])
         TD.check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, what)
+        # from launch records, with the merge as a kernel and inside the sweep: the same bits
+        TD.check_records(ds, kv, items, sched, indptr, what)
         if w["kv_dtype"] == "bf16":
             plain = ds.out.clone()
             ds.run(persistent=True)

@@ -17,6 +17,9 @@ import paper_2511_14116_amd as fs
 from paper_2511_14116_amd.device import DeviceShare
 from workloads import make_requests, make_q, make_kv_pool
 
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import test_gpu_parity as TD      # noqa: E402  (helper: check_merge_in_sweep)
+
 pytestmark = pytest.mark.gpu
 
 ABS_TOL, REL_TOL, LSE_TOL = 2e-3, 1e-2, 1e-3
@@ -65,6 +68,11 @@ def run_units(w, q, rank, n_units, owner, o_owner=None):
         ds.run_records(units=True)
         torch.cuda.synchronize()
         from_records = [ds.out.clone(), ds.lse.clone(), ds.part_o.clone(), ds.part_lse.clone()]
+        # and with the split pairs merged inside the sweep (pair counters handed over): the same final bits
+        TD.check_merge_in_sweep(ds, from_records[:2], True, f"units={n_units} rank {rank}")
+        for a, b in zip(from_records[2:], (ds.part_o, ds.part_lse)):
+            assert (torch.isnan(a) == torch.isnan(b)).all() and torch.equal(torch.nan_to_num(a), torch.nan_to_num(b)), \
+                "merging inside the sweep changed the partial rows"
         for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
             t.fill_(float("nan"))
     ds.run_units()

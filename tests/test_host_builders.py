@@ -168,6 +168,15 @@ def test_launch_records_bit_exact_and_errors():
         with pytest.raises(fs.FsError) as e:
             fs.fs_build_launch_records(sh, items, args[0], ci, args[1], args[2])
         assert e.value.status == fs.FS_EINVAL
+    # an item that does not sit at row (chunk_indptr[pair] + chunk) * G, where the merge would look for it
+    moved = items.copy(); moved["part_row"][1] += 2
+    wrong_chunk = items.copy(); wrong_chunk["chunk"][0] = 3
+    for bad in (moved, wrong_chunk):
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_build_launch_records(sh, bad, sched, ci, page_indptr, page_ids)
+        assert e.value.status == fs.FS_EINVAL
+        with pytest.raises(ValueError):
+            oracle.build_launch_records(_items_as_rows(bad), sched, ci, page_indptr, page_ids, 2)
 
 
 def test_sched_sort_fallback_path_matches():
@@ -255,11 +264,14 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_units(sh, kv8, None, 3, None, 2, None, 2, None, None, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
-    fs.fs_decode_attention_records(sh, kv, None, 0, None, 0, None, 0, None, None, None, None)        # empty list: no-op
+    fs.fs_decode_attention_records(sh, kv, None, 0, None, 0, None, 0, None, None, None, None, None)  # empty list: no-op
     for n_items, n_units, n_pairs in ((3, 0, 4), (3, 0, 0), (3, 0, 2)):
         with pytest.raises(fs.FsError) as e:
             fs.fs_decode_attention_records(sh, kv, None, n_items, None, n_units, None, n_pairs, None, None, None, None)
         assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:     # pair counters for a sweep that merges nothing
+        fs.fs_decode_attention_records(sh, kv, None, 3, None, 0, None, 0, None, None, None, None, pair_counters_dev=64)
+    assert e.value.status == fs.FS_EINVAL
     fs.fs_pack_kv_slots(None, 4096, None, 4096, 0, fs.FS_KV_BF16, False)                            # no slots: no-op
     for args in ((None, 4096, None, 4096, 3, fs.FS_KV_BF16), (64, 4096, 8192, 100, 3, fs.FS_KV_BF16), (64, 4096, 8192, 4096, 3, 9)):
         with pytest.raises(fs.FsError) as e:

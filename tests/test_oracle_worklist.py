@@ -208,13 +208,16 @@ def test_launch_records_by_hand():
     rec = build_launch_records(items, sched, indptr, page_indptr, page_ids, 2)
     assert sched.tolist() == [0, 1, 3, 5, 2, 4, 6]
     # launch position 2 is item 3 = (r1,h0) tokens [0,16): first page 3 -> slot 13, one page, part row 6
-    assert rec[2].tolist() == [3, 0, 16, 4, 6, 0, 13, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    # (its pair, number 1, has 2 chunks whose partial rows start at row chunk_indptr[1] * G = 3 * 2)
+    assert rec[2].tolist() == [3, 0, 16, 4, 6, 2, 13, 0, 0, 0, 0, 0, 0, 0, 1, 6]
     # launch position 4 is item 2 = (r0,h0) tokens [32,40): first page 2 -> slot 12, 8 tokens, part row 4
-    assert rec[4].tolist() == [2, 0, 8, 0, 4, 0, 12, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    # (pair 0: 3 chunks, rows from 0)
+    assert rec[4].tolist() == [2, 0, 8, 0, 4, 3, 12, 0, 0, 0, 0, 0, 0, 0, 0, 0]
     # unsplit list, index order: every pair is one item, so every record points at final rows -(p*G) - 1
     items1, pairs1, _, indptr1 = build_worklist(ctx, owner, 0, 0, 4, 2)
     rec1 = build_launch_records(items1, None, indptr1, page_indptr, page_ids, 2)
     assert rec1[:, 4].tolist() == [-1, -3, -5] and rec1[0, 6:14].tolist() == [10, 11, 12, 0, 0, 0, 0, 0]
+    assert rec1[:, 5].tolist() == [1, 1, 1] and rec1[:, 14].tolist() == [0, 1, 2] and rec1[:, 15].tolist() == [0, 2, 4]
     assert build_launch_records(items1, None, indptr1, page_indptr, page_ids, 2, direct_rows=False)[:, 4].tolist() == [0, 2, 4]
     # a first page beyond 2^31 entries keeps its high word
     big = build_launch_records(items1[:1], None, indptr1, np.array([2 ** 33 + 5, 2 ** 33 + 8]), {2 ** 33 + 5 + j: 7 + j for j in range(3)}, 2)
@@ -247,6 +250,10 @@ def test_launch_records_invariants():
                 npg = -(-int(rec[kk, 2]) // 16)
                 assert fp + npg <= page_indptr[it[4] + 1]
                 assert rec[kk, 6:6 + min(8, npg)].tolist() == page_ids[fp: fp + min(8, npg)].tolist()
-                assert not rec[kk, 6 + min(8, npg):].any() and rec[kk, 5] == 0
-                single = indptr[it[4] + 1] - indptr[it[4]] == 1
+                assert not rec[kk, 6 + min(8, npg):14].any()
+                n_chunks = indptr[it[4] + 1] - indptr[it[4]]
+                assert rec[kk, 5] == n_chunks and rec[kk, 14] == it[4] and rec[kk, 15] == indptr[it[4]] * G
+                # the rows of the pair's chunks, as the merge reads them, are those the items name
+                assert it[7] == rec[kk, 15] + it[5] * G
+                single = n_chunks == 1
                 assert rec[kk, 4] == (-(int(it[4]) * G) - 1 if single else it[7])
