@@ -34,7 +34,7 @@ MEASURED_TRAFFIC_BYTES = {
     (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971407938,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
     (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1971832723,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt
     (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408098416,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt
-    (3, 0, 20251117, 512, "requests", "decode_bf16_kernel"): 69069027,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
+    (3, 0, 20251117, 512, "requests", "decode_bf16_kernel"): 69914282,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
     (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3261385,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
     (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561952676,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
 }
