@@ -267,9 +267,9 @@ def main() -> int:
         return 2
     claim = torch.zeros(2, dtype=torch.int32, device=dev)    # the persistent sweep's counters; every launch leaves them at zero
     pair_counters = torch.zeros(n_pairs, dtype=torch.int32, device=dev)   # one per pair for the merge inside the sweep; likewise
-    # Split pairs merged by the sweep itself (no second kernel): pays on a short launch (config 3: 21.9 -> 18.9 us per
+    # Split pairs merged by the sweep itself (no second kernel): pays on a short launch (config 3: 21.7 -> 18.4 us per
     # step), where the merge kernel's launch is a third of the time; on the equal-run sweeps of the large shares the
-    # hand-over at the end of every workgroup's life costs what the second launch cost (config 2: 313.8 against 312.9).
+    # hand-over at the end of every workgroup's life costs what the second launch cost (config 2: 311.5 against 310.0).
     merge_in_sweep = args.merge_in_sweep or (not units and not args.merge_kernel)
     # Launch records: the host resolves every item (page-table offset, chunk count, first slots) while it builds the
     # list, so a workgroup starts with one read instead of four dependent ones.  The counter form takes items only.

@@ -344,7 +344,7 @@ __device__ __forceinline__ void arrive_and_merge(const DecodeParams& P, int n, c
     const float* po = P.part_o;
     const float* pl = P.part_lse;
     for (int g = wave; g < G; g += WAVES)
-      fs_merge::merge_rows<1, true, true>(po, pl, prow / G, chunks, G, g, P.out + (static_cast<int64_t>(pair) * G + g) * fs::kHeadDim,
+      fs_merge::merge_rows<1, false, true>(po, pl, prow / G, chunks, G, g, P.out + (static_cast<int64_t>(pair) * G + g) * fs::kHeadDim,
                               P.lse + static_cast<int64_t>(pair) * G + g, lane);
   }
 }
@@ -537,12 +537,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) decode_bf16_persistent_kernel(c
     // asked for now and travel while the current item streams, so that at the item's end the next pages can be
     // requested at once.  With a counter the next item is only known after the claim (below).
     ItemDesc nxt;
-#ifndef FS_EXP_LATE_DESC
     if constexpr (UNITS) {
       ++cur_k;
       nxt = load_desc_head<WAVES, NBUF>(P, cur_k < unit_end ? cur_k : n_items, n_items, wave, G);
     }
-#endif
     SoftmaxState st;
     st.m = -INFINITY;
     st.l = 0.f;
@@ -590,12 +588,6 @@ __global__ void __launch_bounds__(WAVES * 64, 2) decode_bf16_persistent_kernel(c
       nxt = load_desc_head<WAVES, NBUF>(P, next_k, n_items, wave, G);
       if (second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
     }
-#ifdef FS_EXP_LATE_DESC
-    if constexpr (UNITS) {
-      ++cur_k;
-      nxt = load_desc_head<WAVES, NBUF>(P, cur_k < unit_end ? cur_k : n_items, n_items, wave, G);
-    }
-#endif
     load_desc_q(nxt, P, lane, G);
     prologue(nxt);
     for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
