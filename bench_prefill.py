@@ -145,16 +145,32 @@ def run(args) -> int:
     entries = w["entries"].copy()
     work = (w["prompt"] - w["n_done"]).astype(np.int64)
 
+    # the host calls of a step, marshalled once (a serving loop calls them on the same buffers every step)
+    pending_buf = np.zeros(R, dtype=np.int64)
+    rank_buf = np.zeros(len(work), dtype=np.int32)
+    load_buf = np.zeros(R, dtype=np.int64)
+    ctx_buf = np.zeros(len(n_done_buf), dtype=np.int32)
+    dp_buf = np.zeros((shape.n_req, shape.n_kv_heads), dtype=np.int32)
+    rank_load_buf, dp_load_buf = np.zeros(R, dtype=np.int64), np.zeros(R, dtype=np.int64)
+    call_route = fs.bind_route_requests(pending_buf, work, rank_buf)
+    call_sched = fs.bind_schedule_prefill(R, args.prefill_budget, args.prefill_budget // 2, entries, n_new_buf, load_buf)
+    call_place = fs.bind_build_placement_hybrid_heads(shape, ctx_buf, owner_buf, dp_buf, rank_load_buf, dp_load_buf, layer=0,
+                                                      route=rank_buf)
+
     def step(ev=None):
         t0 = time.perf_counter()
         # host side of the step (library calls): router, Algorithm 1, head-level placement, rank's tile list
-        entries["rank"] = fs.fs_route_requests(np.zeros(R, dtype=np.int64), work)
+        pending_buf.fill(0)
+        call_route()
+        entries["rank"] = rank_buf
         t1 = time.perf_counter()
-        take, _, _ = fs.fs_schedule_prefill(R, args.prefill_budget, args.prefill_budget // 2, entries)
+        call_sched()                             # the batch: tokens taken from every entry, straight into n_new_buf
         t2 = time.perf_counter()
-        n_new_buf[...] = take
-        owner_buf[...] = fs.fs_build_placement_hybrid_heads(shape, np.maximum(n_done_buf + n_new_buf, 1), layer=0,
-                                                           route=entries["rank"])[0]
+        np.add(n_done_buf, n_new_buf, out=ctx_buf)
+        np.maximum(ctx_buf, 1, out=ctx_buf)
+        rank_load_buf.fill(0)
+        dp_load_buf.fill(0)
+        call_place()                             # owner map into owner_buf
         t3 = time.perf_counter()
         st = staging[n_step[0] % N_STAGE]
         n_step[0] += 1

@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     fs_route_request, fs_route_requests, fs_schedule_prefill, fs_plan_kv_reload, fs_replace_failed_gpu, fs_plan_ffn_reload,
     library_path, load_library,
     fs_build_placement, fs_build_placement_hybrid_heads, fs_build_worklist, fs_build_worklist_units, fs_build_launch_records, fs_choose_chunk_tokens, fs_decode_attention, fs_decode_attention_persistent, fs_decode_attention_fused, fs_decode_attention_fused_static, fs_decode_attention_units, fs_decode_attention_records, fs_merge_lse,
-    BoundCall, bind_build_placement, bind_build_placement_hybrid_heads, bind_build_worklist, bind_build_worklist_units, bind_build_prefill_worklist, bind_choose_prefill_chunk, bind_decode_attention, bind_decode_attention_persistent, bind_decode_attention_fused, bind_decode_attention_units, bind_build_launch_records, bind_decode_attention_records, bind_merge_lse,
+    BoundCall, bind_build_placement, bind_build_placement_hybrid_heads, bind_build_worklist, bind_build_worklist_units, bind_build_prefill_worklist, bind_choose_prefill_chunk, bind_route_requests, bind_schedule_prefill, bind_decode_attention, bind_decode_attention_persistent, bind_decode_attention_fused, bind_decode_attention_units, bind_build_launch_records, bind_decode_attention_records, bind_merge_lse,
     fs_kv_elem_offset, fs_pack_kv_slots, fs_stream_read_probe, fs_set_option, fs_get_option, fs_last_error, fs_abi_version,
 )
 from .layout import slot_permutation, pack_slots  # noqa: F401

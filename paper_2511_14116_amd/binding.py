@@ -615,6 +615,39 @@ def bind_build_placement_hybrid_heads(shape: FsShape, ctx_len: np.ndarray, owner
     return BoundCall(lib.fs_build_placement_hybrid_heads, args, (shape, ctx_len, route, owner, dp_rank, rank_load, dp_load))
 
 
+def bind_route_requests(pending: np.ndarray, work: np.ndarray, rank_out: np.ndarray) -> BoundCall:
+    """fs_route_requests on caller-held arrays: pending int64 [R] (in/out: set it before each call), work int64 [n],
+    rank_out int32 [n]."""
+    lib = load_library()
+    for a, dt in ((pending, np.int64), (work, np.int64), (rank_out, np.int32)):
+        if a.dtype != dt or not a.flags.c_contiguous or a.ndim != 1:
+            raise TypeError("bind_route_requests needs contiguous one-dimensional arrays of the documented dtypes")
+    if len(rank_out) != len(work):
+        raise ValueError("rank_out must have one entry per request")
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    args = (C.c_int32(len(pending)), pending.ctypes.data_as(i64p), work.ctypes.data_as(i64p), C.c_int32(len(work)),
+            rank_out.ctypes.data_as(i32p))
+    return BoundCall(lib.fs_route_requests, args, (pending, work, rank_out))
+
+
+def bind_schedule_prefill(n_ranks: int, budget: int, min_tokens: int, entries: np.ndarray, take: np.ndarray,
+                          load: np.ndarray, init_load=None) -> BoundCall:
+    """fs_schedule_prefill on caller-held arrays: entries PREFILL_ENTRY_DTYPE [n] (read at every call), take int32 [n]
+    and load int64 [R] written.  After a call the batch's token count is in .n_items.value."""
+    lib = load_library()
+    if entries.dtype != PREFILL_ENTRY_DTYPE or not entries.flags.c_contiguous or take.dtype != np.int32 or \
+            len(take) != len(entries) or load.dtype != np.int64 or len(load) != n_ranks:
+        raise TypeError("bind_schedule_prefill: arrays do not match the documented layouts")
+    if init_load is not None and (init_load.dtype != np.int64 or len(init_load) != n_ranks):
+        raise TypeError("bind_schedule_prefill: init_load must be int64 [n_ranks]")
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    n_tok = C.c_int32(0)
+    args = (C.c_int32(n_ranks), C.c_int32(budget), C.c_int32(min_tokens), C.c_void_p(entries.ctypes.data),
+            C.c_int32(len(entries)), None if init_load is None else init_load.ctypes.data_as(i64p),
+            take.ctypes.data_as(i32p), load.ctypes.data_as(i64p), C.byref(n_tok))
+    return BoundCall(lib.fs_schedule_prefill, args, (entries, take, load, init_load, n_tok), n_items=n_tok)
+
+
 def bind_build_worklist(shape: FsShape, ctx_len: np.ndarray, owner: np.ndarray, rank: int, chunk_tokens: int,
                         items: np.ndarray, pairs: np.ndarray, sched: np.ndarray, chunk_indptr: np.ndarray) -> BoundCall:
     """fs_build_worklist into caller-held arrays (e.g. views of pinned memory).  After a call the

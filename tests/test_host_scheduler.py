@@ -126,6 +126,36 @@ def test_serving_sized_budget_is_fast_and_balanced():
     assert dt < 0.05
 
 
+def test_bound_router_and_scheduler_reuse_their_buffers():
+    """The pre-marshalled forms (what a serving loop calls every step) give what the plain calls give, and see
+    changed inputs on the next call."""
+    rng = np.random.default_rng(31)
+    R, n = 5, 40
+    work = rng.integers(1, 9000, size=n).astype(np.int64)
+    pending = np.zeros(R, dtype=np.int64); ranks = np.zeros(n, dtype=np.int32)
+    route = fs.bind_route_requests(pending, work, ranks)
+    entries = np.zeros(n, dtype=fs.PREFILL_ENTRY_DTYPE)
+    entries["req"] = np.arange(n); entries["n_done"] = rng.integers(0, 3000, size=n); entries["n_new"] = work
+    take = np.zeros(n, dtype=np.int32); load = np.zeros(R, dtype=np.int64)
+    sched = fs.bind_schedule_prefill(R, 4096, 2048, entries, take, load)
+    for rep in range(3):
+        pending[:] = rep * 100
+        want_pending = pending.copy()
+        want_ranks = fs.fs_route_requests(want_pending, work)
+        route()
+        assert ranks.tobytes() == want_ranks.tobytes() and pending.tobytes() == want_pending.tobytes()
+        entries["rank"] = ranks
+        want_take, want_load, want_n = fs.fs_schedule_prefill(R, 4096, 2048, entries)
+        sched()
+        assert take.tobytes() == want_take.tobytes() and load.tobytes() == want_load.tobytes()
+        assert sched.n_items.value == want_n == int(take.sum())
+        work[rep] += 777; entries["n_new"][rep] = work[rep]          # the next call sees the change
+    with pytest.raises(TypeError):
+        fs.bind_route_requests(pending.astype(np.int32), work, ranks)
+    with pytest.raises(TypeError):
+        fs.bind_schedule_prefill(R, 4096, 2048, entries, take.astype(np.int64), load)
+
+
 def test_errors():
     with pytest.raises(fs.FsError):
         fs.fs_schedule_prefill(0, 4, 0, [])
