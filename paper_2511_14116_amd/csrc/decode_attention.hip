@@ -8,7 +8,7 @@
 // bf16 path (GQA groups up to 16 q-heads):
 //   One workgroup per work item, in the longest-first order the list prescribes; the hardware
 //   dispatcher hands the next item to whichever CU frees a slot, which is list scheduling.
-//   The item's pages are split evenly over the workgroup's wavefronts.  A wavefront streams
+//   The item's pages are dealt to the workgroup's wavefronts in turn.  A wavefront streams
 //   K and V pages with 16-byte-per-lane loads that are each one contiguous 1 KiB run, straight
 //   into MFMA operand registers (the in-slot element order is built for that), several pages
 //   ahead of the arithmetic.  Per page:
@@ -21,6 +21,12 @@
 //
 // fp8 path (e4m3 K/V with one fp32 scale per slot, small groups): plain fp32 VALU, since with
 // one q-head per KV head there is no dense contraction to give the matrix cores.
+//
+// Forms of the sweep, all with the same arithmetic per item (their rows agree bit for bit): one workgroup
+// per item; resident workgroups that claim items from a counter; resident workgroups on equal runs of pages
+// (no counter).  Items come as list entries that the kernel looks up, or as launch records that the host has
+// resolved (one 64-byte read).  A pair that is one item writes its final rows; the chunks of a split pair
+// are merged by fs_merge_lse, or, given a counter per pair, by the workgroup that writes the pair's last rows.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
