@@ -33,7 +33,8 @@ MEASURED_TRAFFIC_BYTES = {
     (2, 0, 20251116, "512 units", "requests", "decode_bf16_persistent_kernel"): 1965833753,   # profiles/decode_bf16_units_kernel_cfg2_70b_rank0.txt
     (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971407938,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
     (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1971832723,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt
-    (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408098416,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt
+    (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408070099,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt
+    (1, 0, 20251115, 2048, "requests", "decode_bf16_kernel"): 407998268,                      # profiles/decode_bf16_kernel_cfg1_8b_hybrid_rank0.txt
     (3, 0, 20251117, 512, "requests", "decode_bf16_kernel"): 69914282,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
     (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3261385,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
     (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561952676,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
@@ -70,7 +71,7 @@ def main() -> int:
     ap.add_argument("--units", type=int, default=None, metavar="N",
                     help="bf16: cut the share into N equal runs of pages (0 = two per compute unit) and sweep them with one "
                          "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units).  Default: that form, "
-                         "two runs per compute unit, once a run would hold 64 pages or more; else the chunked list")
+                         "two runs per compute unit, once a run would hold 256 pages or more; else the chunked list")
     ap.add_argument("--chunked", action="store_true", help="the chunked list (fs_build_worklist) whatever the share's size")
     ap.add_argument("--no-records", action="store_true",
                     help="hand the kernels the items (they look each one up themselves) instead of launch records")
@@ -152,7 +153,10 @@ def main() -> int:
     if args.units is not None and w["kv_dtype"] != "bf16":
         print("bench.py: --units is built for bf16 K/V", file=sys.stderr)
         return 2
-    UNIT_MIN_PAGES = 64      # below this a run is too short to pay for its start: the chunked list measures faster
+    # Below this a run is too short for the equal-run form to pay: the chunked list with one workgroup per record, which
+    # merges split pairs inside the sweep, measures faster (config 1, 89 pages to a run: 72.8 against 77.2 us per step;
+    # config 2, 466 pages to a run: 311 against 318)
+    UNIT_MIN_PAGES = 256
 
     def pages_of(rank):
         return sum(-(-int(ctx[r]) // w["page_tokens"]) for r in range(B) for h in range(Hkv) if owner[r, h] == rank)
