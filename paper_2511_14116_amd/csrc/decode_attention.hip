@@ -350,7 +350,7 @@ __device__ __forceinline__ void arrive_and_merge(const DecodeParams& P, int n, c
     const float* po = P.part_o;
     const float* pl = P.part_lse;
     for (int g = wave; g < G; g += WAVES)
-      fs_merge::merge_rows<1, false, true>(po, pl, prow / G, chunks, G, g, P.out + (static_cast<int64_t>(pair) * G + g) * fs::kHeadDim,
+      fs_merge::merge_rows<1, true>(po, pl, prow / G, chunks, G, g, P.out + (static_cast<int64_t>(pair) * G + g) * fs::kHeadDim,
                               P.lse + static_cast<int64_t>(pair) * G + g, lane);
   }
 }

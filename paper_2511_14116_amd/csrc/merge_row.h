@@ -22,9 +22,6 @@ static __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// RW consecutive output rows of one pair, by one wavefront.  The pair's chunks are c0 .. c0+n-1; chunk c's partial
-// row of q-head g is row (c0 + c)*group + g of part_o / part_lse.  The rows merged are q-heads g0 .. g0+RW-1;
-// out_rows / lse_rows point at the first of them in the final arrays.  A lane owns two of the 128 columns.
 // Loads of partial rows.  COHERENT: as relaxed atomic loads at device scope, which are served from memory and not from
 // this XCD's caches - for a caller that reads rows other workgroups of the same launch have written (the rows
 // must have been stored the same way, see the decode kernels).
@@ -44,9 +41,10 @@ static __device__ __forceinline__ float2 load_f32x2(const float2* p) {
   }
 }
 
-// LEAN: chunk rows beyond the first few are fetched one at a time instead of sixteen at a time - the same sums in
-// the same order with a handful of registers, for callers that merge a pair of few chunks in the middle of other work.
-template <int RW, bool LEAN = false, bool COHERENT = false>
+// RW consecutive output rows of one pair, by one wavefront.  The pair's chunks are c0 .. c0+n-1; chunk c's partial
+// row of q-head g is row (c0 + c)*group + g of part_o / part_lse.  The rows merged are q-heads g0 .. g0+RW-1;
+// out_rows / lse_rows point at the first of them in the final arrays.  A lane owns two of the 128 columns.
+template <int RW, bool COHERENT = false>
 static __device__ __forceinline__ void merge_rows(const float* part_o, const float* part_lse, int64_t c0, int n, int group,
                                                   int g0, float* out_rows, float* lse_rows, int lane) {
   // no fusing of multiplies into adds beyond the fmaf calls written out: every kernel that includes this must
@@ -99,7 +97,7 @@ static __device__ __forceinline__ void merge_rows(const float* part_o, const flo
     // A pair cut into many chunks (a 131072-token context in 1024-token chunks: 128) is one wavefront's
     // serial walk; sixteen rows in flight instead of four turn its 32 round trips into 8.  Same order of sums.
     constexpr int D = 16 / RW;
-    for (; !LEAN && j + D <= cnt; j += D) {
+    for (; j + D <= cnt; j += D) {
       float2 od[D][RW];
 #pragma unroll
       for (int u = 0; u < D; ++u)
@@ -115,7 +113,7 @@ static __device__ __forceinline__ void merge_rows(const float* part_o, const flo
         }
       }
     }
-    for (; !LEAN && j + U <= cnt; j += U) {
+    for (; j + U <= cnt; j += U) {
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
