@@ -19,10 +19,10 @@ import numpy as np
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # HBM-side bytes of one prefill_bf16_kernel launch on the default batch (rocprofv3 --pmc FETCH_SIZE x 2.000 +
 # WRITE_SIZE, see profiles/prefill_bf16_kernel_hybrid_batch_rank0.txt); other batches: not measured
-MEASURED_TRAFFIC_DEFAULT_BATCH = 208039526
-KV_CHUNK_MAX, KV_CHUNK_MIN = 32768, 512    # the split-K chunk of the keys a tile sees is halved from MAX down to MIN ...
-ITEMS_PER_CU = 2.5                         # ... until the list has this many items per compute unit (fs_choose_prefill_chunk)
+MEASURED_TRAFFIC_DEFAULT_BATCH = 195328512
+KV_CHUNK_MAX, KV_CHUNK_MIN = 32768, 512    # bounds of the split-K chunk of the keys a tile sees (fs_choose_prefill_chunk) ...
 N_CU = 256                                 # compute units of an MI355X (the list is a host matter: no device query here)
+N_SLOTS = 2 * N_CU                         # ... which is four thirds of the share of one of the workgroups the chip runs at a time
 
 
 def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64, n_kv_heads=8, seed=20251120,
@@ -46,9 +46,9 @@ def prefill_workload(fs, n_req=64, n_ranks=7, rank=0, budget=8192, n_q_heads=64,
     owner, dp, rank_load, dp_load = fs.fs_build_placement_hybrid_heads(shape, ctx, layer=0, route=entries["rank"])
     G = n_q_heads // n_kv_heads
     tile = fs.fs_prefill_tile_tokens(G)
-    if kv_chunk is None:      # a small batch is cut finer so that every compute unit has work, a large one not at all
+    if kv_chunk is None:      # an item about as long as a workgroup slot's share of the batch; a large batch is not cut at all
         kv_chunk, _ = fs.fs_choose_prefill_chunk(shape, n_done, take, owner, rank, tile, KV_CHUNK_MAX, KV_CHUNK_MIN,
-                                                 int(ITEMS_PER_CU * N_CU))
+                                                 N_SLOTS)
     items, pairs, sched, chunk_indptr, out_indptr = fs.fs_build_prefill_worklist(shape, n_done, take, owner, rank, tile,
                                                                                  kv_chunk)
     return dict(seed=seed, queue=queue, shape=shape, G=G, R=R, rank=rank, budget=budget, prompt=prompt, n_done=n_done,
@@ -136,7 +136,7 @@ def run(args) -> int:
                                               views["out_indptr"])
         staging.append(dict(host=hb, build=call))
     call_chunk = fs.bind_choose_prefill_chunk(shape, n_done_buf, n_new_buf, owner_buf, args.rank, w["tile"], KV_CHUNK_MAX,
-                                              KV_CHUNK_MIN, int(ITEMS_PER_CU * N_CU))
+                                              KV_CHUNK_MIN, N_SLOTS)
     n_step = [0]
     in_place = args.list == "host"
     use_graph = args.graph and not in_place
@@ -335,7 +335,7 @@ def run(args) -> int:
                      "frac": round(flops / (k_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "algorithmic_flops_per_launch": flops,
                      "traffic": MEASURED_TRAFFIC_DEFAULT_BATCH if (args.prefill_queue, args.prefill_budget, args.rank, kv_chunk)
-                     == (64, 8192, 0, 2048) and fs.fs_get_option("prefill_waves") == 8
+                     == (64, 8192, 0, 2272) and fs.fs_get_option("prefill_waves") == 8
                      and fs.fs_get_option("prefill_col_tiles") == 1 else None},
     }
     if cpu is not None:

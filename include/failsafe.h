@@ -691,21 +691,22 @@ FS_API fs_status fs_build_prefill_worklist(const fs_shape* shape, const int32_t*
                                            int64_t* out_indptr,
                                            int64_t* n_items, int64_t* n_pairs, int64_t* n_tiles);
 
-/* fs_choose_prefill_chunk - a split-K chunk for one rank's prefill batch.  A batch with few tiles (the
- * fine-grained chunked prefill of Section 3.1 forms such batches when little is waiting) needs its long
- * contexts cut so that every compute unit has work; a large batch needs no cut, and every cut costs partial
- * rows and merge work.  The chunk is halved from max_chunk down (staying a multiple of 32) until the list, as
- * fs_build_prefill_worklist would build it, has at least min_items items or the next halving would go below
- * min_chunk.
+/* fs_choose_prefill_chunk - a split-K chunk for one rank's prefill batch.  A batch with few long contexts (the
+ * fine-grained chunked prefill of Section 3.1 forms such batches when little is waiting) runs as long as its
+ * longest tile takes unless the keys are cut; a large batch needs no cut, and every cut costs partial rows and
+ * merge work.  The chunk is four thirds of a slot's fair share of the whole: with T the keys the rank's tiles
+ * see, all told, ceil(4 T / (3 n_slots)), rounded up to a multiple of 32 keys and held within
+ * [min_chunk, max_chunk].
  *
  *  max_chunk, min_chunk   multiples of 32, 32 <= min_chunk <= max_chunk
+ *  n_slots          workgroups the GPU runs at a time (two per compute unit for the default kernel shape), >= 1
  *  kv_chunk_tokens  HOST out  the chosen chunk
  *  n_items          HOST out  the list's length with it
  *
- * FS_EINVAL: bad chunk bounds, min_items < 0, and whatever fs_build_prefill_worklist refuses. */
+ * FS_EINVAL: bad chunk bounds, n_slots < 1, and whatever fs_build_prefill_worklist refuses. */
 FS_API fs_status fs_choose_prefill_chunk(const fs_shape* shape, const int32_t* n_done, const int32_t* n_new,
                                          const int32_t* owner, int32_t rank, int32_t tile_tokens,
-                                         int32_t max_chunk, int32_t min_chunk, int64_t min_items,
+                                         int32_t max_chunk, int32_t min_chunk, int64_t n_slots,
                                          int32_t* kv_chunk_tokens, int64_t* n_items);
 
 /* Query tokens one kernel workgroup covers for a group of G q-heads per KV head

@@ -75,21 +75,23 @@ def build_prefill_worklist(n_done, n_new, owner, rank: int, n_q_heads: int, tile
 
 
 def choose_prefill_chunk(n_done, n_new, owner, rank: int, n_q_heads: int, tile_tokens: int, max_chunk: int,
-                         min_chunk: int, min_items: int):
-    """Halve the split-K chunk of the keys from ``max_chunk`` down (staying a multiple of ``min_chunk``'s
-    granule, 32 keys) until ``rank``'s tile list has at least ``min_items`` items or the next halving would
-    fall below ``min_chunk``.  -> (chunk, n_items).  Split-K is this build's device, not the paper's: a
-    batch with few long chunks (Section 3.1's fine-grained chunked prefill forms such batches when little
-    is waiting) would otherwise leave most of the GPU idle, while a large batch needs no split at all."""
+                         min_chunk: int, n_slots: int):
+    """The split-K chunk of the keys for ``rank``'s batch: four thirds of a slot's fair share of the work.  With T the
+    keys that the rank's tiles see, all told, and ``n_slots`` the workgroups the GPU runs at a time, the chunk is
+    ceil(4 T / (3 n_slots)) rounded up to a multiple of 32 keys and held within [min_chunk, max_chunk].
+    -> (chunk, n_items with it).  Split-K is this build's device, not the paper's: a batch with few long contexts
+    (Section 3.1's fine-grained chunked prefill forms such batches when little is waiting) would otherwise run as long as
+    its longest tile takes, while a large batch needs no cut at all; an item about as long as a slot's share of the
+    whole keeps the longest item from sticking out without cutting finer than that needs."""
     if min_chunk < 32 or min_chunk % 32 or max_chunk < min_chunk or max_chunk % 32:
         raise ValueError("chunk bounds must be multiples of 32, min <= max")
-    C = int(max_chunk)
-    while True:
-        n = len(build_prefill_worklist(n_done, n_new, owner, rank, n_q_heads, tile_tokens, C)[0])
-        nxt = (C // 2) // 32 * 32
-        if n >= min_items or nxt < min_chunk:
-            return C, n
-        C = nxt
+    if n_slots < 1:
+        raise ValueError("n_slots < 1")
+    uncut = build_prefill_worklist(n_done, n_new, owner, rank, n_q_heads, tile_tokens, 0)[0]
+    total = sum(int(it[5]) - int(it[4]) for it in uncut)         # one item per tile: kv_end - kv_begin
+    target = -(-4 * total // (3 * int(n_slots)))
+    chunk = min(max(-(-target // 32) * 32, min_chunk), max_chunk)
+    return chunk, len(build_prefill_worklist(n_done, n_new, owner, rank, n_q_heads, tile_tokens, chunk)[0])
 
 
 def prefill_attention_items(q_bits, kv: dict, items, pairs, n_q_heads: int, group: int, tile_tokens: int,

@@ -462,9 +462,10 @@ def fs_build_prefill_worklist(shape: FsShape, n_done, n_new, owner, rank: int, t
 
 
 def fs_choose_prefill_chunk(shape: FsShape, n_done, n_new, owner, rank: int, tile_tokens: int, max_chunk: int,
-                            min_chunk: int, min_items: int):
-    """-> (kv_chunk_tokens, n_items): the split-K chunk, halved from ``max_chunk`` down to at least ``min_chunk``,
-    with which ``rank``'s tile list reaches ``min_items`` items."""
+                            min_chunk: int, n_slots: int):
+    """-> (kv_chunk_tokens, n_items): the split-K chunk for ``rank``'s batch, four thirds of the share of the keys that
+    one of ``n_slots`` concurrently running workgroups would get, within [min_chunk, max_chunk], and the list's length
+    with it."""
     nd, nn, own = _host(n_done, np.int32), _host(n_new, np.int32), _host(owner, np.int32)
     if len(nd) != shape.n_req or len(nn) != shape.n_req or own.size != shape.n_req * shape.n_kv_heads:
         raise ValueError("n_done, n_new and owner must match the shape")
@@ -472,7 +473,7 @@ def fs_choose_prefill_chunk(shape: FsShape, n_done, n_new, owner, rank: int, til
     chunk, n_items = C.c_int32(0), C.c_int64(0)
     _check(load_library().fs_choose_prefill_chunk(C.byref(shape), nd.ctypes.data_as(i32p), nn.ctypes.data_as(i32p),
                                                   own.ctypes.data_as(i32p), rank, tile_tokens, max_chunk, min_chunk,
-                                                  min_items, C.byref(chunk), C.byref(n_items)))
+                                                  n_slots, C.byref(chunk), C.byref(n_items)))
     return chunk.value, n_items.value
 
 
@@ -708,7 +709,7 @@ def bind_build_prefill_worklist(shape: FsShape, n_done: np.ndarray, n_new: np.nd
 
 
 def bind_choose_prefill_chunk(shape: FsShape, n_done: np.ndarray, n_new: np.ndarray, owner: np.ndarray, rank: int,
-                              tile_tokens: int, max_chunk: int, min_chunk: int, min_items: int) -> BoundCall:
+                              tile_tokens: int, max_chunk: int, min_chunk: int, n_slots: int) -> BoundCall:
     """fs_choose_prefill_chunk on caller-held int32 arrays, read at every call.  After a call the chunk is in
     .n_tiles.value and the list's length in .n_items.value."""
     lib = load_library()
@@ -718,7 +719,7 @@ def bind_choose_prefill_chunk(shape: FsShape, n_done: np.ndarray, n_new: np.ndar
     i32p = C.POINTER(C.c_int32)
     chunk, n_items = C.c_int32(0), C.c_int64(0)
     args = (C.byref(shape), n_done.ctypes.data_as(i32p), n_new.ctypes.data_as(i32p), owner.ctypes.data_as(i32p),
-            C.c_int32(rank), C.c_int32(tile_tokens), C.c_int32(max_chunk), C.c_int32(min_chunk), C.c_int64(min_items),
+            C.c_int32(rank), C.c_int32(tile_tokens), C.c_int32(max_chunk), C.c_int32(min_chunk), C.c_int64(n_slots),
             C.byref(chunk), C.byref(n_items))
     return BoundCall(lib.fs_choose_prefill_chunk, args, (shape, n_done, n_new, owner), n_items, None, chunk)
 

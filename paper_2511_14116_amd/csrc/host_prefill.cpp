@@ -114,40 +114,50 @@ extern "C" fs_status fs_build_prefill_worklist(const fs_shape* shape, const int3
 
 extern "C" fs_status fs_choose_prefill_chunk(const fs_shape* shape, const int32_t* n_done, const int32_t* n_new,
                                              const int32_t* owner, int32_t rank, int32_t tile_tokens,
-                                             int32_t max_chunk, int32_t min_chunk, int64_t min_items,
+                                             int32_t max_chunk, int32_t min_chunk, int64_t n_slots,
                                              int32_t* kv_chunk_tokens, int64_t* n_items) {
   if (!kv_chunk_tokens || !n_items) return fs::fail(FS_EINVAL, "fs_choose_prefill_chunk: output pointers are NULL");
   if (min_chunk < 32 || min_chunk % 32 || max_chunk < min_chunk || max_chunk % 32)
     return fs::fail(FS_EINVAL, "fs_choose_prefill_chunk: chunks [%d, %d] must be multiples of 32, min <= max", min_chunk,
                     max_chunk);
-  if (min_items < 0) return fs::fail(FS_EINVAL, "fs_choose_prefill_chunk: min_items %lld < 0", static_cast<long long>(min_items));
-  // The candidates: max_chunk halved (keeping multiples of 32 keys) down to min_chunk.
-  int32_t cand[32];
-  int n_cand = 0;
-  for (int32_t C = max_chunk; C >= min_chunk && n_cand < 32; C = (C / 2) / 32 * 32) cand[n_cand++] = C;
-  // The list builder checks the arguments and counts the first candidate's list; the other candidates are
-  // counted in one more walk over the tiles (an item per chunk of the keys a tile sees).
-  int64_t count[32] = {}, np = 0, nt = 0;
-  if (const fs_status st = fs_build_prefill_worklist(shape, n_done, n_new, owner, rank, tile_tokens, cand[0], nullptr, 0, nullptr,
-                                                     0, nullptr, nullptr, 0, nullptr, &count[0], &np, &nt); st != FS_OK)
+  if (n_slots < 1) return fs::fail(FS_EINVAL, "fs_choose_prefill_chunk: n_slots %lld < 1", static_cast<long long>(n_slots));
+  // The list builder checks the arguments (and counts the uncut list, which is not needed here).
+  int64_t ni = 0, np = 0, nt = 0;
+  if (const fs_status st = fs_build_prefill_worklist(shape, n_done, n_new, owner, rank, tile_tokens, 0, nullptr, 0, nullptr,
+                                                     0, nullptr, nullptr, 0, nullptr, &ni, &np, &nt); st != FS_OK)
     return st;
-  if (count[0] < min_items && n_cand > 1) {
-    const int32_t B = shape->n_req, H = shape->n_kv_heads;
-    for (int c = 1; c < n_cand; ++c) count[c] = 0;
-    for (int32_t r = 0; r < B; ++r) {
-      if (n_new[r] == 0) continue;
-      int64_t mine = 0;
-      for (int32_t h = 0; h < H; ++h) mine += owner[static_cast<int64_t>(r) * H + h] == rank;
-      if (mine == 0) continue;
-      for (int64_t b = 0; b < n_new[r]; b += tile_tokens) {
-        const int64_t keys = n_done[r] + std::min<int64_t>(n_new[r], b + tile_tokens);
-        for (int c = 1; c < n_cand; ++c) count[c] += mine * ((keys + cand[c] - 1) / cand[c]);
-      }
-    }
+  // Keys the rank's tiles see, all told: the tiles of a request see n_done + tile, n_done + 2 tile, ..., n_done + n_new.
+  const int32_t B = shape->n_req, H = shape->n_kv_heads;
+  int64_t total = 0;
+  for (int32_t r = 0; r < B; ++r) {
+    if (n_new[r] == 0) continue;
+    int64_t mine = 0;
+    for (int32_t h = 0; h < H; ++h) mine += owner[static_cast<int64_t>(r) * H + h] == rank;
+    if (mine == 0) continue;
+    const int64_t full = n_new[r] / tile_tokens, rest = n_new[r] % tile_tokens;      // full tiles, tokens of a last short one
+    int64_t keys = full * n_done[r] + static_cast<int64_t>(tile_tokens) * full * (full + 1) / 2;
+    if (rest) keys += static_cast<int64_t>(n_done[r]) + n_new[r];
+    total += mine * keys;
   }
-  int pick = 0;
-  while (count[pick] < min_items && pick + 1 < n_cand) ++pick;
-  *kv_chunk_tokens = cand[pick];
-  *n_items = count[pick];
+  // four thirds of a slot's fair share, up to a multiple of 32 keys, within the bounds
+  const int64_t target = (4 * total + 3 * n_slots - 1) / (3 * n_slots);
+  int64_t chunk = (target + 31) / 32 * 32;
+  chunk = std::min<int64_t>(std::max<int64_t>(chunk, min_chunk), max_chunk);
+  // the list's length with it: an item per chunk of the keys a tile sees
+  int64_t count = 0;
+  for (int32_t r = 0; r < B; ++r) {
+    if (n_new[r] == 0) continue;
+    int64_t mine = 0;
+    for (int32_t h = 0; h < H; ++h) mine += owner[static_cast<int64_t>(r) * H + h] == rank;
+    if (mine == 0) continue;
+    int64_t chunks = 0;
+    for (int64_t b = 0; b < n_new[r]; b += tile_tokens) {
+      const uint32_t keys = static_cast<uint32_t>(n_done[r] + std::min<int64_t>(n_new[r], b + tile_tokens));   // < 2^31: checked by the builder
+      chunks += (keys + static_cast<uint32_t>(chunk) - 1) / static_cast<uint32_t>(chunk);
+    }
+    count += mine * chunks;
+  }
+  *kv_chunk_tokens = static_cast<int32_t>(chunk);
+  *n_items = count;
   return FS_OK;
 }

@@ -389,7 +389,7 @@ def test_bench_batch_full_size_sampled():
     import bench_prefill
     w = bench_prefill.prefill_workload(fs)
     shape, G, pairs, items = w["shape"], w["G"], w["pairs"], w["items"]
-    assert w["tile"] == fs.fs_prefill_tile_tokens(G) and w["kv_chunk"] == 2048      # what the chunk choice gives on this batch
+    assert w["tile"] == fs.fs_prefill_tile_tokens(G) and w["kv_chunk"] == 2272      # what the chunk choice gives on this batch (ceil(4 * 863803 / (3 * 512)) = 2250 -> 2272)
     ctx = (w["n_done"] + w["n_new"]).astype(np.int32)
     kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx)
     q_indptr = np.concatenate([[0], np.cumsum(w["n_new"])]).astype(np.int64)

@@ -105,13 +105,13 @@ def test_chunk_choice_matches_oracle():
         B, H, R, G = int(rng.integers(1, 7)), int(rng.integers(1, 5)), int(rng.integers(1, 4)), int(rng.integers(1, 5))
         n_done = rng.integers(0, 5000, size=B).astype(np.int32); n_new = rng.integers(0, 300, size=B).astype(np.int32)
         owner = rng.integers(0, R, size=(B, H)).astype(np.int32)
-        rank, tile, want = int(rng.integers(0, R)), int(rng.integers(1, 40)), int(rng.integers(0, 200))
+        rank, tile, want = int(rng.integers(0, R)), int(rng.integers(1, 40)), int(rng.integers(1, 700))      # want: slots
         mx = 32 * int(rng.integers(1, 200)); mn = 32 * int(rng.integers(1, mx // 32 + 1))
         shape = fs.FsShape(B, H * G, H, 128, 16, R)
         assert fs.fs_choose_prefill_chunk(shape, n_done, n_new, owner, rank, tile, mx, mn, want) == \
             oracle.choose_prefill_chunk(n_done, n_new, owner, rank, H * G, tile, mx, mn, want)
     shape = fs.FsShape(1, 2, 1, 128, 16, 1)
-    for mx, mn, want in ((100, 32, 1), (64, 128, 1), (64, 16, 1), (64, 32, -1)):
+    for mx, mn, want in ((100, 32, 1), (64, 128, 1), (64, 16, 1), (64, 32, 0)):
         with pytest.raises(fs.FsError) as e:
             fs.fs_choose_prefill_chunk(shape, [0], [5], [[0]], 0, 4, mx, mn, want)
         assert e.value.status == fs.FS_EINVAL

@@ -176,31 +176,40 @@ def test_chunk_partials_merge_back_to_unsplit(chunk):
 
 
 def test_chunk_choice_by_hand_and_on_drawn_batches():
-    """choose_prefill_chunk: a hand-worked case per branch, and on drawn batches that the count is the real
-    list's and every larger candidate was too short."""
+    """choose_prefill_chunk: hand-worked cases for every branch, and on drawn batches the rule restated from a
+    token-by-token count of the keys."""
     import oracle
     from oracle import choose_prefill_chunk
     owner = np.zeros((2, 1), dtype=np.int32)
-    # one pair, 100 processed + 28 new tokens, tiles of 16: tile 0 sees 116 keys, tile 1 sees 128.
+    # one pair, 100 processed + 28 new tokens, tiles of 16: tile 0 sees 116 keys, tile 1 sees 128: T = 244.
     n_done, n_new = [100, 0], [28, 0]
-    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 2) == (256, 2)       # long enough at once
-    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 3) == (64, 4)        # 128: 2 items, 64: 2 + 2
-    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 100) == (32, 8)      # down to the floor: 4 + 4
-    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 96, 32, 5) == (32, 8)         # 96 -> 48 is no multiple of 32: 32
-    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 0) == (256, 2)       # nothing asked for
-    with pytest.raises(ValueError):
-        choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 100, 32, 1)
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 2) == (192, 2)     # ceil(4*244/6) = 163 -> 192; 1 + 1 items
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 1) == (256, 2)     # 326 -> 352, held to the largest
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 100) == (32, 8)    # ceil(976/300) = 4 -> 32; 4 + 4 items
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 64, 100) == (64, 4)    # held to the smallest; 2 + 2 items
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 5) == (96, 4)      # ceil(976/15) = 66 -> 96; 2 + 2 items
+    assert choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, 256, 32, 8) == (64, 4)      # ceil(976/24) = 41 -> 64
+    # both KV heads of the request on this rank: twice the keys
+    both = np.zeros((2, 2), dtype=np.int32)
+    assert choose_prefill_chunk(n_done, n_new, both, 0, 4, 16, 256, 32, 4) == (192, 4)
+    assert choose_prefill_chunk(n_done, n_new, both, 1, 4, 16, 256, 32, 4) == (32, 0)       # nothing on rank 1: the smallest, no items
+    # a last tile of 12 tokens counts its own keys: 3 tiles of 100+16, 100+32, 100+44
+    assert choose_prefill_chunk([100], [44], np.zeros((1, 1), dtype=np.int32), 0, 1, 16, 1024, 32, 1) == (544, 3)   # T = 392: 523 -> 544
+    for bad in ((100, 32, 1), (64, 128, 1), (64, 16, 1), (64, 32, 0)):
+        with pytest.raises(ValueError):
+            choose_prefill_chunk(n_done, n_new, owner, 0, 2, 16, *bad)
     rng = np.random.default_rng(21)
-    for _ in range(40):
+    for _ in range(60):
         B, H, R = int(rng.integers(1, 6)), int(rng.integers(1, 4)), int(rng.integers(1, 3))
         n_done = rng.integers(0, 3000, size=B); n_new = rng.integers(0, 200, size=B)
         owner = rng.integers(0, R, size=(B, H)).astype(np.int32)
-        tile = int(rng.integers(1, 33)); want_items = int(rng.integers(0, 60))
+        tile = int(rng.integers(1, 33)); slots = int(rng.integers(1, 600))
         mx = 32 * int(rng.integers(1, 65)); mn = 32 * int(rng.integers(1, mx // 32 + 1))
-        C, n = choose_prefill_chunk(n_done, n_new, owner, 0, 2 * H, tile, mx, mn, want_items)
+        C, n = choose_prefill_chunk(n_done, n_new, owner, 0, 2 * H, tile, mx, mn, slots)
         assert n == len(oracle.build_prefill_worklist(n_done, n_new, owner, 0, 2 * H, tile, C)[0]) and mn <= C <= mx and C % 32 == 0
-        c = mx
-        while c != C:                      # every larger candidate was too short
-            assert len(oracle.build_prefill_worklist(n_done, n_new, owner, 0, 2 * H, tile, c)[0]) < want_items
-            c = (c // 2) // 32 * 32
-        assert n >= want_items or (C // 2) // 32 * 32 < mn
+        # the keys, token by token: the last token of a tile sees what the tile sees
+        T = sum(int(n_done[r]) + i + 1 for r in range(B) for h in range(H) if owner[r, h] == 0
+                for i in range(int(n_new[r])) if (i + 1) % tile == 0 or i + 1 == int(n_new[r]))
+        share = 4 * T / (3 * slots)
+        assert C == mx or C >= share                       # long enough for four thirds of a share, unless held to the largest
+        assert C == mn or C - 32 < share                   # and not a step longer, unless held to the smallest
