@@ -349,9 +349,18 @@ __device__ __forceinline__ void arrive_and_merge(const DecodeParams& P, int n, c
     if (threadIdx.x == 0) __hip_atomic_store(P.pair_counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const float* po = P.part_o;
     const float* pl = P.part_lse;
-    for (int g = wave; g < G; g += WAVES)
-      fs_merge::merge_rows<1, true>(po, pl, prow / G, chunks, G, g, P.out + (static_cast<int64_t>(pair) * G + g) * fs::kHeadDim,
-                              P.lse + static_cast<int64_t>(pair) * G + g, lane);
+    // a wavefront takes as many q-heads side by side as divide the group evenly over the workgroup (their loads travel
+    // together: one trip to memory instead of one per q-head); the sums of a row are the same in every form
+    const int64_t c0 = prow / G;
+    float* const out0 = P.out + static_cast<int64_t>(pair) * G * fs::kHeadDim;
+    float* const lse0 = P.lse + static_cast<int64_t>(pair) * G;
+    if (G % (2 * WAVES) == 0) {
+      for (int g = 2 * wave; g < G; g += 2 * WAVES)
+        fs_merge::merge_rows<2, true>(po, pl, c0, chunks, G, g, out0 + g * fs::kHeadDim, lse0 + g, lane);
+    } else {
+      for (int g = wave; g < G; g += WAVES)
+        fs_merge::merge_rows<1, true>(po, pl, c0, chunks, G, g, out0 + g * fs::kHeadDim, lse0 + g, lane);
+    }
   }
 }
 
