@@ -35,7 +35,7 @@ MEASURED_TRAFFIC_BYTES = {
     (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1971832723,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt
     (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408070099,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt
     (1, 0, 20251115, 2048, "requests", "decode_bf16_kernel"): 407998268,                      # profiles/decode_bf16_kernel_cfg1_8b_hybrid_rank0.txt
-    (3, 0, 20251117, 512, "requests", "decode_bf16_kernel"): 69914282,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
+    (3, 0, 20251117, 688, "requests", "decode_bf16_kernel"): 69331506,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
     (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3261385,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
     (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561952676,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
 }
@@ -142,7 +142,7 @@ def main() -> int:
     n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
 
     def chunk_for(rank):
-        """The config's chunk; where it is the builder's choice, halved until the rank's list has an item per CU."""
+        """The config's chunk; where it is the builder's choice, four thirds of a compute unit's share of the rank's tokens."""
         if args.chunk is not None:
             return args.chunk
         if w.get("chunk_adaptive") and w["chunk_tokens"] > MIN_CHUNK:

@@ -215,21 +215,21 @@ FS_API fs_status fs_build_worklist_units(const fs_shape* shape, const int32_t* c
 /* ---------------------------------------------------------------------------
  * fs_choose_chunk_tokens - a split-K chunk size for one rank's share.  The ragged share of
  * Section 3.1 can be a handful of very long contexts (the skew the paper's load-aware routing is
- * there for); a list with fewer items than the GPU has compute units leaves most of it idle, so
- * the chunk is halved, from max_chunk down (rounded down to whole pages), until rank's list, as
- * fs_build_worklist would build it, has at least min_items items or the next halving would go
- * below min_chunk.
+ * there for), and a launch runs as long as its longest item.  The chunk is four thirds of a slot's fair
+ * share of the whole: with T the cached tokens of rank's (request, KV head) pairs, all told,
+ * ceil(4 T / (3 n_slots)), rounded up to whole pages and held within [min_chunk, max_chunk].
  *
  *  ctx_len, owner   HOST in   as for fs_build_worklist
  *  max_chunk, min_chunk       multiples of page_tokens, page_tokens <= min_chunk <= max_chunk
- *  min_items        the length the list should reach (e.g. the number of compute units)
+ *  n_slots          workgroups the GPU should be running at a time (the number of compute units
+ *                   measures best for the decode sweep), >= 1
  *  chunk_tokens     HOST out  the chosen chunk
  *  n_items          HOST out  the list's length with it
  *
- * FS_EINVAL: bad shape, rank, chunk bounds, min_items < 0, owner outside [0, R), ctx_len < 1.
+ * FS_EINVAL: bad shape, rank, chunk bounds, n_slots < 1, owner outside [0, R), ctx_len < 1.
  */
 FS_API fs_status fs_choose_chunk_tokens(const fs_shape* shape, const int32_t* ctx_len, const int32_t* owner,
-                                        int32_t rank, int32_t max_chunk, int32_t min_chunk, int64_t min_items,
+                                        int32_t rank, int32_t max_chunk, int32_t min_chunk, int64_t n_slots,
                                         int32_t* chunk_tokens, int64_t* n_items);
 
 /* ---------------------------------------------------------------------------

@@ -52,22 +52,23 @@ def build_worklist(ctx_len, owner, rank: int, chunk_tokens: int, n_q_heads: int,
     return items, pairs, np.array(sched, dtype=np.int32), np.array(indptr, dtype=np.int64)
 
 
-def choose_chunk_tokens(ctx_len, owner, rank: int, max_chunk: int, min_chunk: int, min_items: int,
+def choose_chunk_tokens(ctx_len, owner, rank: int, max_chunk: int, min_chunk: int, n_slots: int,
                         n_kv_heads: int, page_tokens: int = 16):
-    """Halve the split-K chunk from ``max_chunk`` down (whole pages) until ``rank``'s list has at least
-    ``min_items`` items or the next halving would fall below ``min_chunk``.  -> (chunk, n_items).
-    The chunk is this build's device for long contexts, not the paper's; the item count is that of
-    ``build_worklist`` with the same chunk."""
+    """The split-K chunk for ``rank``'s share: four thirds of a slot's fair share of the tokens.  With T the cached
+    tokens of the rank's (request, head) pairs, all told, and ``n_slots`` the workgroups the GPU should be running at a
+    time, the chunk is ceil(4 T / (3 n_slots)) rounded up to whole pages and held within [min_chunk, max_chunk].
+    -> (chunk, n_items).  The chunk is this build's device for long contexts, not the paper's: the ragged share of
+    Section 3.1 can be a handful of very long contexts, which would run as long as the longest takes; an item about as
+    long as a slot's share of the whole keeps any from sticking out without cutting finer than that needs.  The item
+    count is that of ``build_worklist`` with the same chunk."""
     if min_chunk < page_tokens or min_chunk % page_tokens or max_chunk < min_chunk or max_chunk % page_tokens:
         raise ValueError("chunk bounds must be whole pages, min <= max")
+    if n_slots < 1:
+        raise ValueError("n_slots < 1")
     lens = [int(ctx_len[r]) for r in range(len(ctx_len)) for h in range(n_kv_heads) if int(owner[r][h]) == rank]
-    C = int(max_chunk)
-    while True:
-        n = sum(-(-L // C) for L in lens)
-        nxt = (C // 2) // page_tokens * page_tokens
-        if n >= min_items or nxt < min_chunk:
-            return C, n
-        C = nxt
+    target = -(-4 * sum(lens) // (3 * int(n_slots)))
+    C = min(max(-(-target // page_tokens) * page_tokens, int(min_chunk)), int(max_chunk))
+    return C, sum(-(-L // C) for L in lens)
 
 
 def build_worklist_units(ctx_len, owner, rank: int, n_units: int, n_q_heads: int, n_kv_heads: int,

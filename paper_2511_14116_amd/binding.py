@@ -303,16 +303,17 @@ def fs_build_launch_records(shape: FsShape, items, order, chunk_indptr, page_ind
 
 
 def fs_choose_chunk_tokens(shape: FsShape, ctx_len, owner, rank: int, max_chunk: int, min_chunk: int,
-                           min_items: int):
-    """-> (chunk_tokens, n_items): the split-K chunk, halved from ``max_chunk`` down to at least ``min_chunk``,
-    with which ``rank``'s list reaches ``min_items`` items."""
+                           n_slots: int):
+    """-> (chunk_tokens, n_items): the split-K chunk for ``rank``'s share, four thirds of the share of the cached tokens
+    that one of ``n_slots`` concurrently running workgroups would get, in whole pages within [min_chunk, max_chunk], and
+    the list's length with it."""
     lib = load_library()
     ctx = _host(ctx_len, np.int32)
     own = _host(owner, np.int32)
     i32p = C.POINTER(C.c_int32)
     chunk, n_items = C.c_int32(0), C.c_int64(0)
     _check(lib.fs_choose_chunk_tokens(C.byref(shape), ctx.ctypes.data_as(i32p), own.ctypes.data_as(i32p), rank,
-                                      max_chunk, min_chunk, min_items, C.byref(chunk), C.byref(n_items)))
+                                      max_chunk, min_chunk, n_slots, C.byref(chunk), C.byref(n_items)))
     return chunk.value, n_items.value
 
 

@@ -110,7 +110,7 @@ extern "C" fs_status fs_build_placement_hybrid_heads(const fs_shape* shape, cons
 }
 
 extern "C" fs_status fs_choose_chunk_tokens(const fs_shape* shape, const int32_t* ctx_len, const int32_t* owner,
-                                            int32_t rank, int32_t max_chunk, int32_t min_chunk, int64_t min_items,
+                                            int32_t rank, int32_t max_chunk, int32_t min_chunk, int64_t n_slots,
                                             int32_t* chunk_tokens, int64_t* n_items) {
   if (fs_status st = check_shape(shape, "fs_choose_chunk_tokens")) return st;
   const int32_t B = shape->n_req, H = shape->n_kv_heads, R = shape->n_ranks, T = shape->page_tokens;
@@ -120,7 +120,7 @@ extern "C" fs_status fs_choose_chunk_tokens(const fs_shape* shape, const int32_t
   if (min_chunk < T || min_chunk % T || max_chunk < min_chunk || max_chunk % T)
     return fs::fail(FS_EINVAL, "fs_choose_chunk_tokens: chunks [%d, %d] must be multiples of page_tokens %d, min <= max",
                     min_chunk, max_chunk, T);
-  if (min_items < 0) return fs::fail(FS_EINVAL, "fs_choose_chunk_tokens: min_items %lld < 0", static_cast<long long>(min_items));
+  if (n_slots < 1) return fs::fail(FS_EINVAL, "fs_choose_chunk_tokens: n_slots %lld < 1", static_cast<long long>(n_slots));
   if (B > 0 && (!ctx_len || !owner)) return fs::fail(FS_EINVAL, "fs_choose_chunk_tokens: NULL input array");
   for (int32_t r = 0; r < B; ++r) {
     if (ctx_len[r] < 1) return fs::fail(FS_EINVAL, "fs_choose_chunk_tokens: ctx_len[%d] = %d < 1", r, ctx_len[r]);
@@ -130,23 +130,23 @@ extern "C" fs_status fs_choose_chunk_tokens(const fs_shape* shape, const int32_t
         return fs::fail(FS_EINVAL, "fs_choose_chunk_tokens: owner[%d][%d] = %d outside [0, %d)", r, h, k, R);
     }
   }
-  // Halve from max_chunk (keeping whole pages) until the list is long enough or min_chunk is reached.
-  int64_t C = max_chunk;
-  for (;;) {
-    int64_t ni = 0;
-    for (int32_t r = 0; r < B; ++r) {
-      const int64_t nc = (static_cast<int64_t>(ctx_len[r]) + C - 1) / C;
-      for (int32_t h = 0; h < H; ++h)
-        if (owner[static_cast<int64_t>(r) * H + h] == rank) ni += nc;
-    }
-    int64_t next = (C / 2) / T * T;
-    if (ni >= min_items || next < min_chunk) {
-      *chunk_tokens = static_cast<int32_t>(C);
-      *n_items = ni;
-      return FS_OK;
-    }
-    C = next;
+  // Four thirds of a slot's fair share of the tokens the rank holds, up to whole pages, within the bounds.
+  int64_t total = 0;
+  for (int32_t r = 0; r < B; ++r)
+    for (int32_t h = 0; h < H; ++h)
+      if (owner[static_cast<int64_t>(r) * H + h] == rank) total += ctx_len[r];
+  const int64_t target = (4 * total + 3 * n_slots - 1) / (3 * n_slots);
+  int64_t C = (target + T - 1) / T * T;
+  C = std::min<int64_t>(std::max<int64_t>(C, min_chunk), max_chunk);
+  int64_t ni = 0;
+  for (int32_t r = 0; r < B; ++r) {
+    const int64_t nc = (static_cast<int64_t>(ctx_len[r]) + C - 1) / C;
+    for (int32_t h = 0; h < H; ++h)
+      if (owner[static_cast<int64_t>(r) * H + h] == rank) ni += nc;
   }
+  *chunk_tokens = static_cast<int32_t>(C);
+  *n_items = ni;
+  return FS_OK;
 }
 
 extern "C" fs_status fs_build_worklist(const fs_shape* shape, const int32_t* ctx_len,

@@ -392,14 +392,14 @@ def test_chunk_choice_matches_oracle():
         owner = rng.integers(0, R, size=(B, H)).astype(np.int32)
         sh = _shape(B, 2 * H, H, R)
         for rank in range(R):
-            for max_c, min_c, want in ((2048, 256, 256), (4096, 16, 37), (512, 512, 10 ** 5), (2048, 48, 0), (48, 16, 9)):
+            for max_c, min_c, want in ((2048, 256, 256), (4096, 16, 37), (512, 512, 10 ** 5), (2048, 48, 1), (48, 16, 9)):      # want: slots
                 got = fs.fs_choose_chunk_tokens(sh, ctx, owner, rank, max_c, min_c, want)
                 assert got == oracle.choose_chunk_tokens(ctx, owner, rank, max_c, min_c, want, H)
                 items, _, _, _ = fs.fs_build_worklist(sh, ctx, owner, rank, got[0])
                 assert len(items) == got[1]
     sh = _shape(2, 4, 2, 2)
     ctx, owner = np.array([5, 9], dtype=np.int32), np.zeros((2, 2), dtype=np.int32)
-    for bad in ((64, 24, 1), (16, 32, 1), (64, 8, 1), (64, 16, -1)):
+    for bad in ((64, 24, 1), (16, 32, 1), (64, 8, 1), (64, 16, 0)):
         with pytest.raises(fs.FsError):
             fs.fs_choose_chunk_tokens(sh, ctx, owner, 0, *bad)
     with pytest.raises(fs.FsError):

@@ -84,35 +84,38 @@ def test_rejects_bad_chunk_and_heads():
 
 
 def test_chunk_choice_by_hand():
-    # rank 0 holds three pairs of 40, 20 and 20 tokens (the tiny list above)
+    # rank 0 holds three pairs of 40, 20 and 20 tokens (the tiny list above): T = 80
     ctx = np.array([40, 20], dtype=np.int32)
     owner, _, _ = build_placement(ctx, [0, 1], 2, 2)
-    # chunk 64: 3 items; 32: 2+1+1 = 4; 16: 3+2+2 = 7
-    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 3, 2) == (64, 3)
-    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 4, 2) == (32, 4)
-    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 5, 2) == (16, 7)
+    # chunk 64: 3 items; 48: 3; 32: 2+1+1 = 4; 16: 3+2+2 = 7
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 1, 2) == (64, 3)        # ceil(320/3) = 107 -> 112 pages' worth, held to 64
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 2, 2) == (64, 3)        # ceil(320/6) = 54 -> 64
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 3, 2) == (48, 3)        # ceil(320/9) = 36 -> 48
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 4, 2) == (32, 4)        # ceil(320/12) = 27 -> 32
+    assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 8, 2) == (16, 7)        # ceil(320/24) = 14 -> 16
     assert choose_chunk_tokens(ctx, owner, 0, 64, 16, 100, 2) == (16, 7)      # never below min_chunk
     assert choose_chunk_tokens(ctx, owner, 0, 64, 32, 100, 2) == (32, 4)
-    assert choose_chunk_tokens(ctx, owner, 0, 48, 16, 4, 2) == (16, 7)        # 48 -> 24 rounds down to one page
-    assert choose_chunk_tokens(ctx, owner, 1, 64, 16, 0, 2) == (64, 1)        # nothing asked for: the largest chunk
-    with pytest.raises(ValueError):
-        choose_chunk_tokens(ctx, owner, 0, 64, 24, 1, 2)
+    assert choose_chunk_tokens(ctx, owner, 1, 64, 16, 1, 2) == (64, 1)        # rank 1 holds one pair of 40 tokens: 54 -> 64
+    assert choose_chunk_tokens(ctx, owner, 1, 64, 16, 2, 2) == (32, 2)        # ceil(160/6) = 27 -> 32
+    for bad in ((64, 24, 1), (64, 16, 0)):
+        with pytest.raises(ValueError):
+            choose_chunk_tokens(ctx, owner, 0, *bad, 2)
 
 
 @pytest.mark.parametrize("seed", range(6))
 def test_chunk_choice_properties(seed):
     ctx, owner, _ = _case(seed, 40, 3, 4, 0.3, lo=1, hi=30000)
     for rank in range(3):
-        for min_items in (0, 1, 50, 256, 10 ** 6):
-            C, n = choose_chunk_tokens(ctx, owner, rank, 2048, 256, min_items, 4)
-            assert C in (2048, 1024, 512, 256)
+        whole, _, _, _ = build_worklist(ctx, owner, rank, 0, 8, 4)         # one item per pair: its tokens
+        T = int(sum(int(it[3]) - int(it[2]) for it in whole))
+        for slots in (1, 7, 50, 256, 10 ** 6):
+            C, n = choose_chunk_tokens(ctx, owner, rank, 2048, 256, slots, 4)
+            assert 256 <= C <= 2048 and C % 16 == 0
             items, _, _, _ = build_worklist(ctx, owner, rank, C, 8, 4)
             assert n == len(items)                              # the count is the real list's
-            if C < 2048:                                        # every larger candidate was too short
-                bigger, _, _, _ = build_worklist(ctx, owner, rank, 2 * C, 8, 4)
-                assert len(bigger) < min_items
-            if n < min_items:
-                assert C == 256
+            share = 4 * T / (3 * slots)
+            assert C == 2048 or C >= share                      # four thirds of a slot's share fit in a chunk, unless held to the largest
+            assert C == 256 or C - 16 < share                   # and not a page more, unless held to the smallest
 
 
 # ---- the list cut into equal runs of pages (one per resident workgroup) ---------------------------------
