@@ -87,6 +87,8 @@ def main() -> int:
     ap.add_argument("--all-ranks", action="store_true", help="also time every rank's share in turn (kernels only) and report the spread")
     ap.add_argument("--force-tail", action="store_true", help="config 3: request 0 gets 131072 tokens")
     ap.add_argument("--seed", type=int, default=None, help="draw the batch from this seed instead of the config's own")
+    ap.add_argument("--kv-dtype", choices=["bf16", "fp8"], default=None,
+                    help="keep the config's batch but hold its K/V in this type (fp8: e4m3 with a scale per slot)")
     ap.add_argument("--path", choices=["decode", "prefill"], default="decode",
                     help="decode: the measured decode-attention share (default); prefill: the chunked-prefill attention share")
     ap.add_argument("--prefill-waves", type=int, default=None)
@@ -130,6 +132,8 @@ def main() -> int:
     # ---- synthetic batch ---------------------------------------------------------------------
     kw = dict(force_first_len=131072) if (args.config == 3 and args.force_tail) else {}
     w = make_requests(args.config, seed=args.seed, **kw)
+    if args.kv_dtype:
+        w["kv_dtype"] = args.kv_dtype
     MIN_CHUNK = 256          # floor of the adaptive split-K chunk (tokens)
     B, Hq, Hkv, R, G = w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["n_ranks"], w["group"]
     shape = fs.FsShape(B, Hq, Hkv, w["head_dim"], w["page_tokens"], R)
@@ -605,7 +609,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {w['name']}: B={B}, Hq={Hq}, Hkv={Hkv}, d=128, page=16, "
                                f"R={R}, rank {args.rank}, " + (f"{n_units} equal runs of pages" if units else f"chunk={chunk}") + f", seed={w['seed']}"
-                               + (", head-level hybrid placement" if args.placement == "heads" else ""),
+                               + (", head-level hybrid placement" if args.placement == "heads" else "")
+                               + (f", K/V held as {args.kv_dtype}" if args.kv_dtype else ""),
                    "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
                    "sweep": "one resident workgroup per run of pages" if units else ("persistent" if persistent else "one workgroup per item"),
@@ -615,6 +620,7 @@ def main() -> int:
                    "merge_launched": bool(args.two_calls or (n_items > n_pairs and not (use_records and merge_in_sweep))),
                    "split_pairs_merged": "by a merge kernel" if (args.two_calls or not use_records or not merge_in_sweep) else
                                          "inside the sweep, by the workgroup that writes a pair's last partial rows",
+                   "kernel": kernel_name,
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),
                    "kv_layout": "separate" if args.separate_kv else "interleaved",

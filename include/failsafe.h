@@ -40,7 +40,7 @@
 extern "C" {
 #endif
 
-#define FS_ABI_VERSION 2
+#define FS_ABI_VERSION 3
 
 #if defined(__GNUC__)
 #define FS_API __attribute__((visibility("default")))
@@ -366,7 +366,7 @@ FS_API fs_status fs_plan_ffn_reload(int32_t n_shards, const int32_t* shard_owner
  *
  *  bf16 K (16 tok x 128):  [d/32][(d%32)/8][tok][d%8]
  *  bf16 V (16 tok x 128):  [d/32][tok/4][d%16][(d/16)%2][tok%4]
- *  fp8  K and V         :  [tok][d]   (token-major, 128 bytes per token)
+ *  fp8  K and V         :  [d/64][(d%64)/16][tok][d%16]   (a 16-byte piece per (token, 16 d))
  *
  * fp8 is OCP e4m3 (finite-only, max 448); element value = code * scale[slot]
  * with one fp32 scale per slot for K and one for V.
@@ -397,9 +397,8 @@ FS_API int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, in
 
 /* fs_pack_kv_slots - KVCache blocks (Section 2.1.1) from token-major order [tok][d] into the element order
  * above, on the device: slot s is read at src_dev + s*src_slot_stride and written at dst_dev +
- * s*dst_slot_stride (so the destination may be the K or the V half of an interleaved pool).  fp8 slots
- * are token-major in both orders and are copied.  The stand-in for an engine's KV-append step, which
- * would write the kernels' order directly.
+ * s*dst_slot_stride (so the destination may be the K or the V half of an interleaved pool).  The stand-in
+ * for an engine's KV-append step, which would write the kernels' order directly.
  *
  *  src_dev  DEVICE in   n_slots slots of 16 x 128 elements, token-major
  *  dst_dev  DEVICE out  the same slots in kernel order; the two pools must not overlap
@@ -428,7 +427,7 @@ FS_API fs_status fs_pack_kv_slots(const void* src_dev, int64_t src_slot_stride, 
  *
  * n_items == 0 is a no-op.  FS_EINVAL: NULL pointers, bad shape, G > 16,
  * misaligned pools/strides.  FS_EUNSUPPORTED: head_dim != 128, page_tokens !=
- * 16, fp8 with G > 8.  FS_EHIP: launch failure.  Item contents are trusted
+ * 16.  FS_EHIP: launch failure.  Item contents are trusted
  * (they are device memory); build them with fs_build_worklist.
  */
 FS_API fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv,

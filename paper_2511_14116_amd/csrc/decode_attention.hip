@@ -19,8 +19,8 @@
 //   softmax weights never move between lanes; only the running max needs a 2-step cross-lane
 //   exchange.  Wavefronts merge (max, sum, O) through LDS at the end of the item.
 //
-// fp8 path (e4m3 K/V with one fp32 scale per slot, small groups): plain fp32 VALU, since with
-// one q-head per KV head there is no dense contraction to give the matrix cores.
+// fp8 path (e4m3 K/V with one fp32 scale per slot): the same two products on the matrix cores; K is converted
+// to bf16 in registers and V is transposed by a product with a constant matrix (see decode_fp8_kernel).
 //
 // Forms of the sweep, all with the same arithmetic per item (their rows agree bit for bit): one workgroup
 // per item; resident workgroups that claim items from a counter; resident workgroups on equal runs of pages
@@ -32,7 +32,6 @@
 #include <algorithm>
 #include <cmath>
 #include <mutex>
-#include <type_traits>
 
 #include "fs_internal.h"
 #include "merge_row.h"
@@ -377,8 +376,13 @@ __device__ __forceinline__ void arrive_and_merge_one(const DecodeParams& P, cons
   arrive_and_merge<WAVES>(P, 1, s_meta, s_meta + 1, s_meta + 2, s_meta + 3, G, wave, lane);
 }
 
-// Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.
-template <int WAVES>
+// Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.  A lane's acc[j] holds four
+// consecutive d of its q-head, from d = 16j + 4*(lane/16) on in the bf16 kernels; FP8_ORDER: from
+// fp8_first_d(j, lane/16) on (decode_fp8_kernel below).
+__device__ __forceinline__ int fp8_first_d(int j, int kb) {
+  return 64 * (j >> 2) + 32 * (j & 1) + 16 * (kb >> 1) + 8 * ((j >> 1) & 1) + 4 * (kb & 1);
+}
+template <int WAVES, bool FP8_ORDER = false>
 __device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_total, int wave, int lane,
                                                 int G, float* __restrict__ part_o,
                                                 float* __restrict__ part_lse, int part_row,
@@ -388,9 +392,9 @@ __device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_
     sm_m[wave * 16 + lane] = st.m;
     sm_l[wave * 16 + lane] = l_total;
   }
-  float* row = sm_o + (wave * 16 + qi) * kORow + 4 * kb;
+  float* row = sm_o + (wave * 16 + qi) * kORow;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + 16 * j) = st.acc[j];
+  for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + (FP8_ORDER ? fp8_first_d(j, kb) : 16 * j + 4 * kb)) = st.acc[j];
   __syncthreads();
   for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
     const int q = idx >> 5, d4 = idx & 31;
@@ -672,36 +676,28 @@ __global__ void __launch_bounds__(WAVES * 64, 2) decode_bf16_persistent_kernel(c
 }
 
 // ---------------------------------------------------------------------------------------------
-// fp8 e4m3 path.  Slots are token-major (128 bytes per token).  Lane (c = lane%8, ts = lane/8)
-// owns d in [16c, 16c+16) and the tokens ts and ts+8 of every page, so one wave-wide 16-byte
-// load covers eight whole token rows (1 KiB contiguous).  The 8 lanes of a token row add their
-// partial dot products with three DPP steps; each of the 8 token subsets keeps its own running
-// (max, sum, o[16]) so nothing else crosses lanes until the item ends.
+// fp8 e4m3 path (one fp32 scale per slot for K and one for V), on the matrix cores for every group size.
+//
+// The slot order [d/64][(d%64)/16][tok][d%16] makes a wave-wide 16-byte load one contiguous 1 KiB run in which
+// lane (tok = lane%16, kb = lane/16) receives 16 consecutive d of its token: d = 64j + 16kb .. for load j = 0, 1
+// (whole 128-byte lines per instruction; with token-major slots the same lanes read half lines and the launch
+// ran at two thirds of the rate, bound by the number of requests a CU may have pending).
+//
+// The first product wants exactly that: a lane holds 8 consecutive d of one token per instruction,
+// d = 64j + 16kb + 8half + e for instruction c = 2j + half (any order of d will do as long as the query operand
+// follows it); K is converted e4m3 -> bf16 in registers, which is exact.
+//     S^T[tok][q] = K . Q^T      4 x v_mfma_f32_16x16x32_bf16, times scale * k_scale of the page
+// The second product reduces over tokens, so it wants a lane to hold several tokens of one d: the transpose of
+// what was loaded.  The matrix cores do that on the way: V's bytes go in as they are, as the A operand of an fp8
+// product whose B operand is a constant matrix of ones and zeros that picks 16 of the 32 d of the slice,
+//     T[tok][n] = sum_k V[tok][k] * E[k][n] = V[tok][d(n)]      8 x v_mfma_f32_16x16x32_fp8_fp8
+// exact in fp32 (one product by 1.0 plus zeros), and the result layout (lane n + 16kb holds tokens 4kb .. 4kb+3 of
+// column n) is the A-operand layout of
+//     O^T[d(n)][q] += V^T . P^T  16 x v_mfma_f32_16x16x16_bf16 (weights times v_scale, as bf16 hi + lo)
+// after packing T to bf16 (exact again).  The rows of O^T come out in the order fp8_first_d states.
+// A kernel that multiplied on the vector units instead (each K and V value once per q-head) kept pace with the
+// page stream for one q-head per KV head and not beyond: with eight it ran at a quarter of this one's rate.
 // ---------------------------------------------------------------------------------------------
-
-__device__ __forceinline__ void cvt16(const u32x4 raw, float (&f)[16]) {
-  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], false);
-    const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], true);
-    f[4 * i + 0] = lo[0]; f[4 * i + 1] = lo[1]; f[4 * i + 2] = hi[0]; f[4 * i + 3] = hi[1];
-  }
-}
-
-// Sum over the 8 lanes that share a token row (lanes 8k .. 8k+7), left in all of them: two quad
-// permutes and a half-row mirror, all as DPP operands of the add (no LDS traffic).
-template <int CTRL>
-__device__ __forceinline__ float dpp_read(float v) {
-  return __uint_as_float(static_cast<uint32_t>(
-      __builtin_amdgcn_update_dpp(0, static_cast<int>(__float_as_uint(v)), CTRL, 0xF, 0xF, true)));
-}
-__device__ __forceinline__ float sum_over_8_lanes(float v) {
-  v += dpp_read<0xB1>(v);     // quad_perm [1,0,3,2]: lane ^ 1
-  v += dpp_read<0x4E>(v);     // quad_perm [2,3,0,1]: lane ^ 2
-  v += dpp_read<0x141>(v);    // row_half_mirror: lane i of a group of 8 reads lane 7 - i, the other quad
-  return v;
-}
 
 struct Fp8Page {
   u32x4 k[2];
@@ -709,8 +705,6 @@ struct Fp8Page {
   float ks, vs;
 };
 
-// `page` is the page's position in the whole page table (scales kept in page-table order are read as a
-// contiguous run along an item, eight pages to a 64-byte line, instead of one line per slot).
 __device__ __forceinline__ void load_page_fp8(Fp8Page& r, const DecodeParams& P, int32_t slot, int64_t page, int lane) {
   const u32x4* kp = reinterpret_cast<const u32x4*>(P.k_pool + slot * P.k_stride) + lane;
   const u32x4* vp = reinterpret_cast<const u32x4*>(P.v_pool + slot * P.v_stride) + lane;
@@ -723,98 +717,139 @@ __device__ __forceinline__ void load_page_fp8(Fp8Page& r, const DecodeParams& P,
   r.vs = P.v_scale[si];
 }
 
-template <int WAVES, int NBUF, int GMAX>
-__global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodeParams P) {
-  // merge buffer: [wave][token subset][g] (m, l) and o[128]
-  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 8 * GMAX * kORow];
-  __shared__ float sm_m[WAVES * 8 * GMAX];
-  __shared__ float sm_l[WAVES * 8 * GMAX];
+// Two fp32 values to one dword of two bf16 by dropping the low halves (exact for values that are bf16 already).
+__device__ __forceinline__ uint32_t pack_bf16_trunc(float lo, float hi) {
+  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+
+// Eight e4m3 bytes (two dwords) to the eight bf16 of a first-product operand: exact, one instruction per pair
+// (the conversion takes a power-of-two scale; 1.0 is 2^0).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
+  const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false);
+  const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, true);
+  const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, false);
+  const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, true);
+  const u32x4 r = {__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, c),
+                   __builtin_bit_cast(uint32_t, d)};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+template <bool FULL>
+__device__ __forceinline__ void consume_page_fp8(SoftmaxState& st, const Fp8Page& pg, const bf16x8 (&qreg)[4],
+                                                  const long (&pick)[2], float scale_log2, int valid, int kb) {
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp8x8_to_bf16x8(pg.k[j].x, pg.k[j].y), qreg[2 * j], s, 0, 0, 0);
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp8x8_to_bf16x8(pg.k[j].z, pg.k[j].w), qreg[2 * j + 1], s, 0, 0, 0);
+  }
+  // V's eight transposes go to the matrix cores now and run under the softmax below
+  f32x4 t[8];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const uint32_t w[4] = {pg.v[j].x, pg.v[j].y, pg.v[j].z, pg.v[j].w};
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const long bytes = static_cast<long>((static_cast<unsigned long>(w[2 * half + 1]) << 32) | w[2 * half]);
+      const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2)
+        t[4 * j + 2 * half + h2] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(bytes, pick[h2], z, 0, 0, 0);
+    }
+  }
+  const float sc = scale_log2 * pg.ks;
+  float x[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) x[r] = s[r] * sc;
+  uint32_t m0 = 0xFFFFFFFFu, m1 = 0xFFFFFFFFu;
+  if (!FULL && valid < fs::kPageTokens) {   // last page of the context: tokens past the end do not exist
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (4 * kb + r >= valid) x[r] = -INFINITY;
+    m0 = (4 * kb + 0 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid ? 0xFFFF0000u : 0u);
+    m1 = (4 * kb + 2 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid ? 0xFFFF0000u : 0u);
+  }
+  float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+  mx = max_xor32(max_xor16(mx));
+  const float m_new = fmaxf(st.m, mx);
+  if (__any(m_new > st.m)) {
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // first page: exp2(-inf) = 0
+    st.l *= alpha;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
+    st.m = m_new;
+  }
+  float p[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(x[r] - st.m);
+  st.l += (p[0] + p[1]) + (p[2] + p[3]);
+  // The weights enter the second product as bf16 hi + lo (16 bits; see consume_page), times the page's V scale.
+  // hi is the value cut to bf16, lo what is left, cut again: two instructions per pair and two per value.
+  float pv[4], rest[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    pv[r] = p[r] * pg.vs;
+    rest[r] = pv[r] - __uint_as_float(__float_as_uint(pv[r]) & 0xFFFF0000u);
+  }
+  const uint2 hi2 = make_uint2(pack_bf16_trunc(pv[0], pv[1]), pack_bf16_trunc(pv[2], pv[3]));
+  const uint2 lo2 = make_uint2(pack_bf16_trunc(rest[0], rest[1]), pack_bf16_trunc(rest[2], rest[3]));
+  const s16x4 pb = __builtin_bit_cast(s16x4, hi2), pc = __builtin_bit_cast(s16x4, lo2);
+  s16x4 va[8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a) {
+    uint2 tv = make_uint2(pack_bf16_trunc(t[a][0], t[a][1]), pack_bf16_trunc(t[a][2], t[a][3]));
+    if (!FULL) { tv.x &= m0; tv.y &= m1; }   // whatever bits sit beyond the end (NaN included) must not reach the product
+    va[a] = __builtin_bit_cast(s16x4, tv);
+  }
+  // eight independent accumulators: the hi products of all, then the lo products, so that none waits for the other
+#pragma unroll
+  for (int a = 0; a < 8; ++a) st.acc[a] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[a], pb, st.acc[a], 0, 0, 0);
+#pragma unroll
+  for (int a = 0; a < 8; ++a) st.acc[a] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[a], pc, st.acc[a], 0, 0, 0);
+}
+
+// (at least two wavefronts per SIMD: within 256 registers the compiler keeps the matrix results in ordinary
+// registers; allowed 512 it parks them in accumulation registers and moves every one back before the vector units
+// can touch it, 57 extra instructions per page)
+template <int WAVES, int NBUF>
+__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+decode_fp8_kernel(const DecodeParams P) {
+  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
+  __shared__ float sm_m[WAVES * 16];
+  __shared__ float sm_l[WAVES * 16];
   __shared__ int s_meta[4];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int c = lane & 7, ts = lane >> 3;
+  const int qi = lane & 15, kb = lane >> 4;
   const int G = P.group;
-  const ItemDesc d = load_desc_head<WAVES, NBUF>(P, static_cast<int>(blockIdx.x), 0x7FFFFFFF, wave, G);
-  const int n_tok = d.n_tok;
+  ItemDesc d = load_desc_head<WAVES, NBUF>(P, static_cast<int>(blockIdx.x), 0x7FFFFFFF, wave, G);
   const int64_t first_page = (static_cast<int64_t>(d.page_hi) << 32) | static_cast<uint32_t>(d.page_lo);
-
-  // this lane's 16 d of every q row, pre-multiplied by the softmax scale (fp32)
-  float qf[GMAX][16];
+  {   // the query rows in the order of d that the K operand has: instruction c takes d = 32kb + 8c .. + 8
+    const int qrow = d.q_row + min(qi, G - 1);
+    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + 2 * kb;
 #pragma unroll
-  for (int g = 0; g < GMAX; ++g) {
-    if (g < G) {
-      const uint4* qp = reinterpret_cast<const uint4*>(P.q + static_cast<int64_t>(d.q_row + g) * fs::kHeadDim + 16 * c);
-      const uint4 a = qp[0], b = qp[1];
-      const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        qf[g][2 * i] = __uint_as_float(w[i] << 16) * P.scale_log2;
-        qf[g][2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u) * P.scale_log2;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) qf[g][i] = 0.f;
+    for (int c = 0; c < 4; ++c) {
+      u32x4 v = qp[8 * (c >> 1) + (c & 1)];
+      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
+      d.q[c] = __builtin_bit_cast(bf16x8, v);
     }
   }
+  // E[k][n] for the two halves of a 32-d slice: column n = lane%16 takes k = 16h2 + n, which sits in the lanes
+  // with kb = 2h2 + n/8 as byte n%8 (0x38 is 1.0 in e4m3)
+  long pick[2];
+#pragma unroll
+  for (int h2 = 0; h2 < 2; ++h2)
+    pick[h2] = (kb == 2 * h2 + (qi >> 3)) ? static_cast<long>(0x38ul << (8 * (qi & 7))) : 0l;
 
-  float m[GMAX], l[GMAX], o[GMAX][16];
+  SoftmaxState st;
+  st.m = -INFINITY;
+  st.l = 0.f;
 #pragma unroll
-  for (int g = 0; g < GMAX; ++g) {
-    m[g] = -INFINITY;
-    l[g] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[g][i] = 0.f;
-  }
+  for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // One page against the q rows of this lane's token subsets.  FULL: all 16 tokens exist (every page
-  // but the last of an item), so nothing is masked.  The exponentials are taken against a reference
-  // max m[g] that moves up to a token's score only when that lies more than 2^8 above it (always on a
-  // subset's first token, where m is -inf; rarely afterwards), so the 17 rescale multiplies leave the
-  // common path; weights stay below 2^8, which costs the fp32 sums nothing.
-  auto consume = [&](const Fp8Page& pg, int valid, auto full_tag) __attribute__((always_inline)) {
-    constexpr bool FULL = decltype(full_tag)::value;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {          // token ts + 8h of this page
-      const bool live = FULL || ts + 8 * h < valid;
-      float kf[16], vf[16];
-      cvt16(pg.k[h], kf);
-      cvt16(pg.v[h], vf);
-      if (!FULL) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) vf[e] = live ? vf[e] : 0.f;   // whatever bits sit there must not reach the sum
-      }
-#pragma unroll
-      for (int g = 0; g < GMAX; ++g) {
-        if (g < G) {
-          float dot = 0.f;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) dot = fmaf(qf[g][e], kf[e], dot);
-          float x = sum_over_8_lanes(dot) * pg.ks;
-          if (!FULL) x = live ? x : -INFINITY;
-          const bool move = x > m[g] + 8.0f;
-          if (__any(move)) {
-            const float alpha = move ? __builtin_amdgcn_exp2f(m[g] - x) : 1.0f;   // m = -inf: exp2(-inf) = 0
-            l[g] *= alpha;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o[g][e] *= alpha;
-            m[g] = move ? x : m[g];
-          }
-          // a subset that has seen no live token yet keeps its state at zero (m = -inf, x = -inf)
-          const float m_ref = (!FULL && m[g] == -INFINITY) ? 0.f : m[g];
-          const float p = __builtin_amdgcn_exp2f(x - m_ref);
-          l[g] += p;
-          const float pv = p * pg.vs;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) o[g][e] = fmaf(pv, vf[e], o[g][e]);
-        }
-      }
-    }
-  };
-
-  // NBUF register buffers; NBUF-1 pages are in flight while one is consumed.  The steady-state loop is
-  // branch-free (every prefetch is in range, every page is full); the ragged end is a second loop.
-  // Index i counts this wavefront's pages; its i-th page is page wave + i*WAVES of the item.
+  // the page pipeline of decode_bf16_kernel
   Fp8Page buf[NBUF];
 #pragma unroll
   for (int u = 0; u < NBUF - 1; ++u)
@@ -826,59 +861,23 @@ __global__ void __launch_bounds__(WAVES * 64) decode_fp8_kernel(const DecodePara
     for (int u = 0; u < NBUF; ++u) {
       const int pg = wave + (i + u + NBUF - 1) * WAVES;
       load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, d.ids[pg], first_page + pg, lane);
-      consume(buf[u], fs::kPageTokens, std::true_type{});
+      consume_page_fp8<true>(st, buf[u], d.q, pick, P.scale_log2, fs::kPageTokens, kb);
     }
   }
-  // here pages i .. i+NBUF-2 (those below n_mine) are in flight in buf[0 .. NBUF-2]
 #pragma unroll
   for (int u = 0; u < 2 * NBUF - 2; ++u) {
     const int pi = i + u;
     if (pi < d.n_mine) {
       const int pn = pi + NBUF - 1;
       if (pn < d.n_mine) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, d.ids[wave + pn * WAVES], first_page + wave + pn * WAVES, lane);
-      consume(buf[u % NBUF], min(fs::kPageTokens, n_tok - (wave + pi * WAVES) * fs::kPageTokens), std::false_type{});
+      consume_page_fp8<false>(st, buf[u % NBUF], d.q, pick, P.scale_log2, min(fs::kPageTokens, d.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
     }
   }
 
-  // merge the WAVES*8 token subsets of each q row
-#pragma unroll
-  for (int g = 0; g < GMAX; ++g) {
-    if (g < G) {
-      const int slot = (wave * 8 + ts) * GMAX + g;
-      if (c == 0) { sm_m[slot] = m[g]; sm_l[slot] = l[g]; }
-      float* row = sm_o + slot * kORow + 16 * c;
-#pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4)
-        *reinterpret_cast<f32x4*>(row + 4 * e4) = f32x4{o[g][4 * e4], o[g][4 * e4 + 1], o[g][4 * e4 + 2], o[g][4 * e4 + 3]};
-    }
-  }
-  __syncthreads();
   const RowDest dst = row_dest(P, d.row);
-  for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
-    const int g = idx >> 5, d4 = idx & 31;
-    float M = -INFINITY;
-    for (int s = 0; s < WAVES * 8; ++s) M = fmaxf(M, sm_m[s * GMAX + g]);
-    float L = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < WAVES * 8; ++s) {
-      const float ms = sm_m[s * GMAX + g];
-      if (ms != -INFINITY) {
-        const float wgt = __builtin_amdgcn_exp2f(ms - M);
-        L += wgt * sm_l[s * GMAX + g];
-        acc += wgt * *reinterpret_cast<const f32x4*>(sm_o + (s * GMAX + g) * kORow + 4 * d4);
-      }
-    }
-    const float inv = 1.0f / L;
-    float* to = dst.o + static_cast<int64_t>(dst.row + g) * fs::kHeadDim + 4 * d4;
-    const float lse_g = (M + __builtin_amdgcn_logf(L)) * kLn2;
-    if (P.pair_counters != nullptr && d.n_chunks > 1) {      // rows another workgroup of this launch will merge
-      store_f32x4_coherent(to, acc * inv);
-      if (d4 == 0) store_f32_coherent(dst.lse + dst.row + g, lse_g);
-    } else {
-      __builtin_nontemporal_store(acc * inv, reinterpret_cast<f32x4*>(to));
-      if (d4 == 0) __builtin_nontemporal_store(lse_g, dst.lse + dst.row + g);
-    }
-  }
+  const float l_total = sum_xor32(sum_xor16(st.l));
+  merge_and_store<WAVES, true>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l,
+                               P.pair_counters != nullptr && d.n_chunks > 1);
   arrive_and_merge_one<WAVES>(P, d, s_meta, G, wave, lane);
 }
 
@@ -930,8 +929,6 @@ fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, 
     return fs::fail(FS_EINVAL, "%s: unknown kv_dtype %d", who, kv->kv_dtype);
   if (bf16_only && kv->kv_dtype != FS_KV_BF16)
     return fs::fail(FS_EUNSUPPORTED, "%s: only bf16 K/V is built (kv_dtype %d)", who, kv->kv_dtype);
-  if (kv->kv_dtype == FS_KV_FP8_E4M3 && G > fs::kMaxGroupFp8)
-    return fs::fail(FS_EUNSUPPORTED, "%s: fp8 KV with group %d > %d", who, G, fs::kMaxGroupFp8);
   if (n_items == 0) return FS_OK;
   if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev ||
       (partials_needed && (!part_o || !part_lse)))
@@ -990,33 +987,26 @@ fs_status device_cu_count(const char* who, int* n_cu_out) {
 fs_status launch_plain(const char* who, const DecodeParams& P, int kv_dtype, int64_t n_items, hipStream_t s) {
   const int waves = fs::options().waves_per_group;
   const int nbuf = fs::options().prefetch_pages + 1;
-  const int G = P.group;
 
-#define FS_PICK(KERNEL, ...)                                                             \
+#define FS_PICK(KERNEL)                                                                  \
   switch (waves * 10 + nbuf) {                                                           \
-    case 12: return launch(who, KERNEL<1, 2 __VA_ARGS__>, 64, P, n_items, s);            \
-    case 13: return launch(who, KERNEL<1, 3 __VA_ARGS__>, 64, P, n_items, s);            \
-    case 14: return launch(who, KERNEL<1, 4 __VA_ARGS__>, 64, P, n_items, s);            \
-    case 22: return launch(who, KERNEL<2, 2 __VA_ARGS__>, 128, P, n_items, s);           \
-    case 23: return launch(who, KERNEL<2, 3 __VA_ARGS__>, 128, P, n_items, s);           \
-    case 24: return launch(who, KERNEL<2, 4 __VA_ARGS__>, 128, P, n_items, s);           \
-    case 42: return launch(who, KERNEL<4, 2 __VA_ARGS__>, 256, P, n_items, s);           \
-    case 43: return launch(who, KERNEL<4, 3 __VA_ARGS__>, 256, P, n_items, s);           \
-    case 44: return launch(who, KERNEL<4, 4 __VA_ARGS__>, 256, P, n_items, s);           \
+    case 12: return launch(who, KERNEL<1, 2>, 64, P, n_items, s);                        \
+    case 13: return launch(who, KERNEL<1, 3>, 64, P, n_items, s);                        \
+    case 14: return launch(who, KERNEL<1, 4>, 64, P, n_items, s);                        \
+    case 22: return launch(who, KERNEL<2, 2>, 128, P, n_items, s);                       \
+    case 23: return launch(who, KERNEL<2, 3>, 128, P, n_items, s);                       \
+    case 24: return launch(who, KERNEL<2, 4>, 128, P, n_items, s);                       \
+    case 42: return launch(who, KERNEL<4, 2>, 256, P, n_items, s);                       \
+    case 43: return launch(who, KERNEL<4, 3>, 256, P, n_items, s);                       \
+    case 44: return launch(who, KERNEL<4, 4>, 256, P, n_items, s);                       \
     default: return fs::fail(FS_EINVAL, "%s: no kernel for waves_per_group %d, prefetch_pages %d", who, waves, nbuf - 1); \
   }
 
   if (kv_dtype == FS_KV_BF16) {
     FS_PICK(decode_bf16_kernel)
   }
-  if (G == 1) {
-#define FS_COMMA_ONE , 1
-    FS_PICK(decode_fp8_kernel, FS_COMMA_ONE)
-#undef FS_COMMA_ONE
-  }
+  FS_PICK(decode_fp8_kernel)
 #undef FS_PICK
-  if (G <= 4) return launch(who, decode_fp8_kernel<2, 2, 4>, 128, P, n_items, s);
-  return launch(who, decode_fp8_kernel<1, 2, 8>, 64, P, n_items, s);
 }
 
 // The persistent form: two resident workgroups per CU claim items from claim_dev.

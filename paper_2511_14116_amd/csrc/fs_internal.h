@@ -13,7 +13,6 @@ fs_status fail(fs_status st, const char* fmt, ...) __attribute__((format(printf,
 constexpr int kHeadDim = 128;
 constexpr int kPageTokens = 16;
 constexpr int kMaxGroup = 16;       // q-heads per KV head that fit one MFMA tile column set
-constexpr int kMaxGroupFp8 = 8;
 constexpr int kPersistentMinItems = 1024;   // list length from which the fused decode call takes the persistent sweep
 
 struct Options {

@@ -396,7 +396,8 @@ extern "C" fs_status fs_build_launch_records(const fs_shape* shape, const fs_wor
 
 extern "C" int32_t fs_kv_elem_offset(int32_t kv_dtype, int32_t is_v, int32_t tok, int32_t d) {
   if (tok < 0 || tok >= fs::kPageTokens || d < 0 || d >= fs::kHeadDim) return -1;
-  if (kv_dtype == FS_KV_FP8_E4M3) return tok * fs::kHeadDim + d;
+  if (kv_dtype == FS_KV_FP8_E4M3)   // K and V: [d/64][(d%64)/16][tok][d%16]: one 16-byte piece per (token, 16 d), 64 pieces to a 1 KiB run
+    return (d / 64) * 1024 + ((d % 64) / 16) * 256 + tok * 16 + (d % 16);
   if (kv_dtype != FS_KV_BF16) return -1;
   if (!is_v)   // K: [d/32][(d%32)/8][tok][d%8]: one 16-byte piece per (token, 8 d) in MFMA A-operand order
     return (d / 32) * 512 + ((d % 32) / 8) * 128 + tok * 8 + (d % 8);

@@ -1,4 +1,4 @@
-// fs_pack_kv_slots: KVCache slots from token-major order into the in-slot element order the bf16
+// fs_pack_kv_slots: KVCache slots from token-major order into the in-slot element order the
 // attention kernels read (fs_kv_elem_offset is the definition), on the device.
 //
 // The paper says nothing about the order of the elements inside a KVCache block; the kernels here
@@ -47,11 +47,14 @@ pack_bf16_slots_kernel(const char* __restrict__ src, int64_t src_stride, char* _
   reinterpret_cast<u32x4*>(dst + slot * dst_stride)[threadIdx.x] = v;
 }
 
-// fp8 slots are token-major in both orders: a strided copy (2 KiB per slot, 128 threads x 16 bytes).
+// fp8, K and V alike, [d/64][(d%64)/16][tok][d%16]: 16-byte piece i of the new order is piece (tok, d/16) of the
+// token-major one (2 KiB per slot, 128 threads x 16 bytes).
 __global__ void __launch_bounds__(128)
-copy_fp8_slots_kernel(const char* __restrict__ src, int64_t src_stride, char* __restrict__ dst, int64_t dst_stride) {
+pack_fp8_slots_kernel(const char* __restrict__ src, int64_t src_stride, char* __restrict__ dst, int64_t dst_stride) {
   const int64_t slot = blockIdx.x;
-  reinterpret_cast<u32x4*>(dst + slot * dst_stride)[threadIdx.x] = reinterpret_cast<const u32x4*>(src + slot * src_stride)[threadIdx.x];
+  const int i = threadIdx.x;
+  const int from = (i & 15) * 8 + (i >> 6) * 4 + ((i & 63) >> 4);
+  reinterpret_cast<u32x4*>(dst + slot * dst_stride)[i] = reinterpret_cast<const u32x4*>(src + slot * src_stride)[from];
 }
 
 }  // namespace
@@ -80,7 +83,7 @@ extern "C" fs_status fs_pack_kv_slots(const void* src_dev, int64_t src_slot_stri
     hipLaunchKernelGGL(pack_bf16_slots_kernel, dim3(static_cast<unsigned>(n_slots)), dim3(256), 0, s, s0,
                        src_slot_stride, static_cast<char*>(dst_dev), dst_slot_stride, is_v ? 1 : 0);
   else
-    hipLaunchKernelGGL(copy_fp8_slots_kernel, dim3(static_cast<unsigned>(n_slots)), dim3(128), 0, s, s0, src_slot_stride,
+    hipLaunchKernelGGL(pack_fp8_slots_kernel, dim3(static_cast<unsigned>(n_slots)), dim3(128), 0, s, s0, src_slot_stride,
                        static_cast<char*>(dst_dev), dst_slot_stride);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fs::fail(FS_EHIP, "fs_pack_kv_slots: launch failed: %s", hipGetErrorString(e));

@@ -51,12 +51,16 @@ def shape_of(w):
     return fs.FsShape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], w["head_dim"], w["page_tokens"], w["n_ranks"])
 
 
-def run_rank(w, q, rank, chunk, owner, interleave=True, use_sched=True, pairs_subset=None, scales_by_page=True):
-    """Build rank's list with the library, run the kernels, return everything needed to compare."""
+def run_rank(w, q, rank, chunk, owner, interleave=True, use_sched=True, pairs_subset=None, scales_by_page=True,
+             kv_edit=None):
+    """Build rank's list with the library, run the kernels, return everything needed to compare.  ``kv_edit(kv)``
+    may rewrite the cache (in place) before it goes to the device; the oracle reads the same arrays."""
     sh = shape_of(w)
     items, pairs, sched, indptr = fs.fs_build_worklist(sh, w["ctx_len"], owner, rank, chunk)
     kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1) if len(pairs) else np.zeros((0, 2)),
                       w["ctx_len"], kv_dtype=w["kv_dtype"])
+    if kv_edit is not None:
+        kv_edit(kv)
     ds = DeviceShare(sh, q, kv, w["sm_scale"], interleave_kv=interleave, scales_by_page=scales_by_page)
     ds.set_worklist(items, pairs, sched, indptr)
     ds.run(use_sched=use_sched)
@@ -296,9 +300,9 @@ def test_empty_rank_is_a_no_op():
 
 
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("G,Hkv", [(1, 8), (4, 2)])
+@pytest.mark.parametrize("G,Hkv", [(1, 8), (2, 4), (3, 2), (4, 2), (6, 2), (8, 1), (12, 1), (16, 1)])
 def test_fp8_small(G, Hkv):
-    rng = np.random.default_rng(G)
+    """fp8 K/V, every group size class up to 16, ragged lengths, split and not."""
     B = 10
     w = make_requests(4, n_req=B)
     w.update(n_q_heads=G * Hkv, n_kv_heads=Hkv, group=G, n_ranks=3,
@@ -308,21 +312,60 @@ def test_fp8_small(G, Hkv):
     owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
     for k in range(3):
         for chunk in (0, 512):
-            say(f"fp8 G={G} rank {k} chunk {chunk}")
+            what = f"fp8 G={G} rank {k} chunk {chunk}"
+            say(what)
             ds, kv, items, pairs, sched, indptr = run_rank(w, q, k, chunk, owner)
             ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), G * Hkv, G, w["sm_scale"])
-            check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"fp8 G={G} rank {k} chunk {chunk}")
+            check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, what)
             # the scales gathered by slot instead of read in page-table order: the same numbers, the same bits
             ds2, *_ = run_rank(w, q, k, chunk, owner, scales_by_page=False)
             assert ds.page_scales is not None and ds2.page_scales is None
             assert torch.equal(ds.out, ds2.out) and torch.equal(ds.lse, ds2.lse)
+            check_records(ds, kv, items, sched, indptr, what)
 
 
-@pytest.mark.parametrize("cfg_id", [1, 4])
+def test_fp8_every_byte_pattern():
+    """A cache that holds every e4m3 bit pattern but the two NaNs - subnormals, both zeros, the largest values - in K
+    and in V, under every lane and byte position of the kernel's loads (K is converted to bf16 by an instruction that
+    takes a scale, V's bytes pass through an fp8 product on their way into the second one: both must be exact)."""
+    G, Hkv, B = 4, 2, 6
+    w = make_requests(4, n_req=B)
+    w.update(n_q_heads=G * Hkv, n_kv_heads=Hkv, group=G, n_ranks=1,
+             ctx_len=np.array([16, 33, 254, 508, 509, 1024], dtype=np.int32))
+    q = make_q(w["seed"], B, G * Hkv, 128)
+    owner, _, _ = fs.fs_build_placement(shape_of(w), w["ctx_len"], w["mode"])
+    patterns = np.array([b for b in range(256) if b & 0x7F != 0x7F], dtype=np.uint8)      # 254 of them
+
+    def every_pattern(kv):
+        rng = np.random.default_rng(5)
+        for pool, scale, s in ((kv["k_pool"], kv["k_scale"], 1.0 / 2048), (kv["v_pool"], kv["v_scale"], 1.0 / 64)):
+            live = pool != np.uint8(0x7F)                      # the unread tails keep their NaN bytes
+            n_slots, T, D = pool.shape
+            # element (slot, t, d) takes pattern (7 slot + 3 t + d) mod 254, so a token row runs through 128 patterns
+            # in a row and every pattern meets every byte position; one slot in four is shuffled instead
+            idx = (7 * np.arange(n_slots)[:, None, None] + 3 * np.arange(T)[None, :, None] + np.arange(D)[None, None, :]) % 254
+            vals = patterns[idx]
+            for sl in range(0, n_slots, 4):
+                vals[sl] = patterns[rng.integers(0, 254, size=(T, D))]
+            pool[live] = vals[live]
+            scale[~np.isnan(scale)] = np.float32(s)
+    for chunk in (0, 256):
+        what = f"fp8 every byte pattern, chunk {chunk}"
+        say(what)
+        ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, chunk, owner, kv_edit=every_pattern)
+        assert set(np.unique(kv["v_pool"])) >= set(patterns.tolist()) and set(np.unique(kv["k_pool"])) >= set(patterns.tolist())
+        ref_o, ref_l = oracle.decode_attention_pairs(q, kv, pairs_rows(pairs), G * Hkv, G, w["sm_scale"])
+        check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, what)
+
+
+@pytest.mark.parametrize("cfg_id", [1, 4, "4 with groups of 4"])
 def test_repeated_launches_agree_bit_for_bit(cfg_id):
     """The kernels have no atomics on data and a fixed order of sums: launches on the same inputs must leave
     the same bits (partials and merged rows), whichever form of the sweep runs.  A difference means a race."""
-    w = make_requests(cfg_id, n_req=96)
+    grouped = cfg_id == "4 with groups of 4"           # fp8 K/V under a group of q-heads
+    w = make_requests(4 if grouped else cfg_id, n_req=96)
+    if grouped:
+        w.update(n_q_heads=32, n_kv_heads=8, group=4)
     q = make_q(w["seed"], 96, w["n_q_heads"], 128)
     owner, _, _ = fs.fs_build_placement(shape_of(w), w["ctx_len"], w["mode"])
     ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 512, owner)

@@ -40,7 +40,7 @@ def test_library_exports_every_declared_symbol():
     lib = C.CDLL(fs.library_path())
     for name in declared:
         assert hasattr(lib, name), name
-    assert fs.fs_abi_version() == 2
+    assert fs.fs_abi_version() == 3
 
 
 def test_struct_sizes_match_the_header():
@@ -320,7 +320,13 @@ def test_slot_orders_are_permutations_with_the_documented_formulas():
     assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 1, 0, 16) == 4
     assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 1, 0, 1) == 8
     assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 1, 0, 32) == 512
-    assert np.array_equal(fs.slot_permutation(fs.FS_KV_FP8_E4M3, True), np.arange(2048))
+    # fp8, K and V alike: 16-byte pieces (16 consecutive d of one token); lanes (d/16 % 4, tok) of a 64-lane load are
+    # contiguous, the two halves of d a kilobyte apart
+    for is_v in (0, 1):
+        assert sorted(fs.slot_permutation(fs.FS_KV_FP8_E4M3, bool(is_v)).tolist()) == list(range(2048))
+        assert [fs.fs_kv_elem_offset(fs.FS_KV_FP8_E4M3, is_v, 0, d) for d in (0, 1, 15, 16, 63, 64, 127)] == [0, 1, 15, 256, 783, 1024, 1807]
+        assert [fs.fs_kv_elem_offset(fs.FS_KV_FP8_E4M3, is_v, t, 0) for t in (1, 2, 15)] == [16, 32, 240]
+        assert fs.fs_kv_elem_offset(fs.FS_KV_FP8_E4M3, is_v, 15, 127) == 2047
     assert fs.fs_kv_elem_offset(fs.FS_KV_BF16, 0, 16, 0) == -1 and fs.fs_kv_elem_offset(7, 0, 0, 0) == -1
     x = np.arange(2 * 2048, dtype=np.uint16).reshape(2, 16, 128)
     y = fs.pack_slots(x, fs.FS_KV_BF16, False)
