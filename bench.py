@@ -37,7 +37,8 @@ MEASURED_TRAFFIC_BYTES = {
     (1, 0, 20251115, 2048, "requests", "decode_bf16_kernel"): 407998268,                      # profiles/decode_bf16_kernel_cfg1_8b_hybrid_rank0.txt
     (3, 0, 20251117, 688, "requests", "decode_bf16_kernel"): 69331506,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
     (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3261385,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
-    (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561952676,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
+    (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561926562,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
+    (2, 0, 20251116, 2048, "requests", "decode_fp8_kernel"): 1007783948,                      # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_rank0.txt (--kv-dtype fp8)
 }
 KERNEL_LAUNCHES = 30       # launches of the attention kernel timed one by one for the roofline figure
 
