@@ -65,12 +65,12 @@ def main() -> int:
                     help="where the kernels read the step's work list: host = in place from the pinned host memory the "
                          "builder writes (no upload; default); device = a copy uploaded every step")
     ap.add_argument("--classic", action="store_true",
-                    help="bf16: one workgroup per item (fs_decode_attention) even for long lists")
+                    help="one workgroup per item (fs_decode_attention) even for long lists")
     ap.add_argument("--persistent", action="store_true",
-                    help="bf16: the persistent form of the sweep (fs_decode_attention_persistent: workgroups claim items, "
+                    help="the persistent form of the sweep (fs_decode_attention_persistent: workgroups claim items, "
                          "partial rows leave in bursts) even for short lists; by default it is used from 1024 items on")
     ap.add_argument("--units", type=int, default=None, metavar="N",
-                    help="bf16: cut the share into N equal runs of pages (0 = two per compute unit) and sweep them with one "
+                    help="cut the share into N equal runs of pages (0 = two per compute unit) and sweep them with one "
                          "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units).  Default: that form, "
                          "two runs per compute unit, once a run would hold 256 pages or more; else the chunked list")
     ap.add_argument("--chunked", action="store_true", help="the chunked list (fs_build_worklist) whatever the share's size")
@@ -155,9 +155,6 @@ def main() -> int:
         return w["chunk_tokens"]
 
     chunk = chunk_for(args.rank)
-    if args.units is not None and w["kv_dtype"] != "bf16":
-        print("bench.py: --units is built for bf16 K/V", file=sys.stderr)
-        return 2
     # Below this a run is too short for the equal-run form to pay: the chunked list with one workgroup per record, which
     # merges split pairs inside the sweep, measures faster (config 1, 89 pages to a run: 72.8 against 77.2 us per step;
     # config 2, 466 pages to a run: 311 against 318)
@@ -172,6 +169,7 @@ def main() -> int:
             return args.units
         return max(1, min(2 * n_cu, pages_of(rank) // 16))
 
+    # (fp8 K/V: the resident forms run and measure no faster than one workgroup per item, which stays the default there)
     units = args.units is not None or (w["kv_dtype"] == "bf16" and not args.chunked and not args.classic and not args.persistent
                                        and args.chunk is None and pages_of(args.rank) >= UNIT_MIN_PAGES * 2 * n_cu)
 
@@ -269,7 +267,7 @@ def main() -> int:
 
     # The persistent form pays off once every workgroup walks several items (it saves the scattered stores
     # and the relaunches); with one item or fewer per workgroup slot it is the same work plus a counter.
-    persistent = w["kv_dtype"] == "bf16" and not args.classic and not units and (args.persistent or n_items >= 1024)
+    persistent = not args.classic and not units and (args.persistent or (w["kv_dtype"] == "bf16" and n_items >= 1024))
     if args.persistent and n_items < 1024 and not args.two_calls:
         print("bench.py: --persistent below 1024 items needs --two-calls (the fused call picks the sweep by list length)",
               file=sys.stderr)
@@ -594,8 +592,7 @@ def main() -> int:
 
     dec_avg_ms = float(dec_batch_ms)
     achieved = decode_bytes / (dec_avg_ms * 1e-3) / 1e9
-    kernel_name = "decode_fp8_kernel" if w["kv_dtype"] == "fp8" else ("decode_bf16_persistent_kernel" if persistent or units
-                                                                        else "decode_bf16_kernel")
+    kernel_name = ("decode_bf16" if w["kv_dtype"] == "bf16" else "decode_fp8") + ("_persistent_kernel" if persistent or units else "_kernel")
     default_shape = (args.waves in (None, 4) and args.prefetch in (None, 2) and not args.separate_kv
                      and not args.scales_by_slot and not (args.config == 3 and args.force_tail))
     key = (args.config, args.rank, w["seed"], f"{n_units} units" if units else chunk, args.placement, kernel_name) if default_shape else None

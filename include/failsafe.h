@@ -435,8 +435,8 @@ FS_API fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv
                               int64_t n_items, float* part_o, float* part_lse, void* stream);
 
 /* ---------------------------------------------------------------------------
- * fs_decode_attention_persistent - the same computation as fs_decode_attention for
- * bf16 K/V, by a fixed set of workgroups (two per CU) that claim items from a counter
+ * fs_decode_attention_persistent - the same computation as fs_decode_attention,
+ * by a fixed set of workgroups (two per CU) that claim items from a counter
  * in list order and write their partial rows in bursts (decode phase, Section 2.1.1;
  * the ragged list of Section 3.1).  An item's pages are split over four wavefronts as
  * in fs_decode_attention's default launch shape ("waves_per_group" = 4), so the two
@@ -449,7 +449,7 @@ FS_API fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view* kv
  *             one another on a stream (or replays of a captured graph) share one pair
  *             without clearing it.  Two launches that overlap in time need two pairs.
  *
- * Everything else as for fs_decode_attention.  FS_EUNSUPPORTED: fp8 K/V.
+ * Everything else as for fs_decode_attention (bf16 or fp8 K/V).
  */
 FS_API fs_status fs_decode_attention_persistent(const fs_shape* shape, const fs_kv_view* kv,
                                                 const fs_work_item* items_dev, const int32_t* sched_dev,
@@ -484,7 +484,7 @@ FS_API fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_kv_vi
 
 /* ---------------------------------------------------------------------------
  * fs_decode_attention_units - decode attention (Section 2.1.1) and split-K merge of a list that
- * fs_build_worklist_units has cut into equal runs, bf16 K/V: one resident workgroup per unit
+ * fs_build_worklist_units has cut into equal runs: one resident workgroup per unit
  * walks its unit's items in order (no counter, nothing handed out at run time: every workgroup
  * streams the same number of pages), a pair that is one item gets its final rows from the sweep,
  * the others are merged as by fs_merge_lse.  out/lse hold, to rounding (another order of sums
@@ -499,7 +499,7 @@ FS_API fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_kv_vi
  *  part_o, part_lse  DEVICE scratch [n_items*G][head_dim], [n_items*G]; may be NULL when n_items == n_pairs
  *  out, lse          DEVICE out  [n_pairs*G][head_dim], [n_pairs*G] fp32
  *
- * n_items == 0 is a no-op.  Errors as for fs_decode_attention_fused; FS_EUNSUPPORTED for fp8 K/V.
+ * n_items == 0 is a no-op.  Errors as for fs_decode_attention_fused (bf16 or fp8 K/V).
  * List contents are trusted (device memory): no unit may be empty.
  */
 FS_API fs_status fs_decode_attention_units(const fs_shape* shape, const fs_kv_view* kv,
@@ -551,7 +551,7 @@ FS_API fs_status fs_build_launch_records(const fs_shape* shape, const fs_work_it
 /* fs_decode_attention_records - decode attention (Section 2.1.1) and split-K merge in one call,
  * from launch records built with direct_rows != 0.  unit_indptr_dev == NULL: one workgroup per
  * record, in the order of the array (bf16 or fp8 K/V).  unit_indptr_dev given: records of a list
- * from fs_build_worklist_units in item order, one resident workgroup per unit (bf16 K/V), as
+ * from fs_build_worklist_units in item order, one resident workgroup per unit, as
  * fs_decode_attention_units.  Rows of unsplit pairs come final from the sweep; the merge runs for
  * split pairs and is not launched when n_items == n_pairs.  out/lse hold what the calls that take
  * items leave for the same list, bit for bit.

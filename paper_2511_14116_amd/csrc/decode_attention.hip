@@ -24,9 +24,10 @@
 //
 // Forms of the sweep, all with the same arithmetic per item (their rows agree bit for bit): one workgroup
 // per item; resident workgroups that claim items from a counter; resident workgroups on equal runs of pages
-// (no counter).  Items come as list entries that the kernel looks up, or as launch records that the host has
-// resolved (one 64-byte read).  A pair that is one item writes its final rows; the chunks of a split pair
-// are merged by fs_merge_lse, or, given a counter per pair, by the workgroup that writes the pair's last rows.
+// (no counter).  Each is written once over the K/V format (Bf16Format, Fp8Format).  Items come as list
+// entries that the kernel looks up, or as launch records that the host has resolved (one 64-byte read).  A
+// pair that is one item writes its final rows; the chunks of a split pair are merged by fs_merge_lse, or,
+// given a counter per pair, by the workgroup that writes the pair's last rows.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -186,495 +187,6 @@ __device__ __forceinline__ void consume_page(SoftmaxState& st, PageRegs& pg, con
   }
 }
 
-// The page table is read-only for the whole launch, but the kernels also write to global memory, so the
-// compiler does not take its word for that and would fetch the page ids with vector loads, which queue up
-// behind the page loads.  Reading them through the constant address space keeps them on the scalar path.
-typedef const int32_t __attribute__((address_space(4))) * const_ids_ptr;
-
-// What a wavefront needs to know of an item.  The item's pages are dealt to the workgroup's wavefronts in
-// turn: wavefront w of W takes pages w, w + W, w + 2W, ... of the item, `n_mine` of them.
-struct ItemDesc {
-  const_ids_ptr ids;    // page ids of the item's first page onwards
-  int32_t page_lo, page_hi;   // position of the item's first page in the whole page table (fp8 scales in page order)
-  int n_tok;            // tokens of the item
-  int n_mine;           // pages of the item this wavefront takes
-  int row;              // first partial row of the item, or -(first final row) - 1 when the item is all of its pair (one-call forms)
-  int q_row;            // first query row of the item's group
-  int pair, n_chunks, pair_row;   // the item's pair, its chunk count and the first partial row of its first chunk (n_chunks = 1 when unknown)
-  int32_t first_ids[3]; // slots of this wavefront's first pages (those the prologue fetches), asked for with the rest
-  bf16x8 q[4];          // Q^T operand of this lane (load_desc_q; bf16 kernels)
-  bool valid;
-};
-
-// The scalar part of the descriptor of the item at launch position k: everything but the query rows.  All of
-// it stays in scalar registers.  With launch records that is one 64-byte read (and the first slots come out of
-// the same record, asked for at the same time); without, the list entry, the item, the page-table offset and
-// chunk count, and the page ids are read one after the other.
-template <int WAVES, int NBUF>
-__device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k, int n_items, int wave, int G) {
-  static_assert(NBUF - 1 <= 3, "first_ids holds three slots");
-  ItemDesc d;
-  d.valid = k < n_items;
-  d.ids = (const_ids_ptr)(uintptr_t)0;
-  d.page_lo = d.page_hi = 0;
-  d.n_tok = 0;
-  d.n_mine = 0;
-  d.row = 0;
-  d.q_row = 0;
-  d.pair = 0;
-  d.n_chunks = 1;
-  d.pair_row = 0;
-#pragma unroll
-  for (int u = 0; u < 3; ++u) d.first_ids[u] = 0;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) d.q[c] = bf16x8{};
-  if (d.valid) {
-    int64_t first_page;
-    int32_t rec_slot[3] = {0, 0, 0};
-    if (P.records) {
-      // k is the same in every lane (it may come from LDS, which the compiler cannot see): saying so keeps
-      // the descriptor and, above all, the page ids on the scalar path
-      const fs_launch_record* rec = P.records + __builtin_amdgcn_readfirstlane(k);
-      first_page = rec->first_page;
-      d.n_tok = __builtin_amdgcn_readfirstlane(rec->n_tok);
-      d.q_row = __builtin_amdgcn_readfirstlane(rec->q_row);
-      d.row = __builtin_amdgcn_readfirstlane(rec->row);
-      d.pair = __builtin_amdgcn_readfirstlane(rec->pair);
-      d.n_chunks = __builtin_amdgcn_readfirstlane(rec->n_chunks);
-      d.pair_row = __builtin_amdgcn_readfirstlane(rec->pair_row);
-#pragma unroll
-      for (int u = 0; u < NBUF - 1; ++u)           // the record holds the item's first eight slots
-        if (wave + u * WAVES < 8) rec_slot[u] = __builtin_amdgcn_readfirstlane(rec->first_slots[wave + u * WAVES]);
-    } else {
-      const int item_idx = __builtin_amdgcn_readfirstlane(P.sched ? P.sched[k] : k);
-      fs_work_item it = P.items[item_idx];
-      it.pair = __builtin_amdgcn_readfirstlane(it.pair);
-      it.tok_begin = __builtin_amdgcn_readfirstlane(it.tok_begin);
-      it.tok_end = __builtin_amdgcn_readfirstlane(it.tok_end);
-      d.n_tok = it.tok_end - it.tok_begin;
-      d.q_row = __builtin_amdgcn_readfirstlane(it.q_row);
-      d.row = __builtin_amdgcn_readfirstlane(it.part_row);
-      first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
-      d.pair = it.pair;
-      if (P.chunk_indptr) {
-        const int64_t c0 = P.chunk_indptr[it.pair];
-        d.n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - c0));
-        d.pair_row = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(c0) * G);
-        if (d.n_chunks == 1) d.row = -(it.pair * G) - 1;
-      }
-    }
-    d.page_lo = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page));
-    d.page_hi = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page >> 32));
-    d.ids = (const_ids_ptr)(reinterpret_cast<uintptr_t>(P.page_ids + ((static_cast<int64_t>(d.page_hi) << 32) | static_cast<uint32_t>(d.page_lo))));
-    const int n_pages = (d.n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
-    d.n_mine = n_pages > wave ? (n_pages - wave + WAVES - 1) / WAVES : 0;
-#pragma unroll
-    for (int u = 0; u < NBUF - 1; ++u) {
-      if (u < d.n_mine) d.first_ids[u] = (P.records && wave + u * WAVES < 8) ? rec_slot[u] : d.ids[wave + u * WAVES];
-    }
-  }
-  return d;
-}
-
-// The query rows of the item, as the Q^T operand of this lane: lane (q = lane%16, kb = lane/16) holds
-// Q[q][32c + 8kb .. +8) for c = 0..3; rows beyond the group are zero (read from a row that exists, then blanked).
-__device__ __forceinline__ void load_desc_q(ItemDesc& d, const DecodeParams& P, int lane, int G) {
-  if (d.valid) {
-    const int qi = lane & 15, kb = lane >> 4;
-    const int qrow = d.q_row + min(qi, G - 1);
-    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      u32x4 v = qp[4 * c];
-      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
-      d.q[c] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
-}
-
-// Where an item's G rows go, from the descriptor's row.
-struct RowDest {
-  float* o;
-  float* lse;
-  int row;
-};
-__device__ __forceinline__ RowDest row_dest(const DecodeParams& P, int row) {
-  if (row < 0) return RowDest{P.out, P.lse, -row - 1};
-  return RowDest{P.part_o, P.part_lse, row};
-}
-
-// A partial row on its way to the workgroup that will merge its pair inside the same launch: relaxed atomic stores
-// at device scope, which are written through to memory instead of waiting in this XCD's L2 (the other workgroup
-// may run on another XCD, whose L2 is not this one's).
-__device__ __forceinline__ void store_f32_coherent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_f32x4_coherent(float* p, const f32x4 v) {
-  auto* q = reinterpret_cast<unsigned long long*>(p);
-  const unsigned long long lo = (static_cast<unsigned long long>(__float_as_uint(v[1])) << 32) | __float_as_uint(v[0]);
-  const unsigned long long hi = (static_cast<unsigned long long>(__float_as_uint(v[3])) << 32) | __float_as_uint(v[2]);
-  __hip_atomic_store(q, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(q + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Split pairs merged inside the sweep.  The workgroup has just issued the stores of the partial rows of `n` items
-// (s_pair/s_chunks/s_prow[j]: pair, chunk count and first partial row of the pair of item j; s_chunks[j] = 1: not
-// split, nothing to do).  One thread per item counts the workgroup in on the pair's counter; the workgroup that
-// brings a counter to the pair's chunk count is the last writer of that pair: it puts the counter back to zero for
-// the next launch and merges the pair's chunks into its final rows, one wavefront per q-head, with the routine of
-// the merge kernel (same bits).  Nobody waits for anybody.
-// What makes the other workgroups' rows visible, without fences (a device-scope fence writes back and invalidates
-// the whole L2 of the XCD, which on the 70B-shaped batch cost the sweep 150 us): partial rows are stored
-// (store_f32*_coherent) and read (merge_rows<.., COHERENT>) as relaxed device-scope atomics, which go to memory
-// past the caches, as the counter's atomic does; a thread counts in only after all the workgroup's stores have been
-// acknowledged (vmcnt(0) in every thread, then the barrier), and the merging workgroup reads only after its atomic
-// has returned the full count, i.e. after every other writer's atomic, each issued after its own stores were done.
-// Takes the workgroup's barriers: every thread must call it.
-template <int WAVES>
-__device__ __forceinline__ void arrive_and_merge(const DecodeParams& P, int n, const int* s_pair, const int* s_chunks,
-                                                 const int* s_prow, int* s_done, int G, int wave, int lane) {
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this thread's stores have reached memory
-  __syncthreads();
-  for (int j = threadIdx.x; j < n; j += WAVES * 64) {
-    const int c = s_chunks[j];
-    s_done[j] = c > 1 && __hip_atomic_fetch_add(P.pair_counters + s_pair[j], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == c - 1;
-  }
-  __syncthreads();
-  for (int j = 0; j < n; ++j) {
-    if (!__builtin_amdgcn_readfirstlane(s_done[j])) continue;
-    const int pair = __builtin_amdgcn_readfirstlane(s_pair[j]);
-    const int chunks = __builtin_amdgcn_readfirstlane(s_chunks[j]);
-    const int prow = __builtin_amdgcn_readfirstlane(s_prow[j]);
-    if (threadIdx.x == 0) __hip_atomic_store(P.pair_counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const float* po = P.part_o;
-    const float* pl = P.part_lse;
-    // a wavefront takes as many q-heads side by side as divide the group evenly over the workgroup (their loads travel
-    // together: one trip to memory instead of one per q-head); the sums of a row are the same in every form
-    const int64_t c0 = prow / G;
-    float* const out0 = P.out + static_cast<int64_t>(pair) * G * fs::kHeadDim;
-    float* const lse0 = P.lse + static_cast<int64_t>(pair) * G;
-    if (G % (2 * WAVES) == 0) {
-      for (int g = 2 * wave; g < G; g += 2 * WAVES)
-        fs_merge::merge_rows<2, true>(po, pl, c0, chunks, G, g, out0 + g * fs::kHeadDim, lse0 + g, lane);
-    } else {
-      for (int g = wave; g < G; g += WAVES)
-        fs_merge::merge_rows<1, true>(po, pl, c0, chunks, G, g, out0 + g * fs::kHeadDim, lse0 + g, lane);
-    }
-  }
-}
-
-// The same for the one item of a workgroup that has no more than that.
-template <int WAVES>
-__device__ __forceinline__ void arrive_and_merge_one(const DecodeParams& P, const ItemDesc& d, int* s_meta, int G, int wave,
-                                                     int lane) {
-  if (P.pair_counters == nullptr || d.n_chunks <= 1) return;     // the same for the whole workgroup
-  if (threadIdx.x == 0) {
-    s_meta[0] = d.pair;
-    s_meta[1] = d.n_chunks;
-    s_meta[2] = d.pair_row;
-  }
-  arrive_and_merge<WAVES>(P, 1, s_meta, s_meta + 1, s_meta + 2, s_meta + 3, G, wave, lane);
-}
-
-// Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.  A lane's acc[j] holds four
-// consecutive d of its q-head, from d = 16j + 4*(lane/16) on in the bf16 kernels; FP8_ORDER: from
-// fp8_first_d(j, lane/16) on (decode_fp8_kernel below).
-__device__ __forceinline__ int fp8_first_d(int j, int kb) {
-  return 64 * (j >> 2) + 32 * (j & 1) + 16 * (kb >> 1) + 8 * ((j >> 1) & 1) + 4 * (kb & 1);
-}
-template <int WAVES, bool FP8_ORDER = false>
-__device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_total, int wave, int lane,
-                                                int G, float* __restrict__ part_o,
-                                                float* __restrict__ part_lse, int part_row,
-                                                float* sm_o, float* sm_m, float* sm_l, bool coherent) {
-  const int qi = lane & 15, kb = lane >> 4;
-  if (lane < 16) {
-    sm_m[wave * 16 + lane] = st.m;
-    sm_l[wave * 16 + lane] = l_total;
-  }
-  float* row = sm_o + (wave * 16 + qi) * kORow;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + (FP8_ORDER ? fp8_first_d(j, kb) : 16 * j + 4 * kb)) = st.acc[j];
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
-    const int q = idx >> 5, d4 = idx & 31;
-    float M = sm_m[q];
-#pragma unroll
-    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sm_m[w * 16 + q]);
-    float L = 0.f;
-    f32x4 o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w) {
-      const float wgt = __builtin_amdgcn_exp2f(sm_m[w * 16 + q] - M);   // a wave with no pages has m = -inf
-      L += wgt * sm_l[w * 16 + q];
-      o += wgt * *reinterpret_cast<const f32x4*>(sm_o + (w * 16 + q) * kORow + 4 * d4);
-    }
-    const float inv = 1.0f / L;
-    // Streaming stores: the partial rows are read once, by the merge.  Measured on the 70B-shaped
-    // batch, plain stores of these 9 MB cost the 2 GB read stream about 20 us, non-temporal ones 13.
-    float* dst = part_o + static_cast<int64_t>(part_row + q) * fs::kHeadDim + 4 * d4;
-    const float lse_q = (M + __builtin_amdgcn_logf(L)) * kLn2;
-    if (coherent) {      // rows another workgroup of this launch will merge (arrive_and_merge)
-      store_f32x4_coherent(dst, o * inv);
-      if (d4 == 0) store_f32_coherent(part_lse + part_row + q, lse_q);
-    } else {
-      __builtin_nontemporal_store(o * inv, reinterpret_cast<f32x4*>(dst));
-      if (d4 == 0) __builtin_nontemporal_store(lse_q, part_lse + part_row + q);
-    }
-  }
-}
-
-template <int WAVES, int NBUF>
-__global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodeParams P) {
-  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
-  __shared__ float sm_m[WAVES * 16];
-  __shared__ float sm_l[WAVES * 16];
-  __shared__ int s_meta[4];
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kb = lane >> 4;
-  const int G = P.group;
-  ItemDesc d = load_desc_head<WAVES, NBUF>(P, static_cast<int>(blockIdx.x), 0x7FFFFFFF, wave, G);
-  load_desc_q(d, P, lane, G);
-
-  SoftmaxState st;
-  st.m = -INFINITY;
-  st.l = 0.f;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // NBUF register buffers; NBUF-1 pages are in flight while one is consumed.  The steady-state
-  // loop is branch-free (every prefetch is in range, every page is full), so the loads of
-  // pages i+1.. stay outstanding while page i is consumed; the ragged end is a second loop.
-  // Index i counts this wavefront's pages; its i-th page is page wave + i*WAVES of the item.
-  PageRegs buf[NBUF];
-#pragma unroll
-  for (int u = 0; u < NBUF - 1; ++u)
-    if (u < d.n_mine) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.first_ids[u], lane);
-
-  int i = 0;
-  for (; i + 2 * NBUF - 2 < d.n_mine; i += NBUF) {
-#pragma unroll
-    for (int u = 0; u < NBUF; ++u) {
-      load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.ids[wave + (i + u + NBUF - 1) * WAVES], lane);
-      consume_page<true>(st, buf[u], d.q, P.scale_log2, fs::kPageTokens, kb);
-    }
-  }
-  // here pages i .. i+NBUF-2 (those below n_mine) are in flight in buf[0 .. NBUF-2]
-#pragma unroll
-  for (int u = 0; u < 2 * NBUF - 2; ++u) {
-    const int pi = i + u;
-    if (pi < d.n_mine) {
-      const int pn = pi + NBUF - 1;
-      if (pn < d.n_mine) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.ids[wave + pn * WAVES], lane);
-      consume_page<false>(st, buf[u % NBUF], d.q, P.scale_log2, min(fs::kPageTokens, d.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
-    }
-  }
-
-  const RowDest dst = row_dest(P, d.row);
-  const float l_total = sum_xor32(sum_xor16(st.l));
-  merge_and_store<WAVES>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l,
-                         P.pair_counters != nullptr && d.n_chunks > 1);
-  arrive_and_merge_one<WAVES>(P, d, s_meta, G, wave, lane);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Persistent form of the bf16 sweep.  A fixed set of workgroups (two per CU) walks the list: the
-// first gridDim.x items go one to each workgroup, every further item is claimed from a counter
-// in the list's longest-first order at the moment a workgroup has streamed its current item
-// (list scheduling, as the hardware dispatcher does for one workgroup per item).  Finished
-// partial rows wait in LDS and leave in one burst when the staging area is full or the
-// workgroup is done: writes scattered through the launch slow the read stream far more than
-// their bytes explain, writes at the end of a workgroup's life mostly do not.  The next item's
-// descriptor, query rows and first pages are fetched while the current item's rows are merged,
-// and the barriers around that merge wait for LDS traffic only, so those loads stay in flight
-// across them.  claim[0] counts the items handed out beyond the first gridDim.x, claim[1] the workgroups
-// that have left; both are zero between launches.
-// ---------------------------------------------------------------------------------------------
-
-constexpr int kStageRows = 64;    // partial rows a workgroup keeps in LDS before it writes them (64 x 512 B)
-constexpr int kSecondShare = 4;   // a CU's second workgroup claims only within the first 1/kSecondShare of the list
-
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// UNITS = true is the form without a counter: workgroup u walks the items [unit_indptr[u], unit_indptr[u+1]) of a
-// list that the host has cut into equal runs of pages (fs_build_worklist_units), so every workgroup streams
-// the same number of bytes and nothing is handed out at run time; `claim` then carries nothing.
-// (two wavefronts per SIMD - two workgroups per CU - is what the launch counts on: at most 256 registers)
-template <int WAVES, int NBUF, bool UNITS>
-__global__ void __launch_bounds__(WAVES * 64, 2) decode_bf16_persistent_kernel(const DecodeParams P, int n_items,
-                                                                            int* __restrict__ claim, int n_first,
-                                                                            const int64_t* __restrict__ unit_indptr) {
-  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
-  __shared__ float sm_m[WAVES * 16];
-  __shared__ float sm_l[WAVES * 16];
-  __shared__ __attribute__((aligned(16))) float st_o[kStageRows * fs::kHeadDim];
-  __shared__ float st_lse[kStageRows];
-  __shared__ int st_row[kStageRows];
-  __shared__ int s_next;
-  // what arrive_and_merge needs to know of the items whose rows are staged (at most kStageRows items: G >= 1)
-  __shared__ int st_pair[kStageRows], st_chunks[kStageRows], st_prow[kStageRows], st_done[kStageRows];
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qi = lane & 15, kb = lane >> 4;
-  const int G = P.group;
-  const int n_groups = gridDim.x;
-
-  int unit_end = 0, cur_k = static_cast<int>(blockIdx.x);
-  if constexpr (UNITS) {
-    cur_k = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x]));
-    unit_end = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x + 1]));   // > cur_k: no unit is empty
-  }
-  ItemDesc cur = load_desc_head<WAVES, NBUF>(P, cur_k, n_items, wave, G);   // a valid item by the launch
-  load_desc_q(cur, P, lane, G);
-
-  PageRegs buf[NBUF];
-  auto prologue = [&](const ItemDesc& d) __attribute__((always_inline)) {
-#pragma unroll
-    for (int u = 0; u < NBUF - 1; ++u)
-      if (u < d.n_mine) load_page(buf[u], P.k_pool, P.v_pool, P.k_stride, P.v_stride, d.first_ids[u], lane);
-  };
-  prologue(cur);
-
-  // Two workgroups share a CU, and the one launched second streams at about half the rate of the first (the
-  // issue arbiter prefers the older wavefront) while the CU's total stays the same.  A late item in its hands
-  // takes twice as long and ends the launch late, so the workgroups beyond the first n_first (one per CU) -
-  // by launch order the second workgroup of a CU - stop claiming once a quarter of the list is handed out;
-  // they are there to fill the CU while the list is long, and leave the rest to their siblings.  (Where launch
-  // order does not map to CUs like that, as many workgroups retire early just the same, which costs nothing
-  // measurable.)
-  const bool second_on_cu = static_cast<int>(blockIdx.x) >= n_first;
-  bool keep_claiming = true;
-  int staged = 0, staged_items = 0;
-  bool staged_split = false;       // some staged item belongs to a split pair
-  for (;;) {
-    // With equal runs the next item is known from the start: its descriptor and the slots of its first pages are
-    // asked for now and travel while the current item streams, so that at the item's end the next pages can be
-    // requested at once.  With a counter the next item is only known after the claim (below).
-    ItemDesc nxt;
-    if constexpr (UNITS) {
-      ++cur_k;
-      nxt = load_desc_head<WAVES, NBUF>(P, cur_k < unit_end ? cur_k : n_items, n_items, wave, G);
-    }
-    SoftmaxState st;
-    st.m = -INFINITY;
-    st.l = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    int i = 0;          // counts this wavefront's pages of the item: its i-th page is page wave + i*WAVES
-    for (; i + 2 * NBUF - 2 < cur.n_mine; i += NBUF) {
-#pragma unroll
-      for (int u = 0; u < NBUF; ++u) {
-        load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[wave + (i + u + NBUF - 1) * WAVES], lane);
-        consume_page<true>(st, buf[u], cur.q, P.scale_log2, fs::kPageTokens, kb);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 2 * NBUF - 2; ++u) {
-      const int pi = i + u;
-      if (pi < cur.n_mine) {
-        const int pn = pi + NBUF - 1;
-        if (pn < cur.n_mine) load_page(buf[(u + NBUF - 1) % NBUF], P.k_pool, P.v_pool, P.k_stride, P.v_stride, cur.ids[wave + pn * WAVES], lane);
-        consume_page<false>(st, buf[u % NBUF], cur.q, P.scale_log2, min(fs::kPageTokens, cur.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
-      }
-    }
-    // merge the wavefronts through LDS into the staging rows
-    const float l_total = sum_xor32(sum_xor16(st.l));
-    if (lane < 16) {
-      sm_m[wave * 16 + lane] = st.m;
-      sm_l[wave * 16 + lane] = l_total;
-    }
-    {
-      float* row = sm_o + (wave * 16 + qi) * kORow + 4 * kb;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + 16 * j) = st.acc[j];
-    }
-    // The next item is claimed only now.  Claiming it earlier would hide the counter's round trip, but a
-    // workgroup would then sit on an item another could have started: claiming at the start of the current
-    // item cost 11 us of the launch on the 70B-shaped batch, two items ahead 20 us, four pages early 4 us.
-    if constexpr (!UNITS) {
-      if (threadIdx.x == 0) s_next = keep_claiming ? atomicAdd(claim, 1) + n_groups : n_items;
-    }
-    lds_barrier();
-    // every page of the current item is consumed: fetch the next item's descriptor and first pages now,
-    // so that they travel while the rows are merged
-    if constexpr (!UNITS) {
-      const int next_k = __builtin_amdgcn_readfirstlane(s_next);
-      nxt = load_desc_head<WAVES, NBUF>(P, next_k, n_items, wave, G);
-      if (second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
-    }
-    load_desc_q(nxt, P, lane, G);
-    prologue(nxt);
-    for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
-      const int q = idx >> 5, d4 = idx & 31;
-      float M = sm_m[q];
-#pragma unroll
-      for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sm_m[w * 16 + q]);
-      float L = 0.f;
-      f32x4 o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int w = 0; w < WAVES; ++w) {
-        const float wgt = __builtin_amdgcn_exp2f(sm_m[w * 16 + q] - M);   // a wave with no pages has m = -inf
-        L += wgt * sm_l[w * 16 + q];
-        o += wgt * *reinterpret_cast<const f32x4*>(sm_o + (w * 16 + q) * kORow + 4 * d4);
-      }
-      const float inv = 1.0f / L;
-      *reinterpret_cast<f32x4*>(st_o + (staged + q) * fs::kHeadDim + 4 * d4) = o * inv;
-      if (d4 == 0) {
-        st_lse[staged + q] = (M + __builtin_amdgcn_logf(L)) * kLn2;
-        st_row[staged + q] = cur.row >= 0 ? cur.row + q : cur.row - q;
-      }
-    }
-    if (P.pair_counters != nullptr) {
-      if (threadIdx.x == 0) {
-        st_pair[staged_items] = cur.pair;
-        st_chunks[staged_items] = cur.n_chunks;
-        st_prow[staged_items] = cur.pair_row;
-      }
-      staged_split |= cur.n_chunks > 1;
-    }
-    ++staged_items;
-    staged += G;
-    lds_barrier();                     // staging rows complete; the merge buffers may be reused
-    const bool last = !nxt.valid;
-    if (last || staged + G > kStageRows) {
-      for (int idx = threadIdx.x; idx < staged * 32; idx += WAVES * 64) {
-        const int r = idx >> 5, d4 = idx & 31;
-        const int row = st_row[r];
-        float* dst = row >= 0 ? P.part_o + static_cast<int64_t>(row) * fs::kHeadDim : P.out + static_cast<int64_t>(-row - 1) * fs::kHeadDim;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(st_o + r * fs::kHeadDim + 4 * d4);
-        if (row >= 0 && P.pair_counters != nullptr) store_f32x4_coherent(dst + 4 * d4, v);     // rows for arrive_and_merge
-        else __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + 4 * d4));
-      }
-      for (int r = threadIdx.x; r < staged; r += WAVES * 64) {
-        const int row = st_row[r];
-        if (row >= 0 && P.pair_counters != nullptr) store_f32_coherent(P.part_lse + row, st_lse[r]);
-        else __builtin_nontemporal_store(st_lse[r], row >= 0 ? P.part_lse + row : P.lse + (-row - 1));
-      }
-      if (staged_split) arrive_and_merge<WAVES>(P, staged_items, st_pair, st_chunks, st_prow, st_done, G, wave, lane);
-      staged = 0;
-      staged_items = 0;
-      staged_split = false;
-      // the next write into the staging rows comes after the next item's first barrier, which every
-      // thread reaches only when it is done reading them here
-    }
-    if (last) break;
-    cur = nxt;
-  }
-  // The last workgroup to leave puts both counters back to zero for the next launch (every other
-  // workgroup has made its last claim by then).
-  if constexpr (!UNITS) {
-    if (threadIdx.x == 0 && atomicAdd(claim + 1, 1) == static_cast<int>(gridDim.x) - 1) {
-      __atomic_store_n(claim, 0, __ATOMIC_RELAXED);
-      __atomic_store_n(claim + 1, 0, __ATOMIC_RELAXED);
-    }
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
 // fp8 e4m3 path (one fp32 scale per slot for K and one for V), on the matrix cores for every group size.
 //
@@ -698,6 +210,11 @@ __global__ void __launch_bounds__(WAVES * 64, 2) decode_bf16_persistent_kernel(c
 // A kernel that multiplied on the vector units instead (each K and V value once per q-head) kept pace with the
 // page stream for one q-head per KV head and not beyond: with eight it ran at a quarter of this one's rate.
 // ---------------------------------------------------------------------------------------------
+
+// Where a lane's rows of O^T start: accumulator a = 4j + 2half + h2 of lane (q, kb) holds d = fp8_first_d(a, kb) .. + 4.
+__device__ __forceinline__ int fp8_first_d(int a, int kb) {
+  return 64 * (a >> 2) + 32 * (a & 1) + 16 * (kb >> 1) + 8 * ((a >> 1) & 1) + 4 * (kb & 1);
+}
 
 struct Fp8Page {
   u32x4 k[2];
@@ -809,24 +326,117 @@ __device__ __forceinline__ void consume_page_fp8(SoftmaxState& st, const Fp8Page
   for (int a = 0; a < 8; ++a) st.acc[a] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va[a], pc, st.acc[a], 0, 0, 0);
 }
 
-// (at least two wavefronts per SIMD: within 256 registers the compiler keeps the matrix results in ordinary
-// registers; allowed 512 it parks them in accumulation registers and moves every one back before the vector units
-// can touch it, 57 extra instructions per page)
-template <int WAVES, int NBUF>
-__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
-decode_fp8_kernel(const DecodeParams P) {
-  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
-  __shared__ float sm_m[WAVES * 16];
-  __shared__ float sm_l[WAVES * 16];
-  __shared__ int s_meta[4];
+// The page table is read-only for the whole launch, but the kernels also write to global memory, so the
+// compiler does not take its word for that and would fetch the page ids with vector loads, which queue up
+// behind the page loads.  Reading them through the constant address space keeps them on the scalar path.
+typedef const int32_t __attribute__((address_space(4))) * const_ids_ptr;
 
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qi = lane & 15, kb = lane >> 4;
-  const int G = P.group;
-  ItemDesc d = load_desc_head<WAVES, NBUF>(P, static_cast<int>(blockIdx.x), 0x7FFFFFFF, wave, G);
-  const int64_t first_page = (static_cast<int64_t>(d.page_hi) << 32) | static_cast<uint32_t>(d.page_lo);
-  {   // the query rows in the order of d that the K operand has: instruction c takes d = 32kb + 8c .. + 8
+// What a wavefront needs to know of an item.  The item's pages are dealt to the workgroup's wavefronts in
+// turn: wavefront w of W takes pages w, w + W, w + 2W, ... of the item, `n_mine` of them.
+struct ItemDesc {
+  const_ids_ptr ids;    // page ids of the item's first page onwards
+  int32_t page_lo, page_hi;   // position of the item's first page in the whole page table (fp8 scales in page order)
+  int n_tok;            // tokens of the item
+  int n_mine;           // pages of the item this wavefront takes
+  int row;              // first partial row of the item, or -(first final row) - 1 when the item is all of its pair (one-call forms)
+  int q_row;            // first query row of the item's group
+  int pair, n_chunks, pair_row;   // the item's pair, its chunk count and the first partial row of its first chunk (n_chunks = 1 when unknown)
+  int32_t first_ids[3]; // slots of this wavefront's first pages (those the prologue fetches), asked for with the rest
+  bf16x8 q[4];          // Q^T operand of this lane (load_desc_q; bf16 kernels)
+  bool valid;
+};
+
+// The scalar part of the descriptor of the item at launch position k: everything but the query rows.  All of
+// it stays in scalar registers.  With launch records that is one 64-byte read (and the first slots come out of
+// the same record, asked for at the same time); without, the list entry, the item, the page-table offset and
+// chunk count, and the page ids are read one after the other.
+template <int WAVES, int NBUF>
+__device__ __forceinline__ ItemDesc load_desc_head(const DecodeParams& P, int k, int n_items, int wave, int G) {
+  static_assert(NBUF - 1 <= 3, "first_ids holds three slots");
+  ItemDesc d;
+  d.valid = k < n_items;
+  d.ids = (const_ids_ptr)(uintptr_t)0;
+  d.page_lo = d.page_hi = 0;
+  d.n_tok = 0;
+  d.n_mine = 0;
+  d.row = 0;
+  d.q_row = 0;
+  d.pair = 0;
+  d.n_chunks = 1;
+  d.pair_row = 0;
+#pragma unroll
+  for (int u = 0; u < 3; ++u) d.first_ids[u] = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) d.q[c] = bf16x8{};
+  if (d.valid) {
+    int64_t first_page;
+    int32_t rec_slot[3] = {0, 0, 0};
+    if (P.records) {
+      // k is the same in every lane (it may come from LDS, which the compiler cannot see): saying so keeps
+      // the descriptor and, above all, the page ids on the scalar path
+      const fs_launch_record* rec = P.records + __builtin_amdgcn_readfirstlane(k);
+      first_page = rec->first_page;
+      d.n_tok = __builtin_amdgcn_readfirstlane(rec->n_tok);
+      d.q_row = __builtin_amdgcn_readfirstlane(rec->q_row);
+      d.row = __builtin_amdgcn_readfirstlane(rec->row);
+      d.pair = __builtin_amdgcn_readfirstlane(rec->pair);
+      d.n_chunks = __builtin_amdgcn_readfirstlane(rec->n_chunks);
+      d.pair_row = __builtin_amdgcn_readfirstlane(rec->pair_row);
+#pragma unroll
+      for (int u = 0; u < NBUF - 1; ++u)           // the record holds the item's first eight slots
+        if (wave + u * WAVES < 8) rec_slot[u] = __builtin_amdgcn_readfirstlane(rec->first_slots[wave + u * WAVES]);
+    } else {
+      const int item_idx = __builtin_amdgcn_readfirstlane(P.sched ? P.sched[k] : k);
+      fs_work_item it = P.items[item_idx];
+      it.pair = __builtin_amdgcn_readfirstlane(it.pair);
+      it.tok_begin = __builtin_amdgcn_readfirstlane(it.tok_begin);
+      it.tok_end = __builtin_amdgcn_readfirstlane(it.tok_end);
+      d.n_tok = it.tok_end - it.tok_begin;
+      d.q_row = __builtin_amdgcn_readfirstlane(it.q_row);
+      d.row = __builtin_amdgcn_readfirstlane(it.part_row);
+      first_page = P.page_indptr[it.pair] + it.tok_begin / fs::kPageTokens;
+      d.pair = it.pair;
+      if (P.chunk_indptr) {
+        const int64_t c0 = P.chunk_indptr[it.pair];
+        d.n_chunks = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(P.chunk_indptr[it.pair + 1] - c0));
+        d.pair_row = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(c0) * G);
+        if (d.n_chunks == 1) d.row = -(it.pair * G) - 1;
+      }
+    }
+    d.page_lo = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page));
+    d.page_hi = __builtin_amdgcn_readfirstlane(static_cast<int32_t>(first_page >> 32));
+    d.ids = (const_ids_ptr)(reinterpret_cast<uintptr_t>(P.page_ids + ((static_cast<int64_t>(d.page_hi) << 32) | static_cast<uint32_t>(d.page_lo))));
+    const int n_pages = (d.n_tok + fs::kPageTokens - 1) / fs::kPageTokens;
+    d.n_mine = n_pages > wave ? (n_pages - wave + WAVES - 1) / WAVES : 0;
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) {
+      if (u < d.n_mine) d.first_ids[u] = (P.records && wave + u * WAVES < 8) ? rec_slot[u] : d.ids[wave + u * WAVES];
+    }
+  }
+  return d;
+}
+
+// The query rows of the item, as the Q^T operand of this lane: lane (q = lane%16, kb = lane/16) holds
+// Q[q][32c + 8kb .. +8) for c = 0..3; rows beyond the group are zero (read from a row that exists, then blanked).
+__device__ __forceinline__ void load_desc_q(ItemDesc& d, const DecodeParams& P, int lane, int G) {
+  if (d.valid) {
+    const int qi = lane & 15, kb = lane >> 4;
+    const int qrow = d.q_row + min(qi, G - 1);
+    const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + kb;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      u32x4 v = qp[4 * c];
+      if (qi >= G) v = u32x4{0u, 0u, 0u, 0u};
+      d.q[c] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+}
+
+// The same for the fp8 kernels, in the order of d that their K operand has: instruction c = 2j + half takes
+// d = 64j + 16kb + 8half .. + 8.
+__device__ __forceinline__ void load_desc_q_fp8(ItemDesc& d, const DecodeParams& P, int lane, int G) {
+  if (d.valid) {
+    const int qi = lane & 15, kb = lane >> 4;
     const int qrow = d.q_row + min(qi, G - 1);
     const u32x4* qp = reinterpret_cast<const u32x4*>(P.q + static_cast<int64_t>(qrow) * fs::kHeadDim) + 2 * kb;
 #pragma unroll
@@ -836,12 +446,201 @@ decode_fp8_kernel(const DecodeParams P) {
       d.q[c] = __builtin_bit_cast(bf16x8, v);
     }
   }
+}
+
+__device__ __forceinline__ int64_t first_page_of(const ItemDesc& d) {
+  return (static_cast<int64_t>(d.page_hi) << 32) | static_cast<uint32_t>(d.page_lo);
+}
+
+// What the two K/V formats differ in, for the kernels below: the registers of a page in flight, how a page is
+// loaded and consumed, the order of d in the query operand and in a lane's rows of O^T (acc[j] holds four
+// consecutive d from first_d(j, lane/16) on).  `page` is the page's position in the whole page table.
+struct Bf16Format {
+  using Page = PageRegs;
+  struct Consts {};
+  static __device__ __forceinline__ Consts consts(int) { return Consts{}; }
+  static __device__ __forceinline__ void load(Page& r, const DecodeParams& P, int32_t slot, int64_t, int lane) {
+    load_page(r, P.k_pool, P.v_pool, P.k_stride, P.v_stride, slot, lane);
+  }
+  template <bool FULL>
+  static __device__ __forceinline__ void consume(SoftmaxState& st, Page& pg, const bf16x8 (&q)[4], const Consts&,
+                                                 float scale_log2, int valid, int kb) {
+    consume_page<FULL>(st, pg, q, scale_log2, valid, kb);
+  }
+  static __device__ __forceinline__ void load_q(ItemDesc& d, const DecodeParams& P, int lane, int G) { load_desc_q(d, P, lane, G); }
+  static __device__ __forceinline__ int first_d(int j, int kb) { return 16 * j + 4 * kb; }
+};
+struct Fp8Format {
+  using Page = Fp8Page;
+  struct Consts { long pick[2]; };
   // E[k][n] for the two halves of a 32-d slice: column n = lane%16 takes k = 16h2 + n, which sits in the lanes
   // with kb = 2h2 + n/8 as byte n%8 (0x38 is 1.0 in e4m3)
-  long pick[2];
+  static __device__ __forceinline__ Consts consts(int lane) {
+    const int qi = lane & 15, kb = lane >> 4;
+    Consts c;
 #pragma unroll
-  for (int h2 = 0; h2 < 2; ++h2)
-    pick[h2] = (kb == 2 * h2 + (qi >> 3)) ? static_cast<long>(0x38ul << (8 * (qi & 7))) : 0l;
+    for (int h2 = 0; h2 < 2; ++h2)
+      c.pick[h2] = (kb == 2 * h2 + (qi >> 3)) ? static_cast<long>(0x38ul << (8 * (qi & 7))) : 0l;
+    return c;
+  }
+  static __device__ __forceinline__ void load(Page& r, const DecodeParams& P, int32_t slot, int64_t page, int lane) {
+    load_page_fp8(r, P, slot, page, lane);
+  }
+  template <bool FULL>
+  static __device__ __forceinline__ void consume(SoftmaxState& st, Page& pg, const bf16x8 (&q)[4], const Consts& c,
+                                                 float scale_log2, int valid, int kb) {
+    consume_page_fp8<FULL>(st, pg, q, c.pick, scale_log2, valid, kb);
+  }
+  static __device__ __forceinline__ void load_q(ItemDesc& d, const DecodeParams& P, int lane, int G) { load_desc_q_fp8(d, P, lane, G); }
+  static __device__ __forceinline__ int first_d(int j, int kb) { return fp8_first_d(j, kb); }
+};
+
+// Where an item's G rows go, from the descriptor's row.
+struct RowDest {
+  float* o;
+  float* lse;
+  int row;
+};
+__device__ __forceinline__ RowDest row_dest(const DecodeParams& P, int row) {
+  if (row < 0) return RowDest{P.out, P.lse, -row - 1};
+  return RowDest{P.part_o, P.part_lse, row};
+}
+
+// A partial row on its way to the workgroup that will merge its pair inside the same launch: relaxed atomic stores
+// at device scope, which are written through to memory instead of waiting in this XCD's L2 (the other workgroup
+// may run on another XCD, whose L2 is not this one's).
+__device__ __forceinline__ void store_f32_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_f32x4_coherent(float* p, const f32x4 v) {
+  auto* q = reinterpret_cast<unsigned long long*>(p);
+  const unsigned long long lo = (static_cast<unsigned long long>(__float_as_uint(v[1])) << 32) | __float_as_uint(v[0]);
+  const unsigned long long hi = (static_cast<unsigned long long>(__float_as_uint(v[3])) << 32) | __float_as_uint(v[2]);
+  __hip_atomic_store(q, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(q + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Split pairs merged inside the sweep.  The workgroup has just issued the stores of the partial rows of `n` items
+// (s_pair/s_chunks/s_prow[j]: pair, chunk count and first partial row of the pair of item j; s_chunks[j] = 1: not
+// split, nothing to do).  One thread per item counts the workgroup in on the pair's counter; the workgroup that
+// brings a counter to the pair's chunk count is the last writer of that pair: it puts the counter back to zero for
+// the next launch and merges the pair's chunks into its final rows, one wavefront per q-head, with the routine of
+// the merge kernel (same bits).  Nobody waits for anybody.
+// What makes the other workgroups' rows visible, without fences (a device-scope fence writes back and invalidates
+// the whole L2 of the XCD, which on the 70B-shaped batch cost the sweep 150 us): partial rows are stored
+// (store_f32*_coherent) and read (merge_rows<.., COHERENT>) as relaxed device-scope atomics, which go to memory
+// past the caches, as the counter's atomic does; a thread counts in only after all the workgroup's stores have been
+// acknowledged (vmcnt(0) in every thread, then the barrier), and the merging workgroup reads only after its atomic
+// has returned the full count, i.e. after every other writer's atomic, each issued after its own stores were done.
+// Takes the workgroup's barriers: every thread must call it.
+template <int WAVES>
+__device__ __forceinline__ void arrive_and_merge(const DecodeParams& P, int n, const int* s_pair, const int* s_chunks,
+                                                 const int* s_prow, int* s_done, int G, int wave, int lane) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this thread's stores have reached memory
+  __syncthreads();
+  for (int j = threadIdx.x; j < n; j += WAVES * 64) {
+    const int c = s_chunks[j];
+    s_done[j] = c > 1 && __hip_atomic_fetch_add(P.pair_counters + s_pair[j], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == c - 1;
+  }
+  __syncthreads();
+  for (int j = 0; j < n; ++j) {
+    if (!__builtin_amdgcn_readfirstlane(s_done[j])) continue;
+    const int pair = __builtin_amdgcn_readfirstlane(s_pair[j]);
+    const int chunks = __builtin_amdgcn_readfirstlane(s_chunks[j]);
+    const int prow = __builtin_amdgcn_readfirstlane(s_prow[j]);
+    if (threadIdx.x == 0) __hip_atomic_store(P.pair_counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float* po = P.part_o;
+    const float* pl = P.part_lse;
+    // a wavefront takes as many q-heads side by side as divide the group evenly over the workgroup (their loads travel
+    // together: one trip to memory instead of one per q-head); the sums of a row are the same in every form
+    const int64_t c0 = prow / G;
+    float* const out0 = P.out + static_cast<int64_t>(pair) * G * fs::kHeadDim;
+    float* const lse0 = P.lse + static_cast<int64_t>(pair) * G;
+    if (G % (2 * WAVES) == 0) {
+      for (int g = 2 * wave; g < G; g += 2 * WAVES)
+        fs_merge::merge_rows<2, true>(po, pl, c0, chunks, G, g, out0 + g * fs::kHeadDim, lse0 + g, lane);
+    } else {
+      for (int g = wave; g < G; g += WAVES)
+        fs_merge::merge_rows<1, true>(po, pl, c0, chunks, G, g, out0 + g * fs::kHeadDim, lse0 + g, lane);
+    }
+  }
+}
+
+// The same for the one item of a workgroup that has no more than that.
+template <int WAVES>
+__device__ __forceinline__ void arrive_and_merge_one(const DecodeParams& P, const ItemDesc& d, int* s_meta, int G, int wave,
+                                                     int lane) {
+  if (P.pair_counters == nullptr || d.n_chunks <= 1) return;     // the same for the whole workgroup
+  if (threadIdx.x == 0) {
+    s_meta[0] = d.pair;
+    s_meta[1] = d.n_chunks;
+    s_meta[2] = d.pair_row;
+  }
+  arrive_and_merge<WAVES>(P, 1, s_meta, s_meta + 1, s_meta + 2, s_meta + 3, G, wave, lane);
+}
+
+// Merge the wavefronts' (m, l, O^T) through LDS and write the item's G partial rows.
+template <int WAVES, typename FMT>
+__device__ __forceinline__ void merge_and_store(const SoftmaxState& st, float l_total, int wave, int lane,
+                                                int G, float* __restrict__ part_o,
+                                                float* __restrict__ part_lse, int part_row,
+                                                float* sm_o, float* sm_m, float* sm_l, bool coherent) {
+  const int qi = lane & 15, kb = lane >> 4;
+  if (lane < 16) {
+    sm_m[wave * 16 + lane] = st.m;
+    sm_l[wave * 16 + lane] = l_total;
+  }
+  float* row = sm_o + (wave * 16 + qi) * kORow;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + FMT::first_d(j, kb)) = st.acc[j];
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
+    const int q = idx >> 5, d4 = idx & 31;
+    float M = sm_m[q];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sm_m[w * 16 + q]);
+    float L = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const float wgt = __builtin_amdgcn_exp2f(sm_m[w * 16 + q] - M);   // a wave with no pages has m = -inf
+      L += wgt * sm_l[w * 16 + q];
+      o += wgt * *reinterpret_cast<const f32x4*>(sm_o + (w * 16 + q) * kORow + 4 * d4);
+    }
+    const float inv = 1.0f / L;
+    // Streaming stores: the partial rows are read once, by the merge.  Measured on the 70B-shaped
+    // batch, plain stores of these 9 MB cost the 2 GB read stream about 20 us, non-temporal ones 13.
+    float* dst = part_o + static_cast<int64_t>(part_row + q) * fs::kHeadDim + 4 * d4;
+    const float lse_q = (M + __builtin_amdgcn_logf(L)) * kLn2;
+    if (coherent) {      // rows another workgroup of this launch will merge (arrive_and_merge)
+      store_f32x4_coherent(dst, o * inv);
+      if (d4 == 0) store_f32_coherent(part_lse + part_row + q, lse_q);
+    } else {
+      __builtin_nontemporal_store(o * inv, reinterpret_cast<f32x4*>(dst));
+      if (d4 == 0) __builtin_nontemporal_store(lse_q, part_lse + part_row + q);
+    }
+  }
+}
+
+// One workgroup per item.  NBUF register buffers; NBUF-1 pages are in flight while one is consumed.  The
+// steady-state loop is branch-free (every prefetch is in range, every page is full), so the loads of pages
+// i+1.. stay outstanding while page i is consumed; the ragged end is a second loop.  Index i counts this
+// wavefront's pages; its i-th page is page wave + i*WAVES of the item.
+template <int WAVES, int NBUF, typename FMT>
+__device__ __forceinline__ void sweep_one_item(const DecodeParams& P) {
+  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
+  __shared__ float sm_m[WAVES * 16];
+  __shared__ float sm_l[WAVES * 16];
+  __shared__ int s_meta[4];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kb = lane >> 4;
+  const int G = P.group;
+  ItemDesc d = load_desc_head<WAVES, NBUF>(P, static_cast<int>(blockIdx.x), 0x7FFFFFFF, wave, G);
+  FMT::load_q(d, P, lane, G);
+  const int64_t first_page = first_page_of(d);
+  const typename FMT::Consts consts = FMT::consts(lane);
 
   SoftmaxState st;
   st.m = -INFINITY;
@@ -849,36 +648,264 @@ decode_fp8_kernel(const DecodeParams P) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // the page pipeline of decode_bf16_kernel
-  Fp8Page buf[NBUF];
+  typename FMT::Page buf[NBUF];
 #pragma unroll
   for (int u = 0; u < NBUF - 1; ++u)
-    if (u < d.n_mine) load_page_fp8(buf[u], P, d.first_ids[u], first_page + wave + u * WAVES, lane);
+    if (u < d.n_mine) FMT::load(buf[u], P, d.first_ids[u], first_page + wave + u * WAVES, lane);
 
   int i = 0;
   for (; i + 2 * NBUF - 2 < d.n_mine; i += NBUF) {
 #pragma unroll
     for (int u = 0; u < NBUF; ++u) {
       const int pg = wave + (i + u + NBUF - 1) * WAVES;
-      load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, d.ids[pg], first_page + pg, lane);
-      consume_page_fp8<true>(st, buf[u], d.q, pick, P.scale_log2, fs::kPageTokens, kb);
+      FMT::load(buf[(u + NBUF - 1) % NBUF], P, d.ids[pg], first_page + pg, lane);
+      FMT::template consume<true>(st, buf[u], d.q, consts, P.scale_log2, fs::kPageTokens, kb);
     }
   }
+  // here pages i .. i+NBUF-2 (those below n_mine) are in flight in buf[0 .. NBUF-2]
 #pragma unroll
   for (int u = 0; u < 2 * NBUF - 2; ++u) {
     const int pi = i + u;
     if (pi < d.n_mine) {
       const int pn = pi + NBUF - 1;
-      if (pn < d.n_mine) load_page_fp8(buf[(u + NBUF - 1) % NBUF], P, d.ids[wave + pn * WAVES], first_page + wave + pn * WAVES, lane);
-      consume_page_fp8<false>(st, buf[u % NBUF], d.q, pick, P.scale_log2, min(fs::kPageTokens, d.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
+      if (pn < d.n_mine) FMT::load(buf[(u + NBUF - 1) % NBUF], P, d.ids[wave + pn * WAVES], first_page + wave + pn * WAVES, lane);
+      FMT::template consume<false>(st, buf[u % NBUF], d.q, consts, P.scale_log2,
+                                   min(fs::kPageTokens, d.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
     }
   }
 
   const RowDest dst = row_dest(P, d.row);
   const float l_total = sum_xor32(sum_xor16(st.l));
-  merge_and_store<WAVES, true>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l,
-                               P.pair_counters != nullptr && d.n_chunks > 1);
+  merge_and_store<WAVES, FMT>(st, l_total, wave, lane, G, dst.o, dst.lse, dst.row, sm_o, sm_m, sm_l,
+                              P.pair_counters != nullptr && d.n_chunks > 1);
   arrive_and_merge_one<WAVES>(P, d, s_meta, G, wave, lane);
+}
+
+template <int WAVES, int NBUF>
+__global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodeParams P) {
+  sweep_one_item<WAVES, NBUF, Bf16Format>(P);
+}
+
+// (at least two wavefronts per SIMD: within 256 registers the compiler keeps the matrix results in ordinary
+// registers; allowed 512 it parks them in accumulation registers and moves every one back before the vector units
+// can touch it, 57 extra instructions per page)
+template <int WAVES, int NBUF>
+__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+decode_fp8_kernel(const DecodeParams P) {
+  sweep_one_item<WAVES, NBUF, Fp8Format>(P);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Persistent form of the sweep.  A fixed set of workgroups (two per CU) walks the list: the
+// first gridDim.x items go one to each workgroup, every further item is claimed from a counter
+// in the list's longest-first order at the moment a workgroup has streamed its current item
+// (list scheduling, as the hardware dispatcher does for one workgroup per item).  Finished
+// partial rows wait in LDS and leave in one burst when the staging area is full or the
+// workgroup is done: writes scattered through the launch slow the read stream far more than
+// their bytes explain, writes at the end of a workgroup's life mostly do not.  The next item's
+// descriptor, query rows and first pages are fetched while the current item's rows are merged,
+// and the barriers around that merge wait for LDS traffic only, so those loads stay in flight
+// across them.  claim[0] counts the items handed out beyond the first gridDim.x, claim[1] the workgroups
+// that have left; both are zero between launches.
+// ---------------------------------------------------------------------------------------------
+
+constexpr int kStageRows = 64;    // partial rows a workgroup keeps in LDS before it writes them (64 x 512 B)
+constexpr int kSecondShare = 4;   // a CU's second workgroup claims only within the first 1/kSecondShare of the list
+
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// UNITS = true is the form without a counter: workgroup u walks the items [unit_indptr[u], unit_indptr[u+1]) of a
+// list that the host has cut into equal runs of pages (fs_build_worklist_units), so every workgroup streams
+// the same number of bytes and nothing is handed out at run time; `claim` then carries nothing.
+template <int WAVES, int NBUF, bool UNITS, typename FMT>
+__device__ __forceinline__ void persistent_sweep(const DecodeParams& P, int n_items, int* __restrict__ claim, int n_first,
+                                                 const int64_t* __restrict__ unit_indptr) {
+  __shared__ __attribute__((aligned(16))) float sm_o[WAVES * 16 * kORow];
+  __shared__ float sm_m[WAVES * 16];
+  __shared__ float sm_l[WAVES * 16];
+  __shared__ __attribute__((aligned(16))) float st_o[kStageRows * fs::kHeadDim];
+  __shared__ float st_lse[kStageRows];
+  __shared__ int st_row[kStageRows];
+  __shared__ int s_next;
+  // what arrive_and_merge needs to know of the items whose rows are staged (at most kStageRows items: G >= 1)
+  __shared__ int st_pair[kStageRows], st_chunks[kStageRows], st_prow[kStageRows], st_done[kStageRows];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qi = lane & 15, kb = lane >> 4;
+  const int G = P.group;
+  const int n_groups = gridDim.x;
+
+  int unit_end = 0, cur_k = static_cast<int>(blockIdx.x);
+  if constexpr (UNITS) {
+    cur_k = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x]));
+    unit_end = __builtin_amdgcn_readfirstlane(static_cast<int>(unit_indptr[blockIdx.x + 1]));   // > cur_k: no unit is empty
+  }
+  ItemDesc cur = load_desc_head<WAVES, NBUF>(P, cur_k, n_items, wave, G);   // a valid item by the launch
+  FMT::load_q(cur, P, lane, G);
+  const typename FMT::Consts consts = FMT::consts(lane);
+
+  typename FMT::Page buf[NBUF];
+  auto prologue = [&](const ItemDesc& d) __attribute__((always_inline)) {
+    const int64_t first_page = first_page_of(d);
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u)
+      if (u < d.n_mine) FMT::load(buf[u], P, d.first_ids[u], first_page + wave + u * WAVES, lane);
+  };
+  prologue(cur);
+
+  // Two workgroups share a CU, and the one launched second streams at about half the rate of the first (the
+  // issue arbiter prefers the older wavefront) while the CU's total stays the same.  A late item in its hands
+  // takes twice as long and ends the launch late, so the workgroups beyond the first n_first (one per CU) -
+  // by launch order the second workgroup of a CU - stop claiming once a quarter of the list is handed out;
+  // they are there to fill the CU while the list is long, and leave the rest to their siblings.  (Where launch
+  // order does not map to CUs like that, as many workgroups retire early just the same, which costs nothing
+  // measurable.)
+  const bool second_on_cu = static_cast<int>(blockIdx.x) >= n_first;
+  bool keep_claiming = true;
+  int staged = 0, staged_items = 0;
+  bool staged_split = false;       // some staged item belongs to a split pair
+  for (;;) {
+    // With equal runs the next item is known from the start: its descriptor and the slots of its first pages are
+    // asked for now and travel while the current item streams, so that at the item's end the next pages can be
+    // requested at once.  With a counter the next item is only known after the claim (below).
+    ItemDesc nxt;
+    if constexpr (UNITS) {
+      ++cur_k;
+      nxt = load_desc_head<WAVES, NBUF>(P, cur_k < unit_end ? cur_k : n_items, n_items, wave, G);
+    }
+    SoftmaxState st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st.acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int64_t first_page = first_page_of(cur);
+    int i = 0;          // counts this wavefront's pages of the item: its i-th page is page wave + i*WAVES
+    for (; i + 2 * NBUF - 2 < cur.n_mine; i += NBUF) {
+#pragma unroll
+      for (int u = 0; u < NBUF; ++u) {
+        const int pg = wave + (i + u + NBUF - 1) * WAVES;
+        FMT::load(buf[(u + NBUF - 1) % NBUF], P, cur.ids[pg], first_page + pg, lane);
+        FMT::template consume<true>(st, buf[u], cur.q, consts, P.scale_log2, fs::kPageTokens, kb);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * NBUF - 2; ++u) {
+      const int pi = i + u;
+      if (pi < cur.n_mine) {
+        const int pn = pi + NBUF - 1;
+        if (pn < cur.n_mine) FMT::load(buf[(u + NBUF - 1) % NBUF], P, cur.ids[wave + pn * WAVES], first_page + wave + pn * WAVES, lane);
+        FMT::template consume<false>(st, buf[u % NBUF], cur.q, consts, P.scale_log2,
+                                     min(fs::kPageTokens, cur.n_tok - (wave + pi * WAVES) * fs::kPageTokens), kb);
+      }
+    }
+    // merge the wavefronts through LDS into the staging rows
+    const float l_total = sum_xor32(sum_xor16(st.l));
+    if (lane < 16) {
+      sm_m[wave * 16 + lane] = st.m;
+      sm_l[wave * 16 + lane] = l_total;
+    }
+    {
+      float* row = sm_o + (wave * 16 + qi) * kORow;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(row + FMT::first_d(j, kb)) = st.acc[j];
+    }
+    // The next item is claimed only now.  Claiming it earlier would hide the counter's round trip, but a
+    // workgroup would then sit on an item another could have started: claiming at the start of the current
+    // item cost 11 us of the launch on the 70B-shaped batch, two items ahead 20 us, four pages early 4 us.
+    if constexpr (!UNITS) {
+      if (threadIdx.x == 0) s_next = keep_claiming ? atomicAdd(claim, 1) + n_groups : n_items;
+    }
+    lds_barrier();
+    // every page of the current item is consumed: fetch the next item's descriptor and first pages now,
+    // so that they travel while the rows are merged
+    if constexpr (!UNITS) {
+      const int next_k = __builtin_amdgcn_readfirstlane(s_next);
+      nxt = load_desc_head<WAVES, NBUF>(P, next_k, n_items, wave, G);
+      if (second_on_cu) keep_claiming = static_cast<int64_t>(next_k) * kSecondShare < n_items;
+    }
+    FMT::load_q(nxt, P, lane, G);
+    prologue(nxt);
+    for (int idx = threadIdx.x; idx < G * 32; idx += WAVES * 64) {
+      const int q = idx >> 5, d4 = idx & 31;
+      float M = sm_m[q];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sm_m[w * 16 + q]);
+      float L = 0.f;
+      f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) {
+        const float wgt = __builtin_amdgcn_exp2f(sm_m[w * 16 + q] - M);   // a wave with no pages has m = -inf
+        L += wgt * sm_l[w * 16 + q];
+        o += wgt * *reinterpret_cast<const f32x4*>(sm_o + (w * 16 + q) * kORow + 4 * d4);
+      }
+      const float inv = 1.0f / L;
+      *reinterpret_cast<f32x4*>(st_o + (staged + q) * fs::kHeadDim + 4 * d4) = o * inv;
+      if (d4 == 0) {
+        st_lse[staged + q] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+        st_row[staged + q] = cur.row >= 0 ? cur.row + q : cur.row - q;
+      }
+    }
+    if (P.pair_counters != nullptr) {
+      if (threadIdx.x == 0) {
+        st_pair[staged_items] = cur.pair;
+        st_chunks[staged_items] = cur.n_chunks;
+        st_prow[staged_items] = cur.pair_row;
+      }
+      staged_split |= cur.n_chunks > 1;
+    }
+    ++staged_items;
+    staged += G;
+    lds_barrier();                     // staging rows complete; the merge buffers may be reused
+    const bool last = !nxt.valid;
+    if (last || staged + G > kStageRows) {
+      for (int idx = threadIdx.x; idx < staged * 32; idx += WAVES * 64) {
+        const int r = idx >> 5, d4 = idx & 31;
+        const int row = st_row[r];
+        float* dst = row >= 0 ? P.part_o + static_cast<int64_t>(row) * fs::kHeadDim : P.out + static_cast<int64_t>(-row - 1) * fs::kHeadDim;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(st_o + r * fs::kHeadDim + 4 * d4);
+        if (row >= 0 && P.pair_counters != nullptr) store_f32x4_coherent(dst + 4 * d4, v);     // rows for arrive_and_merge
+        else __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + 4 * d4));
+      }
+      for (int r = threadIdx.x; r < staged; r += WAVES * 64) {
+        const int row = st_row[r];
+        if (row >= 0 && P.pair_counters != nullptr) store_f32_coherent(P.part_lse + row, st_lse[r]);
+        else __builtin_nontemporal_store(st_lse[r], row >= 0 ? P.part_lse + row : P.lse + (-row - 1));
+      }
+      if (staged_split) arrive_and_merge<WAVES>(P, staged_items, st_pair, st_chunks, st_prow, st_done, G, wave, lane);
+      staged = 0;
+      staged_items = 0;
+      staged_split = false;
+      // the next write into the staging rows comes after the next item's first barrier, which every
+      // thread reaches only when it is done reading them here
+    }
+    if (last) break;
+    cur = nxt;
+  }
+  // The last workgroup to leave puts both counters back to zero for the next launch (every other
+  // workgroup has made its last claim by then).
+  if constexpr (!UNITS) {
+    if (threadIdx.x == 0 && atomicAdd(claim + 1, 1) == static_cast<int>(gridDim.x) - 1) {
+      __atomic_store_n(claim, 0, __ATOMIC_RELAXED);
+      __atomic_store_n(claim + 1, 0, __ATOMIC_RELAXED);
+    }
+  }
+}
+
+// (two wavefronts per SIMD - two workgroups per CU - is what the launch counts on: at most 256 registers)
+template <int WAVES, int NBUF, bool UNITS>
+__global__ void __launch_bounds__(WAVES * 64, 2) decode_bf16_persistent_kernel(const DecodeParams P, int n_items,
+                                                                            int* __restrict__ claim, int n_first,
+                                                                            const int64_t* __restrict__ unit_indptr) {
+  persistent_sweep<WAVES, NBUF, UNITS, Bf16Format>(P, n_items, claim, n_first, unit_indptr);
+}
+template <int WAVES, int NBUF, bool UNITS>
+__global__ void __launch_bounds__(WAVES * 64, 2) decode_fp8_persistent_kernel(const DecodeParams P, int n_items,
+                                                                           int* __restrict__ claim, int n_first,
+                                                                           const int64_t* __restrict__ unit_indptr) {
+  persistent_sweep<WAVES, NBUF, UNITS, Fp8Format>(P, n_items, claim, n_first, unit_indptr);
 }
 
 template <typename K>
@@ -913,7 +940,7 @@ __global__ void zero_counters_kernel(int* __restrict__ claim) {
 // n_items > 0, *P is ready for a launch (the fused fields are left NULL).
 fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, const void* items_dev,
                   const int32_t* sched_dev, int64_t n_items, float* part_o, float* part_lse, bool partials_needed,
-                  bool bf16_only, DecodeParams* P) {
+                  DecodeParams* P) {
   if (!shape || !kv) return fs::fail(FS_EINVAL, "%s: shape or kv is NULL", who);
   if (shape->n_kv_heads < 1 || shape->n_q_heads < shape->n_kv_heads || shape->n_q_heads % shape->n_kv_heads)
     return fs::fail(FS_EINVAL, "%s: n_q_heads %d is not a multiple of n_kv_heads %d", who, shape->n_q_heads,
@@ -927,8 +954,6 @@ fs_status prepare(const char* who, const fs_shape* shape, const fs_kv_view* kv, 
   if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "%s: n_items out of range", who);
   if (kv->kv_dtype != FS_KV_BF16 && kv->kv_dtype != FS_KV_FP8_E4M3)
     return fs::fail(FS_EINVAL, "%s: unknown kv_dtype %d", who, kv->kv_dtype);
-  if (bf16_only && kv->kv_dtype != FS_KV_BF16)
-    return fs::fail(FS_EUNSUPPORTED, "%s: only bf16 K/V is built (kv_dtype %d)", who, kv->kv_dtype);
   if (n_items == 0) return FS_OK;
   if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev ||
       (partials_needed && (!part_o || !part_lse)))
@@ -1009,16 +1034,34 @@ fs_status launch_plain(const char* who, const DecodeParams& P, int kv_dtype, int
 #undef FS_PICK
 }
 
-// The persistent form: two resident workgroups per CU claim items from claim_dev.
-fs_status launch_persistent(const char* who, const DecodeParams& P, int64_t n_items, int32_t* claim_dev, hipStream_t s) {
-  int n_cu = 0;
-  if (const fs_status st = device_cu_count(who, &n_cu); st != FS_OK) return st;
-  const int64_t groups = std::min<int64_t>(n_items, 2ll * n_cu);
-  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, false>), dim3(static_cast<unsigned>(groups)), dim3(256), 0, s, P,
-                     static_cast<int>(n_items), claim_dev, n_cu, static_cast<const int64_t*>(nullptr));
+// Resident workgroups, for either K/V format.  unit_indptr_dev NULL: `groups` workgroups claim items from claim_dev
+// (n_first of them the first on their CU); else workgroup u walks the items of run u.
+fs_status launch_resident(const char* who, const DecodeParams& P, int kv_dtype, int64_t groups, int64_t n_items,
+                          int32_t* claim_dev, int n_first, const int64_t* unit_indptr_dev, hipStream_t s) {
+  const dim3 grid(static_cast<unsigned>(groups)), block(256);
+  const int n = static_cast<int>(n_items);
+  if (kv_dtype == FS_KV_BF16) {
+    if (unit_indptr_dev)
+      hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, true>), grid, block, 0, s, P, n, claim_dev, n_first, unit_indptr_dev);
+    else
+      hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, false>), grid, block, 0, s, P, n, claim_dev, n_first, unit_indptr_dev);
+  } else {
+    if (unit_indptr_dev)
+      hipLaunchKernelGGL((decode_fp8_persistent_kernel<4, 3, true>), grid, block, 0, s, P, n, claim_dev, n_first, unit_indptr_dev);
+    else
+      hipLaunchKernelGGL((decode_fp8_persistent_kernel<4, 3, false>), grid, block, 0, s, P, n, claim_dev, n_first, unit_indptr_dev);
+  }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
   return FS_OK;
+}
+
+// The persistent form: two resident workgroups per CU claim items from claim_dev.
+fs_status launch_persistent(const char* who, const DecodeParams& P, int kv_dtype, int64_t n_items, int32_t* claim_dev,
+                            hipStream_t s) {
+  int n_cu = 0;
+  if (const fs_status st = device_cu_count(who, &n_cu); st != FS_OK) return st;
+  return launch_resident(who, P, kv_dtype, std::min<int64_t>(n_items, 2ll * n_cu), n_items, claim_dev, n_cu, nullptr, s);
 }
 
 }  // namespace
@@ -1028,7 +1071,7 @@ extern "C" fs_status fs_decode_attention(const fs_shape* shape, const fs_kv_view
                                          int64_t n_items, float* part_o, float* part_lse, void* stream) {
   DecodeParams P;
   if (const fs_status st = prepare("fs_decode_attention", shape, kv, items_dev, sched_dev, n_items, part_o, part_lse,
-                                   true, false, &P); st != FS_OK || n_items == 0)
+                                   true, &P); st != FS_OK || n_items == 0)
     return st;
   return launch_plain("fs_decode_attention", P, kv->kv_dtype, n_items, static_cast<hipStream_t>(stream));
 }
@@ -1039,11 +1082,11 @@ extern "C" fs_status fs_decode_attention_persistent(const fs_shape* shape, const
                                                     float* part_lse, void* stream) {
   DecodeParams P;
   if (const fs_status st = prepare("fs_decode_attention_persistent", shape, kv, items_dev, sched_dev, n_items, part_o,
-                                   part_lse, true, true, &P); st != FS_OK || n_items == 0)
+                                   part_lse, true, &P); st != FS_OK || n_items == 0)
     return st;
   if (!claim_dev || (reinterpret_cast<uintptr_t>(claim_dev) & 7))
     return fs::fail(FS_EINVAL, "fs_decode_attention_persistent: claim_dev is NULL or not 8-byte aligned");
-  return launch_persistent("fs_decode_attention_persistent", P, n_items, claim_dev, static_cast<hipStream_t>(stream));
+  return launch_persistent("fs_decode_attention_persistent", P, kv->kv_dtype, n_items, claim_dev, static_cast<hipStream_t>(stream));
 }
 
 extern "C" fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_kv_view* kv,
@@ -1056,7 +1099,7 @@ extern "C" fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_k
                                                         static_cast<long long>(n_pairs));
   const bool split = n_items > n_pairs;            // some pair has more than one item: partial rows and a merge
   DecodeParams P;
-  if (const fs_status st = prepare(who, shape, kv, items_dev, sched_dev, n_items, part_o, part_lse, split, false, &P);
+  if (const fs_status st = prepare(who, shape, kv, items_dev, sched_dev, n_items, part_o, part_lse, split, &P);
       st != FS_OK || n_items == 0)
     return st;
   if (n_pairs == 0) return fs::fail(FS_EINVAL, "%s: %lld items but no pairs", who, static_cast<long long>(n_items));
@@ -1070,8 +1113,9 @@ extern "C" fs_status fs_decode_attention_fused(const fs_shape* shape, const fs_k
   hipStream_t s = static_cast<hipStream_t>(stream);
   // The persistent form pays once every resident workgroup walks several items; below that it is the same
   // work plus a counter.
+  // (bf16 only: with fp8 K/V the resident forms measure no faster than one workgroup per item)
   const bool persistent = claim_dev && kv->kv_dtype == FS_KV_BF16 && n_items >= fs::kPersistentMinItems;
-  const fs_status st = persistent ? launch_persistent(who, P, n_items, claim_dev, s)
+  const fs_status st = persistent ? launch_persistent(who, P, kv->kv_dtype, n_items, claim_dev, s)
                                   : launch_plain(who, P, kv->kv_dtype, n_items, s);
   if (st != FS_OK || !split) return st;
   return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
@@ -1090,7 +1134,7 @@ extern "C" fs_status fs_decode_attention_units(const fs_shape* shape, const fs_k
                                                         static_cast<long long>(n_units));
   const bool split = partials_only || n_items > n_pairs;
   DecodeParams P;
-  if (const fs_status st = prepare(who, shape, kv, items_dev, nullptr, n_items, part_o, part_lse, split, true, &P);
+  if (const fs_status st = prepare(who, shape, kv, items_dev, nullptr, n_items, part_o, part_lse, split, &P);
       st != FS_OK || n_items == 0)
     return st;
   if (n_units == 0 || (!partials_only && n_pairs == 0))
@@ -1104,10 +1148,8 @@ extern "C" fs_status fs_decode_attention_units(const fs_shape* shape, const fs_k
     P.lse = lse;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, true>), dim3(static_cast<unsigned>(n_units)), dim3(256), 0, s, P,
-                     static_cast<int>(n_items), static_cast<int*>(nullptr), 0, unit_indptr_dev);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+  if (const fs_status st = launch_resident(who, P, kv->kv_dtype, n_units, n_items, nullptr, 0, unit_indptr_dev, s); st != FS_OK)
+    return st;
   if (partials_only || n_items == n_pairs) return FS_OK;
   return fs::merge_lse_launch(who, part_o, part_lse, chunk_indptr_dev, n_pairs, P.group, out, lse, /*skip_single=*/true, s);
 }
@@ -1129,7 +1171,7 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
     return fs::fail(FS_EINVAL, "%s: n_units %lld outside [0, n_items]", who, static_cast<long long>(n_units));
   const bool split = sweep_only || n_items > n_pairs;
   DecodeParams P;
-  if (const fs_status st = prepare(who, shape, kv, records_dev, nullptr, n_items, part_o, part_lse, split, units, &P);
+  if (const fs_status st = prepare(who, shape, kv, records_dev, nullptr, n_items, part_o, part_lse, split, &P);
       st != FS_OK || n_items == 0)
     return st;
   if ((!sweep_only && n_pairs == 0) || (units && n_units == 0))
@@ -1150,10 +1192,7 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
   hipStream_t s = static_cast<hipStream_t>(stream);
   fs_status st = FS_OK;
   if (units) {
-    hipLaunchKernelGGL((decode_bf16_persistent_kernel<4, 3, true>), dim3(static_cast<unsigned>(n_units)), dim3(256), 0, s, P,
-                       static_cast<int>(n_items), static_cast<int*>(nullptr), 0, unit_indptr_dev);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) st = fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    st = launch_resident(who, P, kv->kv_dtype, n_units, n_items, nullptr, 0, unit_indptr_dev, s);
   } else {
     st = launch_plain(who, P, kv->kv_dtype, n_items, s);
   }
@@ -1170,7 +1209,7 @@ extern "C" fs_status fs_decode_attention_fused_static(const fs_shape* shape, con
                                                         static_cast<long long>(n_pairs));
   const bool split = n_items > n_pairs;
   DecodeParams P;
-  if (const fs_status st = prepare(who, shape, kv, items_dev, sched_dev, n_items, nullptr, nullptr, false, false, &P);
+  if (const fs_status st = prepare(who, shape, kv, items_dev, sched_dev, n_items, nullptr, nullptr, false, &P);
       st != FS_OK || n_items == 0)
     return st;
   if (n_pairs == 0) return fs::fail(FS_EINVAL, "%s: %lld items but no pairs", who, static_cast<long long>(n_items));
@@ -1215,7 +1254,7 @@ extern "C" fs_status fs_decode_attention_fused_static(const fs_shape* shape, con
     hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, claim);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fs::fail(FS_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
-    st = launch_persistent(who, P, n_items, claim, s);
+    st = launch_persistent(who, P, kv->kv_dtype, n_items, claim, s);
   } else {
     st = launch_plain(who, P, kv->kv_dtype, n_items, s);
   }

@@ -109,7 +109,7 @@ class DeviceShare:
                               self.n_items, self.part_o, self.part_lse, torch.cuda.current_stream().cuda_stream)
 
     def decode_persistent(self, use_sched: bool = True):
-        """The same partials by the persistent form of the sweep (bf16 K/V only)."""
+        """The same partials by the persistent form of the sweep."""
         if not hasattr(self, "claim"):
             self.claim = torch.zeros(2, dtype=torch.int32, device=self.device)   # every launch leaves them at zero
         B.fs_decode_attention_persistent(self.shape, self.view, self.items, self.sched if use_sched else None,
@@ -122,7 +122,7 @@ class DeviceShare:
 
     def run_fused(self, use_sched: bool = True, persistent: bool = True):
         """Sweep and merge in one library call; unsplit pairs get their final rows from the sweep.  With
-        ``persistent`` the counters are handed over and the library takes the persistent sweep for long bf16 lists."""
+        ``persistent`` the counters are handed over and the library takes the persistent sweep for long lists."""
         if persistent and not hasattr(self, "claim"):
             self.claim = torch.zeros(2, dtype=torch.int32, device=self.device)
         B.fs_decode_attention_fused(self.shape, self.view, self.items, self.sched if use_sched else None, self.n_items,

@@ -370,7 +370,7 @@ def test_repeated_launches_agree_bit_for_bit(cfg_id):
     owner, _, _ = fs.fs_build_placement(shape_of(w), w["ctx_len"], w["mode"])
     ds, kv, items, pairs, sched, indptr = run_rank(w, q, 0, 512, owner)
     first = [t.clone() for t in (ds.part_o, ds.part_lse, ds.out, ds.lse)]
-    forms = [False] * 3 + ([True] * 3 if w["kv_dtype"] == "bf16" else [])
+    forms = [False] * 3 + [True] * 3
     for rep, persistent in enumerate(forms):
         for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
             t.fill_(float("nan"))

@@ -86,11 +86,10 @@ def test_decode_on_drawn_shapes(seed):
         TD.check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, what)
         # from launch records, with the merge as a kernel and inside the sweep: the same bits
         TD.check_records(ds, kv, items, sched, indptr, what)
-        if w["kv_dtype"] == "bf16":
-            plain = ds.out.clone()
-            ds.run(persistent=True)
-            torch.cuda.synchronize()
-            assert torch.equal(plain, ds.out), f"{what}: the persistent sweep differs from the plain one"
+        plain = ds.out.clone()
+        ds.run(persistent=True)
+        torch.cuda.synchronize()
+        assert torch.equal(plain, ds.out), f"{what}: the persistent sweep differs from the plain one"
 
 
 @pytest.mark.parametrize("seed", range(2))

@@ -56,7 +56,7 @@ def run_units(w, q, rank, n_units, owner, o_owner=None):
                                                  w["n_q_heads"], w["n_kv_heads"])
     assert items.view(np.int32).reshape(-1, 8).tobytes() == oi.tobytes() and unit_indptr.tobytes() == ou.tobytes()
     assert chunk_indptr.tobytes() == oc.tobytes() and pairs.view(np.int32).reshape(-1, 4).tobytes() == op.tobytes()
-    kv = make_kv_pool(w["seed"], op[:, :2] if len(op) else np.zeros((0, 2)), w["ctx_len"])
+    kv = make_kv_pool(w["seed"], op[:, :2] if len(op) else np.zeros((0, 2)), w["ctx_len"], kv_dtype=w["kv_dtype"])
     ds = DeviceShare(sh, q, kv, w["sm_scale"])
     ds.set_worklist_units(items, pairs, unit_indptr, chunk_indptr)
     # from launch records first (item order, one workgroup per unit), then from the items: the same bits
@@ -123,28 +123,31 @@ def test_small_batches_every_rank(n_units):
         check(full_o, full_l, un_o, un_l, f"cfg{cfg_id} units={n_units}: all ranks gathered vs unsharded")
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (12, 4), (64, 8), (32, 2)])
-def test_group_sizes_and_ragged_lengths(Hq, Hkv):
+def test_group_sizes_and_ragged_lengths(Hq, Hkv, kv_dtype):
     lens = [1, 2, 15, 16, 17, 31, 33, 47, 48, 64, 65, 127, 128, 129, 255, 257, 300, 511, 513, 700, 1000, 1025]
     w = make_requests(0, n_req=len(lens))
-    w.update(n_q_heads=Hq, n_kv_heads=Hkv, group=Hq // Hkv, n_ranks=2, ctx_len=np.array(lens, dtype=np.int32))
+    w.update(n_q_heads=Hq, n_kv_heads=Hkv, group=Hq // Hkv, n_ranks=2, ctx_len=np.array(lens, dtype=np.int32), kv_dtype=kv_dtype)
     q = make_q(w["seed"] + 3, len(lens), Hq, 128)
     sh = fs.FsShape(len(lens), Hq, Hkv, 128, 16, 2)
     owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
     for n_units in (5, 64):
         ds, kv, op, oi, chunk_indptr = run_units(w, q, 1, n_units, owner)
         ref_o, ref_l = oracle.decode_attention_pairs(q, kv, op, Hq, Hq // Hkv, w["sm_scale"], workers=8)
-        check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"G={Hq // Hkv} units={n_units}")
+        check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, f"{kv_dtype} G={Hq // Hkv} units={n_units}")
 
 
-def _full(cfg_id, rank, **req_kw):
+def _full(cfg_id, rank, kv_dtype=None, **req_kw):
     w = make_requests(cfg_id, **req_kw)
+    if kv_dtype:
+        w["kv_dtype"] = kv_dtype
     q = make_q(w["seed"], w["n_req"], w["n_q_heads"], 128)
     sh = fs.FsShape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], 128, 16, w["n_ranks"])
     owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
     o_owner, _, _ = oracle.build_placement(w["ctx_len"], w["mode"], w["n_ranks"], w["n_kv_heads"])
     n_units = 2 * torch.cuda.get_device_properties(0).multi_processor_count       # what bench.py launches
-    what = f"cfg{cfg_id}{' ' + str(req_kw) if req_kw else ''} rank {rank}, {n_units} units"
+    what = f"cfg{cfg_id}{' ' + str(req_kw) if req_kw else ''}{' held as ' + kv_dtype if kv_dtype else ''} rank {rank}, {n_units} units"
     say(f"{what}: generating pool")
     ds, kv, op, oi, chunk_indptr = run_units(w, q, rank, n_units, owner, o_owner)
     say(f"{what}: {len(op)} pairs, {len(oi)} items, {ds.kv_bytes / 1e6:.1f} MB of K+V")
@@ -165,6 +168,14 @@ def test_config1_full_size_every_pair():
 
 def test_config2_full_size_every_pair():
     _full(2, 0)
+
+
+def test_config4_fp8_full_size_every_pair():
+    _full(4, 0)
+
+
+def test_config2_held_as_fp8_full_size_every_pair():
+    _full(2, 0, kv_dtype="fp8")
 
 
 @pytest.mark.parametrize("rank", range(5))

@@ -243,10 +243,10 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_persistent(_shape(1, 4, 2, 3, d=64), kv, None, None, 3, None, None, None)
     assert e.value.status == fs.FS_EUNSUPPORTED
-    kv8 = fs.FsKvView(kv_dtype=fs.FS_KV_FP8_E4M3)
+    kv8 = fs.FsKvView(kv_dtype=fs.FS_KV_FP8_E4M3)                   # fp8 K/V is served by every form: the NULL pointers are what is wrong
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_persistent(sh, kv8, None, None, 3, None, None, None)
-    assert e.value.status == fs.FS_EUNSUPPORTED
+    assert e.value.status == fs.FS_EINVAL
     # the fused call: the same checks, and the pair count must fit the list
     fs.fs_decode_attention_fused(sh, kv, None, None, 0, None, 0, None, None, None, None, None)   # empty list: no-op
     for n_items, n_pairs in ((3, 4), (3, -1), (3, 0), (3, 2)):          # too many pairs, negative, none, NULL pointers
@@ -263,7 +263,7 @@ def test_device_entry_points_validate_before_touching_the_gpu():
         assert e.value.status == fs.FS_EINVAL
     with pytest.raises(fs.FsError) as e:
         fs.fs_decode_attention_units(sh, kv8, None, 3, None, 2, None, 2, None, None, None, None)
-    assert e.value.status == fs.FS_EUNSUPPORTED
+    assert e.value.status == fs.FS_EINVAL
     fs.fs_decode_attention_records(sh, kv, None, 0, None, 0, None, 0, None, None, None, None, None)  # empty list: no-op
     for n_items, n_units, n_pairs in ((3, 0, 4), (3, 0, 0), (3, 0, 2)):
         with pytest.raises(fs.FsError) as e:
