@@ -96,7 +96,8 @@ def run(args) -> int:
         print("bench.py: this rank's prefill share is empty", file=sys.stderr)
         return 2
     ctx = (w["n_done"] + w["n_new"]).astype(np.int32)
-    kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx)
+    kv_dtype = args.kv_dtype or "bf16"
+    kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx, kv_dtype=kv_dtype)
     q_indptr = np.concatenate([[0], np.cumsum(w["n_new"])]).astype(np.int64)
     q = make_prefill_q(w["seed"], int(q_indptr[-1]), shape.n_q_heads, 128)
     ds = DeviceShare(shape, q, kv, 1.0 / np.sqrt(128.0), v_range=v_range)
@@ -311,9 +312,10 @@ def run(args) -> int:
         "metric": "chunked-prefill attention TFLOP/s (% of bf16 MFMA peak) and query-token-heads/s, rank-0 share, 1 MI355X",
         "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 (second product in fp16)" if not args.prefill_wide_v else "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": ("bf16" if kv_dtype == "bf16" else "fp8_e4m3 K/V, products in bf16") + (" (second product in fp16)" if not args.prefill_wide_v else ""), "data": "synthetic",
         "config": {"workload": f"prefill batch: {args.prefill_queue} waiting prompts (lognormal median 8001, cap 123192), budget {args.prefill_budget} tokens, "
-                               f"Hq=64, Hkv=8, d=128, page=16, R=7 head-level hybrid, rank {args.rank}, seed={w['seed']}",
+                               f"Hq=64, Hkv=8, d=128, page=16, R=7 head-level hybrid, rank {args.rank}, seed={w['seed']}"
+                               + (f", K/V held as {kv_dtype}" if kv_dtype != "bf16" else ""),
                    "n_pairs": len(pairs), "n_tiles": ds.n_prefill_tiles, "n_items": len(items), "tile_tokens": w["tile"],
                    "kv_chunk_tokens": kv_chunk, "batch_tokens": int(w["n_tokens"]),
                    "query_rows": rows, "kv_tokens_of_pairs": kv_tokens, "flops": flops,
@@ -330,13 +332,13 @@ def run(args) -> int:
         "host_us_per_step": dict(zip(("all", "router", "scheduler", "placement", "wait_for_staging", "tile_list", "upload_enqueue"),
                                      (round(float(v), 1) for v in np.mean(np.array(host_us), axis=0)))),
         "query_token_heads_per_s": round(rows / G / (ms_per_step * 1e-3), 1),
-        "roofline": {"bound": "mfma", "kernel": "prefill_bf16_kernel", "achieved": round(flops / (k_avg * 1e-3) / 1e12, 2),
+        "roofline": {"bound": "mfma", "kernel": "prefill_bf16_kernel" if kv_dtype == "bf16" else "prefill_fp8_kernel", "achieved": round(flops / (k_avg * 1e-3) / 1e12, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(flops / (k_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "algorithmic_flops_per_launch": flops,
                      "traffic": MEASURED_TRAFFIC_DEFAULT_BATCH if (args.prefill_queue, args.prefill_budget, args.rank, kv_chunk)
                      == (64, 8192, 0, 2272) and fs.fs_get_option("prefill_waves") == 8
-                     and fs.fs_get_option("prefill_col_tiles") == 1 else None},
+                     and fs.fs_get_option("prefill_col_tiles") == 1 and kv_dtype == "bf16" else None},
     }
     if cpu is not None:
         res["cpu_baseline"] = cpu

@@ -60,12 +60,15 @@ enum { FS_MODE_TP = 0, FS_MODE_DP = 1 };          /* per request                
 enum { FS_KV_BF16 = 0, FS_KV_FP8_E4M3 = 1 };      /* storage type of K and V      */
 /* What the caller states about the V values a call can read (fs_kv_view.v_range; used by
  * fs_prefill_attention, ignored by the decode calls):
- *   FS_V_ANY         nothing: any finite bf16 value.  V stays bf16 in the P.V product and the
- *                    softmax weights enter as a sum of two bf16 terms.
- *   FS_V_FP16_RANGE  every V value is 0 or has a magnitude in [2^-14, 65504], i.e. converts to
- *                    fp16 exactly.  The product then runs on fp16 weights and fp16 V (~20% faster).
- *                    A value that breaks the statement is not detected: a larger magnitude counts
- *                    as 65504, a smaller one is rounded toward zero on fp16's subnormal grid. */
+ *   FS_V_ANY         nothing: any finite value.  V stays bf16 in the P.V product (fp8: its codes,
+ *                    which are bf16 values, the slot's scale going to the weights) and the softmax
+ *                    weights enter as a sum of two bf16 terms.
+ *   FS_V_FP16_RANGE  every V value (fp8: code times the slot's scale) is 0 or has a magnitude in
+ *                    [2^-14, 65504], i.e. a bf16 value converts to fp16 exactly (an fp8 one is rounded
+ *                    toward zero to fp16's 11 bits).  The product then runs on fp16 weights and fp16 V
+ *                    (~20% faster).  A value that breaks the statement is not detected: a larger
+ *                    magnitude counts as 65504, a smaller one is rounded toward zero on fp16's
+ *                    subnormal grid. */
 enum { FS_V_ANY = 0, FS_V_FP16_RANGE = 1 };
 
 /* Shape of one decode batch. */
@@ -734,8 +737,11 @@ FS_API int32_t fs_prefill_tile_tokens(int32_t group);
  *
  * n_items == 0 is a no-op.  FS_EINVAL: NULL pointers, bad shape, G > 16,
  * tile_tokens out of range, misaligned pools, sm_scale not finite or <= 0 (the kernel's
- * lazy running maximum is taken on the raw scores), unknown v_range.  FS_EUNSUPPORTED: head_dim != 128,
- * page_tokens != 16, K/V not bf16.  FS_EHIP: launch failure. */
+ * lazy running maximum is taken on the raw scores), unknown v_range or kv_dtype, fp8 K/V without scales.
+ * FS_EUNSUPPORTED: head_dim != 128, page_tokens != 16.  FS_EHIP: launch failure.
+ * bf16 or fp8 K/V.  With fp8 the K scales must be positive (a quantisation scale is; the same lazy maximum
+ * is taken per page before the page's scale is applied), and scales are read by slot or, when
+ * kv->page_scales is given, in page-table order, as in the decode calls. */
 FS_API fs_status fs_prefill_attention(const fs_shape* shape, const fs_kv_view* kv,
                                       const fs_prefill_item* items_dev, const int32_t* sched_dev,
                                       int64_t n_items, int32_t tile_tokens, float* part_o, float* part_lse,

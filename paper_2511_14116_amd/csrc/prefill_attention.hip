@@ -25,7 +25,7 @@
 // product wants from P^T (4 tokens of the first page, the same 4 of the second); the copy into
 // LDS pairs the V rows of the two pages the same way, so nothing crosses lanes except the
 // running max.  This is a dense contraction (G*N rows against L+N keys): the matrix cores bound
-// it, not HBM.
+// it, not HBM.  fp8 K/V takes the same walk; only the copy into LDS differs (see prefill_tile).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -47,6 +47,9 @@ struct PrefillParams {
   const char* __restrict__ v_pool;
   int64_t k_stride;
   int64_t v_stride;
+  const float* __restrict__ k_scale;      // fp8: by slot, or (page_scales given) the (K, V) pairs in page-table order
+  const float* __restrict__ v_scale;      //      by slot, or page_scales + 1
+  int32_t scale_by_page;                  // 1: scale of page i of the table sits at k_scale[2i] / v_scale[2i]
   const int64_t* __restrict__ page_indptr;
   const int32_t* __restrict__ page_ids;
   const fs_prefill_item* __restrict__ items;
@@ -72,10 +75,17 @@ constexpr int kVbOffset = 12288;       // V rows d = 32c + 16 + lane%16: likewis
 
 // A wavefront's share of one page pair on its way from global memory to LDS: NP (K block, V block)
 // couples of 1 KiB, each couple from one page h and one 32-d block c.
-template <int NP>
+// fp8 K/V: the same couples are 512 bytes each (8 bytes per lane) and carry the page's V scale.
+template <int NP, bool FP8>
 struct InFlight {
   u32x4 k[NP];
   u32x4 v[NP];
+};
+template <int NP>
+struct InFlight<NP, true> {
+  uint2 k[NP];
+  uint2 v[NP];
+  float vs[NP];
 };
 
 // max of three / of two as IEEE-754 maximum (v_maximum3_f32): no NaN-quieting moves around it, unlike fmaxf,
@@ -116,10 +126,15 @@ constexpr float kLazy = 8.0f;   // the reference max follows the running max onl
 // way into LDS, exactly for magnitudes from 2^-14 to 65504; smaller ones land on fp16's subnormal grid,
 // larger ones enter as +-65504).  WIDE = true: V stays bf16 and the weights go in as bf16 hi + lo, two
 // products, for caches whose values leave fp16's range.
-template <bool WIDE>
+// TWO_SCALES (fp8 K): the scores of the second page take scale_b (softmax scale times that page's K scale, both
+// positive) and those of the first scale_log2 (likewise); else one scale for both.
+// With both WIDE and TWO_SCALES (fp8 V kept as its exact codes in bf16) the weights of the two pages are multiplied by
+// the pages' V scales vs_a, vs_b before they are split, and the row sum is taken on the vector units from the
+// unscaled weights, each lane its own 8 tokens (st.l[0] is then a partial sum: see the kernel's last step).
+template <bool WIDE, bool TWO_SCALES>
 __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const f32x4 sb, const u32x4 (&va)[4],
-                                           const u32x4 (&vb)[4], float scale_log2, int t0, int pos, int kb,
-                                           bool mask) {
+                                           const u32x4 (&vb)[4], float scale_log2, float scale_b, float vs_a, float vs_b,
+                                           int t0, int pos, int kb, bool mask) {
   // no fused multiply-add on the wide path: there a row's top key must get exp2(0) = 1 exactly, which needs
   // the scaled score rounded the same way on both sides of the subtraction
 #pragma clang fp contract(off)
@@ -139,8 +154,11 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
   // common path does not even form the row's max: every lane checks its own 8 scores (the softmax scale
   // is positive, so the max of the raw scores is the max of the scaled ones), and only if some lane of the
   // wavefront is out of range are the four lanes of each row combined.
-  const float mx_lane = max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max2(s[6], s[7]));
-  if (__any(mx_lane * scale_log2 > st.m + kLazy)) {
+  // (TWO_SCALES: the lane's maximum is formed on scaled scores, one product per page, and `post` is 1)
+  const float mx_lane = TWO_SCALES ? max2(max2(max3(s[0], s[1], s[2]), s[3]) * scale_log2, max2(max3(s[4], s[5], s[6]), s[7]) * scale_b)
+                                   : max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max2(s[6], s[7]));
+  const float post = TWO_SCALES ? 1.0f : scale_log2;
+  if (__any(mx_lane * post > st.m + kLazy)) {
     float mx = mx_lane;
     const unsigned u = __float_as_uint(mx);
     const auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
@@ -149,7 +167,7 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     const unsigned v = __float_as_uint(mx);
     const auto r32 = __builtin_amdgcn_permlane32_swap(v, v, false, false);
     const unsigned c = r32[0], d = r32[1];
-    mx = max2(__uint_as_float(c), __uint_as_float(d)) * scale_log2;
+    mx = max2(__uint_as_float(c), __uint_as_float(d)) * post;
     const bool move = mx > st.m + kLazy;
     const float alpha = move ? __builtin_amdgcn_exp2f(st.m - mx) : 1.0f;   // st.m = -inf: exp2(-inf) = 0
     FS_MATRIX_RESULT_WAIT();
@@ -173,7 +191,7 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     // One fused multiply-add per score: the top key's weight may miss 1 by an ulp of fp32, which the
     // rounding to fp16 below takes back, so a row's first key still weighs exactly 1.
 #pragma unroll
-    for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, st.neg_ref));
+    for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], (TWO_SCALES && r >= 4) ? scale_b : scale_log2, st.neg_ref));
     const f16x8 ph = __builtin_convertvector(p, f16x8);          // weights are below 2^8: no overflow
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -186,9 +204,14 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
     st.l = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones_bits), ph, st.l, 0, 0, 0);
   } else {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * scale_log2 - m_ref);   // product rounded first: the row's top key gets exactly 1
+    for (int r = 0; r < 8; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * ((TWO_SCALES && r >= 4) ? scale_b : scale_log2) - m_ref);   // product rounded first: the row's top key gets exactly 1
     // Weights as bf16 hi + lo (16 significant bits).  hi is p cut to its upper 16 bits (one byte
     // permute packs two of them), lo = p - hi is exact in fp32 and is rounded to bf16.
+    if constexpr (TWO_SCALES) {
+      st.l[0] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+#pragma unroll
+      for (int r = 0; r < 8; ++r) p[r] *= r < 4 ? vs_a : vs_b;
+    }
     u32x4 hi_packed;
     f32x8 lo;
 #pragma unroll
@@ -209,19 +232,22 @@ __device__ __forceinline__ void softmax_pv(TileState& st, const f32x4 sa, const 
       st.acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, pl, st.acc[2 * c + 1], 0, 0, 0);
     }
     // the row sums: a row of ones in place of V^T leaves sum_t p_t in every element of the result column
-    const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
-    st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, ph, st.l, 0, 0, 0);
-    st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pl, st.l, 0, 0, 0);
+    if constexpr (!TWO_SCALES) {
+      const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+      const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+      st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, ph, st.l, 0, 0, 0);
+      st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pl, st.l, 0, 0, 0);
+    }
   }
 }
 
 // One 4 KiB slot of a pool as a raw buffer resource (base in scalar registers).
+template <int BYTES = 4096>
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t slot_buffer(const char* base) {
   const uint64_t a = reinterpret_cast<uint64_t>(base);
   const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
   const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
-  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>((static_cast<uint64_t>(hi) << 32) | lo), 0, 4096,
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>((static_cast<uint64_t>(hi) << 32) | lo), 0, BYTES,
                                            0x00020000 /* raw 32-bit data format */);
 }
 
@@ -232,10 +258,25 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
   return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
+// Eight e4m3 bytes to eight bf16, exactly (the conversion takes a power-of-two scale; 1.0 is 2^0).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 fp8x8_to_bf16x8(uint2 w) {
+  const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, false), b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.x, 1.0f, true);
+  const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, false), d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w.y, 1.0f, true);
+  return u32x4{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, c), __builtin_bit_cast(uint32_t, d)};
+}
+
 // The 8-wavefront, one-column-tile shape is held to 128 registers so that two workgroups (four
 // wavefronts per SIMD) share a CU: the softmax is a long dependent chain and needs the company.
-template <int WAVES, int CT, bool WIDE>
-__global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAVES == 4 && CT == 2) ? 2 : (WAVES == 4 && CT == 1) ? 3 : 1) prefill_bf16_kernel(const PrefillParams P) {
+// FP8: e4m3 K/V (slots in 16-byte pieces per (token, 16 d), a scale per slot for K and for V).  Only the way into
+// LDS differs: a lane fetches 8 bytes of K and 8 of V where the bf16 kernel fetches 16 and 16 (the same 8 d of the same
+// token that its bf16 piece would hold), K is converted to bf16 (exact) and lands where the bf16 piece would; V must
+// arrive as (one d, four tokens) and is transposed by the matrix cores on the way: its bytes are the A operand of an
+// fp8 product with a constant matrix of ones and zeros, whose result - (token, d) in (d, four tokens) order - is
+// scaled, rounded to fp16 (bf16 when WIDE) and stored where the bf16 kernel stores its converted V.  The K scales
+// of the two pages join the softmax scale.
+template <int WAVES, int CT, bool WIDE, bool FP8>
+__device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
   constexpr int NP = 8 / WAVES;        // (K, V) block couples a wavefront moves per page pair
   static_assert(NP >= 1, "at most 8 wavefronts");
   __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
@@ -289,8 +330,16 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     for (int j = 0; j < 8; ++j) st[t].acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // fp8: where a page's scales sit (by slot, or in page-table order), read through the constant address space
+  typedef const float __attribute__((address_space(4))) * const_scale_ptr;
+  const int64_t table0 = FP8 ? P.page_indptr[it.pair] : 0;
+  auto scale_of = [&](const float* scales, int page, int64_t slot) __attribute__((always_inline)) -> float {
+    const int64_t si = P.scale_by_page ? 2 * (table0 + page) : slot;
+    return ((const_scale_ptr)(reinterpret_cast<uintptr_t>(scales)))[si];
+  };
+
   // ---- global -> registers: this wavefront's couples of pair jp ---------------------------------
-  auto fetch = [&](InFlight<NP>& r, int jp) __attribute__((always_inline)) {
+  auto fetch = [&](InFlight<NP, FP8>& r, int jp) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
@@ -301,29 +350,69 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
       // a slot as a raw buffer: its base stays in scalar registers, the lane's place in it is one 32-bit
       // offset (64-bit vector addresses cost this kernel registers it does not have)
       const int64_t slot = ids[page];
-      r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.k_pool + slot * P.k_stride), (c * 64 + lane) * 16, 0, 0);
-      r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.v_pool + slot * P.v_stride), (c * 64 + lane) * 16, 0, 0);
+      if constexpr (FP8) {
+        // the 8 bytes d = 32c + 8kb .. + 8 of token lane%16: half (kb & 1) of piece [c/2][2(c&1) + kb/2][tok];
+        // the wavefront's 64 lanes cover 512 contiguous bytes
+        const int off = (c >> 1) * 1024 + (c & 1) * 512 + (kb >> 1) * 256 + col * 16 + (kb & 1) * 8;
+        r.k[i] = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(slot_buffer<2048>(P.k_pool + slot * P.k_stride), off, 0, 0));
+        r.v[i] = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(slot_buffer<2048>(P.v_pool + slot * P.v_stride), off, 0, 0));
+        r.vs[i] = WIDE ? 1.0f : scale_of(P.v_scale, page, slot);
+      } else {
+        r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.k_pool + slot * P.k_stride), (c * 64 + lane) * 16, 0, 0);
+        r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.v_pool + slot * P.v_stride), (c * 64 + lane) * 16, 0, 0);
+      }
     }
   };
   // ---- registers -> LDS stage s ------------------------------------------------------------------
-  auto deposit = [&](int s, const InFlight<NP>& r, int jp) __attribute__((always_inline)) {
+  auto deposit = [&](int s, const InFlight<NP, FP8>& r, int jp) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
       unsigned char* base = stage[s];
-      *reinterpret_cast<u32x4*>(base + ((h * 4 + c) * 64 + lane) * 16) = r.k[i];
-      u32x4 v = r.v[i];
-      if constexpr (!WIDE) v = u32x4{bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w)};
       // value rows of tokens at or beyond the item's end may hold anything (the unused tail of a last
       // page is never initialised): blank them, 0 * NaN would be NaN in the product
       const int valid = it.kv_end - (page_begin + 2 * jp + h) * fs::kPageTokens;    // tokens of this page inside the item
-      if (valid < fs::kPageTokens) {          // same for the whole wavefront: only an item's last page
-        const uint32_t m0 = (4 * kb + 0 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid ? 0xFFFF0000u : 0u);
-        const uint32_t m1 = (4 * kb + 2 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid ? 0xFFFF0000u : 0u);
-        v = u32x4{v.x & m0, v.y & m1, v.z & m0, v.w & m1};
+      const bool blank = valid < fs::kPageTokens;          // same for the whole wavefront: only an item's last page
+      auto mask01 = [&]() __attribute__((always_inline)) {   // which of this lane's four tokens (4kb .. 4kb+3, two to a word) exist
+        return make_uint2((4 * kb + 0 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 1 < valid ? 0xFFFF0000u : 0u),
+                          (4 * kb + 2 < valid ? 0x0000FFFFu : 0u) | (4 * kb + 3 < valid ? 0xFFFF0000u : 0u));
+      };
+      if constexpr (FP8) {
+        *reinterpret_cast<u32x4*>(base + ((h * 4 + c) * 64 + lane) * 16) = fp8x8_to_bf16x8(r.k[i]);
+        // E[k][n] for the two halves of the 32-d block: column n = lane%16 takes k = 16h2 + n, which sits in the
+        // lanes with kb = 2h2 + n/8 as byte n%8 (0x38 is 1.0 in e4m3)
+        const long bytes = static_cast<long>((static_cast<unsigned long>(r.v[i].y) << 32) | r.v[i].x);
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          const long pick = (kb == 2 * h2 + (col >> 3)) ? static_cast<long>(0x38ul << (8 * (col & 7))) : 0l;
+          f32x4 t = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(bytes, pick, z, 0, 0, 0);
+          uint2 v;     // lane (d = 32c + 16h2 + lane%16): tokens 4kb .. 4kb+3 of page h
+          if constexpr (WIDE) {     // the codes as they are (every e4m3 value is a bf16 value); the scale goes to the weights
+            v = make_uint2(__builtin_amdgcn_perm(__float_as_uint(t[1]), __float_as_uint(t[0]), 0x07060302u),
+                           __builtin_amdgcn_perm(__float_as_uint(t[3]), __float_as_uint(t[2]), 0x07060302u));
+          } else {     // times the page's scale, rounded toward zero: a magnitude above 65504 becomes 65504, not infinity
+            t *= r.vs[i];
+            v = make_uint2(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(t[0], t[1])),
+                           __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(t[2], t[3])));
+          }
+          if (blank) {
+            const uint2 m = mask01();
+            v = make_uint2(v.x & m.x, v.y & m.y);
+          }
+          *reinterpret_cast<uint2*>(base + (h2 ? kVbOffset : kVaOffset) + (c * 64 + lane) * 16 + 8 * h) = v;
+        }
+      } else {
+        *reinterpret_cast<u32x4*>(base + ((h * 4 + c) * 64 + lane) * 16) = r.k[i];
+        u32x4 v = r.v[i];
+        if constexpr (!WIDE) v = u32x4{bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w)};
+        if (blank) {
+          const uint2 m = mask01();
+          v = u32x4{v.x & m.x, v.y & m.y, v.z & m.x, v.w & m.y};
+        }
+        *reinterpret_cast<uint2*>(base + kVaOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(v.x, v.y);
+        *reinterpret_cast<uint2*>(base + kVbOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(v.z, v.w);
       }
-      *reinterpret_cast<uint2*>(base + kVaOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(v.x, v.y);
-      *reinterpret_cast<uint2*>(base + kVbOffset + (c * 64 + lane) * 16 + 8 * h) = make_uint2(v.z, v.w);
     }
   };
   // ---- one page pair from LDS stage s against this wavefront's column tiles -----------------------
@@ -342,6 +431,16 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     }
     if (!any) return;
     const unsigned char* base = stage[s];
+    float scale_a = P.scale_log2, scale_b = P.scale_log2, vs_a = 1.0f, vs_b = 1.0f;
+    if constexpr (FP8) {     // the two pages' K scales join the softmax scale (asked for now, used after the first product)
+      const int pa = min(page_begin + 2 * jp, page_end - 1), pb = min(page_begin + 2 * jp + 1, page_end - 1);
+      scale_a *= scale_of(P.k_scale, pa, ids[pa]);
+      scale_b *= scale_of(P.k_scale, pb, ids[pb]);
+      if constexpr (WIDE) {
+        vs_a = scale_of(P.v_scale, pa, ids[pa]);
+        vs_b = scale_of(P.v_scale, pb, ids[pb]);
+      }
+    }
     f32x4 sa[CT], sb[CT];
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     {
@@ -372,7 +471,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     }
 #pragma unroll
     for (int t = 0; t < CT; ++t) {
-      if (need[t]) softmax_pv<WIDE>(st[t], sa[t], sb[t], va, vb, P.scale_log2, t0, pos[t], kb, !full[t]);
+      if (need[t]) softmax_pv<WIDE, FP8>(st[t], sa[t], sb[t], va, vb, scale_a, scale_b, vs_a, vs_b, t0, pos[t], kb, !full[t]);
     }
   };
 
@@ -381,7 +480,7 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
   // complete and nobody reads stage j%2 any more.  Every wavefront takes every branch below (n_it is the
   // workgroup's), so the barriers match.
   if (n_it < 1) return;        // not produced by the list builder (an item sees at least one key)
-  InFlight<NP> r0, r1;
+  InFlight<NP, FP8> r0, r1;
   fetch(r0, 0);
   fetch(r1, 1);
   deposit(0, r0, 0);
@@ -415,7 +514,17 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
 #pragma unroll
   for (int t = 0; t < CT; ++t) {
     const int tok = tok0 + t * tpc + tl_w;
-    const float l_tot = st[t].l[0];
+    float l_tot = st[t].l[0];
+    if constexpr (WIDE && FP8) {      // partial sums of the four lanes that share the row (softmax_pv)
+      const unsigned u = __float_as_uint(l_tot);
+      const auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+      const unsigned a16 = r16[0], b16 = r16[1];
+      l_tot = __uint_as_float(a16) + __uint_as_float(b16);
+      const unsigned v = __float_as_uint(l_tot);
+      const auto r32 = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+      const unsigned a32 = r32[0], b32 = r32[1];
+      l_tot = __uint_as_float(a32) + __uint_as_float(b32);
+    }
     if (g_w >= G || tok >= P.tile_tokens) continue;          // no such row in the buffers
     const int64_t row = row0 + static_cast<int64_t>(tok) * G + g_w;
     float* o = dst_o + row * fs::kHeadDim + 4 * kb_w;
@@ -431,6 +540,17 @@ __global__ void __launch_bounds__(WAVES * 64, (WAVES == 8 && CT == 1) ? 4 : (WAV
     }
   }
 }
+
+#define FS_PREFILL_BOUNDS(W, C) __launch_bounds__(W * 64, (W == 8 && C == 1) ? 4 : (W == 4 && C == 2) ? 2 : (W == 4 && C == 1) ? 3 : 1)
+template <int WAVES, int CT, bool WIDE>
+__global__ void FS_PREFILL_BOUNDS(WAVES, CT) prefill_bf16_kernel(const PrefillParams P) {
+  prefill_tile<WAVES, CT, WIDE, false>(P);
+}
+template <int WAVES, int CT, bool WIDE>
+__global__ void FS_PREFILL_BOUNDS(WAVES, CT) prefill_fp8_kernel(const PrefillParams P) {
+  prefill_tile<WAVES, CT, WIDE, true>(P);
+}
+#undef FS_PREFILL_BOUNDS
 
 template <typename K>
 fs_status launch(K kernel, int threads, const PrefillParams& P, int64_t n_items, hipStream_t stream) {
@@ -471,8 +591,9 @@ fs_status prefill_launch(const char* who, const fs_shape* shape, const fs_kv_vie
                     fs::kPageTokens);
   const int G = shape->n_q_heads / shape->n_kv_heads;
   if (G > fs::kMaxGroup) return fs::fail(FS_EINVAL, "%s: group %d > %d", who, G, fs::kMaxGroup);
-  if (kv->kv_dtype != FS_KV_BF16)
-    return fs::fail(FS_EUNSUPPORTED, "%s: only bf16 K/V is built (kv_dtype %d)", who, kv->kv_dtype);
+  if (kv->kv_dtype != FS_KV_BF16 && kv->kv_dtype != FS_KV_FP8_E4M3)
+    return fs::fail(FS_EINVAL, "%s: unknown kv_dtype %d", who, kv->kv_dtype);
+  const bool fp8 = kv->kv_dtype == FS_KV_FP8_E4M3;
   if (n_items < 0 || n_items > 0x7FFFFFFF) return fs::fail(FS_EINVAL, "%s: n_items out of range", who);
   const int ct = fs::options().prefill_col_tiles, waves = fs::options().prefill_waves;
   const int cap = waves * ct * (16 / pad_group(G));
@@ -482,7 +603,9 @@ fs_status prefill_launch(const char* who, const fs_shape* shape, const fs_kv_vie
   if (!kv->q || !kv->k_pool || !kv->v_pool || !kv->page_indptr || !kv->page_ids || !items_dev ||
       (partials_needed && (!part_o || !part_lse)))
     return fs::fail(FS_EINVAL, "%s: NULL device pointer", who);
-  const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * 2;
+  if (fp8 && !kv->page_scales && (!kv->k_scale || !kv->v_scale))
+    return fs::fail(FS_EINVAL, "%s: fp8 KV needs page_scales, or k_scale and v_scale", who);
+  const int64_t slot_bytes = static_cast<int64_t>(fs::kPageTokens) * fs::kHeadDim * (fp8 ? 1 : 2);
   if (kv->k_slot_stride < slot_bytes || kv->v_slot_stride < slot_bytes || (kv->k_slot_stride & 15) ||
       (kv->v_slot_stride & 15) || (reinterpret_cast<uintptr_t>(kv->k_pool) & 15) ||
       (reinterpret_cast<uintptr_t>(kv->v_pool) & 15) || (reinterpret_cast<uintptr_t>(kv->q) & 15) ||
@@ -502,6 +625,9 @@ fs_status prefill_launch(const char* who, const fs_shape* shape, const fs_kv_vie
   P.v_pool = static_cast<const char*>(kv->v_pool);
   P.k_stride = kv->k_slot_stride;
   P.v_stride = kv->v_slot_stride;
+  P.k_scale = kv->page_scales ? kv->page_scales : kv->k_scale;
+  P.v_scale = kv->page_scales ? kv->page_scales + 1 : kv->v_scale;
+  P.scale_by_page = kv->page_scales ? 1 : 0;
   P.page_indptr = kv->page_indptr;
   P.page_ids = kv->page_ids;
   P.items = items_dev;
@@ -520,6 +646,9 @@ fs_status prefill_launch(const char* who, const fs_shape* shape, const fs_kv_vie
   const bool wide = kv->v_range != FS_V_FP16_RANGE;   // no statement about V: keep it in bf16
 #define FS_PREFILL_CASE(W, C)                                                                     \
   case W * 10 + C:                                                                                \
+    if (fp8)                                                                                      \
+      return wide ? launch(prefill_fp8_kernel<W, C, true>, W * 64, P, n_items, s)                 \
+                  : launch(prefill_fp8_kernel<W, C, false>, W * 64, P, n_items, s);               \
     return wide ? launch(prefill_bf16_kernel<W, C, true>, W * 64, P, n_items, s)                  \
                 : launch(prefill_bf16_kernel<W, C, false>, W * 64, P, n_items, s)
   switch (waves * 10 + ct) {

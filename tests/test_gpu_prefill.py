@@ -53,7 +53,7 @@ def check(out, lse, ref_o, ref_l, what):
 
 
 def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched=True, interleave=True, chunk=0,
-              kv_edit=None, v_range=fs.FS_V_FP16_RANGE):
+              kv_edit=None, v_range=fs.FS_V_FP16_RANGE, kv_dtype="bf16", scales_by_page=True):
     """``v_range``: what the call is told about V.  The generator draws N(0,1) values, which convert to fp16
     exactly, so the statement FS_V_FP16_RANGE is true unless ``kv_edit`` plants something else."""
     n_done = np.asarray(n_done, dtype=np.int32); n_new = np.asarray(n_new, dtype=np.int32)
@@ -67,12 +67,12 @@ def run_share(seed, n_done, n_new, Hq, Hkv, owner, rank, R, tile=None, use_sched
     assert sched.tobytes() == w_sched.tobytes() and out_indptr.tobytes() == w_indptr.tobytes()
     assert chunk_indptr.tobytes() == w_chunks.tobytes()
     ctx = (n_done + n_new).astype(np.int32)
-    kv = make_kv_pool(seed, w_pairs[:, :2], ctx)
+    kv = make_kv_pool(seed, w_pairs[:, :2], ctx, kv_dtype=kv_dtype)
     if kv_edit is not None:
         kv_edit(kv)
     q_indptr = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
     q = make_prefill_q(seed, int(q_indptr[-1]), Hq, 128)
-    ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave, v_range=v_range)
+    ds = DeviceShare(sh, q, kv, SCALE, interleave_kv=interleave, v_range=v_range, scales_by_page=scales_by_page)
     ds.set_prefill_worklist(items, sched, chunk_indptr, tile, out_indptr)
     ds.prefill(use_sched=use_sched)
     torch.cuda.synchronize()
@@ -116,17 +116,57 @@ def compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, out_indptr):
     check(out[valid], lse[valid], ref_o[valid], ref_l[valid], what)
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (12, 4), (32, 8), (64, 8), (32, 2), (10, 2)])
-def test_group_sizes_ragged_chunks(Hq, Hkv):
-    say(f"group sizes Hq={Hq} Hkv={Hkv}")
+def test_group_sizes_ragged_chunks(Hq, Hkv, kv_dtype):
+    say(f"group sizes Hq={Hq} Hkv={Hkv} {kv_dtype}")
     rng = np.random.default_rng(Hq * 100 + Hkv)
     n_done = [0, 37, 160, 0, 511, 16]
     n_new = [45, 1, 70, 0, 33, 129]
     owner = rng.integers(0, 2, size=(6, Hkv)).astype(np.int32)
     for rank in range(2):
+        # fp8: rank 0 with V stated to fit fp16, rank 1 without a statement (V in bf16, weights as hi + lo)
+        v_range = fs.FS_V_ANY if (kv_dtype == "fp8" and rank == 1) else fs.FS_V_FP16_RANGE
         ds, kv, q, q_indptr, pairs, oi = run_share(40 + Hq + Hkv, n_done, n_new, Hq, Hkv, owner, rank, 2,
-                                                   chunk=(0, 64)[rank])
-        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"Hq={Hq} Hkv={Hkv} rank {rank}", oi)
+                                                   chunk=(0, 64)[rank], kv_dtype=kv_dtype, v_range=v_range)
+        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, f"Hq={Hq} Hkv={Hkv} {kv_dtype} rank {rank}", oi)
+
+
+@pytest.mark.parametrize("v_range", [fs.FS_V_FP16_RANGE, fs.FS_V_ANY])
+def test_fp8_cache_with_every_byte_pattern(v_range):
+    """An fp8 cache that holds all 254 non-NaN e4m3 patterns in K and V under every lane and byte position of the
+    kernel's loads (K converted to bf16 by an instruction that takes a scale, V's bytes through an fp8 product with
+    the selection matrix), scales by slot and in page-table order, split-K and not."""
+    Hq, Hkv = 8, 2
+    n_done = [0, 100, 509, 16]
+    n_new = [33, 17, 70, 254]
+    owner = np.zeros((4, Hkv), dtype=np.int32)
+    patterns = np.array([b for b in range(256) if b & 0x7F != 0x7F], dtype=np.uint8)
+
+    def every_pattern(kv):
+        rng = np.random.default_rng(6)
+        for pool, scale, sc in ((kv["k_pool"], kv["k_scale"], 1.0 / 2048), (kv["v_pool"], kv["v_scale"], 1.0 / 64)):
+            live = pool != np.uint8(0x7F)
+            n_slots, T, D = pool.shape
+            idx = (7 * np.arange(n_slots)[:, None, None] + 3 * np.arange(T)[None, :, None] + np.arange(D)[None, None, :]) % 254
+            vals = patterns[idx]
+            for sl in range(0, n_slots, 4):
+                vals[sl] = patterns[rng.integers(0, 254, size=(T, D))]
+            pool[live] = vals[live]
+            ok = ~np.isnan(scale)
+            scale[ok] = (np.float32(sc) * (1.0 + 0.5 * rng.random(int(ok.sum())))).astype(np.float32)   # a scale of its own per slot
+    for chunk in (0, 64):
+        what = f"prefill, fp8 cache with every byte pattern, v_range {v_range}, chunk {chunk}"
+        say(what)
+        ds, kv, q, q_indptr, pairs, oi = run_share(77, n_done, n_new, Hq, Hkv, owner, 0, 1, chunk=chunk, kv_dtype="fp8",
+                                                   kv_edit=every_pattern, v_range=v_range)
+        assert set(np.unique(kv["v_pool"])) >= set(patterns.tolist()) and set(np.unique(kv["k_pool"])) >= set(patterns.tolist())
+        compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, what, oi)
+        # the scales gathered by slot instead of read in page-table order: the same numbers, the same bits
+        ds2, *_ = run_share(77, n_done, n_new, Hq, Hkv, owner, 0, 1, chunk=chunk, kv_dtype="fp8", kv_edit=every_pattern,
+                            v_range=v_range, scales_by_page=False)
+        assert ds.page_scales is not None and ds2.page_scales is None
+        assert torch.equal(ds.prefill_out, ds2.prefill_out) and torch.equal(ds.prefill_lse, ds2.prefill_lse)
 
 
 @pytest.mark.parametrize("waves,ct", [(4, 1), (4, 2), (4, 4), (8, 1), (8, 2)])

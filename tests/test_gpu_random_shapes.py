@@ -43,6 +43,7 @@ def _defaults():
 @pytest.mark.parametrize("seed", range(4))
 def test_prefill_on_drawn_shapes(seed):
     rng = np.random.default_rng(8100 + seed)
+    rng_kv = np.random.default_rng(8150 + seed)      # the cache's type: a stream of its own, so the cases stay as drawn
     for case in range(25):
         Hkv = int(rng.choice([1, 2, 4, 8])); G = int(rng.choice([1, 2, 3, 4, 5, 8, 16])); Hq = Hkv * G
         R = int(rng.integers(1, 4)); B = int(rng.integers(1, 6))
@@ -54,12 +55,13 @@ def test_prefill_on_drawn_shapes(seed):
         chunk = int(rng.choice([0, 32, 64, 256, 1024]))
         tile = int(rng.integers(1, fs.fs_prefill_tile_tokens(G) + 1)) if rng.random() < 0.3 else None
         wide = int(rng.random() < 0.25)
-        what = f"prefill seed {seed} case {case}: Hkv={Hkv} G={G} R={R} n_done={n_done.tolist()} n_new={n_new.tolist()} chunk={chunk} tile={tile} wide={wide}"
+        kv_dtype = "fp8" if rng_kv.random() < 0.4 else "bf16"
+        what = f"prefill seed {seed} case {case}: {kv_dtype} Hkv={Hkv} G={G} R={R} n_done={n_done.tolist()} n_new={n_new.tolist()} chunk={chunk} tile={tile} wide={wide}"
         TP.say(what)
         ds, kv, q, q_indptr, pairs, oi = TP.run_share(9000 + 100 * seed + case, n_done, n_new, Hq, Hkv, owner,
                                                       int(rng.integers(0, R)), R, tile=tile, chunk=chunk,
                                                       use_sched=bool(rng.random() < 0.8), interleave=bool(rng.random() < 0.7),
-                                                      v_range=fs.FS_V_ANY if wide else fs.FS_V_FP16_RANGE)
+                                                      v_range=fs.FS_V_ANY if wide else fs.FS_V_FP16_RANGE, kv_dtype=kv_dtype)
         if len(pairs):
             TP.compare_all(ds, kv, q, q_indptr, pairs, Hq, G, what, oi)
 
