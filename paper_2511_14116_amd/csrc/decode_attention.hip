@@ -681,14 +681,16 @@ __device__ __forceinline__ void sweep_one_item(const DecodeParams& P) {
   arrive_and_merge_one<WAVES>(P, d, s_meta, G, wave, lane);
 }
 
+// (at least two wavefronts per SIMD, for both formats: within 256 registers the compiler keeps the matrix results
+// in ordinary registers; allowed 512 it parks them in accumulation registers and moves every one back before the
+// vector units can touch it - with fp8 pages 57 extra instructions per page; with bf16 pages the launch is bound by
+// memory and the long lists do not notice, the short ones start faster)
 template <int WAVES, int NBUF>
-__global__ void __launch_bounds__(WAVES * 64) decode_bf16_kernel(const DecodeParams P) {
+__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+decode_bf16_kernel(const DecodeParams P) {
   sweep_one_item<WAVES, NBUF, Bf16Format>(P);
 }
 
-// (at least two wavefronts per SIMD: within 256 registers the compiler keeps the matrix results in ordinary
-// registers; allowed 512 it parks them in accumulation registers and moves every one back before the vector units
-// can touch it, 57 extra instructions per page)
 template <int WAVES, int NBUF>
 __global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 decode_fp8_kernel(const DecodeParams P) {
