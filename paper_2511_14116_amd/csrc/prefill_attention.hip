@@ -333,9 +333,12 @@ __device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
   // fp8: where a page's scales sit (by slot, or in page-table order), read through the constant address space
   typedef const float __attribute__((address_space(4))) * const_scale_ptr;
   const int64_t table0 = FP8 ? P.page_indptr[it.pair] : 0;
-  auto scale_of = [&](const float* scales, int page, int64_t slot) __attribute__((always_inline)) -> float {
-    const int64_t si = P.scale_by_page ? 2 * (table0 + page) : slot;
-    return ((const_scale_ptr)(reinterpret_cast<uintptr_t>(scales)))[si];
+  // (two real branches: as a select, the page-table order would pay for the slot number's read as well)
+  auto scale_of = [&](const float* scales, int page) __attribute__((always_inline)) -> float {
+    const const_scale_ptr sc = (const_scale_ptr)(reinterpret_cast<uintptr_t>(scales));
+    if (P.scale_by_page) return sc[2 * (table0 + page)];
+    asm volatile("");
+    return sc[ids[page]];
   };
 
   // ---- global -> registers: this wavefront's couples of pair jp ---------------------------------
@@ -356,7 +359,7 @@ __device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
         const int off = (c >> 1) * 1024 + (c & 1) * 512 + (kb >> 1) * 256 + col * 16 + (kb & 1) * 8;
         r.k[i] = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(slot_buffer<2048>(P.k_pool + slot * P.k_stride), off, 0, 0));
         r.v[i] = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(slot_buffer<2048>(P.v_pool + slot * P.v_stride), off, 0, 0));
-        r.vs[i] = WIDE ? 1.0f : scale_of(P.v_scale, page, slot);
+        r.vs[i] = WIDE ? 1.0f : scale_of(P.v_scale, page);
       } else {
         r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.k_pool + slot * P.k_stride), (c * 64 + lane) * 16, 0, 0);
         r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(slot_buffer(P.v_pool + slot * P.v_stride), (c * 64 + lane) * 16, 0, 0);
@@ -397,6 +400,7 @@ __device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
                            __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(t[2], t[3])));
           }
           if (blank) {
+            asm volatile("");      // a real branch: as selects the masks cost every step 16 instructions
             const uint2 m = mask01();
             v = make_uint2(v.x & m.x, v.y & m.y);
           }
@@ -434,11 +438,11 @@ __device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
     float scale_a = P.scale_log2, scale_b = P.scale_log2, vs_a = 1.0f, vs_b = 1.0f;
     if constexpr (FP8) {     // the two pages' K scales join the softmax scale (asked for now, used after the first product)
       const int pa = min(page_begin + 2 * jp, page_end - 1), pb = min(page_begin + 2 * jp + 1, page_end - 1);
-      scale_a *= scale_of(P.k_scale, pa, ids[pa]);
-      scale_b *= scale_of(P.k_scale, pb, ids[pb]);
+      scale_a *= scale_of(P.k_scale, pa);
+      scale_b *= scale_of(P.k_scale, pb);
       if constexpr (WIDE) {
-        vs_a = scale_of(P.v_scale, pa, ids[pa]);
-        vs_b = scale_of(P.v_scale, pb, ids[pb]);
+        vs_a = scale_of(P.v_scale, pa);
+        vs_b = scale_of(P.v_scale, pb);
       }
     }
     f32x4 sa[CT], sb[CT];
