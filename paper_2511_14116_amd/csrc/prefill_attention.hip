@@ -342,7 +342,21 @@ __device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
   };
 
   // ---- global -> registers: this wavefront's couples of pair jp ---------------------------------
-  auto fetch = [&](InFlight<NP, FP8>& r, int jp) __attribute__((always_inline)) {
+  // fp8: the scales of the pair that is computed next (pair jc) are read here too, next to the page ids that this step
+  // waits for anyway: read where they are used, their wait would fall between the LDS reads of the walk.
+  float ks_a = 1.0f, ks_b = 1.0f, vs_a = 1.0f, vs_b = 1.0f;
+  auto fetch = [&](InFlight<NP, FP8>& r, int jp, int jc) __attribute__((always_inline)) {
+    if constexpr (FP8) {
+      if (jc >= 0) {
+        const int pa = min(page_begin + 2 * jc, page_end - 1), pb = min(page_begin + 2 * jc + 1, page_end - 1);
+        ks_a = scale_of(P.k_scale, pa);
+        ks_b = scale_of(P.k_scale, pb);
+        if constexpr (WIDE) {
+          vs_a = scale_of(P.v_scale, pa);
+          vs_b = scale_of(P.v_scale, pb);
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int idx = wave * NP + i, h = idx >> 2, c = idx & 3;
@@ -435,16 +449,7 @@ __device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
     }
     if (!any) return;
     const unsigned char* base = stage[s];
-    float scale_a = P.scale_log2, scale_b = P.scale_log2, vs_a = 1.0f, vs_b = 1.0f;
-    if constexpr (FP8) {     // the two pages' K scales join the softmax scale (asked for now, used after the first product)
-      const int pa = min(page_begin + 2 * jp, page_end - 1), pb = min(page_begin + 2 * jp + 1, page_end - 1);
-      scale_a *= scale_of(P.k_scale, pa);
-      scale_b *= scale_of(P.k_scale, pb);
-      if constexpr (WIDE) {
-        vs_a = scale_of(P.v_scale, pa);
-        vs_b = scale_of(P.v_scale, pb);
-      }
-    }
+    const float scale_a = P.scale_log2 * ks_a, scale_b = P.scale_log2 * ks_b;     // fp8: the two pages' K scales join the softmax scale
     f32x4 sa[CT], sb[CT];
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     {
@@ -485,21 +490,21 @@ __device__ __forceinline__ void prefill_tile(const PrefillParams& P) {
   // workgroup's), so the barriers match.
   if (n_it < 1) return;        // not produced by the list builder (an item sees at least one key)
   InFlight<NP, FP8> r0, r1;
-  fetch(r0, 0);
-  fetch(r1, 1);
+  fetch(r0, 0, -1);
+  fetch(r1, 1, -1);
   deposit(0, r0, 0);
-  fetch(r0, 2);
+  fetch(r0, 2, -1);
   __syncthreads();
   for (int j = 0; j < n_it; j += 2) {
     // Copies and fetches run for pairs beyond the item's end too (into a stage nobody reads, from the last
     // page again): one shape of loop body, so every wait for a copy's data leaves exactly the two younger
     // loads in flight.
     deposit(1, r1, j + 1);
-    fetch(r1, j + 3);
+    fetch(r1, j + 3, j);
     compute(0, j);
     __syncthreads();
     deposit(0, r0, j + 2);
-    fetch(r0, j + 4);
+    fetch(r0, j + 4, j + 1);
     if (j + 1 < n_it) compute(1, j + 1);
     __syncthreads();
   }
