@@ -388,7 +388,7 @@ typedef struct {
   float sm_scale;              /* softmax scale, 1/sqrt(head_dim) in the paper's models */
   const float* page_scales;    /* DEVICE [page_indptr[n_pairs]][2] or NULL: fp8 only, the same scales in
                                   page-table order, entry j = (K scale, V scale) of slot page_ids[j].  When
-                                  given, the decode kernels read these (a contiguous run along an item,
+                                  given, the kernels read these (a contiguous run along an item,
                                   0.2% of the K/V bytes) and k_scale/v_scale may be NULL; the by-slot
                                   arrays cost one memory line per slot and scale, ~4% of the bytes.      */
   int32_t v_range;             /* FS_V_ANY (0) or FS_V_FP16_RANGE: see the enum                           */
