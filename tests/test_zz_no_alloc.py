@@ -88,3 +88,28 @@ def test_static_scratch_entry_point_two_calls_in_a_row():
                                             big.chunk_indptr, 5, big.out, big.lse, torch.cuda.current_stream().cuda_stream)
     assert e.value.status == fs.FS_ECAPACITY and "32768" in str(e.value)
     torch.cuda.synchronize()
+
+
+def test_static_scratch_entry_point_with_an_fp8_cache():
+    """The same entry point over fp8 K/V (one workgroup per item; the partial rows of split pairs in the library's
+    array): two calls in a row, the second smaller, the bits of fs_decode_attention_fused, and the oracle's values."""
+    fs.load_library()
+    w1, q1, kv1, pairs1, big = _share(4, n_req=120, max_len=2048, chunk=256)
+    w2, q2, kv2, pairs2, small = _share(4, n_req=30, max_len=700, chunk=128, rank=2)
+    assert w1["kv_dtype"] == "fp8" and big.n_items > big.n_pairs and small.n_pairs < small.n_items < big.n_items
+    say(f"fp8: first list {big.n_items} items / {big.n_pairs} pairs, second {small.n_items} items / {small.n_pairs} pairs")
+    want = []
+    for ds in (big, small):
+        ds.run_fused(persistent=True)
+        torch.cuda.synchronize()
+        want.append((ds.out.clone(), ds.lse.clone()))
+        ds.out.fill_(float("nan")); ds.lse.fill_(float("nan"))
+    _static(big)
+    _static(small)
+    torch.cuda.synchronize()
+    for name, ds, (o, l) in (("first", big, want[0]), ("second", small, want[1])):
+        assert torch.equal(ds.out, o) and torch.equal(ds.lse, l), f"{name} call differs from fs_decode_attention_fused"
+    pr = pairs2.view(np.int32).reshape(-1, 4)
+    ref_o, ref_l = oracle.decode_attention_pairs(q2, kv2, pr, w2["n_q_heads"], w2["group"], w2["sm_scale"], workers=8)
+    out = small.out.cpu().numpy().astype(np.float64); lse = small.lse.cpu().numpy().astype(np.float64)
+    assert (np.abs(out - ref_o) <= 2e-3 + 1e-2 * np.abs(ref_o)).all() and (np.abs(lse - ref_l) <= 1e-3).all()
