@@ -184,6 +184,10 @@ def test_launch_shapes(waves, ct):
         # a tile smaller than the kernel's natural one
         ds, kv, q, q_indptr, pairs, oi = run_share(8, n_done, n_new, 16, 2, owner, 0, 1, tile=3, chunk=96)
         compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct} tile=3", oi)
+        # the same shape over an fp8 cache, with and without a statement about V
+        for v_range in (fs.FS_V_FP16_RANGE, fs.FS_V_ANY):
+            ds, kv, q, q_indptr, pairs, oi = run_share(9, n_done, n_new, 16, 2, owner, 0, 1, chunk=256, kv_dtype="fp8", v_range=v_range)
+            compare_all(ds, kv, q, q_indptr, pairs, 16, 8, f"waves={waves} ct={ct} fp8 v_range={v_range}", oi)
     finally:
         fs.fs_set_option("prefill_waves", DEFAULT_WAVES)
         fs.fs_set_option("prefill_col_tiles", DEFAULT_CT)
@@ -328,20 +332,21 @@ def test_hip_graph_replays_match_eager():
     compare_all(ds, kv, q, q_indptr, pairs, Hq, Hq // Hkv, "graph replay vs oracle", oi)
 
 
-@pytest.mark.parametrize("waves,ct,wide", [(8, 1, 0), (4, 2, 0), (8, 1, 1)])
-def test_repeated_launches_agree_bit_for_bit(waves, ct, wide):
+@pytest.mark.parametrize("waves,ct,wide,kv_dtype", [(8, 1, 0, "bf16"), (4, 2, 0, "bf16"), (8, 1, 1, "bf16"), (8, 1, 0, "fp8"),
+                                                   (8, 1, 1, "fp8"), (4, 1, 0, "fp8")])
+def test_repeated_launches_agree_bit_for_bit(waves, ct, wide, kv_dtype):
     """Launches on the same inputs must leave the same bits in every launch shape (fixed order of sums, no
     atomics on data): a difference means a race between the workgroup's stages, or a matrix-core result read
     before the instruction that writes it has finished (the running reference maximum then comes out of
     whatever the registers held, which moves the rounding of a whole row)."""
-    say(f"prefill: repeated launches, waves={waves} ct={ct} wide={wide}")
+    say(f"prefill: repeated launches, waves={waves} ct={ct} wide={wide} {kv_dtype}")
     fs.fs_set_option("prefill_waves", waves); fs.fs_set_option("prefill_col_tiles", ct)
     try:
         rng = np.random.default_rng(92)
         Hq, Hkv, R = 64, 8, 2
         n_done, n_new = [0, 300, 2100, 16], [260, 70, 130, 900]
         owner = rng.integers(0, R, size=(4, Hkv)).astype(np.int32)
-        ds, kv, q, q_indptr, pairs, oi = run_share(78, n_done, n_new, Hq, Hkv, owner, 0, R, chunk=512,
+        ds, kv, q, q_indptr, pairs, oi = run_share(78, n_done, n_new, Hq, Hkv, owner, 0, R, chunk=512, kv_dtype=kv_dtype,
                                                    v_range=fs.FS_V_ANY if wide else fs.FS_V_FP16_RANGE)
         first = [t.clone() for t in (ds.prefill_part_o, ds.prefill_part_lse, ds.prefill_out, ds.prefill_lse)]
         for rep in range(5):
@@ -422,19 +427,20 @@ def test_empty_share_and_bad_arguments():
         fs.fs_prefill_attention(sh, kvv, dummy, None, 1, 4, dummy, dummy)
 
 
-def test_bench_batch_full_size_sampled():
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_bench_batch_full_size_sampled(kv_dtype):
     """The batch `bench.py --path prefill` times, in its launch configuration: sampled (pair, token)
     rows against the oracle, one by one, plus finiteness of every row."""
-    say("bench batch, sampled rows")
+    say(f"bench batch, sampled rows, {kv_dtype}")
     import bench_prefill
     w = bench_prefill.prefill_workload(fs)
     shape, G, pairs, items = w["shape"], w["G"], w["pairs"], w["items"]
     assert w["tile"] == fs.fs_prefill_tile_tokens(G) and w["kv_chunk"] == 2272      # what the chunk choice gives on this batch (ceil(4 * 863803 / (3 * 512)) = 2250 -> 2272)
     ctx = (w["n_done"] + w["n_new"]).astype(np.int32)
-    kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx)
+    kv = make_kv_pool(w["seed"], np.stack([pairs["req"], pairs["kv_head"]], axis=1), ctx, kv_dtype=kv_dtype)
     q_indptr = np.concatenate([[0], np.cumsum(w["n_new"])]).astype(np.int64)
     q = make_prefill_q(w["seed"], int(q_indptr[-1]), shape.n_q_heads, 128)
-    ds = DeviceShare(shape, q, kv, SCALE)
+    ds = DeviceShare(shape, q, kv, SCALE, v_range=fs.FS_V_FP16_RANGE)
     ds.set_prefill_worklist(items, w["sched"], w["chunk_indptr"], w["tile"], w["out_indptr"])
     ds.prefill()
     torch.cuda.synchronize()
@@ -452,4 +458,4 @@ def test_bench_batch_full_size_sampled():
         row = int(w["out_indptr"][p]) + tok * G
         got_o.append(out[row:row + G]); got_l.append(lse[row:row + G]); ref_o.append(o); ref_l.append(l)
     check(np.concatenate(got_o), np.concatenate(got_l), np.concatenate(ref_o), np.concatenate(ref_l),
-          f"bench batch, {len(samples)} sampled rows")
+          f"bench batch ({kv_dtype}), {len(samples)} sampled rows")
