@@ -30,7 +30,8 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # profiles/).  A figure belongs to one kernel on one list: the key is (config, rank, seed, chunk, placement,
 # kernel); any other run reports null.
 MEASURED_TRAFFIC_BYTES = {
-    (2, 0, 20251116, "512 units", "requests", "decode_bf16_persistent_kernel"): 1965833753,   # profiles/decode_bf16_units_kernel_cfg2_70b_rank0.txt
+    (2, 0, 20251116, 6640, "requests", "decode_bf16_kernel"): 1966163026,                     # profiles/decode_bf16_kernel_cfg2_70b_builders_chunk_rank0.txt
+    (2, 0, 20251116, "512 units", "requests", "decode_bf16_persistent_kernel"): 1965813823,   # profiles/decode_bf16_units_kernel_cfg2_70b_rank0.txt (--units 0)
     (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971407938,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
     (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1971832723,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt
     (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408070099,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt
@@ -38,7 +39,8 @@ MEASURED_TRAFFIC_BYTES = {
     (3, 0, 20251117, 688, "requests", "decode_bf16_kernel"): 69331506,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
     (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3261385,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
     (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561926562,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
-    (2, 0, 20251116, 2048, "requests", "decode_fp8_kernel"): 1007783948,                      # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_rank0.txt (--kv-dtype fp8)
+    (2, 0, 20251116, 2048, "requests", "decode_fp8_kernel"): 1007783948,                      # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_rank0.txt (--kv-dtype fp8 --chunked)
+    (2, 0, 20251116, 6640, "requests", "decode_fp8_kernel"): 992023381,                       # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_builders_chunk_rank0.txt (--kv-dtype fp8)
 }
 KERNEL_LAUNCHES = 30       # launches of the attention kernel timed one by one for the roofline figure
 
@@ -71,9 +73,10 @@ def main() -> int:
                          "partial rows leave in bursts) even for short lists; by default it is used from 1024 items on")
     ap.add_argument("--units", type=int, default=None, metavar="N",
                     help="cut the share into N equal runs of pages (0 = two per compute unit) and sweep them with one "
-                         "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units).  Default: that form, "
-                         "two runs per compute unit, once a run would hold 256 pages or more; else the chunked list")
-    ap.add_argument("--chunked", action="store_true", help="the chunked list (fs_build_worklist) whatever the share's size")
+                         "resident workgroup each (fs_build_worklist_units + fs_decode_attention_units).  Default: the chunked list")
+    ap.add_argument("--chunked", action="store_true",
+                    help="the chunked list (fs_build_worklist) on the config's own chunk also for a large share (default there: "
+                         "a chunk of the builder's choice, one workgroup per item)")
     ap.add_argument("--no-records", action="store_true",
                     help="hand the kernels the items (they look each one up themselves) instead of launch records")
     ap.add_argument("--merge-kernel", action="store_true",
@@ -154,10 +157,7 @@ def main() -> int:
             return fs.fs_choose_chunk_tokens(shape, ctx, owner, rank, w["chunk_tokens"], MIN_CHUNK, n_cu)[0]
         return w["chunk_tokens"]
 
-    chunk = chunk_for(args.rank)
-    # Below this a run is too short for the equal-run form to pay: the chunked list with one workgroup per record, which
-    # merges split pairs inside the sweep, measures faster (config 1, 89 pages to a run: 72.8 against 77.2 us per step;
-    # config 2, 466 pages to a run: 311 against 318)
+    # A share is large when each of the 2 x n_cu workgroups the chip runs at a time has this many pages to read.
     UNIT_MIN_PAGES = 256
 
     def pages_of(rank):
@@ -169,9 +169,24 @@ def main() -> int:
             return args.units
         return max(1, min(2 * n_cu, pages_of(rank) // 16))
 
-    # (fp8 K/V: the resident forms run and measure no faster than one workgroup per item, which stays the default there)
-    units = args.units is not None or (w["kv_dtype"] == "bf16" and not args.chunked and not args.classic and not args.persistent
-                                       and args.chunk is None and pages_of(args.rank) >= UNIT_MIN_PAGES * 2 * n_cu)
+    # A large share, left to the builder (no flag that names a list or a sweep): the chunked list with items of four
+    # ninths of a compute unit's share of the rank's tokens (8/9 of what one of the two workgroups on it gets: the longest
+    # item, launched first, cannot stick out at the end, and no finer, since every cut costs partial rows and an item
+    # start), one workgroup per record, split pairs merged inside the sweep.  Same box, config 2, step time: 304.5-307.5 us
+    # with chunks of 5120-7168 tokens against 311-313 on 512 equal runs (--units 0) and 309-314 on the config's own
+    # 2048-token chunks (--chunked); the sweeps alone tie (299-302 us), the difference is the merge, which the equal-run
+    # form leaves to a second kernel.  Small shares: the config's chunk, or four thirds of a compute unit's share.
+    large = pages_of(args.rank) >= UNIT_MIN_PAGES * 2 * n_cu
+    auto_large = (large and args.units is None and not args.chunked and not args.classic and not args.persistent
+                  and args.chunk is None and w["chunk_tokens"] > 0)
+    if auto_large:
+        args.classic = True
+
+        def chunk_for(rank):      # noqa: F811
+            return fs.fs_choose_chunk_tokens(shape, ctx, owner, rank, 32768, MIN_CHUNK, 3 * n_cu)[0]
+    chunk = chunk_for(args.rank)
+    # (fp8 K/V: the resident forms run and measure no faster than one workgroup per item)
+    units = args.units is not None
 
     if units:
         n_units_req = units_for(args.rank)
@@ -618,6 +633,10 @@ def main() -> int:
                    "merge_launched": bool(args.two_calls or (n_items > n_pairs and not (use_records and merge_in_sweep))),
                    "split_pairs_merged": "by a merge kernel" if (args.two_calls or not use_records or not merge_in_sweep) else
                                          "inside the sweep, by the workgroup that writes a pair's last partial rows",
+                   "chunk_rule": None if units else ("given on the command line" if args.chunk is not None else
+                                                     "the builder's: items of 4/9 of a compute unit's share of the rank's tokens" if auto_large else
+                                                     "the builder's: items of 4/3 of a compute unit's share, at most the config's chunk"
+                                                     if (w.get("chunk_adaptive") and w["chunk_tokens"] > MIN_CHUNK) else "the config's"),
                    "kernel": kernel_name,
                    "waves_per_group": fs.fs_get_option("waves_per_group"),
                    "prefetch_pages": fs.fs_get_option("prefetch_pages"),

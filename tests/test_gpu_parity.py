@@ -433,11 +433,14 @@ def check_fused(ds, indptr, what):
 
 
 # ------------------------------------------------------------------------------------------------
-def _full_config(cfg_id, rank, **req_kw):
+def _full_config(cfg_id, rank, kv_dtype=None, builders_chunk=False, **req_kw):
     """A config at its full size in the launch shape the benchmark times: every pair of the share against
     the oracle (threaded over pairs), and for bf16 the persistent form of the sweep bit for bit against one
-    workgroup per item."""
+    workgroup per item.  builders_chunk: the chunk the benchmark takes for a large share (items of four ninths
+    of a compute unit's share of the rank's tokens) instead of the config's own."""
     w = make_requests(cfg_id, **req_kw)
+    if kv_dtype:
+        w["kv_dtype"] = kv_dtype
     q = make_q(w["seed"], w["n_req"], w["n_q_heads"], 128)
     sh = shape_of(w)
     owner, dp, load = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
@@ -449,7 +452,11 @@ def _full_config(cfg_id, rank, **req_kw):
         chunk, n_chosen = fs.fs_choose_chunk_tokens(sh, w["ctx_len"], owner, rank, w["chunk_tokens"], 256, n_cu)
         assert (chunk, n_chosen) == oracle.choose_chunk_tokens(w["ctx_len"], o_owner, rank, w["chunk_tokens"], 256, n_cu,
                                                                w["n_kv_heads"])
-    what = f"cfg{cfg_id}{' ' + str(req_kw) if req_kw else ''} rank {rank}"
+    if builders_chunk:
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        chunk, n_chosen = fs.fs_choose_chunk_tokens(sh, w["ctx_len"], owner, rank, 32768, 256, 3 * n_cu)
+        assert (chunk, n_chosen) == oracle.choose_chunk_tokens(w["ctx_len"], o_owner, rank, 32768, 256, 3 * n_cu, w["n_kv_heads"])
+    what = f"cfg{cfg_id}{' ' + str(req_kw) if req_kw else ''}{' as ' + kv_dtype if kv_dtype else ''} rank {rank}"
     say(f"{what}: generating pool (chunk {chunk})")
     ds, kv, items, pairs, sched, indptr = run_rank(w, q, rank, chunk, owner)
     oi, op, osch, oind = oracle.build_worklist(w["ctx_len"], o_owner, rank, chunk, w["n_q_heads"], w["n_kv_heads"])
@@ -485,6 +492,13 @@ def test_config1_full_size_every_pair():
 
 def test_config2_full_size_every_pair():
     _full_config(2, 0)
+
+
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_config2_full_size_on_the_builders_chunk_every_pair(kv_dtype):
+    """The 70B-shaped batch as the benchmark launches it by default: the builder's chunk, one workgroup per
+    record, split pairs merged inside the sweep; and the same batch held as fp8."""
+    _full_config(2, 0, kv_dtype=None if kv_dtype == "bf16" else kv_dtype, builders_chunk=True)
 
 
 @pytest.mark.parametrize("rank", range(5))

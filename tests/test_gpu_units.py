@@ -146,7 +146,7 @@ def _full(cfg_id, rank, kv_dtype=None, **req_kw):
     sh = fs.FsShape(w["n_req"], w["n_q_heads"], w["n_kv_heads"], 128, 16, w["n_ranks"])
     owner, _, _ = fs.fs_build_placement(sh, w["ctx_len"], w["mode"])
     o_owner, _, _ = oracle.build_placement(w["ctx_len"], w["mode"], w["n_ranks"], w["n_kv_heads"])
-    n_units = 2 * torch.cuda.get_device_properties(0).multi_processor_count       # what bench.py launches
+    n_units = 2 * torch.cuda.get_device_properties(0).multi_processor_count       # what bench.py --units 0 launches
     what = f"cfg{cfg_id}{' ' + str(req_kw) if req_kw else ''}{' held as ' + kv_dtype if kv_dtype else ''} rank {rank}, {n_units} units"
     say(f"{what}: generating pool")
     ds, kv, op, oi, chunk_indptr = run_units(w, q, rank, n_units, owner, o_owner)
