@@ -30,14 +30,15 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # profiles/).  A figure belongs to one kernel on one list: the key is (config, rank, seed, chunk, placement,
 # kernel); any other run reports null.
 MEASURED_TRAFFIC_BYTES = {
-    (2, 0, 20251116, 6640, "requests", "decode_bf16_kernel"): 1966163026,                     # profiles/decode_bf16_kernel_cfg2_70b_builders_chunk_rank0.txt
+    (2, 0, 20251116, 3728, "requests", "decode_bf16_persistent_kernel"): 1972054537,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_claimed_records_rank0.txt
+    (2, 0, 20251116, 6640, "requests", "decode_bf16_kernel"): 1966161681,                     # profiles/decode_bf16_kernel_cfg2_70b_chunk6640_rank0.txt (--classic --chunk 6640)
     (2, 0, 20251116, "512 units", "requests", "decode_bf16_persistent_kernel"): 1965813823,   # profiles/decode_bf16_units_kernel_cfg2_70b_rank0.txt (--units 0)
-    (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971407938,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt
-    (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1971832723,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt
-    (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408070099,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt
-    (1, 0, 20251115, 2048, "requests", "decode_bf16_kernel"): 407998268,                      # profiles/decode_bf16_kernel_cfg1_8b_hybrid_rank0.txt
-    (3, 0, 20251117, 688, "requests", "decode_bf16_kernel"): 69331506,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
-    (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3261385,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
+    (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971447326,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt (--chunked --persistent)
+    (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1981790715,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt (--chunked --classic)
+    (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408077266,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt (--units 512)
+    (1, 0, 20251115, 2048, "requests", "decode_bf16_kernel"): 407940583,                      # profiles/decode_bf16_kernel_cfg1_8b_hybrid_rank0.txt
+    (3, 0, 20251117, 688, "requests", "decode_bf16_kernel"): 69265476,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
+    (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3205035,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
     (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561926562,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
     (2, 0, 20251116, 2048, "requests", "decode_fp8_kernel"): 1007783948,                      # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_rank0.txt (--kv-dtype fp8 --chunked)
     (2, 0, 20251116, 6640, "requests", "decode_fp8_kernel"): 992023381,                       # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_builders_chunk_rank0.txt (--kv-dtype fp8)
@@ -77,6 +78,9 @@ def main() -> int:
     ap.add_argument("--chunked", action="store_true",
                     help="the chunked list (fs_build_worklist) on the config's own chunk also for a large share (default there: "
                          "a chunk of the builder's choice, one workgroup per item)")
+    ap.add_argument("--claim-records", action="store_true",
+                    help="launch records claimed in order by two resident workgroups per compute unit instead of one workgroup "
+                         "per record (default on a large bf16 share)")
     ap.add_argument("--no-records", action="store_true",
                     help="hand the kernels the items (they look each one up themselves) instead of launch records")
     ap.add_argument("--merge-kernel", action="store_true",
@@ -169,21 +173,29 @@ def main() -> int:
             return args.units
         return max(1, min(2 * n_cu, pages_of(rank) // 16))
 
-    # A large share, left to the builder (no flag that names a list or a sweep): the chunked list with items of four
-    # ninths of a compute unit's share of the rank's tokens (8/9 of what one of the two workgroups on it gets: the longest
-    # item, launched first, cannot stick out at the end, and no finer, since every cut costs partial rows and an item
-    # start), one workgroup per record, split pairs merged inside the sweep.  Same box, config 2, step time: 304.5-307.5 us
-    # with chunks of 5120-7168 tokens against 311-313 on 512 equal runs (--units 0) and 309-314 on the config's own
-    # 2048-token chunks (--chunked); the sweeps alone tie (299-302 us), the difference is the merge, which the equal-run
-    # form leaves to a second kernel.  Small shares: the config's chunk, or four thirds of a compute unit's share.
+    # A large share, left to the builder (no flag that names a list or a sweep): the chunked list launched from records,
+    # split pairs merged inside the sweep, on a chunk that is a fraction of what one of a compute unit's two resident
+    # workgroups gets of the rank's tokens (no item may stick out at the end, and no finer than that, since every cut
+    # costs partial rows and an item start).
+    #  bf16: resident workgroups claim the records (half a workgroup's share per item: they take 2-3 each and their rows
+    #    leave in bursts); same box, config 2, step: 300-305 us against 301-308 with one workgroup per record on 8/9 of
+    #    a share, 304-311 on 512 equal runs (--units 0) and 309-314 on the config's own 2048-token chunks (--chunked).
+    #  fp8: one workgroup per record on 8/9 of a share (the resident forms measure no faster with fp8 K/V).
+    # Small shares: one workgroup per record on the config's chunk, or four thirds of a compute unit's share.
     large = pages_of(args.rank) >= UNIT_MIN_PAGES * 2 * n_cu
     auto_large = (large and args.units is None and not args.chunked and not args.classic and not args.persistent
-                  and args.chunk is None and w["chunk_tokens"] > 0)
+                  and args.chunk is None and w["chunk_tokens"] > 0 and not args.no_records and not args.two_calls)
+    if args.claim_records and (args.units is not None or args.no_records or args.two_calls or args.persistent):
+        print("bench.py: --claim-records goes with the chunked list launched from records in one call", file=sys.stderr)
+        return 2
+    claim_records = args.claim_records or (auto_large and w["kv_dtype"] == "bf16")
     if auto_large:
-        args.classic = True
+        large_slots = 16 * n_cu // 3 if claim_records else 3 * n_cu
+        if not claim_records:
+            args.classic = True
 
         def chunk_for(rank):      # noqa: F811
-            return fs.fs_choose_chunk_tokens(shape, ctx, owner, rank, 32768, MIN_CHUNK, 3 * n_cu)[0]
+            return fs.fs_choose_chunk_tokens(shape, ctx, owner, rank, 32768, MIN_CHUNK, large_slots)[0]
     chunk = chunk_for(args.rank)
     # (fp8 K/V: the resident forms run and measure no faster than one workgroup per item)
     units = args.units is not None
@@ -282,7 +294,7 @@ def main() -> int:
 
     # The persistent form pays off once every workgroup walks several items (it saves the scattered stores
     # and the relaunches); with one item or fewer per workgroup slot it is the same work plus a counter.
-    persistent = not args.classic and not units and (args.persistent or (w["kv_dtype"] == "bf16" and n_items >= 1024))
+    persistent = not args.classic and not units and not claim_records and (args.persistent or (w["kv_dtype"] == "bf16" and n_items >= 1024))
     if args.persistent and n_items < 1024 and not args.two_calls:
         print("bench.py: --persistent below 1024 items needs --two-calls (the fused call picks the sweep by list length)",
               file=sys.stderr)
@@ -309,11 +321,13 @@ def main() -> int:
             if use_records:
                 ui = (base + off_sched) if units else None
                 dec.append(fs.bind_decode_attention_records(shape, ds.view, base + off_records2, n_items, ui, n_units if units else 0,
-                                                            None, 0, part_o, part_lse, out, lse, None, stream_ptr))
+                                                            None, 0, part_o, part_lse, out, lse, None,
+                                                            claim if claim_records else None, stream_ptr))
                 mrg.append(fs.bind_merge_lse(part_o, part_lse, base + off_indptr, n_pairs, G, w["head_dim"], out, lse, stream_ptr))
                 fused.append(fs.bind_decode_attention_records(shape, ds.view, base + off_records, n_items, ui, n_units if units else 0,
                                                               base + off_indptr, n_pairs, part_o, part_lse, out, lse,
-                                                              pair_counters if merge_in_sweep else None, stream_ptr))
+                                                              pair_counters if merge_in_sweep else None,
+                                                              claim if claim_records else None, stream_ptr))
                 continue
             if units:
                 dec.append(fs.bind_decode_attention_units(shape, ds.view, base + off_items, n_items, base + off_sched, n_units,
@@ -607,7 +621,7 @@ def main() -> int:
 
     dec_avg_ms = float(dec_batch_ms)
     achieved = decode_bytes / (dec_avg_ms * 1e-3) / 1e9
-    kernel_name = ("decode_bf16" if w["kv_dtype"] == "bf16" else "decode_fp8") + ("_persistent_kernel" if persistent or units else "_kernel")
+    kernel_name = ("decode_bf16" if w["kv_dtype"] == "bf16" else "decode_fp8") + ("_persistent_kernel" if persistent or units or claim_records else "_kernel")
     default_shape = (args.waves in (None, 4) and args.prefetch in (None, 2) and not args.separate_kv
                      and not args.scales_by_slot and not (args.config == 3 and args.force_tail))
     key = (args.config, args.rank, w["seed"], f"{n_units} units" if units else chunk, args.placement, kernel_name) if default_shape else None
@@ -626,7 +640,8 @@ def main() -> int:
                                + (f", K/V held as {args.kv_dtype}" if args.kv_dtype else ""),
                    "n_pairs": n_pairs, "n_items": n_items, "kv_token_heads": tok_heads,
                    "kv_bytes": kv_bytes, "step_bytes": step_bytes,
-                   "sweep": "one resident workgroup per run of pages" if units else ("persistent" if persistent else "one workgroup per item"),
+                   "sweep": "one resident workgroup per run of pages" if units else ("persistent" if persistent else
+                            "resident workgroups claiming launch records" if claim_records else "one workgroup per item"),
                    "step_calls": "fs_build_launch_records + fs_decode_attention_records" if use_records else
                                  ("fs_decode_attention_units" + (" (sweep alone) + fs_merge_lse" if args.two_calls else "")) if units else
                                  ("fs_decode_attention[_persistent] + fs_merge_lse" if args.two_calls else "fs_decode_attention_fused"),
@@ -634,7 +649,8 @@ def main() -> int:
                    "split_pairs_merged": "by a merge kernel" if (args.two_calls or not use_records or not merge_in_sweep) else
                                          "inside the sweep, by the workgroup that writes a pair's last partial rows",
                    "chunk_rule": None if units else ("given on the command line" if args.chunk is not None else
-                                                     "the builder's: items of 4/9 of a compute unit's share of the rank's tokens" if auto_large else
+                                                     ("the builder's: items of half a resident workgroup's share of the rank's tokens" if claim_records else
+                                                      "the builder's: items of 8/9 of a resident workgroup's share of the rank's tokens") if auto_large else
                                                      "the builder's: items of 4/3 of a compute unit's share, at most the config's chunk"
                                                      if (w.get("chunk_adaptive") and w["chunk_tokens"] > MIN_CHUNK) else "the config's"),
                    "kernel": kernel_name,

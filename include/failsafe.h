@@ -40,7 +40,7 @@
 extern "C" {
 #endif
 
-#define FS_ABI_VERSION 3
+#define FS_ABI_VERSION 4
 
 #if defined(__GNUC__)
 #define FS_API __attribute__((visibility("default")))
@@ -553,7 +553,8 @@ FS_API fs_status fs_build_launch_records(const fs_shape* shape, const fs_work_it
 
 /* fs_decode_attention_records - decode attention (Section 2.1.1) and split-K merge in one call,
  * from launch records built with direct_rows != 0.  unit_indptr_dev == NULL: one workgroup per
- * record, in the order of the array (bf16 or fp8 K/V).  unit_indptr_dev given: records of a list
+ * record, in the order of the array, or with claim_dev resident workgroups that claim the records
+ * in that order (bf16 or fp8 K/V).  unit_indptr_dev given: records of a list
  * from fs_build_worklist_units in item order, one resident workgroup per unit, as
  * fs_decode_attention_units.  Rows of unsplit pairs come final from the sweep; the merge runs for
  * split pairs and is not launched when n_items == n_pairs.  out/lse hold what the calls that take
@@ -573,15 +574,22 @@ FS_API fs_status fs_build_launch_records(const fs_shape* shape, const fs_work_it
  *                    The counters must all be zero when the call is made; every call leaves them zero
  *                    (a launch that did not run to its end may not).  Calls that share counters must not
  *                    overlap.  Same bits in out/lse as with NULL.
+ *  claim_dev         DEVICE scratch, two int32, 8-byte aligned, or NULL.  Given (unit_indptr_dev NULL): two
+ *                    resident workgroups per compute unit claim the records in the order of the array and
+ *                    write their rows in bursts, as fs_decode_attention_persistent does with items; whatever
+ *                    the length of the list (the caller chooses the form).  Both counters must be zero when
+ *                    the call is made and every call leaves them zero; calls that share them must not
+ *                    overlap.  Same bits in out/lse as with NULL.
  *
  * The page table of kv must be the one the records were built from.  Errors as for
- * fs_decode_attention_fused; FS_EINVAL also for pair_counters_dev without chunk_indptr_dev. */
+ * fs_decode_attention_fused; FS_EINVAL also for pair_counters_dev without chunk_indptr_dev and for
+ * claim_dev together with unit_indptr_dev or not 8-byte aligned. */
 FS_API fs_status fs_decode_attention_records(const fs_shape* shape, const fs_kv_view* kv,
                                              const fs_launch_record* records_dev, int64_t n_items,
                                              const int64_t* unit_indptr_dev, int64_t n_units,
                                              const int64_t* chunk_indptr_dev, int64_t n_pairs,
                                              float* part_o, float* part_lse, float* out, float* lse,
-                                             int32_t* pair_counters_dev, void* stream);
+                                             int32_t* pair_counters_dev, int32_t* claim_dev, void* stream);
 
 /* ---------------------------------------------------------------------------
  * fs_decode_attention_fused_static - fs_decode_attention_fused for callers that cannot allocate

@@ -89,7 +89,7 @@ def load_library(path: str | None = None):
     lib.fs_build_launch_records.restype = C.c_int
     lib.fs_decode_attention_records.argtypes = [C.POINTER(FsShape), C.POINTER(FsKvView), C.c_void_p, C.c_int64,
                                                 C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
-                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fs_decode_attention_records.restype = C.c_int
     lib.fs_choose_chunk_tokens.argtypes = [C.POINTER(FsShape), i32p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                            i32p, i64p]
@@ -540,11 +540,11 @@ def fs_decode_attention_units(shape: FsShape, kv: FsKvView, items_dev, n_items: 
 
 def fs_decode_attention_records(shape: FsShape, kv: FsKvView, records_dev, n_items: int, unit_indptr_dev, n_units: int,
                                 chunk_indptr_dev, n_pairs: int, part_o, part_lse, out, lse, pair_counters_dev=None,
-                                stream=None) -> None:
+                                claim_dev=None, stream=None) -> None:
     st = load_library().fs_decode_attention_records(C.byref(shape), C.byref(kv), _ptr(records_dev), n_items,
                                                     _ptr(unit_indptr_dev), n_units, _ptr(chunk_indptr_dev), n_pairs,
                                                     _ptr(part_o), _ptr(part_lse), _ptr(out), _ptr(lse),
-                                                    _ptr(pair_counters_dev), _ptr(stream))
+                                                    _ptr(pair_counters_dev), _ptr(claim_dev), _ptr(stream))
     _check(st)
 
 
@@ -776,13 +776,14 @@ def bind_build_launch_records(shape: FsShape, items: np.ndarray, order, chunk_in
 
 def bind_decode_attention_records(shape: FsShape, kv: FsKvView, records_dev, n_items: int, unit_indptr_dev, n_units: int,
                                   chunk_indptr_dev, n_pairs: int, part_o, part_lse, out, lse, pair_counters_dev=None,
-                                  stream=None) -> BoundCall:
+                                  claim_dev=None, stream=None) -> BoundCall:
     lib = load_library()
     args = (C.byref(shape), C.byref(kv), _vp(records_dev), C.c_int64(n_items), _vp(unit_indptr_dev), C.c_int64(n_units),
             _vp(chunk_indptr_dev), C.c_int64(n_pairs), _vp(part_o), _vp(part_lse), _vp(out), _vp(lse),
-            _vp(pair_counters_dev), _vp(stream))
+            _vp(pair_counters_dev), _vp(claim_dev), _vp(stream))
     return BoundCall(lib.fs_decode_attention_records, args,
-                     (shape, kv, records_dev, unit_indptr_dev, chunk_indptr_dev, part_o, part_lse, out, lse, pair_counters_dev))
+                     (shape, kv, records_dev, unit_indptr_dev, chunk_indptr_dev, part_o, part_lse, out, lse, pair_counters_dev,
+                      claim_dev))
 
 
 def bind_merge_lse(part_o, part_lse, chunk_indptr_dev, n_pairs: int, group: int, head_dim: int,

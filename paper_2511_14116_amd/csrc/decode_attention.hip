@@ -1161,7 +1161,7 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
                                                  const int64_t* unit_indptr_dev, int64_t n_units,
                                                  const int64_t* chunk_indptr_dev, int64_t n_pairs,
                                                  float* part_o, float* part_lse, float* out, float* lse,
-                                                 int32_t* pair_counters_dev, void* stream) {
+                                                 int32_t* pair_counters_dev, int32_t* claim_dev, void* stream) {
   const char* who = "fs_decode_attention_records";
   const bool sweep_only = chunk_indptr_dev == nullptr;     // no merge: the rows go where the records say
   if (sweep_only && pair_counters_dev)
@@ -1171,6 +1171,10 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
   const bool units = unit_indptr_dev != nullptr;
   if (units && (n_units < 0 || n_units > n_items))
     return fs::fail(FS_EINVAL, "%s: n_units %lld outside [0, n_items]", who, static_cast<long long>(n_units));
+  if (claim_dev && units)
+    return fs::fail(FS_EINVAL, "%s: claim_dev with unit_indptr_dev (equal runs are not claimed)", who);
+  if (claim_dev && (reinterpret_cast<uintptr_t>(claim_dev) & 7))
+    return fs::fail(FS_EINVAL, "%s: claim_dev is not 8-byte aligned", who);
   const bool split = sweep_only || n_items > n_pairs;
   DecodeParams P;
   if (const fs_status st = prepare(who, shape, kv, records_dev, nullptr, n_items, part_o, part_lse, split, &P);
@@ -1195,6 +1199,8 @@ extern "C" fs_status fs_decode_attention_records(const fs_shape* shape, const fs
   fs_status st = FS_OK;
   if (units) {
     st = launch_resident(who, P, kv->kv_dtype, n_units, n_items, nullptr, 0, unit_indptr_dev, s);
+  } else if (claim_dev) {
+    st = launch_persistent(who, P, kv->kv_dtype, n_items, claim_dev, s);
   } else {
     st = launch_plain(who, P, kv->kv_dtype, n_items, s);
   }

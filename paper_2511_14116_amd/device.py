@@ -93,15 +93,18 @@ class DeviceShare:
         assert len(records) == self.n_items
         self.records = torch.from_numpy(np.ascontiguousarray(records).view(np.int32).reshape(-1, 16)).to(self.device)
 
-    def run_records(self, units: bool = False, merge_in_sweep: bool = False):
-        """Sweep and merge in one call from launch records (one workgroup per record, or per unit).  With
-        ``merge_in_sweep`` the pair counters are handed over and split pairs are merged by the sweep itself."""
+    def run_records(self, units: bool = False, merge_in_sweep: bool = False, claim: bool = False):
+        """Sweep and merge in one call from launch records (one workgroup per record, or per unit; with ``claim``
+        resident workgroups that claim the records in order).  With ``merge_in_sweep`` the pair counters are
+        handed over and split pairs are merged by the sweep itself."""
         if merge_in_sweep and (not hasattr(self, "pair_counters") or len(self.pair_counters) < self.n_pairs):
             self.pair_counters = torch.zeros(max(self.n_pairs, 1), dtype=torch.int32, device=self.device)   # every call leaves them zero
+        if claim and not hasattr(self, "claim"):
+            self.claim = torch.zeros(2, dtype=torch.int32, device=self.device)   # every launch leaves them at zero
         B.fs_decode_attention_records(self.shape, self.view, self.records, self.n_items,
                                       self.unit_indptr if units else None, self.n_units if units else 0,
                                       self.chunk_indptr, self.n_pairs, self.part_o, self.part_lse, self.out, self.lse,
-                                      self.pair_counters if merge_in_sweep else None,
+                                      self.pair_counters if merge_in_sweep else None, self.claim if claim else None,
                                       torch.cuda.current_stream().cuda_stream)
 
     def decode(self, use_sched: bool = True):

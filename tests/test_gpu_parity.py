@@ -391,24 +391,32 @@ def check_records(ds, kv, items, sched, indptr, what):
     ds.set_records(rec)
     for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
         t.fill_(float("nan"))
-    ds.run_records()
-    torch.cuda.synchronize()
-    assert torch.equal(ds.out, ref[0]) and torch.equal(ds.lse, ref[1]), f"{what}: the records call leaves other final rows"
+    for claim in (False, True):          # one workgroup per record; resident workgroups claiming the records
+        for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
+            t.fill_(float("nan"))
+        ds.run_records(claim=claim)
+        torch.cuda.synchronize()
+        assert torch.equal(ds.out, ref[0]) and torch.equal(ds.lse, ref[1]), f"{what}: the records call (claim={claim}) leaves other final rows"
+        assert not claim or ds.claim.cpu().tolist() == [0, 0], f"{what}: the claim counters are not back at zero"
     check_merge_in_sweep(ds, ref, False, what)
+    check_merge_in_sweep(ds, ref, False, what, claim=True)
 
 
-def check_merge_in_sweep(ds, ref, units, what):
+def check_merge_in_sweep(ds, ref, units, what, claim=False):
     """The same call with pair counters: split pairs are merged by the workgroup that writes their last partial rows,
-    no merge kernel runs.  Twice in a row (the counters must be back at zero), same bits as ``ref`` = [out, lse]."""
+    no merge kernel runs.  Twice in a row (the counters must be back at zero), same bits as ``ref`` = [out, lse].
+    claim: resident workgroups that claim the records instead of one workgroup per record."""
+    what = f"{what} (claim={claim})"
     for rep in range(2):
         for t in (ds.part_o, ds.part_lse, ds.out, ds.lse):
             t.fill_(float("nan"))
-        ds.run_records(units=units, merge_in_sweep=True)
+        ds.run_records(units=units, merge_in_sweep=True, claim=claim)
         torch.cuda.synchronize()
         bad = (~((ds.out == ref[0]).all(dim=1) & (ds.lse == ref[1]))).nonzero().flatten().cpu().numpy()
         assert len(bad) == 0, (f"{what}: merge inside the sweep (units={units}, call {rep}) leaves other final rows: {len(bad)} rows, "
                                f"first {int(bad[0])} (pair {int(bad[0]) // ds.group}), lse {float(ds.lse[int(bad[0])])} vs {float(ref[1][int(bad[0])])}")
         assert int(ds.pair_counters.abs().sum()) == 0, f"{what}: the pair counters are not back at zero after call {rep}"
+        assert not claim or ds.claim.cpu().tolist() == [0, 0], f"{what}: the claim counters are not back at zero after call {rep}"
 
 
 def check_fused(ds, indptr, what):
@@ -436,8 +444,9 @@ def check_fused(ds, indptr, what):
 def _full_config(cfg_id, rank, kv_dtype=None, builders_chunk=False, **req_kw):
     """A config at its full size in the launch shape the benchmark times: every pair of the share against
     the oracle (threaded over pairs), and for bf16 the persistent form of the sweep bit for bit against one
-    workgroup per item.  builders_chunk: the chunk the benchmark takes for a large share (items of four ninths
-    of a compute unit's share of the rank's tokens) instead of the config's own."""
+    workgroup per item.  builders_chunk: the chunk the benchmark takes for a large share instead of the config's own
+    (items of half a resident workgroup's share of the rank's tokens with bf16 K/V, where resident workgroups claim the
+    launch records; of 8/9 of it with fp8, one workgroup per record)."""
     w = make_requests(cfg_id, **req_kw)
     if kv_dtype:
         w["kv_dtype"] = kv_dtype
@@ -454,8 +463,9 @@ def _full_config(cfg_id, rank, kv_dtype=None, builders_chunk=False, **req_kw):
                                                                w["n_kv_heads"])
     if builders_chunk:
         n_cu = torch.cuda.get_device_properties(0).multi_processor_count
-        chunk, n_chosen = fs.fs_choose_chunk_tokens(sh, w["ctx_len"], owner, rank, 32768, 256, 3 * n_cu)
-        assert (chunk, n_chosen) == oracle.choose_chunk_tokens(w["ctx_len"], o_owner, rank, 32768, 256, 3 * n_cu, w["n_kv_heads"])
+        slots = 16 * n_cu // 3 if w["kv_dtype"] == "bf16" else 3 * n_cu
+        chunk, n_chosen = fs.fs_choose_chunk_tokens(sh, w["ctx_len"], owner, rank, 32768, 256, slots)
+        assert (chunk, n_chosen) == oracle.choose_chunk_tokens(w["ctx_len"], o_owner, rank, 32768, 256, slots, w["n_kv_heads"])
     what = f"cfg{cfg_id}{' ' + str(req_kw) if req_kw else ''}{' as ' + kv_dtype if kv_dtype else ''} rank {rank}"
     say(f"{what}: generating pool (chunk {chunk})")
     ds, kv, items, pairs, sched, indptr = run_rank(w, q, rank, chunk, owner)
@@ -496,8 +506,9 @@ def test_config2_full_size_every_pair():
 
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 def test_config2_full_size_on_the_builders_chunk_every_pair(kv_dtype):
-    """The 70B-shaped batch as the benchmark launches it by default: the builder's chunk, one workgroup per
-    record, split pairs merged inside the sweep; and the same batch held as fp8."""
+    """The 70B-shaped batch as the benchmark launches it by default: the builder's chunk, launch records (claimed by
+    resident workgroups and one workgroup per record), split pairs merged inside the sweep; and the same batch held
+    as fp8."""
     _full_config(2, 0, kv_dtype=None if kv_dtype == "bf16" else kv_dtype, builders_chunk=True)
 
 
@@ -546,10 +557,12 @@ def test_hip_graph_replays_match_eager():
     check(ds.out.cpu().numpy(), ds.lse.cpu().numpy(), ref_o, ref_l, "graph replay vs oracle")
 
 
-def test_hip_graph_replays_of_the_sweep_that_merges():
+@pytest.mark.parametrize("claiming", [False, True])
+def test_hip_graph_replays_of_the_sweep_that_merges(claiming):
     """fs_decode_attention_records with pair counters (split pairs merged inside the sweep) captured as a HIP
     graph: the counters go back to zero inside every launch, so replays need nothing cleared between them; every
-    replay, with eager launches of the same call and of the two-call form in between, gives the eager bits."""
+    replay, with eager launches of the same call and of the two-call form in between, gives the eager bits.
+    claiming: resident workgroups that claim the records, whose two counters go back to zero the same way."""
     w = make_requests(1, n_req=24, max_len=2500)
     q = make_q(w["seed"], 24, w["n_q_heads"], 128)
     sh = shape_of(w)
@@ -559,9 +572,10 @@ def test_hip_graph_replays_of_the_sweep_that_merges():
     assert ds.n_items > ds.n_pairs
     ds.set_records(fs.fs_build_launch_records(sh, items, sched, indptr, kv["page_indptr"], kv["page_ids"]))
     counters = torch.zeros(ds.n_pairs, dtype=torch.int32, device=ds.device)
+    claim = torch.zeros(2, dtype=torch.int32, device=ds.device) if claiming else None
     cap = torch.cuda.Stream()
     call = fs.bind_decode_attention_records(sh, ds.view, ds.records, ds.n_items, None, 0, ds.chunk_indptr, ds.n_pairs,
-                                            ds.part_o, ds.part_lse, ds.out, ds.lse, counters, cap.cuda_stream)
+                                            ds.part_o, ds.part_lse, ds.out, ds.lse, counters, claim, cap.cuda_stream)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=cap):
@@ -573,6 +587,7 @@ def test_hip_graph_replays_of_the_sweep_that_merges():
         torch.cuda.synchronize()
         assert torch.equal(ds.out, eager_o) and torch.equal(ds.lse, eager_l), f"replay {rep} differs"
         assert int(counters.abs().sum()) == 0, f"replay {rep} left a pair counter standing"
+        assert claim is None or claim.cpu().tolist() == [0, 0], f"replay {rep} left a claim counter standing"
         ds.run()                       # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(ds.out, eager_o)

@@ -40,7 +40,7 @@ def test_library_exports_every_declared_symbol():
     lib = C.CDLL(fs.library_path())
     for name in declared:
         assert hasattr(lib, name), name
-    assert fs.fs_abi_version() == 3
+    assert fs.fs_abi_version() == 4
 
 
 def test_struct_sizes_match_the_header():
@@ -272,6 +272,12 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     with pytest.raises(fs.FsError) as e:     # pair counters for a sweep that merges nothing
         fs.fs_decode_attention_records(sh, kv, None, 3, None, 0, None, 0, None, None, None, None, pair_counters_dev=64)
     assert e.value.status == fs.FS_EINVAL
+    with pytest.raises(fs.FsError) as e:     # claim counters with equal runs: those are not claimed
+        fs.fs_decode_attention_records(sh, kv, None, 3, 64, 2, 64, 2, None, None, None, None, claim_dev=64)
+    assert e.value.status == fs.FS_EINVAL and "claim_dev" in str(e.value)
+    with pytest.raises(fs.FsError) as e:     # claim counters not 8-byte aligned
+        fs.fs_decode_attention_records(sh, kv, None, 3, None, 0, 64, 2, None, None, None, None, claim_dev=68)
+    assert e.value.status == fs.FS_EINVAL and "claim_dev" in str(e.value)
     fs.fs_pack_kv_slots(None, 4096, None, 4096, 0, fs.FS_KV_BF16, False)                            # no slots: no-op
     for args in ((None, 4096, None, 4096, 3, fs.FS_KV_BF16), (64, 4096, 8192, 100, 3, fs.FS_KV_BF16), (64, 4096, 8192, 4096, 3, 9)):
         with pytest.raises(fs.FsError) as e:
