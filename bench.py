@@ -566,7 +566,14 @@ def main() -> int:
                 run_k = ds_k.run_units
             else:
                 ds_k.set_worklist(it_k, pr_k, sc_k, ip_k)
-                run_k = (lambda: ds_k.run(persistent=persistent)) if args.two_calls else (lambda: ds_k.run_fused(persistent=persistent))
+                if use_records:          # as the step launches it: from launch records, split pairs merged as the step merges them
+                    ds_k.set_records(fs.fs_build_launch_records(shape, it_k, sc_k, ip_k, kv_k["page_indptr"], kv_k["page_ids"]))
+                    pc_k = torch.zeros(max(len(pr_k), 1), dtype=torch.int32, device=dev)
+                    run_k = fs.bind_decode_attention_records(shape, ds_k.view, ds_k.records, ds_k.n_items, None, 0, ds_k.chunk_indptr,
+                                                             ds_k.n_pairs, ds_k.part_o, ds_k.part_lse, ds_k.out, ds_k.lse,
+                                                             pc_k if merge_in_sweep else None, claim if claim_records else None, sptr)
+                else:
+                    run_k = (lambda: ds_k.run(persistent=persistent)) if args.two_calls else (lambda: ds_k.run_fused(persistent=persistent))
             for _ in range(5):
                 run_k()
             r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
