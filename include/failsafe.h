@@ -224,8 +224,11 @@ FS_API fs_status fs_build_worklist_units(const fs_shape* shape, const int32_t* c
  *
  *  ctx_len, owner   HOST in   as for fs_build_worklist
  *  max_chunk, min_chunk       multiples of page_tokens, page_tokens <= min_chunk <= max_chunk
- *  n_slots          workgroups the GPU should be running at a time (the number of compute units
- *                   measures best for the decode sweep), >= 1
+ *  n_slots          what the whole is shared among, >= 1.  Measured best for the decode sweep: the number of
+ *                   compute units with max_chunk 2048 for a share of less than ~2 M token-heads; for a larger
+ *                   one, with max_chunk 32768, 16/3 per compute unit when resident workgroups claim the launch
+ *                   records (items of half of what one of a compute unit's two workgroups gets) and 3 per
+ *                   compute unit with one workgroup per record (8/9 of it)
  *  chunk_tokens     HOST out  the chosen chunk
  *  n_items          HOST out  the list's length with it
  *
