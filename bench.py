@@ -30,18 +30,18 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 # profiles/).  A figure belongs to one kernel on one list: the key is (config, rank, seed, chunk, placement,
 # kernel); any other run reports null.
 MEASURED_TRAFFIC_BYTES = {
-    (2, 0, 20251116, 3728, "requests", "decode_bf16_persistent_kernel"): 1972054537,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_claimed_records_rank0.txt
-    (2, 0, 20251116, 6640, "requests", "decode_bf16_kernel"): 1966161681,                     # profiles/decode_bf16_kernel_cfg2_70b_chunk6640_rank0.txt (--classic --chunk 6640)
-    (2, 0, 20251116, "512 units", "requests", "decode_bf16_persistent_kernel"): 1965813823,   # profiles/decode_bf16_units_kernel_cfg2_70b_rank0.txt (--units 0)
-    (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971447326,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt (--chunked --persistent)
-    (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1981790715,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt (--chunked --classic)
-    (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408077266,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt (--units 512)
-    (1, 0, 20251115, 2048, "requests", "decode_bf16_kernel"): 407940583,                      # profiles/decode_bf16_kernel_cfg1_8b_hybrid_rank0.txt
-    (3, 0, 20251117, 688, "requests", "decode_bf16_kernel"): 69265476,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
-    (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3205035,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
-    (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561926562,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
+    (2, 0, 20251116, 3728, "requests", "decode_bf16_persistent_kernel"): 1972031652,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_claimed_records_rank0.txt
+    (2, 0, 20251116, 6640, "requests", "decode_bf16_kernel"): 1966162992,                     # profiles/decode_bf16_kernel_cfg2_70b_chunk6640_rank0.txt (--classic --chunk 6640)
+    (2, 0, 20251116, "512 units", "requests", "decode_bf16_persistent_kernel"): 1965815821,   # profiles/decode_bf16_units_kernel_cfg2_70b_rank0.txt (--units 0)
+    (2, 0, 20251116, 2048, "requests", "decode_bf16_persistent_kernel"): 1971410666,          # profiles/decode_bf16_persistent_kernel_cfg2_70b_rank0.txt (--chunked --persistent)
+    (2, 0, 20251116, 2048, "requests", "decode_bf16_kernel"): 1981789512,                     # profiles/decode_bf16_kernel_cfg2_70b_rank0.txt (--chunked --classic)
+    (1, 0, 20251115, "512 units", "requests", "decode_bf16_persistent_kernel"): 408077179,    # profiles/decode_bf16_units_kernel_cfg1_8b_hybrid_rank0.txt (--units 512)
+    (1, 0, 20251115, 2048, "requests", "decode_bf16_kernel"): 407940537,                      # profiles/decode_bf16_kernel_cfg1_8b_hybrid_rank0.txt
+    (3, 0, 20251117, 688, "requests", "decode_bf16_kernel"): 69265433,                        # profiles/decode_bf16_kernel_cfg3_skew_rank0.txt
+    (0, 0, 20251114, 0, "requests", "decode_bf16_kernel"): 3205046,                           # profiles/decode_bf16_kernel_cfg0_tiny_rank0.txt
+    (4, 0, 20251118, 0, "requests", "decode_fp8_kernel"): 1561925135,                         # profiles/decode_fp8_kernel_cfg4_mha_fp8_rank0.txt
     (2, 0, 20251116, 2048, "requests", "decode_fp8_kernel"): 1007783948,                      # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_rank0.txt (--kv-dtype fp8 --chunked)
-    (2, 0, 20251116, 6640, "requests", "decode_fp8_kernel"): 992023381,                       # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_builders_chunk_rank0.txt (--kv-dtype fp8)
+    (2, 0, 20251116, 6640, "requests", "decode_fp8_kernel"): 992022007,                       # profiles/decode_fp8_kernel_cfg2_70b_as_fp8_builders_chunk_rank0.txt (--kv-dtype fp8)
 }
 KERNEL_LAUNCHES = 30       # launches of the attention kernel timed one by one for the roofline figure
 
